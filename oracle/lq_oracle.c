@@ -1,0 +1,437 @@
+/*
+ * lq_oracle.c -- plain CPU oracle for the LoRaQ inference forward (TEST INFRASTRUCTURE).
+ *
+ * This file is the slow, scalar, obviously-correct definition that the GPU library is
+ * checked against.  It is NOT part of the product: only tests, the smoke check and the
+ * bench's cpu_baseline leg may call it.  It shares no source, header, table or helper
+ * with the HIP path.
+ *
+ * What it computes (paper Fig. 1 and Eq. 5; orientation X: M x K, W: N x K, L: N x r,
+ * R: r x K, Y: M x N, all row-major):
+ *
+ *     P     = W - deq(Q2(L)) deq(Q2(R))                      residual weights (Fig. 1)
+ *     Y     = deq(Q1(X) Q1(P)^T) + deq(Q2(Q2(X) Q2(R)^T) Q2(L)^T)
+ *
+ * Q1 is the 4-bit main format, Q2 the sub-16-bit branch format.  Two families:
+ *   INT  : symmetric signed integers, round-to-nearest-even, fp32 scales
+ *          (SINT4-style block scales along K for Q1(P), App. A.3; per-token / per-channel
+ *          scales elsewhere); integer accumulate, fp32 dequantisation.
+ *   MX   : Q1 = MXFP4 (E2M1 elements, blocks of 32 along K, E8M0 power-of-two scale,
+ *          App. A.3), Q2 = FP8 E4M3 with one fp32 scale per token / per channel;
+ *          fp64 accumulate, result rounded once to fp32.
+ *
+ * Readings of points the paper leaves open (all "parity unpinned" by the paper; the tests
+ * pin self-consistency only):
+ *   - "round to nearest" = ties to even;
+ *   - integer codes are symmetric, [-qmax, qmax], qmax = 2^(b-1)-1;
+ *   - scale s = amax / qmax, codes = rne(v * (qmax / amax)), both in fp32
+ *     (reciprocal-multiply form of v / s); all-zero vector: s = 1, codes 0;
+ *   - the intermediate X R^T is re-quantised per token at the branch activation width
+ *     (the paper lists this as future work; the benchmark spec requires it);
+ *   - MX scale exponent = floor(log2 amax) - 2 (2 = largest E2M1 exponent), elements
+ *     saturate at +-6; all-zero block: E8M0 byte 0;
+ *   - P is built from the *dequantised* quantised factors (Fig. 1), optionally from the
+ *     unquantised ones (residual_from_quantized = 0).
+ *
+ * Build: gcc -O2 -fno-fast-math -ffp-contract=off -fopenmp -shared -fPIC
+ * OpenMP is used across token rows (or weight rows) only; no blocking, no reordering.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define LQO_API __attribute__((visibility("default")))
+
+/* ------------------------------------------------------------------------------------ */
+/* small helpers                                                                          */
+/* ------------------------------------------------------------------------------------ */
+
+static float absmax_f32(const float *v, int64_t n)
+{
+    float a = 0.0f;
+    for (int64_t i = 0; i < n; ++i) {
+        float t = fabsf(v[i]);
+        if (t > a) a = t;
+    }
+    return a;
+}
+
+/* fp32 -> bf16 bits, round-to-nearest-even (finite inputs). */
+static uint16_t bf16_rne(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7FFFu + lsb;
+    return (uint16_t)(u >> 16);
+}
+
+LQO_API uint16_t lqo_bf16_rne(float f) { return bf16_rne(f); }
+
+/* ------------------------------------------------------------------------------------ */
+/* symmetric integer quantiser (SINT4-style; App. A.3 "round-to-nearest" on scaled values) */
+/* ------------------------------------------------------------------------------------ */
+
+/* One vector of n values sharing one scale.  q in [-qmax, qmax]. */
+LQO_API void lqo_quant_int(const float *v, int64_t n, int qmax, int8_t *q, float *scale)
+{
+    float a = absmax_f32(v, n);
+    float s, inv;
+    if (a == 0.0f) {
+        s = 1.0f;
+        inv = 1.0f;
+    } else {
+        s = a / (float)qmax;
+        inv = (float)qmax / a;
+    }
+    for (int64_t i = 0; i < n; ++i) {
+        float u = v[i] * inv;
+        float r = nearbyintf(u); /* default rounding mode: ties to even */
+        if (r > (float)qmax) r = (float)qmax;
+        if (r < -(float)qmax) r = -(float)qmax;
+        q[i] = (int8_t)r;
+    }
+    *scale = s;
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* element formats of the MX family (App. A.3)                                            */
+/* ------------------------------------------------------------------------------------ */
+
+/* E2M1: 1 sign, 2 exponent (bias 1), 1 mantissa bit.  code = s e e m (4 bits). */
+LQO_API float lqo_e2m1_decode(uint8_t code)
+{
+    int s = (code >> 3) & 1, e = (code >> 1) & 3, m = code & 1;
+    float mag;
+    if (e == 0)
+        mag = 0.5f * (float)m; /* subnormal: m * 2^(1-1) * 2^-1 */
+    else
+        mag = ldexpf(1.0f + 0.5f * (float)m, e - 1);
+    return s ? -mag : mag;
+}
+
+/* E4M3 (OCP "FN" flavour): 1 sign, 4 exponent (bias 7), 3 mantissa; no Inf; S.1111.111 = NaN;
+   largest finite 448. */
+LQO_API float lqo_e4m3_decode(uint8_t code)
+{
+    int s = (code >> 7) & 1, e = (code >> 3) & 15, m = code & 7;
+    float mag;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0)
+        mag = ldexpf((float)m, -9); /* m/8 * 2^-6 */
+    else
+        mag = ldexpf(1.0f + (float)m / 8.0f, e - 7);
+    return s ? -mag : mag;
+}
+
+/* E8M0: value 2^(E-127); byte 0xFF is NaN and is never produced here. */
+LQO_API double lqo_e8m0_decode(uint8_t e) { return ldexp(1.0, (int)e - 127); }
+
+/* Nearest representable magnitude among codes 0..ncodes-1 of a monotone decode table,
+   ties to the even code (= even mantissa), saturating at the top code. */
+static int nearest_code(float mag, const float *table, int ncodes)
+{
+    if (mag >= table[ncodes - 1]) return ncodes - 1;
+    int lo = 0;
+    while (lo + 1 < ncodes && table[lo + 1] <= mag) ++lo; /* table[lo] <= mag < table[lo+1] */
+    double dl = (double)mag - (double)table[lo];
+    double dh = (double)table[lo + 1] - (double)mag;
+    if (dl < dh) return lo;
+    if (dh < dl) return lo + 1;
+    return (lo & 1) ? lo + 1 : lo;
+}
+
+LQO_API uint8_t lqo_e2m1_encode(float u)
+{
+    float table[8];
+    for (int c = 0; c < 8; ++c) table[c] = lqo_e2m1_decode((uint8_t)c);
+    int s = signbit(u) ? 1 : 0;
+    int c = nearest_code(fabsf(u), table, 8);
+    return (uint8_t)((s << 3) | c);
+}
+
+LQO_API uint8_t lqo_e4m3_encode(float u)
+{
+    float table[127];
+    for (int c = 0; c < 127; ++c) table[c] = lqo_e4m3_decode((uint8_t)c);
+    int s = signbit(u) ? 1 : 0;
+    int c = nearest_code(fabsf(u), table, 127);
+    return (uint8_t)((s << 7) | c);
+}
+
+/* MXFP4: K values in blocks of 32; one E8M0 byte per block; one E2M1 code per byte of `codes`. */
+LQO_API void lqo_quant_mxfp4(const float *v, int64_t K, uint8_t *codes, uint8_t *e8m0)
+{
+    for (int64_t b = 0; b < K / 32; ++b) {
+        const float *blk = v + 32 * b;
+        float a = absmax_f32(blk, 32);
+        int e;
+        if (a == 0.0f) {
+            e = -127;
+        } else {
+            int ex;
+            (void)frexpf(a, &ex); /* a = f * 2^ex, f in [0.5,1) => floor(log2 a) = ex-1 */
+            e = (ex - 1) - 2;
+            if (e < -127) e = -127;
+            if (e > 127) e = 127;
+        }
+        e8m0[b] = (uint8_t)(e + 127);
+        for (int i = 0; i < 32; ++i) {
+            float u = ldexpf(blk[i], -e); /* exact power-of-two scaling */
+            codes[32 * b + i] = lqo_e2m1_encode(u);
+        }
+    }
+}
+
+/* FP8 E4M3 with one fp32 scale for the whole vector: s = amax/448. */
+LQO_API void lqo_quant_fp8(const float *v, int64_t n, uint8_t *codes, float *scale)
+{
+    float a = absmax_f32(v, n);
+    float s, inv;
+    if (a == 0.0f) {
+        s = 1.0f;
+        inv = 1.0f;
+    } else {
+        s = a / 448.0f;
+        inv = 448.0f / a;
+    }
+    for (int64_t i = 0; i < n; ++i) codes[i] = lqo_e4m3_encode(v[i] * inv);
+    *scale = s;
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* INT family                                                                             */
+/* ------------------------------------------------------------------------------------ */
+
+/* Offline packing step (Fig. 1; Eq. 5): quantise the factors with Q2, form the residual P,
+   quantise P with Q1 in groups of g along K.
+   qmax_bw : qmax of the branch weight format (127 / 31 / 7).
+   Outputs: pq N x K, sw N x (K/g), lq N x r, sl N, rq r x K, sr r, P (optional, N x K). */
+LQO_API void lqo_pack_int(int64_t N, int64_t K, int r, int g, int qmax_bw,
+                          int residual_from_quantized, const float *W, const float *L,
+                          const float *R, int8_t *pq, float *sw, int8_t *lq, float *sl,
+                          int8_t *rq, float *sr, float *P_out)
+{
+    const int64_t G = K / g;
+    for (int j = 0; j < r; ++j) lqo_quant_int(R + (int64_t)j * K, K, qmax_bw, rq + (int64_t)j * K, &sr[j]);
+    for (int64_t n = 0; n < N; ++n) lqo_quant_int(L + n * r, r, qmax_bw, lq + n * r, &sl[n]);
+
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        float *P = (float *)malloc(sizeof(float) * (size_t)K);
+        for (int64_t k = 0; k < K; ++k) {
+            double d = 0.0;
+            for (int j = 0; j < r; ++j) {
+                float lh, rh;
+                if (residual_from_quantized) {
+                    lh = (float)lq[n * r + j] * sl[n];
+                    rh = (float)rq[(int64_t)j * K + k] * sr[j];
+                } else {
+                    lh = L[n * r + j];
+                    rh = R[(int64_t)j * K + k];
+                }
+                d += (double)lh * (double)rh;
+            }
+            P[k] = (float)((double)W[n * K + k] - d);
+        }
+        for (int64_t gi = 0; gi < G; ++gi)
+            lqo_quant_int(P + gi * g, g, 7, pq + n * K + gi * g, &sw[n * G + gi]);
+        if (P_out) memcpy(P_out + n * K, P, sizeof(float) * (size_t)K);
+        free(P);
+    }
+}
+
+/* Per-call activation step: 4-bit codes for the main product, b-bit codes for the branch,
+   the skinny contraction with Q2(R) and the re-quantisation of its result.
+   qmax_a : qmax of the branch activation format (127 / 31).
+   Outputs: xq M x K, sx M, xb M x K, sxb M, accT M x r (int32), T M x r, tq M x r, st M.
+   Any of xb / accT / T may be NULL. */
+LQO_API void lqo_quantize_act_int(int64_t M, int64_t K, int r, int qmax_a, const float *X,
+                                  const int8_t *rq, const float *sr, int8_t *xq, float *sx,
+                                  int8_t *xb, float *sxb, int32_t *accT, float *T,
+                                  int8_t *tq, float *st)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const float *x = X + m * K;
+        lqo_quant_int(x, K, 7, xq + m * K, &sx[m]);
+        if (r == 0) continue;
+        int8_t *xbrow = (int8_t *)malloc((size_t)K);
+        float *Trow = (float *)malloc(sizeof(float) * (size_t)r);
+        float s_b;
+        lqo_quant_int(x, K, qmax_a, xbrow, &s_b);
+        sxb[m] = s_b;
+        for (int j = 0; j < r; ++j) {
+            int32_t a = 0;
+            for (int64_t k = 0; k < K; ++k) a += (int32_t)xbrow[k] * (int32_t)rq[(int64_t)j * K + k];
+            if (accT) accT[m * r + j] = a;
+            Trow[j] = ((float)a * s_b) * sr[j];
+        }
+        lqo_quant_int(Trow, r, qmax_a, tq + m * r, &st[m]);
+        if (xb) memcpy(xb + m * K, xbrow, (size_t)K);
+        if (T) memcpy(T + m * r, Trow, sizeof(float) * (size_t)r);
+        free(xbrow);
+        free(Trow);
+    }
+}
+
+/* Forward: main 4-bit product with per-group fp32 dequantisation, rank-r expansion, sum.
+   Outputs: acc M x N x G int32 (optional), acc2 M x N int32 (optional), ymain, ybr, y32
+   (fp32, M x N, each optional) and Y (bf16 bits, M x N). */
+LQO_API void lqo_fwd_int(int64_t M, int64_t N, int64_t K, int r, int g, const int8_t *xq,
+                         const float *sx, const int8_t *pq, const float *sw, const int8_t *tq,
+                         const float *st, const int8_t *lq, const float *sl, int32_t *acc,
+                         int32_t *acc2, float *ymain, float *ybr, float *y32, uint16_t *Y)
+{
+    const int64_t G = K / g;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            float t = 0.0f;
+            for (int64_t gi = 0; gi < G; ++gi) {
+                int32_t a = 0;
+                for (int k = 0; k < g; ++k)
+                    a += (int32_t)xq[m * K + gi * g + k] * (int32_t)pq[n * K + gi * g + k];
+                if (acc) acc[(m * N + n) * G + gi] = a;
+                t = fmaf((float)a, sw[n * G + gi], t);
+            }
+            float ym = sx[m] * t;
+            float yb = 0.0f;
+            if (r > 0) {
+                int32_t a2 = 0;
+                for (int j = 0; j < r; ++j) a2 += (int32_t)tq[m * r + j] * (int32_t)lq[n * r + j];
+                if (acc2) acc2[m * N + n] = a2;
+                yb = ((float)a2 * st[m]) * sl[n];
+            } else if (acc2) {
+                acc2[m * N + n] = 0;
+            }
+            float y = ym + yb;
+            if (ymain) ymain[m * N + n] = ym;
+            if (ybr) ybr[m * N + n] = yb;
+            if (y32) y32[m * N + n] = y;
+            if (Y) Y[m * N + n] = bf16_rne(y);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* MX family                                                                              */
+/* ------------------------------------------------------------------------------------ */
+
+/* Outputs: pc N x K E2M1 codes (one per byte), pe N x K/32 E8M0, l8 N x r E4M3, sl N,
+   r8 r x K E4M3, sr r, P (optional). */
+LQO_API void lqo_pack_mx(int64_t N, int64_t K, int r, int residual_from_quantized,
+                         const float *W, const float *L, const float *R, uint8_t *pc,
+                         uint8_t *pe, uint8_t *l8, float *sl, uint8_t *r8, float *sr,
+                         float *P_out)
+{
+    for (int j = 0; j < r; ++j) lqo_quant_fp8(R + (int64_t)j * K, K, r8 + (int64_t)j * K, &sr[j]);
+    for (int64_t n = 0; n < N; ++n) lqo_quant_fp8(L + n * r, r, l8 + n * r, &sl[n]);
+
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        float *P = (float *)malloc(sizeof(float) * (size_t)K);
+        for (int64_t k = 0; k < K; ++k) {
+            double d = 0.0;
+            for (int j = 0; j < r; ++j) {
+                float lh, rh;
+                if (residual_from_quantized) {
+                    lh = lqo_e4m3_decode(l8[n * r + j]) * sl[n];
+                    rh = lqo_e4m3_decode(r8[(int64_t)j * K + k]) * sr[j];
+                } else {
+                    lh = L[n * r + j];
+                    rh = R[(int64_t)j * K + k];
+                }
+                d += (double)lh * (double)rh;
+            }
+            P[k] = (float)((double)W[n * K + k] - d);
+        }
+        lqo_quant_mxfp4(P, K, pc + n * K, pe + n * (K / 32));
+        if (P_out) memcpy(P_out + n * K, P, sizeof(float) * (size_t)K);
+        free(P);
+    }
+}
+
+/* Outputs: xc M x K E2M1 codes, xe M x K/32 E8M0, xb8 M x K E4M3 (optional), sxb M,
+   T M x r fp32 (optional), tq8 M x r E4M3, st M. */
+LQO_API void lqo_quantize_act_mx(int64_t M, int64_t K, int r, const float *X,
+                                 const uint8_t *r8, const float *sr, uint8_t *xc, uint8_t *xe,
+                                 uint8_t *xb8, float *sxb, float *T, uint8_t *tq8, float *st)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const float *x = X + m * K;
+        lqo_quant_mxfp4(x, K, xc + m * K, xe + m * (K / 32));
+        if (r == 0) continue;
+        uint8_t *xbrow = (uint8_t *)malloc((size_t)K);
+        float *Trow = (float *)malloc(sizeof(float) * (size_t)r);
+        float s_b;
+        lqo_quant_fp8(x, K, xbrow, &s_b);
+        sxb[m] = s_b;
+        for (int j = 0; j < r; ++j) {
+            double a = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                a += (double)lqo_e4m3_decode(xbrow[k]) * (double)lqo_e4m3_decode(r8[(int64_t)j * K + k]);
+            Trow[j] = (float)(((double)s_b * (double)sr[j]) * a);
+        }
+        lqo_quant_fp8(Trow, r, tq8 + m * r, &st[m]);
+        if (xb8) memcpy(xb8 + m * K, xbrow, (size_t)K);
+        if (T) memcpy(T + m * r, Trow, sizeof(float) * (size_t)r);
+        free(xbrow);
+        free(Trow);
+    }
+}
+
+LQO_API void lqo_fwd_mx(int64_t M, int64_t N, int64_t K, int r, const uint8_t *xc,
+                        const uint8_t *xe, const uint8_t *pc, const uint8_t *pe,
+                        const uint8_t *tq8, const float *st, const uint8_t *l8, const float *sl,
+                        float *ymain, float *ybr, float *y32, uint16_t *Y)
+{
+    const int64_t B = K / 32;
+    /* element values decoded once up front (decode only; no arithmetic is moved) */
+    float *vw = (float *)malloc(sizeof(float) * (size_t)(N * K));
+    for (int64_t i = 0; i < N * K; ++i) vw[i] = lqo_e2m1_decode(pc[i]);
+    float *vl = (float *)malloc(sizeof(float) * (size_t)(N * (r > 0 ? r : 1)));
+    for (int64_t i = 0; i < N * r; ++i) vl[i] = lqo_e4m3_decode(l8[i]);
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        float *vx = (float *)malloc(sizeof(float) * (size_t)K);
+        for (int64_t k = 0; k < K; ++k) vx[k] = lqo_e2m1_decode(xc[m * K + k]);
+        for (int64_t n = 0; n < N; ++n) {
+            double t = 0.0;
+            for (int64_t b = 0; b < B; ++b) {
+                double d = 0.0;
+                for (int k = 0; k < 32; ++k)
+                    d += (double)vx[32 * b + k] * (double)vw[n * K + 32 * b + k];
+                t += lqo_e8m0_decode(xe[m * B + b]) * lqo_e8m0_decode(pe[n * B + b]) * d;
+            }
+            float ym = (float)t;
+            float yb = 0.0f;
+            if (r > 0) {
+                double a = 0.0;
+                for (int j = 0; j < r; ++j)
+                    a += (double)lqo_e4m3_decode(tq8[m * r + j]) * (double)vl[n * r + j];
+                yb = (float)(((double)st[m] * (double)sl[n]) * a);
+            }
+            float y = ym + yb;
+            if (ymain) ymain[m * N + n] = ym;
+            if (ybr) ybr[m * N + n] = yb;
+            if (y32) y32[m * N + n] = y;
+            if (Y) Y[m * N + n] = bf16_rne(y);
+        }
+        free(vx);
+    }
+    free(vw);
+    free(vl);
+}
+
+LQO_API int lqo_num_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    n = omp_get_max_threads();
+#endif
+    return n;
+}

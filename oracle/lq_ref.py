@@ -1,0 +1,282 @@
+"""ctypes front-end of the CPU oracle (TEST INFRASTRUCTURE, not part of the product).
+
+Only tests, the smoke check and the bench's cpu_baseline leg may import this module.
+It loads ``liblq_oracle.so`` (built from ``lq_oracle.c`` by ``oracle/build.py``) and hands
+numpy arrays to it.  It never touches the HIP library or its Python binding.
+
+Orientation (paper Fig. 1, Eq. 5): X is M x K, W is N x K, L is N x r, R is r x K, Y is M x N.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblq_oracle.so")
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError("oracle library missing: run `python oracle/build.py`")
+        _lib = C.CDLL(_LIB_PATH)
+        _lib.lqo_e2m1_decode.restype = C.c_float
+        _lib.lqo_e2m1_decode.argtypes = [C.c_uint8]
+        _lib.lqo_e4m3_decode.restype = C.c_float
+        _lib.lqo_e4m3_decode.argtypes = [C.c_uint8]
+        _lib.lqo_e8m0_decode.restype = C.c_double
+        _lib.lqo_e8m0_decode.argtypes = [C.c_uint8]
+        _lib.lqo_e2m1_encode.restype = C.c_uint8
+        _lib.lqo_e2m1_encode.argtypes = [C.c_float]
+        _lib.lqo_e4m3_encode.restype = C.c_uint8
+        _lib.lqo_e4m3_encode.argtypes = [C.c_float]
+        _lib.lqo_bf16_rne.restype = C.c_uint16
+        _lib.lqo_bf16_rne.argtypes = [C.c_float]
+        _lib.lqo_num_threads.restype = C.c_int
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+QMAX = {4: 7, 6: 31, 8: 127}
+
+
+def num_threads() -> int:
+    return int(lib().lqo_num_threads())
+
+
+# ---------------------------------------------------------------------------------------
+# element-level entry points (used by the pins)
+# ---------------------------------------------------------------------------------------
+
+def quant_int(v, qmax: int):
+    """One vector, one scale: (codes int8, scale float32)."""
+    v = _f32(v).ravel()
+    q = np.empty(v.size, np.int8)
+    s = np.empty(1, np.float32)
+    lib().lqo_quant_int(_p(v), C.c_int64(v.size), C.c_int(qmax), _p(q), _p(s))
+    return q, s[0]
+
+
+def quant_mxfp4(v):
+    """One row of K values (K % 32 == 0): (E2M1 codes uint8 [K], E8M0 bytes uint8 [K/32])."""
+    v = _f32(v).ravel()
+    assert v.size % 32 == 0
+    c = np.empty(v.size, np.uint8)
+    e = np.empty(v.size // 32, np.uint8)
+    lib().lqo_quant_mxfp4(_p(v), C.c_int64(v.size), _p(c), _p(e))
+    return c, e
+
+
+def quant_fp8(v):
+    v = _f32(v).ravel()
+    c = np.empty(v.size, np.uint8)
+    s = np.empty(1, np.float32)
+    lib().lqo_quant_fp8(_p(v), C.c_int64(v.size), _p(c), _p(s))
+    return c, s[0]
+
+
+def e2m1_decode(codes):
+    return np.array([lib().lqo_e2m1_decode(int(c)) for c in np.asarray(codes).ravel()],
+                    np.float32).reshape(np.shape(codes))
+
+
+def e4m3_decode(codes):
+    return np.array([lib().lqo_e4m3_decode(int(c)) for c in np.asarray(codes).ravel()],
+                    np.float32).reshape(np.shape(codes))
+
+
+def e8m0_decode(codes):
+    return np.array([lib().lqo_e8m0_decode(int(c)) for c in np.asarray(codes).ravel()],
+                    np.float64).reshape(np.shape(codes))
+
+
+def e2m1_encode(u: float) -> int:
+    return int(lib().lqo_e2m1_encode(C.c_float(u)))
+
+
+def e4m3_encode(u: float) -> int:
+    return int(lib().lqo_e4m3_encode(C.c_float(u)))
+
+
+def bf16_rne(f: float) -> int:
+    return int(lib().lqo_bf16_rne(C.c_float(f)))
+
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+# ---------------------------------------------------------------------------------------
+# INT family
+# ---------------------------------------------------------------------------------------
+
+@dataclass
+class PackedInt:
+    N: int
+    K: int
+    r: int
+    g: int
+    pq: np.ndarray   # N x K int8 in [-7,7]
+    sw: np.ndarray   # N x G float32
+    lq: np.ndarray   # N x r int8
+    sl: np.ndarray   # N float32
+    rq: np.ndarray   # r x K int8
+    sr: np.ndarray   # r float32
+    P: np.ndarray    # N x K float32 residual before Q1
+
+
+def pack_int(W, L, R, g: int, br_w_bits: int, residual_from_quantized: bool = True) -> PackedInt:
+    W = _f32(W)
+    N, K = W.shape
+    r = 0 if L is None else int(np.shape(L)[1])
+    assert K % g == 0
+    Lc = _f32(L) if r else np.zeros((N, 0), np.float32)
+    Rc = _f32(R) if r else np.zeros((0, K), np.float32)
+    G = K // g
+    out = PackedInt(N, K, r, g, np.empty((N, K), np.int8), np.empty((N, G), np.float32),
+                    np.empty((N, r), np.int8), np.ones(N, np.float32),
+                    np.empty((r, K), np.int8), np.ones(r, np.float32),
+                    np.empty((N, K), np.float32))
+    lib().lqo_pack_int(C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(g),
+                       C.c_int(QMAX[br_w_bits]), C.c_int(1 if residual_from_quantized else 0),
+                       _p(W), _p(Lc), _p(Rc), _p(out.pq), _p(out.sw), _p(out.lq), _p(out.sl),
+                       _p(out.rq), _p(out.sr), _p(out.P))
+    return out
+
+
+@dataclass
+class ActInt:
+    M: int
+    xq: np.ndarray    # M x K int8 in [-7,7]
+    sx: np.ndarray    # M
+    xb: np.ndarray    # M x K int8
+    sxb: np.ndarray   # M
+    accT: np.ndarray  # M x r int32
+    T: np.ndarray     # M x r float32
+    tq: np.ndarray    # M x r int8
+    st: np.ndarray    # M
+
+
+def quantize_act_int(X, pk: PackedInt, br_a_bits: int) -> ActInt:
+    X = _f32(X)
+    M, K = X.shape
+    assert K == pk.K
+    r = pk.r
+    out = ActInt(M, np.empty((M, K), np.int8), np.empty(M, np.float32),
+                 np.zeros((M, K), np.int8), np.ones(M, np.float32),
+                 np.zeros((M, r), np.int32), np.zeros((M, r), np.float32),
+                 np.zeros((M, r), np.int8), np.ones(M, np.float32))
+    lib().lqo_quantize_act_int(C.c_int64(M), C.c_int64(K), C.c_int(r), C.c_int(QMAX[br_a_bits]),
+                               _p(X), _p(pk.rq), _p(pk.sr), _p(out.xq), _p(out.sx), _p(out.xb),
+                               _p(out.sxb), _p(out.accT), _p(out.T), _p(out.tq), _p(out.st))
+    return out
+
+
+@dataclass
+class FwdOut:
+    acc: Optional[np.ndarray]    # M x N x G int32 (INT only, optional)
+    acc2: Optional[np.ndarray]   # M x N int32 (INT only, optional)
+    ymain: np.ndarray            # M x N float32
+    ybr: np.ndarray              # M x N float32
+    y32: np.ndarray              # M x N float32
+    Y: np.ndarray                # M x N uint16 (bf16 bits)
+
+
+def fwd_int(pk: PackedInt, act: ActInt, want_acc: bool = False) -> FwdOut:
+    M, N, K, r, g = act.M, pk.N, pk.K, pk.r, pk.g
+    G = K // g
+    acc = np.empty((M, N, G), np.int32) if want_acc else None
+    acc2 = np.empty((M, N), np.int32) if want_acc else None
+    out = FwdOut(acc, acc2, np.empty((M, N), np.float32), np.empty((M, N), np.float32),
+                 np.empty((M, N), np.float32), np.empty((M, N), np.uint16))
+    lib().lqo_fwd_int(C.c_int64(M), C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(g),
+                      _p(act.xq), _p(act.sx), _p(pk.pq), _p(pk.sw), _p(act.tq), _p(act.st),
+                      _p(pk.lq), _p(pk.sl), _p(acc), _p(acc2), _p(out.ymain), _p(out.ybr),
+                      _p(out.y32), _p(out.Y))
+    return out
+
+
+# ---------------------------------------------------------------------------------------
+# MX family
+# ---------------------------------------------------------------------------------------
+
+@dataclass
+class PackedMx:
+    N: int
+    K: int
+    r: int
+    pc: np.ndarray   # N x K uint8 E2M1 codes
+    pe: np.ndarray   # N x K/32 uint8 E8M0
+    l8: np.ndarray   # N x r uint8 E4M3
+    sl: np.ndarray
+    r8: np.ndarray   # r x K uint8 E4M3
+    sr: np.ndarray
+    P: np.ndarray
+
+
+def pack_mx(W, L, R, residual_from_quantized: bool = True) -> PackedMx:
+    W = _f32(W)
+    N, K = W.shape
+    r = 0 if L is None else int(np.shape(L)[1])
+    assert K % 32 == 0
+    Lc = _f32(L) if r else np.zeros((N, 0), np.float32)
+    Rc = _f32(R) if r else np.zeros((0, K), np.float32)
+    out = PackedMx(N, K, r, np.empty((N, K), np.uint8), np.empty((N, K // 32), np.uint8),
+                   np.empty((N, r), np.uint8), np.ones(N, np.float32),
+                   np.empty((r, K), np.uint8), np.ones(r, np.float32), np.empty((N, K), np.float32))
+    lib().lqo_pack_mx(C.c_int64(N), C.c_int64(K), C.c_int(r),
+                      C.c_int(1 if residual_from_quantized else 0), _p(W), _p(Lc), _p(Rc),
+                      _p(out.pc), _p(out.pe), _p(out.l8), _p(out.sl), _p(out.r8), _p(out.sr),
+                      _p(out.P))
+    return out
+
+
+@dataclass
+class ActMx:
+    M: int
+    xc: np.ndarray    # M x K uint8 E2M1
+    xe: np.ndarray    # M x K/32 uint8 E8M0
+    xb8: np.ndarray   # M x K uint8 E4M3
+    sxb: np.ndarray
+    T: np.ndarray     # M x r float32
+    tq8: np.ndarray   # M x r uint8 E4M3
+    st: np.ndarray
+
+
+def quantize_act_mx(X, pk: PackedMx) -> ActMx:
+    X = _f32(X)
+    M, K = X.shape
+    r = pk.r
+    out = ActMx(M, np.empty((M, K), np.uint8), np.empty((M, K // 32), np.uint8),
+                np.zeros((M, K), np.uint8), np.ones(M, np.float32), np.zeros((M, r), np.float32),
+                np.zeros((M, r), np.uint8), np.ones(M, np.float32))
+    lib().lqo_quantize_act_mx(C.c_int64(M), C.c_int64(K), C.c_int(r), _p(X), _p(pk.r8), _p(pk.sr),
+                              _p(out.xc), _p(out.xe), _p(out.xb8), _p(out.sxb), _p(out.T),
+                              _p(out.tq8), _p(out.st))
+    return out
+
+
+def fwd_mx(pk: PackedMx, act: ActMx) -> FwdOut:
+    M, N, K, r = act.M, pk.N, pk.K, pk.r
+    out = FwdOut(None, None, np.empty((M, N), np.float32), np.empty((M, N), np.float32),
+                 np.empty((M, N), np.float32), np.empty((M, N), np.uint16))
+    lib().lqo_fwd_mx(C.c_int64(M), C.c_int64(N), C.c_int64(K), C.c_int(r), _p(act.xc), _p(act.xe),
+                     _p(pk.pc), _p(pk.pe), _p(act.tq8), _p(act.st), _p(pk.l8), _p(pk.sl),
+                     _p(out.ymain), _p(out.ybr), _p(out.y32), _p(out.Y))
+    return out

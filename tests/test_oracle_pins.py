@@ -1,0 +1,544 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU).
+
+Each test names the passage or identity it pins.  None of them re-types the oracle's own
+formula: they use exact rational / big-integer arithmetic, numpy's integer matmul, closed
+forms, invariants and the format tables of the OCP MX specification the paper cites.
+"""
+import itertools
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from paper_2604_18117_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "ocp_mx_element_formats.txt")
+
+
+def _golden():
+    out = {"e2m1": None, "e4m3": [], "e8m0": [], "budget": []}
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        t = line.split()
+        if t[0] == "e2m1":
+            out["e2m1"] = [float(v) for v in t[1:]]
+        elif t[0] == "e4m3":
+            out["e4m3"].append((int(t[1], 16), float(t[2])))
+        elif t[0] == "e8m0":
+            out["e8m0"].append((int(t[1]), float(t[2])))
+        elif t[0] == "budget":
+            out["budget"].append(tuple(int(v) for v in t[1:]))
+    return out
+
+
+def _small_int_problem(oracle, seed=0, M=24, K=256, N=40, r=8, g=64, bw=8, ba=8, lr_std=1e-3):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    X[:, rng.choice(K, 3, replace=False)] *= 15
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    L = (rng.standard_normal((N, r)) * lr_std).astype(np.float32)
+    R = (rng.standard_normal((r, K)) * lr_std).astype(np.float32)
+    pk = oracle.pack_int(W, L, R, g, bw)
+    act = oracle.quantize_act_int(X, pk, ba)
+    out = oracle.fwd_int(pk, act, want_acc=True)
+    return X, W, L, R, pk, act, out
+
+
+# --------------------------------------------------------------------------------------
+# element formats (App. A.3, values fixed by the OCP MX specification)
+# --------------------------------------------------------------------------------------
+
+def test_e2m1_table_matches_spec(oracle):
+    g = _golden()
+    dec = oracle.e2m1_decode(np.arange(16, dtype=np.uint8))
+    assert list(dec[:8]) == g["e2m1"]
+    assert list(dec[8:]) == [-v if v else -0.0 for v in g["e2m1"]]
+    assert np.signbit(dec[8])
+
+
+def test_e4m3_e8m0_landmarks(oracle):
+    g = _golden()
+    for code, val in g["e4m3"]:
+        assert float(oracle.e4m3_decode(np.uint8(code))) == val
+    assert np.isnan(oracle.e4m3_decode(np.uint8(0x7F)))
+    for code, val in g["e8m0"]:
+        assert float(oracle.e8m0_decode(np.uint8(code))) == val
+    # monotone over the finite positive codes, all 256 codes round-trip (idempotence of Q)
+    dec = oracle.e4m3_decode(np.arange(127, dtype=np.uint8))
+    assert np.all(np.diff(dec) > 0)
+    for c in range(256):
+        if c & 0x7F == 0x7F:
+            continue
+        v = float(oracle.e4m3_decode(np.uint8(c)))
+        assert oracle.e4m3_encode(v) == c
+
+
+def test_budget_example():
+    # Section 3.3: 16 bits/value x rank 32 = 512 bits/channel => rank 64 at 8 b, 128 at 4 b
+    for bits, rank, budget in _golden()["budget"]:
+        assert bits * rank == budget
+        assert budget // 8 == 64 and budget // 4 == 128
+
+
+def test_e2m1_rounding_is_nearest_even_and_saturating(oracle):
+    vals = [0, 0.5, 1, 1.5, 2, 3, 4, 6]
+    # exact ties go to the code with even mantissa bit
+    ties = {0.25: 0.0, 0.75: 1.0, 1.25: 1.0, 1.75: 2.0, 2.5: 2.0, 3.5: 4.0, 5.0: 4.0}
+    for u, want in ties.items():
+        for sgn in (1, -1):
+            got = float(oracle.e2m1_decode(np.uint8(oracle.e2m1_encode(sgn * u))))
+            assert got == sgn * want
+    # brute force: nearest representable for a dense sweep (non-ties)
+    for u in np.linspace(-9, 9, 7201):
+        got = float(oracle.e2m1_decode(np.uint8(oracle.e2m1_encode(float(u)))))
+        best = min(abs(abs(u) - v) for v in vals)
+        assert abs(abs(got) - abs(u)) <= best + 1e-12
+        assert abs(got) <= 6
+        if got != 0:
+            assert np.sign(got) == np.sign(u)
+
+
+def test_e4m3_rounding_nearest_even_saturating(oracle):
+    dec = oracle.e4m3_decode(np.arange(127, dtype=np.uint8)).astype(np.float64)
+    rng = np.random.default_rng(1)
+    us = np.concatenate([rng.uniform(-460, 460, 3000), rng.uniform(-1, 1, 3000),
+                         rng.uniform(-0.02, 0.02, 2000), [448.0, 464.0, 1e4, -1e4]])
+    for u in us:
+        u = float(np.float32(u))
+        c = oracle.e4m3_encode(u)
+        got = float(oracle.e4m3_decode(np.uint8(c)))
+        best = np.min(np.abs(dec - abs(u)))
+        assert abs(abs(got) - abs(u)) <= best
+        assert abs(got) <= 448
+    # exact ties: midpoint of neighbours goes to the even code
+    for c in range(0, 126):
+        mid = float(np.float32((dec[c] + dec[c + 1]) / 2))
+        if mid == (dec[c] + dec[c + 1]) / 2:
+            assert oracle.e4m3_encode(mid) == (c if c % 2 == 0 else c + 1)
+
+
+def test_mxfp4_block_scale_and_bound(oracle):
+    # App. A.3: blocks of 32, power-of-two scale.  Scale exponent = floor(log2 amax) - 2.
+    rng = np.random.default_rng(2)
+    v = (rng.standard_normal(32 * 40) * np.exp(rng.uniform(-6, 6, 32 * 40))).astype(np.float32)
+    v[64:96] = 0.0
+    codes, e = oracle.quant_mxfp4(v)
+    assert e[2] == 0 and np.all(codes[64:96] & 7 == 0)
+    deq = oracle.e2m1_decode(codes).astype(np.float64).reshape(-1, 32)
+    sc = oracle.e8m0_decode(e)
+    vb = v.astype(np.float64).reshape(-1, 32)
+    for b in range(vb.shape[0]):
+        a = np.abs(vb[b]).max()
+        if a == 0:
+            continue
+        assert sc[b] == 2.0 ** (np.floor(np.log2(a)) - 2)
+        u = vb[b] / sc[b]
+        assert np.abs(u).max() < 8
+        # error bound: half the local spacing below 6, |u|-6 above (saturation)
+        err = np.abs(u - deq[b])
+        spacing = np.where(np.abs(u) < 2, 0.5, np.where(np.abs(u) < 4, 1.0, 2.0))
+        bound = np.where(np.abs(u) <= 6, spacing / 2, np.abs(u) - 6)
+        assert np.all(err <= bound + 1e-12)
+    # idempotence (Section 3.2): Q(deq(Q(v))) gives the same codes and scales, unless the
+    # block maximum dropped below its binade by rounding (then the scale may shrink)
+    back = (deq * sc[:, None]).astype(np.float32).ravel()
+    codes2, e2 = oracle.quant_mxfp4(back)
+    deq2 = oracle.e2m1_decode(codes2).astype(np.float64).reshape(-1, 32) * oracle.e8m0_decode(e2)[:, None]
+    assert np.array_equal(deq2.ravel().astype(np.float32), back)
+
+
+# --------------------------------------------------------------------------------------
+# integer quantiser
+# --------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("qmax", [7, 31, 127])
+def test_int_quantiser_error_bound_and_range(oracle, qmax):
+    # |x - s q| <= s/2 (round to nearest), codes symmetric in [-qmax, qmax], amax maps to qmax
+    rng = np.random.default_rng(qmax)
+    for n in (1, 5, 64, 1152):
+        v = (rng.standard_normal(n) * 10 ** rng.uniform(-3, 3)).astype(np.float32)
+        q, s = oracle.quant_int(v, qmax)
+        assert q.min() >= -qmax and q.max() <= qmax
+        assert abs(int(q[np.argmax(np.abs(v))])) == qmax
+        sd = float(s)
+        assert np.all(np.abs(v.astype(np.float64) - sd * q) <= sd / 2 * (1 + 2 ** -20))
+        # exact-rational statement of "nearest": |qmax*x/amax - q| <= 1/2 (+ fp32 slack)
+        amax = Fraction(float(np.abs(v).max()))
+        for x, qi in zip(v[:64], q[:64]):
+            assert abs(Fraction(float(x)) * qmax / amax - int(qi)) <= Fraction(1, 2) + Fraction(1, 2 ** 18)
+
+
+def test_int_quantiser_ties_to_even_and_zero(oracle):
+    # amax = 2 => 7/amax = 3.5 exactly: x=1 -> 3.5 -> 4 (even); x = 3/7*... use exact cases
+    q, s = oracle.quant_int(np.array([2.0, 1.0, -1.0, 3.0 / 7 * 2], np.float32), 7)
+    assert list(q[:3]) == [7, 4, -4]
+    # amax = 14: inv = 0.5; 5 -> 2.5 -> 2, 7 -> 3.5 -> 4, 3 -> 1.5 -> 2, 1 -> 0.5 -> 0
+    q, s = oracle.quant_int(np.array([14, 5, 7, 3, 1, -1, -3, -5], np.float32), 7)
+    assert list(q) == [7, 2, 4, 2, 0, 0, -2, -2]
+    assert s == np.float32(2.0)
+    q, s = oracle.quant_int(np.zeros(8, np.float32), 7)
+    assert s == np.float32(1.0) and not q.any()
+
+
+@pytest.mark.parametrize("qmax", [7, 31, 127])
+def test_int_quantiser_idempotent(oracle, qmax):
+    # Section 3.2: Q(X) = X on the image of Q.  Codes are reproduced exactly; the scale is
+    # reproduced to one ulp (qmax is not a power of two), exactly for power-of-two scales.
+    rng = np.random.default_rng(10 + qmax)
+    v = rng.standard_normal(512).astype(np.float32)
+    q, s = oracle.quant_int(v, qmax)
+    deq = (q.astype(np.float32) * s)
+    q2, s2 = oracle.quant_int(deq, qmax)
+    assert np.array_equal(q, q2)
+    assert abs(float(s2) - float(s)) <= np.spacing(np.float32(s))
+    v[0] = qmax * 0.25
+    v[1:] = np.clip(v[1:], -1, 1)
+    q, s = oracle.quant_int(v, qmax)
+    assert s == np.float32(0.25)
+    q2, s2 = oracle.quant_int(q.astype(np.float32) * s, qmax)
+    assert s2 == s and np.array_equal(q, q2)
+
+
+def test_scale_and_sign_equivariance(oracle):
+    # scaling by 2^k scales the scale, leaves codes; negation negates codes (symmetric range)
+    rng = np.random.default_rng(3)
+    v = rng.standard_normal(300).astype(np.float32)
+    q, s = oracle.quant_int(v, 7)
+    q2, s2 = oracle.quant_int(v * np.float32(8), 7)
+    q3, s3 = oracle.quant_int(-v, 7)
+    assert np.array_equal(q, q2) and s2 == s * np.float32(8)
+    assert np.array_equal(q3, -q) and s3 == s
+
+
+# --------------------------------------------------------------------------------------
+# whole INT path
+# --------------------------------------------------------------------------------------
+
+def test_integer_contractions_match_numpy_int64(oracle):
+    # the three contractions are textbook integer matrix products
+    X, W, L, R, pk, act, out = _small_int_problem(oracle)
+    M, K = X.shape
+    N, G, g = pk.N, pk.K // pk.g, pk.g
+    xq = act.xq.astype(np.int64).reshape(M, G, g)
+    pq = pk.pq.astype(np.int64).reshape(N, G, g)
+    assert np.array_equal(out.acc, np.einsum("mgk,ngk->mng", xq, pq))
+    assert np.array_equal(act.accT, act.xb.astype(np.int64) @ pk.rq.astype(np.int64).T)
+    assert np.array_equal(out.acc2, act.tq.astype(np.int64) @ pk.lq.astype(np.int64).T)
+
+
+def test_forward_matches_exact_rational_dequant(oracle):
+    # y32 equals the exact value of sx*sum_g acc*sw + acc2*st*sl up to fp32 rounding of the
+    # G+4 operations involved; Y is y32 rounded to bf16 (nearest even).
+    X, W, L, R, pk, act, out = _small_int_problem(oracle, M=6, N=10)
+    G = pk.K // pk.g
+    for m in range(6):
+        for n in range(10):
+            terms = [Fraction(int(out.acc[m, n, gi])) * Fraction(float(pk.sw[n, gi])) for gi in range(G)]
+            main = Fraction(float(act.sx[m])) * sum(terms)
+            br = Fraction(int(out.acc2[m, n])) * Fraction(float(act.st[m])) * Fraction(float(pk.sl[n]))
+            mag = float(Fraction(float(act.sx[m])) * sum(abs(t) for t in terms) + abs(br))
+            assert abs(float(main + br) - float(out.y32[m, n])) <= (G + 4) * 2 ** -24 * mag
+            assert abs(float(main) - float(out.ymain[m, n])) <= (G + 2) * 2 ** -24 * mag
+            assert abs(float(br) - float(out.ybr[m, n])) <= 3 * 2 ** -24 * abs(float(br)) + 1e-45
+    y = out.y32.astype(np.float64)
+    Yf = oracle.bf16_bits_to_f32(out.Y).astype(np.float64)
+    assert np.all(np.abs(Yf - y) <= np.abs(y) * 2 ** -8 + 1e-40)   # half a bf16 ulp
+    # bf16 rounding: exact ties to even
+    assert oracle.bf16_rne(float(np.float32(1.0 + 2 ** -8))) == 0x3F80       # tie -> even (down)
+    assert oracle.bf16_rne(float(np.float32(1.0 + 3 * 2 ** -8))) == 0x3F82   # tie -> even (up)
+    assert oracle.bf16_rne(-2.5) == 0xC020
+
+
+def test_rank0_equals_plain_w4a4(oracle):
+    # rank 0, or L = R = 0: P == W and the branch contributes +0 (bit for bit)
+    X, W, L, R, pk, act, out = _small_int_problem(oracle)
+    pk0 = oracle.pack_int(W, None, None, 64, 8)
+    act0 = oracle.quantize_act_int(X, pk0, 8)
+    out0 = oracle.fwd_int(pk0, act0, want_acc=True)
+    pkz = oracle.pack_int(W, np.zeros_like(L), np.zeros_like(R), 64, 8)
+    actz = oracle.quantize_act_int(X, pkz, 8)
+    outz = oracle.fwd_int(pkz, actz, want_acc=True)
+    assert np.array_equal(pk0.P, W) and np.array_equal(pkz.P, W)
+    assert np.array_equal(pk0.pq, pkz.pq) and np.array_equal(pk0.sw, pkz.sw)
+    assert np.array_equal(out0.Y, outz.Y) and np.array_equal(out0.y32, outz.y32)
+    assert not outz.ybr.any() and not out0.ybr.any()
+    assert np.array_equal(out0.y32, out0.ymain)
+    # and the main product alone is the plain W4A4 product of the dequantised tensors
+    Xd = act0.xq.astype(np.float64) * act0.sx[:, None]
+    Wd = (pk0.pq.astype(np.float64).reshape(pk0.N, -1, 64) * pk0.sw[:, :, None]).reshape(pk0.N, -1)
+    ref = Xd @ Wd.T
+    assert np.max(np.abs(ref - out0.y32)) <= 1e-5 * np.max(np.abs(ref))
+
+
+def _on_grid_problem(rng, M, K, N, r, g, qmax_b):
+    G = K // g
+    pq = rng.integers(-7, 8, size=(N, K)).astype(np.int64)
+    pq.reshape(N, G, g)[:, :, 0] = rng.choice([-7, 7], size=(N, G))
+    sw = 2.0 ** rng.integers(-8, -5, size=(N, G))
+    P0 = (pq.reshape(N, G, g) * sw[:, :, None]).reshape(N, K)
+    lq = rng.integers(-3, 4, size=(N, r)).astype(np.int64)
+    lq[np.arange(N), rng.integers(0, r, N)] = rng.choice([-qmax_b, qmax_b], size=N)
+    rq = rng.integers(-3, 4, size=(r, K)).astype(np.int64)
+    rq[np.arange(r), rng.integers(0, K, r)] = rng.choice([-qmax_b, qmax_b], size=r)
+    sl = 2.0 ** rng.integers(-11, -9, size=N)
+    sr = 2.0 ** rng.integers(-5, -3, size=r)
+    Lh, Rh = lq * sl[:, None], rq * sr[:, None]
+    W = P0 + Lh @ Rh
+    assert np.array_equal(W.astype(np.float32).astype(np.float64), W)
+    # X on both activation grids: entries in {0, +-a}, a = 7*qmax_b*2^k
+    a = 7.0 * qmax_b * 2.0 ** rng.integers(-6, -2, size=M)
+    sign = rng.choice([-1, 0, 1], size=(M, K))
+    sign[:, 0] = 1
+    X = sign * a[:, None]
+    return X, W, Lh, Rh, pq, sw, lq, sl, rq, sr
+
+
+@pytest.mark.parametrize("bits", [8, 6, 4])
+def test_exact_rank_r_residual_is_recovered(oracle, bits):
+    # Fixed point of Section 3.2 / Eq. 5: if W + (-L)R lies in the image of Q1 and L, R in the
+    # image of Q2, packing is lossless: codes recovered, deq(Q1(P)) + L^R^ == W exactly.
+    rng = np.random.default_rng(40 + bits)
+    qb = {8: 127, 6: 31, 4: 7}[bits]
+    M, K, N, r, g = 8, 128, 12, 4, 64
+    X, W, Lh, Rh, pq, sw, lq, sl, rq, sr = _on_grid_problem(rng, M, K, N, r, g, qb)
+    pk = oracle.pack_int(W, Lh, Rh, g, bits)
+    assert np.array_equal(pk.pq, pq) and np.array_equal(pk.sw, sw.astype(np.float32))
+    assert np.array_equal(pk.lq, lq) and np.array_equal(pk.rq, rq)
+    assert np.array_equal(pk.sl, sl.astype(np.float32)) and np.array_equal(pk.sr, sr.astype(np.float32))
+    Wrec = (pk.pq.astype(np.float64).reshape(N, -1, g) * pk.sw[:, :, None]).reshape(N, K) + \
+        (pk.lq * pk.sl[:, None].astype(np.float64)) @ (pk.rq * pk.sr[:, None].astype(np.float64))
+    assert np.array_equal(Wrec, W)
+    # output side: the only loss left is the re-quantisation of T = X R^T (error <= st/2 each)
+    ba = 8 if bits != 6 else 6
+    qa = {8: 127, 6: 31}[ba]
+    if ba != bits:
+        # X must sit on the branch-activation grid too: rebuild with a = 7*qa*2^k
+        a = 7.0 * qa * 2.0 ** rng.integers(-6, -2, size=M)
+        X = np.sign(X) * a[:, None]
+    act = oracle.quantize_act_int(X, pk, ba)
+    assert np.array_equal(act.xq.astype(np.float64) * act.sx[:, None], X)
+    assert np.array_equal(act.xb.astype(np.float64) * act.sxb[:, None], X)
+    out = oracle.fwd_int(pk, act)
+    exact = X @ W.T
+    gap = (act.st[:, None].astype(np.float64) / 2) * np.abs(Lh).sum(1)[None, :]
+    assert np.all(np.abs(out.y32 - exact) <= gap * (1 + 1e-6) + 1e-6 * np.abs(exact).max())
+
+
+def test_single_component_branch_is_lossless(oracle):
+    # r = 1: every T row is on its own grid (T/st = +-qmax), so Y = X W^T up to fp32 rounding
+    rng = np.random.default_rng(7)
+    M, K, N, g = 8, 128, 12, 64
+    X, W, Lh, Rh, *_ = _on_grid_problem(rng, M, K, N, 1, g, 127)
+    pk = oracle.pack_int(W, Lh, Rh, g, 8)
+    act = oracle.quantize_act_int(X, pk, 8)
+    assert np.all(np.abs(act.tq) == 127)
+    out = oracle.fwd_int(pk, act)
+    exact = X @ W.T
+    assert np.max(np.abs(out.y32 - exact)) <= 4e-7 * np.max(np.abs(exact)) * 8
+
+
+def test_residual_definition_and_flag(oracle):
+    # Fig. 1: P = W - Q2(L)Q2(R) (dequantised factors); flag 0 gives P = W - L R.
+    X, W, L, R, pk, act, out = _small_int_problem(oracle, lr_std=0.05)
+    Lh = pk.lq.astype(np.float64) * pk.sl[:, None]
+    Rh = pk.rq.astype(np.float64) * pk.sr[:, None]
+    assert np.max(np.abs(pk.P - (W - Lh @ Rh))) <= 2 ** -23 * np.max(np.abs(W)) * 2
+    pk2 = oracle.pack_int(W, L, R, 64, 8, residual_from_quantized=False)
+    assert np.max(np.abs(pk2.P - (W.astype(np.float64) - L.astype(np.float64) @ R))) <= 2 ** -23 * np.max(np.abs(W)) * 2
+    assert not np.array_equal(pk.P, pk2.P)
+    # sign convention: the branch is ADDED.  W_eff = deq(Q1 P) + L^R^ is closer to W than deq(Q1 P)
+    Pd = (pk.pq.astype(np.float64).reshape(pk.N, -1, 64) * pk.sw[:, :, None]).reshape(pk.N, -1)
+    assert np.linalg.norm(Pd + Lh @ Rh - W) < 0.5 * np.linalg.norm(Pd - Lh @ Rh - W)
+
+
+def test_error_upper_bound_eq2(oracle):
+    # Eq. 2: ||XW - Q(X)Q(W)|| <= ||X-Q(X)|| ||W|| + ||Q(X)|| ||W-Q(W)||  (Frobenius)
+    X, W, L, R, pk, act, out = _small_int_problem(oracle)
+    pk0 = oracle.pack_int(W, None, None, 64, 8)
+    Xd = act.xq.astype(np.float64) * act.sx[:, None]
+    Wd = (pk0.pq.astype(np.float64).reshape(pk0.N, -1, 64) * pk0.sw[:, :, None]).reshape(pk0.N, -1)
+    fro = np.linalg.norm
+    lhs = fro(X.astype(np.float64) @ W.T.astype(np.float64) - Xd @ Wd.T)
+    rhs = fro(X - Xd) * fro(W) + fro(Xd) * fro(W - Wd)
+    assert lhs <= rhs
+    # and the low-rank branch reduces the weight-side error when L R is the weight's own error
+    E = (W - Wd).astype(np.float64)
+    U, S, Vt = np.linalg.svd(E, full_matrices=False)
+    r = 8
+    Lc, Rc = (U[:, :r] * S[:r]).astype(np.float32), Vt[:r].astype(np.float32)
+    pkc = oracle.pack_int(W, Lc, Rc, 64, 8)
+    Pd = (pkc.pq.astype(np.float64).reshape(pkc.N, -1, 64) * pkc.sw[:, :, None]).reshape(pkc.N, -1)
+    Weff = Pd + (pkc.lq * pkc.sl[:, None].astype(np.float64)) @ (pkc.rq * pkc.sr[:, None].astype(np.float64))
+    assert fro(Weff - W) < fro(Wd - W) * 1.05
+
+
+def test_permutation_equivariance(oracle):
+    X, W, L, R, pk, act, out = _small_int_problem(oracle)
+    rng = np.random.default_rng(5)
+    pm, pn = rng.permutation(X.shape[0]), rng.permutation(W.shape[0])
+    # tokens are independent rows; output channels are independent columns
+    act_p = oracle.quantize_act_int(X[pm], pk, 8)
+    assert np.array_equal(oracle.fwd_int(pk, act_p).Y, out.Y[pm])
+    pk_p = oracle.pack_int(W[pn], L[pn], R, 64, 8)
+    assert np.array_equal(oracle.fwd_int(pk_p, act).Y, out.Y[:, pn])
+    # permuting K inside a group, jointly on X, W, R, leaves all accumulators unchanged
+    K = X.shape[1]
+    pk_idx = np.concatenate([g0 + rng.permutation(64) for g0 in range(0, K, 64)])
+    pk_k = oracle.pack_int(W[:, pk_idx], L, R[:, pk_idx], 64, 8)
+    act_k = oracle.quantize_act_int(X[:, pk_idx], pk_k, 8)
+    out_k = oracle.fwd_int(pk_k, act_k, want_acc=True)
+    assert np.array_equal(out_k.acc, out.acc) and np.array_equal(out_k.acc2, out.acc2)
+    assert np.array_equal(out_k.Y, out.Y)
+
+
+def test_power_of_two_scaling_and_negation(oracle):
+    X, W, L, R, pk, act, out = _small_int_problem(oracle)
+    a4 = oracle.quantize_act_int(X * np.float32(4), pk, 8)
+    assert np.array_equal(a4.xq, act.xq) and np.array_equal(a4.tq, act.tq)
+    assert np.array_equal(a4.sx, act.sx * 4) and np.array_equal(a4.st, act.st * 4)
+    assert np.array_equal(oracle.fwd_int(pk, a4).y32, out.y32 * 4)
+    an = oracle.quantize_act_int(-X, pk, 8)
+    assert np.array_equal(oracle.fwd_int(pk, an).y32, -out.y32)
+
+
+def test_accumulator_ranges(oracle):
+    # worst cases stay far inside int32: |acc_g| <= 49 g, |accT| <= 127^2 K, |acc2| <= 127^2 r
+    M, K, N, r, g = 2, 4608, 2, 128, 128
+    X = np.full((M, K), 3.0, np.float32)
+    W = np.full((N, K), -0.5, np.float32)
+    L = np.full((N, r), 1.0, np.float32)
+    R = np.full((r, K), 1.0, np.float32)
+    pk = oracle.pack_int(W, L * 0, R, g, 8)
+    act = oracle.quantize_act_int(X, pk, 8)
+    out = oracle.fwd_int(pk, act, want_acc=True)
+    assert np.all(out.acc == -49 * g) and 49 * 128 < 2 ** 22
+    assert np.all(act.accT == 127 * 127 * K) and 127 * 127 * 4608 < 2 ** 31
+    pk2 = oracle.pack_int(W, L, R, g, 8)        # all-equal T row => tq = 127, lq = 127
+    act2 = oracle.quantize_act_int(X, pk2, 8)
+    out2 = oracle.fwd_int(pk2, act2, want_acc=True)
+    assert np.all(act2.tq == 127) and np.all(pk2.lq == 127)
+    assert np.all(out2.acc2 == 127 * 127 * r)
+
+
+def test_closed_form_constants(oracle):
+    # X = c 1, W = w 1, no branch: codes all +-7, acc = 49 g, y = K c w up to fp32 rounding
+    M, K, N, g = 3, 256, 5, 64
+    c, w = 0.75, -0.0123
+    pk = oracle.pack_int(np.full((N, K), w, np.float32), None, None, g, 8)
+    act = oracle.quantize_act_int(np.full((M, K), c, np.float32), pk, 8)
+    out = oracle.fwd_int(pk, act, want_acc=True)
+    assert np.all(act.xq == 7) and np.all(pk.pq == -7) and np.all(out.acc == -49 * g)
+    want = K * float(np.float32(c)) * float(np.float32(w))
+    assert np.max(np.abs(out.y32 - want)) <= 8 * 2 ** -24 * abs(want)
+
+
+def test_exhaustive_tiny_int(oracle):
+    # all 15^2 x 15^2 on-grid pairs with K = g = 2 ... 3 checked against Python integers
+    # (rows that contain a +-7 are on the grid of Q, so codes must come back unchanged)
+    sx, swt = 0.25, 2.0 ** -5
+    codes = range(-7, 8)
+    rows = [c for c in itertools.product(codes, repeat=2) if max(abs(v) for v in c) == 7]
+    X = np.array(rows, np.float32) * np.float32(sx)
+    W = np.array(rows, np.float32) * np.float32(swt)
+    pk = oracle.pack_int(W, None, None, 2, 8)
+    act = oracle.quantize_act_int(X, pk, 8)
+    out = oracle.fwd_int(pk, act, want_acc=True)
+    assert np.array_equal(act.xq, np.array(rows)) and np.array_equal(pk.pq, np.array(rows))
+    assert np.all(act.sx == np.float32(sx)) and np.all(pk.sw == np.float32(swt))
+    for i, a in enumerate(rows):
+        for j, b in enumerate(rows):
+            dot = a[0] * b[0] + a[1] * b[1]
+            assert out.acc[i, j, 0] == dot
+            assert out.y32[i, j] == np.float32(dot * sx * swt)   # exact: small dyadic numbers
+    # off-grid rows (max |code| < 7): nearest-integer property in exact rationals
+    rows3 = list(itertools.product(range(-3, 4), repeat=3))
+    X3 = np.array(rows3, np.float32)
+    pk3 = oracle.pack_int(np.ones((1, 3), np.float32), None, None, 3, 8)
+    act3 = oracle.quantize_act_int(X3, pk3, 8)
+    for row, q, s in zip(rows3, act3.xq, act3.sx):
+        amax = max(abs(v) for v in row)
+        if amax == 0:
+            assert s == 1 and not q.any()
+            continue
+        assert s == np.float32(amax) / np.float32(7)
+        for v, qi in zip(row, q):
+            assert abs(Fraction(7 * v, amax) - int(qi)) <= Fraction(1, 2) + Fraction(1, 10 ** 6)
+
+
+# --------------------------------------------------------------------------------------
+# whole MX path
+# --------------------------------------------------------------------------------------
+
+def test_mx_forward_against_exact_rationals(oracle):
+    rng = np.random.default_rng(11)
+    M, K, N, r = 5, 64, 6, 4
+    X = wl.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    L = (rng.standard_normal((N, r)) * 1e-3).astype(np.float32)
+    R = (rng.standard_normal((r, K)) * 1e-3).astype(np.float32)
+    pk = oracle.pack_mx(W, L, R)
+    act = oracle.quantize_act_mx(X, pk)
+    out = oracle.fwd_mx(pk, act)
+    F = Fraction
+    vx = oracle.e2m1_decode(act.xc)
+    vw = oracle.e2m1_decode(pk.pc)
+    sx = oracle.e8m0_decode(act.xe)
+    sw = oracle.e8m0_decode(pk.pe)
+    t8 = oracle.e4m3_decode(act.tq8)
+    l8 = oracle.e4m3_decode(pk.l8)
+    x8 = oracle.e4m3_decode(act.xb8)
+    r8 = oracle.e4m3_decode(pk.r8)
+    for m in range(M):
+        for j in range(r):
+            T = F(float(act.sxb[m])) * F(float(pk.sr[j])) * sum(F(float(a)) * F(float(b)) for a, b in zip(x8[m], r8[j]))
+            assert abs(float(T) - float(act.T[m, j])) <= 2 ** -22 * abs(float(T))
+        for n in range(N):
+            main = sum(F(float(sx[m, b])) * F(float(sw[n, b])) *
+                       sum(F(float(vx[m, 32 * b + k])) * F(float(vw[n, 32 * b + k])) for k in range(32))
+                       for b in range(K // 32))
+            br = F(float(act.st[m])) * F(float(pk.sl[n])) * sum(F(float(a)) * F(float(b)) for a, b in zip(t8[m], l8[n]))
+            assert out.ymain[m, n] == np.float32(float(main))      # single rounding of an exact sum
+            assert abs(float(br) - float(out.ybr[m, n])) <= 2 ** -22 * abs(float(br))
+            assert out.y32[m, n] == np.float32(out.ymain[m, n]) + np.float32(out.ybr[m, n])
+    # MX quantisation error of X is bounded per block (half spacing unless saturated)
+    Xd = vx.astype(np.float64).reshape(M, -1, 32) * sx[:, :, None]
+    err = np.abs(Xd.reshape(M, K) - X)
+    assert np.all(err <= np.repeat(sx, 32, axis=1) * 2.0)
+    # FP8 branch codes: relative error <= 2^-4 for normal values, amax -> 448
+    assert np.all(np.abs(x8).max(axis=1) == 448)
+    big = np.abs(X) > np.abs(X).max(axis=1, keepdims=True) * 2.0 ** -6
+    rel = np.abs(x8 * act.sxb[:, None] - X) / np.abs(X)
+    assert np.all(rel[big] <= 2 ** -4 * (1 + 1e-6))
+
+
+def test_mx_rank0_and_residual(oracle):
+    rng = np.random.default_rng(12)
+    M, K, N, r = 4, 96, 5, 4
+    X = wl.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    pk0 = oracle.pack_mx(W, None, None)
+    pkz = oracle.pack_mx(W, np.zeros((N, r), np.float32), np.zeros((r, K), np.float32))
+    assert np.array_equal(pk0.P, W) and np.array_equal(pkz.pc, pk0.pc) and np.array_equal(pkz.pe, pk0.pe)
+    o0 = oracle.fwd_mx(pk0, oracle.quantize_act_mx(X, pk0))
+    oz = oracle.fwd_mx(pkz, oracle.quantize_act_mx(X, pkz))
+    assert np.array_equal(o0.Y, oz.Y) and not oz.ybr.any()
+    # on-grid P (E2M1 values times power-of-two block scales) is recovered exactly
+    codes = rng.integers(0, 16, size=(N, K)).astype(np.uint8)
+    codes.reshape(N, -1, 32)[:, :, 0] = 7          # a 6 in each block fixes the scale
+    sc = 2.0 ** rng.integers(-9, -5, size=(N, K // 32))
+    Wg = (oracle.e2m1_decode(codes).astype(np.float64).reshape(N, -1, 32) * sc[:, :, None]).reshape(N, K)
+    pkg = oracle.pack_mx(Wg.astype(np.float32), None, None)
+    assert np.array_equal(oracle.e2m1_decode(pkg.pc), oracle.e2m1_decode(codes))
+    assert np.array_equal(oracle.e8m0_decode(pkg.pe), sc)   # floor(log2(6 s)) - 2 = log2 s
+
+
+def test_workload_generator_is_seeded():
+    l = wl.shrink(wl.LAYERS["c2_qkv"], M=16, K=128, N=64, r=16)
+    a, b = wl.make_inputs(l), wl.make_inputs(l)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    X = a[0]
+    assert np.array_equal(wl.round_to_bf16(X), X)
+    assert [x.shape for x in a] == [(16, 128), (64, 128), (64, 16), (16, 128)]
