@@ -1,0 +1,143 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: per-call activation step + fused forward of one quantized
+linear layer with a quantized low-rank branch, on synthetic DiT-shaped layers, one MI355X.
+
+A "step" is one pass of the whole per-call path (lq_quantize_act + lq_linear_lowrank_fwd)
+over one batch of M tokens already resident in HBM; weight packing is offline and untimed.
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_TFLOPS = 5033.0   # MI355X dense FP8 / INT8 matrix peak (the main product runs on the FP8 pipe)
+
+
+def layer_ops(l):
+    return 2.0 * l.M * l.N * l.K + 2.0 * l.M * l.r * l.K + 2.0 * l.M * l.N * l.r
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2_qkv", help="layer name from workloads.LAYERS")
+    ap.add_argument("--oracle-seconds", type=float, default=15.0, help="CPU budget of the oracle leg (0 = skip)")
+    ap.add_argument("--sets", type=int, default=4, help="distinct buffer sets rotated through")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (the path shards over tokens with no collective; "
+              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2604_18117_amd import binding as lq
+    from paper_2604_18117_amd import workloads as wl
+    from tests.gpu_util import to_dev_x
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    layer = wl.LAYERS[args.workload]
+    X, W, L, R = wl.make_inputs(layer)
+    cfg = lq.config_for_layer(layer)
+    M = layer.M
+    packed = lq.lq_pack_weights(cfg, torch.from_numpy(W).cuda(), torch.from_numpy(L).cuda(),
+                                torch.from_numpy(R).cuda())
+    nsets = max(1, args.sets)
+    rng = np.random.default_rng(123)
+    Xs, acts, Ys = [], [], []
+    for i in range(nsets):
+        Xi = X if i == 0 else X[rng.permutation(M)]      # same distribution, different bytes
+        Xs.append(to_dev_x(Xi, layer.x_dtype))
+        acts.append(torch.empty(lq.lq_act_sizes(cfg, M), dtype=torch.uint8, device="cuda"))
+        Ys.append(torch.empty((M, layer.N), dtype=torch.bfloat16, device="cuda"))
+
+    def step(i):
+        k = i % nsets
+        lq.lq_quantize_act(cfg, packed, Xs[k], act=acts[k])
+        lq.lq_linear_lowrank_fwd(cfg, packed, acts[k], M, Y=Ys[k])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps, whole-path wall clock --------------------------------
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        k = i % nsets
+        ev[i][0].record()
+        lq.lq_quantize_act(cfg, packed, Xs[k], act=acts[k])
+        ev[i][1].record()
+        lq.lq_linear_lowrank_fwd(cfg, packed, acts[k], M, Y=Ys[k])
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / K
+    act_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    fwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    ops = layer_ops(layer)
+    fwd_ops = 2.0 * layer.M * layer.N * (layer.K + layer.r)
+    tops = ops / (ms_step * 1e-3) / 1e12
+    fwd_tops = fwd_ops / (fwd_ms * 1e-3) / 1e12
+    # activation kernel: algorithmic HBM bytes = X in, 4-bit codes + scales + tq out
+    xb = 2 if layer.x_dtype == "bf16" else 4
+    act_bytes = layer.M * layer.K * (xb + 0.5) + layer.M * (layer.r + 8)
+    act_gbs = act_bytes / (act_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "fused W4A4+low-rank linear TOPS and % of MFMA roofline on MI355X",
+        "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int4 codes on the fp8 MFMA pipe, int8 branch, fp32 dequant",
+        "data": "synthetic",
+        "config": {"workload": layer.name, "M": layer.M, "K": layer.K, "N": layer.N, "rank": layer.r,
+                   "main": f"W4A4 INT4 g{layer.g}", "branch": f"W{layer.br_w_bits}A{layer.br_a_bits}",
+                   "x_dtype": layer.x_dtype, "buffer_sets": nsets},
+        "roofline": {"bound": "mfma", "kernel": "fwd_int_kernel", "achieved": round(fwd_tops, 2),
+                     "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(fwd_tops / PEAK_MFMA_TFLOPS, 4),
+                     "traffic": None, "avg_kernel_ms": round(fwd_ms, 5)},
+        "act_kernel": {"bound": "hbm", "avg_kernel_ms": round(act_ms, 5), "achieved": round(act_gbs, 1),
+                       "peak": 8000.0, "unit": "GB/s", "frac": round(act_gbs / 8000.0, 4)},
+    }
+
+    # ---- CPU oracle leg (reported baseline only): bounded row sample of the same workload -----
+    if args.oracle_seconds > 0:
+        from oracle import lq_ref
+        pk = lq_ref.pack_int(W, L, R, layer.g, layer.br_w_bits)
+        probe = 16
+        t = time.perf_counter()
+        a = lq_ref.quantize_act_int(X[:probe], pk, layer.br_a_bits)
+        lq_ref.fwd_int(pk, a)
+        dt = time.perf_counter() - t
+        rows = int(max(probe, min(M, probe * args.oracle_seconds / max(dt, 1e-6))))
+        rows = max(16, rows // 16 * 16)
+        t = time.perf_counter()
+        a = lq_ref.quantize_act_int(X[:rows], pk, layer.br_a_bits)
+        o = lq_ref.fwd_int(pk, a)
+        dt = time.perf_counter() - t
+        cpu_tops = ops * (rows / M) / dt / 1e12
+        # parity spot check of the bench's own launch against those rows
+        from tests.gpu_util import bf16_to_bits
+        lq.lq_quantize_act(cfg, packed, Xs[0], act=acts[0])
+        lq.lq_linear_lowrank_fwd(cfg, packed, acts[0], M, Y=Ys[0])
+        torch.cuda.synchronize()
+        same = bool(np.array_equal(bf16_to_bits(Ys[0][:rows]), o.Y))
+        out["cpu_baseline"] = {"value": round(cpu_tops, 5), "unit": "TOPS", "cores": lq_ref.num_threads(),
+                               "kind": "oracle", "seconds": round(dt, 2),
+                               "sample": f"first {rows} of {M} token rows, activation step + forward, "
+                                         f"scaled linearly in M", "gpu_rows_bit_exact": same}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,158 @@
+/*
+ * lq.h -- C ABI of the MI355X (gfx950) library for the forward pass of a fully quantized
+ * linear layer with a quantized low-rank error-compensation branch (paper Fig. 1, Eq. 5):
+ *
+ *     P = W - deq(Q2(L)) deq(Q2(R))                              (offline, lq_pack_weights)
+ *     Y = deq(Q1(X) Q1(P)^T) + deq(Q2( Q2(X) Q2(R)^T ) Q2(L)^T)  (per call)
+ *
+ * Orientation, all row-major: X is M x K (tokens x in-features), W is N x K, L is N x r,
+ * R is r x K, Y is M x N.  In the paper's notation (Section 3.1/3.2: X in R^{m x d},
+ * W in R^{d x n}, L in R^{d x rho}, R in R^{rho x n}) this is M=m, K=d, N=n, W = W_paper^T,
+ * L = R_paper^T, R = L_paper^T.
+ *
+ * Q1 is the 4-bit main format, Q2 the sub-16-bit branch format (Section 3.3).  Families:
+ *   INT : Q1 = signed INT4, symmetric [-7,7], round-to-nearest-even; weights carry one fp32
+ *         scale per group of `main_w_group` values along K (SINT4-style blocks, App. A.3),
+ *         activations one fp32 scale per token.  Q2 = signed INT8 / INT6 / INT4 with one
+ *         scale per token (activations, intermediate) or per row of L / R (weights).
+ *         Integer accumulation, fp32 dequantisation.
+ *   MX  : Q1 = MXFP4 (E2M1 elements, blocks of 32 along K, E8M0 scale, App. A.3) for both
+ *         operands; Q2 = FP8 E4M3 with one fp32 scale per token / per row.
+ *
+ * General rules
+ *   - Every pointer named "device" is GPU memory of the current HIP device, owned by the
+ *     caller; the library never allocates, frees or keeps device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All calls are
+ *     asynchronous on it and never synchronise.
+ *   - Argument errors are found on the host before anything is launched and reported by the
+ *     return value; a failed launch returns LQ_ERR_DEVICE.  Nothing throws.
+ *   - Inputs must be finite (NaN / Inf give undefined codes).
+ *   - Shape contract: K % 64 == 0, K % main_w_group == 0, N % 64 == 0,
+ *     rank in {0,16,32,64,128}, 1 <= M, row strides >= row lengths.
+ *   - Calls are deterministic: no atomics, no split-K; repeated calls give identical bits.
+ */
+#ifndef LQ_H
+#define LQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LQ_OK = 0,
+    LQ_ERR_NULL = 1,             /* a required pointer is NULL                           */
+    LQ_ERR_SHAPE = 2,            /* a dimension violates the shape contract              */
+    LQ_ERR_UNSUPPORTED = 3,      /* format combination not implemented                   */
+    LQ_ERR_ALIGN = 4,            /* a pointer or stride is not aligned as documented     */
+    LQ_ERR_BUFFER_TOO_SMALL = 5, /* caller's buffer smaller than lq_*_sizes reports       */
+    LQ_ERR_DEVICE = 6            /* the HIP runtime rejected a launch                    */
+} lq_status;
+
+typedef enum {
+    LQ_INT4 = 0,
+    LQ_INT6 = 1,
+    LQ_INT8 = 2,
+    LQ_MXFP4_E2M1 = 3,
+    LQ_FP8_E4M3 = 4
+} lq_fmt;
+
+typedef enum { LQ_F32 = 0, LQ_BF16 = 1 } lq_dtype;
+
+/* Problem statement of one layer (Section 3.1-3.3: W, L, R, rank, bit widths, block size,
+   scale granularity).  Plain data; pass by pointer. */
+typedef struct {
+    int64_t N, K;                    /* out-features, in-features                                 */
+    int32_t rank;                    /* r; 0 = no branch (plain W4A4)                            */
+    int32_t main_w;                  /* lq_fmt: LQ_INT4 | LQ_MXFP4_E2M1                          */
+    int32_t main_a;                  /* lq_fmt: must equal main_w                                 */
+    int32_t main_w_group;            /* INT: 64 | 128 values along K per weight scale; MX: 32    */
+    int32_t main_a_group;            /* INT: 0 = one scale per token; MX: 32                     */
+    int32_t br_w;                    /* lq_fmt of Q2(L), Q2(R): INT8|INT6|INT4, or FP8 (MX)      */
+    int32_t br_a;                    /* lq_fmt of Q2(X), Q2(X R^T): INT8|INT6, or FP8 (MX)       */
+    int32_t residual_from_quantized; /* 1: P = W - deq(Q2 L) deq(Q2 R) (Fig. 1); 0: P = W - L R  */
+    int32_t x_dtype;                 /* lq_dtype of X                                             */
+    int32_t reserved;                /* must be 0                                                 */
+} lq_config;
+
+/* Optional parity taps.  Every member may be NULL.  Device pointers, plain row-major. */
+typedef struct {
+    int8_t  *xb;    /* M x K   branch activation codes (INT) / E4M3 bytes (MX)                  */
+    float   *sxb;   /* M       branch activation scales                                        */
+    int32_t *accT;  /* M x r   integer accumulators of Q2(X) Q2(R)^T (INT only)                 */
+    float   *T;     /* M x r   dequantised intermediate before re-quantisation                  */
+} lq_act_debug;
+
+typedef struct {
+    int32_t *acc;   /* M x N x G   per-group accumulators of the main product (INT only)       */
+    int32_t *acc2;  /* M x N       accumulators of the rank-r expansion (INT only)             */
+    float   *y32;   /* M x N       fp32 sum before the bf16 rounding                            */
+} lq_fwd_debug;
+
+/* Plain row-major views of a packed weight blob / an activation blob (device pointers,
+   any may be NULL).  INT family: codes are int8; MX family: pq / xq hold one E2M1 code per
+   byte, pe / xe the E8M0 bytes (N x K/32, M x K/32), lq / rq / tq E4M3 bytes. */
+typedef struct {
+    int8_t  *pq;    /* N x K                                                                   */
+    float   *sw;    /* N x (K / main_w_group)     (INT)                                        */
+    uint8_t *pe;    /* N x (K / 32)               (MX)                                         */
+    int8_t  *lq;    /* N x r                                                                   */
+    float   *sl;    /* N                                                                       */
+    int8_t  *rq;    /* r x K                                                                   */
+    float   *sr;    /* r                                                                       */
+} lq_weights_view;
+
+typedef struct {
+    int8_t  *xq;    /* M x K                                                                   */
+    float   *sx;    /* M                          (INT)                                        */
+    uint8_t *xe;    /* M x (K / 32)               (MX)                                         */
+    int8_t  *tq;    /* M x r                                                                   */
+    float   *st;    /* M                                                                       */
+} lq_act_view;
+
+const char *lq_status_string(lq_status s);
+
+/* Bytes of the packed weight blob for `cfg`.  Host-only. */
+lq_status lq_packed_sizes(const lq_config *cfg, size_t *packed_bytes);
+
+/* Offline packing (Fig. 1; Eq. 5): quantise L and R with Q2, form the residual P, quantise
+   it with Q1 and lay everything out for the kernels.
+   W (N x K), L (N x r), R (r x K): device, fp32, dense row-major; L and R may be NULL iff
+   rank == 0.  `packed`: device, 256-byte aligned, at least packed_bytes.  Contents are an
+   opaque function of cfg and the inputs; read them back with lq_unpack_weights. */
+lq_status lq_pack_weights(const lq_config *cfg, const float *W, const float *L, const float *R,
+                          void *packed, size_t packed_bytes, void *stream);
+
+/* Bytes of the activation blob for M tokens.  Host-only. */
+lq_status lq_act_sizes(const lq_config *cfg, int64_t M, size_t *act_bytes);
+
+/* Per-call activation step (Section 3.4; low-rank branch of Fig. 1): one pass over X emits the
+   4-bit main codes and scales, quantises X for the branch, contracts it with Q2(R) and
+   re-quantises the M x r result per token.
+   X: device, M x K of cfg.x_dtype, row stride ldx elements (ldx >= K, ldx*elemsize % 16 == 0,
+   X 16-byte aligned).  `packed`: blob written by lq_pack_weights for the same cfg.
+   `act`: device, 256-byte aligned, at least act_bytes.  dbg may be NULL. */
+lq_status lq_quantize_act(const lq_config *cfg, const void *packed, const void *X, int64_t M,
+                          int64_t ldx, void *act, size_t act_bytes, const lq_act_debug *dbg,
+                          void *stream);
+
+/* Forward (Fig. 1): main 4-bit product with per-group dequantisation, rank-r expansion of the
+   re-quantised intermediate, sum, bf16 rounding.
+   Y: device, M x N bf16, row stride ldy elements (ldy >= N, ldy even, Y 4-byte aligned).
+   dbg may be NULL (production); with dbg the same kernel also writes the taps. */
+lq_status lq_linear_lowrank_fwd(const lq_config *cfg, const void *packed, const void *act,
+                                int64_t M, void *Y, int64_t ldy, const lq_fwd_debug *dbg,
+                                void *stream);
+
+/* Decode the opaque blobs into plain row-major arrays (test / inspection helpers). */
+lq_status lq_unpack_weights(const lq_config *cfg, const void *packed, const lq_weights_view *out,
+                            void *stream);
+lq_status lq_unpack_act(const lq_config *cfg, const void *act, int64_t M, const lq_act_view *out,
+                        void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LQ_H */

@@ -306,7 +306,7 @@ LQO_API void lqo_fwd_int(int64_t M, int64_t N, int64_t K, int r, int g, const in
             } else if (acc2) {
                 acc2[m * N + n] = 0;
             }
-            float y = ym + yb;
+            float y = fmaf(sx[m], t, yb); /* sum node of Fig. 1: one rounding for scale-and-add */
             if (ymain) ymain[m * N + n] = ym;
             if (ybr) ybr[m * N + n] = yb;
             if (y32) y32[m * N + n] = y;

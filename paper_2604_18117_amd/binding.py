@@ -1,0 +1,250 @@
+"""Thin ctypes binding of liblq.so: argument marshalling only, same names as include/lq.h.
+
+PyTorch is used for device memory and the current stream, nothing else: every step of the
+path runs in the library's kernels.  Importing this module fails loudly when the HIP library
+has not been built (``python paper_2604_18117_amd/build.py``); there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblq.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(f"{_LIB_PATH} is missing: build it with `python paper_2604_18117_amd/build.py`")
+_lib = C.CDLL(_LIB_PATH)
+
+LQ_OK = 0
+LQ_ERR_NULL, LQ_ERR_SHAPE, LQ_ERR_UNSUPPORTED, LQ_ERR_ALIGN, LQ_ERR_BUFFER_TOO_SMALL, LQ_ERR_DEVICE = range(1, 7)
+LQ_INT4, LQ_INT6, LQ_INT8, LQ_MXFP4_E2M1, LQ_FP8_E4M3 = range(5)
+LQ_F32, LQ_BF16 = 0, 1
+_INT_FMT = {4: LQ_INT4, 6: LQ_INT6, 8: LQ_INT8}
+
+
+class lq_config(C.Structure):
+    _fields_ = [("N", C.c_int64), ("K", C.c_int64), ("rank", C.c_int32), ("main_w", C.c_int32),
+                ("main_a", C.c_int32), ("main_w_group", C.c_int32), ("main_a_group", C.c_int32),
+                ("br_w", C.c_int32), ("br_a", C.c_int32), ("residual_from_quantized", C.c_int32),
+                ("x_dtype", C.c_int32), ("reserved", C.c_int32)]
+
+
+class lq_act_debug(C.Structure):
+    _fields_ = [("xb", C.c_void_p), ("sxb", C.c_void_p), ("accT", C.c_void_p), ("T", C.c_void_p)]
+
+
+class lq_fwd_debug(C.Structure):
+    _fields_ = [("acc", C.c_void_p), ("acc2", C.c_void_p), ("y32", C.c_void_p)]
+
+
+class lq_weights_view(C.Structure):
+    _fields_ = [("pq", C.c_void_p), ("sw", C.c_void_p), ("pe", C.c_void_p), ("lq", C.c_void_p),
+                ("sl", C.c_void_p), ("rq", C.c_void_p), ("sr", C.c_void_p)]
+
+
+class lq_act_view(C.Structure):
+    _fields_ = [("xq", C.c_void_p), ("sx", C.c_void_p), ("xe", C.c_void_p), ("tq", C.c_void_p),
+                ("st", C.c_void_p)]
+
+
+EXPORTS = ["lq_status_string", "lq_packed_sizes", "lq_pack_weights", "lq_act_sizes", "lq_quantize_act",
+           "lq_linear_lowrank_fwd", "lq_unpack_weights", "lq_unpack_act"]
+
+_lib.lq_status_string.restype = C.c_char_p
+_lib.lq_status_string.argtypes = [C.c_int]
+_lib.lq_packed_sizes.argtypes = [C.POINTER(lq_config), C.POINTER(C.c_size_t)]
+_lib.lq_act_sizes.argtypes = [C.POINTER(lq_config), C.c_int64, C.POINTER(C.c_size_t)]
+_lib.lq_pack_weights.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                 C.c_size_t, C.c_void_p]
+_lib.lq_quantize_act.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                 C.c_void_p, C.c_size_t, C.POINTER(lq_act_debug), C.c_void_p]
+_lib.lq_linear_lowrank_fwd.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                       C.c_int64, C.POINTER(lq_fwd_debug), C.c_void_p]
+_lib.lq_unpack_weights.argtypes = [C.POINTER(lq_config), C.c_void_p, C.POINTER(lq_weights_view), C.c_void_p]
+_lib.lq_unpack_act.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_int64, C.POINTER(lq_act_view), C.c_void_p]
+
+
+class LqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lq_status_string(status)} (status {status})")
+
+
+def lq_status_string(status: int) -> str:
+    return _lib.lq_status_string(int(status)).decode()
+
+
+def _check(st: int, where: str):
+    if st != LQ_OK:
+        raise LqError(st, where)
+
+
+def raw():
+    """The ctypes library handle (for tests of the error paths, which need no GPU)."""
+    return _lib
+
+
+def make_config(N: int, K: int, rank: int, family: str = "int", group: int = 64, br_w_bits: int = 8,
+                br_a_bits: int = 8, x_dtype: str = "bf16", residual_from_quantized: bool = True) -> lq_config:
+    if family == "int":
+        return lq_config(N, K, rank, LQ_INT4, LQ_INT4, group, 0, _INT_FMT[br_w_bits], _INT_FMT[br_a_bits],
+                         1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32, 0)
+    if family == "mx":
+        return lq_config(N, K, rank, LQ_MXFP4_E2M1, LQ_MXFP4_E2M1, 32, 32, LQ_FP8_E4M3, LQ_FP8_E4M3,
+                         1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32, 0)
+    raise ValueError(family)
+
+
+def config_for_layer(layer) -> lq_config:
+    return make_config(layer.N, layer.K, layer.r, layer.family, layer.g, layer.br_w_bits, layer.br_a_bits,
+                       layer.x_dtype)
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def lq_packed_sizes(cfg: lq_config) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.lq_packed_sizes(C.byref(cfg), C.byref(n)), "lq_packed_sizes")
+    return int(n.value)
+
+
+def lq_act_sizes(cfg: lq_config, M: int) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.lq_act_sizes(C.byref(cfg), M, C.byref(n)), "lq_act_sizes")
+    return int(n.value)
+
+
+def lq_pack_weights(cfg: lq_config, W: torch.Tensor, L: Optional[torch.Tensor], R: Optional[torch.Tensor],
+                    packed: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """W (N x K), L (N x r), R (r x K): fp32 CUDA tensors, contiguous.  Returns the packed blob."""
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous()
+    for t in (L, R):
+        assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous())
+    if packed is None:
+        packed = torch.empty(lq_packed_sizes(cfg), dtype=torch.uint8, device=W.device)
+    _check(_lib.lq_pack_weights(C.byref(cfg), _ptr(W), _ptr(L), _ptr(R), _ptr(packed), packed.numel(),
+                                C.c_void_p(_stream())), "lq_pack_weights")
+    return packed
+
+
+@dataclass
+class ActDebug:
+    xb: torch.Tensor
+    sxb: torch.Tensor
+    accT: torch.Tensor
+    T: torch.Tensor
+
+
+def lq_quantize_act(cfg: lq_config, packed: torch.Tensor, X: torch.Tensor, act: Optional[torch.Tensor] = None,
+                    debug: bool = False):
+    """X: M x K CUDA tensor (fp32 or bf16, row stride may exceed K).  Returns the activation blob
+    (and the parity taps when debug=True)."""
+    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+    assert X.dtype == (torch.bfloat16 if cfg.x_dtype == LQ_BF16 else torch.float32)
+    M = X.shape[0]
+    if act is None:
+        act = torch.empty(lq_act_sizes(cfg, M), dtype=torch.uint8, device=X.device)
+    dbg = None
+    taps = None
+    if debug:
+        r = max(cfg.rank, 1)
+        taps = ActDebug(torch.zeros((M, cfg.K), dtype=torch.int8, device=X.device),
+                        torch.zeros(M, dtype=torch.float32, device=X.device),
+                        torch.zeros((M, r), dtype=torch.int32, device=X.device),
+                        torch.zeros((M, r), dtype=torch.float32, device=X.device))
+        dbg = lq_act_debug(taps.xb.data_ptr(), taps.sxb.data_ptr(), taps.accT.data_ptr(), taps.T.data_ptr())
+    _check(_lib.lq_quantize_act(C.byref(cfg), _ptr(packed), _ptr(X), M, X.stride(0), _ptr(act), act.numel(),
+                                C.byref(dbg) if dbg is not None else None, C.c_void_p(_stream())),
+           "lq_quantize_act")
+    return (act, taps) if debug else act
+
+
+@dataclass
+class FwdDebug:
+    acc: Optional[torch.Tensor]
+    acc2: torch.Tensor
+    y32: torch.Tensor
+
+
+def lq_linear_lowrank_fwd(cfg: lq_config, packed: torch.Tensor, act: torch.Tensor, M: int,
+                          Y: Optional[torch.Tensor] = None, debug: bool = False, debug_acc: bool = True):
+    """Returns Y (M x N bf16); with debug=True also the taps (acc only if debug_acc)."""
+    if Y is None:
+        Y = torch.empty((M, cfg.N), dtype=torch.bfloat16, device=act.device)
+    assert Y.is_cuda and Y.dtype == torch.bfloat16 and Y.stride(1) == 1 and Y.shape == (M, cfg.N)
+    dbg = None
+    taps = None
+    if debug:
+        G = cfg.K // cfg.main_w_group
+        taps = FwdDebug(torch.zeros((M, cfg.N, G), dtype=torch.int32, device=act.device) if debug_acc else None,
+                        torch.zeros((M, cfg.N), dtype=torch.int32, device=act.device),
+                        torch.zeros((M, cfg.N), dtype=torch.float32, device=act.device))
+        dbg = lq_fwd_debug(taps.acc.data_ptr() if debug_acc else None, taps.acc2.data_ptr(), taps.y32.data_ptr())
+    _check(_lib.lq_linear_lowrank_fwd(C.byref(cfg), _ptr(packed), _ptr(act), M, _ptr(Y), Y.stride(0),
+                                      C.byref(dbg) if dbg is not None else None, C.c_void_p(_stream())),
+           "lq_linear_lowrank_fwd")
+    return (Y, taps) if debug else Y
+
+
+@dataclass
+class WeightsView:
+    pq: torch.Tensor
+    sw: Optional[torch.Tensor]
+    pe: Optional[torch.Tensor]
+    lq: torch.Tensor
+    sl: torch.Tensor
+    rq: torch.Tensor
+    sr: torch.Tensor
+
+
+def lq_unpack_weights(cfg: lq_config, packed: torch.Tensor) -> WeightsView:
+    dev = packed.device
+    N, K, r = cfg.N, cfg.K, cfg.rank
+    mx = cfg.main_w == LQ_MXFP4_E2M1
+    v = WeightsView(torch.zeros((N, K), dtype=torch.int8, device=dev),
+                    None if mx else torch.zeros((N, K // cfg.main_w_group), dtype=torch.float32, device=dev),
+                    torch.zeros((N, K // 32), dtype=torch.uint8, device=dev) if mx else None,
+                    torch.zeros((N, max(r, 1)), dtype=torch.int8, device=dev),
+                    torch.zeros(N, dtype=torch.float32, device=dev),
+                    torch.zeros((max(r, 1), K), dtype=torch.int8, device=dev),
+                    torch.zeros(max(r, 1), dtype=torch.float32, device=dev))
+    view = lq_weights_view(v.pq.data_ptr(), v.sw.data_ptr() if v.sw is not None else None,
+                           v.pe.data_ptr() if v.pe is not None else None, v.lq.data_ptr(), v.sl.data_ptr(),
+                           v.rq.data_ptr(), v.sr.data_ptr())
+    _check(_lib.lq_unpack_weights(C.byref(cfg), _ptr(packed), C.byref(view), C.c_void_p(_stream())),
+           "lq_unpack_weights")
+    return v
+
+
+@dataclass
+class ActView:
+    xq: torch.Tensor
+    sx: Optional[torch.Tensor]
+    xe: Optional[torch.Tensor]
+    tq: torch.Tensor
+    st: torch.Tensor
+
+
+def lq_unpack_act(cfg: lq_config, act: torch.Tensor, M: int) -> ActView:
+    dev = act.device
+    K, r = cfg.K, cfg.rank
+    mx = cfg.main_w == LQ_MXFP4_E2M1
+    v = ActView(torch.zeros((M, K), dtype=torch.int8, device=dev),
+                None if mx else torch.zeros(M, dtype=torch.float32, device=dev),
+                torch.zeros((M, K // 32), dtype=torch.uint8, device=dev) if mx else None,
+                torch.zeros((M, max(r, 1)), dtype=torch.int8, device=dev),
+                torch.zeros(M, dtype=torch.float32, device=dev))
+    view = lq_act_view(v.xq.data_ptr(), v.sx.data_ptr() if v.sx is not None else None,
+                       v.xe.data_ptr() if v.xe is not None else None, v.tq.data_ptr(), v.st.data_ptr())
+    _check(_lib.lq_unpack_act(C.byref(cfg), _ptr(act), M, C.byref(view), C.c_void_p(_stream())), "lq_unpack_act")
+    return v

@@ -1,0 +1,276 @@
+// Per-call activation kernel, INT family (Section 3.4 and the low-rank branch of Fig. 1).
+// One pass over X does, per token row:
+//   sx = amax/7,      xq = rne(x * 7/amax)          4-bit main codes (sign-magnitude nibbles)
+//   sxb = amax/qa,    xb = rne(x * qa/amax)         branch codes, kept in registers only
+//   accT = xb . rq^T  (int8 MFMA, int32)            skinny contraction with Q2(R)
+//   T = (float(accT) * sxb) * sr ;  st = max|T|/qa ;  tq = rne(T * qa/max|T|)
+//
+// Decomposition: a workgroup of 4 wavefronts owns 16 token rows; lane l of every wavefront
+// works on row l%16 and on the 16-value quarter l/16 of each 64-deep K chunk, which is
+// exactly the A-operand layout of v_mfma_i32_16x16x64_i8.  The 64-chunks of K are dealt
+// round-robin to the 4 wavefronts, so a whole row block lives in registers between the
+// amax pass and the quantisation pass: X is read from HBM once.
+#include "lq_internal.h"
+
+namespace lq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+struct ActParams {
+    const void* X;
+    int64_t ldx;
+    int M, K, C64, r, rp;
+    float qa;  // qmax of the branch activation format
+    const int8_t* rq;
+    const float* sr;
+    uint8_t* xq;
+    float* sx;
+    int8_t* tq;
+    float* st;
+    int8_t* dbg_xb;
+    float* dbg_sxb;
+    int32_t* dbg_accT;
+    float* dbg_T;
+};
+
+template <bool BF16>
+struct XChunk;
+
+template <>
+struct XChunk<true> {  // 16 bf16 values = 8 dwords
+    uint32_t w[8];
+    __device__ __forceinline__ void load(const void* X, size_t elem, bool ok)
+    {
+        v4i a = {0, 0, 0, 0}, b = {0, 0, 0, 0};
+        if (ok) {
+            const v4i* p = (const v4i*)((const uint16_t*)X + elem);
+            a = p[0];
+            b = p[1];
+        }
+        w[0] = a[0]; w[1] = a[1]; w[2] = a[2]; w[3] = a[3];
+        w[4] = b[0]; w[5] = b[1]; w[6] = b[2]; w[7] = b[3];
+    }
+    __device__ __forceinline__ float get(int i) const
+    {
+        return __uint_as_float((i & 1) ? (w[i >> 1] & 0xFFFF0000u) : (w[i >> 1] << 16));
+    }
+};
+
+template <>
+struct XChunk<false> {  // 16 fp32 values
+    float v[16];
+    __device__ __forceinline__ void load(const void* X, size_t elem, bool ok)
+    {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            v4i a = {0, 0, 0, 0};
+            if (ok) a = ((const v4i*)((const float*)X + elem))[q];
+            v[4 * q] = __int_as_float(a[0]);
+            v[4 * q + 1] = __int_as_float(a[1]);
+            v[4 * q + 2] = __int_as_float(a[2]);
+            v[4 * q + 3] = __int_as_float(a[3]);
+        }
+    }
+    __device__ __forceinline__ float get(int i) const { return v[i]; }
+};
+
+__device__ __forceinline__ void scales(float amax, float qmax, float* s, float* inv)
+{
+    if (amax == 0.0f) {
+        *s = 1.0f;
+        *inv = 1.0f;
+    } else {
+        *s = amax / qmax;
+        *inv = qmax / amax;
+    }
+}
+
+// round-to-nearest-even of a value with |u| < 2^22, returned in the low bits (two's complement)
+__device__ __forceinline__ uint32_t rne_bits(float u) { return __float_as_uint(__fadd_rn(u, 12582912.0f)); }
+
+template <bool BF16, int MAXC, int NJB>
+__global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
+{
+    __shared__ float s_amax[4][16];
+    __shared__ float s_sxb[16];
+    __shared__ int s_acc[4][NJB > 0 ? NJB : 1][64][4];  // [wave][j block][lane][4]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r16 = lane & 15, kq = lane >> 4;
+    const int row = blockIdx.x * 16 + r16;
+    const bool row_ok = row < p.M;
+    const int C64 = p.C64;
+    constexpr int njb = NJB;  // rank / 16
+
+    XChunk<BF16> xc[MAXC];
+#pragma unroll
+    for (int ci = 0; ci < MAXC; ++ci) {
+        const int c = wave + 4 * ci;
+        xc[ci].load(p.X, (size_t)row * p.ldx + (size_t)c * 64 + kq * 16, row_ok && c < C64);
+    }
+
+    // ---- per-row amax -------------------------------------------------------------------
+    float a = 0.f;
+#pragma unroll
+    for (int ci = 0; ci < MAXC; ++ci)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) a = fmaxf(a, fabsf(xc[ci].get(i)));
+    a = fmaxf(a, __shfl_xor(a, 16, 64));
+    a = fmaxf(a, __shfl_xor(a, 32, 64));
+    if (kq == 0) s_amax[wave][r16] = a;
+    __syncthreads();
+    a = fmaxf(fmaxf(s_amax[0][r16], s_amax[1][r16]), fmaxf(s_amax[2][r16], s_amax[3][r16]));
+
+    float s4, inv4, sb, invb;
+    scales(a, 7.0f, &s4, &inv4);
+    scales(a, p.qa, &sb, &invb);
+    if (wave == 0 && kq == 0) {
+        p.sx[row] = s4;
+        s_sxb[r16] = sb;
+        if (p.dbg_sxb && row_ok) p.dbg_sxb[row] = sb;
+        if (p.r == 0) p.st[row] = 1.0f;
+    }
+
+    v4i acc[NJB > 0 ? NJB : 1];
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb) acc[jb] = v4i{0, 0, 0, 0};
+
+    const int rb = row >> 5;
+#pragma unroll
+    for (int ci = 0; ci < MAXC; ++ci) {
+        const int c = wave + 4 * ci;
+        if (c < C64) {  // wave-uniform
+            // main codes: magnitude from |x|, sign from x
+            uint32_t pk[2] = {0u, 0u};
+            uint32_t xb4[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float x = xc[ci].get(i);
+                const uint32_t m = __float_as_uint(__fadd_rn(__fmul_rn(fabsf(x), inv4), 8388608.0f)) & 7u;
+                const uint32_t sgn = __float_as_uint(x) >> 31;
+                pk[i >> 3] |= nib_put(i & 7, sgn, m);
+                const uint32_t b = rne_bits(__fmul_rn(x, invb)) & 0xFFu;
+                xb4[i >> 2] |= b << (8 * (i & 3));
+            }
+            uint8_t* dst = p.xq + ((size_t)((size_t)rb * C64 + c) * 64 + (row & 31) + 32 * (kq >> 1)) * 16 + (kq & 1) * 8;
+            *(uint2*)dst = make_uint2(pk[0], pk[1]);
+            if (p.dbg_xb && row_ok)
+                *(v4i*)(p.dbg_xb + (size_t)row * p.K + c * 64 + kq * 16) = v4i{(int)xb4[0], (int)xb4[1], (int)xb4[2], (int)xb4[3]};
+            if (njb > 0) {
+                const v4i av = {(int)xb4[0], (int)xb4[1], (int)xb4[2], (int)xb4[3]};
+#pragma unroll
+                for (int jb = 0; jb < NJB; ++jb) {
+                    const v4i bv = *(const v4i*)(p.rq + ((size_t)((size_t)c * njb + jb) * 64 + lane) * 16);
+                    acc[jb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bv, acc[jb], 0, 0, 0);
+                }
+            }
+        }
+    }
+    if (njb == 0) return;
+
+    // ---- combine the 4 wavefronts' partial accumulators, dequantise, re-quantise ----------
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb) *(v4i*)&s_acc[wave][jb][lane][0] = acc[jb];
+    __syncthreads();
+    if (wave != 0) return;
+
+    // lane holds column j = jb*16 + lane%16 and token rows 4*(lane/16) + i
+    float T[NJB > 0 ? NJB : 1][4];
+    float tmax[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb) {
+        {
+            v4i s = *(const v4i*)&s_acc[0][jb][lane][0];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) {
+                const v4i o = *(const v4i*)&s_acc[w][jb][lane][0];
+                s += o;
+            }
+            const float srj = p.sr[jb * 16 + r16];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int tok = 4 * kq + i;
+                const float tv = __fmul_rn(__fmul_rn((float)s[i], s_sxb[tok]), srj);
+                T[jb][i] = tv;
+                tmax[i] = fmaxf(tmax[i], fabsf(tv));
+                const int grow = blockIdx.x * 16 + tok;
+                if (grow < p.M) {
+                    if (p.dbg_accT) p.dbg_accT[(size_t)grow * p.r + jb * 16 + r16] = s[i];
+                    if (p.dbg_T) p.dbg_T[(size_t)grow * p.r + jb * 16 + r16] = tv;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int o = 8; o >= 1; o >>= 1) tmax[i] = fmaxf(tmax[i], __shfl_xor(tmax[i], o, 64));
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int grow = blockIdx.x * 16 + 4 * kq + i;
+        float stv, invt;
+        scales(tmax[i], p.qa, &stv, &invt);
+        if (r16 == 0) p.st[grow] = stv;
+#pragma unroll
+        for (int jb = 0; jb < NJB; ++jb)
+            p.tq[(size_t)grow * p.rp + jb * 16 + r16] = (int8_t)(rne_bits(__fmul_rn(T[jb][i], invt)) & 0xFFu);
+        if (p.rp > p.r && r16 < (p.rp - p.r)) p.tq[(size_t)grow * p.rp + p.r + r16] = 0;
+    }
+}
+
+template <bool BF16, int MAXC, int NJB>
+static hipError_t launch_one(const ActParams& p, int64_t Mp, hipStream_t s)
+{
+    hipLaunchKernelGGL((act_int_kernel<BF16, MAXC, NJB>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+template <bool BF16, int MAXC>
+static hipError_t launch_rank(const ActParams& p, int64_t Mp, hipStream_t s)
+{
+    switch (p.r) {
+        case 0: return launch_one<BF16, MAXC, 0>(p, Mp, s);
+        case 16: return launch_one<BF16, MAXC, 1>(p, Mp, s);
+        case 32: return launch_one<BF16, MAXC, 2>(p, Mp, s);
+        case 64: return launch_one<BF16, MAXC, 4>(p, Mp, s);
+        default: return launch_one<BF16, MAXC, 8>(p, Mp, s);
+    }
+}
+
+hipError_t launch_quantize_act_int(const Dims& d, int x_dtype, const uint8_t* packed, const void* X,
+                                   int64_t M, int64_t ldx, uint8_t* act, const lq_act_debug* dbg,
+                                   hipStream_t s)
+{
+    const PackedLayout pl = packed_layout(d);
+    const ActLayout al = act_layout(d, M);
+    ActParams p;
+    p.X = X;
+    p.ldx = ldx;
+    p.M = (int)M;
+    p.K = (int)d.K;
+    p.C64 = d.C64;
+    p.r = d.r;
+    p.rp = d.rp;
+    p.qa = (float)d.qmax_ba;
+    p.rq = (const int8_t*)(packed + pl.off_rq);
+    p.sr = (const float*)(packed + pl.off_sr);
+    p.xq = act + al.off_xq;
+    p.sx = (float*)(act + al.off_sx);
+    p.tq = (int8_t*)(act + al.off_tq);
+    p.st = (float*)(act + al.off_st);
+    p.dbg_xb = dbg ? dbg->xb : nullptr;
+    p.dbg_sxb = dbg ? dbg->sxb : nullptr;
+    p.dbg_accT = dbg ? dbg->accT : nullptr;
+    p.dbg_T = dbg ? dbg->T : nullptr;
+    const int maxc = (d.C64 + 3) / 4;
+    if (x_dtype == LQ_BF16) {
+        if (maxc <= 5) return launch_rank<true, 5>(p, al.Mp, s);
+        if (maxc <= 9) return launch_rank<true, 9>(p, al.Mp, s);
+        return launch_rank<true, 18>(p, al.Mp, s);
+    }
+    if (maxc <= 5) return launch_rank<false, 5>(p, al.Mp, s);
+    return launch_rank<false, 9>(p, al.Mp, s);
+}
+
+}  // namespace lq

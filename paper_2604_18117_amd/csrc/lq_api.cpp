@@ -1,0 +1,215 @@
+// Host side of the C ABI: argument validation, layout arithmetic, dispatch.  Every error is
+// detected here, before any launch, so that all error paths can be exercised without a GPU.
+#include <hip/hip_runtime.h>
+
+#include "lq_internal.h"
+
+namespace lq {
+
+static int int_qmax(int fmt)
+{
+    switch (fmt) {
+        case LQ_INT4: return 7;
+        case LQ_INT6: return 31;
+        case LQ_INT8: return 127;
+        default: return 0;
+    }
+}
+
+lq_status make_dims(const lq_config* cfg, Dims* d)
+{
+    if (!cfg) return LQ_ERR_NULL;
+    if (cfg->reserved != 0) return LQ_ERR_UNSUPPORTED;
+    if (cfg->N <= 0 || cfg->K <= 0 || cfg->N > (1 << 24) || cfg->K > (1 << 24)) return LQ_ERR_SHAPE;
+    if (cfg->K % 64 != 0 || cfg->N % 64 != 0) return LQ_ERR_SHAPE;
+    const int r = cfg->rank;
+    if (!(r == 0 || r == 16 || r == 32 || r == 64 || r == 128)) return LQ_ERR_SHAPE;
+    if (cfg->x_dtype != LQ_F32 && cfg->x_dtype != LQ_BF16) return LQ_ERR_UNSUPPORTED;
+    if (cfg->residual_from_quantized != 0 && cfg->residual_from_quantized != 1) return LQ_ERR_UNSUPPORTED;
+    d->N = cfg->N;
+    d->K = cfg->K;
+    d->r = r;
+    d->rp = (r + 31) / 32 * 32;
+    d->C64 = (int)(cfg->K / 64);
+    if (cfg->main_w == LQ_INT4) {
+        if (cfg->main_a != LQ_INT4) return LQ_ERR_UNSUPPORTED;
+        if (cfg->main_w_group != 64 && cfg->main_w_group != 128) return LQ_ERR_SHAPE;
+        if (cfg->K % cfg->main_w_group != 0) return LQ_ERR_SHAPE;
+        if (cfg->main_a_group != 0) return LQ_ERR_UNSUPPORTED;
+        const int qw = int_qmax(cfg->br_w), qa = int_qmax(cfg->br_a);
+        if (qw == 0 || qa == 0 || cfg->br_a == LQ_INT4) return LQ_ERR_UNSUPPORTED;
+        d->mx = false;
+        d->g = cfg->main_w_group;
+        d->qmax_bw = qw;
+        d->qmax_ba = qa;
+    } else if (cfg->main_w == LQ_MXFP4_E2M1) {
+        if (cfg->main_a != LQ_MXFP4_E2M1) return LQ_ERR_UNSUPPORTED;
+        if (cfg->main_w_group != 32 || cfg->main_a_group != 32) return LQ_ERR_SHAPE;
+        if (cfg->br_w != LQ_FP8_E4M3 || cfg->br_a != LQ_FP8_E4M3) return LQ_ERR_UNSUPPORTED;
+        d->mx = true;
+        d->g = 32;
+        d->qmax_bw = d->qmax_ba = 0;
+    } else {
+        return LQ_ERR_UNSUPPORTED;
+    }
+    d->G = (int)(cfg->K / d->g);
+    return LQ_OK;
+}
+
+PackedLayout packed_layout(const Dims& d)
+{
+    PackedLayout pl;
+    size_t o = 0;
+    pl.off_pq = o;
+    o = align256(o + (size_t)d.N * d.K / 2);
+    pl.off_sw = o;
+    o = align256(o + (d.mx ? (size_t)d.N * d.G : (size_t)d.N * d.G * 4));
+    pl.off_lq = o;
+    o = align256(o + (size_t)d.N * d.rp);
+    pl.off_sl = o;
+    o = align256(o + (size_t)d.N * 4);
+    pl.off_rq = o;
+    o = align256(o + (size_t)d.r * d.K);
+    pl.off_sr = o;
+    o = align256(o + (size_t)(d.r > 0 ? d.r : 1) * 4);
+    pl.total = o;
+    return pl;
+}
+
+ActLayout act_layout(const Dims& d, int64_t M)
+{
+    ActLayout al;
+    al.Mp = (M + 31) / 32 * 32;
+    size_t o = 0;
+    al.off_xq = o;
+    o = align256(o + (size_t)al.Mp * d.K / 2);
+    al.off_sx = o;
+    o = align256(o + (d.mx ? (size_t)al.Mp * d.G : (size_t)al.Mp * 4));
+    al.off_tq = o;
+    o = align256(o + (size_t)al.Mp * d.rp);
+    al.off_st = o;
+    o = align256(o + (size_t)al.Mp * 4);
+    al.total = o;
+    return al;
+}
+
+}  // namespace lq
+
+using namespace lq;
+
+extern "C" {
+
+const char* lq_status_string(lq_status s)
+{
+    switch (s) {
+        case LQ_OK: return "ok";
+        case LQ_ERR_NULL: return "null pointer";
+        case LQ_ERR_SHAPE: return "shape violates the contract";
+        case LQ_ERR_UNSUPPORTED: return "unsupported format combination";
+        case LQ_ERR_ALIGN: return "misaligned pointer or stride";
+        case LQ_ERR_BUFFER_TOO_SMALL: return "buffer too small";
+        case LQ_ERR_DEVICE: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+lq_status lq_packed_sizes(const lq_config* cfg, size_t* packed_bytes)
+{
+    if (!cfg || !packed_bytes) return LQ_ERR_NULL;
+    Dims d;
+    lq_status st = make_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    *packed_bytes = packed_layout(d).total;
+    return LQ_OK;
+}
+
+lq_status lq_act_sizes(const lq_config* cfg, int64_t M, size_t* act_bytes)
+{
+    if (!cfg || !act_bytes) return LQ_ERR_NULL;
+    Dims d;
+    lq_status st = make_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (M < 1 || M > (1 << 24)) return LQ_ERR_SHAPE;
+    *act_bytes = act_layout(d, M).total;
+    return LQ_OK;
+}
+
+static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+lq_status lq_pack_weights(const lq_config* cfg, const float* W, const float* L, const float* R, void* packed,
+                          size_t packed_bytes, void* stream)
+{
+    Dims d;
+    lq_status st = make_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!W || !packed) return LQ_ERR_NULL;
+    if (d.r > 0 && (!L || !R)) return LQ_ERR_NULL;
+    if (!aligned(packed, 256) || !aligned(W, 4)) return LQ_ERR_ALIGN;
+    if (packed_bytes < packed_layout(d).total) return LQ_ERR_BUFFER_TOO_SMALL;
+    if (d.mx) return LQ_ERR_UNSUPPORTED;
+    hipError_t e = launch_pack_int(d, cfg->residual_from_quantized, W, L, R, (uint8_t*)packed, (hipStream_t)stream);
+    return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
+lq_status lq_quantize_act(const lq_config* cfg, const void* packed, const void* X, int64_t M, int64_t ldx,
+                          void* act, size_t act_bytes, const lq_act_debug* dbg, void* stream)
+{
+    Dims d;
+    lq_status st = make_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!X || !act) return LQ_ERR_NULL;
+    if (d.r > 0 && !packed) return LQ_ERR_NULL;
+    if (M < 1 || M > (1 << 24) || ldx < d.K) return LQ_ERR_SHAPE;
+    const size_t es = cfg->x_dtype == LQ_BF16 ? 2 : 4;
+    if (!aligned(X, 16) || (ldx * es) % 16 != 0 || !aligned(act, 256) || (packed && !aligned(packed, 256)))
+        return LQ_ERR_ALIGN;
+    if (act_bytes < act_layout(d, M).total) return LQ_ERR_BUFFER_TOO_SMALL;
+    if (d.mx) return LQ_ERR_UNSUPPORTED;
+    const int maxc = (d.C64 + 3) / 4;
+    if (maxc > (cfg->x_dtype == LQ_BF16 ? 18 : 9)) return LQ_ERR_UNSUPPORTED;  // K beyond the register-resident row
+    hipError_t e = launch_quantize_act_int(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,
+                                           (hipStream_t)stream);
+    return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
+lq_status lq_linear_lowrank_fwd(const lq_config* cfg, const void* packed, const void* act, int64_t M, void* Y,
+                                int64_t ldy, const lq_fwd_debug* dbg, void* stream)
+{
+    Dims d;
+    lq_status st = make_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!packed || !act || !Y) return LQ_ERR_NULL;
+    if (M < 1 || M > (1 << 24) || ldy < d.N) return LQ_ERR_SHAPE;
+    if (!aligned(packed, 256) || !aligned(act, 256) || !aligned(Y, 4) || (ldy & 1)) return LQ_ERR_ALIGN;
+    if (d.mx) return LQ_ERR_UNSUPPORTED;
+    hipError_t e = launch_fwd_int(d, (const uint8_t*)packed, (const uint8_t*)act, M, (uint16_t*)Y, ldy, dbg,
+                                  (hipStream_t)stream);
+    return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
+lq_status lq_unpack_weights(const lq_config* cfg, const void* packed, const lq_weights_view* out, void* stream)
+{
+    Dims d;
+    lq_status st = make_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!packed || !out) return LQ_ERR_NULL;
+    if (!aligned(packed, 256)) return LQ_ERR_ALIGN;
+    if (d.mx) return LQ_ERR_UNSUPPORTED;
+    hipError_t e = launch_unpack_weights_int(d, (const uint8_t*)packed, out, (hipStream_t)stream);
+    return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
+lq_status lq_unpack_act(const lq_config* cfg, const void* act, int64_t M, const lq_act_view* out, void* stream)
+{
+    Dims d;
+    lq_status st = make_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!act || !out) return LQ_ERR_NULL;
+    if (M < 1 || M > (1 << 24)) return LQ_ERR_SHAPE;
+    if (!aligned(act, 256)) return LQ_ERR_ALIGN;
+    if (d.mx) return LQ_ERR_UNSUPPORTED;
+    hipError_t e = launch_unpack_act_int(d, (const uint8_t*)act, M, out, (hipStream_t)stream);
+    return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
+}  // extern "C"

@@ -1,0 +1,315 @@
+// Forward kernel, INT family (paper Fig. 1: residual branch + low-rank branch + sum).
+//
+//   acc[m,n,g] = sum_{k in g} xq[m,k] pq[n,k]           4-bit codes, exact
+//   t[m,n]     = fma(acc[m,n,g], sw[n,g], t)            ascending g, fp32
+//   acc2[m,n]  = sum_j tq[m,j] lq[n,j]                  int8 MFMA, int32
+//   y          = fma(sx[m], t, (float(acc2) * st[m]) * sl[n]);   Y = bf16_rne(y)
+//
+// The 4-bit codes are fed to the matrix cores as FP8-E4M3 subnormals (byte s0000mmm =
+// +-m * 2^-9): every product and every partial sum of a 64..128-deep group is an integer
+// multiple of 2^-18 below 2^13 * 2^-18, so the fp32 MFMA accumulator holds the integer
+// accumulator exactly and the per-group dequantisation is ONE fp32 FMA per output (no
+// int->float conversion); the factor 2^18 is folded into the stored weight scales.
+//
+// Work decomposition: a workgroup of WM x WN wavefronts computes a (WM*128) x (WN*64) tile
+// of Y; each wavefront owns 128 x 64 (4 x 2 MFMA tiles of 32 x 32, 128 fp32 running sums per
+// lane).  Activation codes go global -> registers -> (nibble to byte) -> LDS once per
+// workgroup; weight codes are read by each wavefront straight from global memory in operand
+// order (they are shared by only WM wavefronts) and expanded in registers.
+#include "lq_internal.h"
+
+namespace lq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+struct FwdParams {
+    const uint8_t* xq;
+    const float* sx;
+    const int8_t* tq;
+    const float* st;
+    const uint8_t* pq;
+    const float* swT;
+    const int8_t* lq;
+    const float* sl;
+    uint16_t* Y;
+    int64_t ldy;
+    int M, N, G, C64, rp, nrb;
+    int tilesM, tilesN;
+    int32_t* dbg_acc;
+    int32_t* dbg_acc2;
+    float* dbg_y32;
+};
+
+__device__ __forceinline__ v8i expand8(v4i p)
+{
+    v8i o;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        o[2 * d] = (int)nib_lo((uint32_t)p[d]);
+        o[2 * d + 1] = (int)nib_hi((uint32_t)p[d]);
+    }
+    return o;
+}
+
+template <int WM, int WN, int GC, bool DBG>
+__global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
+{
+    constexpr int NW = WM * WN;
+    constexpr int RBT = WM * 4;  // 32-row blocks per workgroup tile
+    static_assert(RBT % NW == 0 || NW % RBT == 0, "staging split");
+    constexpr int SPW = (RBT + NW - 1) / NW;  // row blocks staged per wavefront
+    constexpr int PF = (GC == 1) ? 2 : 1;     // weight prefetch distance in steps
+
+    // [buffer][chunk in group][row block][part][lane][16 B]
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * GC * RBT * 2048];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int half = lane >> 5, l32 = lane & 31;
+
+    // XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs, so give each
+    // XCD one contiguous run of tiles (row-major over (m,n)): its L2 then sees few row tiles.
+    const int tiles = p.tilesM * p.tilesN;
+    const int per = tiles >> 3, rem = tiles & 7;
+    const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
+    const int tile = xcd * per + (xcd < rem ? xcd : rem) + loc;
+    const int tile_m = tile / p.tilesN, tile_n = tile - tile_m * p.tilesN;
+
+    const int rb0 = tile_m * RBT;
+    const int cb0 = tile_n * (WN * 2) + wn * 2;
+    const bool active = (cb0 * 32 < p.N) && ((rb0 + wm * 4) < p.nrb);
+
+    const int C64 = p.C64, G = p.G;
+
+    // ---- staging registers: packed activation codes for the next step -------------------
+    v4i apk[SPW][GC];
+    auto load_a = [&](int step) {
+#pragma unroll
+        for (int i = 0; i < SPW; ++i) {
+            const int rbl = wave * SPW + i;
+            const int rb = rb0 + rbl;
+#pragma unroll
+            for (int cc = 0; cc < GC; ++cc) {
+                v4i v = {0, 0, 0, 0};
+                if (rbl < RBT && rb < p.nrb)
+                    v = *(const v4i*)(p.xq + ((size_t)((size_t)rb * C64 + step * GC + cc) * 64 + lane) * 16);
+                apk[i][cc] = v;
+            }
+        }
+    };
+    auto store_a = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < SPW; ++i) {
+            const int rbl = wave * SPW + i;
+            if (rbl < RBT) {
+#pragma unroll
+                for (int cc = 0; cc < GC; ++cc) {
+                    v8i e = expand8(apk[i][cc]);
+                    uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + rbl) * 2048) + lane * 16;
+                    *(v4i*)(base) = v4i{e[0], e[1], e[2], e[3]};
+                    *(v4i*)(base + 1024) = v4i{e[4], e[5], e[6], e[7]};
+                }
+            }
+        }
+    };
+
+    // ---- weight prefetch ring ------------------------------------------------------------
+    v4i bq[PF + 1][GC][2];
+    float swq[PF + 1][2];
+    auto load_b = [&](int slot, int step) {
+#pragma unroll
+        for (int cbi = 0; cbi < 2; ++cbi) {
+#pragma unroll
+            for (int cc = 0; cc < GC; ++cc) {
+                v4i v = {0, 0, 0, 0};
+                if (active && step < G)
+                    v = *(const v4i*)(p.pq + ((size_t)((size_t)(cb0 + cbi) * C64 + step * GC + cc) * 64 + lane) * 16);
+                bq[slot][cc][cbi] = v;
+            }
+            float s = 0.f;
+            if (active && step < G) s = p.swT[(size_t)step * p.N + (cb0 + cbi) * 32 + l32];
+            swq[slot][cbi] = s;
+        }
+    };
+
+    v16f t[4][2];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) t[a][b][i] = 0.f;
+
+    load_a(0);
+#pragma unroll
+    for (int d = 0; d <= PF; ++d) load_b(d, d);
+
+    for (int s = 0; s < G; ++s) {
+        const int buf = s & 1;
+        store_a(buf);
+        if (s + 1 < G) load_a(s + 1);
+        __syncthreads();
+
+        if (active) {
+            v8i bu[GC][2];
+            float sw[2];
+#pragma unroll
+            for (int cbi = 0; cbi < 2; ++cbi) {
+#pragma unroll
+                for (int cc = 0; cc < GC; ++cc) bu[cc][cbi] = expand8(bq[0][cc][cbi]);
+                sw[cbi] = swq[0][cbi];
+            }
+#pragma unroll
+            for (int d = 0; d < PF; ++d) {
+#pragma unroll
+                for (int cbi = 0; cbi < 2; ++cbi) {
+#pragma unroll
+                    for (int cc = 0; cc < GC; ++cc) bq[d][cc][cbi] = bq[d + 1][cc][cbi];
+                    swq[d][cbi] = swq[d + 1][cbi];
+                }
+            }
+            load_b(PF, s + PF + 1);
+
+#pragma unroll
+            for (int rbi = 0; rbi < 4; ++rbi) {
+                v8i a[GC];
+#pragma unroll
+                for (int cc = 0; cc < GC; ++cc) {
+                    const uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wm * 4 + rbi) * 2048) + lane * 16;
+                    v4i lo = *(const v4i*)(base);
+                    v4i hi = *(const v4i*)(base + 1024);
+                    a[cc] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                }
+#pragma unroll
+                for (int cbi = 0; cbi < 2; ++cbi) {
+                    v16f d = {0};
+#pragma unroll
+                    for (int cc = 0; cc < GC; ++cc)
+                        d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[cc], bu[cc][cbi], d, 0, 0, 0, 0, 0, 0);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) t[rbi][cbi][i] = __builtin_fmaf(d[i], sw[cbi], t[rbi][cbi][i]);
+                    if (DBG) {
+                        if (p.dbg_acc) {
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) {
+                                const int row = (rb0 + wm * 4 + rbi) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+                                const int col = (cb0 + cbi) * 32 + l32;
+                                if (row < p.M)
+                                    p.dbg_acc[((size_t)row * p.N + col) * G + s] = (int)(d[i] * 262144.0f);
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+    if (!active) return;
+
+    // ---- epilogue: rank-r expansion, scales, sum, bf16 -------------------------------------
+    const int nk = p.rp >> 5;
+    float slv[2];
+    v4i lqf[2][4];
+#pragma unroll
+    for (int cbi = 0; cbi < 2; ++cbi) {
+        const int col = (cb0 + cbi) * 32 + l32;
+        slv[cbi] = p.sl[col];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            v4i v = {0, 0, 0, 0};
+            if (kk < nk) v = *(const v4i*)(p.lq + (size_t)col * p.rp + kk * 32 + half * 16);
+            lqf[cbi][kk] = v;
+        }
+    }
+#pragma unroll
+    for (int rbi = 0; rbi < 4; ++rbi) {
+        const int rbase = (rb0 + wm * 4 + rbi) * 32;
+        if (rbase >= p.M) break;
+        v4i tqf[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            v4i v = {0, 0, 0, 0};
+            if (kk < nk) v = *(const v4i*)(p.tq + (size_t)(rbase + l32) * p.rp + kk * 32 + half * 16);
+            tqf[kk] = v;
+        }
+        // per-row scales: rows 8*q + 4*half + 0..3 are contiguous -> one 16-byte load each
+        v4f sxv[4], stv[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            sxv[q] = *(const v4f*)(p.sx + rbase + 8 * q + 4 * half);
+            stv[q] = *(const v4f*)(p.st + rbase + 8 * q + 4 * half);
+        }
+#pragma unroll
+        for (int cbi = 0; cbi < 2; ++cbi) {
+            v16i a2 = {0};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                if (kk < nk) a2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(tqf[kk], lqf[cbi][kk], a2, 0, 0, 0);
+            const int col = (cb0 + cbi) * 32 + l32;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = rbase + 8 * (i >> 2) + 4 * half + (i & 3);
+                const float ybr = ((float)a2[i] * stv[i >> 2][i & 3]) * slv[cbi];
+                const float y = __builtin_fmaf(sxv[i >> 2][i & 3], t[rbi][cbi][i], ybr);
+                if (row < p.M) {
+                    p.Y[(size_t)row * p.ldy + col] = (uint16_t)bf16_bits(y);
+                    if (DBG) {
+                        if (p.dbg_acc2) p.dbg_acc2[(size_t)row * p.N + col] = a2[i];
+                        if (p.dbg_y32) p.dbg_y32[(size_t)row * p.N + col] = y;
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int WM, int WN, int GC, bool DBG>
+static hipError_t launch_cfg(const FwdParams& p0, hipStream_t s)
+{
+    FwdParams p = p0;
+    p.tilesM = (p.nrb + WM * 4 - 1) / (WM * 4);
+    p.tilesN = (p.N + WN * 64 - 1) / (WN * 64);
+    dim3 grid((unsigned)(p.tilesM * p.tilesN)), block(WM * WN * 64);
+    hipLaunchKernelGGL((fwd_int_kernel<WM, WN, GC, DBG>), grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_fwd_int(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M,
+                          uint16_t* Y, int64_t ldy, const lq_fwd_debug* dbg, hipStream_t s)
+{
+    const PackedLayout pl = packed_layout(d);
+    const ActLayout al = act_layout(d, M);
+    FwdParams p;
+    p.xq = act + al.off_xq;
+    p.sx = (const float*)(act + al.off_sx);
+    p.tq = (const int8_t*)(act + al.off_tq);
+    p.st = (const float*)(act + al.off_st);
+    p.pq = packed + pl.off_pq;
+    p.swT = (const float*)(packed + pl.off_sw);
+    p.lq = (const int8_t*)(packed + pl.off_lq);
+    p.sl = (const float*)(packed + pl.off_sl);
+    p.Y = Y;
+    p.ldy = ldy;
+    p.M = (int)M;
+    p.N = (int)d.N;
+    p.G = d.G;
+    p.C64 = d.C64;
+    p.rp = d.rp;
+    p.nrb = (int)(al.Mp / 32);
+    p.tilesM = p.tilesN = 0;
+    p.dbg_acc = dbg ? dbg->acc : nullptr;
+    p.dbg_acc2 = dbg ? dbg->acc2 : nullptr;
+    p.dbg_y32 = dbg ? dbg->y32 : nullptr;
+    const bool want_dbg = dbg && (dbg->acc || dbg->acc2 || dbg->y32);
+    if (d.g == 64) {
+        return want_dbg ? launch_cfg<2, 4, 1, true>(p, s) : launch_cfg<2, 4, 1, false>(p, s);
+    } else {
+        return want_dbg ? launch_cfg<2, 4, 2, true>(p, s) : launch_cfg<2, 4, 2, false>(p, s);
+    }
+}
+
+}  // namespace lq

@@ -1,0 +1,117 @@
+// Internal declarations shared by the translation units of liblq (device layouts, launch
+// prototypes).  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "lq.h"
+
+namespace lq {
+
+// ---------------------------------------------------------------------------------------
+// Device data layout (INT family).  All sections start 256-byte aligned.
+//
+// 4-bit codes are stored sign-magnitude, 8 codes c0..c7 per dword, such that two cheap
+// bit operations turn a dword into two dwords of FP8-E4M3 *subnormal* bytes  s0000mmm
+// (value +-m * 2^-9, exact for |m| <= 7):
+//     lo = p & 0x87878787          -> bytes of c0..c3
+//     hi = rotl(p, 4) & 0x87878787 -> bytes of c4..c7
+// i.e. for i in 0..3:  c_i   : sign at bit 8i+7, magnitude at bits 8i+2..8i
+//                      c_4+i : sign at bit 8i+3, magnitude at bits 8j+6..8j+4, j = (i-1)&3
+//
+// "Fragment order" for a 64-deep K chunk and a block of 32 rows (tokens or out-channels):
+//     [block][chunk][half = (k%64)/32][row % 32][16 bytes = 32 codes = dwords (k%32)/8]
+// so that lane l of a wavefront reads its v_mfma_f32_32x32x64_f8f6f4 operand (row l%32,
+// K half l/32) as one aligned 16-byte load at (block, chunk) base + 16*l.
+//
+// For main_w_group == 128 the same bytes are consumed by v_mfma_f32_16x16x128_f8f6f4 (one
+// whole group per instruction); the fragment order is then
+//     [block of 16 rows][group][quarter = (k%128)/32][row % 16][16 bytes]
+// ---------------------------------------------------------------------------------------
+
+struct Dims {
+    int64_t N, K;
+    int r;        // rank
+    int rp;       // rank padded to a multiple of 32 (0 if r == 0)
+    int g;        // main weight group (64 | 128; MX: 32)
+    int G;        // K / g
+    int C64;      // K / 64
+    bool mx;      // MX family
+    int qmax_bw;  // INT branch weight qmax
+    int qmax_ba;  // INT branch activation qmax
+};
+
+struct PackedLayout {
+    size_t off_pq;   // main codes, fragment order, N*K/2 bytes
+    size_t off_sw;   // INT: [G][N] fp32, pre-multiplied by 2^18;  MX: E8M0 bytes
+    size_t off_lq;   // [N][rp] int8 (zero padded) / E4M3 bytes
+    size_t off_sl;   // [N] fp32
+    size_t off_rq;   // branch R codes in the activation kernel's operand order, r*K bytes
+    size_t off_sr;   // [r] fp32
+    size_t total;
+};
+
+struct ActLayout {
+    int64_t Mp;      // M rounded up to 32
+    size_t off_xq;   // main codes, fragment order, Mp*K/2 bytes
+    size_t off_sx;   // INT: [Mp] fp32;  MX: E8M0 bytes
+    size_t off_tq;   // [Mp][rp] int8 / E4M3
+    size_t off_st;   // [Mp] fp32
+    size_t total;
+};
+
+lq_status make_dims(const lq_config* cfg, Dims* d);
+PackedLayout packed_layout(const Dims& d);
+ActLayout act_layout(const Dims& d, int64_t M);
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// ---- launchers (each validates nothing: the API layer has done it) ----------------------
+hipError_t launch_pack_int(const Dims& d, int residual_from_quantized, const float* W,
+                           const float* L, const float* R, uint8_t* packed, hipStream_t s);
+hipError_t launch_unpack_weights_int(const Dims& d, const uint8_t* packed,
+                                     const lq_weights_view* out, hipStream_t s);
+hipError_t launch_unpack_act_int(const Dims& d, const uint8_t* act, int64_t M,
+                                 const lq_act_view* out, hipStream_t s);
+hipError_t launch_quantize_act_int(const Dims& d, int x_dtype, const uint8_t* packed,
+                                   const void* X, int64_t M, int64_t ldx, uint8_t* act,
+                                   const lq_act_debug* dbg, hipStream_t s);
+hipError_t launch_fwd_int(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M,
+                          uint16_t* Y, int64_t ldy, const lq_fwd_debug* dbg, hipStream_t s);
+
+// ---- device helpers ----------------------------------------------------------------------
+#if defined(__HIPCC__)
+__device__ __forceinline__ uint32_t nib_lo(uint32_t p) { return p & 0x87878787u; }
+__device__ __forceinline__ uint32_t nib_hi(uint32_t p)
+{
+    return __builtin_rotateleft32(p, 4) & 0x87878787u;
+}
+
+// Insert code e (0..7) with sign bit s (0|1) and magnitude m (0..7) into a packed dword.
+__device__ __forceinline__ uint32_t nib_put(int e, uint32_t s, uint32_t m)
+{
+    if (e < 4) return (s << (8 * e + 7)) | (m << (8 * e));
+    const int i = e - 4, j = (i - 1) & 3;
+    return (s << (8 * i + 3)) | (m << (8 * j + 4));
+}
+
+// Extract code e of a packed dword as a signed integer.
+__device__ __forceinline__ int nib_get(uint32_t p, int e)
+{
+    const uint32_t v = (e < 4) ? nib_lo(p) : nib_hi(p);
+    const uint32_t b = (v >> (8 * (e & 3))) & 0xFFu;
+    const int m = (int)(b & 7u);
+    return (b & 0x80u) ? -m : m;
+}
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ uint32_t bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+#endif
+
+}  // namespace lq

@@ -1,0 +1,63 @@
+"""Helpers of the GPU parity tests: run one layer through the HIP library and the CPU oracle."""
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+from paper_2604_18117_amd import workloads as wl
+
+
+def to_dev_x(X: np.ndarray, x_dtype: str) -> torch.Tensor:
+    if x_dtype == "bf16":
+        bits = wl.f32_to_bf16_bits(X).view(np.int16)
+        return torch.from_numpy(bits.copy()).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(X, np.float32)).cuda()
+
+
+def bf16_to_bits(t: torch.Tensor) -> np.ndarray:
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+@dataclass
+class GpuRun:
+    cfg: object
+    packed: torch.Tensor
+    act: torch.Tensor
+    Y: torch.Tensor
+    wv: object = None
+    av: object = None
+    adbg: object = None
+    fdbg: object = None
+
+
+def run_gpu(layer, X, W, L, R, debug=True, debug_acc=True):
+    from paper_2604_18117_amd import binding as lq
+    cfg = lq.config_for_layer(layer)
+    Wd = torch.from_numpy(W).cuda()
+    Ld = torch.from_numpy(L).cuda() if layer.r else None
+    Rd = torch.from_numpy(R).cuda() if layer.r else None
+    Xd = to_dev_x(X, layer.x_dtype)
+    packed = lq.lq_pack_weights(cfg, Wd, Ld, Rd)
+    M = X.shape[0]
+    if debug:
+        act, adbg = lq.lq_quantize_act(cfg, packed, Xd, debug=True)
+        Y, fdbg = lq.lq_linear_lowrank_fwd(cfg, packed, act, M, debug=True, debug_acc=debug_acc)
+        out = GpuRun(cfg, packed, act, Y, lq.lq_unpack_weights(cfg, packed), lq.lq_unpack_act(cfg, act, M),
+                     adbg, fdbg)
+    else:
+        act = lq.lq_quantize_act(cfg, packed, Xd)
+        Y = lq.lq_linear_lowrank_fwd(cfg, packed, act, M)
+        out = GpuRun(cfg, packed, act, Y)
+    torch.cuda.synchronize()
+    return out
+
+
+def run_oracle_int(oracle, layer, X, W, L, R, want_acc=True):
+    pk = oracle.pack_int(W, L if layer.r else None, R if layer.r else None, layer.g, layer.br_w_bits)
+    act = oracle.quantize_act_int(X, pk, layer.br_a_bits)
+    out = oracle.fwd_int(pk, act, want_acc=want_acc)
+    return pk, act, out
+
+
+def n(t):
+    return t.cpu().numpy()
