@@ -140,7 +140,7 @@ lq_status lq_quantize_act(const lq_config *cfg, const void *packed, const void *
 
 /* Forward (Fig. 1): main 4-bit product with per-group dequantisation, rank-r expansion of the
    re-quantised intermediate, sum, bf16 rounding.
-   Y: device, M x N bf16, row stride ldy elements (ldy >= N, ldy even, Y 4-byte aligned).
+   Y: device, M x N bf16, row stride ldy elements (ldy >= N, ldy % 8 == 0, Y 16-byte aligned).
    dbg may be NULL (production); with dbg the same kernel also writes the taps. */
 lq_status lq_linear_lowrank_fwd(const lq_config *cfg, const void *packed, const void *act,
                                 int64_t M, void *Y, int64_t ldy, const lq_fwd_debug *dbg,

@@ -180,7 +180,7 @@ lq_status lq_linear_lowrank_fwd(const lq_config* cfg, const void* packed, const 
     if (st != LQ_OK) return st;
     if (!packed || !act || !Y) return LQ_ERR_NULL;
     if (M < 1 || M > (1 << 24) || ldy < d.N) return LQ_ERR_SHAPE;
-    if (!aligned(packed, 256) || !aligned(act, 256) || !aligned(Y, 4) || (ldy & 1)) return LQ_ERR_ALIGN;
+    if (!aligned(packed, 256) || !aligned(act, 256) || !aligned(Y, 16) || (ldy & 7)) return LQ_ERR_ALIGN;
     if (d.mx) return LQ_ERR_UNSUPPORTED;
     hipError_t e = launch_fwd_int(d, (const uint8_t*)packed, (const uint8_t*)act, M, (uint16_t*)Y, ldy, dbg,
                                   (hipStream_t)stream);

@@ -62,10 +62,13 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
     constexpr int RBT = WM * 4;  // 32-row blocks per workgroup tile
     static_assert(RBT % NW == 0 || NW % RBT == 0, "staging split");
     constexpr int SPW = (RBT + NW - 1) / NW;  // row blocks staged per wavefront
-    constexpr int PF = (GC == 1) ? 2 : 1;     // weight prefetch distance in steps
 
     // [buffer][chunk in group][row block][part][lane][16 B]
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * GC * RBT * 2048];
+    constexpr int EPI_ROW = 144;                 // bytes per staged output row (128 + pad: no bank conflicts)
+    constexpr int EPI_WAVE = 32 * EPI_ROW;        // one 32 x 64 bf16 block per wavefront
+    constexpr int LDS_MAIN = 2 * GC * RBT * 2048;
+    constexpr int LDS_BYTES = LDS_MAIN > NW * EPI_WAVE ? LDS_MAIN : NW * EPI_WAVE;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -117,10 +120,10 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
         }
     };
 
-    // ---- weight prefetch ring ------------------------------------------------------------
-    v4i bq[PF + 1][GC][2];
-    float swq[PF + 1][2];
-    auto load_b = [&](int slot, int step) {
+    // ---- weight codes and scales of the next step (prefetched one step ahead) --------------
+    v4i bq[GC][2];
+    float swq[2];
+    auto load_b = [&](int step) {
 #pragma unroll
         for (int cbi = 0; cbi < 2; ++cbi) {
 #pragma unroll
@@ -128,11 +131,11 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
                 v4i v = {0, 0, 0, 0};
                 if (active && step < G)
                     v = *(const v4i*)(p.pq + ((size_t)((size_t)(cb0 + cbi) * C64 + step * GC + cc) * 64 + lane) * 16);
-                bq[slot][cc][cbi] = v;
+                bq[cc][cbi] = v;
             }
             float s = 0.f;
             if (active && step < G) s = p.swT[(size_t)step * p.N + (cb0 + cbi) * 32 + l32];
-            swq[slot][cbi] = s;
+            swq[cbi] = s;
         }
     };
 
@@ -145,8 +148,7 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
             for (int i = 0; i < 16; ++i) t[a][b][i] = 0.f;
 
     load_a(0);
-#pragma unroll
-    for (int d = 0; d <= PF; ++d) load_b(d, d);
+    load_b(0);
 
     for (int s = 0; s < G; ++s) {
         const int buf = s & 1;
@@ -160,57 +162,70 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
 #pragma unroll
             for (int cbi = 0; cbi < 2; ++cbi) {
 #pragma unroll
-                for (int cc = 0; cc < GC; ++cc) bu[cc][cbi] = expand8(bq[0][cc][cbi]);
-                sw[cbi] = swq[0][cbi];
+                for (int cc = 0; cc < GC; ++cc) bu[cc][cbi] = expand8(bq[cc][cbi]);
+                sw[cbi] = swq[cbi];
             }
-#pragma unroll
-            for (int d = 0; d < PF; ++d) {
-#pragma unroll
-                for (int cbi = 0; cbi < 2; ++cbi) {
-#pragma unroll
-                    for (int cc = 0; cc < GC; ++cc) bq[d][cc][cbi] = bq[d + 1][cc][cbi];
-                    swq[d][cbi] = swq[d + 1][cbi];
-                }
-            }
-            load_b(PF, s + PF + 1);
+            load_b(s + 1);
 
+            // Software pipeline over the 8 MFMA tiles of the wavefront: the matrix core works
+            // on tile j+1 while the vector ALU folds tile j into the running sums.
+            auto lds_a = [&](int rbi, int cc) -> v8i {
+                const uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wm * 4 + rbi) * 2048) + lane * 16;
+                const v4i lo = *(const v4i*)(base);
+                const v4i hi = *(const v4i*)(base + 1024);
+                return v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            };
+            auto tile_mfma = [&](const v8i (&a)[GC], int cbi) -> v16f {
+                v16f d = {0};
 #pragma unroll
-            for (int rbi = 0; rbi < 4; ++rbi) {
-                v8i a[GC];
+                for (int cc = 0; cc < GC; ++cc)
+                    d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[cc], bu[cc][cbi], d, 0, 0, 0, 0, 0, 0);
+                return d;
+            };
+            v8i af[2][GC];
+            v16f dd[2];
 #pragma unroll
-                for (int cc = 0; cc < GC; ++cc) {
-                    const uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wm * 4 + rbi) * 2048) + lane * 16;
-                    v4i lo = *(const v4i*)(base);
-                    v4i hi = *(const v4i*)(base + 1024);
-                    a[cc] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            for (int cc = 0; cc < GC; ++cc) af[0][cc] = lds_a(0, cc);
+            dd[0] = tile_mfma(af[0], 0);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int rbi = j >> 1, cbi = j & 1;
+                if (j + 1 < 8) {
+                    const int nrbi = (j + 1) >> 1, ncbi = (j + 1) & 1;
+                    dd[(j + 1) & 1] = tile_mfma(af[nrbi & 1], ncbi);
                 }
+                if (cbi == 0 && rbi + 1 < 4) {  // operand of the next row block, one tile ahead
 #pragma unroll
-                for (int cbi = 0; cbi < 2; ++cbi) {
-                    v16f d = {0};
+                    for (int cc = 0; cc < GC; ++cc) af[(rbi + 1) & 1][cc] = lds_a(rbi + 1, cc);
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int cc = 0; cc < GC; ++cc)
-                        d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[cc], bu[cc][cbi], d, 0, 0, 0, 0, 0, 0);
+                for (int i = 0; i < 16; ++i) t[rbi][cbi][i] = __builtin_fmaf(dd[j & 1][i], sw[cbi], t[rbi][cbi][i]);
+                if (DBG) {
+                    if (p.dbg_acc) {
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) t[rbi][cbi][i] = __builtin_fmaf(d[i], sw[cbi], t[rbi][cbi][i]);
-                    if (DBG) {
-                        if (p.dbg_acc) {
-#pragma unroll
-                            for (int i = 0; i < 16; ++i) {
-                                const int row = (rb0 + wm * 4 + rbi) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-                                const int col = (cb0 + cbi) * 32 + l32;
-                                if (row < p.M)
-                                    p.dbg_acc[((size_t)row * p.N + col) * G + s] = (int)(d[i] * 262144.0f);
-                            }
+                        for (int i = 0; i < 16; ++i) {
+                            const int row = (rb0 + wm * 4 + rbi) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+                            const int col = (cb0 + cbi) * 32 + l32;
+                            if (row < p.M)
+                                p.dbg_acc[((size_t)row * p.N + col) * G + s] = (int)(dd[j & 1][i] * 262144.0f);
                         }
                     }
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
 
+    // ---- epilogue: rank-r expansion, scales, sum, bf16 -------------------------------------
+    // Each wavefront turns one 32 x 64 block at a time into bf16, transposes it through its own
+    // LDS slice and writes full 128-byte rows (16 bytes per lane).
+    __syncthreads();  // everyone is done reading the operand buffers
     if (!active) return;
 
-    // ---- epilogue: rank-r expansion, scales, sum, bf16 -------------------------------------
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    uint8_t* stage = lds + wave * EPI_WAVE;
     const int nk = p.rp >> 5;
     float slv[2];
     v4i lqf[2][4];
@@ -225,6 +240,8 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
             lqf[cbi][kk] = v;
         }
     }
+    const int wr_off = (4 * half) * EPI_ROW + l32 * 2;        // this lane's column in the staged block
+    const int rd_row = lane >> 3, rd_seg = lane & 7;          // read-back: 8 lanes per 128-byte row
 #pragma unroll
     for (int rbi = 0; rbi < 4; ++rbi) {
         const int rbase = (rb0 + wm * 4 + rbi) * 32;
@@ -249,20 +266,39 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
                 if (kk < nk) a2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(tqf[kk], lqf[cbi][kk], a2, 0, 0, 0);
-            const int col = (cb0 + cbi) * 32 + l32;
+            float y[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int row = rbase + 8 * (i >> 2) + 4 * half + (i & 3);
-                const float ybr = ((float)a2[i] * stv[i >> 2][i & 3]) * slv[cbi];
-                const float y = __builtin_fmaf(sxv[i >> 2][i & 3], t[rbi][cbi][i], ybr);
-                if (row < p.M) {
-                    p.Y[(size_t)row * p.ldy + col] = (uint16_t)bf16_bits(y);
-                    if (DBG) {
+                const float ybr = __fmul_rn(__fmul_rn((float)a2[i], stv[i >> 2][i & 3]), slv[cbi]);
+                y[i] = __builtin_fmaf(sxv[i >> 2][i & 3], t[rbi][cbi][i], ybr);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const bf16x2 h = __builtin_convertvector(f32x2{y[i], y[i + 1]}, bf16x2);
+                const uint32_t w = __builtin_bit_cast(uint32_t, h);
+                const int o = wr_off + (8 * (i >> 2) + (i & 3)) * EPI_ROW + cbi * 64;
+                *(uint16_t*)(stage + o) = (uint16_t)(w & 0xFFFFu);
+                *(uint16_t*)(stage + o + EPI_ROW) = (uint16_t)(w >> 16);
+            }
+            if (DBG) {
+                const int col = (cb0 + cbi) * 32 + l32;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int row = rbase + 8 * (i >> 2) + 4 * half + (i & 3);
+                    if (row < p.M) {
                         if (p.dbg_acc2) p.dbg_acc2[(size_t)row * p.N + col] = a2[i];
-                        if (p.dbg_y32) p.dbg_y32[(size_t)row * p.N + col] = y;
+                        if (p.dbg_y32) p.dbg_y32[(size_t)row * p.N + col] = y[i];
                     }
                 }
             }
+        }
+        // read the block back row-wise (LDS operations of one wavefront complete in order)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int rl = q * 8 + rd_row;
+            const v4i v = *(const v4i*)(stage + rl * EPI_ROW + rd_seg * 16);
+            const int row = rbase + rl;
+            if (row < p.M) *(v4i*)(p.Y + (size_t)row * p.ldy + cb0 * 32 + rd_seg * 8) = v;
         }
     }
 }
