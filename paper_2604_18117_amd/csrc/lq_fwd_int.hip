@@ -70,7 +70,8 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
     constexpr int LDS_BYTES = LDS_MAIN > NW * EPI_WAVE ? LDS_MAIN : NW * EPI_WAVE;
     __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps address math scalar
     const int wm = wave / WN, wn = wave % WN;
     const int half = lane >> 5, l32 = lane & 31;
 
@@ -88,54 +89,54 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
 
     const int C64 = p.C64, G = p.G;
 
-    // ---- staging registers: packed activation codes for the next step -------------------
-    v4i apk[SPW][GC];
-    auto load_a = [&](int step) {
+    // ---- operand streams -----------------------------------------------------------------
+    // Global loads run TWO steps ahead of their use (an L2 round trip is about as long as one
+    // step), in two alternating register sets per stream; the step loop is unrolled by two so
+    // that the sets are addressed statically.  Steps and row blocks are clamped instead of
+    // predicated: the loop body stays branch-free, and a clamped load only re-reads valid data
+    // that never reaches a stored output.
+    static_assert(RBT % NW == 0, "every wavefront stages the same number of row blocks");
+    const uint32_t lane16 = (uint32_t)lane * 16u;
+    const uint8_t* xq_base[SPW];
 #pragma unroll
-        for (int i = 0; i < SPW; ++i) {
-            const int rbl = wave * SPW + i;
-            const int rb = rb0 + rbl;
+    for (int i = 0; i < SPW; ++i) {
+        int rb = rb0 + wave * SPW + i;
+        rb = rb < p.nrb ? rb : p.nrb - 1;
+        xq_base[i] = p.xq + (size_t)rb * C64 * 1024;
+    }
+    const int cbw = (cb0 * 32 < p.N) ? cb0 : 0;  // wavefronts past the last column read block 0 (unused)
+    const uint8_t* pq_base[2] = {p.pq + (size_t)cbw * C64 * 1024, p.pq + (size_t)(cbw + 1) * C64 * 1024};
+    const float* sw_base = p.swT + cbw * 32;
+
+    struct AStage { v4i v[SPW][GC]; };
+    struct BStage { v4i v[GC][2]; float sw[2]; };
+    auto load_a = [&](AStage& a, int step) {
+        const int st = step < G ? step : G - 1;
+#pragma unroll
+        for (int i = 0; i < SPW; ++i)
+#pragma unroll
+            for (int cc = 0; cc < GC; ++cc)
+                a.v[i][cc] = *(const v4i*)(xq_base[i] + (size_t)(st * GC + cc) * 1024 + lane16);
+    };
+    auto store_a = [&](const AStage& a, int buf) {
+#pragma unroll
+        for (int i = 0; i < SPW; ++i)
 #pragma unroll
             for (int cc = 0; cc < GC; ++cc) {
-                v4i v = {0, 0, 0, 0};
-                if (rbl < RBT && rb < p.nrb)
-                    v = *(const v4i*)(p.xq + ((size_t)((size_t)rb * C64 + step * GC + cc) * 64 + lane) * 16);
-                apk[i][cc] = v;
+                const v8i e = expand8(a.v[i][cc]);
+                uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wave * SPW + i) * 2048) + lane16;
+                *(v4i*)(base) = v4i{e[0], e[1], e[2], e[3]};
+                *(v4i*)(base + 1024) = v4i{e[4], e[5], e[6], e[7]};
             }
-        }
     };
-    auto store_a = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < SPW; ++i) {
-            const int rbl = wave * SPW + i;
-            if (rbl < RBT) {
-#pragma unroll
-                for (int cc = 0; cc < GC; ++cc) {
-                    v8i e = expand8(apk[i][cc]);
-                    uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + rbl) * 2048) + lane * 16;
-                    *(v4i*)(base) = v4i{e[0], e[1], e[2], e[3]};
-                    *(v4i*)(base + 1024) = v4i{e[4], e[5], e[6], e[7]};
-                }
-            }
-        }
-    };
-
-    // ---- weight codes and scales of the next step (prefetched one step ahead) --------------
-    v4i bq[GC][2];
-    float swq[2];
-    auto load_b = [&](int step) {
+    auto load_b = [&](BStage& b, int step) {
+        const int st = step < G ? step : G - 1;
 #pragma unroll
         for (int cbi = 0; cbi < 2; ++cbi) {
 #pragma unroll
-            for (int cc = 0; cc < GC; ++cc) {
-                v4i v = {0, 0, 0, 0};
-                if (active && step < G)
-                    v = *(const v4i*)(p.pq + ((size_t)((size_t)(cb0 + cbi) * C64 + step * GC + cc) * 64 + lane) * 16);
-                bq[cc][cbi] = v;
-            }
-            float s = 0.f;
-            if (active && step < G) s = p.swT[(size_t)step * p.N + (cb0 + cbi) * 32 + l32];
-            swq[cbi] = s;
+            for (int cc = 0; cc < GC; ++cc)
+                b.v[cc][cbi] = *(const v4i*)(pq_base[cbi] + (size_t)(st * GC + cc) * 1024 + lane16);
+            b.sw[cbi] = sw_base[(size_t)st * p.N + cbi * 32 + l32];
         }
     };
 
@@ -147,46 +148,48 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
 #pragma unroll
             for (int i = 0; i < 16; ++i) t[a][b][i] = 0.f;
 
-    load_a(0);
-    load_b(0);
+    v8i bu[GC][2];   // expanded weight operands of the current step
+    float sw[2];     // their scales
+    auto expand_b = [&](const BStage& b) {
+#pragma unroll
+        for (int cbi = 0; cbi < 2; ++cbi) {
+#pragma unroll
+            for (int cc = 0; cc < GC; ++cc) bu[cc][cbi] = expand8(b.v[cc][cbi]);
+            // a real move: keeps `sw` in a register of its own, so that the next load can land
+            // in b.sw directly (a coalesced copy would force a wait on that fresh load)
+            asm volatile("v_mov_b32 %0, %1" : "=v"(sw[cbi]) : "v"(b.sw[cbi]));
+        }
+    };
 
-    for (int s = 0; s < G; ++s) {
+    // One step = one weight group.  On entry: LDS buffer s&1 holds the activation operands of
+    // step s, `bu`/`sw` the weight operands of step s, `a`/`b` the packed data of step s+1
+    // (loaded two steps ago).  During the step the data of step s+1 is expanded (activations
+    // into the other LDS buffer, weights in registers) in the shadow of MFMAs already in
+    // flight, and the loads for step s+3 are issued into `a`/`b`.
+    auto do_step = [&](int s, AStage& a, BStage& b) {
         const int buf = s & 1;
-        store_a(buf);
-        if (s + 1 < G) load_a(s + 1);
-        __syncthreads();
-
-        if (active) {
-            v8i bu[GC][2];
-            float sw[2];
-#pragma unroll
-            for (int cbi = 0; cbi < 2; ++cbi) {
-#pragma unroll
-                for (int cc = 0; cc < GC; ++cc) bu[cc][cbi] = expand8(bq[cc][cbi]);
-                sw[cbi] = swq[cbi];
-            }
-            load_b(s + 1);
-
-            // Software pipeline over the 8 MFMA tiles of the wavefront: the matrix core works
-            // on tile j+1 while the vector ALU folds tile j into the running sums.
+        {
             auto lds_a = [&](int rbi, int cc) -> v8i {
-                const uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wm * 4 + rbi) * 2048) + lane * 16;
+                const uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wm * 4 + rbi) * 2048) + lane16;
                 const v4i lo = *(const v4i*)(base);
                 const v4i hi = *(const v4i*)(base + 1024);
                 return v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
             };
-            auto tile_mfma = [&](const v8i (&a)[GC], int cbi) -> v16f {
+            auto tile_mfma = [&](const v8i (&af)[GC], int cbi) -> v16f {
                 v16f d = {0};
 #pragma unroll
                 for (int cc = 0; cc < GC; ++cc)
-                    d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[cc], bu[cc][cbi], d, 0, 0, 0, 0, 0, 0);
+                    d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(af[cc], bu[cc][cbi], d, 0, 0, 0, 0, 0, 0);
                 return d;
             };
             v8i af[2][GC];
             v16f dd[2];
+            const float swc[2] = {sw[0], sw[1]};
 #pragma unroll
             for (int cc = 0; cc < GC; ++cc) af[0][cc] = lds_a(0, cc);
             dd[0] = tile_mfma(af[0], 0);
+            // software pipeline over the 8 MFMA tiles: the matrix core works on tile j+1 while
+            // the vector ALU folds tile j into the running sums
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int rbi = j >> 1, cbi = j & 1;
@@ -198,11 +201,19 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
 #pragma unroll
                     for (int cc = 0; cc < GC; ++cc) af[(rbi + 1) & 1][cc] = lds_a(rbi + 1, cc);
                 }
+                if (j == 0) {  // fills the pipeline start-up bubble
+                    store_a(a, buf ^ 1);
+                    load_a(a, s + 3);
+                }
+                if (j == 7) {  // the last MFMA of the step is in flight: bu is free
+                    expand_b(b);
+                    load_b(b, s + 3);
+                }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) t[rbi][cbi][i] = __builtin_fmaf(dd[j & 1][i], sw[cbi], t[rbi][cbi][i]);
+                for (int i = 0; i < 16; ++i) t[rbi][cbi][i] = __builtin_fmaf(dd[j & 1][i], swc[cbi], t[rbi][cbi][i]);
                 if (DBG) {
-                    if (p.dbg_acc) {
+                    if (p.dbg_acc && active) {
 #pragma unroll
                         for (int i = 0; i < 16; ++i) {
                             const int row = (rb0 + wm * 4 + rbi) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
@@ -215,13 +226,39 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        __syncthreads();
+    };
+    AStage a0, a1;
+    BStage b0, b1;
+    load_a(a0, 0);
+    load_b(b0, 0);
+    store_a(a0, 0);
+    expand_b(b0);
+    // issue order = the loop's steady-state order (the wait counts are derived from it)
+    __builtin_amdgcn_sched_barrier(0);
+    load_a(a0, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_b(b0, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_a(a1, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    load_b(b1, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+
+    // Every wavefront runs the same branch-free loop; one without valid output (past the last
+    // column or row block of a partial tile) works on clamped operands and stores nothing.
+    int s = 0;
+    for (; s + 1 < G; s += 2) {
+        do_step(s, a0, b0);
+        do_step(s + 1, a1, b1);
     }
+    if (s < G) do_step(s, a0, b0);
 
     // ---- epilogue: rank-r expansion, scales, sum, bf16 -------------------------------------
     // Each wavefront turns one 32 x 64 block at a time into bf16, transposes it through its own
     // LDS slice and writes full 128-byte rows (16 bytes per lane).
-    __syncthreads();  // everyone is done reading the operand buffers
-    if (!active) return;
+    if (!active) return;  // (the loop's last barrier already separates operand reads from the staging below)
 
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     typedef float f32x2 __attribute__((ext_vector_type(2)));
