@@ -62,6 +62,7 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
     constexpr int RBT = WM * 4;  // 32-row blocks per workgroup tile
     static_assert(RBT % NW == 0 || NW % RBT == 0, "staging split");
     constexpr int SPW = (RBT + NW - 1) / NW;  // row blocks staged per wavefront
+    constexpr int STAGES = (GC == 1) ? 2 : 1; // register sets of the global-load pipeline
 
     // [buffer][chunk in group][row block][part][lane][16 B]
     constexpr int EPI_ROW = 144;                 // bytes per staged output row (128 + pad: no bank conflicts)
@@ -203,11 +204,11 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
                 }
                 if (j == 0) {  // fills the pipeline start-up bubble
                     store_a(a, buf ^ 1);
-                    load_a(a, s + 3);
+                    load_a(a, s + 1 + STAGES);
                 }
                 if (j == 7) {  // the last MFMA of the step is in flight: bu is free
                     expand_b(b);
-                    load_b(b, s + 3);
+                    load_b(b, s + 1 + STAGES);
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -228,32 +229,49 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
         }
         __syncthreads();
     };
-    AStage a0, a1;
-    BStage b0, b1;
-    load_a(a0, 0);
-    load_b(b0, 0);
-    store_a(a0, 0);
-    expand_b(b0);
-    // issue order = the loop's steady-state order (the wait counts are derived from it)
-    __builtin_amdgcn_sched_barrier(0);
-    load_a(a0, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    load_b(b0, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    load_a(a1, 2);
-    __builtin_amdgcn_sched_barrier(0);
-    load_b(b1, 2);
-    __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();
-
-    // Every wavefront runs the same branch-free loop; one without valid output (past the last
-    // column or row block of a partial tile) works on clamped operands and stores nothing.
-    int s = 0;
-    for (; s + 1 < G; s += 2) {
-        do_step(s, a0, b0);
-        do_step(s + 1, a1, b1);
+    // Two register sets (loads two steps ahead) for 64-deep groups; for 128-deep groups a step
+    // is twice as long and one set (loads one step ahead) hides the latency with fewer registers.
+    if constexpr (STAGES == 2) {
+        AStage a0, a1;
+        BStage b0, b1;
+        load_a(a0, 0);
+        load_b(b0, 0);
+        store_a(a0, 0);
+        expand_b(b0);
+        // issue order = the loop's steady-state order (the wait counts are derived from it)
+        __builtin_amdgcn_sched_barrier(0);
+        load_a(a0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        load_b(b0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        load_a(a1, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        load_b(b1, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        // Every wavefront runs the same branch-free loop; one without valid output (past the
+        // last column or row block of a partial tile) works on clamped operands, stores nothing.
+        int s = 0;
+        for (; s + 1 < G; s += 2) {
+            do_step(s, a0, b0);
+            do_step(s + 1, a1, b1);
+        }
+        if (s < G) do_step(s, a0, b0);
+    } else {
+        AStage a0;
+        BStage b0;
+        load_a(a0, 0);
+        load_b(b0, 0);
+        store_a(a0, 0);
+        expand_b(b0);
+        __builtin_amdgcn_sched_barrier(0);
+        load_a(a0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        load_b(b0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        for (int s = 0; s < G; ++s) do_step(s, a0, b0);
     }
-    if (s < G) do_step(s, a0, b0);
 
     // ---- epilogue: rank-r expansion, scales, sum, bf16 -------------------------------------
     // Each wavefront turns one 32 x 64 block at a time into bf16, transposes it through its own
@@ -379,9 +397,9 @@ hipError_t launch_fwd_int(const Dims& d, const uint8_t* packed, const uint8_t* a
     p.dbg_y32 = dbg ? dbg->y32 : nullptr;
     const bool want_dbg = dbg && (dbg->acc || dbg->acc2 || dbg->y32);
     if (d.g == 64) {
-        return want_dbg ? launch_cfg<2, 4, 1, true>(p, s) : launch_cfg<2, 4, 1, false>(p, s);
+        return want_dbg ? launch_cfg<1, 4, 1, true>(p, s) : launch_cfg<1, 4, 1, false>(p, s);
     } else {
-        return want_dbg ? launch_cfg<2, 4, 2, true>(p, s) : launch_cfg<2, 4, 2, false>(p, s);
+        return want_dbg ? launch_cfg<1, 4, 2, true>(p, s) : launch_cfg<1, 4, 2, false>(p, s);
     }
 }
 
