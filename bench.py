@@ -30,6 +30,8 @@ def main():
     ap.add_argument("--workload", default="c2_qkv", help="layer name from workloads.LAYERS")
     ap.add_argument("--oracle-seconds", type=float, default=15.0, help="CPU budget of the oracle leg (0 = skip)")
     ap.add_argument("--sets", type=int, default=4, help="distinct buffer sets rotated through")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
+                    help="only run a plain device-to-device copy of BYTES (calibrates the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (the path shards over tokens with no collective; "
@@ -44,6 +46,15 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_probe:
+        src = torch.empty(args.copy_probe, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": args.copy_probe, "copies": 3}))
+        return
     layer = wl.LAYERS[args.workload]
     X, W, L, R = wl.make_inputs(layer)
     cfg = lq.config_for_layer(layer)
