@@ -16,6 +16,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_MFMA_TFLOPS = 5033.0   # MI355X dense FP8 / INT8 matrix peak (the main product runs on the FP8 pipe)
+# HBM bytes per forward launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/fwd_int_kernel_c2_qkv.md),
+# each scaled by the factor a plain copy of known size gives (2.0 for FETCH_SIZE, 1.0 for WRITE_SIZE).
+MEASURED_TRAFFIC_BYTES = {"c2_qkv": 22226.0 * 1024 * 2.0 + 55296.0 * 1024 * 1.0}
 
 
 def layer_ops(l):
@@ -116,7 +119,7 @@ def main():
                    "x_dtype": layer.x_dtype, "buffer_sets": nsets},
         "roofline": {"bound": "mfma", "kernel": "fwd_int_kernel", "achieved": round(fwd_tops, 2),
                      "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(fwd_tops / PEAK_MFMA_TFLOPS, 4),
-                     "traffic": None, "avg_kernel_ms": round(fwd_ms, 5)},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(layer.name), "algorithmic_ops": fwd_ops, "avg_kernel_ms": round(fwd_ms, 5)},
         "act_kernel": {"bound": "hbm", "avg_kernel_ms": round(act_ms, 5), "achieved": round(act_gbs, 1),
                        "peak": 8000.0, "unit": "GB/s", "frac": round(act_gbs / 8000.0, 4)},
     }

@@ -1,0 +1,113 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every symbol the header
+declares, reports sizes, and rejects bad arguments before launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lq():
+    if not os.path.exists(os.path.join(ROOT, "paper_2604_18117_amd", "liblq.so")):
+        from paper_2604_18117_amd import build
+        build.build()
+    from paper_2604_18117_amd import binding
+    return binding
+
+
+def test_exports_every_declared_symbol(lq):
+    header = open(os.path.join(ROOT, "include", "lq.h")).read()
+    declared = set(re.findall(r"\b(lq_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(lq.EXPORTS)
+    for name in declared:
+        assert getattr(lq.raw(), name) is not None
+
+
+def test_status_strings(lq):
+    seen = {lq.lq_status_string(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+
+
+def test_sizes_follow_the_layout(lq):
+    cfg = lq.make_config(3456, 1152, 32, "int", 64, 8, 8)
+    pb = lq.lq_packed_sizes(cfg)
+    # codes N*K/2 + scales N*G*4 + lq N*32 + sl N*4 + rq r*K + sr r*4, each section 256-aligned
+    parts = [3456 * 1152 // 2, 3456 * 18 * 4, 3456 * 32, 3456 * 4, 32 * 1152, 32 * 4]
+    assert pb == sum((x + 255) // 256 * 256 for x in parts)
+    ab = lq.lq_act_sizes(cfg, 8192)
+    parts = [8192 * 1152 // 2, 8192 * 4, 8192 * 32, 8192 * 4]
+    assert ab == sum((x + 255) // 256 * 256 for x in parts)
+    # M is padded to a multiple of 32 rows
+    assert lq.lq_act_sizes(cfg, 1) == lq.lq_act_sizes(cfg, 32) < lq.lq_act_sizes(cfg, 33)
+
+
+def _cfg(lq, **kw):
+    base = dict(N=128, K=256, rank=32, family="int", group=64, br_w_bits=8, br_a_bits=8)
+    base.update(kw)
+    return lq.make_config(base["N"], base["K"], base["rank"], base["family"], base["group"],
+                          base["br_w_bits"], base["br_a_bits"])
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(N=100), "LQ_ERR_SHAPE"), (dict(K=96), "LQ_ERR_SHAPE"), (dict(rank=24), "LQ_ERR_SHAPE"),
+    (dict(group=32), "LQ_ERR_SHAPE"), (dict(K=192, group=128), "LQ_ERR_SHAPE"), (dict(N=0), "LQ_ERR_SHAPE"),
+])
+def test_shape_contract(lq, kw, status):
+    n = C.c_size_t(0)
+    cfg = _cfg(lq, **kw)
+    assert lq.raw().lq_packed_sizes(C.byref(cfg), C.byref(n)) == getattr(lq, status)
+
+
+def test_unsupported_combinations(lq):
+    n = C.c_size_t(0)
+    cfg = _cfg(lq)
+    cfg.br_a = lq.LQ_INT4           # branch activations narrower than 6 bits are not a defined regime
+    assert lq.raw().lq_packed_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    cfg = _cfg(lq)
+    cfg.main_a = lq.LQ_INT8
+    assert lq.raw().lq_packed_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    cfg = _cfg(lq)
+    cfg.reserved = 1
+    assert lq.raw().lq_packed_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    cfg = _cfg(lq)
+    cfg.main_a_group = 64           # per-token-group activations are reserved
+    assert lq.raw().lq_packed_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+
+
+def test_argument_errors_before_any_launch(lq):
+    raw = lq.raw()
+    cfg = _cfg(lq)
+    good = C.c_void_p(1 << 20)       # fake, suitably aligned addresses: never dereferenced on these paths
+    odd = C.c_void_p((1 << 20) + 4)
+    pb, ab = lq.lq_packed_sizes(cfg), lq.lq_act_sizes(cfg, 64)
+    assert raw.lq_packed_sizes(None, None) == lq.LQ_ERR_NULL
+    assert raw.lq_pack_weights(C.byref(cfg), None, good, good, good, pb, None) == lq.LQ_ERR_NULL
+    assert raw.lq_pack_weights(C.byref(cfg), good, None, good, good, pb, None) == lq.LQ_ERR_NULL
+    assert raw.lq_pack_weights(C.byref(cfg), good, good, good, odd, pb, None) == lq.LQ_ERR_ALIGN
+    assert raw.lq_pack_weights(C.byref(cfg), good, good, good, good, pb - 1, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert raw.lq_quantize_act(C.byref(cfg), good, None, 64, 256, good, ab, None, None) == lq.LQ_ERR_NULL
+    assert raw.lq_quantize_act(C.byref(cfg), None, good, 64, 256, good, ab, None, None) == lq.LQ_ERR_NULL
+    assert raw.lq_quantize_act(C.byref(cfg), good, good, 0, 256, good, ab, None, None) == lq.LQ_ERR_SHAPE
+    assert raw.lq_quantize_act(C.byref(cfg), good, good, 64, 255, good, ab, None, None) == lq.LQ_ERR_SHAPE
+    assert raw.lq_quantize_act(C.byref(cfg), good, good, 64, 260, good, ab, None, None) == lq.LQ_ERR_ALIGN
+    assert raw.lq_quantize_act(C.byref(cfg), good, odd, 64, 256, good, ab, None, None) == lq.LQ_ERR_ALIGN
+    assert raw.lq_quantize_act(C.byref(cfg), good, good, 64, 256, good, ab - 1, None, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, good, 64, None, 128, None, None) == lq.LQ_ERR_NULL
+    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, good, 64, good, 64, None, None) == lq.LQ_ERR_SHAPE
+    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, good, 64, good, 132, None, None) == lq.LQ_ERR_ALIGN
+    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, good, 64, odd, 128, None, None) == lq.LQ_ERR_ALIGN
+    assert raw.lq_unpack_weights(C.byref(cfg), None, None, None) == lq.LQ_ERR_NULL
+    assert raw.lq_unpack_act(C.byref(cfg), good, 0, None, None) == lq.LQ_ERR_NULL
+    # K beyond the register-resident row of the activation kernel
+    big = _cfg(lq, K=8192)
+    assert raw.lq_quantize_act(C.byref(big), good, good, 64, 8192, good, 1 << 30, None, None) == lq.LQ_ERR_UNSUPPORTED
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "single-GPU" in r.stderr
