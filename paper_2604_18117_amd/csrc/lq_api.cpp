@@ -46,9 +46,11 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         if (cfg->main_a != LQ_MXFP4_E2M1) return LQ_ERR_UNSUPPORTED;
         if (cfg->main_w_group != 32 || cfg->main_a_group != 32) return LQ_ERR_SHAPE;
         if (cfg->br_w != LQ_FP8_E4M3 || cfg->br_a != LQ_FP8_E4M3) return LQ_ERR_UNSUPPORTED;
+        if (cfg->K % 128 != 0) return LQ_ERR_SHAPE;  // the MX forward stages K in steps of 128
         d->mx = true;
         d->g = 32;
         d->qmax_bw = d->qmax_ba = 0;
+        d->rp = (r + 63) / 64 * 64;                  // FP8 expansion runs 64 deep
     } else {
         return LQ_ERR_UNSUPPORTED;
     }
@@ -63,7 +65,7 @@ PackedLayout packed_layout(const Dims& d)
     pl.off_pq = o;
     o = align256(o + (size_t)d.N * d.K / 2);
     pl.off_sw = o;
-    o = align256(o + (d.mx ? (size_t)d.N * d.G : (size_t)d.N * d.G * 4));
+    o = align256(o + (d.mx ? (size_t)(d.N / 32) * ((d.C64 + 3) / 4) * 256 : (size_t)d.N * d.G * 4));
     pl.off_lq = o;
     o = align256(o + (size_t)d.N * d.rp);
     pl.off_sl = o;
@@ -84,7 +86,7 @@ ActLayout act_layout(const Dims& d, int64_t M)
     al.off_xq = o;
     o = align256(o + (size_t)al.Mp * d.K / 2);
     al.off_sx = o;
-    o = align256(o + (d.mx ? (size_t)al.Mp * d.G : (size_t)al.Mp * 4));
+    o = align256(o + (d.mx ? (size_t)(al.Mp / 32) * ((d.C64 + 3) / 4) * 256 : (size_t)al.Mp * 4));
     al.off_tq = o;
     o = align256(o + (size_t)al.Mp * d.rp);
     al.off_st = o;
@@ -146,8 +148,8 @@ lq_status lq_pack_weights(const lq_config* cfg, const float* W, const float* L, 
     if (d.r > 0 && (!L || !R)) return LQ_ERR_NULL;
     if (!aligned(packed, 256) || !aligned(W, 4)) return LQ_ERR_ALIGN;
     if (packed_bytes < packed_layout(d).total) return LQ_ERR_BUFFER_TOO_SMALL;
-    if (d.mx) return LQ_ERR_UNSUPPORTED;
-    hipError_t e = launch_pack_int(d, cfg->residual_from_quantized, W, L, R, (uint8_t*)packed, (hipStream_t)stream);
+    hipError_t e = d.mx ? launch_pack_mx(d, cfg->residual_from_quantized, W, L, R, (uint8_t*)packed, (hipStream_t)stream)
+                        : launch_pack_int(d, cfg->residual_from_quantized, W, L, R, (uint8_t*)packed, (hipStream_t)stream);
     return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }
 
@@ -164,11 +166,12 @@ lq_status lq_quantize_act(const lq_config* cfg, const void* packed, const void* 
     if (!aligned(X, 16) || (ldx * es) % 16 != 0 || !aligned(act, 256) || (packed && !aligned(packed, 256)))
         return LQ_ERR_ALIGN;
     if (act_bytes < act_layout(d, M).total) return LQ_ERR_BUFFER_TOO_SMALL;
-    if (d.mx) return LQ_ERR_UNSUPPORTED;
     const int maxc = (d.C64 + 3) / 4;
     if (maxc > (cfg->x_dtype == LQ_BF16 ? 18 : 9)) return LQ_ERR_UNSUPPORTED;  // K beyond the register-resident row
-    hipError_t e = launch_quantize_act_int(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,
-                                           (hipStream_t)stream);
+    hipError_t e = d.mx ? launch_quantize_act_mx(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,
+                                                 (hipStream_t)stream)
+                        : launch_quantize_act_int(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,
+                                                  (hipStream_t)stream);
     return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }
 
@@ -181,9 +184,10 @@ lq_status lq_linear_lowrank_fwd(const lq_config* cfg, const void* packed, const 
     if (!packed || !act || !Y) return LQ_ERR_NULL;
     if (M < 1 || M > (1 << 24) || ldy < d.N) return LQ_ERR_SHAPE;
     if (!aligned(packed, 256) || !aligned(act, 256) || !aligned(Y, 16) || (ldy & 7)) return LQ_ERR_ALIGN;
-    if (d.mx) return LQ_ERR_UNSUPPORTED;
-    hipError_t e = launch_fwd_int(d, (const uint8_t*)packed, (const uint8_t*)act, M, (uint16_t*)Y, ldy, dbg,
-                                  (hipStream_t)stream);
+    hipError_t e = d.mx ? launch_fwd_mx(d, (const uint8_t*)packed, (const uint8_t*)act, M, (uint16_t*)Y, ldy, dbg,
+                                        (hipStream_t)stream)
+                        : launch_fwd_int(d, (const uint8_t*)packed, (const uint8_t*)act, M, (uint16_t*)Y, ldy, dbg,
+                                         (hipStream_t)stream);
     return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }
 
@@ -194,8 +198,8 @@ lq_status lq_unpack_weights(const lq_config* cfg, const void* packed, const lq_w
     if (st != LQ_OK) return st;
     if (!packed || !out) return LQ_ERR_NULL;
     if (!aligned(packed, 256)) return LQ_ERR_ALIGN;
-    if (d.mx) return LQ_ERR_UNSUPPORTED;
-    hipError_t e = launch_unpack_weights_int(d, (const uint8_t*)packed, out, (hipStream_t)stream);
+    hipError_t e = d.mx ? launch_unpack_weights_mx(d, (const uint8_t*)packed, out, (hipStream_t)stream)
+                        : launch_unpack_weights_int(d, (const uint8_t*)packed, out, (hipStream_t)stream);
     return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }
 
@@ -207,8 +211,8 @@ lq_status lq_unpack_act(const lq_config* cfg, const void* act, int64_t M, const 
     if (!act || !out) return LQ_ERR_NULL;
     if (M < 1 || M > (1 << 24)) return LQ_ERR_SHAPE;
     if (!aligned(act, 256)) return LQ_ERR_ALIGN;
-    if (d.mx) return LQ_ERR_UNSUPPORTED;
-    hipError_t e = launch_unpack_act_int(d, (const uint8_t*)act, M, out, (hipStream_t)stream);
+    hipError_t e = d.mx ? launch_unpack_act_mx(d, (const uint8_t*)act, M, out, (hipStream_t)stream)
+                        : launch_unpack_act_int(d, (const uint8_t*)act, M, out, (hipStream_t)stream);
     return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }
 

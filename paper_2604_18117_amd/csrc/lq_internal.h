@@ -26,9 +26,12 @@ namespace lq {
 // so that lane l of a wavefront reads its v_mfma_f32_32x32x64_f8f6f4 operand (row l%32,
 // K half l/32) as one aligned 16-byte load at (block, chunk) base + 16*l.
 //
-// For main_w_group == 128 the same bytes are consumed by v_mfma_f32_16x16x128_f8f6f4 (one
-// whole group per instruction); the fragment order is then
-//     [block of 16 rows][group][quarter = (k%128)/32][row % 16][16 bytes]
+// MX family: E2M1 codes in the same fragment order, code i of a lane's 32 in nibble i of its 16
+// bytes (the FP4 operand layout of v_mfma_scale_f32_32x32x64_f8f6f4).  E8M0 scales:
+//     [block of 32 rows][quad = chunk/4][lane = row%32 + 32*half][4 bytes = chunks 4q..4q+3]
+// so that a lane's scale operand for four consecutive chunks is one dword and the instruction's
+// op_sel picks the chunk's byte (padding bytes hold 127 = 2^0).  Branch codes are E4M3 bytes;
+// lq / tq rows are zero-padded to a multiple of 64.
 // ---------------------------------------------------------------------------------------
 
 struct Dims {
@@ -80,6 +83,18 @@ hipError_t launch_quantize_act_int(const Dims& d, int x_dtype, const uint8_t* pa
                                    const lq_act_debug* dbg, hipStream_t s);
 hipError_t launch_fwd_int(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M,
                           uint16_t* Y, int64_t ldy, const lq_fwd_debug* dbg, hipStream_t s);
+
+hipError_t launch_pack_mx(const Dims& d, int residual_from_quantized, const float* W, const float* L,
+                          const float* R, uint8_t* packed, hipStream_t s);
+hipError_t launch_unpack_weights_mx(const Dims& d, const uint8_t* packed, const lq_weights_view* out,
+                                    hipStream_t s);
+hipError_t launch_unpack_act_mx(const Dims& d, const uint8_t* act, int64_t M, const lq_act_view* out,
+                                hipStream_t s);
+hipError_t launch_quantize_act_mx(const Dims& d, int x_dtype, const uint8_t* packed, const void* X,
+                                  int64_t M, int64_t ldx, uint8_t* act, const lq_act_debug* dbg,
+                                  hipStream_t s);
+hipError_t launch_fwd_mx(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M,
+                         uint16_t* Y, int64_t ldy, const lq_fwd_debug* dbg, hipStream_t s);
 
 // ---- device helpers ----------------------------------------------------------------------
 #if defined(__HIPCC__)

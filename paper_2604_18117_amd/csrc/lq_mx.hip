@@ -1,0 +1,764 @@
+// MX family (App. A.3 "MX Formats"): main product in MXFP4 (E2M1 elements, blocks of 32 along K,
+// E8M0 power-of-two scale) on v_mfma_scale_f32_32x32x64_f8f6f4 -- the hardware applies both block
+// scales, so there is no vector-ALU dequantisation at all -- and the low-rank branch in FP8 E4M3
+// with one fp32 scale per token / per row of L, R (Fig. 1, Eq. 5).
+//
+//   pack      : Q2(R), Q2(L) -> E4M3;  P = W - deq(Q2 L) deq(Q2 R) (fp64 chain, one rounding);
+//               Q1(P) -> E2M1 + E8M0 per 32 values
+//   act       : Q1(X) -> E2M1 + E8M0;  Q2(X) -> E4M3 (registers only);  T = (X8 . R8^T * sxb) * sr;
+//               Q2(T) -> E4M3 + st
+//   forward   : t = sum_blocks 2^(ex+ew) (x . p)  [scaled MFMA, fp32 accumulate];
+//               y = t + (tq8 . l8^T * st) * sl;  Y = bf16_rne(y)
+//
+// Block scale exponent = (exponent field of the block amax) - 2, i.e. floor(log2 amax) - 2; elements
+// are converted by v_cvt_scalef32_pk_fp4_f32 (nearest even, saturating at +-6) and
+// v_cvt_pk_fp8_f32 (nearest even; inputs are clamped to +-448 first because the instruction
+// returns NaN, not 448, above 464).
+#include <type_traits>
+
+#include "lq_internal.h"
+
+namespace lq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// ---------------------------------------------------------------------------------------------
+// shared device helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ size_t mx_code_offset(int row, int k, int C64)  // dword holding code (row,k)
+{
+    const int blk = row >> 5, c = k >> 6, half = (k & 63) >> 5, d = (k & 31) >> 3;
+    return ((size_t)((size_t)blk * C64 + c) * 64 + (row & 31) + 32 * half) * 16 + d * 4;
+}
+__device__ __forceinline__ size_t mx_scale_offset(int row, int c, int half, int CQ)  // byte of block (row, c, half)
+{
+    return ((size_t)((size_t)(row >> 5) * CQ + (c >> 2)) * 64 + (row & 31) + 32 * half) * 4 + (c & 3);
+}
+__device__ __forceinline__ size_t mx_rq_offset(int j, int k, int r)
+{
+    const int c = k >> 6, kq = (k & 63) >> 4;
+    return ((size_t)((size_t)c * (r >> 4) + (j >> 4)) * 64 + (j & 15) + 16 * kq) * 16 + (k & 15);
+}
+__device__ __forceinline__ uint32_t e8m0_of(float amax)  // floor(log2 amax) - 2 + 127, clamped at 0
+{
+    const int e = (int)((__float_as_uint(amax) >> 23) & 0xFFu) - 2;
+    return (amax == 0.0f || e < 0) ? 0u : (uint32_t)e;
+}
+__device__ __forceinline__ float e8m0_value(uint32_t E)  // 2^(E-127) as a float (E >= 1), 2^-127 for E = 0
+{
+    return E ? __uint_as_float(E << 23) : __uint_as_float(0x00400000u);
+}
+__device__ __forceinline__ uint32_t fp8_byte(float u)  // E4M3, nearest even, saturating
+{
+    u = fminf(fmaxf(u, -448.0f), 448.0f);
+    return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(u, u, 0, false) & 0xFFu;
+}
+__device__ __forceinline__ uint32_t fp8_pair(float u0, float u1)  // two E4M3 bytes in the low half
+{
+    u0 = fminf(fmaxf(u0, -448.0f), 448.0f);
+    u1 = fminf(fmaxf(u1, -448.0f), 448.0f);
+    return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(u0, u1, 0, false) & 0xFFFFu;
+}
+__device__ __forceinline__ float fp8_value(uint32_t byte) { return __builtin_amdgcn_cvt_f32_fp8((int)byte, 0); }
+__device__ __forceinline__ void fp8_scales(float amax, float* s, float* inv)
+{
+    if (amax == 0.0f) {
+        *s = 1.0f;
+        *inv = 1.0f;
+    } else {
+        *s = amax / 448.0f;
+        *inv = 448.0f / amax;
+    }
+}
+__device__ __forceinline__ float wmax64(float v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// pack
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void mx_fill_kernel(uint8_t* p, size_t n, uint8_t v)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+__global__ __launch_bounds__(256) void mx_pack_r_kernel(const float* R, int K, int r, uint8_t* r8, float* sr)
+{
+    __shared__ float red[4];
+    const int j = blockIdx.x, tid = threadIdx.x;
+    float a = 0.f;
+    for (int k = tid; k < K; k += 256) a = fmaxf(a, fabsf(R[(size_t)j * K + k]));
+    a = wmax64(a);
+    if ((tid & 63) == 0) red[tid >> 6] = a;
+    __syncthreads();
+    a = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float s, inv;
+    fp8_scales(a, &s, &inv);
+    if (tid == 0) sr[j] = s;
+    for (int k = tid; k < K; k += 256) r8[mx_rq_offset(j, k, r)] = (uint8_t)fp8_byte(__fmul_rn(R[(size_t)j * K + k], inv));
+}
+
+__global__ __launch_bounds__(256) void mx_pack_l_kernel(const float* L, int N, int r, int rp, uint8_t* l8, float* sl)
+{
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    float a = 0.f;
+    for (int j = 0; j < r; ++j) a = fmaxf(a, fabsf(L[(size_t)n * r + j]));
+    float s, inv;
+    fp8_scales(a, &s, &inv);
+    sl[n] = s;
+    for (int j = 0; j < rp; ++j)
+        l8[(size_t)n * rp + j] = (j < r) ? (uint8_t)fp8_byte(__fmul_rn(L[(size_t)n * r + j], inv)) : (uint8_t)0;
+}
+
+// one wavefront per (n, 64-chunk): lane = k % 64, two blocks of 32
+__global__ __launch_bounds__(256) void mx_pack_p_kernel(const float* W, const float* L, const float* R, int N, int K,
+                                                        int r, int rp, int from_q, const uint8_t* l8, const float* sl,
+                                                        const uint8_t* r8, const float* sr, uint8_t* pc, uint8_t* pe)
+{
+    const int lane = threadIdx.x & 63;
+    const int C64 = K >> 6, CQ = (C64 + 3) >> 2;
+    const size_t wid = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (wid >= (size_t)N * C64) return;
+    const int n = (int)(wid / C64), c = (int)(wid % C64);
+    const int k = c * 64 + lane;
+    double d = 0.0;
+    for (int j = 0; j < r; ++j) {
+        float lh, rh;
+        if (from_q) {
+            lh = __fmul_rn(fp8_value(l8[(size_t)n * rp + j]), sl[n]);
+            rh = __fmul_rn(fp8_value(r8[mx_rq_offset(j, k, r)]), sr[j]);
+        } else {
+            lh = L[(size_t)n * r + j];
+            rh = R[(size_t)j * K + k];
+        }
+        d = fma((double)lh, (double)rh, d);
+    }
+    const float P = (float)((double)W[(size_t)n * K + k] - d);
+    float a = fabsf(P);
+#pragma unroll
+    for (int o = 16; o >= 1; o >>= 1) a = fmaxf(a, __shfl_xor(a, o, 64));  // amax of the 32-block (half wave)
+    const uint32_t E = e8m0_of(a);
+    uint32_t code = 0;
+    if (a != 0.0f) code = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, P, 0.0f, e8m0_value(E), 0) & 0xFu;
+    uint32_t w = code << (4 * (lane & 7));
+    w |= __shfl_xor(w, 1, 64);
+    w |= __shfl_xor(w, 2, 64);
+    w |= __shfl_xor(w, 4, 64);
+    if ((lane & 7) == 0) *(uint32_t*)(pc + mx_code_offset(n, k, C64)) = w;
+    if ((lane & 31) == 0) pe[mx_scale_offset(n, c, lane >> 5, CQ)] = (uint8_t)E;
+}
+
+hipError_t launch_pack_mx(const Dims& d, int from_q, const float* W, const float* L, const float* R, uint8_t* packed,
+                          hipStream_t s)
+{
+    const PackedLayout pl = packed_layout(d);
+    uint8_t* l8 = packed + pl.off_lq;
+    float* sl = (float*)(packed + pl.off_sl);
+    uint8_t* r8 = packed + pl.off_rq;
+    float* sr = (float*)(packed + pl.off_sr);
+    const int N = (int)d.N, K = (int)d.K;
+    const size_t pe_bytes = (size_t)(N / 32) * ((d.C64 + 3) / 4) * 256;
+    hipLaunchKernelGGL(mx_fill_kernel, dim3((unsigned)((pe_bytes + 255) / 256)), dim3(256), 0, s, packed + pl.off_sw,
+                       pe_bytes, (uint8_t)127);
+    if (d.r > 0) hipLaunchKernelGGL(mx_pack_r_kernel, dim3(d.r), dim3(256), 0, s, R, K, d.r, r8, sr);
+    hipLaunchKernelGGL(mx_pack_l_kernel, dim3((N + 255) / 256), dim3(256), 0, s, d.r > 0 ? L : (const float*)nullptr, N,
+                       d.r, d.rp, l8, sl);
+    const size_t waves = (size_t)N * d.C64;
+    hipLaunchKernelGGL(mx_pack_p_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, W, L, R, N, K, d.r, d.rp,
+                       from_q, l8, sl, r8, sr, packed + pl.off_pq, packed + pl.off_sw);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// plain views
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void mx_unpack_w_kernel(const uint8_t* packed, PackedLayout pl, int N, int K, int r,
+                                                          int rp, lq_weights_view out)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int C64 = K >> 6, CQ = (C64 + 3) >> 2, B = K >> 5;
+    if (idx < (size_t)N * K && out.pq) {
+        const int n = (int)(idx / K), k = (int)(idx % K);
+        const uint32_t w = *(const uint32_t*)(packed + pl.off_pq + mx_code_offset(n, k, C64));
+        out.pq[idx] = (int8_t)((w >> (4 * (k & 7))) & 0xFu);
+    }
+    if (idx < (size_t)N * B && out.pe) {
+        const int n = (int)(idx / B), b = (int)(idx % B);
+        out.pe[idx] = packed[pl.off_sw + mx_scale_offset(n, b >> 1, b & 1, CQ)];
+    }
+    if (idx < (size_t)N * r && out.lq) {
+        const int n = (int)(idx / r), j = (int)(idx % r);
+        out.lq[idx] = (int8_t)packed[pl.off_lq + (size_t)n * rp + j];
+    }
+    if (idx < (size_t)N && out.sl) out.sl[idx] = ((const float*)(packed + pl.off_sl))[idx];
+    if (idx < (size_t)r * K && out.rq) {
+        const int j = (int)(idx / K), k = (int)(idx % K);
+        out.rq[idx] = (int8_t)packed[pl.off_rq + mx_rq_offset(j, k, r)];
+    }
+    if (idx < (size_t)r && out.sr) out.sr[idx] = ((const float*)(packed + pl.off_sr))[idx];
+}
+
+hipError_t launch_unpack_weights_mx(const Dims& d, const uint8_t* packed, const lq_weights_view* out, hipStream_t s)
+{
+    const PackedLayout pl = packed_layout(d);
+    const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * d.K;
+    hipLaunchKernelGGL(mx_unpack_w_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, packed, pl, (int)d.N,
+                       (int)d.K, d.r, d.rp, *out);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void mx_unpack_a_kernel(const uint8_t* act, ActLayout al, int M, int K, int r, int rp,
+                                                          lq_act_view out)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int C64 = K >> 6, CQ = (C64 + 3) >> 2, B = K >> 5;
+    if (idx < (size_t)M * K && out.xq) {
+        const int m = (int)(idx / K), k = (int)(idx % K);
+        const uint32_t w = *(const uint32_t*)(act + al.off_xq + mx_code_offset(m, k, C64));
+        out.xq[idx] = (int8_t)((w >> (4 * (k & 7))) & 0xFu);
+    }
+    if (idx < (size_t)M * B && out.xe) {
+        const int m = (int)(idx / B), b = (int)(idx % B);
+        out.xe[idx] = act[al.off_sx + mx_scale_offset(m, b >> 1, b & 1, CQ)];
+    }
+    if (idx < (size_t)M && out.st) out.st[idx] = ((const float*)(act + al.off_st))[idx];
+    if (idx < (size_t)M * r && out.tq) {
+        const int m = (int)(idx / r), j = (int)(idx % r);
+        out.tq[idx] = (int8_t)act[al.off_tq + (size_t)m * rp + j];
+    }
+}
+
+hipError_t launch_unpack_act_mx(const Dims& d, const uint8_t* act, int64_t M, const lq_act_view* out, hipStream_t s)
+{
+    const ActLayout al = act_layout(d, M);
+    const size_t n = (size_t)M * (d.K > d.r ? d.K : d.r);
+    hipLaunchKernelGGL(mx_unpack_a_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, act, al, (int)M,
+                       (int)d.K, d.r, d.rp, *out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// activation kernel: same decomposition as the INT one (16 token rows per workgroup, lane =
+// (row l%16, 16-value quarter l/16 of each 64-chunk), chunks dealt round-robin to 4 wavefronts)
+// ---------------------------------------------------------------------------------------------
+struct MxActParams {
+    const void* X;
+    int64_t ldx;
+    int M, K, C64, CQ, r, rp;
+    const uint8_t* r8;
+    const float* sr;
+    uint8_t* xc;
+    uint8_t* xe;
+    uint8_t* tq8;
+    float* st;
+    int8_t* dbg_xb;
+    float* dbg_sxb;
+    float* dbg_T;
+};
+
+template <bool BF16>
+struct MxChunk;
+template <>
+struct MxChunk<true> {
+    uint32_t w[8];
+    __device__ __forceinline__ void load(const void* X, size_t elem, bool ok)
+    {
+        v4i a = {0, 0, 0, 0}, b = {0, 0, 0, 0};
+        if (ok) {
+            const v4i* p = (const v4i*)((const uint16_t*)X + elem);
+            a = p[0];
+            b = p[1];
+        }
+        w[0] = a[0]; w[1] = a[1]; w[2] = a[2]; w[3] = a[3];
+        w[4] = b[0]; w[5] = b[1]; w[6] = b[2]; w[7] = b[3];
+    }
+    __device__ __forceinline__ float get(int i) const
+    {
+        return __uint_as_float((i & 1) ? (w[i >> 1] & 0xFFFF0000u) : (w[i >> 1] << 16));
+    }
+};
+template <>
+struct MxChunk<false> {
+    float v[16];
+    __device__ __forceinline__ void load(const void* X, size_t elem, bool ok)
+    {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            v4i a = {0, 0, 0, 0};
+            if (ok) a = ((const v4i*)((const float*)X + elem))[q];
+            v[4 * q] = __int_as_float(a[0]);
+            v[4 * q + 1] = __int_as_float(a[1]);
+            v[4 * q + 2] = __int_as_float(a[2]);
+            v[4 * q + 3] = __int_as_float(a[3]);
+        }
+    }
+    __device__ __forceinline__ float get(int i) const { return v[i]; }
+};
+
+template <bool BF16, int MAXC, int NJB>
+__global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
+{
+    __shared__ float s_amax[4][16];
+    __shared__ float s_sxb[16];
+    __shared__ float s_acc[4][NJB > 0 ? NJB : 1][64][4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r16 = lane & 15, kq = lane >> 4;
+    const int row = blockIdx.x * 16 + r16;
+    const bool row_ok = row < p.M;
+    const int C64 = p.C64;
+
+    MxChunk<BF16> xc[MAXC];
+#pragma unroll
+    for (int ci = 0; ci < MAXC; ++ci) {
+        const int c = wave + 4 * ci;
+        xc[ci].load(p.X, (size_t)row * p.ldx + (size_t)c * 64 + kq * 16, row_ok && c < C64);
+    }
+
+    // amax of the lane's 16 values per chunk (reused for the block scale) and of the whole row
+    float a16[MAXC];
+    float a = 0.f;
+#pragma unroll
+    for (int ci = 0; ci < MAXC; ++ci) {
+        float m = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(xc[ci].get(i)));
+        a16[ci] = m;
+        a = fmaxf(a, m);
+    }
+    a = fmaxf(a, __shfl_xor(a, 16, 64));
+    a = fmaxf(a, __shfl_xor(a, 32, 64));
+    if (kq == 0) s_amax[wave][r16] = a;
+    __syncthreads();
+    a = fmaxf(fmaxf(s_amax[0][r16], s_amax[1][r16]), fmaxf(s_amax[2][r16], s_amax[3][r16]));
+    float sb, invb;
+    fp8_scales(a, &sb, &invb);
+    if (wave == 0 && kq == 0) {
+        s_sxb[r16] = sb;
+        if (p.dbg_sxb && row_ok) p.dbg_sxb[row] = sb;
+        if (NJB == 0) p.st[row] = 1.0f;
+    }
+
+    v4f acc[NJB > 0 ? NJB : 1];
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb) acc[jb] = v4f{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+    for (int ci = 0; ci < MAXC; ++ci) {
+        const int c = wave + 4 * ci;
+        if (c < C64) {  // wave-uniform
+            // MXFP4: block of 32 = this lane's 16 values and its neighbour's (kq ^ 1)
+            const float ab = fmaxf(a16[ci], __shfl_xor(a16[ci], 16, 64));
+            const uint32_t E = e8m0_of(ab);
+            const float sc = e8m0_value(E);
+            uint32_t pk[2] = {0u, 0u};
+            uint32_t x8[4];
+#define LQ_CVT4(J) pk[(J) >> 2] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(pk[(J) >> 2], xc[ci].get(2 * (J)), xc[ci].get(2 * (J) + 1), sc, (J) & 3)
+            if (ab != 0.0f) {
+                LQ_CVT4(0); LQ_CVT4(1); LQ_CVT4(2); LQ_CVT4(3); LQ_CVT4(4); LQ_CVT4(5); LQ_CVT4(6); LQ_CVT4(7);
+            }
+#undef LQ_CVT4
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const float x0 = xc[ci].get(i), x1 = xc[ci].get(i + 1);
+                const uint32_t h = fp8_pair(__fmul_rn(x0, invb), __fmul_rn(x1, invb));
+                if ((i & 2) == 0)
+                    x8[i >> 2] = h;
+                else
+                    x8[i >> 2] |= h << 16;
+            }
+            uint8_t* dst = p.xc + ((size_t)((size_t)(row >> 5) * C64 + c) * 64 + (row & 31) + 32 * (kq >> 1)) * 16 + (kq & 1) * 8;
+            *(uint2*)dst = make_uint2(pk[0], pk[1]);
+            if ((kq & 1) == 0) p.xe[mx_scale_offset(row, c, kq >> 1, p.CQ)] = (uint8_t)E;
+            if (p.dbg_xb && row_ok)
+                *(v4i*)(p.dbg_xb + (size_t)row * p.K + c * 64 + kq * 16) = v4i{(int)x8[0], (int)x8[1], (int)x8[2], (int)x8[3]};
+            if (NJB > 0) {
+                const long alo = (long)(((unsigned long)x8[1] << 32) | x8[0]);
+                const long ahi = (long)(((unsigned long)x8[3] << 32) | x8[2]);
+#pragma unroll
+                for (int jb = 0; jb < NJB; ++jb) {
+                    const v4i bv = *(const v4i*)(p.r8 + ((size_t)((size_t)c * NJB + jb) * 64 + lane) * 16);
+                    const long blo = (long)(((unsigned long)(uint32_t)bv[1] << 32) | (uint32_t)bv[0]);
+                    const long bhi = (long)(((unsigned long)(uint32_t)bv[3] << 32) | (uint32_t)bv[2]);
+                    acc[jb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(alo, blo, acc[jb], 0, 0, 0);
+                    acc[jb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(ahi, bhi, acc[jb], 0, 0, 0);
+                }
+            }
+        }
+    }
+    if (NJB == 0) return;
+
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb) *(v4f*)&s_acc[wave][jb][lane][0] = acc[jb];
+    __syncthreads();
+    if (wave != 0) return;
+
+    float T[NJB > 0 ? NJB : 1][4];
+    float tmax[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb) {
+        v4f s = *(const v4f*)&s_acc[0][jb][lane][0];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const v4f o = *(const v4f*)&s_acc[w][jb][lane][0];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s[i] = __fadd_rn(s[i], o[i]);
+        }
+        const float srj = p.sr[jb * 16 + r16];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int tok = 4 * kq + i;
+            const float tv = __fmul_rn(__fmul_rn(s[i], s_sxb[tok]), srj);
+            T[jb][i] = tv;
+            tmax[i] = fmaxf(tmax[i], fabsf(tv));
+            const int grow = blockIdx.x * 16 + tok;
+            if (grow < p.M && p.dbg_T) p.dbg_T[(size_t)grow * p.r + jb * 16 + r16] = tv;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int o = 8; o >= 1; o >>= 1) tmax[i] = fmaxf(tmax[i], __shfl_xor(tmax[i], o, 64));
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int grow = blockIdx.x * 16 + 4 * kq + i;
+        float stv, invt;
+        fp8_scales(tmax[i], &stv, &invt);
+        if (r16 == 0) p.st[grow] = stv;
+#pragma unroll
+        for (int jb = 0; jb < NJB; ++jb) p.tq8[(size_t)grow * p.rp + jb * 16 + r16] = (uint8_t)fp8_byte(__fmul_rn(T[jb][i], invt));
+        for (int j = p.r + r16; j < p.rp; j += 16) p.tq8[(size_t)grow * p.rp + j] = 0;
+    }
+}
+
+template <bool BF16, int MAXC, int NJB>
+static hipError_t mx_act_launch(const MxActParams& p, int64_t Mp, hipStream_t s)
+{
+    hipLaunchKernelGGL((mx_act_kernel<BF16, MAXC, NJB>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+template <bool BF16, int MAXC>
+static hipError_t mx_act_rank(const MxActParams& p, int64_t Mp, hipStream_t s)
+{
+    switch (p.r) {
+        case 0: return mx_act_launch<BF16, MAXC, 0>(p, Mp, s);
+        case 16: return mx_act_launch<BF16, MAXC, 1>(p, Mp, s);
+        case 32: return mx_act_launch<BF16, MAXC, 2>(p, Mp, s);
+        case 64: return mx_act_launch<BF16, MAXC, 4>(p, Mp, s);
+        default: return mx_act_launch<BF16, MAXC, 8>(p, Mp, s);
+    }
+}
+
+hipError_t launch_quantize_act_mx(const Dims& d, int x_dtype, const uint8_t* packed, const void* X, int64_t M,
+                                  int64_t ldx, uint8_t* act, const lq_act_debug* dbg, hipStream_t s)
+{
+    const PackedLayout pl = packed_layout(d);
+    const ActLayout al = act_layout(d, M);
+    MxActParams p;
+    p.X = X;
+    p.ldx = ldx;
+    p.M = (int)M;
+    p.K = (int)d.K;
+    p.C64 = d.C64;
+    p.CQ = (d.C64 + 3) / 4;
+    p.r = d.r;
+    p.rp = d.rp;
+    p.r8 = packed + pl.off_rq;
+    p.sr = (const float*)(packed + pl.off_sr);
+    p.xc = act + al.off_xq;
+    p.xe = act + al.off_sx;
+    p.tq8 = act + al.off_tq;
+    p.st = (float*)(act + al.off_st);
+    p.dbg_xb = dbg ? dbg->xb : nullptr;
+    p.dbg_sxb = dbg ? dbg->sxb : nullptr;
+    p.dbg_T = dbg ? dbg->T : nullptr;
+    // scale bytes of the padding chunks (the last quad may be partial) must be valid E8M0 values
+    const size_t xe_bytes = (size_t)(al.Mp / 32) * p.CQ * 256;
+    if (d.C64 & 3)
+        hipLaunchKernelGGL(mx_fill_kernel, dim3((unsigned)((xe_bytes + 255) / 256)), dim3(256), 0, s, p.xe, xe_bytes,
+                           (uint8_t)127);
+    const int maxc = (d.C64 + 3) / 4;
+    if (x_dtype == LQ_BF16) {
+        if (maxc <= 5) return mx_act_rank<true, 5>(p, al.Mp, s);
+        if (maxc <= 9) return mx_act_rank<true, 9>(p, al.Mp, s);
+        return mx_act_rank<true, 18>(p, al.Mp, s);
+    }
+    if (maxc <= 5) return mx_act_rank<false, 5>(p, al.Mp, s);
+    return mx_act_rank<false, 9>(p, al.Mp, s);
+}
+
+// ---------------------------------------------------------------------------------------------
+// forward: 1 x 4 wavefronts per workgroup, 128 x 64 outputs per wavefront, K staged 128 at a time
+// ---------------------------------------------------------------------------------------------
+struct MxFwdParams {
+    const uint8_t* xc;
+    const uint8_t* xe;
+    const uint8_t* tq8;
+    const float* st;
+    const uint8_t* pc;
+    const uint8_t* pe;
+    const uint8_t* l8;
+    const float* sl;
+    uint16_t* Y;
+    int64_t ldy;
+    int M, N, C64, CQ, S, rp, nrb;
+    int tilesM, tilesN;
+    float* dbg_y32;
+};
+
+template <bool DBG>
+__global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
+{
+    constexpr int WN = 4, RBT = 4;
+    constexpr int EPI_ROW = 144, EPI_WAVE = 32 * EPI_ROW;
+    constexpr int LDS_MAIN = 2 * 2 * RBT * 1024;  // [buffer][chunk in stage][row block][lane][16 B]
+    constexpr int LDS_BYTES = LDS_MAIN > 4 * EPI_WAVE ? LDS_MAIN : 4 * EPI_WAVE;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, l32 = lane & 31;
+
+    const int tiles = p.tilesM * p.tilesN;
+    const int per = tiles >> 3, rem = tiles & 7;
+    const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
+    const int tile = xcd * per + (xcd < rem ? xcd : rem) + loc;
+    const int tile_m = tile / p.tilesN, tile_n = tile - tile_m * p.tilesN;
+    const int rb0 = tile_m * RBT;
+    const int cb0 = tile_n * (WN * 2) + wave * 2;
+    const bool active = (cb0 * 32 < p.N) && (rb0 < p.nrb);
+    const int C64 = p.C64, CQ = p.CQ, S = p.S;
+
+    const uint32_t lane16 = (uint32_t)lane * 16u, lane4 = (uint32_t)lane * 4u;
+    int rbs = rb0 + wave;  // row block staged by this wavefront
+    rbs = rbs < p.nrb ? rbs : p.nrb - 1;
+    const uint8_t* xc_base = p.xc + (size_t)rbs * C64 * 1024;
+    const int cbw = (cb0 * 32 < p.N) ? cb0 : 0;
+    const uint8_t* pc_base[2] = {p.pc + (size_t)cbw * C64 * 1024, p.pc + (size_t)(cbw + 1) * C64 * 1024};
+    const uint8_t* pe_base[2] = {p.pe + (size_t)cbw * CQ * 256, p.pe + (size_t)(cbw + 1) * CQ * 256};
+    const uint8_t* xe_base[4];
+#pragma unroll
+    for (int rbi = 0; rbi < 4; ++rbi) {
+        int rb = rb0 + rbi;
+        rb = rb < p.nrb ? rb : p.nrb - 1;
+        xe_base[rbi] = p.xe + (size_t)rb * CQ * 256;
+    }
+
+    struct AStage { v4i v[2]; };
+    struct BStage { v4i v[2][2]; };
+    auto load_a = [&](AStage& a, int stage) {
+        const int st = stage < S ? stage : S - 1;
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc) a.v[cc] = *(const v4i*)(xc_base + (size_t)(st * 2 + cc) * 1024 + lane16);
+    };
+    auto store_a = [&](const AStage& a, int buf) {
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc) *(v4i*)(lds + (size_t)(((buf * 2 + cc) * RBT + wave) * 1024) + lane16) = a.v[cc];
+    };
+    auto load_b = [&](BStage& b, int stage) {
+        const int st = stage < S ? stage : S - 1;
+#pragma unroll
+        for (int cbi = 0; cbi < 2; ++cbi)
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) b.v[cc][cbi] = *(const v4i*)(pc_base[cbi] + (size_t)(st * 2 + cc) * 1024 + lane16);
+    };
+    // scale dwords of one quad of chunks (= two stages)
+    struct Scales { int a[4]; int b[2]; };
+    auto load_s = [&](Scales& sc, int quad) {
+        const int q = quad < CQ ? quad : CQ - 1;
+#pragma unroll
+        for (int rbi = 0; rbi < 4; ++rbi) sc.a[rbi] = *(const int*)(xe_base[rbi] + (size_t)q * 256 + lane4);
+#pragma unroll
+        for (int cbi = 0; cbi < 2; ++cbi) sc.b[cbi] = *(const int*)(pe_base[cbi] + (size_t)q * 256 + lane4);
+    };
+
+    v16f t[4][2];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) t[a][b][i] = 0.f;
+
+    // One stage = 128 values of K = two 64-chunks.  PAR (0|1) = parity of the stage inside its
+    // quad of chunks: the op_sel immediates are 2*PAR and 2*PAR+1.
+    auto do_stage = [&](auto par, int s, AStage& a, BStage& b, const Scales& sc) {
+        constexpr int PAR = decltype(par)::value;
+        const int buf = s & 1;
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc) {
+#pragma unroll
+            for (int rbi = 0; rbi < 4; ++rbi) {
+                const v4i av = *(const v4i*)(lds + (size_t)(((buf * 2 + cc) * RBT + rbi) * 1024) + lane16);
+                const v8i a8 = {av[0], av[1], av[2], av[3], 0, 0, 0, 0};
+#pragma unroll
+                for (int cbi = 0; cbi < 2; ++cbi) {
+                    const v4i bq = b.v[cc][cbi];
+                    const v8i b8 = {bq[0], bq[1], bq[2], bq[3], 0, 0, 0, 0};
+                    if (cc == 0)
+                        t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, t[rbi][cbi], 4, 4, 2 * PAR,
+                                                                                     sc.a[rbi], 2 * PAR, sc.b[cbi]);
+                    else
+                        t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, t[rbi][cbi], 4, 4, 2 * PAR + 1,
+                                                                                     sc.a[rbi], 2 * PAR + 1, sc.b[cbi]);
+                }
+            }
+            if (cc == 0) {  // stage s+1 goes to the other LDS buffer while this one is being consumed
+                store_a(a, buf ^ 1);
+                load_a(a, s + 3);
+            }
+        }
+        load_b(b, s + 2);
+        __syncthreads();
+    };
+
+    AStage a0, a1;
+    BStage b0, b1;
+    Scales s0, s1;
+    load_a(a0, 0);
+    load_b(b0, 0);
+    load_s(s0, 0);
+    store_a(a0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_a(a0, 1);
+    load_b(b1, 1);
+    load_a(a1, 2);
+    load_s(s1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+
+    // stages come in groups of four (two quads of chunks): quad q uses scale set q & 1
+    int s = 0;
+    for (; s + 3 < S; s += 4) {
+        do_stage(std::integral_constant<int, 0>{}, s, a0, b0, s0);
+        do_stage(std::integral_constant<int, 1>{}, s + 1, a1, b1, s0);
+        load_s(s0, (s >> 1) + 2);
+        do_stage(std::integral_constant<int, 0>{}, s + 2, a0, b0, s1);
+        do_stage(std::integral_constant<int, 1>{}, s + 3, a1, b1, s1);
+        load_s(s1, (s >> 1) + 3);
+    }
+    if (s < S) {
+        do_stage(std::integral_constant<int, 0>{}, s, a0, b0, s0);
+        if (s + 1 < S) do_stage(std::integral_constant<int, 1>{}, s + 1, a1, b1, s0);
+        if (s + 2 < S) do_stage(std::integral_constant<int, 0>{}, s + 2, a0, b0, s1);
+    }
+
+    if (!active) return;
+
+    // ---- epilogue: FP8 rank-r expansion, scales, sum, bf16, transposed full-line stores -------
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    uint8_t* stage = lds + wave * EPI_WAVE;
+    const int nk = p.rp >> 6;
+    float slv[2];
+    v8i lf[2][2];
+#pragma unroll
+    for (int cbi = 0; cbi < 2; ++cbi) {
+        const int col = (cb0 + cbi) * 32 + l32;
+        slv[cbi] = p.sl[col];
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            v8i v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (kk < nk) v = *(const v8i*)(p.l8 + (size_t)col * p.rp + kk * 64 + half * 32);
+            lf[cbi][kk] = v;
+        }
+    }
+    const int wr_off = (4 * half) * EPI_ROW + l32 * 2;
+    const int rd_row = lane >> 3, rd_seg = lane & 7;
+#pragma unroll
+    for (int rbi = 0; rbi < 4; ++rbi) {
+        const int rbase = (rb0 + rbi) * 32;
+        if (rbase >= p.M) break;
+        v8i tf[2];
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            v8i v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (kk < nk) v = *(const v8i*)(p.tq8 + (size_t)(rbase + l32) * p.rp + kk * 64 + half * 32);
+            tf[kk] = v;
+        }
+        v4f stv[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) stv[q] = *(const v4f*)(p.st + rbase + 8 * q + 4 * half);
+#pragma unroll
+        for (int cbi = 0; cbi < 2; ++cbi) {
+            v16f a2 = {0};
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk)
+                if (kk < nk) a2 = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(tf[kk], lf[cbi][kk], a2, 0, 0, 0, 0, 0, 0);
+            float y[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float ybr = __fmul_rn(__fmul_rn(a2[i], stv[i >> 2][i & 3]), slv[cbi]);
+                y[i] = __fadd_rn(t[rbi][cbi][i], ybr);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const bf16x2 h = __builtin_convertvector(f32x2{y[i], y[i + 1]}, bf16x2);
+                const uint32_t w = __builtin_bit_cast(uint32_t, h);
+                const int o = wr_off + (8 * (i >> 2) + (i & 3)) * EPI_ROW + cbi * 64;
+                *(uint16_t*)(stage + o) = (uint16_t)(w & 0xFFFFu);
+                *(uint16_t*)(stage + o + EPI_ROW) = (uint16_t)(w >> 16);
+            }
+            if (DBG) {
+                const int col = (cb0 + cbi) * 32 + l32;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int row = rbase + 8 * (i >> 2) + 4 * half + (i & 3);
+                    if (row < p.M && p.dbg_y32) p.dbg_y32[(size_t)row * p.N + col] = y[i];
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int rl = q * 8 + rd_row;
+            const v4i v = *(const v4i*)(stage + rl * EPI_ROW + rd_seg * 16);
+            const int row = rbase + rl;
+            if (row < p.M) *(v4i*)(p.Y + (size_t)row * p.ldy + cb0 * 32 + rd_seg * 8) = v;
+        }
+    }
+}
+
+hipError_t launch_fwd_mx(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M, uint16_t* Y, int64_t ldy,
+                         const lq_fwd_debug* dbg, hipStream_t s)
+{
+    const PackedLayout pl = packed_layout(d);
+    const ActLayout al = act_layout(d, M);
+    MxFwdParams p;
+    p.xc = act + al.off_xq;
+    p.xe = act + al.off_sx;
+    p.tq8 = act + al.off_tq;
+    p.st = (const float*)(act + al.off_st);
+    p.pc = packed + pl.off_pq;
+    p.pe = packed + pl.off_sw;
+    p.l8 = packed + pl.off_lq;
+    p.sl = (const float*)(packed + pl.off_sl);
+    p.Y = Y;
+    p.ldy = ldy;
+    p.M = (int)M;
+    p.N = (int)d.N;
+    p.C64 = d.C64;
+    p.CQ = (d.C64 + 3) / 4;
+    p.S = d.C64 / 2;
+    p.rp = d.rp;
+    p.nrb = (int)(al.Mp / 32);
+    p.tilesM = (p.nrb + 3) / 4;
+    p.tilesN = (p.N + 255) / 256;
+    p.dbg_y32 = dbg ? dbg->y32 : nullptr;
+    dim3 grid((unsigned)(p.tilesM * p.tilesN)), block(256);
+    if (p.dbg_y32)
+        hipLaunchKernelGGL(mx_fwd_kernel<true>, grid, block, 0, s, p);
+    else
+        hipLaunchKernelGGL(mx_fwd_kernel<false>, grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace lq

@@ -39,6 +39,8 @@ def run_gpu(layer, X, W, L, R, debug=True, debug_acc=True):
     Xd = to_dev_x(X, layer.x_dtype)
     packed = lq.lq_pack_weights(cfg, Wd, Ld, Rd)
     M = X.shape[0]
+    if debug and layer.family == "mx":
+        debug_acc = False
     if debug:
         act, adbg = lq.lq_quantize_act(cfg, packed, Xd, debug=True)
         Y, fdbg = lq.lq_linear_lowrank_fwd(cfg, packed, act, M, debug=True, debug_acc=debug_acc)

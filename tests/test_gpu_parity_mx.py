@@ -1,0 +1,148 @@
+"""GPU parity, MX family (MXFP4 main on the scaled MFMA, FP8 branch) against the CPU oracle.
+
+Bar: every code and scale computed from source data (X, P, L, R) bit-exact (+0 and -0 codes are
+the same value); quantities that pass through fp32 accumulation in the matrix core (T, y) within a
+bound derived from the arithmetic; re-quantised intermediate codes may differ from the oracle's only
+where T sits on a rounding boundary (counted, each difference at most one code step).
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_18117_amd import workloads as wl
+from tests.gpu_util import bf16_to_bits, n, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+E2M1 = np.array([0, .5, 1, 1.5, 2, 3, 4, 6, -0., -.5, -1, -1.5, -2, -3, -4, -6], np.float32)
+
+
+def _e4m3_table(oracle):
+    return oracle.e4m3_decode(np.arange(256, dtype=np.uint8))
+
+
+def _run_oracle(oracle, layer, X, W, L, R):
+    pk = oracle.pack_mx(W, L if layer.r else None, R if layer.r else None)
+    act = oracle.quantize_act_mx(X, pk)
+    return pk, act
+
+
+def _compare(oracle, layer, X, W, L, R, rows=None):
+    """rows: None = compare everything, else the sampled token rows (oracle sees only those)."""
+    g = run_gpu(layer, X, W, L, R, debug=True, debug_acc=False)
+    Xo = X if rows is None else X[rows]
+    sel = slice(None) if rows is None else rows
+    pk, act = _run_oracle(oracle, layer, Xo, W, L, R)
+    f8 = _e4m3_table(oracle)
+    r = layer.r
+    # ---- offline packing: exact
+    assert np.array_equal(E2M1[n(g.wv.pq).view(np.uint8)], E2M1[pk.pc]), "pq"
+    assert np.array_equal(n(g.wv.pe), pk.pe), "pe"
+    assert np.array_equal(n(g.wv.sl), pk.sl), "sl"
+    if r:
+        assert np.array_equal(f8[n(g.wv.lq).view(np.uint8)], f8[pk.l8]), "l8"
+        assert np.array_equal(f8[n(g.wv.rq).view(np.uint8)], f8[pk.r8]), "r8"
+        assert np.array_equal(n(g.wv.sr), pk.sr), "sr"
+    # ---- activation step: codes and scales from X exact
+    assert np.array_equal(E2M1[n(g.av.xq).view(np.uint8)[sel]], E2M1[act.xc]), "xc"
+    assert np.array_equal(n(g.av.xe)[sel], act.xe), "xe"
+    tq_gpu = n(g.av.tq).view(np.uint8)[sel]
+    st_gpu = n(g.av.st)[sel]
+    if r:
+        assert np.array_equal(f8[n(g.adbg.xb).view(np.uint8)[sel]], f8[act.xb8]), "xb8"
+        assert np.array_equal(n(g.adbg.sxb)[sel], act.sxb), "sxb"
+        # T: K fp32 accumulations of products bounded by 448^2 sxb sr
+        T_gpu = n(g.adbg.T)[sel]
+        tb = 2.0 ** -15 * (np.abs(f8[act.xb8].astype(np.float64)) @ np.abs(f8[pk.r8].astype(np.float64)).T) \
+            * act.sxb[:, None] * pk.sr[None, :] + 1e-30
+        assert np.all(np.abs(T_gpu - act.T) <= tb), "T"
+        assert np.allclose(st_gpu, act.st, rtol=2e-4, atol=0), "st"
+        diff = tq_gpu != act.tq8
+        diff &= ~(((tq_gpu & 0x7F) == 0) & ((act.tq8 & 0x7F) == 0))
+        assert diff.mean() <= 1e-2, f"tq8 mismatch rate {diff.mean()}"
+        # every GPU code is a correct E4M3 rounding of a value within the accumulation bound of the
+        # oracle's T: |deq - T| <= half the local code spacing (in units of st) + bound
+        u = np.abs(act.T.astype(np.float64)) / st_gpu[:, None]
+        step = np.exp2(np.maximum(np.floor(np.log2(np.maximum(u, 2.0 ** -6))) - 3, -9))
+        deq = f8[tq_gpu].astype(np.float64) * st_gpu[:, None]
+        slack = st_gpu[:, None] * (0.5 * step * (1 + 1e-3) + 2e-4 * u) + tb
+        assert np.all(np.abs(deq - act.T) <= slack), "tq8 is not a rounding of T"
+    # ---- forward: the oracle is fed the GPU's re-quantised intermediate, so that what is compared
+    # is the forward arithmetic alone
+    act_g = dataclasses.replace(act, tq8=np.ascontiguousarray(tq_gpu), st=np.ascontiguousarray(st_gpu))
+    out = oracle.fwd_mx(pk, act_g)
+    y_gpu = n(g.fdbg.y32)[sel]
+    Xd = np.abs(E2M1[act.xc].astype(np.float64).reshape(Xo.shape[0], -1, 32)) * oracle.e8m0_decode(act.xe)[:, :, None]
+    Wd = np.abs(E2M1[pk.pc].astype(np.float64).reshape(layer.N, -1, 32)) * oracle.e8m0_decode(pk.pe)[:, :, None]
+    A = Xd.reshape(Xo.shape[0], -1) @ Wd.reshape(layer.N, -1).T          # sum of |terms| of the main product
+    bound = 2.0 ** -15 * (A + np.abs(out.ybr)) + 1e-30
+    assert np.all(np.abs(y_gpu - out.y32) <= bound), f"y32 max excess {np.max(np.abs(y_gpu - out.y32) / bound)}"
+    # bf16 output = nearest-even rounding of the kernel's own fp32 value ...
+    Yb = bf16_to_bits(g.Y)[sel]
+    want = ((y_gpu.view(np.uint32) + 0x7FFF + ((y_gpu.view(np.uint32) >> 16) & 1)) >> 16).astype(np.uint16)
+    assert np.array_equal(Yb, want), "Y is not bf16_rne(y32)"
+    # ... and against the oracle: the stated 2e-3 bound on everything that is not a rounding-boundary flip
+    Yf = oracle.bf16_bits_to_f32(Yb).astype(np.float64)
+    Yo = oracle.bf16_bits_to_f32(out.Y).astype(np.float64)
+    tau = 1e-3 * np.sqrt(np.mean(out.y32.astype(np.float64) ** 2)) + 1e-30
+    rel = np.abs(Yf - Yo) / np.maximum(np.abs(out.y32), tau)
+    flips = Yb != out.Y
+    assert flips.mean() <= 2e-3, f"bf16 flip rate {flips.mean()}"
+    assert np.all(rel[~flips] <= 2e-3)
+    assert np.all(rel[flips] <= 2.0 ** -7 * 1.01)      # a flip is exactly one bf16 ulp
+    g2 = run_gpu(layer, X, W, L, R, debug=False)
+    assert torch.equal(g2.Y, g.Y)
+    return g
+
+
+SMALL = [
+    # M (ragged), K (multiple of 128), N (partial 256-wide tile), r, x_dtype
+    (300, 256, 320, 32, "bf16"),
+    (77, 384, 64, 16, "f32"),
+    (130, 1152, 192, 64, "bf16"),
+    (64, 128, 64, 0, "bf16"),
+    (33, 640, 128, 128, "bf16"),
+    (1, 128, 64, 32, "f32"),
+]
+
+
+@pytest.mark.parametrize("M,K,N,r,xd", SMALL)
+def test_small_shapes(oracle, M, K, N, r, xd):
+    layer = wl.Layer("t", M, K, N, r, "mx", 32, 8, 8, xd, seed=M + K)
+    X, W, L, R = wl.make_inputs(layer)
+    _compare(oracle, layer, X, W, L, R)
+
+
+def test_degenerate_inputs(oracle):
+    layer = wl.Layer("t", 70, 256, 64, 16, "mx", 32, 8, 8, "bf16", seed=3)
+    X, W, L, R = wl.make_inputs(layer)
+    X[3] = 0.0
+    X[5, :] = 0.0
+    X[5, 7] = -2.0
+    X[9, 32:64] = 0.0     # an all-zero block inside a token
+    W[2] = 0.0
+    W[4, 64:96] = 0.0
+    L[4] = 0.0
+    R[1] = 0.0
+    _compare(oracle, layer, X, W, L, R)
+    _compare(oracle, layer, np.zeros_like(X), W, L, R)
+
+
+def test_wide_dynamic_range_blocks(oracle):
+    layer = wl.Layer("t", 64, 256, 64, 32, "mx", 32, 8, 8, "bf16", seed=5)
+    X, W, L, R = wl.make_inputs(layer)
+    rng = np.random.default_rng(7)
+    X *= wl.round_to_bf16(np.exp2(rng.integers(-20, 20, size=(64, 8)).repeat(32, axis=1)).astype(np.float32))
+    W *= np.exp2(rng.integers(-10, 10, size=(64, 8)).repeat(32, axis=1)).astype(np.float32)
+    _compare(oracle, layer, wl.round_to_bf16(X), W, L, R)
+
+
+@pytest.mark.parametrize("name", ["c5_qkv", "c5_attn_out", "c5_cross_kv", "c5_fc1", "c5_fc2"])
+def test_full_size_sampled_rows(oracle, name):
+    layer = wl.LAYERS[name]
+    X, W, L, R = wl.make_inputs(layer)
+    rng = np.random.default_rng(1)
+    rows = np.sort(np.concatenate([[0, layer.M - 1], rng.choice(layer.M, 14, replace=False)]))
+    _compare(oracle, layer, X, W, L, R, rows=rows)
