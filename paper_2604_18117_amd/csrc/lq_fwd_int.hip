@@ -11,11 +11,11 @@
 // accumulator exactly and the per-group dequantisation is ONE fp32 FMA per output (no
 // int->float conversion); the factor 2^18 is folded into the stored weight scales.
 //
-// Work decomposition: a workgroup of WM x WN wavefronts computes a (WM*128) x (WN*64) tile
-// of Y; each wavefront owns 128 x 64 (4 x 2 MFMA tiles of 32 x 32, 128 fp32 running sums per
-// lane).  Activation codes go global -> registers -> (nibble to byte) -> LDS once per
-// workgroup; weight codes are read by each wavefront straight from global memory in operand
-// order (they are shared by only WM wavefronts) and expanded in registers.
+// Work decomposition: a workgroup of 4 wavefronts computes a 128 x 256 tile of Y (64 x 256 for
+// the half tiles at the tail of the grid); each wavefront owns 128 x 64 (4 x 2 MFMA tiles of
+// 32 x 32, 128 fp32 running sums per lane).  Activation codes go global -> registers -> (nibble
+// to byte) -> LDS once per workgroup; weight codes are read by each wavefront straight from
+// global memory in operand order (no other wavefront needs them) and expanded in registers.
 #include "lq_internal.h"
 
 namespace lq {
@@ -38,7 +38,7 @@ struct FwdParams {
     uint16_t* Y;
     int64_t ldy;
     int M, N, G, C64, rp, nrb;
-    int tilesM, tilesN;
+    int tilesM, tilesN, n_full;
     int32_t* dbg_acc;
     int32_t* dbg_acc2;
     float* dbg_y32;
@@ -55,38 +55,34 @@ __device__ __forceinline__ v8i expand8(v4i p)
     return o;
 }
 
-template <int WM, int WN, int GC, bool DBG>
-__global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
+constexpr int WN = 4;                          // wavefronts per workgroup, side by side along N
+constexpr int NW = WN;
+constexpr int RBT = 4;                         // 32-row blocks staged per workgroup (LDS slots)
+constexpr int EPI_ROW = 144;                   // bytes per staged output row (128 + pad: no bank conflicts)
+constexpr int EPI_WAVE = 32 * EPI_ROW;         // one 32 x 64 bf16 block per wavefront
+template <int GC>
+constexpr int lds_bytes()
 {
-    constexpr int NW = WM * WN;
-    constexpr int RBT = WM * 4;  // 32-row blocks per workgroup tile
-    static_assert(RBT % NW == 0 || NW % RBT == 0, "staging split");
-    constexpr int SPW = (RBT + NW - 1) / NW;  // row blocks staged per wavefront
-    constexpr int STAGES = (GC == 1) ? 2 : 1; // register sets of the global-load pipeline
-
     // [buffer][chunk in group][row block][part][lane][16 B]
-    constexpr int EPI_ROW = 144;                 // bytes per staged output row (128 + pad: no bank conflicts)
-    constexpr int EPI_WAVE = 32 * EPI_ROW;        // one 32 x 64 bf16 block per wavefront
-    constexpr int LDS_MAIN = 2 * GC * RBT * 2048;
-    constexpr int LDS_BYTES = LDS_MAIN > NW * EPI_WAVE ? LDS_MAIN : NW * EPI_WAVE;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES];
+    return 2 * GC * RBT * 2048 > NW * EPI_WAVE ? 2 * GC * RBT * 2048 : NW * EPI_WAVE;
+}
+
+// One output tile of (NRB*32) x 256: rows rb0*32.., columns tile_n*256...  NRB = 4 (full tile) or
+// 2 (half tile, used for the tail of the grid).  NK = 32-deep chunks of the padded rank: 0|1|2|4.
+template <int GC, int NK, int NRB, bool DBG>
+__device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const int rb0, const int tile_n)
+{
+    constexpr int SPW = 1;                      // row blocks staged per wavefront
+    constexpr int STAGES = (GC == 1) ? 2 : 1;   // register sets of the global-load pipeline
+    constexpr int NT = NRB * 2;                 // 32 x 32 MFMA tiles per wavefront and step
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps address math scalar
-    const int wm = wave / WN, wn = wave % WN;
+    const int wn = wave;
     const int half = lane >> 5, l32 = lane & 31;
 
-    // XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs, so give each
-    // XCD one contiguous run of tiles (row-major over (m,n)): its L2 then sees few row tiles.
-    const int tiles = p.tilesM * p.tilesN;
-    const int per = tiles >> 3, rem = tiles & 7;
-    const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
-    const int tile = xcd * per + (xcd < rem ? xcd : rem) + loc;
-    const int tile_m = tile / p.tilesN, tile_n = tile - tile_m * p.tilesN;
-
-    const int rb0 = tile_m * RBT;
     const int cb0 = tile_n * (WN * 2) + wn * 2;
-    const bool active = (cb0 * 32 < p.N) && ((rb0 + wm * 4) < p.nrb);
+    const bool active = (cb0 * 32 < p.N) && (rb0 < p.nrb);
 
     const int C64 = p.C64, G = p.G;
 
@@ -96,7 +92,8 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
     // that the sets are addressed statically.  Steps and row blocks are clamped instead of
     // predicated: the loop body stays branch-free, and a clamped load only re-reads valid data
     // that never reaches a stored output.
-    static_assert(RBT % NW == 0, "every wavefront stages the same number of row blocks");
+    // Every wavefront stages one row block; with a half tile the upper two stage (clamped)
+    // blocks that are not read.
     const uint32_t lane16 = (uint32_t)lane * 16u;
     const uint8_t* xq_base[SPW];
 #pragma unroll
@@ -141,9 +138,9 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
         }
     };
 
-    v16f t[4][2];
+    v16f t[NRB][2];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < NRB; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -171,7 +168,7 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
         const int buf = s & 1;
         {
             auto lds_a = [&](int rbi, int cc) -> v8i {
-                const uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wm * 4 + rbi) * 2048) + lane16;
+                const uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + rbi) * 2048) + lane16;
                 const v4i lo = *(const v4i*)(base);
                 const v4i hi = *(const v4i*)(base + 1024);
                 return v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
@@ -192,13 +189,13 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
             // software pipeline over the 8 MFMA tiles: the matrix core works on tile j+1 while
             // the vector ALU folds tile j into the running sums
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+            for (int j = 0; j < NT; ++j) {
                 const int rbi = j >> 1, cbi = j & 1;
-                if (j + 1 < 8) {
+                if (j + 1 < NT) {
                     const int nrbi = (j + 1) >> 1, ncbi = (j + 1) & 1;
                     dd[(j + 1) & 1] = tile_mfma(af[nrbi & 1], ncbi);
                 }
-                if (cbi == 0 && rbi + 1 < 4) {  // operand of the next row block, one tile ahead
+                if (cbi == 0 && rbi + 1 < NRB) {  // operand of the next row block, one tile ahead
 #pragma unroll
                     for (int cc = 0; cc < GC; ++cc) af[(rbi + 1) & 1][cc] = lds_a(rbi + 1, cc);
                 }
@@ -206,7 +203,7 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
                     store_a(a, buf ^ 1);
                     load_a(a, s + 1 + STAGES);
                 }
-                if (j == 7) {  // the last MFMA of the step is in flight: bu is free
+                if (j == NT - 1) {  // the last MFMA of the step is in flight: bu is free
                     expand_b(b);
                     load_b(b, s + 1 + STAGES);
                 }
@@ -217,7 +214,7 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
                     if (p.dbg_acc && active) {
 #pragma unroll
                         for (int i = 0; i < 16; ++i) {
-                            const int row = (rb0 + wm * 4 + rbi) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+                            const int row = (rb0 + rbi) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
                             const int col = (cb0 + cbi) * 32 + l32;
                             if (row < p.M)
                                 p.dbg_acc[((size_t)row * p.N + col) * G + s] = (int)(dd[j & 1][i] * 262144.0f);
@@ -281,55 +278,68 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     typedef float f32x2 __attribute__((ext_vector_type(2)));
     uint8_t* stage = lds + wave * EPI_WAVE;
-    const int nk = p.rp >> 5;
+    constexpr int NKA = NK > 0 ? NK : 1;
     float slv[2];
-    v4i lqf[2][4];
+    v4i lqf[2][NKA];
 #pragma unroll
     for (int cbi = 0; cbi < 2; ++cbi) {
         const int col = (cb0 + cbi) * 32 + l32;
         slv[cbi] = p.sl[col];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            v4i v = {0, 0, 0, 0};
-            if (kk < nk) v = *(const v4i*)(p.lq + (size_t)col * p.rp + kk * 32 + half * 16);
-            lqf[cbi][kk] = v;
-        }
+        for (int kk = 0; kk < NK; ++kk)
+            lqf[cbi][kk] = *(const v4i*)(p.lq + (size_t)col * p.rp + kk * 32 + half * 16);
     }
     const int wr_off = (4 * half) * EPI_ROW + l32 * 2;        // this lane's column in the staged block
     const int rd_row = lane >> 3, rd_seg = lane & 7;          // read-back: 8 lanes per 128-byte row
+    // Per-row-block operands (intermediate codes, per-token scales).  Row blocks past the end of
+    // a partial tile are clamped (their results are never stored), so the loads of block rbi+1
+    // can be issued while block rbi is still being processed.
+    v4i tqf[NKA];
+    v4f sxv[4], stv[4];
+    auto load_tq = [&](int rbi) {
+        int rb = rb0 + rbi;
+        rb = rb < p.nrb ? rb : p.nrb - 1;
 #pragma unroll
-    for (int rbi = 0; rbi < 4; ++rbi) {
-        const int rbase = (rb0 + wm * 4 + rbi) * 32;
-        if (rbase >= p.M) break;
-        v4i tqf[4];
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            v4i v = {0, 0, 0, 0};
-            if (kk < nk) v = *(const v4i*)(p.tq + (size_t)(rbase + l32) * p.rp + kk * 32 + half * 16);
-            tqf[kk] = v;
-        }
-        // per-row scales: rows 8*q + 4*half + 0..3 are contiguous -> one 16-byte load each
-        v4f sxv[4], stv[4];
+        for (int kk = 0; kk < NK; ++kk)
+            tqf[kk] = *(const v4i*)(p.tq + (size_t)(rb * 32 + l32) * p.rp + kk * 32 + half * 16);
+    };
+    auto load_scales = [&](int rbi) {  // rows 8*q + 4*half + 0..3 are contiguous -> one 16-byte load each
+        int rb = rb0 + rbi;
+        rb = rb < p.nrb ? rb : p.nrb - 1;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            sxv[q] = *(const v4f*)(p.sx + rbase + 8 * q + 4 * half);
-            stv[q] = *(const v4f*)(p.st + rbase + 8 * q + 4 * half);
+            sxv[q] = *(const v4f*)(p.sx + rb * 32 + 8 * q + 4 * half);
+            stv[q] = *(const v4f*)(p.st + rb * 32 + 8 * q + 4 * half);
         }
+    };
+    load_tq(0);
+    load_scales(0);
+#pragma unroll
+    for (int rbi = 0; rbi < NRB; ++rbi) {
+        const int rbase = (rb0 + rbi) * 32;
+        v16i a2[2];
 #pragma unroll
         for (int cbi = 0; cbi < 2; ++cbi) {
-            v16i a2 = {0};
+            a2[cbi] = v16i{0};
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                if (kk < nk) a2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(tqf[kk], lqf[cbi][kk], a2, 0, 0, 0);
-            float y[16];
+            for (int kk = 0; kk < NK; ++kk)
+                a2[cbi] = __builtin_amdgcn_mfma_i32_32x32x32_i8(tqf[kk], lqf[cbi][kk], a2[cbi], 0, 0, 0);
+        }
+        if (rbi + 1 < NRB) load_tq(rbi + 1);  // the matrix core has read tqf: fetch the next block's codes
+        float y[2][16];
+#pragma unroll
+        for (int cbi = 0; cbi < 2; ++cbi)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const float ybr = __fmul_rn(__fmul_rn((float)a2[i], stv[i >> 2][i & 3]), slv[cbi]);
-                y[i] = __builtin_fmaf(sxv[i >> 2][i & 3], t[rbi][cbi][i], ybr);
+                const float ybr = __fmul_rn(__fmul_rn((float)a2[cbi][i], stv[i >> 2][i & 3]), slv[cbi]);
+                y[cbi][i] = __builtin_fmaf(sxv[i >> 2][i & 3], t[rbi][cbi][i], ybr);
             }
+        if (rbi + 1 < NRB) load_scales(rbi + 1);
+#pragma unroll
+        for (int cbi = 0; cbi < 2; ++cbi) {
 #pragma unroll
             for (int i = 0; i < 16; i += 2) {
-                const bf16x2 h = __builtin_convertvector(f32x2{y[i], y[i + 1]}, bf16x2);
+                const bf16x2 h = __builtin_convertvector(f32x2{y[cbi][i], y[cbi][i + 1]}, bf16x2);
                 const uint32_t w = __builtin_bit_cast(uint32_t, h);
                 const int o = wr_off + (8 * (i >> 2) + (i & 3)) * EPI_ROW + cbi * 64;
                 *(uint16_t*)(stage + o) = (uint16_t)(w & 0xFFFFu);
@@ -341,8 +351,8 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
                 for (int i = 0; i < 16; ++i) {
                     const int row = rbase + 8 * (i >> 2) + 4 * half + (i & 3);
                     if (row < p.M) {
-                        if (p.dbg_acc2) p.dbg_acc2[(size_t)row * p.N + col] = a2[i];
-                        if (p.dbg_y32) p.dbg_y32[(size_t)row * p.N + col] = y[i];
+                        if (p.dbg_acc2) p.dbg_acc2[(size_t)row * p.N + col] = a2[cbi][i];
+                        if (p.dbg_y32) p.dbg_y32[(size_t)row * p.N + col] = y[cbi][i];
                     }
                 }
             }
@@ -358,15 +368,80 @@ __global__ __launch_bounds__(WM* WN * 64, 2) void fwd_int_kernel(FwdParams p)
     }
 }
 
-template <int WM, int WN, int GC, bool DBG>
+// Grid: the first n_full workgroups compute full 128 x 256 tiles, in row-major tile order; the
+// remaining tiles (if they are few, see launch_cfg) are each split into two 64 x 256 half tiles,
+// which shortens the last, sparsely filled round of the grid.  XCD-aware order in both regions: workgroup ids are
+// dealt round-robin to the 8 XCDs, so each XCD gets one contiguous run of tiles (its L2 then sees
+// few distinct row tiles); n_full is a multiple of 8.
+__device__ __forceinline__ int xcd_order(int b, int n)
+{
+    const int per = n >> 3, rem = n & 7;
+    const int xcd = b & 7, loc = b >> 3;
+    return xcd * per + (xcd < rem ? xcd : rem) + loc;
+}
+
+template <int GC, int NK, bool DBG>
+__global__ __launch_bounds__(NW * 64, 2) void fwd_int_kernel(FwdParams p)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[lds_bytes<GC>()];
+    const int b = blockIdx.x;
+    if (b < p.n_full) {
+        const int tile = xcd_order(b, p.n_full);
+        const int tile_m = tile / p.tilesN, tile_n = tile - tile_m * p.tilesN;
+        fwd_tile<GC, NK, 4, DBG>(p, lds, tile_m * 4, tile_n);
+    } else {
+        const int hh = xcd_order(b - p.n_full, 2 * (p.tilesM * p.tilesN - p.n_full));
+        const int tile = p.n_full + (hh >> 1);
+        const int tile_m = tile / p.tilesN, tile_n = tile - tile_m * p.tilesN;
+        const int rb0 = tile_m * 4 + (hh & 1) * 2;
+        if (rb0 >= p.nrb) return;  // lower half of a partial last row tile: nothing to do
+        fwd_tile<GC, NK, 2, DBG>(p, lds, rb0, tile_n);
+    }
+}
+
+// Workgroup slots of the device: two workgroups (of 256 registers per lane) per compute unit.
+static int workgroup_slots()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 512;
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+        cached[dev] = 2 * cus;
+    }
+    return cached[dev];
+}
+
+template <int GC, int NK, bool DBG>
 static hipError_t launch_cfg(const FwdParams& p0, hipStream_t s)
 {
     FwdParams p = p0;
-    p.tilesM = (p.nrb + WM * 4 - 1) / (WM * 4);
+    p.tilesM = (p.nrb + 3) / 4;
     p.tilesN = (p.N + WN * 64 - 1) / (WN * 64);
-    dim3 grid((unsigned)(p.tilesM * p.tilesN)), block(WM * WN * 64);
-    hipLaunchKernelGGL((fwd_int_kernel<WM, WN, GC, DBG>), grid, block, 0, s, p);
+    const int tiles = p.tilesM * p.tilesN;
+    const int slots = workgroup_slots() & ~7;
+    // Full rounds of the grid use full tiles.  A half tile costs about 2/3 of a full one (the weight
+    // operands are expanded per wavefront either way), so splitting the remainder pays only while
+    // the halves still fit one per compute unit: measured +5 % on a 1152 -> 4608 layer (2.25 rounds),
+    // nothing at 1.75 rounds, a loss at 0.6 rounds.
+    int n_full = (tiles / slots) * slots;
+    if (4 * (tiles - n_full) > slots) n_full = tiles;
+    p.n_full = n_full;
+    dim3 grid((unsigned)(n_full + 2 * (tiles - n_full))), block(NW * 64);
+    hipLaunchKernelGGL((fwd_int_kernel<GC, NK, DBG>), grid, block, 0, s, p);
     return hipGetLastError();
+}
+
+template <int GC, bool DBG>
+static hipError_t launch_rank(int nk, const FwdParams& p, hipStream_t s)
+{
+    switch (nk) {
+        case 0: return launch_cfg<GC, 0, DBG>(p, s);
+        case 1: return launch_cfg<GC, 1, DBG>(p, s);
+        case 2: return launch_cfg<GC, 2, DBG>(p, s);
+        default: return launch_cfg<GC, 4, DBG>(p, s);
+    }
 }
 
 hipError_t launch_fwd_int(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M,
@@ -391,15 +466,16 @@ hipError_t launch_fwd_int(const Dims& d, const uint8_t* packed, const uint8_t* a
     p.C64 = d.C64;
     p.rp = d.rp;
     p.nrb = (int)(al.Mp / 32);
-    p.tilesM = p.tilesN = 0;
+    p.tilesM = p.tilesN = p.n_full = 0;
     p.dbg_acc = dbg ? dbg->acc : nullptr;
     p.dbg_acc2 = dbg ? dbg->acc2 : nullptr;
     p.dbg_y32 = dbg ? dbg->y32 : nullptr;
     const bool want_dbg = dbg && (dbg->acc || dbg->acc2 || dbg->y32);
+    const int nk = d.rp >> 5;  // 0 | 1 | 2 | 4 (the rank is one of 0, 16, 32, 64, 128)
     if (d.g == 64) {
-        return want_dbg ? launch_cfg<1, 4, 1, true>(p, s) : launch_cfg<1, 4, 1, false>(p, s);
+        return want_dbg ? launch_rank<1, true>(nk, p, s) : launch_rank<1, false>(nk, p, s);
     } else {
-        return want_dbg ? launch_cfg<1, 4, 2, true>(p, s) : launch_cfg<1, 4, 2, false>(p, s);
+        return want_dbg ? launch_rank<2, true>(nk, p, s) : launch_rank<2, false>(nk, p, s);
     }
 }
 

@@ -515,7 +515,8 @@ struct MxFwdParams {
     float* dbg_y32;
 };
 
-template <bool DBG>
+// NK = 64-deep chunks of the (padded) rank: 0 | 1 | 2
+template <int NK, bool DBG>
 __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
 {
     constexpr int WN = 4, RBT = 4;
@@ -657,52 +658,63 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     // ---- epilogue: FP8 rank-r expansion, scales, sum, bf16, transposed full-line stores -------
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     typedef float f32x2 __attribute__((ext_vector_type(2)));
+    constexpr int NKA = NK > 0 ? NK : 1;
     uint8_t* stage = lds + wave * EPI_WAVE;
-    const int nk = p.rp >> 6;
     float slv[2];
-    v8i lf[2][2];
+    v8i lf[2][NKA];
 #pragma unroll
     for (int cbi = 0; cbi < 2; ++cbi) {
         const int col = (cb0 + cbi) * 32 + l32;
         slv[cbi] = p.sl[col];
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            v8i v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (kk < nk) v = *(const v8i*)(p.l8 + (size_t)col * p.rp + kk * 64 + half * 32);
-            lf[cbi][kk] = v;
-        }
+        for (int kk = 0; kk < NK; ++kk) lf[cbi][kk] = *(const v8i*)(p.l8 + (size_t)col * p.rp + kk * 64 + half * 32);
     }
     const int wr_off = (4 * half) * EPI_ROW + l32 * 2;
     const int rd_row = lane >> 3, rd_seg = lane & 7;
+    // Operands of row block rbi+1 are fetched while block rbi is processed; blocks past the end of
+    // a partial tile are clamped and never stored.
+    v8i tf[NKA];
+    v4f stv[4];
+    auto load_tq = [&](int rbi) {
+        int rb = rb0 + rbi;
+        rb = rb < p.nrb ? rb : p.nrb - 1;
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) tf[kk] = *(const v8i*)(p.tq8 + (size_t)(rb * 32 + l32) * p.rp + kk * 64 + half * 32);
+    };
+    auto load_scales = [&](int rbi) {
+        int rb = rb0 + rbi;
+        rb = rb < p.nrb ? rb : p.nrb - 1;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) stv[q] = *(const v4f*)(p.st + rb * 32 + 8 * q + 4 * half);
+    };
+    load_tq(0);
+    load_scales(0);
 #pragma unroll
     for (int rbi = 0; rbi < 4; ++rbi) {
         const int rbase = (rb0 + rbi) * 32;
-        if (rbase >= p.M) break;
-        v8i tf[2];
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            v8i v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (kk < nk) v = *(const v8i*)(p.tq8 + (size_t)(rbase + l32) * p.rp + kk * 64 + half * 32);
-            tf[kk] = v;
-        }
-        v4f stv[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) stv[q] = *(const v4f*)(p.st + rbase + 8 * q + 4 * half);
+        v16f a2[2];
 #pragma unroll
         for (int cbi = 0; cbi < 2; ++cbi) {
-            v16f a2 = {0};
+            a2[cbi] = v16f{0};
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk)
-                if (kk < nk) a2 = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(tf[kk], lf[cbi][kk], a2, 0, 0, 0, 0, 0, 0);
-            float y[16];
+            for (int kk = 0; kk < NK; ++kk)
+                a2[cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(tf[kk], lf[cbi][kk], a2[cbi], 0, 0, 0, 0, 0, 0);
+        }
+        if (rbi + 1 < 4) load_tq(rbi + 1);
+        float y[2][16];
+#pragma unroll
+        for (int cbi = 0; cbi < 2; ++cbi)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const float ybr = __fmul_rn(__fmul_rn(a2[i], stv[i >> 2][i & 3]), slv[cbi]);
-                y[i] = __fadd_rn(t[rbi][cbi][i], ybr);
+                const float ybr = __fmul_rn(__fmul_rn(a2[cbi][i], stv[i >> 2][i & 3]), slv[cbi]);
+                y[cbi][i] = __fadd_rn(t[rbi][cbi][i], ybr);
             }
+        if (rbi + 1 < 4) load_scales(rbi + 1);
+#pragma unroll
+        for (int cbi = 0; cbi < 2; ++cbi) {
 #pragma unroll
             for (int i = 0; i < 16; i += 2) {
-                const bf16x2 h = __builtin_convertvector(f32x2{y[i], y[i + 1]}, bf16x2);
+                const bf16x2 h = __builtin_convertvector(f32x2{y[cbi][i], y[cbi][i + 1]}, bf16x2);
                 const uint32_t w = __builtin_bit_cast(uint32_t, h);
                 const int o = wr_off + (8 * (i >> 2) + (i & 3)) * EPI_ROW + cbi * 64;
                 *(uint16_t*)(stage + o) = (uint16_t)(w & 0xFFFFu);
@@ -713,7 +725,7 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int row = rbase + 8 * (i >> 2) + 4 * half + (i & 3);
-                    if (row < p.M && p.dbg_y32) p.dbg_y32[(size_t)row * p.N + col] = y[i];
+                    if (row < p.M && p.dbg_y32) p.dbg_y32[(size_t)row * p.N + col] = y[cbi][i];
                 }
             }
         }
@@ -725,6 +737,16 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
             if (row < p.M) *(v4i*)(p.Y + (size_t)row * p.ldy + cb0 * 32 + rd_seg * 8) = v;
         }
     }
+}
+
+template <int NK>
+static void mx_fwd_launch(const MxFwdParams& p, hipStream_t s)
+{
+    dim3 grid((unsigned)(p.tilesM * p.tilesN)), block(256);
+    if (p.dbg_y32)
+        hipLaunchKernelGGL((mx_fwd_kernel<NK, true>), grid, block, 0, s, p);
+    else
+        hipLaunchKernelGGL((mx_fwd_kernel<NK, false>), grid, block, 0, s, p);
 }
 
 hipError_t launch_fwd_mx(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M, uint16_t* Y, int64_t ldy,
@@ -753,11 +775,11 @@ hipError_t launch_fwd_mx(const Dims& d, const uint8_t* packed, const uint8_t* ac
     p.tilesM = (p.nrb + 3) / 4;
     p.tilesN = (p.N + 255) / 256;
     p.dbg_y32 = dbg ? dbg->y32 : nullptr;
-    dim3 grid((unsigned)(p.tilesM * p.tilesN)), block(256);
-    if (p.dbg_y32)
-        hipLaunchKernelGGL(mx_fwd_kernel<true>, grid, block, 0, s, p);
-    else
-        hipLaunchKernelGGL(mx_fwd_kernel<false>, grid, block, 0, s, p);
+    switch (p.rp >> 6) {
+        case 0: mx_fwd_launch<0>(p, s); break;
+        case 1: mx_fwd_launch<1>(p, s); break;
+        default: mx_fwd_launch<2>(p, s); break;
+    }
     return hipGetLastError();
 }
 

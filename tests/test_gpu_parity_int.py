@@ -73,6 +73,15 @@ def test_small_shapes_bit_exact(oracle, M, K, N, r, g, bw, ba, xd):
     _compare_all(oracle, layer, X, W, L, R)
 
 
+@pytest.mark.parametrize("M,K,N,r,g,bw,ba", [(2000, 128, 2304, 16, 64, 8, 8), (2100, 256, 2304, 32, 128, 4, 8)])
+def test_full_tiles_bit_exact(oracle, M, K, N, r, g, bw, ba):
+    """Large enough (more than a quarter of the device's workgroup slots) that the grid runs
+    full 128 x 256 tiles, the small shapes above run as half tiles; ragged last row tile."""
+    layer = wl.Layer("t", M, K, N, r, "int", g, bw, ba, "bf16", outlier_scale=15.0, n_outliers=2, seed=M + K)
+    X, W, L, R = wl.make_inputs(layer)
+    _compare_all(oracle, layer, X, W, L, R)
+
+
 def test_config1_exact(oracle):
     layer = wl.LAYERS["c1_single"]
     X, W, L, R = wl.make_inputs(layer)
@@ -126,7 +135,10 @@ def test_full_size_sampled_rows(oracle, name):
     X, W, L, R = wl.make_inputs(layer)
     g = run_gpu(layer, X, W, L, R, debug=False)
     rng = np.random.default_rng(1)
-    rows = np.sort(np.concatenate([[0, layer.M - 1], rng.choice(layer.M, 22, replace=False)]))
+    # first and last rows, both halves of the last row tile (the tail of the grid may run as half
+    # tiles), and a random sample
+    fixed = [0, layer.M - 1, layer.M - 40, layer.M - 100]
+    rows = np.unique(np.concatenate([fixed, rng.choice(layer.M, 20, replace=False)]))
     pk, act, out = run_oracle_int(oracle, layer, X[rows], W, L, R, want_acc=False)
     av = n(g.av.xq) if g.av is not None else None
     from paper_2604_18117_amd import binding as lq
