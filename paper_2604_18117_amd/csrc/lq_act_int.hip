@@ -15,6 +15,7 @@
 namespace lq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 
 struct ActParams {
     const void* X;
@@ -109,12 +110,40 @@ __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
         xc[ci].load(p.X, (size_t)row * p.ldx + (size_t)c * 64 + kq * 16, row_ok && c < C64);
     }
 
+    // Operands that do not depend on X are requested now, so that their latency overlaps the
+    // load of X: the Q2(R) fragments of this wavefront's first chunk (later chunks are fetched one
+    // chunk ahead inside the loop) and the row scales of R.
+    constexpr int NJA = NJB > 0 ? NJB : 1;
+    v4i bv[2][NJA];
+    auto load_rq = [&](v4i (&dst)[NJA], int ci) {
+        int c = wave + 4 * ci;
+        c = c < C64 ? c : C64 - 1;  // clamped: a fragment past the end is fetched but not used
+#pragma unroll
+        for (int jb = 0; jb < NJB; ++jb) dst[jb] = *(const v4i*)(p.rq + ((size_t)((size_t)c * NJB + jb) * 64 + lane) * 16);
+    };
+    load_rq(bv[0], 0);
+    float srj[NJA];
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb) srj[jb] = p.sr[jb * 16 + r16];
+
     // ---- per-row amax -------------------------------------------------------------------
     float a = 0.f;
+    if constexpr (BF16) {
+        // |bf16| is monotonic in its low 15 bits: packed unsigned 16-bit max, two values per op
+        us2 m2 = {0, 0};
 #pragma unroll
-    for (int ci = 0; ci < MAXC; ++ci)
+        for (int ci = 0; ci < MAXC; ++ci)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) a = fmaxf(a, fabsf(xc[ci].get(i)));
+            for (int d = 0; d < 8; ++d)
+                m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, xc[ci].w[d] & 0x7FFF7FFFu));
+        const uint32_t mm = m2[0] > m2[1] ? m2[0] : m2[1];
+        a = __uint_as_float(mm << 16);
+    } else {
+#pragma unroll
+        for (int ci = 0; ci < MAXC; ++ci)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) a = fmaxf(a, fabsf(xc[ci].get(i)));
+    }
     a = fmaxf(a, __shfl_xor(a, 16, 64));
     a = fmaxf(a, __shfl_xor(a, 32, 64));
     if (kq == 0) s_amax[wave][r16] = a;
@@ -139,18 +168,50 @@ __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
 #pragma unroll
     for (int ci = 0; ci < MAXC; ++ci) {
         const int c = wave + 4 * ci;
+        if (ci + 1 < MAXC) load_rq(bv[(ci + 1) & 1], ci + 1);
         if (c < C64) {  // wave-uniform
-            // main codes: magnitude from |x|, sign from x
             uint32_t pk[2] = {0u, 0u};
             uint32_t xb4[4] = {0u, 0u, 0u, 0u};
+            if constexpr (BF16) {
+                // Magnitudes: |x|*inv + 2^23 has the code in its low bits and 0x4B in its top byte;
+                // eight of them are summed at their nibble positions with shift-adds (the top
+                // bytes shifted by 0 and 4 add up to the constant removed first, the others leave
+                // the dword).  Signs: the high bytes of four bf16 values are gathered with one
+                // byte permute.  Branch codes: low bytes of x*invb + 1.5*2^23, gathered likewise.
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float x = xc[ci].get(i);
-                const uint32_t m = __float_as_uint(__fadd_rn(__fmul_rn(fabsf(x), inv4), 8388608.0f)) & 7u;
-                const uint32_t sgn = __float_as_uint(x) >> 31;
-                pk[i >> 3] |= nib_put(i & 7, sgn, m);
-                const uint32_t b = rne_bits(__fmul_rn(x, invb)) & 0xFFu;
-                xb4[i >> 2] |= b << (8 * (i & 3));
+                for (int h = 0; h < 2; ++h) {
+                    uint32_t acc = 0u - 0xFB000000u;
+                    uint32_t tb[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float x = xc[ci].get(8 * h + e);
+                        const uint32_t mb = __float_as_uint(__fadd_rn(__fmul_rn(fabsf(x), inv4), 8388608.0f));
+                        const int sh = e < 4 ? 8 * e : 8 * ((e - 5) & 3) + 4;
+                        acc += mb << sh;
+                        tb[e] = rne_bits(__fmul_rn(x, invb));
+                    }
+                    const uint32_t* w = &xc[ci].w[4 * h];
+                    const uint32_t s03 = __builtin_amdgcn_perm(w[1], w[0], 0x07050301u);
+                    const uint32_t s47 = __builtin_amdgcn_perm(w[3], w[2], 0x07050301u);
+                    pk[h] = acc | (s03 & 0x80808080u) | ((s47 >> 4) & 0x08080808u);
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const uint32_t p01 = __builtin_amdgcn_perm(tb[4 * q + 1], tb[4 * q], 0x0c0c0400u);
+                        const uint32_t p23 = __builtin_amdgcn_perm(tb[4 * q + 3], tb[4 * q + 2], 0x0c0c0400u);
+                        xb4[2 * h + q] = __builtin_amdgcn_perm(p23, p01, 0x05040100u);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    // main codes: magnitude from |x|, sign from x
+                    const float x = xc[ci].get(i);
+                    const uint32_t m = __float_as_uint(__fadd_rn(__fmul_rn(fabsf(x), inv4), 8388608.0f)) & 7u;
+                    const uint32_t sgn = __float_as_uint(x) >> 31;
+                    pk[i >> 3] |= nib_put(i & 7, sgn, m);
+                    const uint32_t b = rne_bits(__fmul_rn(x, invb)) & 0xFFu;
+                    xb4[i >> 2] |= b << (8 * (i & 3));
+                }
             }
             uint8_t* dst = p.xq + ((size_t)((size_t)rb * C64 + c) * 64 + (row & 31) + 32 * (kq >> 1)) * 16 + (kq & 1) * 8;
             *(uint2*)dst = make_uint2(pk[0], pk[1]);
@@ -159,10 +220,8 @@ __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
             if (njb > 0) {
                 const v4i av = {(int)xb4[0], (int)xb4[1], (int)xb4[2], (int)xb4[3]};
 #pragma unroll
-                for (int jb = 0; jb < NJB; ++jb) {
-                    const v4i bv = *(const v4i*)(p.rq + ((size_t)((size_t)c * njb + jb) * 64 + lane) * 16);
-                    acc[jb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bv, acc[jb], 0, 0, 0);
-                }
+                for (int jb = 0; jb < NJB; ++jb)
+                    acc[jb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bv[ci & 1][jb], acc[jb], 0, 0, 0);
             }
         }
     }
@@ -186,11 +245,10 @@ __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
                 const v4i o = *(const v4i*)&s_acc[w][jb][lane][0];
                 s += o;
             }
-            const float srj = p.sr[jb * 16 + r16];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int tok = 4 * kq + i;
-                const float tv = __fmul_rn(__fmul_rn((float)s[i], s_sxb[tok]), srj);
+                const float tv = __fmul_rn(__fmul_rn((float)s[i], s_sxb[tok]), srj[jb]);
                 T[jb][i] = tv;
                 tmax[i] = fmaxf(tmax[i], fabsf(tv));
                 const int grow = blockIdx.x * 16 + tok;

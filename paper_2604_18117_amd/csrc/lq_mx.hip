@@ -24,6 +24,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 
 // ---------------------------------------------------------------------------------------------
 // shared device helpers
@@ -61,6 +62,16 @@ __device__ __forceinline__ uint32_t fp8_pair(float u0, float u1)  // two E4M3 by
     u0 = fminf(fmaxf(u0, -448.0f), 448.0f);
     u1 = fminf(fmaxf(u1, -448.0f), 448.0f);
     return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(u0, u1, 0, false) & 0xFFFFu;
+}
+// four E4M3 bytes from four in-range-or-not values: one median (saturation) and half a convert each
+__device__ __forceinline__ uint32_t fp8_quad(float u0, float u1, float u2, float u3)
+{
+    u0 = __builtin_amdgcn_fmed3f(u0, -448.0f, 448.0f);
+    u1 = __builtin_amdgcn_fmed3f(u1, -448.0f, 448.0f);
+    u2 = __builtin_amdgcn_fmed3f(u2, -448.0f, 448.0f);
+    u3 = __builtin_amdgcn_fmed3f(u3, -448.0f, 448.0f);
+    const int lo = __builtin_amdgcn_cvt_pk_fp8_f32(u0, u1, 0, false);
+    return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(u2, u3, lo, true);
 }
 __device__ __forceinline__ float fp8_value(uint32_t byte) { return __builtin_amdgcn_cvt_f32_fp8((int)byte, 0); }
 __device__ __forceinline__ void fp8_scales(float amax, float* s, float* inv)
@@ -323,14 +334,38 @@ __global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
         xc[ci].load(p.X, (size_t)row * p.ldx + (size_t)c * 64 + kq * 16, row_ok && c < C64);
     }
 
+    // Operands that do not depend on X are requested now (their latency overlaps the load of X):
+    // the Q2(R) fragments of the first chunk (later ones one chunk ahead, in the loop), R's scales.
+    constexpr int NJA = NJB > 0 ? NJB : 1;
+    v4i bvs[2][NJA];
+    auto load_r8 = [&](v4i (&dst)[NJA], int ci) {
+        int c = wave + 4 * ci;
+        c = c < C64 ? c : C64 - 1;  // clamped: a fragment past the end is fetched but not used
+#pragma unroll
+        for (int jb = 0; jb < NJB; ++jb) dst[jb] = *(const v4i*)(p.r8 + ((size_t)((size_t)c * NJB + jb) * 64 + lane) * 16);
+    };
+    load_r8(bvs[0], 0);
+    float srj[NJA];
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb) srj[jb] = p.sr[jb * 16 + r16];
+
     // amax of the lane's 16 values per chunk (reused for the block scale) and of the whole row
     float a16[MAXC];
     float a = 0.f;
 #pragma unroll
     for (int ci = 0; ci < MAXC; ++ci) {
         float m = 0.f;
+        if constexpr (BF16) {
+            // |bf16| is monotonic in its low 15 bits: packed unsigned 16-bit max, two values per op
+            us2 m2 = {0, 0};
 #pragma unroll
-        for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(xc[ci].get(i)));
+            for (int d = 0; d < 8; ++d) m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, xc[ci].w[d] & 0x7FFF7FFFu));
+            const uint32_t mm = m2[0] > m2[1] ? m2[0] : m2[1];
+            m = __uint_as_float(mm << 16);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(xc[ci].get(i)));
+        }
         a16[ci] = m;
         a = fmaxf(a, m);
     }
@@ -354,6 +389,7 @@ __global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
 #pragma unroll
     for (int ci = 0; ci < MAXC; ++ci) {
         const int c = wave + 4 * ci;
+        if (ci + 1 < MAXC) load_r8(bvs[(ci + 1) & 1], ci + 1);
         if (c < C64) {  // wave-uniform
             // MXFP4: block of 32 = this lane's 16 values and its neighbour's (kq ^ 1)
             const float ab = fmaxf(a16[ci], __shfl_xor(a16[ci], 16, 64));
@@ -367,14 +403,9 @@ __global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
             }
 #undef LQ_CVT4
 #pragma unroll
-            for (int i = 0; i < 16; i += 2) {
-                const float x0 = xc[ci].get(i), x1 = xc[ci].get(i + 1);
-                const uint32_t h = fp8_pair(__fmul_rn(x0, invb), __fmul_rn(x1, invb));
-                if ((i & 2) == 0)
-                    x8[i >> 2] = h;
-                else
-                    x8[i >> 2] |= h << 16;
-            }
+            for (int q = 0; q < 4; ++q)
+                x8[q] = fp8_quad(__fmul_rn(xc[ci].get(4 * q), invb), __fmul_rn(xc[ci].get(4 * q + 1), invb),
+                                 __fmul_rn(xc[ci].get(4 * q + 2), invb), __fmul_rn(xc[ci].get(4 * q + 3), invb));
             uint8_t* dst = p.xc + ((size_t)((size_t)(row >> 5) * C64 + c) * 64 + (row & 31) + 32 * (kq >> 1)) * 16 + (kq & 1) * 8;
             *(uint2*)dst = make_uint2(pk[0], pk[1]);
             if ((kq & 1) == 0) p.xe[mx_scale_offset(row, c, kq >> 1, p.CQ)] = (uint8_t)E;
@@ -385,13 +416,16 @@ __global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
                 const long ahi = (long)(((unsigned long)x8[3] << 32) | x8[2]);
 #pragma unroll
                 for (int jb = 0; jb < NJB; ++jb) {
-                    const v4i bv = *(const v4i*)(p.r8 + ((size_t)((size_t)c * NJB + jb) * 64 + lane) * 16);
+                    const v4i bv = bvs[ci & 1][jb];
                     const long blo = (long)(((unsigned long)(uint32_t)bv[1] << 32) | (uint32_t)bv[0]);
                     const long bhi = (long)(((unsigned long)(uint32_t)bv[3] << 32) | (uint32_t)bv[2]);
                     acc[jb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(alo, blo, acc[jb], 0, 0, 0);
                     acc[jb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(ahi, bhi, acc[jb], 0, 0, 0);
                 }
             }
+        } else if (c < 4 * p.CQ) {
+            // padding chunk of the last quad: its scale bytes must be valid E8M0 values (2^0)
+            if ((kq & 1) == 0) p.xe[mx_scale_offset(row, c, kq >> 1, p.CQ)] = (uint8_t)127;
         }
     }
     if (NJB == 0) return;
@@ -412,11 +446,10 @@ __global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
 #pragma unroll
             for (int i = 0; i < 4; ++i) s[i] = __fadd_rn(s[i], o[i]);
         }
-        const float srj = p.sr[jb * 16 + r16];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int tok = 4 * kq + i;
-            const float tv = __fmul_rn(__fmul_rn(s[i], s_sxb[tok]), srj);
+            const float tv = __fmul_rn(__fmul_rn(s[i], s_sxb[tok]), srj[jb]);
             T[jb][i] = tv;
             tmax[i] = fmaxf(tmax[i], fabsf(tv));
             const int grow = blockIdx.x * 16 + tok;
@@ -481,11 +514,6 @@ hipError_t launch_quantize_act_mx(const Dims& d, int x_dtype, const uint8_t* pac
     p.dbg_xb = dbg ? dbg->xb : nullptr;
     p.dbg_sxb = dbg ? dbg->sxb : nullptr;
     p.dbg_T = dbg ? dbg->T : nullptr;
-    // scale bytes of the padding chunks (the last quad may be partial) must be valid E8M0 values
-    const size_t xe_bytes = (size_t)(al.Mp / 32) * p.CQ * 256;
-    if (d.C64 & 3)
-        hipLaunchKernelGGL(mx_fill_kernel, dim3((unsigned)((xe_bytes + 255) / 256)), dim3(256), 0, s, p.xe, xe_bytes,
-                           (uint8_t)127);
     const int maxc = (d.C64 + 3) / 4;
     if (x_dtype == LQ_BF16) {
         if (maxc <= 5) return mx_act_rank<true, 5>(p, al.Mp, s);
