@@ -717,6 +717,11 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     };
     load_tq(0);
     load_scales(0);
+    // this lane's output pointer: row rd_row of the tile, 16 bytes at column segment rd_seg; it moves
+    // down 8 rows per store (4 stores per row block), rows past M are skipped
+    uint16_t* yptr = p.Y + (size_t)(rb0 * 32 + rd_row) * p.ldy + cb0 * 32 + rd_seg * 8;
+    const size_t ystep = (size_t)8 * p.ldy;
+    v4i ov[4];
 #pragma unroll
     for (int rbi = 0; rbi < 4; ++rbi) {
         const int rbase = (rb0 + rbi) * 32;
@@ -758,11 +763,11 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
             }
         }
 #pragma unroll
+        for (int q = 0; q < 4; ++q) ov[q] = *(const v4i*)(stage + (q * 8 + rd_row) * EPI_ROW + rd_seg * 16);
+#pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int rl = q * 8 + rd_row;
-            const v4i v = *(const v4i*)(stage + rl * EPI_ROW + rd_seg * 16);
-            const int row = rbase + rl;
-            if (row < p.M) *(v4i*)(p.Y + (size_t)row * p.ldy + cb0 * 32 + rd_seg * 8) = v;
+            if (rbase + q * 8 + rd_row < p.M) *(v4i*)yptr = ov[q];
+            yptr += ystep;
         }
     }
 }
