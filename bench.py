@@ -17,9 +17,11 @@ sys.path.insert(0, ROOT)
 
 # MI355X dense matrix peaks: FP8 / INT8 (the INT4 main product runs on the FP8 pipe) and FP4 (MXFP4)
 PEAK_MFMA_TFLOPS = {"int": 5033.0, "mx": 10066.0}
-# HBM bytes per forward launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/fwd_int_kernel_c2_qkv.md),
+# HBM bytes per forward launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/fwd_int_kernel_c2_qkv.md,
+# profiles/mx_fwd_kernel_c5_qkv.md),
 # each scaled by the factor a plain copy of known size gives (2.0 for FETCH_SIZE, 1.0 for WRITE_SIZE).
-MEASURED_TRAFFIC_BYTES = {"c2_qkv": 22226.0 * 1024 * 2.0 + 55296.0 * 1024 * 1.0}
+MEASURED_TRAFFIC_BYTES = {"c2_qkv": 22004.6 * 1024 * 2.0 + 55296.0 * 1024 * 1.0,
+                          "c5_qkv": 42285.7 * 1024 * 2.0 + 110592.0 * 1024 * 1.0}
 
 
 def layer_ops(l):
