@@ -39,6 +39,7 @@ struct FwdParams {
     int64_t ldy;
     int M, N, G, C64, rp, nrb;
     int tilesM, tilesN, n_full;
+    int split_last;  // the last tile column has exactly 128 valid channels: run it 2 x 2
     int32_t* dbg_acc;
     int32_t* dbg_acc2;
     float* dbg_y32;
@@ -67,9 +68,13 @@ constexpr int lds_bytes()
     return 2 * GC * RBT * 2048 > NW * EPI_WAVE ? 2 * GC * RBT * 2048 : NW * EPI_WAVE;
 }
 
-// One output tile of (NRB*32) x 256: rows rb0*32.., columns tile_n*256...  NRB = 4 (full tile) or
+// One output tile: rows rb0*32.., columns tile_n*256...  Each wavefront owns NRB row blocks x 64
+// columns.  SPLIT = false: the 4 wavefronts sit side by side (tile of NRB*32 x 256).  SPLIT = true
+// (NRB = 2): they are arranged 2 x 2 over a 128 x 128 tile, used for a last tile column that has
+// only 128 valid channels, where two of four side-by-side wavefronts would idle through the loop.
+// NRB = 4 (full tile) or
 // 2 (half tile, used for the tail of the grid).  NK = 32-deep chunks of the padded rank: 0|1|2|4.
-template <int GC, int NK, int NRB, bool DBG>
+template <int GC, int NK, int NRB, bool DBG, bool SPLIT = false>
 __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const int rb0, const int tile_n)
 {
     constexpr int SPW = 1;                      // row blocks staged per wavefront
@@ -78,11 +83,14 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps address math scalar
-    const int wn = wave;
+    static_assert(!SPLIT || NRB == 2, "2 x 2 arrangement uses two row blocks per wavefront");
+    const int wn = SPLIT ? (wave & 1) : wave;
+    const int wm = SPLIT ? (wave >> 1) : 0;
+    const int rbw = rb0 + wm * NRB;             // first row block owned by this wavefront
     const int half = lane >> 5, l32 = lane & 31;
 
     const int cb0 = tile_n * (WN * 2) + wn * 2;
-    const bool active = (cb0 * 32 < p.N) && (rb0 < p.nrb);
+    const bool active = (cb0 * 32 < p.N) && (rbw < p.nrb);
 
     const int C64 = p.C64, G = p.G;
 
@@ -168,7 +176,7 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         const int buf = s & 1;
         {
             auto lds_a = [&](int rbi, int cc) -> v8i {
-                const uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + rbi) * 2048) + lane16;
+                const uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wm * NRB + rbi) * 2048) + lane16;
                 const v4i lo = *(const v4i*)(base);
                 const v4i hi = *(const v4i*)(base + 1024);
                 return v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
@@ -214,7 +222,7 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
                     if (p.dbg_acc && active) {
 #pragma unroll
                         for (int i = 0; i < 16; ++i) {
-                            const int row = (rb0 + rbi) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+                            const int row = (rbw + rbi) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
                             const int col = (cb0 + cbi) * 32 + l32;
                             if (row < p.M)
                                 p.dbg_acc[((size_t)row * p.N + col) * G + s] = (int)(dd[j & 1][i] * 262144.0f);
@@ -297,14 +305,14 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     v4i tqf[NKA];
     v4f sxv[4], stv[4];
     auto load_tq = [&](int rbi) {
-        int rb = rb0 + rbi;
+        int rb = rbw + rbi;
         rb = rb < p.nrb ? rb : p.nrb - 1;
 #pragma unroll
         for (int kk = 0; kk < NK; ++kk)
             tqf[kk] = *(const v4i*)(p.tq + (size_t)(rb * 32 + l32) * p.rp + kk * 32 + half * 16);
     };
     auto load_scales = [&](int rbi) {  // rows 8*q + 4*half + 0..3 are contiguous -> one 16-byte load each
-        int rb = rb0 + rbi;
+        int rb = rbw + rbi;
         rb = rb < p.nrb ? rb : p.nrb - 1;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -316,12 +324,12 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     load_scales(0);
     // this lane's output pointer: row rd_row of the tile, 16 bytes at column segment rd_seg; it moves
     // down 8 rows per store (4 stores per row block), rows past M are skipped
-    uint16_t* yptr = p.Y + (size_t)(rb0 * 32 + rd_row) * p.ldy + cb0 * 32 + rd_seg * 8;
+    uint16_t* yptr = p.Y + (size_t)(rbw * 32 + rd_row) * p.ldy + cb0 * 32 + rd_seg * 8;
     const size_t ystep = (size_t)8 * p.ldy;
     v4i ov[4];
 #pragma unroll
     for (int rbi = 0; rbi < NRB; ++rbi) {
-        const int rbase = (rb0 + rbi) * 32;
+        const int rbase = (rbw + rbi) * 32;
         v16i a2[2];
 #pragma unroll
         for (int cbi = 0; cbi < 2; ++cbi) {
@@ -393,7 +401,10 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_int_kernel(FwdParams p)
     if (b < p.n_full) {
         const int tile = xcd_order(b, p.n_full);
         const int tile_m = tile / p.tilesN, tile_n = tile - tile_m * p.tilesN;
-        fwd_tile<GC, NK, 4, DBG>(p, lds, tile_m * 4, tile_n);
+        if (p.split_last && tile_n == p.tilesN - 1)
+            fwd_tile<GC, NK, 2, DBG, true>(p, lds, tile_m * 4, tile_n);
+        else
+            fwd_tile<GC, NK, 4, DBG>(p, lds, tile_m * 4, tile_n);
     } else {
         const int hh = xcd_order(b - p.n_full, 2 * (p.tilesM * p.tilesN - p.n_full));
         const int tile = p.n_full + (hh >> 1);
@@ -433,6 +444,7 @@ static hipError_t launch_cfg(const FwdParams& p0, hipStream_t s)
     int n_full = (tiles / slots) * slots;
     if (4 * (tiles - n_full) > slots) n_full = tiles;
     p.n_full = n_full;
+    p.split_last = (p.N & 255) == 128;
     dim3 grid((unsigned)(n_full + 2 * (tiles - n_full))), block(NW * 64);
     hipLaunchKernelGGL((fwd_int_kernel<GC, NK, DBG>), grid, block, 0, s, p);
     return hipGetLastError();
@@ -471,7 +483,7 @@ hipError_t launch_fwd_int(const Dims& d, const uint8_t* packed, const uint8_t* a
     p.C64 = d.C64;
     p.rp = d.rp;
     p.nrb = (int)(al.Mp / 32);
-    p.tilesM = p.tilesN = p.n_full = 0;
+    p.tilesM = p.tilesN = p.n_full = p.split_last = 0;
     p.dbg_acc = dbg ? dbg->acc : nullptr;
     p.dbg_acc2 = dbg ? dbg->acc2 : nullptr;
     p.dbg_y32 = dbg ? dbg->y32 : nullptr;

@@ -73,10 +73,12 @@ def test_small_shapes_bit_exact(oracle, M, K, N, r, g, bw, ba, xd):
     _compare_all(oracle, layer, X, W, L, R)
 
 
-@pytest.mark.parametrize("M,K,N,r,g,bw,ba", [(2000, 128, 2304, 16, 64, 8, 8), (2100, 256, 2304, 32, 128, 4, 8)])
+@pytest.mark.parametrize("M,K,N,r,g,bw,ba", [(2000, 128, 2304, 16, 64, 8, 8), (2100, 256, 2304, 32, 128, 4, 8),
+                                                 (2100, 128, 2176, 32, 64, 8, 8)])
 def test_full_tiles_bit_exact(oracle, M, K, N, r, g, bw, ba):
     """Large enough (more than a quarter of the device's workgroup slots) that the grid runs
-    full 128 x 256 tiles, the small shapes above run as half tiles; ragged last row tile."""
+    full 128 x 256 tiles, the small shapes above run as half tiles; ragged last row tile; the third
+    case has a last tile column with 128 valid channels (wavefronts arranged 2 x 2 there)."""
     layer = wl.Layer("t", M, K, N, r, "int", g, bw, ba, "bf16", outlier_scale=15.0, n_outliers=2, seed=M + K)
     X, W, L, R = wl.make_inputs(layer)
     _compare_all(oracle, layer, X, W, L, R)
