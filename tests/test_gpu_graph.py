@@ -1,0 +1,56 @@
+"""The per-call path (activation step + forward) recorded into a HIP graph: two kernel nodes, no
+memset nodes, no allocation.  Every replay must give the eager result, also with other work and
+synchronisations between the replays and with new contents in the same input buffer."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_18117_amd import binding as lq
+from paper_2604_18117_amd import workloads as wl
+from tests.gpu_util import to_dev_x
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("family,g", [("int", 64), ("int", 128), ("mx", 32)])
+def test_graph_replays_match_eager(family, g):
+    layer = wl.Layer("t", 700, 512, 640, 32, family, g, 8, 8, "bf16", outlier_scale=10.0, n_outliers=4, seed=11)
+    X, W, L, R = wl.make_inputs(layer)
+    cfg = lq.config_for_layer(layer)
+    packed = lq.lq_pack_weights(cfg, torch.from_numpy(W).cuda(), torch.from_numpy(L).cuda(), torch.from_numpy(R).cuda())
+    M = layer.M
+    rng = np.random.default_rng(5)
+    inputs = [to_dev_x(X if i == 0 else X[rng.permutation(M)] * np.float32(0.5 + i), "bf16") for i in range(3)]
+    # eager results
+    eager = []
+    for Xi in inputs:
+        act = lq.lq_quantize_act(cfg, packed, Xi)
+        eager.append(lq.lq_linear_lowrank_fwd(cfg, packed, act, M).clone())
+    torch.cuda.synchronize()
+    # capture on a side stream with static buffers
+    Xs = inputs[0].clone()
+    act = torch.empty(lq.lq_act_sizes(cfg, M), dtype=torch.uint8, device="cuda")
+    Y = torch.empty((M, layer.N), dtype=torch.bfloat16, device="cuda")
+    graph = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        lq.lq_quantize_act(cfg, packed, Xs, act=act)          # warm-up outside the capture
+        lq.lq_linear_lowrank_fwd(cfg, packed, act, M, Y=Y)
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=s):
+        lq.lq_quantize_act(cfg, packed, Xs, act=act)
+        lq.lq_linear_lowrank_fwd(cfg, packed, act, M, Y=Y)
+    for rep in range(6):
+        i = rep % 3
+        Xs.copy_(inputs[i])
+        Y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y.view(torch.int16), eager[i].view(torch.int16)), f"replay {rep}"
+        # eager work of the same library between replays
+        a2 = lq.lq_quantize_act(cfg, packed, inputs[(i + 1) % 3])
+        y2 = lq.lq_linear_lowrank_fwd(cfg, packed, a2, M)
+        torch.cuda.synchronize()
+        assert torch.equal(y2.view(torch.int16), eager[(i + 1) % 3].view(torch.int16))
