@@ -4,7 +4,9 @@ linear layer with a quantized low-rank branch, on synthetic DiT-shaped layers, o
 
 A "step" is one pass of the whole per-call path (lq_quantize_act + lq_linear_lowrank_fwd)
 over one batch of M tokens already resident in HBM; weight packing is offline and untimed.
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (whole-path TOPS), ms_per_step, the workload, a `roofline` object for
+the forward kernel (bound, achieved, peak, fraction, measured HBM traffic), an `act_kernel` object and a
+`cpu_baseline` object (the CPU oracle timed on the host cores on the same workload).
 """
 import argparse
 import json
@@ -43,8 +45,8 @@ def main():
                     help="only run a plain device-to-device copy of BYTES (calibrates the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build is single-GPU (the path shards over tokens with no collective; "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build is single-GPU (token rows are independent through the whole path, so it "
+              "would shard over tokens with no collective); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
