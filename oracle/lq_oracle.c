@@ -19,6 +19,10 @@
  *   MX   : Q1 = MXFP4 (E2M1 elements, blocks of 32 along K, E8M0 power-of-two scale,
  *          App. A.3), Q2 = FP8 E4M3 with one fp32 scale per token / per channel;
  *          fp64 accumulate, result rounded once to fp32.
+ *   MXB  : as MX, but Q2 = MXFP8e4 (App. A.3: E4M3 elements, blocks of 32 along the
+ *          contraction axis, E8M0 scale) for X, R, the intermediate X R^T and L, i.e. the
+ *          all-MX setting of the paper's mixed-precision tables (Section 4.3); no fp32
+ *          scale anywhere; the two branches are summed in fp64 and rounded once.
  *
  * Readings of points the paper leaves open (all "parity unpinned" by the paper; the tests
  * pin self-consistency only):
@@ -30,6 +34,8 @@
  *     (the paper lists this as future work; the benchmark spec requires it);
  *   - MX scale exponent = floor(log2 amax) - 2 (2 = largest E2M1 exponent), elements
  *     saturate at +-6; all-zero block: E8M0 byte 0;
+ *   - MXFP8e4 scale exponent = floor(log2 amax) - 8 (8 = largest E4M3 exponent), elements
+ *     saturate at +-448; the rank is a multiple of 32 so that blocks along r are whole;
  *   - P is built from the *dequantised* quantised factors (Fig. 1), optionally from the
  *     unquantised ones (residual_from_quantized = 0).
  *
@@ -424,6 +430,145 @@ LQO_API void lqo_fwd_mx(int64_t M, int64_t N, int64_t K, int r, const uint8_t *x
     }
     free(vw);
     free(vl);
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* MXB family: block-scaled FP8 branch                                                    */
+/* ------------------------------------------------------------------------------------ */
+
+/* MXFP8e4: n values (n a multiple of 32) in blocks of 32; one E8M0 byte per block; E4M3 codes. */
+LQO_API void lqo_quant_mxfp8(const float *v, int64_t n, uint8_t *codes, uint8_t *e8m0)
+{
+    for (int64_t b = 0; b < n / 32; ++b) {
+        const float *blk = v + 32 * b;
+        float a = absmax_f32(blk, 32);
+        int e;
+        if (a == 0.0f) {
+            e = -127;
+        } else {
+            int ex;
+            (void)frexpf(a, &ex); /* floor(log2 a) = ex - 1 */
+            e = (ex - 1) - 8;
+            if (e < -127) e = -127;
+            if (e > 127) e = 127;
+        }
+        e8m0[b] = (uint8_t)(e + 127);
+        for (int i = 0; i < 32; ++i) codes[32 * b + i] = lqo_e4m3_encode(ldexpf(blk[i], -e));
+    }
+}
+
+/* value of an MXFP8e4 element */
+static double mxfp8_value(uint8_t code, uint8_t e8m0)
+{
+    return (double)lqo_e4m3_decode(code) * lqo_e8m0_decode(e8m0);
+}
+
+/* Outputs: pc N x K E2M1, pe N x K/32; l8 N x r E4M3, le N x r/32 (blocks along r);
+   r8 r x K E4M3, re r x K/32 (blocks along K); P (optional). */
+LQO_API void lqo_pack_mxb(int64_t N, int64_t K, int r, int residual_from_quantized,
+                          const float *W, const float *L, const float *R, uint8_t *pc,
+                          uint8_t *pe, uint8_t *l8, uint8_t *le, uint8_t *r8, uint8_t *re,
+                          float *P_out)
+{
+    const int64_t BK = K / 32;
+    const int BR = r / 32;
+    for (int j = 0; j < r; ++j) lqo_quant_mxfp8(R + (int64_t)j * K, K, r8 + (int64_t)j * K, re + (int64_t)j * BK);
+    for (int64_t n = 0; n < N; ++n) lqo_quant_mxfp8(L + n * r, r, l8 + n * r, le + n * BR);
+
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        float *P = (float *)malloc(sizeof(float) * (size_t)K);
+        for (int64_t k = 0; k < K; ++k) {
+            double d = 0.0;
+            for (int j = 0; j < r; ++j) {
+                double lh, rh;
+                if (residual_from_quantized) {
+                    lh = mxfp8_value(l8[n * r + j], le[n * BR + j / 32]);
+                    rh = mxfp8_value(r8[(int64_t)j * K + k], re[(int64_t)j * BK + k / 32]);
+                } else {
+                    lh = L[n * r + j];
+                    rh = R[(int64_t)j * K + k];
+                }
+                d += lh * rh;
+            }
+            P[k] = (float)((double)W[n * K + k] - d);
+        }
+        lqo_quant_mxfp4(P, K, pc + n * K, pe + n * BK);
+        if (P_out) memcpy(P_out + n * K, P, sizeof(float) * (size_t)K);
+        free(P);
+    }
+}
+
+/* Outputs: xc M x K E2M1, xe M x K/32; xb8 M x K E4M3, xbe M x K/32; T M x r fp32 (the fp64
+   contraction rounded once); tq8 M x r E4M3, te M x r/32. */
+LQO_API void lqo_quantize_act_mxb(int64_t M, int64_t K, int r, const float *X, const uint8_t *r8,
+                                  const uint8_t *re, uint8_t *xc, uint8_t *xe, uint8_t *xb8,
+                                  uint8_t *xbe, float *T, uint8_t *tq8, uint8_t *te)
+{
+    const int64_t BK = K / 32;
+    const int BR = r / 32;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const float *x = X + m * K;
+        lqo_quant_mxfp4(x, K, xc + m * K, xe + m * BK);
+        if (r == 0) continue;
+        lqo_quant_mxfp8(x, K, xb8 + m * K, xbe + m * BK);
+        float *Trow = (float *)malloc(sizeof(float) * (size_t)r);
+        for (int j = 0; j < r; ++j) {
+            double a = 0.0;
+            for (int64_t b = 0; b < BK; ++b) {
+                double d = 0.0;
+                for (int k = 0; k < 32; ++k)
+                    d += (double)lqo_e4m3_decode(xb8[m * K + 32 * b + k]) *
+                         (double)lqo_e4m3_decode(r8[(int64_t)j * K + 32 * b + k]);
+                a += lqo_e8m0_decode(xbe[m * BK + b]) * lqo_e8m0_decode(re[(int64_t)j * BK + b]) * d;
+            }
+            Trow[j] = (float)a;
+        }
+        lqo_quant_mxfp8(Trow, r, tq8 + m * r, te + m * BR);
+        if (T) memcpy(T + m * r, Trow, sizeof(float) * (size_t)r);
+        free(Trow);
+    }
+}
+
+LQO_API void lqo_fwd_mxb(int64_t M, int64_t N, int64_t K, int r, const uint8_t *xc,
+                         const uint8_t *xe, const uint8_t *pc, const uint8_t *pe,
+                         const uint8_t *tq8, const uint8_t *te, const uint8_t *l8,
+                         const uint8_t *le, float *ymain, float *ybr, float *y32, uint16_t *Y)
+{
+    const int64_t B = K / 32;
+    const int BR = r / 32;
+    float *vw = (float *)malloc(sizeof(float) * (size_t)(N * K));
+    for (int64_t i = 0; i < N * K; ++i) vw[i] = lqo_e2m1_decode(pc[i]);
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        float *vx = (float *)malloc(sizeof(float) * (size_t)K);
+        for (int64_t k = 0; k < K; ++k) vx[k] = lqo_e2m1_decode(xc[m * K + k]);
+        for (int64_t n = 0; n < N; ++n) {
+            double t = 0.0;
+            for (int64_t b = 0; b < B; ++b) {
+                double d = 0.0;
+                for (int k = 0; k < 32; ++k)
+                    d += (double)vx[32 * b + k] * (double)vw[n * K + 32 * b + k];
+                t += lqo_e8m0_decode(xe[m * B + b]) * lqo_e8m0_decode(pe[n * B + b]) * d;
+            }
+            double u = 0.0;
+            for (int b = 0; b < BR; ++b) {
+                double d = 0.0;
+                for (int j = 0; j < 32; ++j)
+                    d += (double)lqo_e4m3_decode(tq8[m * r + 32 * b + j]) *
+                         (double)lqo_e4m3_decode(l8[n * r + 32 * b + j]);
+                u += lqo_e8m0_decode(te[m * BR + b]) * lqo_e8m0_decode(le[n * BR + b]) * d;
+            }
+            float y = (float)(t + u); /* sum node of Fig. 1: both accumulators, one rounding */
+            if (ymain) ymain[m * N + n] = (float)t;
+            if (ybr) ybr[m * N + n] = (float)u;
+            if (y32) y32[m * N + n] = y;
+            if (Y) Y[m * N + n] = bf16_rne(y);
+        }
+        free(vx);
+    }
+    free(vw);
 }
 
 LQO_API int lqo_num_threads(void)

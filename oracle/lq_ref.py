@@ -280,3 +280,81 @@ def fwd_mx(pk: PackedMx, act: ActMx) -> FwdOut:
                      _p(pk.pc), _p(pk.pe), _p(act.tq8), _p(act.st), _p(pk.l8), _p(pk.sl),
                      _p(out.ymain), _p(out.ybr), _p(out.y32), _p(out.Y))
     return out
+
+
+# ---------------------------------------------------------------------------------------
+# MXB family: MXFP4 main, MXFP8e4 (block-scaled E4M3) branch
+# ---------------------------------------------------------------------------------------
+
+def quant_mxfp8(v):
+    v = _f32(v).ravel()
+    assert v.size % 32 == 0
+    codes = np.empty(v.size, np.uint8)
+    e = np.empty(v.size // 32, np.uint8)
+    lib().lqo_quant_mxfp8(_p(v), C.c_int64(v.size), _p(codes), _p(e))
+    return codes, e
+
+
+@dataclass
+class PackedMxb:
+    N: int
+    K: int
+    r: int
+    pc: np.ndarray   # N x K uint8 E2M1 codes
+    pe: np.ndarray   # N x K/32 uint8 E8M0
+    l8: np.ndarray   # N x r uint8 E4M3
+    le: np.ndarray   # N x r/32 uint8 E8M0
+    r8: np.ndarray   # r x K uint8 E4M3
+    re: np.ndarray   # r x K/32 uint8 E8M0
+    P: np.ndarray
+
+
+def pack_mxb(W, L, R, residual_from_quantized: bool = True) -> PackedMxb:
+    W = _f32(W)
+    N, K = W.shape
+    r = 0 if L is None else int(np.shape(L)[1])
+    assert K % 32 == 0 and r % 32 == 0
+    Lc = _f32(L) if r else np.zeros((N, 0), np.float32)
+    Rc = _f32(R) if r else np.zeros((0, K), np.float32)
+    out = PackedMxb(N, K, r, np.empty((N, K), np.uint8), np.empty((N, K // 32), np.uint8),
+                    np.empty((N, r), np.uint8), np.empty((N, r // 32), np.uint8),
+                    np.empty((r, K), np.uint8), np.empty((r, K // 32), np.uint8), np.empty((N, K), np.float32))
+    lib().lqo_pack_mxb(C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(1 if residual_from_quantized else 0),
+                       _p(W), _p(Lc), _p(Rc), _p(out.pc), _p(out.pe), _p(out.l8), _p(out.le), _p(out.r8),
+                       _p(out.re), _p(out.P))
+    return out
+
+
+@dataclass
+class ActMxb:
+    M: int
+    xc: np.ndarray    # M x K uint8 E2M1
+    xe: np.ndarray    # M x K/32 uint8 E8M0
+    xb8: np.ndarray   # M x K uint8 E4M3
+    xbe: np.ndarray   # M x K/32 uint8 E8M0
+    T: np.ndarray     # M x r float32
+    tq8: np.ndarray   # M x r uint8 E4M3
+    te: np.ndarray    # M x r/32 uint8 E8M0
+
+
+def quantize_act_mxb(X, pk: PackedMxb) -> ActMxb:
+    X = _f32(X)
+    M, K = X.shape
+    r = pk.r
+    out = ActMxb(M, np.empty((M, K), np.uint8), np.empty((M, K // 32), np.uint8), np.zeros((M, K), np.uint8),
+                 np.zeros((M, K // 32), np.uint8), np.zeros((M, r), np.float32), np.zeros((M, r), np.uint8),
+                 np.zeros((M, r // 32), np.uint8))
+    lib().lqo_quantize_act_mxb(C.c_int64(M), C.c_int64(K), C.c_int(r), _p(X), _p(pk.r8), _p(pk.re),
+                               _p(out.xc), _p(out.xe), _p(out.xb8), _p(out.xbe), _p(out.T), _p(out.tq8),
+                               _p(out.te))
+    return out
+
+
+def fwd_mxb(pk: PackedMxb, act: ActMxb) -> FwdOut:
+    M, N, K, r = act.M, pk.N, pk.K, pk.r
+    out = FwdOut(None, None, np.empty((M, N), np.float32), np.empty((M, N), np.float32),
+                 np.empty((M, N), np.float32), np.empty((M, N), np.uint16))
+    lib().lqo_fwd_mxb(C.c_int64(M), C.c_int64(N), C.c_int64(K), C.c_int(r), _p(act.xc), _p(act.xe),
+                      _p(pk.pc), _p(pk.pe), _p(act.tq8), _p(act.te), _p(pk.l8), _p(pk.le),
+                      _p(out.ymain), _p(out.ybr), _p(out.y32), _p(out.Y))
+    return out

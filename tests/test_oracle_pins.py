@@ -535,6 +535,114 @@ def test_mx_rank0_and_residual(oracle):
     assert np.array_equal(oracle.e8m0_decode(pkg.pe), sc)   # floor(log2(6 s)) - 2 = log2 s
 
 
+# --------------------------------------------------------------------------------------
+# MXB family: block-scaled E4M3 branch (App. A.3 "MXFP8e4": blocks of 32, E8M0 scale)
+# --------------------------------------------------------------------------------------
+
+def test_mxfp8_block_scale_nearest_and_idempotent(oracle):
+    rng = np.random.default_rng(21)
+    v = (rng.standard_normal(32 * 60) * np.exp(rng.uniform(-8, 8, 32 * 60))).astype(np.float32)
+    v[96:128] = 0.0
+    v[128] = 0.75; v[129:160] = 0.0                      # a lone value fixes scale and code by hand
+    codes, e = oracle.quant_mxfp8(v)
+    assert e[3] == 0 and np.all(codes[96:128] & 0x7F == 0)
+    # 0.75 = 1.5 * 2^-1: floor(log2) = -1, E = -1 - 8 + 127; element = 0.75 * 2^9 = 384 = 1.5 * 2^8 -> e=15, m=4
+    assert e[4] == 118 and codes[128] == ((15 << 3) | 4)
+    dec_tab = oracle.e4m3_decode(np.arange(127, dtype=np.uint8)).astype(np.float64)
+    deq = oracle.e4m3_decode(codes).astype(np.float64).reshape(-1, 32)
+    sc = oracle.e8m0_decode(e)
+    vb = v.astype(np.float64).reshape(-1, 32)
+    for b in range(vb.shape[0]):
+        a = np.abs(vb[b]).max()
+        if a == 0:
+            continue
+        assert sc[b] == 2.0 ** (np.floor(np.log2(a)) - 8)          # exponent rule
+        u = vb[b] / sc[b]                                           # exact (power of two)
+        assert 256 <= np.abs(u).max() < 512
+        for ui, di in zip(u, deq[b]):                               # nearest representable, saturating at 448
+            best = np.min(np.abs(dec_tab - abs(ui)))
+            assert abs(abs(di) - abs(ui)) <= best and abs(di) <= 448
+            assert di == 0 or np.sign(di) == np.sign(ui)
+    # idempotence (Section 3.2): the block maximum stays in its binade, so codes and scales repeat
+    back = (deq * sc[:, None]).astype(np.float32).ravel()
+    codes2, e2 = oracle.quant_mxfp8(back)
+    nz = np.repeat(np.abs(vb).max(axis=1) > 0, 32)
+    assert np.array_equal(e2[np.abs(vb).max(axis=1) > 0], e[np.abs(vb).max(axis=1) > 0])
+    assert np.array_equal(oracle.e4m3_decode(codes2)[nz], oracle.e4m3_decode(codes)[nz])
+    # scaling by a power of two moves only the scale byte
+    codes3, e3 = oracle.quant_mxfp8(v * np.float32(2.0 ** 5))
+    assert np.array_equal(codes3[nz], codes[nz]) and np.array_equal(e3[e > 0].astype(int), e[e > 0].astype(int) + 5)
+
+
+def test_mxb_forward_against_exact_rationals(oracle):
+    rng = np.random.default_rng(22)
+    M, K, N, r = 4, 64, 5, 32
+    X = wl.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    L = (rng.standard_normal((N, r)) * 3e-2).astype(np.float32)
+    R = (rng.standard_normal((r, K)) * 3e-2).astype(np.float32)
+    pk = oracle.pack_mxb(W, L, R)
+    act = oracle.quantize_act_mxb(X, pk)
+    out = oracle.fwd_mxb(pk, act)
+    F = Fraction
+    f = lambda a: F(float(a))
+    vx, vw = oracle.e2m1_decode(act.xc), oracle.e2m1_decode(pk.pc)
+    sx, sw = oracle.e8m0_decode(act.xe), oracle.e8m0_decode(pk.pe)
+    x8, r8, t8, l8 = (oracle.e4m3_decode(c) for c in (act.xb8, pk.r8, act.tq8, pk.l8))
+    xbe, re, te, le = (oracle.e8m0_decode(c) for c in (act.xbe, pk.re, act.te, pk.le))
+    # residual: P = fl(W - sum_j Lhat Rhat) from the dequantised factors (Fig. 1), exact in rationals
+    for n in range(N):
+        for k in range(0, K, 7):
+            d = sum(f(l8[n, j]) * f(le[n, j // 32]) * f(r8[j, k]) * f(re[j, k // 32]) for j in range(r))
+            assert pk.P[n, k] == np.float32(float(f(W[n, k]) - d))
+    # the factors' codes are the block quantiser applied to their rows
+    c, e = oracle.quant_mxfp8(R[3]); assert np.array_equal(c, pk.r8[3]) and np.array_equal(e, pk.re[3])
+    c, e = oracle.quant_mxfp8(L[2]); assert np.array_equal(c, pk.l8[2]) and np.array_equal(e, pk.le[2])
+    c, e = oracle.quant_mxfp8(X[1]); assert np.array_equal(c, act.xb8[1]) and np.array_equal(e, act.xbe[1])
+    for m in range(M):
+        Tex = []
+        for j in range(r):
+            T = sum(f(xbe[m, b]) * f(re[j, b]) * sum(f(x8[m, 32 * b + k]) * f(r8[j, 32 * b + k]) for k in range(32))
+                    for b in range(K // 32))
+            assert act.T[m, j] == np.float32(float(T))               # one rounding of the exact contraction
+            Tex.append(T)
+        c, e = oracle.quant_mxfp8(act.T[m]); assert np.array_equal(c, act.tq8[m]) and np.array_equal(e, act.te[m])
+        for n in range(N):
+            main = sum(f(sx[m, b]) * f(sw[n, b]) * sum(f(vx[m, 32 * b + k]) * f(vw[n, 32 * b + k]) for k in range(32))
+                       for b in range(K // 32))
+            br = sum(f(te[m, b]) * f(le[n, b]) * sum(f(t8[m, 32 * b + j]) * f(l8[n, 32 * b + j]) for j in range(32))
+                     for b in range(r // 32))
+            assert out.ymain[m, n] == np.float32(float(main)) and out.ybr[m, n] == np.float32(float(br))
+            assert out.y32[m, n] == np.float32(float(main + br))     # both accumulators, one rounding
+            assert out.Y[m, n] == oracle.bf16_rne(float(out.y32[m, n]))
+    # the branch approximates X R^T L^T: block-FP8 relative error 2^-4 per factor
+    ref = X.astype(np.float64) @ R.astype(np.float64).T @ L.astype(np.float64).T
+    assert np.abs(out.ybr - ref).max() <= 0.2 * np.abs(ref).max()
+
+
+def test_mxb_rank0_equals_mx_rank0_and_grid_factors_are_exact(oracle):
+    rng = np.random.default_rng(23)
+    M, K, N, r = 4, 96, 6, 32
+    X = wl.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    pa, pb = oracle.pack_mx(W, None, None), oracle.pack_mxb(W, None, None)
+    assert np.array_equal(pa.pc, pb.pc) and np.array_equal(pa.pe, pb.pe)
+    ya = oracle.fwd_mx(pa, oracle.quantize_act_mx(X, pa))
+    yb = oracle.fwd_mxb(pb, oracle.quantize_act_mxb(X, pb))
+    assert np.array_equal(ya.Y, yb.Y) and np.array_equal(ya.y32, yb.y32)
+    pz = oracle.pack_mxb(W, np.zeros((N, r), np.float32), np.zeros((r, K), np.float32))
+    yz = oracle.fwd_mxb(pz, oracle.quantize_act_mxb(X, pz))
+    assert np.array_equal(yz.Y, yb.Y) and not yz.ybr.any()
+    # factors that already lie on the MXFP8e4 grid are stored without loss (Section 3.2 fixed point)
+    cod = rng.integers(0, 127, size=(r, K)).astype(np.uint8) | (rng.integers(0, 2, size=(r, K)).astype(np.uint8) << 7)
+    cod.reshape(r, -1, 32)[:, :, 0] = 126                      # 448 in every block fixes the scale
+    sc = 2.0 ** rng.integers(-12, -6, size=(r, K // 32))
+    Rg = (oracle.e4m3_decode(cod).astype(np.float64).reshape(r, -1, 32) * sc[:, :, None]).reshape(r, K).astype(np.float32)
+    pg = oracle.pack_mxb(W, np.zeros((N, r), np.float32), Rg)
+    back = oracle.e4m3_decode(pg.r8).astype(np.float64).reshape(r, -1, 32) * oracle.e8m0_decode(pg.re)[:, :, None]
+    assert np.array_equal(back.reshape(r, K).astype(np.float32), Rg)
+
+
 def test_workload_generator_is_seeded():
     l = wl.shrink(wl.LAYERS["c2_qkv"], M=16, K=128, N=64, r=16)
     a, b = wl.make_inputs(l), wl.make_inputs(l)
