@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 # MI355X dense matrix peaks: FP8 / INT8 (the INT4 main product runs on the FP8 pipe) and FP4 (MXFP4)
-PEAK_MFMA_TFLOPS = {"int": 5033.0, "mx": 10066.0}
+PEAK_MFMA_TFLOPS = {"int": 5033.0, "mx": 10066.0, "mxb": 10066.0}
 # HBM bytes per forward launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/fwd_int_kernel_c2_qkv.md,
 # profiles/mx_fwd_kernel_c5_qkv.md),
 # each scaled by the factor a plain copy of known size gives (2.0 for FETCH_SIZE, 1.0 for WRITE_SIZE).
@@ -136,13 +136,14 @@ def main():
     act_bytes = layer.M * layer.K * (xb + 0.5) + layer.M * (layer.r + 8)
     act_gbs = act_bytes / (act_ms * 1e-3) / 1e9
 
-    mx = layer.family == "mx"
+    mx = layer.family in ("mx", "mxb")
+    mxb = layer.family == "mxb"
     peak = PEAK_MFMA_TFLOPS[layer.family]
     # algorithmic HBM bytes of the forward launch: 4-bit codes of both operands and their scales, the
     # rank-r operands, per-token / per-channel scales in, bf16 Y out
     rp = 0 if layer.r == 0 else (-(-layer.r // 64) * 64 if mx else -(-layer.r // 32) * 32)
     if mx:
-        scale_bytes = (layer.M + layer.N) * (layer.K // 32) + 4 * (layer.M + layer.N)
+        scale_bytes = (layer.M + layer.N) * (layer.K // 32) + (rp // 32 if mxb else 4) * (layer.M + layer.N)
     else:
         scale_bytes = 4 * layer.N * (layer.K // layer.g) + 4 * (2 * layer.M + layer.N)
     fwd_bytes = (layer.M + layer.N) * layer.K / 2 + scale_bytes + (layer.M + layer.N) * rp + 2.0 * layer.M * layer.N
@@ -158,7 +159,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": layer.name, "M": layer.M, "K": layer.K, "N": layer.N, "rank": layer.r,
                    "main": "W4A4 MXFP4 block 32" if mx else f"W4A4 INT4 g{layer.g}",
-                   "branch": "W8A8 FP8 E4M3" if mx else f"W{layer.br_w_bits}A{layer.br_a_bits}",
+                   "branch": "W8A8 MXFP8e4 block 32" if mxb else "W8A8 FP8 E4M3" if mx else f"W{layer.br_w_bits}A{layer.br_a_bits}",
                    "x_dtype": layer.x_dtype, "buffer_sets": nsets,
                    "arithmetic": ("e2m1 x e8m0 on the scaled FP4 MFMA, e4m3 branch, fp32 accumulate" if mx else
                                   "int4 codes (exact, on the FP8 MFMA pipe), int8 branch, fp32 dequantisation")},
@@ -181,7 +182,10 @@ def main():
     # ---- CPU oracle leg (reported baseline only): bounded row sample of the same workload -----
     if args.oracle_seconds > 0:
         from oracle import lq_ref
-        if mx:
+        if mxb:
+            pk = lq_ref.pack_mxb(W, L, R)
+            run_rows = lambda n_rows: lq_ref.fwd_mxb(pk, lq_ref.quantize_act_mxb(X[:n_rows], pk))
+        elif mx:
             pk = lq_ref.pack_mx(W, L, R)
             run_rows = lambda n_rows: lq_ref.fwd_mx(pk, lq_ref.quantize_act_mx(X[:n_rows], pk))
         else:

@@ -17,7 +17,10 @@
  *         scale per token (activations, intermediate) or per row of L / R (weights).
  *         Integer accumulation, fp32 dequantisation.
  *   MX  : Q1 = MXFP4 (E2M1 elements, blocks of 32 along K, E8M0 scale, App. A.3) for both
- *         operands; Q2 = FP8 E4M3 with one fp32 scale per token / per row.
+ *         operands; Q2 = FP8 E4M3 with one fp32 scale per token / per row, or (all-MX setting of
+ *         the mixed-precision tables, Section 4.3) MXFP8e4: E4M3 elements in blocks of 32 along
+ *         the contraction axis (K for X and R, the rank for X R^T and L) with E8M0 scales; then
+ *         no fp32 scale exists and the branch accumulates into the main product's accumulator.
  *
  * General rules
  *   - Every pointer named "device" is GPU memory of the current HIP device, owned by the
@@ -28,7 +31,8 @@
  *     return value; a failed launch returns LQ_ERR_DEVICE.  Nothing throws.
  *   - Inputs must be finite (NaN / Inf give undefined codes).
  *   - Shape contract: K % 64 == 0, K % main_w_group == 0, N % 64 == 0,
- *     rank in {0,16,32,64,128}, 1 <= M, row strides >= row lengths.
+ *     rank in {0,16,32,64,128} ({0,32,64,128} with an MXFP8e4 branch), 1 <= M,
+ *     row strides >= row lengths; MX family: K % 128 == 0.
  *   - Calls are deterministic: no atomics, no split-K; repeated calls give identical bits.
  */
 #ifndef LQ_H
@@ -56,7 +60,8 @@ typedef enum {
     LQ_INT6 = 1,
     LQ_INT8 = 2,
     LQ_MXFP4_E2M1 = 3,
-    LQ_FP8_E4M3 = 4
+    LQ_FP8_E4M3 = 4,     /* E4M3 elements, one fp32 scale per token / per row                    */
+    LQ_MXFP8_E4M3 = 5    /* "MXFP8e4" (App. A.3): E4M3 elements, blocks of 32, E8M0 scale         */
 } lq_fmt;
 
 typedef enum { LQ_F32 = 0, LQ_BF16 = 1 } lq_dtype;
@@ -70,8 +75,8 @@ typedef struct {
     int32_t main_a;                  /* lq_fmt: must equal main_w                                 */
     int32_t main_w_group;            /* INT: 64 | 128 values along K per weight scale; MX: 32    */
     int32_t main_a_group;            /* INT: 0 = one scale per token; MX: 32                     */
-    int32_t br_w;                    /* lq_fmt of Q2(L), Q2(R): INT8|INT6|INT4, or FP8 (MX)      */
-    int32_t br_a;                    /* lq_fmt of Q2(X), Q2(X R^T): INT8|INT6, or FP8 (MX)       */
+    int32_t br_w;                    /* lq_fmt of Q2(L), Q2(R): INT8|INT6|INT4; MX: FP8 | MXFP8  */
+    int32_t br_a;                    /* lq_fmt of Q2(X), Q2(X R^T): INT8|INT6; MX: = br_w        */
     int32_t residual_from_quantized; /* 1: P = W - deq(Q2 L) deq(Q2 R) (Fig. 1); 0: P = W - L R  */
     int32_t x_dtype;                 /* lq_dtype of X                                             */
     int32_t reserved;                /* must be 0                                                 */
@@ -80,9 +85,10 @@ typedef struct {
 /* Optional parity taps.  Every member may be NULL.  Device pointers, plain row-major. */
 typedef struct {
     int8_t  *xb;    /* M x K   branch activation codes (INT) / E4M3 bytes (MX)                  */
-    float   *sxb;   /* M       branch activation scales                                        */
+    float   *sxb;   /* M       branch activation scales (not with an MXFP8e4 branch)           */
     int32_t *accT;  /* M x r   integer accumulators of Q2(X) Q2(R)^T (INT only)                 */
     float   *T;     /* M x r   dequantised intermediate before re-quantisation                  */
+    uint8_t *xbe;   /* M x K/32  E8M0 bytes of the branch activation blocks (MXFP8e4 branch)    */
 } lq_act_debug;
 
 typedef struct {
@@ -102,6 +108,8 @@ typedef struct {
     float   *sl;    /* N                                                                       */
     int8_t  *rq;    /* r x K                                                                   */
     float   *sr;    /* r                                                                       */
+    uint8_t *le;    /* N x r/32   E8M0 bytes of L's blocks (MXFP8e4 branch; then sl, sr unused) */
+    uint8_t *re;    /* r x K/32   E8M0 bytes of R's blocks (MXFP8e4 branch)                     */
 } lq_weights_view;
 
 typedef struct {
@@ -110,6 +118,7 @@ typedef struct {
     uint8_t *xe;    /* M x (K / 32)               (MX)                                         */
     int8_t  *tq;    /* M x r                                                                   */
     float   *st;    /* M                                                                       */
+    uint8_t *te;    /* M x r/32   E8M0 bytes of the intermediate's blocks (MXFP8e4 branch)      */
 } lq_act_view;
 
 const char *lq_status_string(lq_status s);

@@ -21,7 +21,7 @@ _lib = C.CDLL(_LIB_PATH)
 
 LQ_OK = 0
 LQ_ERR_NULL, LQ_ERR_SHAPE, LQ_ERR_UNSUPPORTED, LQ_ERR_ALIGN, LQ_ERR_BUFFER_TOO_SMALL, LQ_ERR_DEVICE = range(1, 7)
-LQ_INT4, LQ_INT6, LQ_INT8, LQ_MXFP4_E2M1, LQ_FP8_E4M3 = range(5)
+LQ_INT4, LQ_INT6, LQ_INT8, LQ_MXFP4_E2M1, LQ_FP8_E4M3, LQ_MXFP8_E4M3 = range(6)
 LQ_F32, LQ_BF16 = 0, 1
 _INT_FMT = {4: LQ_INT4, 6: LQ_INT6, 8: LQ_INT8}
 
@@ -34,7 +34,8 @@ class lq_config(C.Structure):
 
 
 class lq_act_debug(C.Structure):
-    _fields_ = [("xb", C.c_void_p), ("sxb", C.c_void_p), ("accT", C.c_void_p), ("T", C.c_void_p)]
+    _fields_ = [("xb", C.c_void_p), ("sxb", C.c_void_p), ("accT", C.c_void_p), ("T", C.c_void_p),
+                ("xbe", C.c_void_p)]
 
 
 class lq_fwd_debug(C.Structure):
@@ -43,12 +44,12 @@ class lq_fwd_debug(C.Structure):
 
 class lq_weights_view(C.Structure):
     _fields_ = [("pq", C.c_void_p), ("sw", C.c_void_p), ("pe", C.c_void_p), ("lq", C.c_void_p),
-                ("sl", C.c_void_p), ("rq", C.c_void_p), ("sr", C.c_void_p)]
+                ("sl", C.c_void_p), ("rq", C.c_void_p), ("sr", C.c_void_p), ("le", C.c_void_p), ("re", C.c_void_p)]
 
 
 class lq_act_view(C.Structure):
     _fields_ = [("xq", C.c_void_p), ("sx", C.c_void_p), ("xe", C.c_void_p), ("tq", C.c_void_p),
-                ("st", C.c_void_p)]
+                ("st", C.c_void_p), ("te", C.c_void_p)]
 
 
 EXPORTS = ["lq_status_string", "lq_packed_sizes", "lq_pack_weights", "lq_act_sizes", "lq_quantize_act",
@@ -93,8 +94,9 @@ def make_config(N: int, K: int, rank: int, family: str = "int", group: int = 64,
     if family == "int":
         return lq_config(N, K, rank, LQ_INT4, LQ_INT4, group, 0, _INT_FMT[br_w_bits], _INT_FMT[br_a_bits],
                          1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32, 0)
-    if family == "mx":
-        return lq_config(N, K, rank, LQ_MXFP4_E2M1, LQ_MXFP4_E2M1, 32, 32, LQ_FP8_E4M3, LQ_FP8_E4M3,
+    if family in ("mx", "mxb"):  # "mxb": MXFP8e4 (block-scaled E4M3) branch instead of fp32-scaled E4M3
+        br = LQ_MXFP8_E4M3 if family == "mxb" else LQ_FP8_E4M3
+        return lq_config(N, K, rank, LQ_MXFP4_E2M1, LQ_MXFP4_E2M1, 32, 32, br, br,
                          1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32, 0)
     raise ValueError(family)
 
@@ -143,6 +145,7 @@ class ActDebug:
     sxb: torch.Tensor
     accT: torch.Tensor
     T: torch.Tensor
+    xbe: Optional[torch.Tensor] = None
 
 
 def lq_quantize_act(cfg: lq_config, packed: torch.Tensor, X: torch.Tensor, act: Optional[torch.Tensor] = None,
@@ -161,8 +164,10 @@ def lq_quantize_act(cfg: lq_config, packed: torch.Tensor, X: torch.Tensor, act: 
         taps = ActDebug(torch.zeros((M, cfg.K), dtype=torch.int8, device=X.device),
                         torch.zeros(M, dtype=torch.float32, device=X.device),
                         torch.zeros((M, r), dtype=torch.int32, device=X.device),
-                        torch.zeros((M, r), dtype=torch.float32, device=X.device))
-        dbg = lq_act_debug(taps.xb.data_ptr(), taps.sxb.data_ptr(), taps.accT.data_ptr(), taps.T.data_ptr())
+                        torch.zeros((M, r), dtype=torch.float32, device=X.device),
+                        torch.zeros((M, cfg.K // 32), dtype=torch.uint8, device=X.device))
+        dbg = lq_act_debug(taps.xb.data_ptr(), taps.sxb.data_ptr(), taps.accT.data_ptr(), taps.T.data_ptr(),
+                           taps.xbe.data_ptr())
     _check(_lib.lq_quantize_act(C.byref(cfg), _ptr(packed), _ptr(X), M, X.stride(0), _ptr(act), act.numel(),
                                 C.byref(dbg) if dbg is not None else None, C.c_void_p(_stream())),
            "lq_quantize_act")
@@ -205,6 +210,8 @@ class WeightsView:
     sl: torch.Tensor
     rq: torch.Tensor
     sr: torch.Tensor
+    le: Optional[torch.Tensor] = None
+    re: Optional[torch.Tensor] = None
 
 
 def lq_unpack_weights(cfg: lq_config, packed: torch.Tensor) -> WeightsView:
@@ -217,10 +224,12 @@ def lq_unpack_weights(cfg: lq_config, packed: torch.Tensor) -> WeightsView:
                     torch.zeros((N, max(r, 1)), dtype=torch.int8, device=dev),
                     torch.zeros(N, dtype=torch.float32, device=dev),
                     torch.zeros((max(r, 1), K), dtype=torch.int8, device=dev),
-                    torch.zeros(max(r, 1), dtype=torch.float32, device=dev))
+                    torch.zeros(max(r, 1), dtype=torch.float32, device=dev),
+                    torch.zeros((N, max(r // 32, 1)), dtype=torch.uint8, device=dev),
+                    torch.zeros((max(r, 1), K // 32), dtype=torch.uint8, device=dev))
     view = lq_weights_view(v.pq.data_ptr(), v.sw.data_ptr() if v.sw is not None else None,
                            v.pe.data_ptr() if v.pe is not None else None, v.lq.data_ptr(), v.sl.data_ptr(),
-                           v.rq.data_ptr(), v.sr.data_ptr())
+                           v.rq.data_ptr(), v.sr.data_ptr(), v.le.data_ptr(), v.re.data_ptr())
     _check(_lib.lq_unpack_weights(C.byref(cfg), _ptr(packed), C.byref(view), C.c_void_p(_stream())),
            "lq_unpack_weights")
     return v
@@ -233,6 +242,7 @@ class ActView:
     xe: Optional[torch.Tensor]
     tq: torch.Tensor
     st: torch.Tensor
+    te: Optional[torch.Tensor] = None
 
 
 def lq_unpack_act(cfg: lq_config, act: torch.Tensor, M: int) -> ActView:
@@ -243,8 +253,10 @@ def lq_unpack_act(cfg: lq_config, act: torch.Tensor, M: int) -> ActView:
                 None if mx else torch.zeros(M, dtype=torch.float32, device=dev),
                 torch.zeros((M, K // 32), dtype=torch.uint8, device=dev) if mx else None,
                 torch.zeros((M, max(r, 1)), dtype=torch.int8, device=dev),
-                torch.zeros(M, dtype=torch.float32, device=dev))
+                torch.zeros(M, dtype=torch.float32, device=dev),
+                torch.zeros((M, max(r // 32, 1)), dtype=torch.uint8, device=dev))
     view = lq_act_view(v.xq.data_ptr(), v.sx.data_ptr() if v.sx is not None else None,
-                       v.xe.data_ptr() if v.xe is not None else None, v.tq.data_ptr(), v.st.data_ptr())
+                       v.xe.data_ptr() if v.xe is not None else None, v.tq.data_ptr(), v.st.data_ptr(),
+                       v.te.data_ptr())
     _check(_lib.lq_unpack_act(C.byref(cfg), _ptr(act), M, C.byref(view), C.c_void_p(_stream())), "lq_unpack_act")
     return v

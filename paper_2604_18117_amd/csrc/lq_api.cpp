@@ -39,14 +39,17 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         const int qw = int_qmax(cfg->br_w), qa = int_qmax(cfg->br_a);
         if (qw == 0 || qa == 0 || cfg->br_a == LQ_INT4) return LQ_ERR_UNSUPPORTED;
         d->mx = false;
+        d->mxb = false;
         d->g = cfg->main_w_group;
         d->qmax_bw = qw;
         d->qmax_ba = qa;
     } else if (cfg->main_w == LQ_MXFP4_E2M1) {
         if (cfg->main_a != LQ_MXFP4_E2M1) return LQ_ERR_UNSUPPORTED;
         if (cfg->main_w_group != 32 || cfg->main_a_group != 32) return LQ_ERR_SHAPE;
-        if (cfg->br_w != LQ_FP8_E4M3 || cfg->br_a != LQ_FP8_E4M3) return LQ_ERR_UNSUPPORTED;
+        if (cfg->br_w != cfg->br_a || (cfg->br_w != LQ_FP8_E4M3 && cfg->br_w != LQ_MXFP8_E4M3)) return LQ_ERR_UNSUPPORTED;
         if (cfg->K % 128 != 0) return LQ_ERR_SHAPE;  // the MX forward stages K in steps of 128
+        d->mxb = cfg->br_w == LQ_MXFP8_E4M3;
+        if (d->mxb && r % 32 != 0) return LQ_ERR_SHAPE;  // whole blocks of 32 along the rank
         d->mx = true;
         d->g = 32;
         d->qmax_bw = d->qmax_ba = 0;
@@ -69,11 +72,11 @@ PackedLayout packed_layout(const Dims& d)
     pl.off_lq = o;
     o = align256(o + (size_t)d.N * d.rp);
     pl.off_sl = o;
-    o = align256(o + (size_t)d.N * 4);
+    o = align256(o + (size_t)d.N * (d.mxb ? 8 : 4));  // fp32 per channel, or a scale dword per (channel, rank half)
     pl.off_rq = o;
     o = align256(o + (size_t)d.r * d.K);
     pl.off_sr = o;
-    o = align256(o + (size_t)(d.r > 0 ? d.r : 1) * 4);
+    o = align256(o + (d.mxb ? (size_t)(d.K / 128) * (d.r / 16) * 256 + 4 : (size_t)(d.r > 0 ? d.r : 1) * 4));
     pl.total = o;
     return pl;
 }
@@ -90,7 +93,7 @@ ActLayout act_layout(const Dims& d, int64_t M)
     al.off_tq = o;
     o = align256(o + (size_t)al.Mp * d.rp);
     al.off_st = o;
-    o = align256(o + (size_t)al.Mp * 4);
+    o = align256(o + (size_t)al.Mp * (d.mxb ? 8 : 4));
     al.total = o;
     return al;
 }

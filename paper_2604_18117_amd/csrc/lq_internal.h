@@ -32,6 +32,17 @@ namespace lq {
 // so that a lane's scale operand for four consecutive chunks is one dword and the instruction's
 // op_sel picks the chunk's byte (padding bytes hold 127 = 2^0).  Branch codes are E4M3 bytes;
 // lq / tq rows are zero-padded to a multiple of 64.
+//
+// MX family with an MXFP8e4 branch (E4M3 elements, blocks of 32 along the contraction axis, E8M0
+// scales; no fp32 scales): with 8-bit operands the scaled MFMA gives a lane 16 bytes of each of two
+// 32-blocks, and lane (row, h) supplies the scale of block h:
+//     v_mfma_scale_f32_32x32x64 : lane (row, h): bytes 0..15 = k 16h..16h+15, bytes 16..31 = k 32+16h..
+//     v_mfma_scale_f32_16x16x128: lane (row, q): bytes 0..15 = k 16q..16q+15, bytes 16..31 = k 64+16q..;
+//                                 lane (row, q) supplies the scale of block q
+// lq / tq : [block of 32 rows][64-chunk of the rank][lane][32 bytes] (mxb_frag8_offset); le / te (in the
+// sl / st sections): one dword per (row block, lane), byte cc = scale of rank block 2*cc + h.
+// rq : [128-chunk of K][rank/16][lane][32 bytes] (mxb_rq_offset); re (in the sr section): one dword
+// per (chunk, rank/16, lane), byte 0 = scale of K block 4*chunk + q.
 // ---------------------------------------------------------------------------------------
 
 struct Dims {
@@ -42,6 +53,7 @@ struct Dims {
     int G;        // K / g
     int C64;      // K / 64
     bool mx;      // MX family
+    bool mxb;     // MX family with a block-scaled (MXFP8e4) branch
     int qmax_bw;  // INT branch weight qmax
     int qmax_ba;  // INT branch activation qmax
 };

@@ -84,6 +84,38 @@ __device__ __forceinline__ void fp8_scales(float amax, float* s, float* inv)
         *inv = 448.0f / amax;
     }
 }
+// ---- MXFP8e4 branch (block-scaled E4M3): operand layouts of the 8-bit scaled MFMA forms ----
+__device__ __forceinline__ size_t mxb_frag8_offset(int row, int j, int rp)  // byte (row, rank index j) of lq / tq
+{
+    const int blk = row >> 5, cc = j >> 6, jj = j & 63;
+    const int h = (jj & 31) >> 4, byte = (jj & 15) + ((jj >> 5) << 4);
+    return ((size_t)((size_t)blk * (rp >> 6) + cc) * 64 + (row & 31) + 32 * h) * 32 + byte;
+}
+__device__ __forceinline__ size_t mxb_scale_offset(int row, int rb)  // scale byte (row, rank block rb) of le / te
+{
+    return ((size_t)(row >> 5) * 64 + (row & 31) + 32 * (rb & 1)) * 4 + (rb >> 1);
+}
+__device__ __forceinline__ size_t mxb_rq_offset(int j, int k, int r)  // byte (rank row j, k) of rq
+{
+    const int c = k >> 7, kk = k & 127;
+    const int q = (kk & 63) >> 4, byte = (kk & 15) + ((kk >> 6) << 4);
+    return ((size_t)((size_t)c * (r >> 4) + (j >> 4)) * 64 + (j & 15) + 16 * q) * 32 + byte;
+}
+__device__ __forceinline__ size_t mxb_re_offset(int j, int kb, int r)  // scale dword (rank row j, K block kb) of re
+{
+    return ((size_t)((size_t)(kb >> 2) * (r >> 4) + (j >> 4)) * 64 + (j & 15) + 16 * (kb & 3)) * 4;
+}
+__device__ __forceinline__ uint32_t e8m0_of_fp8(float amax)  // floor(log2 amax) - 8 + 127, clamped at 0
+{
+    const int e = (int)((__float_as_uint(amax) >> 23) & 0xFFu) - 8;
+    return (amax == 0.0f || e < 0) ? 0u : (uint32_t)e;
+}
+__device__ __forceinline__ float e8m0_inverse(uint32_t E)  // 2^(127-E), exact (E <= 253)
+{
+    return __uint_as_float((254u - E) << 23);
+}
+__device__ __forceinline__ double e8m0_double(uint32_t E) { return __builtin_ldexp(1.0, (int)E - 127); }
+
 __device__ __forceinline__ float wmax64(float v)
 {
 #pragma unroll
@@ -129,7 +161,35 @@ __global__ __launch_bounds__(256) void mx_pack_l_kernel(const float* L, int N, i
         l8[(size_t)n * rp + j] = (j < r) ? (uint8_t)fp8_byte(__fmul_rn(L[(size_t)n * r + j], inv)) : (uint8_t)0;
 }
 
-// one wavefront per (n, 64-chunk): lane = k % 64, two blocks of 32
+// MXFP8e4 factors: one thread per (row, block of 32).  mode 0: rows of R, blocks along K, into the
+// activation kernel's operand order; mode 1: rows of L, blocks along the rank, into the forward's.
+__global__ __launch_bounds__(256) void mxb_pack_rows_kernel(const float* A, int rows, int len, int mode, int r, int rp,
+                                                            uint8_t* codes, uint8_t* scales)
+{
+    const int nb = len >> 5;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)rows * nb) return;
+    const int row = (int)(idx / nb), b = (int)(idx % nb);
+    const float* v = A + (size_t)row * len + 32 * b;
+    float a = 0.f;
+    for (int i = 0; i < 32; ++i) a = fmaxf(a, fabsf(v[i]));
+    const uint32_t E = e8m0_of_fp8(a);
+    const float inv = e8m0_inverse(E);
+    for (int i = 0; i < 32; ++i) {
+        const uint8_t c = (uint8_t)fp8_byte(__fmul_rn(v[i], inv));
+        if (mode == 0)
+            codes[mxb_rq_offset(row, 32 * b + i, r)] = c;
+        else
+            codes[mxb_frag8_offset(row, 32 * b + i, rp)] = c;
+    }
+    if (mode == 0)
+        *(uint32_t*)(scales + mxb_re_offset(row, b, r)) = 0x7F7F7F00u | E;
+    else
+        scales[mxb_scale_offset(row, b)] = (uint8_t)E;
+}
+
+// one wavefront per (n, 64-chunk): lane = k % 64, two blocks of 32.  from_q: 0 = unquantised factors,
+// 1 = E4M3 codes with fp32 row scales, 2 = MXFP8e4 codes with E8M0 block scales (sl, sr hold le, re).
 __global__ __launch_bounds__(256) void mx_pack_p_kernel(const float* W, const float* L, const float* R, int N, int K,
                                                         int r, int rp, int from_q, const uint8_t* l8, const float* sl,
                                                         const uint8_t* r8, const float* sr, uint8_t* pc, uint8_t* pe)
@@ -142,6 +202,14 @@ __global__ __launch_bounds__(256) void mx_pack_p_kernel(const float* W, const fl
     const int k = c * 64 + lane;
     double d = 0.0;
     for (int j = 0; j < r; ++j) {
+        if (from_q == 2) {  // element * 2^e is exact in fp64, and so is the product of two of them
+            const uint8_t* le = (const uint8_t*)sl;
+            const uint8_t* re = (const uint8_t*)sr;
+            const double lh = (double)fp8_value(l8[mxb_frag8_offset(n, j, rp)]) * e8m0_double(le[mxb_scale_offset(n, j >> 5)]);
+            const double rh = (double)fp8_value(r8[mxb_rq_offset(j, k, r)]) * e8m0_double(re[mxb_re_offset(j, k >> 5, r)]);
+            d = fma(lh, rh, d);
+            continue;
+        }
         float lh, rh;
         if (from_q) {
             lh = __fmul_rn(fp8_value(l8[(size_t)n * rp + j]), sl[n]);
@@ -179,12 +247,24 @@ hipError_t launch_pack_mx(const Dims& d, int from_q, const float* W, const float
     const size_t pe_bytes = (size_t)(N / 32) * ((d.C64 + 3) / 4) * 256;
     hipLaunchKernelGGL(mx_fill_kernel, dim3((unsigned)((pe_bytes + 255) / 256)), dim3(256), 0, s, packed + pl.off_sw,
                        pe_bytes, (uint8_t)127);
-    if (d.r > 0) hipLaunchKernelGGL(mx_pack_r_kernel, dim3(d.r), dim3(256), 0, s, R, K, d.r, r8, sr);
-    hipLaunchKernelGGL(mx_pack_l_kernel, dim3((N + 255) / 256), dim3(256), 0, s, d.r > 0 ? L : (const float*)nullptr, N,
-                       d.r, d.rp, l8, sl);
+    if (d.mxb) {
+        // padding of the rank to 64: zero codes, scale 2^0
+        const size_t lq_bytes = (size_t)N * d.rp, le_bytes = (size_t)N * 8;
+        if (lq_bytes) hipLaunchKernelGGL(mx_fill_kernel, dim3((unsigned)((lq_bytes + 255) / 256)), dim3(256), 0, s, l8, lq_bytes, (uint8_t)0);
+        hipLaunchKernelGGL(mx_fill_kernel, dim3((unsigned)((le_bytes + 255) / 256)), dim3(256), 0, s, (uint8_t*)sl, le_bytes, (uint8_t)127);
+        if (d.r > 0) {
+            const size_t nr = (size_t)d.r * (K / 32), nl = (size_t)N * (d.r / 32);
+            hipLaunchKernelGGL(mxb_pack_rows_kernel, dim3((unsigned)((nr + 255) / 256)), dim3(256), 0, s, R, d.r, K, 0, d.r, d.rp, r8, (uint8_t*)sr);
+            hipLaunchKernelGGL(mxb_pack_rows_kernel, dim3((unsigned)((nl + 255) / 256)), dim3(256), 0, s, L, N, d.r, 1, d.r, d.rp, l8, (uint8_t*)sl);
+        }
+    } else {
+        if (d.r > 0) hipLaunchKernelGGL(mx_pack_r_kernel, dim3(d.r), dim3(256), 0, s, R, K, d.r, r8, sr);
+        hipLaunchKernelGGL(mx_pack_l_kernel, dim3((N + 255) / 256), dim3(256), 0, s, d.r > 0 ? L : (const float*)nullptr, N,
+                           d.r, d.rp, l8, sl);
+    }
     const size_t waves = (size_t)N * d.C64;
     hipLaunchKernelGGL(mx_pack_p_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, W, L, R, N, K, d.r, d.rp,
-                       from_q, l8, sl, r8, sr, packed + pl.off_pq, packed + pl.off_sw);
+                       (from_q && d.mxb) ? 2 : from_q, l8, sl, r8, sr, packed + pl.off_pq, packed + pl.off_sw);
     return hipGetLastError();
 }
 
@@ -192,7 +272,7 @@ hipError_t launch_pack_mx(const Dims& d, int from_q, const float* W, const float
 // plain views
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void mx_unpack_w_kernel(const uint8_t* packed, PackedLayout pl, int N, int K, int r,
-                                                          int rp, lq_weights_view out)
+                                                          int rp, int mxb, lq_weights_view out)
 {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     const int C64 = K >> 6, CQ = (C64 + 3) >> 2, B = K >> 5;
@@ -207,14 +287,25 @@ __global__ __launch_bounds__(256) void mx_unpack_w_kernel(const uint8_t* packed,
     }
     if (idx < (size_t)N * r && out.lq) {
         const int n = (int)(idx / r), j = (int)(idx % r);
-        out.lq[idx] = (int8_t)packed[pl.off_lq + (size_t)n * rp + j];
+        out.lq[idx] = (int8_t)packed[pl.off_lq + (mxb ? mxb_frag8_offset(n, j, rp) : (size_t)n * rp + j)];
     }
-    if (idx < (size_t)N && out.sl) out.sl[idx] = ((const float*)(packed + pl.off_sl))[idx];
     if (idx < (size_t)r * K && out.rq) {
         const int j = (int)(idx / K), k = (int)(idx % K);
-        out.rq[idx] = (int8_t)packed[pl.off_rq + mx_rq_offset(j, k, r)];
+        out.rq[idx] = (int8_t)packed[pl.off_rq + (mxb ? mxb_rq_offset(j, k, r) : mx_rq_offset(j, k, r))];
     }
-    if (idx < (size_t)r && out.sr) out.sr[idx] = ((const float*)(packed + pl.off_sr))[idx];
+    if (mxb) {
+        if (idx < (size_t)N * (r >> 5) && out.le) {
+            const int n = (int)(idx / (r >> 5)), b = (int)(idx % (r >> 5));
+            out.le[idx] = packed[pl.off_sl + mxb_scale_offset(n, b)];
+        }
+        if (idx < (size_t)r * B && out.re) {
+            const int j = (int)(idx / B), b = (int)(idx % B);
+            out.re[idx] = packed[pl.off_sr + mxb_re_offset(j, b, r)];
+        }
+    } else {
+        if (idx < (size_t)N && out.sl) out.sl[idx] = ((const float*)(packed + pl.off_sl))[idx];
+        if (idx < (size_t)r && out.sr) out.sr[idx] = ((const float*)(packed + pl.off_sr))[idx];
+    }
 }
 
 hipError_t launch_unpack_weights_mx(const Dims& d, const uint8_t* packed, const lq_weights_view* out, hipStream_t s)
@@ -222,12 +313,12 @@ hipError_t launch_unpack_weights_mx(const Dims& d, const uint8_t* packed, const 
     const PackedLayout pl = packed_layout(d);
     const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * d.K;
     hipLaunchKernelGGL(mx_unpack_w_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, packed, pl, (int)d.N,
-                       (int)d.K, d.r, d.rp, *out);
+                       (int)d.K, d.r, d.rp, d.mxb ? 1 : 0, *out);
     return hipGetLastError();
 }
 
 __global__ __launch_bounds__(256) void mx_unpack_a_kernel(const uint8_t* act, ActLayout al, int M, int K, int r, int rp,
-                                                          lq_act_view out)
+                                                          int mxb, lq_act_view out)
 {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     const int C64 = K >> 6, CQ = (C64 + 3) >> 2, B = K >> 5;
@@ -240,10 +331,14 @@ __global__ __launch_bounds__(256) void mx_unpack_a_kernel(const uint8_t* act, Ac
         const int m = (int)(idx / B), b = (int)(idx % B);
         out.xe[idx] = act[al.off_sx + mx_scale_offset(m, b >> 1, b & 1, CQ)];
     }
-    if (idx < (size_t)M && out.st) out.st[idx] = ((const float*)(act + al.off_st))[idx];
+    if (idx < (size_t)M && out.st && !mxb) out.st[idx] = ((const float*)(act + al.off_st))[idx];
     if (idx < (size_t)M * r && out.tq) {
         const int m = (int)(idx / r), j = (int)(idx % r);
-        out.tq[idx] = (int8_t)act[al.off_tq + (size_t)m * rp + j];
+        out.tq[idx] = (int8_t)act[al.off_tq + (mxb ? mxb_frag8_offset(m, j, rp) : (size_t)m * rp + j)];
+    }
+    if (mxb && idx < (size_t)M * (r >> 5) && out.te) {
+        const int m = (int)(idx / (r >> 5)), b = (int)(idx % (r >> 5));
+        out.te[idx] = act[al.off_st + mxb_scale_offset(m, b)];
     }
 }
 
@@ -252,7 +347,7 @@ hipError_t launch_unpack_act_mx(const Dims& d, const uint8_t* act, int64_t M, co
     const ActLayout al = act_layout(d, M);
     const size_t n = (size_t)M * (d.K > d.r ? d.K : d.r);
     hipLaunchKernelGGL(mx_unpack_a_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, act, al, (int)M,
-                       (int)d.K, d.r, d.rp, *out);
+                       (int)d.K, d.r, d.rp, d.mxb ? 1 : 0, *out);
     return hipGetLastError();
 }
 
@@ -491,9 +586,13 @@ static hipError_t mx_act_rank(const MxActParams& p, int64_t Mp, hipStream_t s)
     }
 }
 
+static hipError_t launch_quantize_act_mxb(const Dims& d, int x_dtype, const uint8_t* packed, const void* X, int64_t M,
+                                          int64_t ldx, uint8_t* act, const lq_act_debug* dbg, hipStream_t s);
+
 hipError_t launch_quantize_act_mx(const Dims& d, int x_dtype, const uint8_t* packed, const void* X, int64_t M,
                                   int64_t ldx, uint8_t* act, const lq_act_debug* dbg, hipStream_t s)
 {
+    if (d.mxb) return launch_quantize_act_mxb(d, x_dtype, packed, X, M, ldx, act, dbg, s);
     const PackedLayout pl = packed_layout(d);
     const ActLayout al = act_layout(d, M);
     MxActParams p;
@@ -525,6 +624,235 @@ hipError_t launch_quantize_act_mx(const Dims& d, int x_dtype, const uint8_t* pac
 }
 
 // ---------------------------------------------------------------------------------------------
+// activation kernel with an MXFP8e4 branch.  Same decomposition as above, but K is walked in chunks
+// of 128 (= one v_mfma_scale_f32_16x16x128_f8f6f4): lane (row l%16, q = l/16) holds the 16 values
+// k = 16q.. of each 64-half of the chunk, which is both the fragment position of the 4-bit main codes
+// and, as E4M3, bytes 0..15 / 16..31 of the lane's 8-bit MFMA operand.  A 32-block is shared by the
+// lane pair (q, q^1); the MFMA takes the scale of block q from lane (row, q), so lanes 1 and 2 swap.
+// ---------------------------------------------------------------------------------------------
+struct MxbActParams {
+    const void* X;
+    int64_t ldx;
+    int M, K, C64, CQ, C128, r, rp;
+    const uint8_t* r8;
+    const uint8_t* re;
+    uint8_t* xc;
+    uint8_t* xe;
+    uint8_t* tq8;
+    uint8_t* te;
+    int8_t* dbg_xb;
+    uint8_t* dbg_xbe;
+    float* dbg_T;
+};
+
+template <bool BF16, int MAXC, int NJB>
+__global__ __launch_bounds__(256) void mxb_act_kernel(MxbActParams p)
+{
+    constexpr int NJA = NJB > 0 ? NJB : 1;
+    __shared__ float s_acc[4][NJA][64][4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r16 = lane & 15, q = lane >> 4;
+    const int row = blockIdx.x * 16 + r16;
+    const bool row_ok = row < p.M;
+    const int C64 = p.C64, C128 = p.C128;
+
+    MxChunk<BF16> xh[MAXC][2];
+#pragma unroll
+    for (int ci = 0; ci < MAXC; ++ci) {
+        const int c = wave + 4 * ci;
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+            xh[ci][hh].load(p.X, (size_t)row * p.ldx + (size_t)c * 128 + hh * 64 + q * 16, row_ok && c < C128);
+    }
+    // R fragments and their scale dwords: first chunk now, later ones one chunk ahead
+    v8i bvs[2][NJA];
+    int bss[2][NJA];
+    auto load_r8 = [&](int slot, int ci) {
+        int c = wave + 4 * ci;
+        c = c < C128 ? c : C128 - 1;  // clamped: a fragment past the end is fetched but not used
+#pragma unroll
+        for (int jb = 0; jb < NJB; ++jb) {
+            bvs[slot][jb] = *(const v8i*)(p.r8 + ((size_t)((size_t)c * NJB + jb) * 64 + lane) * 32);
+            bss[slot][jb] = *(const int*)(p.re + ((size_t)((size_t)c * NJB + jb) * 64 + lane) * 4);
+        }
+    };
+    load_r8(0, 0);
+
+    v4f acc[NJA];
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb) acc[jb] = v4f{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+    for (int ci = 0; ci < MAXC; ++ci) {
+        const int c = wave + 4 * ci;
+        if (ci + 1 < MAXC) load_r8((ci + 1) & 1, ci + 1);
+        if (c < C128) {  // wave-uniform
+            uint32_t x8[8];
+            uint32_t Eh[2];
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const MxChunk<BF16>& xc = xh[ci][hh];
+                float m = 0.f;
+                if constexpr (BF16) {
+                    us2 m2 = {0, 0};
+#pragma unroll
+                    for (int d = 0; d < 8; ++d) m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, xc.w[d] & 0x7FFF7FFFu));
+                    const uint32_t mm = m2[0] > m2[1] ? m2[0] : m2[1];
+                    m = __uint_as_float(mm << 16);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(xc.get(i)));
+                }
+                const float ab = fmaxf(m, __shfl_xor(m, 16, 64));  // amax of the 32-block (lanes q, q^1)
+                // main codes: MXFP4
+                const uint32_t E4 = e8m0_of(ab);
+                const float sc = e8m0_value(E4);
+                uint32_t pk[2] = {0u, 0u};
+#define LQ_CVT4(J) pk[(J) >> 2] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(pk[(J) >> 2], xc.get(2 * (J)), xc.get(2 * (J) + 1), sc, (J) & 3)
+                if (ab != 0.0f) {
+                    LQ_CVT4(0); LQ_CVT4(1); LQ_CVT4(2); LQ_CVT4(3); LQ_CVT4(4); LQ_CVT4(5); LQ_CVT4(6); LQ_CVT4(7);
+                }
+#undef LQ_CVT4
+                const int c64 = 2 * c + hh;
+                uint8_t* dst = p.xc + ((size_t)((size_t)(row >> 5) * C64 + c64) * 64 + (row & 31) + 32 * (q >> 1)) * 16 + (q & 1) * 8;
+                *(uint2*)dst = make_uint2(pk[0], pk[1]);
+                if ((q & 1) == 0) p.xe[mx_scale_offset(row, c64, q >> 1, p.CQ)] = (uint8_t)E4;
+                // branch codes: MXFP8e4 of the same block
+                const uint32_t E8 = e8m0_of_fp8(ab);
+                const float inv8 = e8m0_inverse(E8);
+                Eh[hh] = E8;
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    x8[4 * hh + g] = fp8_quad(__fmul_rn(xc.get(4 * g), inv8), __fmul_rn(xc.get(4 * g + 1), inv8),
+                                              __fmul_rn(xc.get(4 * g + 2), inv8), __fmul_rn(xc.get(4 * g + 3), inv8));
+                if (p.dbg_xb && row_ok)
+                    *(v4i*)(p.dbg_xb + (size_t)row * p.K + (size_t)c * 128 + hh * 64 + q * 16) =
+                        v4i{(int)x8[4 * hh], (int)x8[4 * hh + 1], (int)x8[4 * hh + 2], (int)x8[4 * hh + 3]};
+                if (p.dbg_xbe && row_ok && (q & 1) == 0) p.dbg_xbe[(size_t)row * (p.K >> 5) + 4 * c + 2 * hh + (q >> 1)] = (uint8_t)E8;
+            }
+            if (NJB > 0) {
+                // lane q knows blocks (q>>1) [first half] and 2+(q>>1) [second half]; it must supply block q
+                const uint32_t send = (q == 1) ? Eh[1] : Eh[0];
+                const uint32_t recv = (uint32_t)__shfl_xor((int)send, 48, 64);
+                const int sa = (int)((q == 0) ? Eh[0] : (q == 3) ? Eh[1] : recv);
+                const v8i a8 = {(int)x8[0], (int)x8[1], (int)x8[2], (int)x8[3], (int)x8[4], (int)x8[5], (int)x8[6], (int)x8[7]};
+#pragma unroll
+                for (int jb = 0; jb < NJB; ++jb)
+                    acc[jb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, bvs[ci & 1][jb], acc[jb], 0, 0, 0, sa, 0,
+                                                                            bss[ci & 1][jb]);
+            }
+        } else {
+            // padding chunks of the last quad: their scale bytes must be valid E8M0 values (2^0)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+                if (2 * c + hh < 4 * p.CQ && (q & 1) == 0) p.xe[mx_scale_offset(row, 2 * c + hh, q >> 1, p.CQ)] = (uint8_t)127;
+        }
+    }
+    if (NJB == 0) return;
+
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb) *(v4f*)&s_acc[wave][jb][lane][0] = acc[jb];
+    __syncthreads();
+    if (wave != 0) return;
+
+    // lane holds column j = jb*16 + lane%16 of the intermediate for token rows 4*q + i
+    float T[NJA][4];
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb) {
+        v4f sum = *(const v4f*)&s_acc[0][jb][lane][0];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const v4f o = *(const v4f*)&s_acc[w][jb][lane][0];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sum[i] = __fadd_rn(sum[i], o[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            T[jb][i] = sum[i];
+            const int grow = blockIdx.x * 16 + 4 * q + i;
+            if (grow < p.M && p.dbg_T) p.dbg_T[(size_t)grow * p.r + jb * 16 + r16] = sum[i];
+        }
+    }
+    // re-quantise per token and per block of 32 along the rank (two 16-column groups per block)
+#pragma unroll
+    for (int bb = 0; bb < (NJB + 1) / 2; ++bb) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float tm = fmaxf(fabsf(T[2 * bb][i]), fabsf(T[2 * bb + 1][i]));
+#pragma unroll
+            for (int o = 8; o >= 1; o >>= 1) tm = fmaxf(tm, __shfl_xor(tm, o, 64));
+            const int grow = blockIdx.x * 16 + 4 * q + i;
+            const uint32_t E = e8m0_of_fp8(tm);
+            const float inv = e8m0_inverse(E);
+            if (r16 == 0) p.te[mxb_scale_offset(grow, bb)] = (uint8_t)E;
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+                p.tq8[mxb_frag8_offset(grow, (2 * bb + g) * 16 + r16, p.rp)] = (uint8_t)fp8_byte(__fmul_rn(T[2 * bb + g][i], inv));
+        }
+    }
+    // padding of the rank to a multiple of 64: zero codes, scale 2^0
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int grow = blockIdx.x * 16 + 4 * q + i;
+        for (int j = p.r + r16; j < p.rp; j += 16) p.tq8[mxb_frag8_offset(grow, j, p.rp)] = 0;
+        if (r16 == 0)
+            for (int bb = p.r >> 5; bb < (p.rp >> 5); ++bb) p.te[mxb_scale_offset(grow, bb)] = (uint8_t)127;
+    }
+}
+
+template <bool BF16, int MAXC, int NJB>
+static hipError_t mxb_act_launch(const MxbActParams& p, int64_t Mp, hipStream_t s)
+{
+    hipLaunchKernelGGL((mxb_act_kernel<BF16, MAXC, NJB>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+template <bool BF16, int MAXC>
+static hipError_t mxb_act_rank(const MxbActParams& p, int64_t Mp, hipStream_t s)
+{
+    switch (p.r) {
+        case 0: return mxb_act_launch<BF16, MAXC, 0>(p, Mp, s);
+        case 32: return mxb_act_launch<BF16, MAXC, 2>(p, Mp, s);
+        case 64: return mxb_act_launch<BF16, MAXC, 4>(p, Mp, s);
+        default: return mxb_act_launch<BF16, MAXC, 8>(p, Mp, s);
+    }
+}
+
+static hipError_t launch_quantize_act_mxb(const Dims& d, int x_dtype, const uint8_t* packed, const void* X, int64_t M,
+                                          int64_t ldx, uint8_t* act, const lq_act_debug* dbg, hipStream_t s)
+{
+    const PackedLayout pl = packed_layout(d);
+    const ActLayout al = act_layout(d, M);
+    MxbActParams p;
+    p.X = X;
+    p.ldx = ldx;
+    p.M = (int)M;
+    p.K = (int)d.K;
+    p.C64 = d.C64;
+    p.CQ = (d.C64 + 3) / 4;
+    p.C128 = d.C64 / 2;
+    p.r = d.r;
+    p.rp = d.rp;
+    p.r8 = packed + pl.off_rq;
+    p.re = packed + pl.off_sr;
+    p.xc = act + al.off_xq;
+    p.xe = act + al.off_sx;
+    p.tq8 = act + al.off_tq;
+    p.te = act + al.off_st;
+    p.dbg_xb = dbg ? dbg->xb : nullptr;
+    p.dbg_xbe = dbg ? dbg->xbe : nullptr;
+    p.dbg_T = dbg ? dbg->T : nullptr;
+    const int maxc = (p.C128 + 3) / 4;  // 128-chunks per wavefront
+    if (x_dtype == LQ_BF16) {
+        if (maxc <= 3) return mxb_act_rank<true, 3>(p, al.Mp, s);
+        if (maxc <= 5) return mxb_act_rank<true, 5>(p, al.Mp, s);
+        return mxb_act_rank<true, 9>(p, al.Mp, s);
+    }
+    if (maxc <= 3) return mxb_act_rank<false, 3>(p, al.Mp, s);
+    return mxb_act_rank<false, 5>(p, al.Mp, s);
+}
+
+// ---------------------------------------------------------------------------------------------
 // forward: 1 x 4 wavefronts per workgroup, 128 x 64 outputs per wavefront, K staged 128 at a time
 // ---------------------------------------------------------------------------------------------
 struct MxFwdParams {
@@ -543,8 +871,9 @@ struct MxFwdParams {
     float* dbg_y32;
 };
 
-// NK = 64-deep chunks of the (padded) rank: 0 | 1 | 2
-template <int NK, bool DBG>
+// NK = 64-deep chunks of the (padded) rank: 0 | 1 | 2.  BLK: the branch is MXFP8e4 (block scales,
+// accumulated by the scaled MFMA straight into the main product's accumulators).
+template <int NK, bool DBG, bool BLK>
 __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
 {
     constexpr int WN = 4, RBT = 4;
@@ -683,19 +1012,50 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
 
     if (!active) return;
 
+    if constexpr (BLK) {
+        // ---- MXFP8e4 branch: tq . lq^T with both block scales, on top of the main accumulators.
+        // Operands are stored in the 8-bit operand order of the instruction (32 bytes per lane and
+        // 64-chunk of the rank); the scale dword of a lane holds the byte of chunk cc at position cc.
+#pragma unroll
+        for (int cc = 0; cc < NK; ++cc) {
+            v8i lb[2];
+            int lsc[2];
+#pragma unroll
+            for (int cbi = 0; cbi < 2; ++cbi) {
+                lb[cbi] = *(const v8i*)(p.l8 + ((size_t)((size_t)(cb0 + cbi) * NK + cc) * 64 + lane) * 32);
+                lsc[cbi] = *(const int*)((const uint8_t*)p.sl + ((size_t)(cb0 + cbi) * 64 + lane) * 4);
+            }
+#pragma unroll
+            for (int rbi = 0; rbi < 4; ++rbi) {
+                int rb = rb0 + rbi;
+                rb = rb < p.nrb ? rb : p.nrb - 1;
+                const v8i ta = *(const v8i*)(p.tq8 + ((size_t)((size_t)rb * NK + cc) * 64 + lane) * 32);
+                const int tsc = *(const int*)((const uint8_t*)p.st + ((size_t)rb * 64 + lane) * 4);
+#pragma unroll
+                for (int cbi = 0; cbi < 2; ++cbi) {
+                    if (cc == 0)
+                        t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ta, lb[cbi], t[rbi][cbi], 0, 0, 0, tsc, 0, lsc[cbi]);
+                    else
+                        t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ta, lb[cbi], t[rbi][cbi], 0, 0, 1, tsc, 1, lsc[cbi]);
+                }
+            }
+        }
+    }
+
     // ---- epilogue: FP8 rank-r expansion, scales, sum, bf16, transposed full-line stores -------
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     typedef float f32x2 __attribute__((ext_vector_type(2)));
-    constexpr int NKA = NK > 0 ? NK : 1;
+    constexpr int NKF = BLK ? 0 : NK;  // chunks of the fp32-scaled branch handled in this epilogue
+    constexpr int NKA = NKF > 0 ? NKF : 1;
     uint8_t* stage = lds + wave * EPI_WAVE;
-    float slv[2];
+    float slv[2] = {0.f, 0.f};
     v8i lf[2][NKA];
 #pragma unroll
     for (int cbi = 0; cbi < 2; ++cbi) {
         const int col = (cb0 + cbi) * 32 + l32;
-        slv[cbi] = p.sl[col];
+        if (!BLK) slv[cbi] = p.sl[col];
 #pragma unroll
-        for (int kk = 0; kk < NK; ++kk) lf[cbi][kk] = *(const v8i*)(p.l8 + (size_t)col * p.rp + kk * 64 + half * 32);
+        for (int kk = 0; kk < NKF; ++kk) lf[cbi][kk] = *(const v8i*)(p.l8 + (size_t)col * p.rp + kk * 64 + half * 32);
     }
     const int wr_off = (4 * half) * EPI_ROW + l32 * 2;
     const int rd_row = lane >> 3, rd_seg = lane & 7;
@@ -707,9 +1067,10 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
         int rb = rb0 + rbi;
         rb = rb < p.nrb ? rb : p.nrb - 1;
 #pragma unroll
-        for (int kk = 0; kk < NK; ++kk) tf[kk] = *(const v8i*)(p.tq8 + (size_t)(rb * 32 + l32) * p.rp + kk * 64 + half * 32);
+        for (int kk = 0; kk < NKF; ++kk) tf[kk] = *(const v8i*)(p.tq8 + (size_t)(rb * 32 + l32) * p.rp + kk * 64 + half * 32);
     };
     auto load_scales = [&](int rbi) {
+        if (BLK) return;
         int rb = rb0 + rbi;
         rb = rb < p.nrb ? rb : p.nrb - 1;
 #pragma unroll
@@ -730,7 +1091,7 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
         for (int cbi = 0; cbi < 2; ++cbi) {
             a2[cbi] = v16f{0};
 #pragma unroll
-            for (int kk = 0; kk < NK; ++kk)
+            for (int kk = 0; kk < NKF; ++kk)
                 a2[cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(tf[kk], lf[cbi][kk], a2[cbi], 0, 0, 0, 0, 0, 0);
         }
         if (rbi + 1 < 4) load_tq(rbi + 1);
@@ -739,8 +1100,12 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
         for (int cbi = 0; cbi < 2; ++cbi)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const float ybr = __fmul_rn(__fmul_rn(a2[cbi][i], stv[i >> 2][i & 3]), slv[cbi]);
-                y[cbi][i] = __fadd_rn(t[rbi][cbi][i], ybr);
+                if (BLK) {
+                    y[cbi][i] = t[rbi][cbi][i];
+                } else {
+                    const float ybr = __fmul_rn(__fmul_rn(a2[cbi][i], stv[i >> 2][i & 3]), slv[cbi]);
+                    y[cbi][i] = __fadd_rn(t[rbi][cbi][i], ybr);
+                }
             }
         if (rbi + 1 < 4) load_scales(rbi + 1);
 #pragma unroll
@@ -772,14 +1137,14 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     }
 }
 
-template <int NK>
+template <int NK, bool BLK>
 static void mx_fwd_launch(const MxFwdParams& p, hipStream_t s)
 {
     dim3 grid((unsigned)(p.tilesM * p.tilesN)), block(256);
     if (p.dbg_y32)
-        hipLaunchKernelGGL((mx_fwd_kernel<NK, true>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((mx_fwd_kernel<NK, true, BLK>), grid, block, 0, s, p);
     else
-        hipLaunchKernelGGL((mx_fwd_kernel<NK, false>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((mx_fwd_kernel<NK, false, BLK>), grid, block, 0, s, p);
 }
 
 hipError_t launch_fwd_mx(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M, uint16_t* Y, int64_t ldy,
@@ -808,10 +1173,18 @@ hipError_t launch_fwd_mx(const Dims& d, const uint8_t* packed, const uint8_t* ac
     p.tilesM = (p.nrb + 3) / 4;
     p.tilesN = (p.N + 255) / 256;
     p.dbg_y32 = dbg ? dbg->y32 : nullptr;
-    switch (p.rp >> 6) {
-        case 0: mx_fwd_launch<0>(p, s); break;
-        case 1: mx_fwd_launch<1>(p, s); break;
-        default: mx_fwd_launch<2>(p, s); break;
+    if (d.mxb) {  // sl / st hold the E8M0 scale dwords of L / of the intermediate
+        switch (p.rp >> 6) {
+            case 0: mx_fwd_launch<0, false>(p, s); break;
+            case 1: mx_fwd_launch<1, true>(p, s); break;
+            default: mx_fwd_launch<2, true>(p, s); break;
+        }
+    } else {
+        switch (p.rp >> 6) {
+            case 0: mx_fwd_launch<0, false>(p, s); break;
+            case 1: mx_fwd_launch<1, false>(p, s); break;
+            default: mx_fwd_launch<2, false>(p, s); break;
+        }
     }
     return hipGetLastError();
 }

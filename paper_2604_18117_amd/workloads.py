@@ -26,7 +26,7 @@ class Layer:
     K: int
     N: int
     r: int
-    family: str            # "int" (INT4 main, integer branch) | "mx" (MXFP4 main, FP8 branch)
+    family: str            # "int" (INT4 main, integer branch) | "mx" (MXFP4 main, FP8 branch) | "mxb" (MXFP8e4 branch)
     g: int                 # main weight group along K (INT: 64|128; MX: 32)
     br_w_bits: int         # branch weight width (INT: 8|6|4; MX: 8)
     br_a_bits: int         # branch activation width (INT: 8|6; MX: 8)
@@ -74,7 +74,10 @@ CFG5 = [_mx_layer("c5_qkv", 1152, 3456), _mx_layer("c5_attn_out", 1152, 1152),
         _mx_layer("c5_cross_out", 1152, 1152), _mx_layer("c5_fc1", 1152, 4608),
         _mx_layer("c5_fc2", 4608, 1152)]
 
-CONFIGS: Dict[str, List[Layer]] = {"c1": CFG1, "c2": CFG2, "c3": CFG3, "c4": CFG4, "c5": CFG5}
+# The same seven layers with an MXFP8e4 (block-scaled E4M3) branch: the all-MX mixed-precision setting.
+CFG5B = [replace(l, name="c5b" + l.name[2:], family="mxb") for l in CFG5]
+
+CONFIGS: Dict[str, List[Layer]] = {"c1": CFG1, "c2": CFG2, "c3": CFG3, "c4": CFG4, "c5": CFG5, "c5b": CFG5B}
 LAYERS: Dict[str, Layer] = {l.name: l for ls in CONFIGS.values() for l in ls}
 
 

@@ -77,6 +77,25 @@ def test_unsupported_combinations(lq):
     assert lq.raw().lq_packed_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
 
 
+def test_mx_family_contract(lq):
+    n = C.c_size_t(0)
+    raw = lq.raw()
+    for fam in ("mx", "mxb"):
+        assert raw.lq_packed_sizes(C.byref(_cfg(lq, family=fam, K=256)), C.byref(n)) == lq.LQ_OK
+        assert raw.lq_packed_sizes(C.byref(_cfg(lq, family=fam, K=192)), C.byref(n)) == lq.LQ_ERR_SHAPE
+    # blocks of 32 along the rank: a block-scaled branch has no rank 16
+    assert raw.lq_packed_sizes(C.byref(_cfg(lq, family="mx", rank=16)), C.byref(n)) == lq.LQ_OK
+    assert raw.lq_packed_sizes(C.byref(_cfg(lq, family="mxb", rank=16)), C.byref(n)) == lq.LQ_ERR_SHAPE
+    cfg = _cfg(lq, family="mxb")
+    cfg.br_a = lq.LQ_FP8_E4M3       # both branch operands share one format
+    assert raw.lq_packed_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    # codes N*K/2, E8M0 dwords per (32 rows, quad of 64-chunks, lane), lq N*64, one scale dword per
+    # (channel, rank half), rq r*K, one scale dword per (128-chunk, 16 rank rows, lane) (+4)
+    cfg = lq.make_config(3456, 1152, 32, "mxb")
+    parts = [3456 * 1152 // 2, 3456 // 32 * 5 * 256, 3456 * 64, 3456 * 8, 32 * 1152, 9 * 2 * 256 + 4]
+    assert lq.lq_packed_sizes(cfg) == sum((x + 255) // 256 * 256 for x in parts)
+
+
 def test_argument_errors_before_any_launch(lq):
     raw = lq.raw()
     cfg = _cfg(lq)

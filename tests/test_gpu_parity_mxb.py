@@ -1,0 +1,148 @@
+"""GPU parity, MX family with an MXFP8e4 branch (all-MX setting of the mixed-precision tables,
+Section 4.3; element formats of App. A.3) against the CPU oracle.
+
+Bar: every code and E8M0 byte computed from source data (X, P, L, R) bit-exact (+0 and -0 codes are
+the same value); the intermediate T and the output pass through the matrix core's own accumulation
+(block-scaled 8-bit products summed in an order and an internal width the instruction set does not
+document; measured worst case 2^-14.9 of the sum of the magnitudes of the terms) and are bounded by
+2^-13 of that sum; the re-quantised
+intermediate must be a correct block quantisation of a value within that bound of the oracle's T.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_18117_amd import workloads as wl
+from tests.gpu_util import bf16_to_bits, n, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+E2M1 = np.array([0, .5, 1, 1.5, 2, 3, 4, 6, -0., -.5, -1, -1.5, -2, -3, -4, -6], np.float32)
+
+
+def _compare(oracle, layer, X, W, L, R, rows=None):
+    g = run_gpu(layer, X, W, L, R, debug=True, debug_acc=False)
+    Xo = X if rows is None else X[rows]
+    sel = slice(None) if rows is None else rows
+    r = layer.r
+    pk = oracle.pack_mxb(W, L if r else None, R if r else None)
+    act = oracle.quantize_act_mxb(Xo, pk)
+    f8 = oracle.e4m3_decode(np.arange(256, dtype=np.uint8))
+    Mo = Xo.shape[0]
+    # ---- offline packing: exact
+    assert np.array_equal(E2M1[n(g.wv.pq).view(np.uint8)], E2M1[pk.pc]), "pq"
+    assert np.array_equal(n(g.wv.pe), pk.pe), "pe"
+    if r:
+        assert np.array_equal(f8[n(g.wv.lq).view(np.uint8)], f8[pk.l8]), "l8"
+        assert np.array_equal(n(g.wv.le), pk.le), "le"
+        assert np.array_equal(f8[n(g.wv.rq).view(np.uint8)], f8[pk.r8]), "r8"
+        assert np.array_equal(n(g.wv.re), pk.re), "re"
+    # ---- activation step: codes and block scales from X exact
+    assert np.array_equal(E2M1[n(g.av.xq).view(np.uint8)[sel]], E2M1[act.xc]), "xc"
+    assert np.array_equal(n(g.av.xe)[sel], act.xe), "xe"
+    tq_gpu = n(g.av.tq).view(np.uint8)[sel] if r else np.zeros((Mo, 0), np.uint8)
+    te_gpu = n(g.av.te)[sel] if r else np.zeros((Mo, 0), np.uint8)
+    if r:
+        assert np.array_equal(f8[n(g.adbg.xb).view(np.uint8)[sel]], f8[act.xb8]), "xb8"
+        assert np.array_equal(n(g.adbg.xbe)[sel], act.xbe), "xbe"
+        T_gpu = n(g.adbg.T)[sel]
+        xs = np.abs(f8[act.xb8].astype(np.float64).reshape(Mo, -1, 32)) * oracle.e8m0_decode(act.xbe)[:, :, None]
+        rs = np.abs(f8[pk.r8].astype(np.float64).reshape(r, -1, 32)) * oracle.e8m0_decode(pk.re)[:, :, None]
+        tb = 2.0 ** -13 * (xs.reshape(Mo, -1) @ rs.reshape(r, -1).T) + 1e-300
+        assert np.all(np.abs(T_gpu - act.T) <= tb), f"T max excess {np.max(np.abs(T_gpu - act.T) / tb)}"
+        # block exponents: equal except where a block's amax sits within the bound of a power of two
+        ediff = te_gpu != act.te
+        assert ediff.mean() <= 1e-2, f"te mismatch rate {ediff.mean()}"
+        assert np.all(np.abs(te_gpu.astype(int) - act.te.astype(int)) <= 1)
+        # every GPU element is a correct saturating E4M3 rounding, under the GPU's block scale, of a
+        # value within the accumulation bound of the oracle's T
+        sc = np.repeat(oracle.e8m0_decode(te_gpu), 32, axis=1)
+        u = np.abs(act.T.astype(np.float64)) / sc
+        step = np.exp2(np.maximum(np.floor(np.log2(np.maximum(u, 2.0 ** -6))) - 3, -9))
+        half = np.where(u > 448.0, u - 448.0, 0.5 * step * (1 + 1e-6))
+        deq = f8[tq_gpu].astype(np.float64) * sc
+        assert np.all(np.abs(deq - act.T) <= sc * half + tb), "tq8 is not a block rounding of T"
+        same = ~ediff.repeat(32, axis=1)
+        diff = (tq_gpu != act.tq8) & ~(((tq_gpu & 0x7F) == 0) & ((act.tq8 & 0x7F) == 0)) & same
+        assert diff.mean() <= 1e-2, f"tq8 mismatch rate {diff.mean()}"
+    # ---- forward: the oracle is fed the GPU's re-quantised intermediate
+    act_g = dataclasses.replace(act, tq8=np.ascontiguousarray(tq_gpu), te=np.ascontiguousarray(te_gpu))
+    out = oracle.fwd_mxb(pk, act_g)
+    y_gpu = n(g.fdbg.y32)[sel]
+    Xd = np.abs(E2M1[act.xc].astype(np.float64).reshape(Mo, -1, 32)) * oracle.e8m0_decode(act.xe)[:, :, None]
+    Wd = np.abs(E2M1[pk.pc].astype(np.float64).reshape(layer.N, -1, 32)) * oracle.e8m0_decode(pk.pe)[:, :, None]
+    A = Xd.reshape(Mo, -1) @ Wd.reshape(layer.N, -1).T
+    if r:
+        Td = np.abs(f8[tq_gpu].astype(np.float64).reshape(Mo, -1, 32)) * oracle.e8m0_decode(te_gpu)[:, :, None]
+        Ld = np.abs(f8[pk.l8].astype(np.float64).reshape(layer.N, -1, 32)) * oracle.e8m0_decode(pk.le)[:, :, None]
+        A = A + Td.reshape(Mo, -1) @ Ld.reshape(layer.N, -1).T
+    bound = 2.0 ** -13 * A + 1e-300
+    assert np.all(np.abs(y_gpu - out.y32) <= bound), f"y32 max excess {np.max(np.abs(y_gpu - out.y32) / bound)}"
+    Yb = bf16_to_bits(g.Y)[sel]
+    want = ((y_gpu.view(np.uint32) + 0x7FFF + ((y_gpu.view(np.uint32) >> 16) & 1)) >> 16).astype(np.uint16)
+    assert np.array_equal(Yb, want), "Y is not bf16_rne(y32)"
+    Yf = oracle.bf16_bits_to_f32(Yb).astype(np.float64)
+    Yo = oracle.bf16_bits_to_f32(out.Y).astype(np.float64)
+    tau = 1e-3 * np.sqrt(np.mean(out.y32.astype(np.float64) ** 2)) + 1e-300
+    rel = np.abs(Yf - Yo) / np.maximum(np.abs(out.y32), tau)
+    flips = Yb != out.Y
+    assert flips.mean() <= 2e-3, f"bf16 flip rate {flips.mean()}"
+    assert np.all(rel[~flips] <= 2e-3)
+    assert np.all(rel[flips] <= 2.0 ** -7 * 1.01)
+    g2 = run_gpu(layer, X, W, L, R, debug=False)
+    assert torch.equal(g2.Y, g.Y)
+    return g
+
+
+SMALL = [
+    # M (ragged), K (multiple of 128), N (partial 256-wide tile), r (multiple of 32), x_dtype
+    (300, 256, 320, 32, "bf16"),
+    (77, 384, 64, 32, "f32"),
+    (130, 1152, 192, 64, "bf16"),
+    (64, 128, 64, 0, "bf16"),
+    (33, 640, 128, 128, "bf16"),
+    (1, 128, 64, 32, "f32"),
+]
+
+
+@pytest.mark.parametrize("M,K,N,r,xd", SMALL)
+def test_small_shapes(oracle, M, K, N, r, xd):
+    layer = wl.Layer("t", M, K, N, r, "mxb", 32, 8, 8, xd, seed=M + K)
+    X, W, L, R = wl.make_inputs(layer)
+    _compare(oracle, layer, X, W, L, R)
+
+
+def test_degenerate_inputs(oracle):
+    layer = wl.Layer("t", 70, 256, 64, 32, "mxb", 32, 8, 8, "bf16", seed=3)
+    X, W, L, R = wl.make_inputs(layer)
+    X[3] = 0.0
+    X[5, :] = 0.0
+    X[5, 7] = -2.0
+    X[9, 32:64] = 0.0
+    W[2] = 0.0
+    W[4, 64:96] = 0.0
+    L[4] = 0.0
+    R[1] = 0.0
+    _compare(oracle, layer, X, W, L, R)
+    _compare(oracle, layer, np.zeros_like(X), W, L, R)
+
+
+def test_wide_dynamic_range_blocks(oracle):
+    layer = wl.Layer("t", 64, 256, 64, 32, "mxb", 32, 8, 8, "bf16", seed=5)
+    X, W, L, R = wl.make_inputs(layer)
+    rng = np.random.default_rng(7)
+    X *= wl.round_to_bf16(np.exp2(rng.integers(-20, 20, size=(64, 8)).repeat(32, axis=1)).astype(np.float32))
+    W *= np.exp2(rng.integers(-10, 10, size=(64, 8)).repeat(32, axis=1)).astype(np.float32)
+    R *= np.exp2(rng.integers(-6, 6, size=(32, 8)).repeat(32, axis=1)).astype(np.float32)
+    _compare(oracle, layer, wl.round_to_bf16(X), W, L, R)
+
+
+@pytest.mark.parametrize("name", ["c5_qkv", "c5_fc2"])
+def test_full_size_sampled_rows(oracle, name):
+    layer = dataclasses.replace(wl.LAYERS[name], family="mxb")
+    X, W, L, R = wl.make_inputs(layer)
+    rng = np.random.default_rng(1)
+    rows = np.sort(np.concatenate([[0, layer.M - 1], rng.choice(layer.M, 14, replace=False)]))
+    _compare(oracle, layer, X, W, L, R, rows=rows)
