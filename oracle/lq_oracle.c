@@ -23,6 +23,10 @@
  *          contraction axis, E8M0 scale) for X, R, the intermediate X R^T and L, i.e. the
  *          all-MX setting of the paper's mixed-precision tables (Section 4.3); no fp32
  *          scale anywhere; the two branches are summed in fp64 and rounded once.
+ *   MXI  : Q1 = MXINT4 for both operands of the main product, Q2 = MXINT8 for the branch
+ *          activations and the intermediate, MXINT8 or MXINT4 for L and R (App. A.3: "signed
+ *          int4 and int8" elements, blocks of 32, E8M0 scale; the integer rows of the
+ *          mixed-precision tables, Section 4.3); fp64 accumulate, one rounding.
  *
  * Readings of points the paper leaves open (all "parity unpinned" by the paper; the tests
  * pin self-consistency only):
@@ -36,6 +40,12 @@
  *     saturate at +-6; all-zero block: E8M0 byte 0;
  *   - MXFP8e4 scale exponent = floor(log2 amax) - 8 (8 = largest E4M3 exponent), elements
  *     saturate at +-448; the rank is a multiple of 32 so that blocks along r are whole;
+ *   - MXINT element of width b: integer code c in [-(2^(b-1)-1), 2^(b-1)-1] with b-2 fraction
+ *     bits, value = c * 2^-(b-2) * 2^(E-127) with the shared exponent E-127 = floor(log2 amax)
+ *     (the MX specification's INT8 element, 1 sign + 1 integer + 6 fraction bits and largest
+ *     element exponent 0, and the same pattern at 4 bits: 1 + 1 + 2); the block maximum
+ *     therefore lands in the top octave of the code range, a value that would round to
+ *     2^(b-1) saturates, -2^(b-1) is never produced; all-zero block: E8M0 byte 0;
  *   - P is built from the *dequantised* quantised factors (Fig. 1), optionally from the
  *     unquantised ones (residual_from_quantized = 0).
  *
@@ -569,6 +579,148 @@ LQO_API void lqo_fwd_mxb(int64_t M, int64_t N, int64_t K, int r, const uint8_t *
         free(vx);
     }
     free(vw);
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* MXI family: MXINT4 main product, MXINT8 / MXINT4 branch                                */
+/* ------------------------------------------------------------------------------------ */
+
+/* MXINT of width `bits` (8 or 4): n values (a multiple of 32) in blocks of 32; one E8M0 byte
+   per block holding the shared exponent floor(log2 amax) + 127; one integer code per value,
+   value = code * 2^-(bits-2) * 2^(byte-127). */
+LQO_API void lqo_quant_mxint(const float *v, int64_t n, int bits, int8_t *codes, uint8_t *e8m0)
+{
+    const int qmax = (1 << (bits - 1)) - 1;
+    const int frac = bits - 2;
+    for (int64_t b = 0; b < n / 32; ++b) {
+        const float *blk = v + 32 * b;
+        float a = absmax_f32(blk, 32);
+        int s;
+        if (a == 0.0f) {
+            s = -127;
+        } else {
+            int ex;
+            (void)frexpf(a, &ex); /* floor(log2 a) = ex - 1 */
+            s = ex - 1;
+            if (s < -127) s = -127;
+            if (s > 127) s = 127;
+        }
+        e8m0[b] = (uint8_t)(s + 127);
+        for (int i = 0; i < 32; ++i) {
+            float u = ldexpf(blk[i], frac - s); /* exact power-of-two scaling into code units */
+            float q = nearbyintf(u);            /* ties to even */
+            if (q > (float)qmax) q = (float)qmax;
+            if (q < -(float)qmax) q = -(float)qmax;
+            codes[32 * b + i] = (int8_t)q;
+        }
+    }
+}
+
+/* value of an MXINT element */
+static double mxint_value(int8_t code, uint8_t e8m0, int bits)
+{
+    return ldexp((double)code, (int)e8m0 - 127 - (bits - 2));
+}
+
+/* bw_bits: width of the branch weight format (8 or 4).
+   Outputs: pq N x K int4 codes (one per byte), pe N x K/32; lq N x r, le N x r/32 (blocks
+   along r); rq r x K, re r x K/32 (blocks along K); P (optional). */
+LQO_API void lqo_pack_mxi(int64_t N, int64_t K, int r, int bw_bits, int residual_from_quantized,
+                          const float *W, const float *L, const float *R, int8_t *pq,
+                          uint8_t *pe, int8_t *lq, uint8_t *le, int8_t *rq, uint8_t *re,
+                          float *P_out)
+{
+    const int64_t BK = K / 32;
+    const int BR = r / 32;
+    for (int j = 0; j < r; ++j) lqo_quant_mxint(R + (int64_t)j * K, K, bw_bits, rq + (int64_t)j * K, re + (int64_t)j * BK);
+    for (int64_t n = 0; n < N; ++n) lqo_quant_mxint(L + n * r, r, bw_bits, lq + n * r, le + n * BR);
+
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        float *P = (float *)malloc(sizeof(float) * (size_t)K);
+        for (int64_t k = 0; k < K; ++k) {
+            double d = 0.0;
+            for (int j = 0; j < r; ++j) {
+                double lh, rh;
+                if (residual_from_quantized) {
+                    lh = mxint_value(lq[n * r + j], le[n * BR + j / 32], bw_bits);
+                    rh = mxint_value(rq[(int64_t)j * K + k], re[(int64_t)j * BK + k / 32], bw_bits);
+                } else {
+                    lh = L[n * r + j];
+                    rh = R[(int64_t)j * K + k];
+                }
+                d += lh * rh;
+            }
+            P[k] = (float)((double)W[n * K + k] - d);
+        }
+        lqo_quant_mxint(P, K, 4, pq + n * K, pe + n * BK);
+        if (P_out) memcpy(P_out + n * K, P, sizeof(float) * (size_t)K);
+        free(P);
+    }
+}
+
+/* Outputs: xq M x K int4 codes, xe M x K/32; xb M x K int8 codes, xbe M x K/32; T M x r fp32
+   (the fp64 contraction rounded once); tq M x r int8 codes, te M x r/32. */
+LQO_API void lqo_quantize_act_mxi(int64_t M, int64_t K, int r, int bw_bits, const float *X,
+                                  const int8_t *rq, const uint8_t *re, int8_t *xq, uint8_t *xe,
+                                  int8_t *xb, uint8_t *xbe, float *T, int8_t *tq, uint8_t *te)
+{
+    const int64_t BK = K / 32;
+    const int BR = r / 32;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const float *x = X + m * K;
+        lqo_quant_mxint(x, K, 4, xq + m * K, xe + m * BK);
+        if (r == 0) continue;
+        lqo_quant_mxint(x, K, 8, xb + m * K, xbe + m * BK);
+        float *Trow = (float *)malloc(sizeof(float) * (size_t)r);
+        for (int j = 0; j < r; ++j) {
+            double a = 0.0;
+            for (int64_t b = 0; b < BK; ++b) {
+                int32_t d = 0;
+                for (int k = 0; k < 32; ++k)
+                    d += (int32_t)xb[m * K + 32 * b + k] * (int32_t)rq[(int64_t)j * K + 32 * b + k];
+                a += ldexp((double)d, ((int)xbe[m * BK + b] - 127 - 6) + ((int)re[(int64_t)j * BK + b] - 127 - (bw_bits - 2)));
+            }
+            Trow[j] = (float)a;
+        }
+        lqo_quant_mxint(Trow, r, 8, tq + m * r, te + m * BR);
+        if (T) memcpy(T + m * r, Trow, sizeof(float) * (size_t)r);
+        free(Trow);
+    }
+}
+
+LQO_API void lqo_fwd_mxi(int64_t M, int64_t N, int64_t K, int r, int bw_bits, const int8_t *xq,
+                         const uint8_t *xe, const int8_t *pq, const uint8_t *pe, const int8_t *tq,
+                         const uint8_t *te, const int8_t *lq, const uint8_t *le, float *ymain,
+                         float *ybr, float *y32, uint16_t *Y)
+{
+    const int64_t B = K / 32;
+    const int BR = r / 32;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            double t = 0.0;
+            for (int64_t b = 0; b < B; ++b) {
+                int32_t d = 0;
+                for (int k = 0; k < 32; ++k)
+                    d += (int32_t)xq[m * K + 32 * b + k] * (int32_t)pq[n * K + 32 * b + k];
+                t += ldexp((double)d, ((int)xe[m * B + b] - 127 - 2) + ((int)pe[n * B + b] - 127 - 2));
+            }
+            double u = 0.0;
+            for (int b = 0; b < BR; ++b) {
+                int32_t d = 0;
+                for (int j = 0; j < 32; ++j)
+                    d += (int32_t)tq[m * r + 32 * b + j] * (int32_t)lq[n * r + 32 * b + j];
+                u += ldexp((double)d, ((int)te[m * BR + b] - 127 - 6) + ((int)le[n * BR + b] - 127 - (bw_bits - 2)));
+            }
+            float y = (float)(t + u); /* sum node of Fig. 1: both accumulators, one rounding */
+            if (ymain) ymain[m * N + n] = (float)t;
+            if (ybr) ybr[m * N + n] = (float)u;
+            if (y32) y32[m * N + n] = y;
+            if (Y) Y[m * N + n] = bf16_rne(y);
+        }
+    }
 }
 
 LQO_API int lqo_num_threads(void)

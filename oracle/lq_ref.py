@@ -358,3 +358,87 @@ def fwd_mxb(pk: PackedMxb, act: ActMxb) -> FwdOut:
                       _p(pk.pc), _p(pk.pe), _p(act.tq8), _p(act.te), _p(pk.l8), _p(pk.le),
                       _p(out.ymain), _p(out.ybr), _p(out.y32), _p(out.Y))
     return out
+
+
+# ---------------------------------------------------------------------------------------
+# MXI family: MXINT4 main, MXINT8 / MXINT4 branch
+# ---------------------------------------------------------------------------------------
+
+def quant_mxint(v, bits: int):
+    v = _f32(v).ravel()
+    assert v.size % 32 == 0 and bits in (4, 8)
+    codes = np.empty(v.size, np.int8)
+    e = np.empty(v.size // 32, np.uint8)
+    lib().lqo_quant_mxint(_p(v), C.c_int64(v.size), C.c_int(bits), _p(codes), _p(e))
+    return codes, e
+
+
+def mxint_scale(e8m0, bits: int):
+    """Value of one code step of a block: 2^(byte - 127 - (bits - 2)), as float64."""
+    return np.ldexp(1.0, np.asarray(e8m0).astype(np.int64) - 127 - (bits - 2))
+
+
+@dataclass
+class PackedMxi:
+    N: int
+    K: int
+    r: int
+    bw_bits: int
+    pq: np.ndarray   # N x K int8 (4-bit codes)
+    pe: np.ndarray   # N x K/32 uint8 E8M0
+    lq: np.ndarray   # N x r int8
+    le: np.ndarray   # N x r/32 uint8
+    rq: np.ndarray   # r x K int8
+    re: np.ndarray   # r x K/32 uint8
+    P: np.ndarray
+
+
+def pack_mxi(W, L, R, bw_bits: int = 8, residual_from_quantized: bool = True) -> PackedMxi:
+    W = _f32(W)
+    N, K = W.shape
+    r = 0 if L is None else int(np.shape(L)[1])
+    assert K % 32 == 0 and r % 32 == 0 and bw_bits in (4, 8)
+    Lc = _f32(L) if r else np.zeros((N, 0), np.float32)
+    Rc = _f32(R) if r else np.zeros((0, K), np.float32)
+    out = PackedMxi(N, K, r, bw_bits, np.empty((N, K), np.int8), np.empty((N, K // 32), np.uint8),
+                    np.empty((N, r), np.int8), np.empty((N, r // 32), np.uint8),
+                    np.empty((r, K), np.int8), np.empty((r, K // 32), np.uint8), np.empty((N, K), np.float32))
+    lib().lqo_pack_mxi(C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(bw_bits),
+                       C.c_int(1 if residual_from_quantized else 0), _p(W), _p(Lc), _p(Rc), _p(out.pq), _p(out.pe),
+                       _p(out.lq), _p(out.le), _p(out.rq), _p(out.re), _p(out.P))
+    return out
+
+
+@dataclass
+class ActMxi:
+    M: int
+    xq: np.ndarray    # M x K int8 (4-bit codes)
+    xe: np.ndarray    # M x K/32 uint8
+    xb: np.ndarray    # M x K int8
+    xbe: np.ndarray   # M x K/32 uint8
+    T: np.ndarray     # M x r float32
+    tq: np.ndarray    # M x r int8
+    te: np.ndarray    # M x r/32 uint8
+
+
+def quantize_act_mxi(X, pk: PackedMxi) -> ActMxi:
+    X = _f32(X)
+    M, K = X.shape
+    r = pk.r
+    out = ActMxi(M, np.empty((M, K), np.int8), np.empty((M, K // 32), np.uint8), np.zeros((M, K), np.int8),
+                 np.zeros((M, K // 32), np.uint8), np.zeros((M, r), np.float32), np.zeros((M, r), np.int8),
+                 np.zeros((M, r // 32), np.uint8))
+    lib().lqo_quantize_act_mxi(C.c_int64(M), C.c_int64(K), C.c_int(r), C.c_int(pk.bw_bits), _p(X), _p(pk.rq),
+                               _p(pk.re), _p(out.xq), _p(out.xe), _p(out.xb), _p(out.xbe), _p(out.T), _p(out.tq),
+                               _p(out.te))
+    return out
+
+
+def fwd_mxi(pk: PackedMxi, act: ActMxi) -> FwdOut:
+    M, N, K, r = act.M, pk.N, pk.K, pk.r
+    out = FwdOut(None, None, np.empty((M, N), np.float32), np.empty((M, N), np.float32),
+                 np.empty((M, N), np.float32), np.empty((M, N), np.uint16))
+    lib().lqo_fwd_mxi(C.c_int64(M), C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(pk.bw_bits), _p(act.xq),
+                      _p(act.xe), _p(pk.pq), _p(pk.pe), _p(act.tq), _p(act.te), _p(pk.lq), _p(pk.le),
+                      _p(out.ymain), _p(out.ybr), _p(out.y32), _p(out.Y))
+    return out

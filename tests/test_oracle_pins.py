@@ -17,7 +17,7 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "ocp_mx_element_forma
 
 
 def _golden():
-    out = {"e2m1": None, "e4m3": [], "e8m0": [], "budget": []}
+    out = {"e2m1": None, "e4m3": [], "e8m0": [], "budget": [], "mxint": {}}
     for line in open(GOLDEN):
         line = line.strip()
         if not line or line.startswith("#"):
@@ -29,6 +29,8 @@ def _golden():
             out["e4m3"].append((int(t[1], 16), float(t[2])))
         elif t[0] == "e8m0":
             out["e8m0"].append((int(t[1]), float(t[2])))
+        elif t[0] == "mxint":
+            out["mxint"][int(t[1])] = (float(t[2]), float(t[3]))
         elif t[0] == "budget":
             out["budget"].append(tuple(int(v) for v in t[1:]))
     return out
@@ -641,6 +643,140 @@ def test_mxb_rank0_equals_mx_rank0_and_grid_factors_are_exact(oracle):
     pg = oracle.pack_mxb(W, np.zeros((N, r), np.float32), Rg)
     back = oracle.e4m3_decode(pg.r8).astype(np.float64).reshape(r, -1, 32) * oracle.e8m0_decode(pg.re)[:, :, None]
     assert np.array_equal(back.reshape(r, K).astype(np.float32), Rg)
+
+
+# --------------------------------------------------------------------------------------
+# MXI family: MXINT4 main, MXINT8 / MXINT4 branch (App. A.3: signed int elements, blocks of 32,
+# E8M0 scale; the integer rows of the mixed-precision tables, Section 4.3)
+# --------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_mxint_block_quantiser(oracle, bits):
+    step, top = _golden()["mxint"][bits]
+    qmax = 2 ** (bits - 1) - 1
+    assert top == qmax * step and step == 2.0 ** -(bits - 2)
+    rng = np.random.default_rng(31 + bits)
+    v = (rng.standard_normal(32 * 80) * np.exp(rng.uniform(-8, 8, 32 * 80))).astype(np.float32)
+    v[64:96] = 0.0
+    v[96] = 1.0; v[97] = -0.3; v[98:128] = 0.0           # hand-checked block: shared exponent 0
+    v[128] = -7.9; v[129] = 2.5; v[130:160] = 0.0        # 7.9 = 1.975 * 2^2: shared exponent 2
+    codes, e = oracle.quant_mxint(v, bits)
+    assert e[2] == 0 and not codes[64:96].any()
+    assert e[3] == 127 and codes[96] == 2 ** (bits - 2) and codes[97] == -round(0.3 / step)
+    assert e[4] == 129 and codes[128] == -(qmax if bits == 4 else 126) and codes[129] == round(2.5 / 4 / step)
+    assert np.abs(codes.astype(int)).max() <= qmax
+    vb = v.astype(np.float64).reshape(-1, 32)
+    cb = codes.astype(np.float64).reshape(-1, 32)
+    for b in range(vb.shape[0]):
+        a = np.abs(vb[b]).max()
+        if a == 0:
+            continue
+        shared = 2.0 ** np.floor(np.log2(a))                      # the specification's shared scale
+        assert 2.0 ** (int(e[b]) - 127) == shared
+        u = vb[b] / shared                                          # exact; |u| < 2
+        deq = cb[b] * step
+        grid = np.arange(-qmax, qmax + 1) * step
+        for ui, di in zip(u, deq):                                  # nearest grid point (saturating)
+            assert abs(di - ui) <= np.min(np.abs(grid - ui))
+        assert np.abs(deq).max() >= 1.0                             # the maximum sits in the top octave
+        inside = np.abs(u) <= top
+        assert np.all(np.abs(deq - u)[inside] <= step / 2) and np.all(np.abs(deq - u)[~inside] < step)
+    # exact ties go to the even code
+    t = np.zeros(32, np.float32); t[0] = 1.0
+    t[1:5] = np.array([0.5, 1.5, 2.5, -3.5], np.float32) * np.float32(step)
+    ct, _ = oracle.quant_mxint(t, bits)
+    assert list(ct[1:5]) == [0, 2, 2, -4]
+    # idempotence (Section 3.2) and power-of-two equivariance
+    back = (cb * step * (2.0 ** (e.astype(np.float64) - 127))[:, None]).astype(np.float32).ravel()
+    c2, e2 = oracle.quant_mxint(back, bits)
+    nzb = np.abs(vb).max(axis=1) > 0
+    assert np.array_equal(e2[nzb], e[nzb]) and np.array_equal(c2.reshape(-1, 32)[nzb], codes.reshape(-1, 32)[nzb])
+    c3, e3 = oracle.quant_mxint(v * np.float32(2.0 ** -7), bits)
+    assert np.array_equal(c3, codes) and np.array_equal(e3[nzb].astype(int), e[nzb].astype(int) - 7)
+    c4, _ = oracle.quant_mxint(-v, bits)
+    assert np.array_equal(c4, -codes)
+
+
+@pytest.mark.parametrize("bw", [8, 4])
+def test_mxi_forward_against_exact_rationals(oracle, bw):
+    rng = np.random.default_rng(32 + bw)
+    M, K, N, r = 4, 64, 5, 32
+    X = wl.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    L = (rng.standard_normal((N, r)) * 3e-2).astype(np.float32)
+    R = (rng.standard_normal((r, K)) * 3e-2).astype(np.float32)
+    pk = oracle.pack_mxi(W, L, R, bw)
+    act = oracle.quantize_act_mxi(X, pk)
+    out = oracle.fwd_mxi(pk, act)
+    F = Fraction
+    sc = lambda byte, bits: F(2) ** (int(byte) - 127 - (bits - 2))
+    val = lambda codes, bytes_, bits: [[F(int(c)) * sc(bytes_[i][j // 32], bits) for j, c in enumerate(row)]
+                                       for i, row in enumerate(codes)]
+    xv, pv = val(act.xq, act.xe, 4), val(pk.pq, pk.pe, 4)
+    xbv, rv = val(act.xb, act.xbe, 8), val(pk.rq, pk.re, bw)
+    tv, lv = val(act.tq, act.te, 8), val(pk.lq, pk.le, bw)
+    for n in range(N):                                           # residual from the dequantised factors
+        for k in range(0, K, 5):
+            d = sum(lv[n][j] * rv[j][k] for j in range(r))
+            assert pk.P[n, k] == np.float32(float(F(float(W[n, k])) - d))
+    c, e = oracle.quant_mxint(R[3], bw); assert np.array_equal(c, pk.rq[3]) and np.array_equal(e, pk.re[3])
+    c, e = oracle.quant_mxint(L[2], bw); assert np.array_equal(c, pk.lq[2]) and np.array_equal(e, pk.le[2])
+    c, e = oracle.quant_mxint(pk.P[1], 4); assert np.array_equal(c, pk.pq[1]) and np.array_equal(e, pk.pe[1])
+    c, e = oracle.quant_mxint(X[1], 4); assert np.array_equal(c, act.xq[1]) and np.array_equal(e, act.xe[1])
+    c, e = oracle.quant_mxint(X[1], 8); assert np.array_equal(c, act.xb[1]) and np.array_equal(e, act.xbe[1])
+    for m in range(M):
+        for j in range(r):
+            T = sum(xbv[m][k] * rv[j][k] for k in range(K))
+            assert act.T[m, j] == np.float32(float(T))              # one rounding of the exact contraction
+        c, e = oracle.quant_mxint(act.T[m], 8); assert np.array_equal(c, act.tq[m]) and np.array_equal(e, act.te[m])
+        for n in range(N):
+            main = sum(xv[m][k] * pv[n][k] for k in range(K))
+            br = sum(tv[m][j] * lv[n][j] for j in range(r))
+            assert out.ymain[m, n] == np.float32(float(main)) and out.ybr[m, n] == np.float32(float(br))
+            assert out.y32[m, n] == np.float32(float(main + br))
+            assert out.Y[m, n] == oracle.bf16_rne(float(out.y32[m, n]))
+    # the integer contractions inside the blocks are textbook integer matmuls (uniform scales)
+    Xu = np.tile(np.arange(-16, 16, dtype=np.float32) / 8, (M, K // 32)); Xu[:, 0::32] = 1.9
+    Wu = np.tile(np.arange(16, -16, -1, dtype=np.float32) / 16, (N, K // 32)); Wu[:, 1::32] = 1.9
+    pu = oracle.pack_mxi(Wu, None, None, bw)
+    au = oracle.quantize_act_mxi(Xu, pu)
+    assert np.all(au.xe == 127) and np.all(pu.pe == 127)
+    ref = (au.xq.astype(np.int64) @ pu.pq.astype(np.int64).T) / 16.0
+    assert np.array_equal(oracle.fwd_mxi(pu, au).y32, ref.astype(np.float32))
+    # the 8-bit branch approximates X R^T L^T far better than the 4-bit main product's step
+    ref = X.astype(np.float64) @ R.astype(np.float64).T @ L.astype(np.float64).T
+    assert np.abs(out.ybr - ref).max() <= (0.03 if bw == 8 else 0.4) * np.abs(ref).max()
+
+
+def test_mxi_rank0_zero_factors_and_lossless_grids(oracle):
+    rng = np.random.default_rng(35)
+    M, K, N, r = 4, 96, 6, 32
+    X = wl.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    p0 = oracle.pack_mxi(W, None, None)
+    pz = oracle.pack_mxi(W, np.zeros((N, r), np.float32), np.zeros((r, K), np.float32))
+    assert np.array_equal(p0.P, W) and np.array_equal(p0.pq, pz.pq) and np.array_equal(p0.pe, pz.pe)
+    y0 = oracle.fwd_mxi(p0, oracle.quantize_act_mxi(X, p0))
+    yz = oracle.fwd_mxi(pz, oracle.quantize_act_mxi(X, pz))
+    assert np.array_equal(y0.Y, yz.Y) and not yz.ybr.any()
+    # Section 3.2 fixed point: weights on the MXINT4 grid, factors on the MXINT8 grid, an input on the
+    # MXINT4 grid: everything is stored without loss and the main product equals X W^T exactly
+    cw = rng.integers(-7, 8, size=(N, K)); cw.reshape(N, -1, 32)[:, :, 0] = 5
+    sw = 2.0 ** rng.integers(-9, -5, size=(N, K // 32))
+    Wg = (cw.reshape(N, -1, 32) * sw[:, :, None] / 4).reshape(N, K).astype(np.float32)
+    cx = rng.integers(-7, 8, size=(M, K)); cx.reshape(M, -1, 32)[:, :, 3] = -6
+    sx = 2.0 ** rng.integers(-3, 3, size=(M, K // 32))
+    Xg = (cx.reshape(M, -1, 32) * sx[:, :, None] / 4).reshape(M, K).astype(np.float32)
+    pg = oracle.pack_mxi(Wg, None, None)
+    ag = oracle.quantize_act_mxi(Xg, pg)
+    assert np.array_equal(pg.pq, cw) and np.array_equal(ag.xq, cx)
+    assert np.array_equal(oracle.mxint_scale(pg.pe, 4) * 4, sw) and np.array_equal(oracle.mxint_scale(ag.xe, 4) * 4, sx)
+    exact = Xg.astype(np.float64) @ Wg.astype(np.float64).T          # exact in fp64 at these magnitudes
+    assert np.array_equal(oracle.fwd_mxi(pg, ag).y32, exact.astype(np.float32))
+    # inputs in the block maximum's own octave with 6 fraction bits pass through MXINT8 unchanged
+    Xs = (np.round(rng.uniform(1.0, 1.98, size=(M, K)) * 64) / 64 * rng.choice([-1, 1], size=(M, K))).astype(np.float32)
+    cs, es = oracle.quant_mxint(Xs, 8)
+    assert np.array_equal((cs.astype(np.float64) * np.repeat(oracle.mxint_scale(es, 8), 32)).astype(np.float32), Xs.ravel())
 
 
 def test_workload_generator_is_seeded():
