@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 # MI355X dense matrix peaks: FP8 / INT8 (the INT4 main product runs on the FP8 pipe) and FP4 (MXFP4)
-PEAK_MFMA_TFLOPS = {"int": 5033.0, "mx": 10066.0, "mxb": 10066.0}
+PEAK_MFMA_TFLOPS = {"int": 5033.0, "mx": 10066.0, "mxb": 10066.0, "mxi": 5033.0}
 # HBM bytes per forward launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/fwd_int_kernel_c2_qkv.md,
 # profiles/mx_fwd_kernel_c5_qkv.md),
 # each scaled by the factor a plain copy of known size gives (2.0 for FETCH_SIZE, 1.0 for WRITE_SIZE).
@@ -136,14 +136,17 @@ def main():
     act_bytes = layer.M * layer.K * (xb + 0.5) + layer.M * (layer.r + 8)
     act_gbs = act_bytes / (act_ms * 1e-3) / 1e9
 
-    mx = layer.family in ("mx", "mxb")
+    mx = layer.family in ("mx", "mxb", "mxi")      # block-scaled main product (E8M0 per 32 values)
     mxb = layer.family == "mxb"
+    mxi = layer.family == "mxi"
     peak = PEAK_MFMA_TFLOPS[layer.family]
     # algorithmic HBM bytes of the forward launch: 4-bit codes of both operands and their scales, the
     # rank-r operands, per-token / per-channel scales in, bf16 Y out
     rp = 0 if layer.r == 0 else (-(-layer.r // 64) * 64 if mx else -(-layer.r // 32) * 32)
+    if mxi:  # branch elements travel as bf16 (2 bytes each), one scale byte per 32 values
+        rp = 2 * layer.r
     if mx:
-        scale_bytes = (layer.M + layer.N) * (layer.K // 32) + (rp // 32 if mxb else 4) * (layer.M + layer.N)
+        scale_bytes = (layer.M + layer.N) * (layer.K // 32) + (0 if mxi else rp // 32 if mxb else 4) * (layer.M + layer.N)
     else:
         scale_bytes = 4 * layer.N * (layer.K // layer.g) + 4 * (2 * layer.M + layer.N)
     fwd_bytes = (layer.M + layer.N) * layer.K / 2 + scale_bytes + (layer.M + layer.N) * rp + 2.0 * layer.M * layer.N
@@ -155,13 +158,15 @@ def main():
         "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "mxfp4" if mx else "int4",
+        "dtype": "mxint4" if mxi else "mxfp4" if mx else "int4",
         "data": "synthetic",
         "config": {"workload": layer.name, "M": layer.M, "K": layer.K, "N": layer.N, "rank": layer.r,
-                   "main": "W4A4 MXFP4 block 32" if mx else f"W4A4 INT4 g{layer.g}",
-                   "branch": "W8A8 MXFP8e4 block 32" if mxb else "W8A8 FP8 E4M3" if mx else f"W{layer.br_w_bits}A{layer.br_a_bits}",
+                   "main": "W4A4 MXINT4 block 32" if mxi else "W4A4 MXFP4 block 32" if mx else f"W4A4 INT4 g{layer.g}",
+                   "branch": f"W{layer.br_w_bits}A8 MXINT block 32" if mxi else "W8A8 MXFP8e4 block 32" if mxb else "W8A8 FP8 E4M3" if mx else f"W{layer.br_w_bits}A{layer.br_a_bits}",
                    "x_dtype": layer.x_dtype, "buffer_sets": nsets,
-                   "arithmetic": ("e2m1 x e8m0 on the scaled FP4 MFMA, e4m3 branch, fp32 accumulate" if mx else
+                   "arithmetic": ("int4 codes as FP8 subnormals with E8M0 block scales on the scaled FP8 MFMA, "
+                                  "bf16-exact MXINT branch, fp32 accumulate" if mxi else
+                                  "e2m1 x e8m0 on the scaled FP4 MFMA, e4m3 branch, fp32 accumulate" if mx else
                                   "int4 codes (exact, on the FP8 MFMA pipe), int8 branch, fp32 dequantisation")},
         # the bound is whichever of ops/peak and bytes/bandwidth is the longer time for this layer (the
         # K = 1152 MXFP4 layers write 2 bytes per 2*1152 ops at the FP4 rate: below the ridge)
@@ -174,7 +179,7 @@ def main():
     }
 
     out["roofline"].update({
-        "kernel": "mx_fwd_kernel" if mx else "fwd_int_kernel", "traffic": MEASURED_TRAFFIC_BYTES.get(layer.name),
+        "kernel": "mxi_fwd_kernel" if mxi else "mx_fwd_kernel" if mx else "fwd_int_kernel", "traffic": MEASURED_TRAFFIC_BYTES.get(layer.name),
         "algorithmic_ops": fwd_ops, "algorithmic_bytes": fwd_bytes, "avg_kernel_ms": round(fwd_ms, 5),
         "event_pair_ms": round(fwd_raw_ms, 5), "empty_event_pair_ms": round(empty_ms, 5),
         "frac_of_mfma_peak": round(fwd_tops / peak, 4), "frac_of_hbm_peak": round(fwd_gbs / 8000.0, 4)})
@@ -182,7 +187,10 @@ def main():
     # ---- CPU oracle leg (reported baseline only): bounded row sample of the same workload -----
     if args.oracle_seconds > 0:
         from oracle import lq_ref
-        if mxb:
+        if mxi:
+            pk = lq_ref.pack_mxi(W, L, R, layer.br_w_bits)
+            run_rows = lambda n_rows: lq_ref.fwd_mxi(pk, lq_ref.quantize_act_mxi(X[:n_rows], pk))
+        elif mxb:
             pk = lq_ref.pack_mxb(W, L, R)
             run_rows = lambda n_rows: lq_ref.fwd_mxb(pk, lq_ref.quantize_act_mxb(X[:n_rows], pk))
         elif mx:

@@ -21,6 +21,11 @@
  *         the mixed-precision tables, Section 4.3) MXFP8e4: E4M3 elements in blocks of 32 along
  *         the contraction axis (K for X and R, the rank for X R^T and L) with E8M0 scales; then
  *         no fp32 scale exists and the branch accumulates into the main product's accumulator.
+ *   MXI : the integer MX formats of App. A.3 (the integer rows of the mixed-precision tables,
+ *         Section 4.3): Q1 = MXINT4 for both operands; Q2 = MXINT8 for X and X R^T, MXINT8 or
+ *         MXINT4 for L and R.  Element of width b: code c in [-(2^(b-1)-1), 2^(b-1)-1], value
+ *         c * 2^-(b-2) * 2^(E-127), E - 127 = floor(log2 amax) of the block of 32 (E = 0 for an
+ *         all-zero block).  Block maxima must be zero or lie in [2^-100, 2^120].
  *
  * General rules
  *   - Every pointer named "device" is GPU memory of the current HIP device, owned by the
@@ -31,7 +36,7 @@
  *     return value; a failed launch returns LQ_ERR_DEVICE.  Nothing throws.
  *   - Inputs must be finite (NaN / Inf give undefined codes).
  *   - Shape contract: K % 64 == 0, K % main_w_group == 0, N % 64 == 0,
- *     rank in {0,16,32,64,128} ({0,32,64,128} with an MXFP8e4 branch), 1 <= M,
+ *     rank in {0,16,32,64,128} ({0,32,64,128} with a block-scaled branch), 1 <= M,
  *     row strides >= row lengths; MX family: K % 128 == 0.
  *   - Calls are deterministic: no atomics, no split-K; repeated calls give identical bits.
  */
@@ -61,7 +66,9 @@ typedef enum {
     LQ_INT8 = 2,
     LQ_MXFP4_E2M1 = 3,
     LQ_FP8_E4M3 = 4,     /* E4M3 elements, one fp32 scale per token / per row                    */
-    LQ_MXFP8_E4M3 = 5    /* "MXFP8e4" (App. A.3): E4M3 elements, blocks of 32, E8M0 scale         */
+    LQ_MXFP8_E4M3 = 5,   /* "MXFP8e4" (App. A.3): E4M3 elements, blocks of 32, E8M0 scale         */
+    LQ_MXINT4 = 6,       /* "MXINT4" (App. A.3): signed int4 elements, blocks of 32, E8M0 scale    */
+    LQ_MXINT8 = 7        /* "MXINT8" (App. A.3): signed int8 elements, blocks of 32, E8M0 scale    */
 } lq_fmt;
 
 typedef enum { LQ_F32 = 0, LQ_BF16 = 1 } lq_dtype;
@@ -73,10 +80,10 @@ typedef struct {
     int32_t rank;                    /* r; 0 = no branch (plain W4A4)                            */
     int32_t main_w;                  /* lq_fmt: LQ_INT4 | LQ_MXFP4_E2M1                          */
     int32_t main_a;                  /* lq_fmt: must equal main_w                                 */
-    int32_t main_w_group;            /* INT: 64 | 128 values along K per weight scale; MX: 32    */
-    int32_t main_a_group;            /* INT: 0 = one scale per token; MX: 32                     */
-    int32_t br_w;                    /* lq_fmt of Q2(L), Q2(R): INT8|INT6|INT4; MX: FP8 | MXFP8  */
-    int32_t br_a;                    /* lq_fmt of Q2(X), Q2(X R^T): INT8|INT6; MX: = br_w        */
+    int32_t main_w_group;            /* INT: 64 | 128 values along K per weight scale; MX, MXI: 32 */
+    int32_t main_a_group;            /* INT: 0 = one scale per token; MX, MXI: 32                 */
+    int32_t br_w;                    /* lq_fmt of Q2(L), Q2(R): INT8|INT6|INT4; MX: FP8 | MXFP8; MXI: MXINT8 | MXINT4 */
+    int32_t br_a;                    /* lq_fmt of Q2(X), Q2(X R^T): INT8|INT6; MX: = br_w; MXI: MXINT8 */
     int32_t residual_from_quantized; /* 1: P = W - deq(Q2 L) deq(Q2 R) (Fig. 1); 0: P = W - L R  */
     int32_t x_dtype;                 /* lq_dtype of X                                             */
     int32_t reserved;                /* must be 0                                                 */

@@ -21,7 +21,7 @@ _lib = C.CDLL(_LIB_PATH)
 
 LQ_OK = 0
 LQ_ERR_NULL, LQ_ERR_SHAPE, LQ_ERR_UNSUPPORTED, LQ_ERR_ALIGN, LQ_ERR_BUFFER_TOO_SMALL, LQ_ERR_DEVICE = range(1, 7)
-LQ_INT4, LQ_INT6, LQ_INT8, LQ_MXFP4_E2M1, LQ_FP8_E4M3, LQ_MXFP8_E4M3 = range(6)
+LQ_INT4, LQ_INT6, LQ_INT8, LQ_MXFP4_E2M1, LQ_FP8_E4M3, LQ_MXFP8_E4M3, LQ_MXINT4, LQ_MXINT8 = range(8)
 LQ_F32, LQ_BF16 = 0, 1
 _INT_FMT = {4: LQ_INT4, 6: LQ_INT6, 8: LQ_INT8}
 
@@ -97,6 +97,9 @@ def make_config(N: int, K: int, rank: int, family: str = "int", group: int = 64,
     if family in ("mx", "mxb"):  # "mxb": MXFP8e4 (block-scaled E4M3) branch instead of fp32-scaled E4M3
         br = LQ_MXFP8_E4M3 if family == "mxb" else LQ_FP8_E4M3
         return lq_config(N, K, rank, LQ_MXFP4_E2M1, LQ_MXFP4_E2M1, 32, 32, br, br,
+                         1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32, 0)
+    if family == "mxi":          # MXINT4 main; MXINT8 branch activations; MXINT8 or MXINT4 branch weights
+        return lq_config(N, K, rank, LQ_MXINT4, LQ_MXINT4, 32, 32, LQ_MXINT8 if br_w_bits == 8 else LQ_MXINT4, LQ_MXINT8,
                          1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32, 0)
     raise ValueError(family)
 
@@ -217,7 +220,7 @@ class WeightsView:
 def lq_unpack_weights(cfg: lq_config, packed: torch.Tensor) -> WeightsView:
     dev = packed.device
     N, K, r = cfg.N, cfg.K, cfg.rank
-    mx = cfg.main_w == LQ_MXFP4_E2M1
+    mx = cfg.main_w in (LQ_MXFP4_E2M1, LQ_MXINT4)
     v = WeightsView(torch.zeros((N, K), dtype=torch.int8, device=dev),
                     None if mx else torch.zeros((N, K // cfg.main_w_group), dtype=torch.float32, device=dev),
                     torch.zeros((N, K // 32), dtype=torch.uint8, device=dev) if mx else None,
@@ -248,7 +251,7 @@ class ActView:
 def lq_unpack_act(cfg: lq_config, act: torch.Tensor, M: int) -> ActView:
     dev = act.device
     K, r = cfg.K, cfg.rank
-    mx = cfg.main_w == LQ_MXFP4_E2M1
+    mx = cfg.main_w in (LQ_MXFP4_E2M1, LQ_MXINT4)
     v = ActView(torch.zeros((M, K), dtype=torch.int8, device=dev),
                 None if mx else torch.zeros(M, dtype=torch.float32, device=dev),
                 torch.zeros((M, K // 32), dtype=torch.uint8, device=dev) if mx else None,

@@ -31,6 +31,8 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
     d->r = r;
     d->rp = (r + 31) / 32 * 32;
     d->C64 = (int)(cfg->K / 64);
+    d->mx = d->mxb = d->mxi = false;
+    d->bw_bits = 0;
     if (cfg->main_w == LQ_INT4) {
         if (cfg->main_a != LQ_INT4) return LQ_ERR_UNSUPPORTED;
         if (cfg->main_w_group != 64 && cfg->main_w_group != 128) return LQ_ERR_SHAPE;
@@ -39,7 +41,6 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         const int qw = int_qmax(cfg->br_w), qa = int_qmax(cfg->br_a);
         if (qw == 0 || qa == 0 || cfg->br_a == LQ_INT4) return LQ_ERR_UNSUPPORTED;
         d->mx = false;
-        d->mxb = false;
         d->g = cfg->main_w_group;
         d->qmax_bw = qw;
         d->qmax_ba = qa;
@@ -54,6 +55,15 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         d->g = 32;
         d->qmax_bw = d->qmax_ba = 0;
         d->rp = (r + 63) / 64 * 64;                  // FP8 expansion runs 64 deep
+    } else if (cfg->main_w == LQ_MXINT4) {
+        if (cfg->main_a != LQ_MXINT4) return LQ_ERR_UNSUPPORTED;
+        if (cfg->main_w_group != 32 || cfg->main_a_group != 32) return LQ_ERR_SHAPE;
+        if (cfg->br_a != LQ_MXINT8 || (cfg->br_w != LQ_MXINT8 && cfg->br_w != LQ_MXINT4)) return LQ_ERR_UNSUPPORTED;
+        if (r % 32 != 0) return LQ_ERR_SHAPE;  // whole blocks of 32 along the rank
+        d->mxi = true;
+        d->bw_bits = cfg->br_w == LQ_MXINT8 ? 8 : 4;
+        d->g = 32;
+        d->qmax_bw = d->qmax_ba = 0;
     } else {
         return LQ_ERR_UNSUPPORTED;
     }
@@ -68,15 +78,18 @@ PackedLayout packed_layout(const Dims& d)
     pl.off_pq = o;
     o = align256(o + (size_t)d.N * d.K / 2);
     pl.off_sw = o;
-    o = align256(o + (d.mx ? (size_t)(d.N / 32) * ((d.C64 + 3) / 4) * 256 : (size_t)d.N * d.G * 4));
+    o = align256(o + ((d.mx || d.mxi) ? (size_t)(d.N / 32) * ((d.C64 + 3) / 4) * 256 : (size_t)d.N * d.G * 4));
     pl.off_lq = o;
-    o = align256(o + (size_t)d.N * d.rp);
+    o = align256(o + (size_t)d.N * d.rp * (d.mxi ? 2 : 1));  // MXI: dequantised elements as bf16
     pl.off_sl = o;
-    o = align256(o + (size_t)d.N * (d.mxb ? 8 : 4));  // fp32 per channel, or a scale dword per (channel, rank half)
+    // fp32 per channel; MXFP8e4: a scale dword per (channel, rank half); MXI: a byte per (channel, rank block)
+    o = align256(o + (d.mxi ? (size_t)d.N * (d.r / 32) + 4 : (size_t)d.N * (d.mxb ? 8 : 4)));
     pl.off_rq = o;
-    o = align256(o + (size_t)d.r * d.K);
+    o = align256(o + (size_t)d.r * d.K * (d.mxi ? 2 : 1));
     pl.off_sr = o;
-    o = align256(o + (d.mxb ? (size_t)(d.K / 128) * (d.r / 16) * 256 + 4 : (size_t)(d.r > 0 ? d.r : 1) * 4));
+    o = align256(o + (d.mxi   ? (size_t)d.r * (d.K / 32) + 4
+                      : d.mxb ? (size_t)(d.K / 128) * (d.r / 16) * 256 + 4
+                              : (size_t)(d.r > 0 ? d.r : 1) * 4));
     pl.total = o;
     return pl;
 }
@@ -89,11 +102,11 @@ ActLayout act_layout(const Dims& d, int64_t M)
     al.off_xq = o;
     o = align256(o + (size_t)al.Mp * d.K / 2);
     al.off_sx = o;
-    o = align256(o + (d.mx ? (size_t)(al.Mp / 32) * ((d.C64 + 3) / 4) * 256 : (size_t)al.Mp * 4));
+    o = align256(o + ((d.mx || d.mxi) ? (size_t)(al.Mp / 32) * ((d.C64 + 3) / 4) * 256 : (size_t)al.Mp * 4));
     al.off_tq = o;
-    o = align256(o + (size_t)al.Mp * d.rp);
+    o = align256(o + (size_t)al.Mp * d.rp * (d.mxi ? 2 : 1));
     al.off_st = o;
-    o = align256(o + (size_t)al.Mp * (d.mxb ? 8 : 4));
+    o = align256(o + (d.mxi ? (size_t)al.Mp * (d.r / 32) + 4 : (size_t)al.Mp * (d.mxb ? 8 : 4)));
     al.total = o;
     return al;
 }
@@ -151,7 +164,8 @@ lq_status lq_pack_weights(const lq_config* cfg, const float* W, const float* L, 
     if (d.r > 0 && (!L || !R)) return LQ_ERR_NULL;
     if (!aligned(packed, 256) || !aligned(W, 4)) return LQ_ERR_ALIGN;
     if (packed_bytes < packed_layout(d).total) return LQ_ERR_BUFFER_TOO_SMALL;
-    hipError_t e = d.mx ? launch_pack_mx(d, cfg->residual_from_quantized, W, L, R, (uint8_t*)packed, (hipStream_t)stream)
+    hipError_t e = d.mxi ? launch_pack_mxi(d, cfg->residual_from_quantized, W, L, R, (uint8_t*)packed, (hipStream_t)stream)
+                   : d.mx ? launch_pack_mx(d, cfg->residual_from_quantized, W, L, R, (uint8_t*)packed, (hipStream_t)stream)
                         : launch_pack_int(d, cfg->residual_from_quantized, W, L, R, (uint8_t*)packed, (hipStream_t)stream);
     return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }
@@ -171,7 +185,9 @@ lq_status lq_quantize_act(const lq_config* cfg, const void* packed, const void* 
     if (act_bytes < act_layout(d, M).total) return LQ_ERR_BUFFER_TOO_SMALL;
     const int maxc = (d.C64 + 3) / 4;
     if (maxc > (cfg->x_dtype == LQ_BF16 ? 18 : 9)) return LQ_ERR_UNSUPPORTED;  // K beyond the register-resident row
-    hipError_t e = d.mx ? launch_quantize_act_mx(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,
+    hipError_t e = d.mxi ? launch_quantize_act_mxi(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,
+                                                   (hipStream_t)stream)
+                   : d.mx ? launch_quantize_act_mx(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,
                                                  (hipStream_t)stream)
                         : launch_quantize_act_int(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,
                                                   (hipStream_t)stream);
@@ -187,7 +203,9 @@ lq_status lq_linear_lowrank_fwd(const lq_config* cfg, const void* packed, const 
     if (!packed || !act || !Y) return LQ_ERR_NULL;
     if (M < 1 || M > (1 << 24) || ldy < d.N) return LQ_ERR_SHAPE;
     if (!aligned(packed, 256) || !aligned(act, 256) || !aligned(Y, 16) || (ldy & 7)) return LQ_ERR_ALIGN;
-    hipError_t e = d.mx ? launch_fwd_mx(d, (const uint8_t*)packed, (const uint8_t*)act, M, (uint16_t*)Y, ldy, dbg,
+    hipError_t e = d.mxi ? launch_fwd_mxi(d, (const uint8_t*)packed, (const uint8_t*)act, M, (uint16_t*)Y, ldy, dbg,
+                                          (hipStream_t)stream)
+                   : d.mx ? launch_fwd_mx(d, (const uint8_t*)packed, (const uint8_t*)act, M, (uint16_t*)Y, ldy, dbg,
                                         (hipStream_t)stream)
                         : launch_fwd_int(d, (const uint8_t*)packed, (const uint8_t*)act, M, (uint16_t*)Y, ldy, dbg,
                                          (hipStream_t)stream);
@@ -201,7 +219,8 @@ lq_status lq_unpack_weights(const lq_config* cfg, const void* packed, const lq_w
     if (st != LQ_OK) return st;
     if (!packed || !out) return LQ_ERR_NULL;
     if (!aligned(packed, 256)) return LQ_ERR_ALIGN;
-    hipError_t e = d.mx ? launch_unpack_weights_mx(d, (const uint8_t*)packed, out, (hipStream_t)stream)
+    hipError_t e = d.mxi ? launch_unpack_weights_mxi(d, (const uint8_t*)packed, out, (hipStream_t)stream)
+                   : d.mx ? launch_unpack_weights_mx(d, (const uint8_t*)packed, out, (hipStream_t)stream)
                         : launch_unpack_weights_int(d, (const uint8_t*)packed, out, (hipStream_t)stream);
     return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }
@@ -214,7 +233,8 @@ lq_status lq_unpack_act(const lq_config* cfg, const void* act, int64_t M, const 
     if (!act || !out) return LQ_ERR_NULL;
     if (M < 1 || M > (1 << 24)) return LQ_ERR_SHAPE;
     if (!aligned(act, 256)) return LQ_ERR_ALIGN;
-    hipError_t e = d.mx ? launch_unpack_act_mx(d, (const uint8_t*)act, M, out, (hipStream_t)stream)
+    hipError_t e = d.mxi ? launch_unpack_act_mxi(d, (const uint8_t*)act, M, out, (hipStream_t)stream)
+                   : d.mx ? launch_unpack_act_mx(d, (const uint8_t*)act, M, out, (hipStream_t)stream)
                         : launch_unpack_act_int(d, (const uint8_t*)act, M, out, (hipStream_t)stream);
     return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }

@@ -43,6 +43,12 @@ namespace lq {
 // sl / st sections): one dword per (row block, lane), byte cc = scale of rank block 2*cc + h.
 // rq : [128-chunk of K][rank/16][lane][32 bytes] (mxb_rq_offset); re (in the sr section): one dword
 // per (chunk, rank/16, lane), byte 0 = scale of K block 4*chunk + q.
+//
+// MXI family (MXINT4 main, MXINT8 / MXINT4 branch): main codes as 4-bit sign-magnitude nibbles in the
+// fragment order of the 8-bit scaled MFMA (mxi_frag_offset), scale bytes in the MX layout above holding
+// shared exponent + 127 + 7; the dequantised branch elements as bf16 in bf16-MFMA operand order
+// (lq / tq sections: [block of 32 rows][rank/16][lane][8 bf16]; rq section: [64-chunk][rank/16][2][lane]
+// [8 bf16]); their E8M0 bytes row-major in the sl / sr / st sections (kept for the views only).
 // ---------------------------------------------------------------------------------------
 
 struct Dims {
@@ -54,6 +60,8 @@ struct Dims {
     int C64;      // K / 64
     bool mx;      // MX family
     bool mxb;     // MX family with a block-scaled (MXFP8e4) branch
+    bool mxi;     // MXI family: MXINT4 main product, MXINT8 / MXINT4 branch (then mx is false)
+    int bw_bits;  // MXI: width of the branch weight format (8 | 4)
     int qmax_bw;  // INT branch weight qmax
     int qmax_ba;  // INT branch activation qmax
 };
@@ -107,6 +115,18 @@ hipError_t launch_quantize_act_mx(const Dims& d, int x_dtype, const uint8_t* pac
                                   hipStream_t s);
 hipError_t launch_fwd_mx(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M,
                          uint16_t* Y, int64_t ldy, const lq_fwd_debug* dbg, hipStream_t s);
+
+hipError_t launch_pack_mxi(const Dims& d, int residual_from_quantized, const float* W, const float* L,
+                           const float* R, uint8_t* packed, hipStream_t s);
+hipError_t launch_unpack_weights_mxi(const Dims& d, const uint8_t* packed, const lq_weights_view* out,
+                                     hipStream_t s);
+hipError_t launch_unpack_act_mxi(const Dims& d, const uint8_t* act, int64_t M, const lq_act_view* out,
+                                 hipStream_t s);
+hipError_t launch_quantize_act_mxi(const Dims& d, int x_dtype, const uint8_t* packed, const void* X,
+                                   int64_t M, int64_t ldx, uint8_t* act, const lq_act_debug* dbg,
+                                   hipStream_t s);
+hipError_t launch_fwd_mxi(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M,
+                          uint16_t* Y, int64_t ldy, const lq_fwd_debug* dbg, hipStream_t s);
 
 // ---- device helpers ----------------------------------------------------------------------
 #if defined(__HIPCC__)

@@ -27,6 +27,7 @@ class Layer:
     N: int
     r: int
     family: str            # "int" (INT4 main, integer branch) | "mx" (MXFP4 main, FP8 branch) | "mxb" (MXFP8e4 branch)
+                           # | "mxi" (MXINT4 main, MXINT8 branch activations, MXINT8 / MXINT4 branch weights)
     g: int                 # main weight group along K (INT: 64|128; MX: 32)
     br_w_bits: int         # branch weight width (INT: 8|6|4; MX: 8)
     br_a_bits: int         # branch activation width (INT: 8|6; MX: 8)
@@ -77,7 +78,13 @@ CFG5 = [_mx_layer("c5_qkv", 1152, 3456), _mx_layer("c5_attn_out", 1152, 1152),
 # The same seven layers with an MXFP8e4 (block-scaled E4M3) branch: the all-MX mixed-precision setting.
 CFG5B = [replace(l, name="c5b" + l.name[2:], family="mxb") for l in CFG5]
 
-CONFIGS: Dict[str, List[Layer]] = {"c1": CFG1, "c2": CFG2, "c3": CFG3, "c4": CFG4, "c5": CFG5, "c5b": CFG5B}
+# The same seven layers in the integer MX formats: MXINT4 main, MXINT8 branch of rank 64 (the pairing of
+# the paper's mixed-precision table for integer formats), and MXINT4 branch weights of rank 128.
+CFG5I = [replace(l, name="c5i" + l.name[2:], family="mxi", r=64) for l in CFG5]
+CFG5I4 = [replace(l, name="c5i4" + l.name[2:], family="mxi", r=128, br_w_bits=4) for l in CFG5]
+
+CONFIGS: Dict[str, List[Layer]] = {"c1": CFG1, "c2": CFG2, "c3": CFG3, "c4": CFG4, "c5": CFG5, "c5b": CFG5B,
+                                   "c5i": CFG5I, "c5i4": CFG5I4}
 LAYERS: Dict[str, Layer] = {l.name: l for ls in CONFIGS.values() for l in ls}
 
 

@@ -39,7 +39,7 @@ def run_gpu(layer, X, W, L, R, debug=True, debug_acc=True):
     Xd = to_dev_x(X, layer.x_dtype)
     packed = lq.lq_pack_weights(cfg, Wd, Ld, Rd)
     M = X.shape[0]
-    if debug and layer.family in ("mx", "mxb"):
+    if debug and layer.family in ("mx", "mxb", "mxi"):
         debug_acc = False
     if debug:
         act, adbg = lq.lq_quantize_act(cfg, packed, Xd, debug=True)

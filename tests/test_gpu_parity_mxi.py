@@ -1,0 +1,162 @@
+"""GPU parity, MXI family (MXINT4 main on the 8-bit scaled MFMA, MXINT8 / MXINT4 branch on the bf16
+MFMA; integer MX formats of App. A.3, integer rows of the tables of Section 4.3) against the CPU oracle.
+
+Bar: every code and E8M0 byte computed from source data (X, P, L, R) bit-exact; products are exact on
+both sides, so the only difference is the matrix core's fp32 accumulation across blocks against the
+oracle's fp64: the intermediate T and the output are bounded by 2^-13 of the sum of the magnitudes of
+their terms (the same bound as for the other block-scaled family), and are bit-exact where every
+partial sum is exactly representable (uniform block scales); the re-quantised intermediate must be a
+correct block quantisation of a value within that bound of the oracle's T.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_18117_amd import workloads as wl
+from tests.gpu_util import bf16_to_bits, n, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _vals(oracle, codes, ebytes, bits):
+    """|value| of MXINT elements: rows x (blocks x 32)."""
+    rows = codes.shape[0]
+    return (np.abs(codes.astype(np.float64)).reshape(rows, -1, 32) * oracle.mxint_scale(ebytes, bits)[:, :, None]).reshape(rows, -1)
+
+
+def _compare(oracle, layer, X, W, L, R, rows=None, exact=False):
+    g = run_gpu(layer, X, W, L, R, debug=True, debug_acc=False)
+    Xo = X if rows is None else X[rows]
+    sel = slice(None) if rows is None else rows
+    r, bw = layer.r, layer.br_w_bits
+    pk = oracle.pack_mxi(W, L if r else None, R if r else None, bw)
+    act = oracle.quantize_act_mxi(Xo, pk)
+    Mo = Xo.shape[0]
+    # ---- offline packing: exact
+    assert np.array_equal(n(g.wv.pq), pk.pq), "pq"
+    assert np.array_equal(n(g.wv.pe), pk.pe), "pe"
+    if r:
+        assert np.array_equal(n(g.wv.lq), pk.lq), "lq"
+        assert np.array_equal(n(g.wv.le), pk.le), "le"
+        assert np.array_equal(n(g.wv.rq), pk.rq), "rq"
+        assert np.array_equal(n(g.wv.re), pk.re), "re"
+    # ---- activation step: codes and block scales from X exact
+    assert np.array_equal(n(g.av.xq)[sel], act.xq), "xq"
+    assert np.array_equal(n(g.av.xe)[sel], act.xe), "xe"
+    tq_gpu = n(g.av.tq)[sel] if r else np.zeros((Mo, 0), np.int8)
+    te_gpu = n(g.av.te)[sel] if r else np.zeros((Mo, 0), np.uint8)
+    if r:
+        assert np.array_equal(n(g.adbg.xb)[sel], act.xb), "xb"
+        assert np.array_equal(n(g.adbg.xbe)[sel], act.xbe), "xbe"
+        T_gpu = n(g.adbg.T)[sel]
+        tb = 2.0 ** -13 * (_vals(oracle, act.xb, act.xbe, 8) @ _vals(oracle, pk.rq, pk.re, bw).T) + 1e-300
+        assert np.all(np.abs(T_gpu - act.T) <= tb), f"T max excess {np.max(np.abs(T_gpu - act.T) / tb)}"
+        ediff = te_gpu != act.te
+        assert ediff.mean() <= 1e-2, f"te mismatch rate {ediff.mean()}"
+        assert np.all(np.abs(te_gpu.astype(int) - act.te.astype(int)) <= 1)
+        # every GPU element is a correct saturating rounding, on the GPU's block grid, of a value within
+        # the accumulation bound of the oracle's T
+        step = np.repeat(oracle.mxint_scale(te_gpu, 8), 32, axis=1)
+        u = np.abs(act.T.astype(np.float64)) / step
+        half = np.where(u > 127.0, u - 127.0, 0.5 * (1 + 1e-9))
+        deq = tq_gpu.astype(np.float64) * step
+        assert np.abs(tq_gpu.astype(int)).max() <= 127
+        assert np.all(np.abs(deq - act.T) <= step * half + tb), "tq is not a block rounding of T"
+        same = ~ediff.repeat(32, axis=1)
+        diff = (tq_gpu != act.tq) & same
+        assert diff.mean() <= 1e-2, f"tq mismatch rate {diff.mean()}"
+        if exact:
+            assert np.array_equal(T_gpu, act.T) and np.array_equal(tq_gpu, act.tq) and np.array_equal(te_gpu, act.te)
+    # ---- forward: the oracle is fed the GPU's re-quantised intermediate
+    act_g = dataclasses.replace(act, tq=np.ascontiguousarray(tq_gpu), te=np.ascontiguousarray(te_gpu))
+    out = oracle.fwd_mxi(pk, act_g)
+    y_gpu = n(g.fdbg.y32)[sel]
+    A = _vals(oracle, act.xq, act.xe, 4) @ _vals(oracle, pk.pq, pk.pe, 4).T
+    if r:
+        A = A + _vals(oracle, tq_gpu, te_gpu, 8) @ _vals(oracle, pk.lq, pk.le, bw).T
+    bound = 2.0 ** -13 * A + 1e-300
+    assert np.all(np.abs(y_gpu - out.y32) <= bound), f"y32 max excess {np.max(np.abs(y_gpu - out.y32) / bound)}"
+    if exact:
+        assert np.array_equal(y_gpu, out.y32), "y32 (exactly representable partial sums)"
+    Yb = bf16_to_bits(g.Y)[sel]
+    want = ((y_gpu.view(np.uint32) + 0x7FFF + ((y_gpu.view(np.uint32) >> 16) & 1)) >> 16).astype(np.uint16)
+    assert np.array_equal(Yb, want), "Y is not bf16_rne(y32)"
+    Yf = oracle.bf16_bits_to_f32(Yb).astype(np.float64)
+    Yo = oracle.bf16_bits_to_f32(out.Y).astype(np.float64)
+    tau = 1e-3 * np.sqrt(np.mean(out.y32.astype(np.float64) ** 2)) + 1e-300
+    rel = np.abs(Yf - Yo) / np.maximum(np.abs(out.y32), tau)
+    flips = Yb != out.Y
+    assert flips.mean() <= 2e-3, f"bf16 flip rate {flips.mean()}"
+    assert np.all(rel[~flips] <= 2e-3)
+    assert np.all(rel[flips] <= 2.0 ** -7 * 1.01)
+    g2 = run_gpu(layer, X, W, L, R, debug=False)
+    assert torch.equal(g2.Y, g.Y)
+    return g
+
+
+SMALL = [
+    # M (ragged), K (multiple of 64), N (partial 256-wide tile), r (multiple of 32), branch weight bits, x_dtype
+    (300, 256, 320, 32, 8, "bf16"),
+    (77, 320, 64, 32, 4, "f32"),
+    (130, 1152, 192, 64, 8, "bf16"),
+    (64, 64, 64, 0, 8, "bf16"),
+    (33, 704, 128, 128, 4, "bf16"),
+    (1, 128, 64, 32, 8, "f32"),
+    (257, 576, 512, 64, 8, "bf16"),
+]
+
+
+@pytest.mark.parametrize("M,K,N,r,bw,xd", SMALL)
+def test_small_shapes(oracle, M, K, N, r, bw, xd):
+    layer = wl.Layer("t", M, K, N, r, "mxi", 32, bw, 8, xd, seed=M + K)
+    X, W, L, R = wl.make_inputs(layer)
+    _compare(oracle, layer, X, W, L, R)
+
+
+def test_uniform_scales_are_bit_exact(oracle):
+    """All blocks share one scale per operand and every partial sum stays below 2^24 code units:
+    the fp32 accumulators hold the integer contractions exactly, so nothing may differ."""
+    M, K, N, r = 96, 384, 128, 32
+    layer = wl.Layer("t", M, K, N, r, "mxi", 32, 8, 8, "bf16", seed=11)
+    rng = np.random.default_rng(11)
+    X = (rng.integers(-7, 8, size=(M, K)) / 4.0).astype(np.float32); X[:, 0::32] = 1.75
+    W = (rng.integers(-7, 8, size=(N, K)) / 64.0).astype(np.float32); W[:, 1::32] = 7 / 64.0
+    R = (rng.integers(-3, 4, size=(r, K)) / 256.0).astype(np.float32); R[:, 2::32] = 1 / 64.0
+    L = np.zeros((N, r), np.float32); L[:, 0] = rng.integers(-5, 6, size=N) / 16.0; L[:, 5] = 1.0
+    _compare(oracle, layer, X, W, L, R, exact=True)
+
+
+def test_degenerate_inputs(oracle):
+    layer = wl.Layer("t", 70, 256, 64, 32, "mxi", 32, 8, 8, "bf16", seed=3)
+    X, W, L, R = wl.make_inputs(layer)
+    X[3] = 0.0
+    X[5, :] = 0.0
+    X[5, 7] = -2.0
+    X[9, 32:64] = 0.0
+    W[2] = 0.0
+    W[4, 64:96] = 0.0
+    L[4] = 0.0
+    R[1] = 0.0
+    _compare(oracle, layer, X, W, L, R)
+    _compare(oracle, layer, np.zeros_like(X), W, L, R)
+
+
+def test_wide_dynamic_range_blocks(oracle):
+    layer = wl.Layer("t", 64, 256, 64, 32, "mxi", 32, 8, 8, "bf16", seed=5)
+    X, W, L, R = wl.make_inputs(layer)
+    rng = np.random.default_rng(7)
+    X *= wl.round_to_bf16(np.exp2(rng.integers(-20, 20, size=(64, 8)).repeat(32, axis=1)).astype(np.float32))
+    W *= np.exp2(rng.integers(-10, 10, size=(64, 8)).repeat(32, axis=1)).astype(np.float32)
+    R *= np.exp2(rng.integers(-6, 6, size=(32, 8)).repeat(32, axis=1)).astype(np.float32)
+    _compare(oracle, layer, wl.round_to_bf16(X), W, L, R)
+
+
+@pytest.mark.parametrize("name", ["c5i_qkv", "c5i_fc2", "c5i4_attn_out"])
+def test_full_size_sampled_rows(oracle, name):
+    layer = wl.LAYERS[name]
+    X, W, L, R = wl.make_inputs(layer)
+    rng = np.random.default_rng(1)
+    rows = np.sort(np.concatenate([[0, layer.M - 1], rng.choice(layer.M, 14, replace=False)]))
+    _compare(oracle, layer, X, W, L, R, rows=rows)
