@@ -256,7 +256,8 @@ hipError_t launch_unpack_act_mxi(const Dims& d, const uint8_t* act, int64_t M, c
 // ---------------------------------------------------------------------------------------------
 // activation kernel.  Same decomposition as the other families (16 token rows per workgroup, lane =
 // (row l%16, 16-value quarter l/16 of each 64-chunk), chunks dealt round-robin to 4 wavefronts), but
-// every scale is local to a block of 32, so there is no pass over the whole row before coding.
+// every scale is local to a block of 32, so there is no pass over the whole row before coding: the row
+// is streamed through a few chunk slots and K is not limited by the register file.
 // ---------------------------------------------------------------------------------------------
 struct MxiActParams {
     const void* X;
@@ -327,10 +328,11 @@ __device__ __forceinline__ uint32_t bf16_pair(float lo, float hi)  // upper halv
     return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
 }
 
-template <bool BF16, int MAXC, int NJB>
+template <bool BF16, int NJB>
 __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
 {
     constexpr int NJA = NJB > 0 ? NJB : 1;
+    constexpr int PF = 2;  // 64-chunks in flight per wavefront (measured: 2 beats 4, 6, 8 -- fewer registers, more resident workgroups)
     __shared__ float s_acc[4][NJA][64][4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -338,13 +340,14 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
     const int row = blockIdx.x * 16 + r16;
     const bool row_ok = row < p.M;
     const int C64 = p.C64;
+    const int nmy = (C64 - wave + 3) >> 2;  // chunks of this wavefront: c = wave + 4 * ci, ci < nmy
 
-    MxiChunk<BF16> xc[MAXC];
+    // No scale spans more than a block of 32, so the row is streamed: PF chunks are in flight, a slot
+    // is refilled as soon as its chunk has been coded.
+    MxiChunk<BF16> xc[PF];
 #pragma unroll
-    for (int ci = 0; ci < MAXC; ++ci) {
-        const int c = wave + 4 * ci;
-        xc[ci].load(p.X, (size_t)row * p.ldx + (size_t)c * 64 + kq * 16, row_ok && c < C64);
-    }
+    for (int i = 0; i < PF; ++i)
+        xc[i].load(p.X, (size_t)row * p.ldx + (size_t)(wave + 4 * i) * 64 + kq * 16, row_ok && i < nmy);
     // dequantised R fragments (bf16): first chunk now, later ones one chunk ahead
     v4i bvs[2][NJA][2];
     auto load_r = [&](int slot, int ci) {
@@ -362,22 +365,24 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
 #pragma unroll
     for (int jb = 0; jb < NJB; ++jb) acc[jb] = v4f{0.f, 0.f, 0.f, 0.f};
 
+    for (int base = 0; base < nmy; base += PF) {
 #pragma unroll
-    for (int ci = 0; ci < MAXC; ++ci) {
+    for (int sl = 0; sl < PF; ++sl) {
+        const int ci = base + sl;
         const int c = wave + 4 * ci;
-        if (ci + 1 < MAXC) load_r((ci + 1) & 1, ci + 1);
-        if (c < C64) {  // wave-uniform
+        load_r((sl + 1) & 1, ci + 1);
+        if (ci < nmy) {  // wave-uniform
             float m = 0.f;
             if constexpr (BF16) {
                 // |bf16| is monotonic in its low 15 bits: packed unsigned 16-bit max, two values per op
                 us2 m2 = {0, 0};
 #pragma unroll
-                for (int d = 0; d < 8; ++d) m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, xc[ci].w[d] & 0x7FFF7FFFu));
+                for (int d = 0; d < 8; ++d) m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, xc[sl].w[d] & 0x7FFF7FFFu));
                 const uint32_t mm = m2[0] > m2[1] ? m2[0] : m2[1];
                 m = __uint_as_float(mm << 16);
             } else {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(xc[ci].get(i)));
+                for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(xc[sl].get(i)));
             }
             const float ab = fmaxf(m, __shfl_xor(m, 16, 64));  // block of 32 = lanes kq, kq ^ 1
             const uint32_t field = exp_field(ab);
@@ -393,12 +398,12 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
                     uint32_t sum = 0u - 0xFB000000u;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        const float x = xc[ci].get(8 * h + e);
+                        const float x = xc[sl].get(8 * h + e);
                         const uint32_t mb = __float_as_uint(__fadd_rn(fminf(__fmul_rn(fabsf(x), inv4), 7.0f), 8388608.0f));
                         const int sh = e < 4 ? 8 * e : 8 * ((e - 5) & 3) + 4;
                         sum += mb << sh;
                     }
-                    const uint32_t* w = &xc[ci].w[4 * h];
+                    const uint32_t* w = &xc[sl].w[4 * h];
                     const uint32_t s03 = __builtin_amdgcn_perm(w[1], w[0], 0x07050301u);
                     const uint32_t s47 = __builtin_amdgcn_perm(w[3], w[2], 0x07050301u);
                     pk[h] = sum | (s03 & 0x80808080u) | ((s47 >> 4) & 0x08080808u);
@@ -406,7 +411,7 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
             } else {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const float x = xc[ci].get(i);
+                    const float x = xc[sl].get(i);
                     const uint32_t mg = __float_as_uint(__fadd_rn(fminf(__fmul_rn(fabsf(x), inv4), 7.0f), 8388608.0f)) & 7u;
                     pk[i >> 3] |= nib_put(i & 7, __float_as_uint(x) >> 31, mg);
                 }
@@ -419,7 +424,7 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
                 // ---- branch: MXINT8 of the same block, kept as dequantised bf16
                 float v8[16];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) v8[i] = mxint8_round(xc[ci].get(i), field);
+                for (int i = 0; i < 16; ++i) v8[i] = mxint8_round(xc[sl].get(i), field);
                 v4i au[2];
 #pragma unroll
                 for (int u = 0; u < 2; ++u)
@@ -438,12 +443,16 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
 #pragma unroll
                     for (int u = 0; u < 2; ++u)
                         acc[jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, au[u]),
-                                                                         __builtin_bit_cast(v8bf, bvs[ci & 1][jb][u]), acc[jb], 0, 0, 0);
+                                                                         __builtin_bit_cast(v8bf, bvs[sl & 1][jb][u]), acc[jb], 0, 0, 0);
             }
-        } else if (c < 4 * p.CQ) {
-            // padding chunk of the last quad: its scale bytes must be valid E8M0 values (2^0)
-            if ((kq & 1) == 0) p.xe[mxi_scale_offset(row, c, kq >> 1, p.CQ)] = (uint8_t)127;
         }
+        // refill the slot with the chunk PF positions further on
+        xc[sl].load(p.X, (size_t)row * p.ldx + (size_t)(c + 4 * PF) * 64 + kq * 16, row_ok && ci + PF < nmy);
+    }
+    }
+    {   // padding chunk of the last quad (at most one per wavefront): its scale bytes must be valid E8M0 values (2^0)
+        const int c = wave + 4 * nmy;
+        if (c < 4 * p.CQ && (kq & 1) == 0) p.xe[mxi_scale_offset(row, c, kq >> 1, p.CQ)] = (uint8_t)127;
     }
     if (NJB == 0) return;
 
@@ -491,20 +500,20 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
     }
 }
 
-template <bool BF16, int MAXC, int NJB>
+template <bool BF16, int NJB>
 static hipError_t mxi_act_launch(const MxiActParams& p, int64_t Mp, hipStream_t s)
 {
-    hipLaunchKernelGGL((mxi_act_kernel<BF16, MAXC, NJB>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((mxi_act_kernel<BF16, NJB>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
     return hipGetLastError();
 }
-template <bool BF16, int MAXC>
+template <bool BF16>
 static hipError_t mxi_act_rank(const MxiActParams& p, int64_t Mp, hipStream_t s)
 {
     switch (p.r) {
-        case 0: return mxi_act_launch<BF16, MAXC, 0>(p, Mp, s);
-        case 32: return mxi_act_launch<BF16, MAXC, 2>(p, Mp, s);
-        case 64: return mxi_act_launch<BF16, MAXC, 4>(p, Mp, s);
-        default: return mxi_act_launch<BF16, MAXC, 8>(p, Mp, s);
+        case 0: return mxi_act_launch<BF16, 0>(p, Mp, s);
+        case 32: return mxi_act_launch<BF16, 2>(p, Mp, s);
+        case 64: return mxi_act_launch<BF16, 4>(p, Mp, s);
+        default: return mxi_act_launch<BF16, 8>(p, Mp, s);
     }
 }
 
@@ -530,14 +539,7 @@ hipError_t launch_quantize_act_mxi(const Dims& d, int x_dtype, const uint8_t* pa
     p.dbg_xb = dbg ? dbg->xb : nullptr;
     p.dbg_xbe = dbg ? dbg->xbe : nullptr;
     p.dbg_T = dbg ? dbg->T : nullptr;
-    const int maxc = (d.C64 + 3) / 4;
-    if (x_dtype == LQ_BF16) {
-        if (maxc <= 5) return mxi_act_rank<true, 5>(p, al.Mp, s);
-        if (maxc <= 9) return mxi_act_rank<true, 9>(p, al.Mp, s);
-        return mxi_act_rank<true, 18>(p, al.Mp, s);
-    }
-    if (maxc <= 5) return mxi_act_rank<false, 5>(p, al.Mp, s);
-    return mxi_act_rank<false, 9>(p, al.Mp, s);
+    return x_dtype == LQ_BF16 ? mxi_act_rank<true>(p, al.Mp, s) : mxi_act_rank<false>(p, al.Mp, s);
 }
 
 // ---------------------------------------------------------------------------------------------

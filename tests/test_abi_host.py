@@ -123,6 +123,31 @@ def test_argument_errors_before_any_launch(lq):
     # K beyond the register-resident row of the activation kernel
     big = _cfg(lq, K=8192)
     assert raw.lq_quantize_act(C.byref(big), good, good, 64, 8192, good, 1 << 30, None, None) == lq.LQ_ERR_UNSUPPORTED
+    big = _cfg(lq, K=8192, family="mx")
+    assert raw.lq_quantize_act(C.byref(big), good, good, 64, 8192, good, 1 << 30, None, None) == lq.LQ_ERR_UNSUPPORTED
+
+
+def test_mxi_contract(lq):
+    n = C.c_size_t(0)
+    raw = lq.raw()
+    assert raw.lq_packed_sizes(C.byref(_cfg(lq, family="mxi", K=192)), C.byref(n)) == lq.LQ_OK     # K % 64 only
+    assert raw.lq_packed_sizes(C.byref(_cfg(lq, family="mxi", rank=16)), C.byref(n)) == lq.LQ_ERR_SHAPE
+    assert raw.lq_packed_sizes(C.byref(_cfg(lq, family="mxi", br_w_bits=4, rank=128)), C.byref(n)) == lq.LQ_OK
+    cfg = _cfg(lq, family="mxi")
+    cfg.br_a = lq.LQ_MXINT4          # branch activations stay at 8 bits
+    assert raw.lq_packed_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    cfg = _cfg(lq, family="mxi")
+    cfg.main_a = lq.LQ_MXFP4_E2M1    # no mixing of integer and floating-point formats within a layer (Section 4.1)
+    assert raw.lq_packed_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    # 4-bit codes N*K/2, scale dwords per (32 rows, quad of chunks, lane), bf16 factors with one byte per block
+    cfg = lq.make_config(3456, 1152, 64, "mxi")
+    parts = [3456 * 1152 // 2, 3456 // 32 * 5 * 256, 3456 * 64 * 2, 3456 * 2 + 4, 64 * 1152 * 2, 64 * 36 + 4]
+    assert lq.lq_packed_sizes(cfg) == sum((x + 255) // 256 * 256 for x in parts)
+    # the block-local scales need no register-resident row: K is not limited
+    good = C.c_void_p(1 << 20)
+    big = _cfg(lq, family="mxi", K=8192)
+    assert raw.lq_quantize_act(C.byref(big), good, good, 64, 8000, good, 1 << 30, None, None) == lq.LQ_ERR_SHAPE
+    assert raw.lq_act_sizes(C.byref(big), 64, C.byref(n)) == lq.LQ_OK
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -105,6 +105,8 @@ SMALL = [
     (33, 704, 128, 128, 4, "bf16"),
     (1, 128, 64, 32, 8, "f32"),
     (257, 576, 512, 64, 8, "bf16"),
+    (40, 5120, 64, 32, 8, "bf16"),      # K beyond what the row-resident activation kernels of the other families take
+    (18, 2368, 64, 64, 4, "f32"),
 ]
 
 
