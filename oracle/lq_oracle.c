@@ -23,6 +23,8 @@
  *          contraction axis, E8M0 scale) for X, R, the intermediate X R^T and L, i.e. the
  *          all-MX setting of the paper's mixed-precision tables (Section 4.3); no fp32
  *          scale anywhere; the two branches are summed in fp64 and rounded once.
+ *   MXB6 : as MXB with MXFP6e2 elements (App. A.3: E2M3, 1 sign + 2 exponent + 3 mantissa bits,
+ *          bias 1, largest magnitude 7.5) in place of E4M3; scale exponent floor(log2 amax) - 2.
  *   MXI  : Q1 = MXINT4 for both operands of the main product, Q2 = MXINT8 for the branch
  *          activations and the intermediate, MXINT8 or MXINT4 for L and R (App. A.3: "signed
  *          int4 and int8" elements, blocks of 32, E8M0 scale; the integer rows of the
@@ -721,6 +723,164 @@ LQO_API void lqo_fwd_mxi(int64_t M, int64_t N, int64_t K, int r, int bw_bits, co
             if (Y) Y[m * N + n] = bf16_rne(y);
         }
     }
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* MXB6 family: block-scaled FP6 (E2M3) branch                                            */
+/* ------------------------------------------------------------------------------------ */
+
+/* E2M3: 1 sign, 2 exponent (bias 1), 3 mantissa bits; no Inf / NaN; largest magnitude 7.5.
+   code = s ee mmm (6 bits). */
+LQO_API float lqo_e2m3_decode(uint8_t code)
+{
+    int s = (code >> 5) & 1, e = (code >> 3) & 3, m = code & 7;
+    float mag;
+    if (e == 0)
+        mag = (float)m / 8.0f; /* subnormal: m/8 * 2^(1-1) */
+    else
+        mag = ldexpf(1.0f + (float)m / 8.0f, e - 1);
+    return s ? -mag : mag;
+}
+
+LQO_API uint8_t lqo_e2m3_encode(float u)
+{
+    float table[32];
+    for (int c = 0; c < 32; ++c) table[c] = lqo_e2m3_decode((uint8_t)c);
+    int s = signbit(u) ? 1 : 0;
+    int c = nearest_code(fabsf(u), table, 32);
+    return (uint8_t)((s << 5) | c);
+}
+
+/* MXFP6e2: n values (a multiple of 32) in blocks of 32; one E8M0 byte per block; E2M3 codes. */
+LQO_API void lqo_quant_mxfp6(const float *v, int64_t n, uint8_t *codes, uint8_t *e8m0)
+{
+    for (int64_t b = 0; b < n / 32; ++b) {
+        const float *blk = v + 32 * b;
+        float a = absmax_f32(blk, 32);
+        int e;
+        if (a == 0.0f) {
+            e = -127;
+        } else {
+            int ex;
+            (void)frexpf(a, &ex); /* floor(log2 a) = ex - 1 */
+            e = (ex - 1) - 2;     /* 2 = largest E2M3 exponent */
+            if (e < -127) e = -127;
+            if (e > 127) e = 127;
+        }
+        e8m0[b] = (uint8_t)(e + 127);
+        for (int i = 0; i < 32; ++i) codes[32 * b + i] = lqo_e2m3_encode(ldexpf(blk[i], -e));
+    }
+}
+
+static double mxfp6_value(uint8_t code, uint8_t e8m0)
+{
+    return (double)lqo_e2m3_decode(code) * lqo_e8m0_decode(e8m0);
+}
+
+/* Outputs as lqo_pack_mxb, with E2M3 codes (one per byte) for the factors. */
+LQO_API void lqo_pack_mxb6(int64_t N, int64_t K, int r, int residual_from_quantized,
+                           const float *W, const float *L, const float *R, uint8_t *pc,
+                           uint8_t *pe, uint8_t *l6, uint8_t *le, uint8_t *r6, uint8_t *re,
+                           float *P_out)
+{
+    const int64_t BK = K / 32;
+    const int BR = r / 32;
+    for (int j = 0; j < r; ++j) lqo_quant_mxfp6(R + (int64_t)j * K, K, r6 + (int64_t)j * K, re + (int64_t)j * BK);
+    for (int64_t n = 0; n < N; ++n) lqo_quant_mxfp6(L + n * r, r, l6 + n * r, le + n * BR);
+
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        float *P = (float *)malloc(sizeof(float) * (size_t)K);
+        for (int64_t k = 0; k < K; ++k) {
+            double d = 0.0;
+            for (int j = 0; j < r; ++j) {
+                double lh, rh;
+                if (residual_from_quantized) {
+                    lh = mxfp6_value(l6[n * r + j], le[n * BR + j / 32]);
+                    rh = mxfp6_value(r6[(int64_t)j * K + k], re[(int64_t)j * BK + k / 32]);
+                } else {
+                    lh = L[n * r + j];
+                    rh = R[(int64_t)j * K + k];
+                }
+                d += lh * rh;
+            }
+            P[k] = (float)((double)W[n * K + k] - d);
+        }
+        lqo_quant_mxfp4(P, K, pc + n * K, pe + n * BK);
+        if (P_out) memcpy(P_out + n * K, P, sizeof(float) * (size_t)K);
+        free(P);
+    }
+}
+
+/* Outputs as lqo_quantize_act_mxb, with E2M3 codes for the branch activations and the intermediate. */
+LQO_API void lqo_quantize_act_mxb6(int64_t M, int64_t K, int r, const float *X, const uint8_t *r6,
+                                   const uint8_t *re, uint8_t *xc, uint8_t *xe, uint8_t *xb6,
+                                   uint8_t *xbe, float *T, uint8_t *tq6, uint8_t *te)
+{
+    const int64_t BK = K / 32;
+    const int BR = r / 32;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const float *x = X + m * K;
+        lqo_quant_mxfp4(x, K, xc + m * K, xe + m * BK);
+        if (r == 0) continue;
+        lqo_quant_mxfp6(x, K, xb6 + m * K, xbe + m * BK);
+        float *Trow = (float *)malloc(sizeof(float) * (size_t)r);
+        for (int j = 0; j < r; ++j) {
+            double a = 0.0;
+            for (int64_t b = 0; b < BK; ++b) {
+                double d = 0.0;
+                for (int k = 0; k < 32; ++k)
+                    d += (double)lqo_e2m3_decode(xb6[m * K + 32 * b + k]) *
+                         (double)lqo_e2m3_decode(r6[(int64_t)j * K + 32 * b + k]);
+                a += lqo_e8m0_decode(xbe[m * BK + b]) * lqo_e8m0_decode(re[(int64_t)j * BK + b]) * d;
+            }
+            Trow[j] = (float)a;
+        }
+        lqo_quant_mxfp6(Trow, r, tq6 + m * r, te + m * BR);
+        if (T) memcpy(T + m * r, Trow, sizeof(float) * (size_t)r);
+        free(Trow);
+    }
+}
+
+LQO_API void lqo_fwd_mxb6(int64_t M, int64_t N, int64_t K, int r, const uint8_t *xc,
+                          const uint8_t *xe, const uint8_t *pc, const uint8_t *pe,
+                          const uint8_t *tq6, const uint8_t *te, const uint8_t *l6,
+                          const uint8_t *le, float *ymain, float *ybr, float *y32, uint16_t *Y)
+{
+    const int64_t B = K / 32;
+    const int BR = r / 32;
+    float *vw = (float *)malloc(sizeof(float) * (size_t)(N * K));
+    for (int64_t i = 0; i < N * K; ++i) vw[i] = lqo_e2m1_decode(pc[i]);
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        float *vx = (float *)malloc(sizeof(float) * (size_t)K);
+        for (int64_t k = 0; k < K; ++k) vx[k] = lqo_e2m1_decode(xc[m * K + k]);
+        for (int64_t n = 0; n < N; ++n) {
+            double t = 0.0;
+            for (int64_t b = 0; b < B; ++b) {
+                double d = 0.0;
+                for (int k = 0; k < 32; ++k)
+                    d += (double)vx[32 * b + k] * (double)vw[n * K + 32 * b + k];
+                t += lqo_e8m0_decode(xe[m * B + b]) * lqo_e8m0_decode(pe[n * B + b]) * d;
+            }
+            double u = 0.0;
+            for (int b = 0; b < BR; ++b) {
+                double d = 0.0;
+                for (int j = 0; j < 32; ++j)
+                    d += (double)lqo_e2m3_decode(tq6[m * r + 32 * b + j]) *
+                         (double)lqo_e2m3_decode(l6[n * r + 32 * b + j]);
+                u += lqo_e8m0_decode(te[m * BR + b]) * lqo_e8m0_decode(le[n * BR + b]) * d;
+            }
+            float y = (float)(t + u); /* sum node of Fig. 1: both accumulators, one rounding */
+            if (ymain) ymain[m * N + n] = (float)t;
+            if (ybr) ybr[m * N + n] = (float)u;
+            if (y32) y32[m * N + n] = y;
+            if (Y) Y[m * N + n] = bf16_rne(y);
+        }
+        free(vx);
+    }
+    free(vw);
 }
 
 LQO_API int lqo_num_threads(void)

@@ -32,6 +32,10 @@ def lib():
         _lib.lqo_e4m3_decode.argtypes = [C.c_uint8]
         _lib.lqo_e8m0_decode.restype = C.c_double
         _lib.lqo_e8m0_decode.argtypes = [C.c_uint8]
+        _lib.lqo_e2m3_decode.restype = C.c_float
+        _lib.lqo_e2m3_decode.argtypes = [C.c_uint8]
+        _lib.lqo_e2m3_encode.restype = C.c_uint8
+        _lib.lqo_e2m3_encode.argtypes = [C.c_float]
         _lib.lqo_e2m1_encode.restype = C.c_uint8
         _lib.lqo_e2m1_encode.argtypes = [C.c_float]
         _lib.lqo_e4m3_encode.restype = C.c_uint8
@@ -99,6 +103,15 @@ def e2m1_decode(codes):
 def e4m3_decode(codes):
     return np.array([lib().lqo_e4m3_decode(int(c)) for c in np.asarray(codes).ravel()],
                     np.float32).reshape(np.shape(codes))
+
+
+def e2m3_decode(codes):
+    codes = np.asarray(codes, np.uint8)
+    return np.array([lib().lqo_e2m3_decode(int(c) & 63) for c in codes.ravel()], np.float32).reshape(codes.shape)
+
+
+def e2m3_encode(u: float) -> int:
+    return int(lib().lqo_e2m3_encode(float(u)))
 
 
 def e8m0_decode(codes):
@@ -295,6 +308,20 @@ def quant_mxfp8(v):
     return codes, e
 
 
+def quant_mxfp6(v):
+    v = _f32(v).ravel()
+    assert v.size % 32 == 0
+    codes = np.empty(v.size, np.uint8)
+    e = np.empty(v.size // 32, np.uint8)
+    lib().lqo_quant_mxfp6(_p(v), C.c_int64(v.size), _p(codes), _p(e))
+    return codes, e
+
+
+def mxb_decode(codes, elem: int):
+    """Element values of a block-scaled FP branch: E4M3 (elem 8) or E2M3 (elem 6)."""
+    return e4m3_decode(codes) if elem == 8 else e2m3_decode(codes)
+
+
 @dataclass
 class PackedMxb:
     N: int
@@ -307,9 +334,10 @@ class PackedMxb:
     r8: np.ndarray   # r x K uint8 E4M3
     re: np.ndarray   # r x K/32 uint8 E8M0
     P: np.ndarray
+    elem: int = 8    # 8: E4M3 elements (MXFP8e4); 6: E2M3 elements (MXFP6e2), same field names
 
 
-def pack_mxb(W, L, R, residual_from_quantized: bool = True) -> PackedMxb:
+def pack_mxb(W, L, R, residual_from_quantized: bool = True, elem: int = 8) -> PackedMxb:
     W = _f32(W)
     N, K = W.shape
     r = 0 if L is None else int(np.shape(L)[1])
@@ -318,8 +346,8 @@ def pack_mxb(W, L, R, residual_from_quantized: bool = True) -> PackedMxb:
     Rc = _f32(R) if r else np.zeros((0, K), np.float32)
     out = PackedMxb(N, K, r, np.empty((N, K), np.uint8), np.empty((N, K // 32), np.uint8),
                     np.empty((N, r), np.uint8), np.empty((N, r // 32), np.uint8),
-                    np.empty((r, K), np.uint8), np.empty((r, K // 32), np.uint8), np.empty((N, K), np.float32))
-    lib().lqo_pack_mxb(C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(1 if residual_from_quantized else 0),
+                    np.empty((r, K), np.uint8), np.empty((r, K // 32), np.uint8), np.empty((N, K), np.float32), elem)
+    (lib().lqo_pack_mxb if elem == 8 else lib().lqo_pack_mxb6)(C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(1 if residual_from_quantized else 0),
                        _p(W), _p(Lc), _p(Rc), _p(out.pc), _p(out.pe), _p(out.l8), _p(out.le), _p(out.r8),
                        _p(out.re), _p(out.P))
     return out
@@ -344,7 +372,7 @@ def quantize_act_mxb(X, pk: PackedMxb) -> ActMxb:
     out = ActMxb(M, np.empty((M, K), np.uint8), np.empty((M, K // 32), np.uint8), np.zeros((M, K), np.uint8),
                  np.zeros((M, K // 32), np.uint8), np.zeros((M, r), np.float32), np.zeros((M, r), np.uint8),
                  np.zeros((M, r // 32), np.uint8))
-    lib().lqo_quantize_act_mxb(C.c_int64(M), C.c_int64(K), C.c_int(r), _p(X), _p(pk.r8), _p(pk.re),
+    (lib().lqo_quantize_act_mxb if pk.elem == 8 else lib().lqo_quantize_act_mxb6)(C.c_int64(M), C.c_int64(K), C.c_int(r), _p(X), _p(pk.r8), _p(pk.re),
                                _p(out.xc), _p(out.xe), _p(out.xb8), _p(out.xbe), _p(out.T), _p(out.tq8),
                                _p(out.te))
     return out
@@ -354,7 +382,7 @@ def fwd_mxb(pk: PackedMxb, act: ActMxb) -> FwdOut:
     M, N, K, r = act.M, pk.N, pk.K, pk.r
     out = FwdOut(None, None, np.empty((M, N), np.float32), np.empty((M, N), np.float32),
                  np.empty((M, N), np.float32), np.empty((M, N), np.uint16))
-    lib().lqo_fwd_mxb(C.c_int64(M), C.c_int64(N), C.c_int64(K), C.c_int(r), _p(act.xc), _p(act.xe),
+    (lib().lqo_fwd_mxb if pk.elem == 8 else lib().lqo_fwd_mxb6)(C.c_int64(M), C.c_int64(N), C.c_int64(K), C.c_int(r), _p(act.xc), _p(act.xe),
                       _p(pk.pc), _p(pk.pe), _p(act.tq8), _p(act.te), _p(pk.l8), _p(pk.le),
                       _p(out.ymain), _p(out.ybr), _p(out.y32), _p(out.Y))
     return out

@@ -17,7 +17,7 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "ocp_mx_element_forma
 
 
 def _golden():
-    out = {"e2m1": None, "e4m3": [], "e8m0": [], "budget": [], "mxint": {}}
+    out = {"e2m1": None, "e2m3": None, "e4m3": [], "e8m0": [], "budget": [], "mxint": {}}
     for line in open(GOLDEN):
         line = line.strip()
         if not line or line.startswith("#"):
@@ -25,6 +25,8 @@ def _golden():
         t = line.split()
         if t[0] == "e2m1":
             out["e2m1"] = [float(v) for v in t[1:]]
+        elif t[0] == "e2m3":
+            out["e2m3"] = [float(v) for v in t[1:]]
         elif t[0] == "e4m3":
             out["e4m3"].append((int(t[1], 16), float(t[2])))
         elif t[0] == "e8m0":
@@ -576,21 +578,23 @@ def test_mxfp8_block_scale_nearest_and_idempotent(oracle):
     assert np.array_equal(codes3[nz], codes[nz]) and np.array_equal(e3[e > 0].astype(int), e[e > 0].astype(int) + 5)
 
 
-def test_mxb_forward_against_exact_rationals(oracle):
+@pytest.mark.parametrize("elem", [8, 6])
+def test_mxb_forward_against_exact_rationals(oracle, elem):
     rng = np.random.default_rng(22)
+    quant = oracle.quant_mxfp8 if elem == 8 else oracle.quant_mxfp6
     M, K, N, r = 4, 64, 5, 32
     X = wl.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
     W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
     L = (rng.standard_normal((N, r)) * 3e-2).astype(np.float32)
     R = (rng.standard_normal((r, K)) * 3e-2).astype(np.float32)
-    pk = oracle.pack_mxb(W, L, R)
+    pk = oracle.pack_mxb(W, L, R, elem=elem)
     act = oracle.quantize_act_mxb(X, pk)
     out = oracle.fwd_mxb(pk, act)
     F = Fraction
     f = lambda a: F(float(a))
     vx, vw = oracle.e2m1_decode(act.xc), oracle.e2m1_decode(pk.pc)
     sx, sw = oracle.e8m0_decode(act.xe), oracle.e8m0_decode(pk.pe)
-    x8, r8, t8, l8 = (oracle.e4m3_decode(c) for c in (act.xb8, pk.r8, act.tq8, pk.l8))
+    x8, r8, t8, l8 = (oracle.mxb_decode(c, elem) for c in (act.xb8, pk.r8, act.tq8, pk.l8))
     xbe, re, te, le = (oracle.e8m0_decode(c) for c in (act.xbe, pk.re, act.te, pk.le))
     # residual: P = fl(W - sum_j Lhat Rhat) from the dequantised factors (Fig. 1), exact in rationals
     for n in range(N):
@@ -598,9 +602,9 @@ def test_mxb_forward_against_exact_rationals(oracle):
             d = sum(f(l8[n, j]) * f(le[n, j // 32]) * f(r8[j, k]) * f(re[j, k // 32]) for j in range(r))
             assert pk.P[n, k] == np.float32(float(f(W[n, k]) - d))
     # the factors' codes are the block quantiser applied to their rows
-    c, e = oracle.quant_mxfp8(R[3]); assert np.array_equal(c, pk.r8[3]) and np.array_equal(e, pk.re[3])
-    c, e = oracle.quant_mxfp8(L[2]); assert np.array_equal(c, pk.l8[2]) and np.array_equal(e, pk.le[2])
-    c, e = oracle.quant_mxfp8(X[1]); assert np.array_equal(c, act.xb8[1]) and np.array_equal(e, act.xbe[1])
+    c, e = quant(R[3]); assert np.array_equal(c, pk.r8[3]) and np.array_equal(e, pk.re[3])
+    c, e = quant(L[2]); assert np.array_equal(c, pk.l8[2]) and np.array_equal(e, pk.le[2])
+    c, e = quant(X[1]); assert np.array_equal(c, act.xb8[1]) and np.array_equal(e, act.xbe[1])
     for m in range(M):
         Tex = []
         for j in range(r):
@@ -608,7 +612,7 @@ def test_mxb_forward_against_exact_rationals(oracle):
                     for b in range(K // 32))
             assert act.T[m, j] == np.float32(float(T))               # one rounding of the exact contraction
             Tex.append(T)
-        c, e = oracle.quant_mxfp8(act.T[m]); assert np.array_equal(c, act.tq8[m]) and np.array_equal(e, act.te[m])
+        c, e = quant(act.T[m]); assert np.array_equal(c, act.tq8[m]) and np.array_equal(e, act.te[m])
         for n in range(N):
             main = sum(f(sx[m, b]) * f(sw[n, b]) * sum(f(vx[m, 32 * b + k]) * f(vw[n, 32 * b + k]) for k in range(32))
                        for b in range(K // 32))
@@ -617,9 +621,49 @@ def test_mxb_forward_against_exact_rationals(oracle):
             assert out.ymain[m, n] == np.float32(float(main)) and out.ybr[m, n] == np.float32(float(br))
             assert out.y32[m, n] == np.float32(float(main + br))     # both accumulators, one rounding
             assert out.Y[m, n] == oracle.bf16_rne(float(out.y32[m, n]))
-    # the branch approximates X R^T L^T: block-FP8 relative error 2^-4 per factor
+    # the branch approximates X R^T L^T: relative error 2^-4 per factor and element (both formats keep
+    # 3 mantissa bits; E2M3's narrow exponent range adds absolute error on the small elements of a block)
     ref = X.astype(np.float64) @ R.astype(np.float64).T @ L.astype(np.float64).T
-    assert np.abs(out.ybr - ref).max() <= 0.2 * np.abs(ref).max()
+    assert np.abs(out.ybr - ref).max() <= (0.2 if elem == 8 else 0.3) * np.abs(ref).max()
+
+
+def test_e2m3_table_rounding_and_block_scale(oracle):
+    g = _golden()
+    dec = oracle.e2m3_decode(np.arange(64, dtype=np.uint8))
+    assert list(dec[:32]) == g["e2m3"] and list(dec[32:]) == [-v if v else -0.0 for v in g["e2m3"]]
+    tab = np.array(g["e2m3"])
+    rng = np.random.default_rng(41)
+    for u in np.concatenate([rng.uniform(-9, 9, 4000), (tab[:-1] + tab[1:]) / 2, -(tab[:-1] + tab[1:]) / 2, [7.5, 7.75, 100.0, -8.0]]):
+        u = float(np.float32(u))
+        c = oracle.e2m3_encode(u)
+        d = float(oracle.e2m3_decode(np.array([c], np.uint8))[0])
+        best = np.min(np.abs(tab - abs(u)))
+        assert abs(abs(d) - abs(u)) == best and (d == 0 or np.sign(d) == np.sign(u))       # nearest, saturating at 7.5
+        if np.sum(np.abs(tab - abs(u)) == best) == 2:                                     # exact tie: even mantissa
+            assert (c & 1) == 0
+    v = (rng.standard_normal(32 * 40) * np.exp(rng.uniform(-8, 8, 32 * 40))).astype(np.float32)
+    v[64:96] = 0.0
+    v[96] = -0.75; v[97] = 0.2; v[98:128] = 0.0      # 0.75 = 1.5 * 2^-1: exponent -1 - 2 = -3: 0.75 * 8 = 6 -> code 28; 1.6 -> 1.625 = code 13
+    codes, e = oracle.quant_mxfp6(v)
+    assert e[2] == 0 and not (codes[64:96] & 31).any()
+    assert e[3] == 124 and codes[96] == (32 | 28) and codes[97] == 13
+    vb = v.astype(np.float64).reshape(-1, 32)
+    deq = oracle.e2m3_decode(codes).astype(np.float64).reshape(-1, 32)
+    for b in range(vb.shape[0]):
+        a = np.abs(vb[b]).max()
+        if a == 0:
+            continue
+        sc = 2.0 ** (int(e[b]) - 127)
+        assert sc == 2.0 ** (np.floor(np.log2(a)) - 2)
+        u = vb[b] / sc
+        assert 4 <= np.abs(u).max() < 8
+        for ui, di in zip(u, deq[b]):
+            assert abs(abs(di) - abs(ui)) <= np.min(np.abs(tab - abs(ui)))
+    back = (deq * (2.0 ** (e.astype(np.float64) - 127))[:, None]).astype(np.float32).ravel()
+    c2, e2 = oracle.quant_mxfp6(back)                                                      # idempotence (Section 3.2)
+    nzb = np.abs(vb).max(axis=1) > 0
+    assert np.array_equal(e2[nzb], e[nzb])
+    assert np.array_equal(oracle.e2m3_decode(c2).reshape(-1, 32)[nzb], oracle.e2m3_decode(codes).reshape(-1, 32)[nzb])
 
 
 def test_mxb_rank0_equals_mx_rank0_and_grid_factors_are_exact(oracle):
