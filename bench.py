@@ -162,7 +162,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": layer.name, "M": layer.M, "K": layer.K, "N": layer.N, "rank": layer.r,
                    "main": "W4A4 MXINT4 block 32" if mxi else "W4A4 MXFP4 block 32" if mx else f"W4A4 INT4 g{layer.g}",
-                   "branch": f"W{layer.br_w_bits}A8 MXINT block 32" if mxi else "W8A8 MXFP8e4 block 32" if mxb else "W8A8 FP8 E4M3" if mx else f"W{layer.br_w_bits}A{layer.br_a_bits}",
+                   "branch": f"W{layer.br_w_bits}A8 MXINT block 32" if mxi else ("W6A6 MXFP6e2 block 32" if layer.br_w_bits == 6 else "W8A8 MXFP8e4 block 32") if mxb else "W8A8 FP8 E4M3" if mx else f"W{layer.br_w_bits}A{layer.br_a_bits}",
                    "x_dtype": layer.x_dtype, "buffer_sets": nsets,
                    "arithmetic": ("int4 codes as FP8 subnormals with E8M0 block scales on the scaled FP8 MFMA, "
                                   "bf16-exact MXINT branch, fp32 accumulate" if mxi else
@@ -191,7 +191,7 @@ def main():
             pk = lq_ref.pack_mxi(W, L, R, layer.br_w_bits)
             run_rows = lambda n_rows: lq_ref.fwd_mxi(pk, lq_ref.quantize_act_mxi(X[:n_rows], pk))
         elif mxb:
-            pk = lq_ref.pack_mxb(W, L, R)
+            pk = lq_ref.pack_mxb(W, L, R, elem=layer.br_w_bits)
             run_rows = lambda n_rows: lq_ref.fwd_mxb(pk, lq_ref.quantize_act_mxb(X[:n_rows], pk))
         elif mx:
             pk = lq_ref.pack_mx(W, L, R)

@@ -18,7 +18,7 @@
  *         Integer accumulation, fp32 dequantisation.
  *   MX  : Q1 = MXFP4 (E2M1 elements, blocks of 32 along K, E8M0 scale, App. A.3) for both
  *         operands; Q2 = FP8 E4M3 with one fp32 scale per token / per row, or (all-MX setting of
- *         the mixed-precision tables, Section 4.3) MXFP8e4: E4M3 elements in blocks of 32 along
+ *         the mixed-precision tables, Section 4.3) MXFP8e4 / MXFP6e2: E4M3 / E2M3 elements in blocks of 32 along
  *         the contraction axis (K for X and R, the rank for X R^T and L) with E8M0 scales; then
  *         no fp32 scale exists and the branch accumulates into the main product's accumulator.
  *   MXI : the integer MX formats of App. A.3 (the integer rows of the mixed-precision tables,
@@ -68,7 +68,8 @@ typedef enum {
     LQ_FP8_E4M3 = 4,     /* E4M3 elements, one fp32 scale per token / per row                    */
     LQ_MXFP8_E4M3 = 5,   /* "MXFP8e4" (App. A.3): E4M3 elements, blocks of 32, E8M0 scale         */
     LQ_MXINT4 = 6,       /* "MXINT4" (App. A.3): signed int4 elements, blocks of 32, E8M0 scale    */
-    LQ_MXINT8 = 7        /* "MXINT8" (App. A.3): signed int8 elements, blocks of 32, E8M0 scale    */
+    LQ_MXINT8 = 7,       /* "MXINT8" (App. A.3): signed int8 elements, blocks of 32, E8M0 scale    */
+    LQ_MXFP6_E2M3 = 8    /* "MXFP6e2" (App. A.3): E2M3 elements, blocks of 32, E8M0 scale          */
 } lq_fmt;
 
 typedef enum { LQ_F32 = 0, LQ_BF16 = 1 } lq_dtype;
@@ -82,7 +83,7 @@ typedef struct {
     int32_t main_a;                  /* lq_fmt: must equal main_w                                 */
     int32_t main_w_group;            /* INT: 64 | 128 values along K per weight scale; MX, MXI: 32 */
     int32_t main_a_group;            /* INT: 0 = one scale per token; MX, MXI: 32                 */
-    int32_t br_w;                    /* lq_fmt of Q2(L), Q2(R): INT8|INT6|INT4; MX: FP8 | MXFP8; MXI: MXINT8 | MXINT4 */
+    int32_t br_w;                    /* lq_fmt of Q2(L), Q2(R): INT8|INT6|INT4; MX: FP8 | MXFP8 | MXFP6; MXI: MXINT8 | MXINT4 */
     int32_t br_a;                    /* lq_fmt of Q2(X), Q2(X R^T): INT8|INT6; MX: = br_w; MXI: MXINT8 */
     int32_t residual_from_quantized; /* 1: P = W - deq(Q2 L) deq(Q2 R) (Fig. 1); 0: P = W - L R  */
     int32_t x_dtype;                 /* lq_dtype of X                                             */
@@ -91,7 +92,7 @@ typedef struct {
 
 /* Optional parity taps.  Every member may be NULL.  Device pointers, plain row-major. */
 typedef struct {
-    int8_t  *xb;    /* M x K   branch activation codes (INT) / E4M3 bytes (MX)                  */
+    int8_t  *xb;    /* M x K   branch activation codes (INT) / E4M3 bytes or E2M3 codes (MX)    */
     float   *sxb;   /* M       branch activation scales (not with an MXFP8e4 branch)           */
     int32_t *accT;  /* M x r   integer accumulators of Q2(X) Q2(R)^T (INT only)                 */
     float   *T;     /* M x r   dequantised intermediate before re-quantisation                  */

@@ -21,7 +21,7 @@ _lib = C.CDLL(_LIB_PATH)
 
 LQ_OK = 0
 LQ_ERR_NULL, LQ_ERR_SHAPE, LQ_ERR_UNSUPPORTED, LQ_ERR_ALIGN, LQ_ERR_BUFFER_TOO_SMALL, LQ_ERR_DEVICE = range(1, 7)
-LQ_INT4, LQ_INT6, LQ_INT8, LQ_MXFP4_E2M1, LQ_FP8_E4M3, LQ_MXFP8_E4M3, LQ_MXINT4, LQ_MXINT8 = range(8)
+LQ_INT4, LQ_INT6, LQ_INT8, LQ_MXFP4_E2M1, LQ_FP8_E4M3, LQ_MXFP8_E4M3, LQ_MXINT4, LQ_MXINT8, LQ_MXFP6_E2M3 = range(9)
 LQ_F32, LQ_BF16 = 0, 1
 _INT_FMT = {4: LQ_INT4, 6: LQ_INT6, 8: LQ_INT8}
 
@@ -94,8 +94,8 @@ def make_config(N: int, K: int, rank: int, family: str = "int", group: int = 64,
     if family == "int":
         return lq_config(N, K, rank, LQ_INT4, LQ_INT4, group, 0, _INT_FMT[br_w_bits], _INT_FMT[br_a_bits],
                          1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32, 0)
-    if family in ("mx", "mxb"):  # "mxb": MXFP8e4 (block-scaled E4M3) branch instead of fp32-scaled E4M3
-        br = LQ_MXFP8_E4M3 if family == "mxb" else LQ_FP8_E4M3
+    if family in ("mx", "mxb"):  # "mxb": block-scaled branch (MXFP8e4, or MXFP6e2 at 6 bits) instead of fp32-scaled E4M3
+        br = (LQ_MXFP6_E2M3 if br_w_bits == 6 else LQ_MXFP8_E4M3) if family == "mxb" else LQ_FP8_E4M3
         return lq_config(N, K, rank, LQ_MXFP4_E2M1, LQ_MXFP4_E2M1, 32, 32, br, br,
                          1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32, 0)
     if family == "mxi":          # MXINT4 main; MXINT8 branch activations; MXINT8 or MXINT4 branch weights

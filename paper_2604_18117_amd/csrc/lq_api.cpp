@@ -32,7 +32,7 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
     d->rp = (r + 31) / 32 * 32;
     d->C64 = (int)(cfg->K / 64);
     d->mx = d->mxb = d->mxi = false;
-    d->bw_bits = 0;
+    d->bw_bits = d->mxb_elem = 0;
     if (cfg->main_w == LQ_INT4) {
         if (cfg->main_a != LQ_INT4) return LQ_ERR_UNSUPPORTED;
         if (cfg->main_w_group != 64 && cfg->main_w_group != 128) return LQ_ERR_SHAPE;
@@ -47,9 +47,12 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
     } else if (cfg->main_w == LQ_MXFP4_E2M1) {
         if (cfg->main_a != LQ_MXFP4_E2M1) return LQ_ERR_UNSUPPORTED;
         if (cfg->main_w_group != 32 || cfg->main_a_group != 32) return LQ_ERR_SHAPE;
-        if (cfg->br_w != cfg->br_a || (cfg->br_w != LQ_FP8_E4M3 && cfg->br_w != LQ_MXFP8_E4M3)) return LQ_ERR_UNSUPPORTED;
+        if (cfg->br_w != cfg->br_a ||
+            (cfg->br_w != LQ_FP8_E4M3 && cfg->br_w != LQ_MXFP8_E4M3 && cfg->br_w != LQ_MXFP6_E2M3))
+            return LQ_ERR_UNSUPPORTED;
         if (cfg->K % 128 != 0) return LQ_ERR_SHAPE;  // the MX forward stages K in steps of 128
-        d->mxb = cfg->br_w == LQ_MXFP8_E4M3;
+        d->mxb = cfg->br_w != LQ_FP8_E4M3;
+        d->mxb_elem = cfg->br_w == LQ_MXFP8_E4M3 ? 8 : cfg->br_w == LQ_MXFP6_E2M3 ? 6 : 0;
         if (d->mxb && r % 32 != 0) return LQ_ERR_SHAPE;  // whole blocks of 32 along the rank
         d->mx = true;
         d->g = 32;
@@ -184,7 +187,8 @@ lq_status lq_quantize_act(const lq_config* cfg, const void* packed, const void* 
         return LQ_ERR_ALIGN;
     if (act_bytes < act_layout(d, M).total) return LQ_ERR_BUFFER_TOO_SMALL;
     const int maxc = (d.C64 + 3) / 4;
-    if (!d.mxi && maxc > (cfg->x_dtype == LQ_BF16 ? 18 : 9)) return LQ_ERR_UNSUPPORTED;  // K beyond the register-resident row
+    if (!d.mxi && d.mxb_elem != 6 && maxc > (cfg->x_dtype == LQ_BF16 ? 18 : 9))
+        return LQ_ERR_UNSUPPORTED;  // K beyond the register-resident row
     hipError_t e = d.mxi ? launch_quantize_act_mxi(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,
                                                    (hipStream_t)stream)
                    : d.mx ? launch_quantize_act_mx(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,

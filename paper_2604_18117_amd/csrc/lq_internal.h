@@ -60,6 +60,7 @@ struct Dims {
     int C64;      // K / 64
     bool mx;      // MX family
     bool mxb;     // MX family with a block-scaled (MXFP8e4) branch
+    int mxb_elem; // block-scaled FP branch: 8 = E4M3 (MXFP8e4), 6 = E2M3 (MXFP6e2); 0 otherwise
     bool mxi;     // MXI family: MXINT4 main product, MXINT8 / MXINT4 branch (then mx is false)
     int bw_bits;  // MXI: width of the branch weight format (8 | 4)
     int qmax_bw;  // INT branch weight qmax
@@ -116,6 +117,13 @@ hipError_t launch_quantize_act_mx(const Dims& d, int x_dtype, const uint8_t* pac
 hipError_t launch_fwd_mx(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M,
                          uint16_t* Y, int64_t ldy, const lq_fwd_debug* dbg, hipStream_t s);
 
+// MXFP6e2 pieces of the MX family (lq_mx6.hip)
+hipError_t launch_pack_rows_mx6(const Dims& d, const float* L, const float* R, uint8_t* packed, hipStream_t s);
+hipError_t launch_unpack_weights_mx6(const Dims& d, const uint8_t* packed, const lq_weights_view* out, hipStream_t s);
+hipError_t launch_unpack_act_mx6(const Dims& d, const uint8_t* act, int64_t M, const lq_act_view* out, hipStream_t s);
+hipError_t launch_quantize_act_mx6(const Dims& d, int x_dtype, const uint8_t* packed, const void* X, int64_t M,
+                                   int64_t ldx, uint8_t* act, const lq_act_debug* dbg, hipStream_t s);
+
 hipError_t launch_pack_mxi(const Dims& d, int residual_from_quantized, const float* W, const float* L,
                            const float* R, uint8_t* packed, hipStream_t s);
 hipError_t launch_unpack_weights_mxi(const Dims& d, const uint8_t* packed, const lq_weights_view* out,
@@ -151,6 +159,33 @@ __device__ __forceinline__ int nib_get(uint32_t p, int e)
     const uint32_t b = (v >> (8 * (e & 3))) & 0xFFu;
     const int m = (int)(b & 7u);
     return (b & 0x80u) ? -m : m;
+}
+
+// ---- MXFP6e2 branch (E2M3 elements, blocks of 32, E8M0 scale): with 6-bit operands a lane of the scaled
+// MFMA holds the 32 values of ONE block as 192 contiguous bits (value i at bits 6i..6i+5); they sit in the
+// first 24 bytes of a 32-byte operand slot.  Slots are ordered like the 8-bit operands of the MXFP8e4 branch:
+// lq / tq: [block of 32 rows][64-chunk of the rank][lane = row%32 + 32*h], h = block within the chunk;
+// rq: [128-chunk of K][rank/16][lane = j%16 + 16*q], q = block within the chunk.  Scale bytes as for MXFP8e4.
+__device__ __forceinline__ size_t mx6_lt_slot(int row, int blk, int rp)
+{
+    return ((size_t)((size_t)(row >> 5) * (rp >> 6) + (blk >> 1)) * 64 + (row & 31) + 32 * (blk & 1)) * 32;
+}
+__device__ __forceinline__ size_t mx6_rq_slot(int j, int kb, int r)
+{
+    return ((size_t)((size_t)(kb >> 2) * (r >> 4) + (j >> 4)) * 64 + (j & 15) + 16 * (kb & 3)) * 32;
+}
+__device__ __forceinline__ uint32_t fp6_get(const uint8_t* slot, int i)  // code i (0..31) of a slot
+{
+    const uint32_t* w = (const uint32_t*)slot;
+    const int bit = 6 * i;
+    const uint64_t v = (uint64_t)w[bit >> 5] | ((uint64_t)w[(bit >> 5) + 1] << 32);  // dword 6 exists: the slot has 8
+    return (uint32_t)(v >> (bit & 31)) & 63u;
+}
+__device__ __forceinline__ float e2m3_value(uint32_t c)  // 1 sign, 2 exponent (bias 1), 3 mantissa bits
+{
+    const int e = (int)(c >> 3) & 3, m = (int)c & 7;
+    const float mag = e ? ldexpf(1.0f + 0.125f * (float)m, e - 1) : 0.125f * (float)m;
+    return (c & 32u) ? -mag : mag;
 }
 
 // fp32 -> bf16 bits, round to nearest even (finite inputs)

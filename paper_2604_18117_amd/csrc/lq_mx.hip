@@ -202,6 +202,14 @@ __global__ __launch_bounds__(256) void mx_pack_p_kernel(const float* W, const fl
     const int k = c * 64 + lane;
     double d = 0.0;
     for (int j = 0; j < r; ++j) {
+        if (from_q == 3) {  // MXFP6e2 factors
+            const uint8_t* le = (const uint8_t*)sl;
+            const uint8_t* re = (const uint8_t*)sr;
+            const double lh = (double)e2m3_value(fp6_get(l8 + mx6_lt_slot(n, j >> 5, rp), j & 31)) * e8m0_double(le[mxb_scale_offset(n, j >> 5)]);
+            const double rh = (double)e2m3_value(fp6_get(r8 + mx6_rq_slot(j, k >> 5, r), k & 31)) * e8m0_double(re[mxb_re_offset(j, k >> 5, r)]);
+            d = fma(lh, rh, d);
+            continue;
+        }
         if (from_q == 2) {  // element * 2^e is exact in fp64, and so is the product of two of them
             const uint8_t* le = (const uint8_t*)sl;
             const uint8_t* re = (const uint8_t*)sr;
@@ -252,7 +260,9 @@ hipError_t launch_pack_mx(const Dims& d, int from_q, const float* W, const float
         const size_t lq_bytes = (size_t)N * d.rp, le_bytes = (size_t)N * 8;
         if (lq_bytes) hipLaunchKernelGGL(mx_fill_kernel, dim3((unsigned)((lq_bytes + 255) / 256)), dim3(256), 0, s, l8, lq_bytes, (uint8_t)0);
         hipLaunchKernelGGL(mx_fill_kernel, dim3((unsigned)((le_bytes + 255) / 256)), dim3(256), 0, s, (uint8_t*)sl, le_bytes, (uint8_t)127);
-        if (d.r > 0) {
+        if (d.r > 0 && d.mxb_elem == 6) {
+            launch_pack_rows_mx6(d, L, R, packed, s);
+        } else if (d.r > 0) {
             const size_t nr = (size_t)d.r * (K / 32), nl = (size_t)N * (d.r / 32);
             hipLaunchKernelGGL(mxb_pack_rows_kernel, dim3((unsigned)((nr + 255) / 256)), dim3(256), 0, s, R, d.r, K, 0, d.r, d.rp, r8, (uint8_t*)sr);
             hipLaunchKernelGGL(mxb_pack_rows_kernel, dim3((unsigned)((nl + 255) / 256)), dim3(256), 0, s, L, N, d.r, 1, d.r, d.rp, l8, (uint8_t*)sl);
@@ -264,7 +274,7 @@ hipError_t launch_pack_mx(const Dims& d, int from_q, const float* W, const float
     }
     const size_t waves = (size_t)N * d.C64;
     hipLaunchKernelGGL(mx_pack_p_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, W, L, R, N, K, d.r, d.rp,
-                       (from_q && d.mxb) ? 2 : from_q, l8, sl, r8, sr, packed + pl.off_pq, packed + pl.off_sw);
+                       (from_q && d.mxb) ? (d.mxb_elem == 6 ? 3 : 2) : from_q, l8, sl, r8, sr, packed + pl.off_pq, packed + pl.off_sw);
     return hipGetLastError();
 }
 
@@ -310,6 +320,7 @@ __global__ __launch_bounds__(256) void mx_unpack_w_kernel(const uint8_t* packed,
 
 hipError_t launch_unpack_weights_mx(const Dims& d, const uint8_t* packed, const lq_weights_view* out, hipStream_t s)
 {
+    if (d.mxb_elem == 6) return launch_unpack_weights_mx6(d, packed, out, s);
     const PackedLayout pl = packed_layout(d);
     const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * d.K;
     hipLaunchKernelGGL(mx_unpack_w_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, packed, pl, (int)d.N,
@@ -344,6 +355,7 @@ __global__ __launch_bounds__(256) void mx_unpack_a_kernel(const uint8_t* act, Ac
 
 hipError_t launch_unpack_act_mx(const Dims& d, const uint8_t* act, int64_t M, const lq_act_view* out, hipStream_t s)
 {
+    if (d.mxb_elem == 6) return launch_unpack_act_mx6(d, act, M, out, s);
     const ActLayout al = act_layout(d, M);
     const size_t n = (size_t)M * (d.K > d.r ? d.K : d.r);
     hipLaunchKernelGGL(mx_unpack_a_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, act, al, (int)M,
@@ -592,6 +604,7 @@ static hipError_t launch_quantize_act_mxb(const Dims& d, int x_dtype, const uint
 hipError_t launch_quantize_act_mx(const Dims& d, int x_dtype, const uint8_t* packed, const void* X, int64_t M,
                                   int64_t ldx, uint8_t* act, const lq_act_debug* dbg, hipStream_t s)
 {
+    if (d.mxb_elem == 6) return launch_quantize_act_mx6(d, x_dtype, packed, X, M, ldx, act, dbg, s);
     if (d.mxb) return launch_quantize_act_mxb(d, x_dtype, packed, X, M, ldx, act, dbg, s);
     const PackedLayout pl = packed_layout(d);
     const ActLayout al = act_layout(d, M);
@@ -873,7 +886,8 @@ struct MxFwdParams {
 
 // NK = 64-deep chunks of the (padded) rank: 0 | 1 | 2.  BLK: the branch is MXFP8e4 (block scales,
 // accumulated by the scaled MFMA straight into the main product's accumulators).
-template <int NK, bool DBG, bool BLK>
+// BFMT: operand format code of the block-scaled branch (0 = E4M3, 2 = E2M3).
+template <int NK, bool DBG, bool BLK, int BFMT = 0>
 __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
 {
     constexpr int WN = 4, RBT = 4;
@@ -1034,9 +1048,9 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
 #pragma unroll
                 for (int cbi = 0; cbi < 2; ++cbi) {
                     if (cc == 0)
-                        t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ta, lb[cbi], t[rbi][cbi], 0, 0, 0, tsc, 0, lsc[cbi]);
+                        t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ta, lb[cbi], t[rbi][cbi], BFMT, BFMT, 0, tsc, 0, lsc[cbi]);
                     else
-                        t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ta, lb[cbi], t[rbi][cbi], 0, 0, 1, tsc, 1, lsc[cbi]);
+                        t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ta, lb[cbi], t[rbi][cbi], BFMT, BFMT, 1, tsc, 1, lsc[cbi]);
                 }
             }
         }
@@ -1137,14 +1151,14 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     }
 }
 
-template <int NK, bool BLK>
+template <int NK, bool BLK, int BFMT = 0>
 static void mx_fwd_launch(const MxFwdParams& p, hipStream_t s)
 {
     dim3 grid((unsigned)(p.tilesM * p.tilesN)), block(256);
     if (p.dbg_y32)
-        hipLaunchKernelGGL((mx_fwd_kernel<NK, true, BLK>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((mx_fwd_kernel<NK, true, BLK, BFMT>), grid, block, 0, s, p);
     else
-        hipLaunchKernelGGL((mx_fwd_kernel<NK, false, BLK>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((mx_fwd_kernel<NK, false, BLK, BFMT>), grid, block, 0, s, p);
 }
 
 hipError_t launch_fwd_mx(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M, uint16_t* Y, int64_t ldy,
@@ -1173,7 +1187,13 @@ hipError_t launch_fwd_mx(const Dims& d, const uint8_t* packed, const uint8_t* ac
     p.tilesM = (p.nrb + 3) / 4;
     p.tilesN = (p.N + 255) / 256;
     p.dbg_y32 = dbg ? dbg->y32 : nullptr;
-    if (d.mxb) {  // sl / st hold the E8M0 scale dwords of L / of the intermediate
+    if (d.mxb_elem == 6) {
+        switch (p.rp >> 6) {
+            case 0: mx_fwd_launch<0, false>(p, s); break;
+            case 1: mx_fwd_launch<1, true, 2>(p, s); break;
+            default: mx_fwd_launch<2, true, 2>(p, s); break;
+        }
+    } else if (d.mxb) {  // sl / st hold the E8M0 scale dwords of L / of the intermediate
         switch (p.rp >> 6) {
             case 0: mx_fwd_launch<0, false>(p, s); break;
             case 1: mx_fwd_launch<1, true>(p, s); break;

@@ -77,13 +77,15 @@ CFG5 = [_mx_layer("c5_qkv", 1152, 3456), _mx_layer("c5_attn_out", 1152, 1152),
 
 # The same seven layers with an MXFP8e4 (block-scaled E4M3) branch: the all-MX mixed-precision setting.
 CFG5B = [replace(l, name="c5b" + l.name[2:], family="mxb") for l in CFG5]
+# ... and with an MXFP6e2 (block-scaled E2M3) branch of rank 64: W6A6 in the branch.
+CFG5B6 = [replace(l, name="c5b6" + l.name[2:], family="mxb", r=64, br_w_bits=6, br_a_bits=6) for l in CFG5]
 
 # The same seven layers in the integer MX formats: MXINT4 main, MXINT8 branch of rank 64 (the pairing of
 # the paper's mixed-precision table for integer formats), and MXINT4 branch weights of rank 128.
 CFG5I = [replace(l, name="c5i" + l.name[2:], family="mxi", r=64) for l in CFG5]
 CFG5I4 = [replace(l, name="c5i4" + l.name[2:], family="mxi", r=128, br_w_bits=4) for l in CFG5]
 
-CONFIGS: Dict[str, List[Layer]] = {"c1": CFG1, "c2": CFG2, "c3": CFG3, "c4": CFG4, "c5": CFG5, "c5b": CFG5B,
+CONFIGS: Dict[str, List[Layer]] = {"c1": CFG1, "c2": CFG2, "c3": CFG3, "c4": CFG4, "c5": CFG5, "c5b": CFG5B, "c5b6": CFG5B6,
                                    "c5i": CFG5I, "c5i4": CFG5I4}
 LAYERS: Dict[str, Layer] = {l.name: l for ls in CONFIGS.values() for l in ls}
 

@@ -89,6 +89,11 @@ def test_mx_family_contract(lq):
     cfg = _cfg(lq, family="mxb")
     cfg.br_a = lq.LQ_FP8_E4M3       # both branch operands share one format
     assert raw.lq_packed_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    # MXFP6e2 branch: 32 six-bit codes sit in a 32-byte operand slot, so the sizes equal the 8-bit ones
+    c6, c8 = _cfg(lq, family="mxb", br_w_bits=6, K=256), _cfg(lq, family="mxb", K=256)
+    assert c6.br_w == c6.br_a == lq.LQ_MXFP6_E2M3
+    assert lq.lq_packed_sizes(c6) == lq.lq_packed_sizes(c8) and lq.lq_act_sizes(c6, 100) == lq.lq_act_sizes(c8, 100)
+    assert raw.lq_packed_sizes(C.byref(_cfg(lq, family="mxb", br_w_bits=6, rank=16)), C.byref(n)) == lq.LQ_ERR_SHAPE
     # codes N*K/2, E8M0 dwords per (32 rows, quad of 64-chunks, lane), lq N*64, one scale dword per
     # (channel, rank half), rq r*K, one scale dword per (128-chunk, 16 rank rows, lane) (+4)
     cfg = lq.make_config(3456, 1152, 32, "mxb")

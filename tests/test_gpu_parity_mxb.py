@@ -1,5 +1,5 @@
-"""GPU parity, MX family with an MXFP8e4 branch (all-MX setting of the mixed-precision tables,
-Section 4.3; element formats of App. A.3) against the CPU oracle.
+"""GPU parity, MX family with a block-scaled FP branch, MXFP8e4 or MXFP6e2 (all-MX setting of the
+mixed-precision tables, Section 4.3; element formats of App. A.3) against the CPU oracle.
 
 Bar: every code and E8M0 byte computed from source data (X, P, L, R) bit-exact (+0 and -0 codes are
 the same value); the intermediate T and the output pass through the matrix core's own accumulation
@@ -27,9 +27,11 @@ def _compare(oracle, layer, X, W, L, R, rows=None):
     Xo = X if rows is None else X[rows]
     sel = slice(None) if rows is None else rows
     r = layer.r
-    pk = oracle.pack_mxb(W, L if r else None, R if r else None)
+    elem = layer.br_w_bits                      # 8: E4M3 elements; 6: E2M3 elements
+    pk = oracle.pack_mxb(W, L if r else None, R if r else None, elem=elem)
     act = oracle.quantize_act_mxb(Xo, pk)
-    f8 = oracle.e4m3_decode(np.arange(256, dtype=np.uint8))
+    f8 = oracle.mxb_decode(np.arange(256, dtype=np.uint8), elem)   # E2M3 ignores the upper two bits
+    top, min_exp = (448.0, -9) if elem == 8 else (7.5, -3)
     Mo = Xo.shape[0]
     # ---- offline packing: exact
     assert np.array_equal(E2M1[n(g.wv.pq).view(np.uint8)], E2M1[pk.pc]), "pq"
@@ -60,12 +62,12 @@ def _compare(oracle, layer, X, W, L, R, rows=None):
         # value within the accumulation bound of the oracle's T
         sc = np.repeat(oracle.e8m0_decode(te_gpu), 32, axis=1)
         u = np.abs(act.T.astype(np.float64)) / sc
-        step = np.exp2(np.maximum(np.floor(np.log2(np.maximum(u, 2.0 ** -6))) - 3, -9))
-        half = np.where(u > 448.0, u - 448.0, 0.5 * step * (1 + 1e-6))
+        step = np.exp2(np.maximum(np.floor(np.log2(np.maximum(u, 2.0 ** (min_exp - 1)))) - 3, min_exp))
+        half = np.where(u > top, u - top, 0.5 * step * (1 + 1e-6))
         deq = f8[tq_gpu].astype(np.float64) * sc
         assert np.all(np.abs(deq - act.T) <= sc * half + tb), "tq8 is not a block rounding of T"
         same = ~ediff.repeat(32, axis=1)
-        diff = (tq_gpu != act.tq8) & ~(((tq_gpu & 0x7F) == 0) & ((act.tq8 & 0x7F) == 0)) & same
+        diff = (f8[tq_gpu] != f8[act.tq8]) & same
         assert diff.mean() <= 1e-2, f"tq8 mismatch rate {diff.mean()}"
     # ---- forward: the oracle is fed the GPU's re-quantised intermediate
     act_g = dataclasses.replace(act, tq8=np.ascontiguousarray(tq_gpu), te=np.ascontiguousarray(te_gpu))
@@ -107,15 +109,24 @@ SMALL = [
 ]
 
 
+@pytest.mark.parametrize("elem", [8, 6])
 @pytest.mark.parametrize("M,K,N,r,xd", SMALL)
-def test_small_shapes(oracle, M, K, N, r, xd):
-    layer = wl.Layer("t", M, K, N, r, "mxb", 32, 8, 8, xd, seed=M + K)
+def test_small_shapes(oracle, M, K, N, r, xd, elem):
+    layer = wl.Layer("t", M, K, N, r, "mxb", 32, elem, elem, xd, seed=M + K)
     X, W, L, R = wl.make_inputs(layer)
     _compare(oracle, layer, X, W, L, R)
 
 
-def test_degenerate_inputs(oracle):
-    layer = wl.Layer("t", 70, 256, 64, 32, "mxb", 32, 8, 8, "bf16", seed=3)
+def test_fp6_large_k_and_rank(oracle):
+    """K beyond the register-resident row of the other MX activation kernels, rank 128, fp32 input."""
+    layer = wl.Layer("t", 40, 5120, 64, 128, "mxb", 32, 6, 6, "f32", seed=9)
+    X, W, L, R = wl.make_inputs(layer)
+    _compare(oracle, layer, X, W, L, R)
+
+
+@pytest.mark.parametrize("elem", [8, 6])
+def test_degenerate_inputs(oracle, elem):
+    layer = wl.Layer("t", 70, 256, 64, 32, "mxb", 32, elem, elem, "bf16", seed=3)
     X, W, L, R = wl.make_inputs(layer)
     X[3] = 0.0
     X[5, :] = 0.0
@@ -129,8 +140,9 @@ def test_degenerate_inputs(oracle):
     _compare(oracle, layer, np.zeros_like(X), W, L, R)
 
 
-def test_wide_dynamic_range_blocks(oracle):
-    layer = wl.Layer("t", 64, 256, 64, 32, "mxb", 32, 8, 8, "bf16", seed=5)
+@pytest.mark.parametrize("elem", [8, 6])
+def test_wide_dynamic_range_blocks(oracle, elem):
+    layer = wl.Layer("t", 64, 256, 64, 32, "mxb", 32, elem, elem, "bf16", seed=5)
     X, W, L, R = wl.make_inputs(layer)
     rng = np.random.default_rng(7)
     X *= wl.round_to_bf16(np.exp2(rng.integers(-20, 20, size=(64, 8)).repeat(32, axis=1)).astype(np.float32))
@@ -139,9 +151,9 @@ def test_wide_dynamic_range_blocks(oracle):
     _compare(oracle, layer, wl.round_to_bf16(X), W, L, R)
 
 
-@pytest.mark.parametrize("name", ["c5_qkv", "c5_fc2"])
+@pytest.mark.parametrize("name", ["c5b_qkv", "c5b_fc2", "c5b6_qkv", "c5b6_fc2"])
 def test_full_size_sampled_rows(oracle, name):
-    layer = dataclasses.replace(wl.LAYERS[name], family="mxb")
+    layer = wl.LAYERS[name]
     X, W, L, R = wl.make_inputs(layer)
     rng = np.random.default_rng(1)
     rows = np.sort(np.concatenate([[0, layer.M - 1], rng.choice(layer.M, 14, replace=False)]))
