@@ -87,8 +87,14 @@ typedef struct {
     int32_t br_a;                    /* lq_fmt of Q2(X), Q2(X R^T): INT8|INT6; MX: = br_w; MXI: MXINT8 */
     int32_t residual_from_quantized; /* 1: P = W - deq(Q2 L) deq(Q2 R) (Fig. 1); 0: P = W - L R  */
     int32_t x_dtype;                 /* lq_dtype of X                                             */
-    int32_t reserved;                /* must be 0                                                 */
+    int32_t flags;                   /* bit set of LQ_FLAG_*; unknown bits are rejected           */
 } lq_config;
+
+/* Activation smoothing (Section 3.4; App. A.1): the activation kernel multiplies channel k of X by
+   1 / gamma[k] before anything else, for both branches (the caller has folded gamma into the columns of
+   W before calibration and packing).  Supported with the INT family; gamma is set with
+   lq_set_smoothing after lq_pack_weights.  K <= 2304 with this flag (the row is held as fp32). */
+#define LQ_FLAG_SMOOTH 1
 
 /* Optional parity taps.  Every member may be NULL.  Device pointers, plain row-major. */
 typedef struct {
@@ -141,6 +147,12 @@ lq_status lq_packed_sizes(const lq_config *cfg, size_t *packed_bytes);
    opaque function of cfg and the inputs; read them back with lq_unpack_weights. */
 lq_status lq_pack_weights(const lq_config *cfg, const float *W, const float *L, const float *R,
                           void *packed, size_t packed_bytes, void *stream);
+
+/* Store the smoothing vector of a layer packed with LQ_FLAG_SMOOTH: gamma is device memory, K fp32
+   values, finite and > 0; the blob keeps the correctly rounded reciprocals 1 / gamma[k].  Until this
+   call the blob holds reciprocals 1.0 (lq_pack_weights writes them).  LQ_ERR_UNSUPPORTED without the flag. */
+lq_status lq_set_smoothing(const lq_config *cfg, const float *gamma, void *packed, size_t packed_bytes,
+                           void *stream);
 
 /* Bytes of the activation blob for M tokens.  Host-only. */
 lq_status lq_act_sizes(const lq_config *cfg, int64_t M, size_t *act_bytes);

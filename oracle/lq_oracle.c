@@ -48,6 +48,7 @@
  *     element exponent 0, and the same pattern at 4 bits: 1 + 1 + 2); the block maximum
  *     therefore lands in the top octave of the code range, a value that would round to
  *     2^(b-1) saturates, -2^(b-1) is never produced; all-zero block: E8M0 byte 0;
+ *   - activation smoothing divides by gamma as a multiplication by fl(1/gamma);
  *   - P is built from the *dequantised* quantised factors (Fig. 1), optionally from the
  *     unquantised ones (residual_from_quantized = 0).
  *
@@ -111,6 +112,19 @@ LQO_API void lqo_quant_int(const float *v, int64_t n, int qmax, int8_t *q, float
         q[i] = (int8_t)r;
     }
     *scale = s;
+}
+
+/* Activation smoothing (Section 3.4; App. A.1): channel k of X is divided by gamma[k] before
+   quantisation, for both branches.  Reading: the division is a multiplication by the correctly
+   rounded reciprocal, Xs = X * fl(1 / gamma), both in fp32 (the reciprocal-multiply form used for
+   every scale of this oracle). */
+LQO_API void lqo_smooth(int64_t M, int64_t K, const float *X, const float *gamma, float *Xs)
+{
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            float rg = 1.0f / gamma[k];
+            Xs[m * K + k] = X[m * K + k] * rg;
+        }
 }
 
 /* ------------------------------------------------------------------------------------ */

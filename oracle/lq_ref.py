@@ -77,6 +77,16 @@ def quant_int(v, qmax: int):
     return q, s[0]
 
 
+def smooth(X, gamma):
+    """Activation smoothing: X[m, k] * fl(1 / gamma[k]) in fp32 (the input every other entry point then sees)."""
+    X = _f32(X)
+    g = _f32(gamma).ravel()
+    assert g.size == X.shape[1] and np.all(g > 0)
+    out = np.empty_like(X)
+    lib().lqo_smooth(C.c_int64(X.shape[0]), C.c_int64(X.shape[1]), _p(X), _p(g), _p(out))
+    return out
+
+
 def quant_mxfp4(v):
     """One row of K values (K % 32 == 0): (E2M1 codes uint8 [K], E8M0 bytes uint8 [K/32])."""
     v = _f32(v).ravel()

@@ -23,6 +23,7 @@ LQ_OK = 0
 LQ_ERR_NULL, LQ_ERR_SHAPE, LQ_ERR_UNSUPPORTED, LQ_ERR_ALIGN, LQ_ERR_BUFFER_TOO_SMALL, LQ_ERR_DEVICE = range(1, 7)
 LQ_INT4, LQ_INT6, LQ_INT8, LQ_MXFP4_E2M1, LQ_FP8_E4M3, LQ_MXFP8_E4M3, LQ_MXINT4, LQ_MXINT8, LQ_MXFP6_E2M3 = range(9)
 LQ_F32, LQ_BF16 = 0, 1
+LQ_FLAG_SMOOTH = 1
 _INT_FMT = {4: LQ_INT4, 6: LQ_INT6, 8: LQ_INT8}
 
 
@@ -30,7 +31,7 @@ class lq_config(C.Structure):
     _fields_ = [("N", C.c_int64), ("K", C.c_int64), ("rank", C.c_int32), ("main_w", C.c_int32),
                 ("main_a", C.c_int32), ("main_w_group", C.c_int32), ("main_a_group", C.c_int32),
                 ("br_w", C.c_int32), ("br_a", C.c_int32), ("residual_from_quantized", C.c_int32),
-                ("x_dtype", C.c_int32), ("reserved", C.c_int32)]
+                ("x_dtype", C.c_int32), ("flags", C.c_int32)]
 
 
 class lq_act_debug(C.Structure):
@@ -52,7 +53,7 @@ class lq_act_view(C.Structure):
                 ("st", C.c_void_p), ("te", C.c_void_p)]
 
 
-EXPORTS = ["lq_status_string", "lq_packed_sizes", "lq_pack_weights", "lq_act_sizes", "lq_quantize_act",
+EXPORTS = ["lq_status_string", "lq_packed_sizes", "lq_pack_weights", "lq_set_smoothing", "lq_act_sizes", "lq_quantize_act",
            "lq_linear_lowrank_fwd", "lq_unpack_weights", "lq_unpack_act"]
 
 _lib.lq_status_string.restype = C.c_char_p
@@ -61,6 +62,7 @@ _lib.lq_packed_sizes.argtypes = [C.POINTER(lq_config), C.POINTER(C.c_size_t)]
 _lib.lq_act_sizes.argtypes = [C.POINTER(lq_config), C.c_int64, C.POINTER(C.c_size_t)]
 _lib.lq_pack_weights.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_size_t, C.c_void_p]
+_lib.lq_set_smoothing.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.lq_quantize_act.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
                                  C.c_void_p, C.c_size_t, C.POINTER(lq_act_debug), C.c_void_p]
 _lib.lq_linear_lowrank_fwd.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
@@ -90,10 +92,14 @@ def raw():
 
 
 def make_config(N: int, K: int, rank: int, family: str = "int", group: int = 64, br_w_bits: int = 8,
-                br_a_bits: int = 8, x_dtype: str = "bf16", residual_from_quantized: bool = True) -> lq_config:
+                br_a_bits: int = 8, x_dtype: str = "bf16", residual_from_quantized: bool = True,
+                smooth: bool = False) -> lq_config:
     if family == "int":
         return lq_config(N, K, rank, LQ_INT4, LQ_INT4, group, 0, _INT_FMT[br_w_bits], _INT_FMT[br_a_bits],
-                         1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32, 0)
+                         1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32,
+                         LQ_FLAG_SMOOTH if smooth else 0)
+    if smooth:
+        raise ValueError("smoothing is fused into the INT family only")
     if family in ("mx", "mxb"):  # "mxb": block-scaled branch (MXFP8e4, or MXFP6e2 at 6 bits) instead of fp32-scaled E4M3
         br = (LQ_MXFP6_E2M3 if br_w_bits == 6 else LQ_MXFP8_E4M3) if family == "mxb" else LQ_FP8_E4M3
         return lq_config(N, K, rank, LQ_MXFP4_E2M1, LQ_MXFP4_E2M1, 32, 32, br, br,
@@ -104,9 +110,9 @@ def make_config(N: int, K: int, rank: int, family: str = "int", group: int = 64,
     raise ValueError(family)
 
 
-def config_for_layer(layer) -> lq_config:
+def config_for_layer(layer, smooth: bool = False) -> lq_config:
     return make_config(layer.N, layer.K, layer.r, layer.family, layer.g, layer.br_w_bits, layer.br_a_bits,
-                       layer.x_dtype)
+                       layer.x_dtype, smooth=smooth)
 
 
 def _stream() -> int:
@@ -121,6 +127,13 @@ def lq_packed_sizes(cfg: lq_config) -> int:
     n = C.c_size_t(0)
     _check(_lib.lq_packed_sizes(C.byref(cfg), C.byref(n)), "lq_packed_sizes")
     return int(n.value)
+
+
+def lq_set_smoothing(cfg: lq_config, packed: torch.Tensor, gamma: torch.Tensor) -> None:
+    """gamma: K fp32 CUDA values > 0; stores their reciprocals in the blob (layer packed with smooth=True)."""
+    assert gamma.is_cuda and gamma.dtype == torch.float32 and gamma.is_contiguous() and gamma.numel() == cfg.K
+    _check(_lib.lq_set_smoothing(C.byref(cfg), _ptr(gamma), _ptr(packed), packed.numel(), C.c_void_p(_stream())),
+           "lq_set_smoothing")
 
 
 def lq_act_sizes(cfg: lq_config, M: int) -> int:

@@ -22,6 +22,7 @@ struct ActParams {
     int64_t ldx;
     int M, K, C64, r, rp;
     float qa;  // qmax of the branch activation format
+    const float* rg;  // reciprocals of the smoothing vector (smoothing variant only)
     const int8_t* rq;
     const float* sr;
     uint8_t* xq;
@@ -75,6 +76,32 @@ struct XChunk<false> {  // 16 fp32 values
     __device__ __forceinline__ float get(int i) const { return v[i]; }
 };
 
+// Smoothing variant: 16 values of X (bf16 or fp32 source) times the reciprocals of the smoothing vector,
+// held as fp32 (the products are no longer bf16 numbers).
+template <bool BF16IN>
+__device__ __forceinline__ void load_smoothed(XChunk<false>& xc, const void* X, size_t elem, const float* rg, bool ok)
+{
+    float raw[16];
+    if constexpr (BF16IN) {
+        XChunk<true> t;
+        t.load(X, elem, ok);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) raw[i] = t.get(i);
+    } else {
+        XChunk<false> t;
+        t.load(X, elem, ok);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) raw[i] = t.get(i);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        v4i g = {0, 0, 0, 0};
+        if (ok) g = ((const v4i*)rg)[q];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xc.v[4 * q + i] = __fmul_rn(raw[4 * q + i], __int_as_float(g[i]));
+    }
+}
+
 __device__ __forceinline__ void scales(float amax, float qmax, float* s, float* inv)
 {
     if (amax == 0.0f) {
@@ -89,9 +116,11 @@ __device__ __forceinline__ void scales(float amax, float qmax, float* s, float* 
 // round-to-nearest-even of a value with |u| < 2^22, returned in the low bits (two's complement)
 __device__ __forceinline__ uint32_t rne_bits(float u) { return __float_as_uint(__fadd_rn(u, 12582912.0f)); }
 
-template <bool BF16, int MAXC, int NJB>
+// BF16IN: element type of X; SM: smoothing variant (X times stored reciprocals, row held as fp32).
+template <bool BF16IN, int MAXC, int NJB, bool SM = false>
 __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
 {
+    constexpr bool BF16 = BF16IN && !SM;  // representation of the row in registers
     __shared__ float s_amax[4][16];
     __shared__ float s_sxb[16];
     __shared__ int s_acc[4][NJB > 0 ? NJB : 1][64][4];  // [wave][j block][lane][4]
@@ -107,7 +136,11 @@ __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
 #pragma unroll
     for (int ci = 0; ci < MAXC; ++ci) {
         const int c = wave + 4 * ci;
-        xc[ci].load(p.X, (size_t)row * p.ldx + (size_t)c * 64 + kq * 16, row_ok && c < C64);
+        if constexpr (SM)
+            load_smoothed<BF16IN>(xc[ci], p.X, (size_t)row * p.ldx + (size_t)c * 64 + kq * 16,
+                                  p.rg + (size_t)(c < C64 ? c : 0) * 64 + kq * 16, row_ok && c < C64);
+        else
+            xc[ci].load(p.X, (size_t)row * p.ldx + (size_t)c * 64 + kq * 16, row_ok && c < C64);
     }
 
     // Operands that do not depend on X are requested now, so that their latency overlaps the
@@ -277,22 +310,22 @@ __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
     }
 }
 
-template <bool BF16, int MAXC, int NJB>
+template <bool BF16, int MAXC, int NJB, bool SM>
 static hipError_t launch_one(const ActParams& p, int64_t Mp, hipStream_t s)
 {
-    hipLaunchKernelGGL((act_int_kernel<BF16, MAXC, NJB>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((act_int_kernel<BF16, MAXC, NJB, SM>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
-template <bool BF16, int MAXC>
+template <bool BF16, int MAXC, bool SM = false>
 static hipError_t launch_rank(const ActParams& p, int64_t Mp, hipStream_t s)
 {
     switch (p.r) {
-        case 0: return launch_one<BF16, MAXC, 0>(p, Mp, s);
-        case 16: return launch_one<BF16, MAXC, 1>(p, Mp, s);
-        case 32: return launch_one<BF16, MAXC, 2>(p, Mp, s);
-        case 64: return launch_one<BF16, MAXC, 4>(p, Mp, s);
-        default: return launch_one<BF16, MAXC, 8>(p, Mp, s);
+        case 0: return launch_one<BF16, MAXC, 0, SM>(p, Mp, s);
+        case 16: return launch_one<BF16, MAXC, 1, SM>(p, Mp, s);
+        case 32: return launch_one<BF16, MAXC, 2, SM>(p, Mp, s);
+        case 64: return launch_one<BF16, MAXC, 4, SM>(p, Mp, s);
+        default: return launch_one<BF16, MAXC, 8, SM>(p, Mp, s);
     }
 }
 
@@ -321,7 +354,12 @@ hipError_t launch_quantize_act_int(const Dims& d, int x_dtype, const uint8_t* pa
     p.dbg_sxb = dbg ? dbg->sxb : nullptr;
     p.dbg_accT = dbg ? dbg->accT : nullptr;
     p.dbg_T = dbg ? dbg->T : nullptr;
+    p.rg = (const float*)(packed + pl.off_rg);
     const int maxc = (d.C64 + 3) / 4;
+    if (d.smooth) {  // K <= 2304: at most 9 chunks per wavefront
+        if (x_dtype == LQ_BF16) return maxc <= 5 ? launch_rank<true, 5, true>(p, al.Mp, s) : launch_rank<true, 9, true>(p, al.Mp, s);
+        return maxc <= 5 ? launch_rank<false, 5, true>(p, al.Mp, s) : launch_rank<false, 9, true>(p, al.Mp, s);
+    }
     if (x_dtype == LQ_BF16) {
         if (maxc <= 5) return launch_rank<true, 5>(p, al.Mp, s);
         if (maxc <= 9) return launch_rank<true, 9>(p, al.Mp, s);

@@ -19,7 +19,7 @@ static int int_qmax(int fmt)
 lq_status make_dims(const lq_config* cfg, Dims* d)
 {
     if (!cfg) return LQ_ERR_NULL;
-    if (cfg->reserved != 0) return LQ_ERR_UNSUPPORTED;
+    if (cfg->flags & ~LQ_FLAG_SMOOTH) return LQ_ERR_UNSUPPORTED;
     if (cfg->N <= 0 || cfg->K <= 0 || cfg->N > (1 << 24) || cfg->K > (1 << 24)) return LQ_ERR_SHAPE;
     if (cfg->K % 64 != 0 || cfg->N % 64 != 0) return LQ_ERR_SHAPE;
     const int r = cfg->rank;
@@ -31,6 +31,7 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
     d->r = r;
     d->rp = (r + 31) / 32 * 32;
     d->C64 = (int)(cfg->K / 64);
+    d->smooth = (cfg->flags & LQ_FLAG_SMOOTH) != 0;
     d->mx = d->mxb = d->mxi = false;
     d->bw_bits = d->mxb_elem = 0;
     if (cfg->main_w == LQ_INT4) {
@@ -40,10 +41,13 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         if (cfg->main_a_group != 0) return LQ_ERR_UNSUPPORTED;
         const int qw = int_qmax(cfg->br_w), qa = int_qmax(cfg->br_a);
         if (qw == 0 || qa == 0 || cfg->br_a == LQ_INT4) return LQ_ERR_UNSUPPORTED;
+        if (d->smooth && cfg->K > 2304) return LQ_ERR_UNSUPPORTED;  // the smoothed row is held as fp32
         d->mx = false;
         d->g = cfg->main_w_group;
         d->qmax_bw = qw;
         d->qmax_ba = qa;
+    } else if (d->smooth) {
+        return LQ_ERR_UNSUPPORTED;  // smoothing is fused into the INT family's activation kernel only
     } else if (cfg->main_w == LQ_MXFP4_E2M1) {
         if (cfg->main_a != LQ_MXFP4_E2M1) return LQ_ERR_UNSUPPORTED;
         if (cfg->main_w_group != 32 || cfg->main_a_group != 32) return LQ_ERR_SHAPE;
@@ -93,6 +97,8 @@ PackedLayout packed_layout(const Dims& d)
     o = align256(o + (d.mxi   ? (size_t)d.r * (d.K / 32) + 4
                       : d.mxb ? (size_t)(d.K / 128) * (d.r / 16) * 256 + 4
                               : (size_t)(d.r > 0 ? d.r : 1) * 4));
+    pl.off_rg = o;
+    if (d.smooth) o = align256(o + (size_t)d.K * 4);
     pl.total = o;
     return pl;
 }
@@ -173,6 +179,18 @@ lq_status lq_pack_weights(const lq_config* cfg, const float* W, const float* L, 
     return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }
 
+lq_status lq_set_smoothing(const lq_config* cfg, const float* gamma, void* packed, size_t packed_bytes, void* stream)
+{
+    Dims d;
+    lq_status st = make_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!d.smooth) return LQ_ERR_UNSUPPORTED;
+    if (!gamma || !packed) return LQ_ERR_NULL;
+    if (!aligned(packed, 256) || !aligned(gamma, 4)) return LQ_ERR_ALIGN;
+    if (packed_bytes < packed_layout(d).total) return LQ_ERR_BUFFER_TOO_SMALL;
+    return launch_set_smoothing(d, gamma, (uint8_t*)packed, (hipStream_t)stream) == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
 lq_status lq_quantize_act(const lq_config* cfg, const void* packed, const void* X, int64_t M, int64_t ldx,
                           void* act, size_t act_bytes, const lq_act_debug* dbg, void* stream)
 {
@@ -180,7 +198,7 @@ lq_status lq_quantize_act(const lq_config* cfg, const void* packed, const void* 
     lq_status st = make_dims(cfg, &d);
     if (st != LQ_OK) return st;
     if (!X || !act) return LQ_ERR_NULL;
-    if (d.r > 0 && !packed) return LQ_ERR_NULL;
+    if ((d.r > 0 || d.smooth) && !packed) return LQ_ERR_NULL;
     if (M < 1 || M > (1 << 24) || ldx < d.K) return LQ_ERR_SHAPE;
     const size_t es = cfg->x_dtype == LQ_BF16 ? 2 : 4;
     if (!aligned(X, 16) || (ldx * es) % 16 != 0 || !aligned(act, 256) || (packed && !aligned(packed, 256)))

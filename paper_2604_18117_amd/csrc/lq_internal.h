@@ -63,6 +63,7 @@ struct Dims {
     int mxb_elem; // block-scaled FP branch: 8 = E4M3 (MXFP8e4), 6 = E2M3 (MXFP6e2); 0 otherwise
     bool mxi;     // MXI family: MXINT4 main product, MXINT8 / MXINT4 branch (then mx is false)
     int bw_bits;  // MXI: width of the branch weight format (8 | 4)
+    bool smooth;  // LQ_FLAG_SMOOTH: the activation kernel multiplies X by the stored reciprocals of gamma
     int qmax_bw;  // INT branch weight qmax
     int qmax_ba;  // INT branch activation qmax
 };
@@ -74,6 +75,7 @@ struct PackedLayout {
     size_t off_sl;   // [N] fp32
     size_t off_rq;   // branch R codes in the activation kernel's operand order, r*K bytes
     size_t off_sr;   // [r] fp32
+    size_t off_rg;   // [K] fp32 reciprocals of the smoothing vector (only with LQ_FLAG_SMOOTH)
     size_t total;
 };
 
@@ -102,6 +104,7 @@ hipError_t launch_unpack_act_int(const Dims& d, const uint8_t* act, int64_t M,
 hipError_t launch_quantize_act_int(const Dims& d, int x_dtype, const uint8_t* packed,
                                    const void* X, int64_t M, int64_t ldx, uint8_t* act,
                                    const lq_act_debug* dbg, hipStream_t s);
+hipError_t launch_set_smoothing(const Dims& d, const float* gamma, uint8_t* packed, hipStream_t s);
 hipError_t launch_fwd_int(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M,
                           uint16_t* Y, int64_t ldy, const lq_fwd_debug* dbg, hipStream_t s);
 

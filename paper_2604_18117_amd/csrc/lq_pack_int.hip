@@ -130,6 +130,21 @@ __global__ __launch_bounds__(256) void pack_p_kernel(const float* W, const float
     }
 }
 
+// reciprocals of the smoothing vector (gamma == nullptr: ones)
+__global__ __launch_bounds__(256) void smooth_recip_kernel(const float* gamma, int K, float* rg)
+{
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    if (k < K) rg[k] = gamma ? __fdiv_rn(1.0f, gamma[k]) : 1.0f;
+}
+
+hipError_t launch_set_smoothing(const Dims& d, const float* gamma, uint8_t* packed, hipStream_t s)
+{
+    const PackedLayout pl = packed_layout(d);
+    hipLaunchKernelGGL(smooth_recip_kernel, dim3((unsigned)((d.K + 255) / 256)), dim3(256), 0, s, gamma, (int)d.K,
+                       (float*)(packed + pl.off_rg));
+    return hipGetLastError();
+}
+
 hipError_t launch_pack_int(const Dims& d, int from_q, const float* W, const float* L,
                            const float* R, uint8_t* packed, hipStream_t s)
 {
@@ -150,6 +165,7 @@ hipError_t launch_pack_int(const Dims& d, int from_q, const float* W, const floa
         hipLaunchKernelGGL(pack_l_kernel, dim3((N + 255) / 256), dim3(256), 0, s, (const float*)nullptr, N, 0, 0,
                            1.0f, lq, sl);
     }
+    if (d.smooth) launch_set_smoothing(d, nullptr, packed, s);
     const size_t waves = (size_t)N * d.G;
     const unsigned blocks = (unsigned)((waves + 3) / 4);
     if (d.g == 64)

@@ -70,7 +70,7 @@ def test_unsupported_combinations(lq):
     cfg.main_a = lq.LQ_INT8
     assert lq.raw().lq_packed_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
     cfg = _cfg(lq)
-    cfg.reserved = 1
+    cfg.flags = 2                   # unknown flag bits are rejected
     assert lq.raw().lq_packed_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
     cfg = _cfg(lq)
     cfg.main_a_group = 64           # per-token-group activations are reserved
@@ -153,6 +153,30 @@ def test_mxi_contract(lq):
     big = _cfg(lq, family="mxi", K=8192)
     assert raw.lq_quantize_act(C.byref(big), good, good, 64, 8000, good, 1 << 30, None, None) == lq.LQ_ERR_SHAPE
     assert raw.lq_act_sizes(C.byref(big), 64, C.byref(n)) == lq.LQ_OK
+
+
+def test_smoothing_contract(lq):
+    raw = lq.raw()
+    n = C.c_size_t(0)
+    good = C.c_void_p(1 << 20)
+    plain, sm = _cfg(lq), lq.make_config(128, 256, 32, smooth=True)
+    assert sm.flags == lq.LQ_FLAG_SMOOTH
+    # one more section: K reciprocals
+    assert lq.lq_packed_sizes(sm) == lq.lq_packed_sizes(plain) + 256 * 4
+    pb = lq.lq_packed_sizes(sm)
+    assert raw.lq_set_smoothing(C.byref(plain), good, good, pb, None) == lq.LQ_ERR_UNSUPPORTED
+    assert raw.lq_set_smoothing(C.byref(sm), None, good, pb, None) == lq.LQ_ERR_NULL
+    assert raw.lq_set_smoothing(C.byref(sm), good, good, pb - 1, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert raw.lq_set_smoothing(C.byref(sm), good, C.c_void_p((1 << 20) + 8), pb, None) == lq.LQ_ERR_ALIGN
+    # the activation kernel needs the blob even without a branch
+    sm0 = lq.make_config(128, 256, 0, smooth=True)
+    assert raw.lq_quantize_act(C.byref(sm0), None, good, 64, 256, good, 1 << 20, None, None) == lq.LQ_ERR_NULL
+    # the smoothed row is held as fp32: K <= 2304; fused into the INT family only
+    big = lq.make_config(128, 4608, 32, smooth=True)
+    assert raw.lq_packed_sizes(C.byref(big), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    mx = lq.make_config(128, 256, 32, "mx")
+    mx.flags = lq.LQ_FLAG_SMOOTH
+    assert raw.lq_packed_sizes(C.byref(mx), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -152,3 +152,42 @@ def test_full_size_sampled_rows(oracle, name):
     assert np.array_equal(n(av.tq)[rows], act.tq) and np.array_equal(n(av.st)[rows], act.st)
     Yb = bf16_to_bits(g.Y)[rows]
     assert np.array_equal(Yb, out.Y)
+
+
+@pytest.mark.parametrize("M,K,N,r,xd", [(200, 1152, 320, 32, "bf16"), (77, 2304, 64, 16, "f32"), (33, 256, 64, 0, "bf16")])
+def test_fused_smoothing(oracle, M, K, N, r, xd):
+    """Activation smoothing (Section 3.4; App. A.1) fused into the activation kernel: the GPU is given the raw X
+    and the smoothing vector; the oracle quantises the smoothed input.  Everything bit-exact as for the plain path."""
+    import torch
+    from paper_2604_18117_amd import binding as lq
+    from tests.gpu_util import to_dev_x
+    layer = wl.shrink(wl.LAYERS["c2_qkv"], M=M, K=K, N=N, r=r)
+    layer = wl.Layer(**{**layer.__dict__, "x_dtype": xd, "seed": M + K})
+    X, W, L, R = wl.make_inputs(layer)
+    gamma = wl.smoothing_vector(X, W)
+    Ws = (W.astype(np.float64) * gamma).astype(np.float32)       # the caller folds gamma into W before packing
+    cfg = lq.config_for_layer(layer, smooth=True)
+    packed = lq.lq_pack_weights(cfg, torch.from_numpy(Ws).cuda(), torch.from_numpy(L).cuda() if r else None,
+                                torch.from_numpy(R).cuda() if r else None)
+    Xd = to_dev_x(X, xd)
+    # before lq_set_smoothing the blob holds reciprocals 1: the plain path
+    a0 = lq.lq_quantize_act(cfg, packed, Xd)
+    pk = oracle.pack_int(Ws, L if r else None, R if r else None, layer.g, layer.br_w_bits)
+    act0 = oracle.quantize_act_int(X, pk, layer.br_a_bits)
+    assert np.array_equal(n(lq.lq_unpack_act(cfg, a0, M).xq), act0.xq)
+    lq.lq_set_smoothing(cfg, packed, torch.from_numpy(gamma).cuda())
+    act_g, adbg = lq.lq_quantize_act(cfg, packed, Xd, debug=True)
+    Y, fdbg = lq.lq_linear_lowrank_fwd(cfg, packed, act_g, M, debug=True, debug_acc=False)
+    av = lq.lq_unpack_act(cfg, act_g, M)
+    torch.cuda.synchronize()
+    Xs = oracle.smooth(X, gamma)
+    act = oracle.quantize_act_int(Xs, pk, layer.br_a_bits)
+    out = oracle.fwd_int(pk, act, want_acc=False)
+    assert np.array_equal(n(av.xq), act.xq) and np.array_equal(n(av.sx), act.sx)
+    if r:
+        assert np.array_equal(n(adbg.xb), act.xb) and np.array_equal(n(adbg.sxb), act.sxb)
+        assert np.array_equal(n(adbg.accT), act.accT) and np.array_equal(n(adbg.T), act.T)
+        assert np.array_equal(n(av.tq), act.tq) and np.array_equal(n(av.st), act.st)
+    assert np.array_equal(n(fdbg.y32), out.y32)
+    assert np.array_equal(bf16_to_bits(Y), out.Y)
+    assert not np.array_equal(act.xq, act0.xq)                   # the smoothing did change the codes

@@ -823,6 +823,39 @@ def test_mxi_rank0_zero_factors_and_lossless_grids(oracle):
     assert np.array_equal((cs.astype(np.float64) * np.repeat(oracle.mxint_scale(es, 8), 32)).astype(np.float32), Xs.ravel())
 
 
+# --------------------------------------------------------------------------------------
+# activation smoothing (Section 3.4; App. A.1)
+# --------------------------------------------------------------------------------------
+
+def test_smoothing_is_a_reciprocal_multiply_and_tames_outlier_channels(oracle):
+    rng = np.random.default_rng(51)
+    M, K, N, r = 48, 256, 32, 16
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    out_cols = rng.choice(K, 4, replace=False)
+    X[:, out_cols] *= 30                                   # the situation smoothing addresses
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    g = wl.smoothing_vector(X, W)
+    assert g.shape == (K,) and np.all(g > 0) and np.all(g[out_cols] > np.median(g) * 3)
+    Xs = oracle.smooth(X, g)
+    # correctly rounded reciprocal, one rounding for the product (exact rationals)
+    for m, k in [(0, 0), (3, int(out_cols[0])), (47, 255), (10, 77)]:
+        rg = np.float32(float(Fraction(1) / Fraction(float(g[k]))))
+        assert Xs[m, k] == np.float32(float(Fraction(float(X[m, k])) * Fraction(float(rg))))
+    assert np.array_equal(oracle.smooth(X, np.ones(K, np.float32)), X)          # gamma = 1: identity
+    p2 = np.exp2(rng.integers(-3, 4, K)).astype(np.float32)
+    assert np.array_equal(oracle.smooth(X, p2), X / p2)                          # powers of two: exact division
+    # the layer is unchanged in exact arithmetic: (X / gamma)(W gamma)^T = X W^T
+    Ws = (W.astype(np.float64) * g).astype(np.float32)
+    ref = X.astype(np.float64) @ W.astype(np.float64).T
+    assert np.abs(Xs.astype(np.float64) @ Ws.astype(np.float64).T - ref).max() <= 1e-5 * np.abs(ref).max()
+    # and the 4-bit product gets closer to it (outlier channels no longer set every token's scale)
+    L = np.zeros((N, r), np.float32); R = np.zeros((r, K), np.float32)
+    def err(Xin, Win):
+        pk = oracle.pack_int(Win, L, R, 64, 8)
+        return np.abs(oracle.fwd_int(pk, oracle.quantize_act_int(Xin, pk, 8), want_acc=False).y32 - ref).mean()
+    assert err(Xs, Ws) < 0.6 * err(X, W)
+
+
 def test_workload_generator_is_seeded():
     l = wl.shrink(wl.LAYERS["c2_qkv"], M=16, K=128, N=64, r=16)
     a, b = wl.make_inputs(l), wl.make_inputs(l)
