@@ -205,7 +205,7 @@ lq_status lq_quantize_act(const lq_config* cfg, const void* packed, const void* 
         return LQ_ERR_ALIGN;
     if (act_bytes < act_layout(d, M).total) return LQ_ERR_BUFFER_TOO_SMALL;
     const int maxc = (d.C64 + 3) / 4;
-    if (!d.mxi && d.mxb_elem != 6 && maxc > (cfg->x_dtype == LQ_BF16 ? 18 : 9))
+    if (!d.mxi && !d.mxb && maxc > (cfg->x_dtype == LQ_BF16 ? 18 : 9))
         return LQ_ERR_UNSUPPORTED;  // K beyond the register-resident row
     hipError_t e = d.mxi ? launch_quantize_act_mxi(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,
                                                    (hipStream_t)stream)

@@ -658,10 +658,11 @@ struct MxbActParams {
     float* dbg_T;
 };
 
-template <bool BF16, int MAXC, int NJB>
+template <bool BF16, int NJB>
 __global__ __launch_bounds__(256) void mxb_act_kernel(MxbActParams p)
 {
     constexpr int NJA = NJB > 0 ? NJB : 1;
+    constexpr int PF = 2;  // 128-chunks in flight per wavefront: no scale spans more than a block, the row is streamed
     __shared__ float s_acc[4][NJA][64][4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -670,14 +671,13 @@ __global__ __launch_bounds__(256) void mxb_act_kernel(MxbActParams p)
     const bool row_ok = row < p.M;
     const int C64 = p.C64, C128 = p.C128;
 
-    MxChunk<BF16> xh[MAXC][2];
+    const int nmy = (C128 - wave + 3) >> 2;  // chunks of this wavefront: c = wave + 4 * ci, ci < nmy
+    MxChunk<BF16> xh[PF][2];
 #pragma unroll
-    for (int ci = 0; ci < MAXC; ++ci) {
-        const int c = wave + 4 * ci;
+    for (int i = 0; i < PF; ++i)
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh)
-            xh[ci][hh].load(p.X, (size_t)row * p.ldx + (size_t)c * 128 + hh * 64 + q * 16, row_ok && c < C128);
-    }
+            xh[i][hh].load(p.X, (size_t)row * p.ldx + (size_t)(wave + 4 * i) * 128 + hh * 64 + q * 16, row_ok && i < nmy);
     // R fragments and their scale dwords: first chunk now, later ones one chunk ahead
     v8i bvs[2][NJA];
     int bss[2][NJA];
@@ -696,16 +696,18 @@ __global__ __launch_bounds__(256) void mxb_act_kernel(MxbActParams p)
 #pragma unroll
     for (int jb = 0; jb < NJB; ++jb) acc[jb] = v4f{0.f, 0.f, 0.f, 0.f};
 
+    for (int base = 0; base < nmy; base += PF) {
 #pragma unroll
-    for (int ci = 0; ci < MAXC; ++ci) {
+    for (int sl = 0; sl < PF; ++sl) {
+        const int ci = base + sl;
         const int c = wave + 4 * ci;
-        if (ci + 1 < MAXC) load_r8((ci + 1) & 1, ci + 1);
-        if (c < C128) {  // wave-uniform
+        load_r8((sl + 1) & 1, ci + 1);
+        if (ci < nmy) {  // wave-uniform
             uint32_t x8[8];
             uint32_t Eh[2];
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh) {
-                const MxChunk<BF16>& xc = xh[ci][hh];
+                const MxChunk<BF16>& xc = xh[sl][hh];
                 float m = 0.f;
                 if constexpr (BF16) {
                     us2 m2 = {0, 0};
@@ -752,15 +754,21 @@ __global__ __launch_bounds__(256) void mxb_act_kernel(MxbActParams p)
                 const v8i a8 = {(int)x8[0], (int)x8[1], (int)x8[2], (int)x8[3], (int)x8[4], (int)x8[5], (int)x8[6], (int)x8[7]};
 #pragma unroll
                 for (int jb = 0; jb < NJB; ++jb)
-                    acc[jb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, bvs[ci & 1][jb], acc[jb], 0, 0, 0, sa, 0,
-                                                                            bss[ci & 1][jb]);
+                    acc[jb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, bvs[sl & 1][jb], acc[jb], 0, 0, 0, sa, 0,
+                                                                            bss[sl & 1][jb]);
             }
-        } else {
-            // padding chunks of the last quad: their scale bytes must be valid E8M0 values (2^0)
-#pragma unroll
-            for (int hh = 0; hh < 2; ++hh)
-                if (2 * c + hh < 4 * p.CQ && (q & 1) == 0) p.xe[mx_scale_offset(row, 2 * c + hh, q >> 1, p.CQ)] = (uint8_t)127;
         }
+        // refill the slot with the chunk PF positions further on
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+            xh[sl][hh].load(p.X, (size_t)row * p.ldx + (size_t)(c + 4 * PF) * 128 + hh * 64 + q * 16, row_ok && ci + PF < nmy);
+    }
+    }
+    {   // padding 64-chunks of the last quad (at most one 128-chunk per wavefront): valid E8M0 bytes (2^0)
+        const int c = wave + 4 * nmy;
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+            if (2 * c + hh < 4 * p.CQ && (q & 1) == 0) p.xe[mx_scale_offset(row, 2 * c + hh, q >> 1, p.CQ)] = (uint8_t)127;
     }
     if (NJB == 0) return;
 
@@ -814,20 +822,20 @@ __global__ __launch_bounds__(256) void mxb_act_kernel(MxbActParams p)
     }
 }
 
-template <bool BF16, int MAXC, int NJB>
+template <bool BF16, int NJB>
 static hipError_t mxb_act_launch(const MxbActParams& p, int64_t Mp, hipStream_t s)
 {
-    hipLaunchKernelGGL((mxb_act_kernel<BF16, MAXC, NJB>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((mxb_act_kernel<BF16, NJB>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
     return hipGetLastError();
 }
-template <bool BF16, int MAXC>
+template <bool BF16>
 static hipError_t mxb_act_rank(const MxbActParams& p, int64_t Mp, hipStream_t s)
 {
     switch (p.r) {
-        case 0: return mxb_act_launch<BF16, MAXC, 0>(p, Mp, s);
-        case 32: return mxb_act_launch<BF16, MAXC, 2>(p, Mp, s);
-        case 64: return mxb_act_launch<BF16, MAXC, 4>(p, Mp, s);
-        default: return mxb_act_launch<BF16, MAXC, 8>(p, Mp, s);
+        case 0: return mxb_act_launch<BF16, 0>(p, Mp, s);
+        case 32: return mxb_act_launch<BF16, 2>(p, Mp, s);
+        case 64: return mxb_act_launch<BF16, 4>(p, Mp, s);
+        default: return mxb_act_launch<BF16, 8>(p, Mp, s);
     }
 }
 
@@ -855,14 +863,7 @@ static hipError_t launch_quantize_act_mxb(const Dims& d, int x_dtype, const uint
     p.dbg_xb = dbg ? dbg->xb : nullptr;
     p.dbg_xbe = dbg ? dbg->xbe : nullptr;
     p.dbg_T = dbg ? dbg->T : nullptr;
-    const int maxc = (p.C128 + 3) / 4;  // 128-chunks per wavefront
-    if (x_dtype == LQ_BF16) {
-        if (maxc <= 3) return mxb_act_rank<true, 3>(p, al.Mp, s);
-        if (maxc <= 5) return mxb_act_rank<true, 5>(p, al.Mp, s);
-        return mxb_act_rank<true, 9>(p, al.Mp, s);
-    }
-    if (maxc <= 3) return mxb_act_rank<false, 3>(p, al.Mp, s);
-    return mxb_act_rank<false, 5>(p, al.Mp, s);
+    return x_dtype == LQ_BF16 ? mxb_act_rank<true>(p, al.Mp, s) : mxb_act_rank<false>(p, al.Mp, s);
 }
 
 // ---------------------------------------------------------------------------------------------

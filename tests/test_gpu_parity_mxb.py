@@ -117,9 +117,10 @@ def test_small_shapes(oracle, M, K, N, r, xd, elem):
     _compare(oracle, layer, X, W, L, R)
 
 
-def test_fp6_large_k_and_rank(oracle):
-    """K beyond the register-resident row of the other MX activation kernels, rank 128, fp32 input."""
-    layer = wl.Layer("t", 40, 5120, 64, 128, "mxb", 32, 6, 6, "f32", seed=9)
+@pytest.mark.parametrize("elem", [8, 6])
+def test_large_k_and_rank(oracle, elem):
+    """K beyond the register-resident row of the fp32-scaled MX activation kernel, rank 128, fp32 input."""
+    layer = wl.Layer("t", 40, 5120, 64, 128, "mxb", 32, elem, elem, "f32", seed=9)
     X, W, L, R = wl.make_inputs(layer)
     _compare(oracle, layer, X, W, L, R)
 
