@@ -12,9 +12,11 @@ from tests.gpu_util import to_dev_x
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("family,g", [("int", 64), ("int", 128), ("mx", 32)])
-def test_graph_replays_match_eager(family, g):
-    layer = wl.Layer("t", 700, 512, 640, 32, family, g, 8, 8, "bf16", outlier_scale=10.0, n_outliers=4, seed=11)
+@pytest.mark.parametrize("family,g,bits", [("int", 64, 8), ("int", 128, 8), ("mx", 32, 8), ("mxb", 32, 8), ("mxb", 32, 6),
+                                           ("mxi", 32, 8)])
+def test_graph_replays_match_eager(family, g, bits):
+    layer = wl.Layer("t", 700, 512, 640, 32, family, g, bits, 8 if family == "mxi" else bits, "bf16", outlier_scale=10.0,
+                     n_outliers=4, seed=11)
     X, W, L, R = wl.make_inputs(layer)
     cfg = lq.config_for_layer(layer)
     packed = lq.lq_pack_weights(cfg, torch.from_numpy(W).cuda(), torch.from_numpy(L).cuda(), torch.from_numpy(R).cuda())
@@ -54,3 +56,25 @@ def test_graph_replays_match_eager(family, g):
         y2 = lq.lq_linear_lowrank_fwd(cfg, packed, a2, M)
         torch.cuda.synchronize()
         assert torch.equal(y2.view(torch.int16), eager[(i + 1) % 3].view(torch.int16))
+
+
+@pytest.mark.parametrize("family,bits", [("mx", 8), ("mxb", 8), ("mxb", 6), ("mxi", 8), ("mxi", 4)])
+def test_strided_views_and_determinism(family, bits):
+    """X and Y as column slices of wider tensors (row strides beyond K and N); repeated calls give identical bits."""
+    layer = wl.Layer("t", 130, 384, 192, 32, family, 32, bits, 8 if family == "mxi" else bits, "bf16", seed=13)
+    X, W, L, R = wl.make_inputs(layer)
+    cfg = lq.config_for_layer(layer)
+    packed = lq.lq_pack_weights(cfg, torch.from_numpy(W).cuda(), torch.from_numpy(L).cuda(), torch.from_numpy(R).cuda())
+    Xd = to_dev_x(X, "bf16")
+    ref = lq.lq_linear_lowrank_fwd(cfg, packed, lq.lq_quantize_act(cfg, packed, Xd), layer.M)
+    wide = torch.zeros((layer.M, layer.K + 64), dtype=torch.bfloat16, device="cuda")
+    wide[:, :layer.K] = Xd
+    wide[:, layer.K:] = 1e4                                     # must never be read into a block
+    Ywide = torch.zeros((layer.M, layer.N + 8), dtype=torch.bfloat16, device="cuda")
+    act = lq.lq_quantize_act(cfg, packed, wide[:, :layer.K])
+    lq.lq_linear_lowrank_fwd(cfg, packed, act, layer.M, Y=Ywide[:, :layer.N])
+    torch.cuda.synchronize()
+    assert torch.equal(Ywide[:, :layer.N].view(torch.int16), ref.view(torch.int16)) and not Ywide[:, layer.N:].any()
+    for _ in range(3):
+        again = lq.lq_linear_lowrank_fwd(cfg, packed, lq.lq_quantize_act(cfg, packed, Xd), layer.M)
+        assert torch.equal(again.view(torch.int16), ref.view(torch.int16))
