@@ -23,7 +23,7 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
     if (cfg->N <= 0 || cfg->K <= 0 || cfg->N > (1 << 24) || cfg->K > (1 << 24)) return LQ_ERR_SHAPE;
     if (cfg->K % 64 != 0 || cfg->N % 64 != 0) return LQ_ERR_SHAPE;
     const int r = cfg->rank;
-    if (!(r == 0 || r == 16 || r == 32 || r == 64 || r == 128)) return LQ_ERR_SHAPE;
+    if (!(r == 0 || r == 16 || r == 32 || r == 64 || r == 96 || r == 128)) return LQ_ERR_SHAPE;
     if (cfg->x_dtype != LQ_F32 && cfg->x_dtype != LQ_BF16) return LQ_ERR_UNSUPPORTED;
     if (cfg->residual_from_quantized != 0 && cfg->residual_from_quantized != 1) return LQ_ERR_UNSUPPORTED;
     d->N = cfg->N;
@@ -39,6 +39,7 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         if (cfg->main_w_group != 64 && cfg->main_w_group != 128) return LQ_ERR_SHAPE;
         if (cfg->K % cfg->main_w_group != 0) return LQ_ERR_SHAPE;
         if (cfg->main_a_group != 0) return LQ_ERR_UNSUPPORTED;
+        if (r == 96) return LQ_ERR_SHAPE;  // rank 96 (a 6-bit budget of 512 bits per channel, padded) only with block-scaled branches
         const int qw = int_qmax(cfg->br_w), qa = int_qmax(cfg->br_a);
         if (qw == 0 || qa == 0 || cfg->br_a == LQ_INT4) return LQ_ERR_UNSUPPORTED;
         if (d->smooth && cfg->K > 2304) return LQ_ERR_UNSUPPORTED;  // the smoothed row is held as fp32
@@ -56,6 +57,7 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
             return LQ_ERR_UNSUPPORTED;
         if (cfg->K % 128 != 0) return LQ_ERR_SHAPE;  // the MX forward stages K in steps of 128
         d->mxb = cfg->br_w != LQ_FP8_E4M3;
+        if (!d->mxb && r == 96) return LQ_ERR_SHAPE;
         d->mxb_elem = cfg->br_w == LQ_MXFP8_E4M3 ? 8 : cfg->br_w == LQ_MXFP6_E2M3 ? 6 : 0;
         if (d->mxb && r % 32 != 0) return LQ_ERR_SHAPE;  // whole blocks of 32 along the rank
         d->mx = true;

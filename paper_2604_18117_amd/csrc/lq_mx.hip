@@ -835,6 +835,7 @@ static hipError_t mxb_act_rank(const MxbActParams& p, int64_t Mp, hipStream_t s)
         case 0: return mxb_act_launch<BF16, 0>(p, Mp, s);
         case 32: return mxb_act_launch<BF16, 2>(p, Mp, s);
         case 64: return mxb_act_launch<BF16, 4>(p, Mp, s);
+        case 96: return mxb_act_launch<BF16, 6>(p, Mp, s);
         default: return mxb_act_launch<BF16, 8>(p, Mp, s);
     }
 }

@@ -420,6 +420,7 @@ static hipError_t mx6_act_rank(const Mx6ActParams& p, int64_t Mp, hipStream_t s)
         case 0: return mx6_act_launch<BF16, 0>(p, Mp, s);
         case 32: return mx6_act_launch<BF16, 2>(p, Mp, s);
         case 64: return mx6_act_launch<BF16, 4>(p, Mp, s);
+        case 96: return mx6_act_launch<BF16, 6>(p, Mp, s);
         default: return mx6_act_launch<BF16, 8>(p, Mp, s);
     }
 }

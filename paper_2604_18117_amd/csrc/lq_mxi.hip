@@ -513,6 +513,7 @@ static hipError_t mxi_act_rank(const MxiActParams& p, int64_t Mp, hipStream_t s)
         case 0: return mxi_act_launch<BF16, 0>(p, Mp, s);
         case 32: return mxi_act_launch<BF16, 2>(p, Mp, s);
         case 64: return mxi_act_launch<BF16, 4>(p, Mp, s);
+        case 96: return mxi_act_launch<BF16, 6>(p, Mp, s);
         default: return mxi_act_launch<BF16, 8>(p, Mp, s);
     }
 }
@@ -570,7 +571,7 @@ __device__ __forceinline__ v8i mxi_expand8(v4i p)  // 32 nibbles -> 32 FP8 subno
     return o;
 }
 
-// NK16 = 16-deep chunks of the rank: 0 | 2 | 4 | 8
+// NK16 = 16-deep chunks of the rank: 0 | 2 | 4 | 6 | 8
 template <int NK16, bool DBG>
 __global__ __launch_bounds__(256, 2) void mxi_fwd_kernel(MxiFwdParams p)
 {
@@ -821,6 +822,7 @@ hipError_t launch_fwd_mxi(const Dims& d, const uint8_t* packed, const uint8_t* a
         case 0: mxi_fwd_launch<0>(p, s); break;
         case 2: mxi_fwd_launch<2>(p, s); break;
         case 4: mxi_fwd_launch<4>(p, s); break;
+        case 6: mxi_fwd_launch<6>(p, s); break;
         default: mxi_fwd_launch<8>(p, s); break;
     }
     return hipGetLastError();

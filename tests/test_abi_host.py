@@ -155,6 +155,15 @@ def test_mxi_contract(lq):
     assert raw.lq_act_sizes(C.byref(big), 64, C.byref(n)) == lq.LQ_OK
 
 
+def test_rank_96_only_with_block_scaled_branches(lq):
+    n = C.c_size_t(0)
+    raw = lq.raw()
+    for fam, kw in (("mxb", {}), ("mxb", dict(br_w_bits=6)), ("mxi", {})):
+        assert raw.lq_packed_sizes(C.byref(_cfg(lq, family=fam, rank=96, **kw)), C.byref(n)) == lq.LQ_OK
+    for fam in ("int", "mx"):
+        assert raw.lq_packed_sizes(C.byref(_cfg(lq, family=fam, rank=96)), C.byref(n)) == lq.LQ_ERR_SHAPE
+
+
 def test_smoothing_contract(lq):
     raw = lq.raw()
     n = C.c_size_t(0)

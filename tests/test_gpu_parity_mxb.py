@@ -106,6 +106,7 @@ SMALL = [
     (64, 128, 64, 0, "bf16"),
     (33, 640, 128, 128, "bf16"),
     (1, 128, 64, 32, "f32"),
+    (50, 256, 64, 96, "bf16"),     # a 6-bit budget of 512 bits per channel gives rank 85: padded to three blocks of 32
 ]
 
 

@@ -107,6 +107,7 @@ SMALL = [
     (257, 576, 512, 64, 8, "bf16"),
     (40, 5120, 64, 32, 8, "bf16"),      # K beyond what the row-resident activation kernels of the other families take
     (18, 2368, 64, 64, 4, "f32"),
+    (50, 256, 64, 96, 8, "bf16"),
 ]
 
 
