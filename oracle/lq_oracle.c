@@ -16,6 +16,9 @@
  *   INT  : symmetric signed integers, round-to-nearest-even, fp32 scales
  *          (SINT4-style block scales along K for Q1(P), App. A.3; per-token / per-channel
  *          scales elsewhere); integer accumulate, fp32 dequantisation.
+ *          With a_group = 64 (the literal SINT4 of App. A.3: blocks of 64 values, one FP16 scale
+ *          per block) both operands of the main product are quantised in blocks of 64 along K
+ *          with FP16 scales; the branch is unchanged.
  *   MX   : Q1 = MXFP4 (E2M1 elements, blocks of 32 along K, E8M0 power-of-two scale,
  *          App. A.3), Q2 = FP8 E4M3 with one fp32 scale per token / per channel;
  *          fp64 accumulate, result rounded once to fp32.
@@ -48,6 +51,11 @@
  *     element exponent 0, and the same pattern at 4 bits: 1 + 1 + 2); the block maximum
  *     therefore lands in the top octave of the code range, a value that would round to
  *     2^(b-1) saturates, -2^(b-1) is never produced; all-zero block: E8M0 byte 0;
+ *   - SINT4 blocks: the stored scale is s = fp16_rne(amax / 7) (kept inside the positive finite
+ *     FP16 range: at least 2^-24, at most 65504; all-zero block: s = 1); codes are taken against
+ *     the STORED scale, code = clamp(rne(v * fl(1 / s)), -7, 7); a block contributes
+ *     fma(float(acc), sx * sw, t) to the running fp32 sum, where the product of the two FP16
+ *     scales is exact in fp32, and the branch is added with one fp32 addition;
  *   - activation smoothing divides by gamma as a multiplication by fl(1/gamma);
  *   - P is built from the *dequantised* quantised factors (Fig. 1), optionally from the
  *     unquantised ones (residual_from_quantized = 0).
@@ -112,6 +120,53 @@ LQO_API void lqo_quant_int(const float *v, int64_t n, int qmax, int8_t *q, float
         q[i] = (int8_t)r;
     }
     *scale = s;
+}
+
+/* fp32 -> nearest value with FP16's precision (11 significant bits, subnormal spacing 2^-24; ties to
+   even), returned as fp32.  Finite inputs.  The exponent range is not limited at the top: magnitudes
+   of 65520 and more come back as 65536 or larger and the caller clamps to 65504. */
+static float f16_round(float f)
+{
+    float a = fabsf(f);
+    float r;
+    if (a == 0.0f) return f;
+    if (a < 6.103515625e-05f) { /* below 2^-14: FP16 subnormals, spacing 2^-24 */
+        r = ldexpf(nearbyintf(ldexpf(a, 24)), -24);
+    } else {
+        int e;
+        (void)frexpf(a, &e);  /* a = m * 2^e, m in [0.5, 1)  ->  a in [2^(e-1), 2^e) */
+        /* 11 significant bits: spacing 2^(e-1-10) */
+        r = ldexpf(nearbyintf(ldexpf(a, 11 - e)), e - 11);
+    }
+    return f < 0.0f ? -r : r;
+}
+
+LQO_API float lqo_f16_round(float f) { return f16_round(f); }
+
+/* SINT4 block quantiser (App. A.3): n values (n a multiple of 64) in blocks of 64, one FP16 scale
+   per block (returned as fp32), round-to-nearest on the scaled values. */
+LQO_API void lqo_quant_sint4(const float *v, int64_t n, int8_t *q, float *scales)
+{
+    for (int64_t b = 0; b < n / 64; ++b) {
+        const float *blk = v + 64 * b;
+        float a = absmax_f32(blk, 64);
+        float s;
+        if (a == 0.0f) {
+            s = 1.0f;
+        } else {
+            s = f16_round(a / 7.0f);
+            if (s < 5.9604644775390625e-08f) s = 5.9604644775390625e-08f; /* 2^-24 */
+            if (s > 65504.0f) s = 65504.0f;
+        }
+        float inv = 1.0f / s;
+        for (int i = 0; i < 64; ++i) {
+            float r = nearbyintf(blk[i] * inv);
+            if (r > 7.0f) r = 7.0f;
+            if (r < -7.0f) r = -7.0f;
+            q[64 * b + i] = (int8_t)r;
+        }
+        scales[b] = s;
+    }
 }
 
 /* Activation smoothing (Section 3.4; App. A.1): channel k of X is divided by gamma[k] before
@@ -239,11 +294,12 @@ LQO_API void lqo_quant_fp8(const float *v, int64_t n, uint8_t *codes, float *sca
 /* Offline packing step (Fig. 1; Eq. 5): quantise the factors with Q2, form the residual P,
    quantise P with Q1 in groups of g along K.
    qmax_bw : qmax of the branch weight format (127 / 31 / 7).
+   sint4_blocks != 0 (then g == 64): Q1 is the literal SINT4 block format with FP16 scales.
    Outputs: pq N x K, sw N x (K/g), lq N x r, sl N, rq r x K, sr r, P (optional, N x K). */
 LQO_API void lqo_pack_int(int64_t N, int64_t K, int r, int g, int qmax_bw,
                           int residual_from_quantized, const float *W, const float *L,
                           const float *R, int8_t *pq, float *sw, int8_t *lq, float *sl,
-                          int8_t *rq, float *sr, float *P_out)
+                          int8_t *rq, float *sr, float *P_out, int sint4_blocks)
 {
     const int64_t G = K / g;
     for (int j = 0; j < r; ++j) lqo_quant_int(R + (int64_t)j * K, K, qmax_bw, rq + (int64_t)j * K, &sr[j]);
@@ -267,8 +323,11 @@ LQO_API void lqo_pack_int(int64_t N, int64_t K, int r, int g, int qmax_bw,
             }
             P[k] = (float)((double)W[n * K + k] - d);
         }
-        for (int64_t gi = 0; gi < G; ++gi)
-            lqo_quant_int(P + gi * g, g, 7, pq + n * K + gi * g, &sw[n * G + gi]);
+        if (sint4_blocks)
+            lqo_quant_sint4(P, K, pq + n * K, sw + n * G);
+        else
+            for (int64_t gi = 0; gi < G; ++gi)
+                lqo_quant_int(P + gi * g, g, 7, pq + n * K + gi * g, &sw[n * G + gi]);
         if (P_out) memcpy(P_out + n * K, P, sizeof(float) * (size_t)K);
         free(P);
     }
@@ -277,17 +336,21 @@ LQO_API void lqo_pack_int(int64_t N, int64_t K, int r, int g, int qmax_bw,
 /* Per-call activation step: 4-bit codes for the main product, b-bit codes for the branch,
    the skinny contraction with Q2(R) and the re-quantisation of its result.
    qmax_a : qmax of the branch activation format (127 / 31).
-   Outputs: xq M x K, sx M, xb M x K, sxb M, accT M x r (int32), T M x r, tq M x r, st M.
+   a_group: 0 = one main scale per token (sx M); 64 = SINT4 blocks along K (sx M x K/64).
+   Outputs: xq M x K, sx, xb M x K, sxb M, accT M x r (int32), T M x r, tq M x r, st M.
    Any of xb / accT / T may be NULL. */
 LQO_API void lqo_quantize_act_int(int64_t M, int64_t K, int r, int qmax_a, const float *X,
                                   const int8_t *rq, const float *sr, int8_t *xq, float *sx,
                                   int8_t *xb, float *sxb, int32_t *accT, float *T,
-                                  int8_t *tq, float *st)
+                                  int8_t *tq, float *st, int a_group)
 {
 #pragma omp parallel for schedule(static)
     for (int64_t m = 0; m < M; ++m) {
         const float *x = X + m * K;
-        lqo_quant_int(x, K, 7, xq + m * K, &sx[m]);
+        if (a_group)
+            lqo_quant_sint4(x, K, xq + m * K, sx + m * (K / 64));
+        else
+            lqo_quant_int(x, K, 7, xq + m * K, &sx[m]);
         if (r == 0) continue;
         int8_t *xbrow = (int8_t *)malloc((size_t)K);
         float *Trow = (float *)malloc(sizeof(float) * (size_t)r);
@@ -309,12 +372,14 @@ LQO_API void lqo_quantize_act_int(int64_t M, int64_t K, int r, int qmax_a, const
 }
 
 /* Forward: main 4-bit product with per-group fp32 dequantisation, rank-r expansion, sum.
+   a_group = 64 (then g == 64): sx is M x G, and a block's accumulator is scaled by the product of
+   the two block scales (exact in fp32 for FP16 scales).
    Outputs: acc M x N x G int32 (optional), acc2 M x N int32 (optional), ymain, ybr, y32
    (fp32, M x N, each optional) and Y (bf16 bits, M x N). */
 LQO_API void lqo_fwd_int(int64_t M, int64_t N, int64_t K, int r, int g, const int8_t *xq,
                          const float *sx, const int8_t *pq, const float *sw, const int8_t *tq,
                          const float *st, const int8_t *lq, const float *sl, int32_t *acc,
-                         int32_t *acc2, float *ymain, float *ybr, float *y32, uint16_t *Y)
+                         int32_t *acc2, float *ymain, float *ybr, float *y32, uint16_t *Y, int a_group)
 {
     const int64_t G = K / g;
 #pragma omp parallel for schedule(static)
@@ -326,9 +391,12 @@ LQO_API void lqo_fwd_int(int64_t M, int64_t N, int64_t K, int r, int g, const in
                 for (int k = 0; k < g; ++k)
                     a += (int32_t)xq[m * K + gi * g + k] * (int32_t)pq[n * K + gi * g + k];
                 if (acc) acc[(m * N + n) * G + gi] = a;
-                t = fmaf((float)a, sw[n * G + gi], t);
+                if (a_group)
+                    t = fmaf((float)a, sx[m * G + gi] * sw[n * G + gi], t);
+                else
+                    t = fmaf((float)a, sw[n * G + gi], t);
             }
-            float ym = sx[m] * t;
+            float ym = a_group ? t : sx[m] * t;
             float yb = 0.0f;
             if (r > 0) {
                 int32_t a2 = 0;
@@ -338,7 +406,8 @@ LQO_API void lqo_fwd_int(int64_t M, int64_t N, int64_t K, int r, int g, const in
             } else if (acc2) {
                 acc2[m * N + n] = 0;
             }
-            float y = fmaf(sx[m], t, yb); /* sum node of Fig. 1: one rounding for scale-and-add */
+            /* sum node of Fig. 1: one rounding for scale-and-add (per-token scale) or for the add */
+            float y = a_group ? t + yb : fmaf(sx[m], t, yb);
             if (ymain) ymain[m * N + n] = ym;
             if (ybr) ybr[m * N + n] = yb;
             if (y32) y32[m * N + n] = y;

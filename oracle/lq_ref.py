@@ -43,6 +43,8 @@ def lib():
         _lib.lqo_bf16_rne.restype = C.c_uint16
         _lib.lqo_bf16_rne.argtypes = [C.c_float]
         _lib.lqo_num_threads.restype = C.c_int
+        _lib.lqo_f16_round.restype = C.c_float
+        _lib.lqo_f16_round.argtypes = [C.c_float]
     return _lib
 
 
@@ -75,6 +77,20 @@ def quant_int(v, qmax: int):
     s = np.empty(1, np.float32)
     lib().lqo_quant_int(_p(v), C.c_int64(v.size), C.c_int(qmax), _p(q), _p(s))
     return q, s[0]
+
+
+def f16_round(f: float) -> float:
+    return float(lib().lqo_f16_round(C.c_float(f)))
+
+
+def quant_sint4(v):
+    """SINT4 blocks: n values (n % 64 == 0) -> (codes int8 [n], FP16-valued scales float32 [n/64])."""
+    v = _f32(v).ravel()
+    assert v.size % 64 == 0
+    q = np.empty(v.size, np.int8)
+    s = np.empty(v.size // 64, np.float32)
+    lib().lqo_quant_sint4(_p(v), C.c_int64(v.size), _p(q), _p(s))
+    return q, s
 
 
 def smooth(X, gamma):
@@ -155,6 +171,7 @@ class PackedInt:
     K: int
     r: int
     g: int
+    sint4: bool      # SINT4 blocks: g == 64, FP16-valued scales
     pq: np.ndarray   # N x K int8 in [-7,7]
     sw: np.ndarray   # N x G float32
     lq: np.ndarray   # N x r int8
@@ -164,22 +181,23 @@ class PackedInt:
     P: np.ndarray    # N x K float32 residual before Q1
 
 
-def pack_int(W, L, R, g: int, br_w_bits: int, residual_from_quantized: bool = True) -> PackedInt:
+def pack_int(W, L, R, g: int, br_w_bits: int, residual_from_quantized: bool = True,
+             sint4_blocks: bool = False) -> PackedInt:
     W = _f32(W)
     N, K = W.shape
     r = 0 if L is None else int(np.shape(L)[1])
-    assert K % g == 0
+    assert K % g == 0 and (g == 64 or not sint4_blocks)
     Lc = _f32(L) if r else np.zeros((N, 0), np.float32)
     Rc = _f32(R) if r else np.zeros((0, K), np.float32)
     G = K // g
-    out = PackedInt(N, K, r, g, np.empty((N, K), np.int8), np.empty((N, G), np.float32),
+    out = PackedInt(N, K, r, g, bool(sint4_blocks), np.empty((N, K), np.int8), np.empty((N, G), np.float32),
                     np.empty((N, r), np.int8), np.ones(N, np.float32),
                     np.empty((r, K), np.int8), np.ones(r, np.float32),
                     np.empty((N, K), np.float32))
     lib().lqo_pack_int(C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(g),
                        C.c_int(QMAX[br_w_bits]), C.c_int(1 if residual_from_quantized else 0),
                        _p(W), _p(Lc), _p(Rc), _p(out.pq), _p(out.sw), _p(out.lq), _p(out.sl),
-                       _p(out.rq), _p(out.sr), _p(out.P))
+                       _p(out.rq), _p(out.sr), _p(out.P), C.c_int(1 if sint4_blocks else 0))
     return out
 
 
@@ -187,7 +205,7 @@ def pack_int(W, L, R, g: int, br_w_bits: int, residual_from_quantized: bool = Tr
 class ActInt:
     M: int
     xq: np.ndarray    # M x K int8 in [-7,7]
-    sx: np.ndarray    # M
+    sx: np.ndarray    # M, or M x K/64 with SINT4 blocks
     xb: np.ndarray    # M x K int8
     sxb: np.ndarray   # M
     accT: np.ndarray  # M x r int32
@@ -197,17 +215,19 @@ class ActInt:
 
 
 def quantize_act_int(X, pk: PackedInt, br_a_bits: int) -> ActInt:
+    """Main activation scales follow the packed weights: SINT4 blocks for both operands or for neither."""
     X = _f32(X)
     M, K = X.shape
     assert K == pk.K
     r = pk.r
-    out = ActInt(M, np.empty((M, K), np.int8), np.empty(M, np.float32),
+    out = ActInt(M, np.empty((M, K), np.int8), np.empty((M, K // 64) if pk.sint4 else M, np.float32),
                  np.zeros((M, K), np.int8), np.ones(M, np.float32),
                  np.zeros((M, r), np.int32), np.zeros((M, r), np.float32),
                  np.zeros((M, r), np.int8), np.ones(M, np.float32))
     lib().lqo_quantize_act_int(C.c_int64(M), C.c_int64(K), C.c_int(r), C.c_int(QMAX[br_a_bits]),
                                _p(X), _p(pk.rq), _p(pk.sr), _p(out.xq), _p(out.sx), _p(out.xb),
-                               _p(out.sxb), _p(out.accT), _p(out.T), _p(out.tq), _p(out.st))
+                               _p(out.sxb), _p(out.accT), _p(out.T), _p(out.tq), _p(out.st),
+                               C.c_int(64 if pk.sint4 else 0))
     return out
 
 
@@ -231,7 +251,7 @@ def fwd_int(pk: PackedInt, act: ActInt, want_acc: bool = False) -> FwdOut:
     lib().lqo_fwd_int(C.c_int64(M), C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(g),
                       _p(act.xq), _p(act.sx), _p(pk.pq), _p(pk.sw), _p(act.tq), _p(act.st),
                       _p(pk.lq), _p(pk.sl), _p(acc), _p(acc2), _p(out.ymain), _p(out.ybr),
-                      _p(out.y32), _p(out.Y))
+                      _p(out.y32), _p(out.Y), C.c_int(64 if pk.sint4 else 0))
     return out
 
 

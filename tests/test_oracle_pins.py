@@ -217,6 +217,148 @@ def test_scale_and_sign_equivariance(oracle):
     assert np.array_equal(q3, -q) and s3 == s
 
 
+
+# --------------------------------------------------------------------------------------
+# SINT4 blocks (App. A.3: blocks of 64 values, one FP16 scale per block, round to nearest)
+# --------------------------------------------------------------------------------------
+
+def test_f16_rounding_matches_ieee_half(oracle):
+    # numpy's float16 cast is an independent implementation of round-to-nearest-even to binary16
+    rng = np.random.default_rng(21)
+    v = (rng.standard_normal(20000) * np.exp2(rng.uniform(-27, 15.9, 20000))).astype(np.float32)
+    special = np.float32([0.0, 2.0 ** -24, 2.0 ** -25, 1.5 * 2.0 ** -25, 2.0 ** -14, 2.0 ** -14 - 2.0 ** -26, 65504.0, 65519.0,
+                          1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 1.0 + 2.0 ** -11 + 2.0 ** -20, -3.0003])
+    v = np.concatenate([v[np.abs(v) < 65520], special, -special])
+    got = np.array([oracle.f16_round(float(x)) for x in v], np.float32)
+    want = v.astype(np.float16).astype(np.float32)
+    assert np.array_equal(got, want)
+    assert oracle.f16_round(float(np.float32(1.0 + 2.0 ** -11))) == 1.0                       # tie -> even
+    assert oracle.f16_round(float(np.float32(1.0 + 3 * 2.0 ** -11))) == 1.0 + 2.0 ** -9       # tie -> even (up)
+
+
+def test_sint4_block_quantiser(oracle):
+    rng = np.random.default_rng(22)
+    v = (rng.standard_normal(64 * 40) * np.repeat(np.exp2(rng.uniform(-12, 8, 40)), 64)).astype(np.float32)
+    q, s = oracle.quant_sint4(v)
+    vb, qb = v.reshape(40, 64), q.reshape(40, 64)
+    # one scale per block of 64, an FP16 number: the nearest one to amax / 7
+    assert s.shape == (40,)
+    assert np.array_equal(s, s.astype(np.float16).astype(np.float32))
+    amax = np.abs(vb).max(axis=1)
+    for b in range(40):
+        exact = Fraction(float(amax[b])) / 7
+        sb = Fraction(float(s[b]))
+        ulp = Fraction(float(np.spacing(np.float16(s[b]))))
+        assert abs(sb - exact) <= ulp / 2 + exact * Fraction(1, 2 ** 23)     # nearest FP16 to the fp32 quotient
+        # codes: nearest integer to x / s (stored scale), within [-7, 7]; the block maximum maps to +-7
+        assert qb[b].min() >= -7 and qb[b].max() <= 7
+        assert abs(int(qb[b][np.argmax(np.abs(vb[b]))])) == 7
+        for x, qi in zip(vb[b], qb[b]):
+            u = Fraction(float(x)) / sb
+            if abs(u) <= 7:
+                assert abs(u - int(qi)) <= Fraction(1, 2) + Fraction(1, 2 ** 18)
+            else:
+                assert abs(int(qi)) == 7      # the scale was rounded down: at most 7 (1 + 2^-11)
+                assert abs(u) <= 7 * (1 + Fraction(1, 2 ** 11))
+    # dequantisation error: half a step (plus the clamp slack above)
+    assert np.all(np.abs(vb.astype(np.float64) - s[:, None].astype(np.float64) * qb) <= s[:, None] * (0.5 + 7 * 2.0 ** -11))
+    # blocks are independent: changing one block leaves the others' codes and scales alone
+    v2 = v.copy()
+    v2[64:128] *= 3
+    q2, s2 = oracle.quant_sint4(v2)
+    keep = np.r_[0:64, 128:v.size]
+    assert np.array_equal(q[keep], q2[keep]) and np.array_equal(np.delete(s, 1), np.delete(s2, 1))
+
+
+def test_sint4_block_edge_cases(oracle):
+    # exact ties with a power-of-two scale: amax = 14 -> s = 2: 5 -> 2.5 -> 2, 7 -> 3.5 -> 4, 3 -> 1.5 -> 2, 1 -> 0.5 -> 0
+    v = np.zeros(128, np.float32)
+    v[:8] = [14, 5, 7, 3, 1, -1, -3, -5]
+    q, s = oracle.quant_sint4(v)
+    assert list(q[:8]) == [7, 2, 4, 2, 0, 0, -2, -2] and s[0] == 2.0
+    assert s[1] == 1.0 and not q[64:].any()                      # all-zero block
+    # scales outside the FP16 range are clamped to it and the codes saturate / flush accordingly
+    tiny = np.zeros(64, np.float32)
+    tiny[0], tiny[1], tiny[2] = 1e-6, 2.0 ** -25 * 1.01, -2.0 ** -26
+    q, s = oracle.quant_sint4(tiny * np.float32(1e-1))           # amax / 7 = 1.4e-8 < 2^-25: rounds to 0 -> 2^-24
+    assert s[0] == np.float32(2.0 ** -24)
+    assert list(q[:3]) == [2, 0, 0]                              # 1e-7 / 2^-24 = 1.68 -> 2
+    q, s = oracle.quant_sint4(tiny)                              # amax / 7 = 1.43e-7 = 2.4 * 2^-24 -> 2 * 2^-24
+    assert s[0] == np.float32(2.0 ** -23)
+    assert list(q[:3]) == [7, 0, 0]                              # 1e-6 / 2^-23 = 8.4 -> clamped to 7
+    huge = np.zeros(64, np.float32)
+    huge[0], huge[1] = 1e6, -3e5
+    q, s = oracle.quant_sint4(huge)
+    assert s[0] == np.float32(65504.0) and list(q[:2]) == [7, -5]   # 1e6 / 65504 = 15.3 -> 7; 3e5 / 65504 = 4.58 -> 5
+    # idempotence on the grid (Section 3.2): codes are reproduced, and so is a scale whose 7-fold is exact
+    rng = np.random.default_rng(23)
+    w = rng.standard_normal(256).astype(np.float32)
+    q, s = oracle.quant_sint4(w)
+    q2, s2 = oracle.quant_sint4((q.reshape(4, 64) * s[:, None]).astype(np.float32).ravel())
+    assert np.array_equal(q, q2)
+    assert np.all(np.abs(s2 - s) <= np.spacing(s.astype(np.float16)).astype(np.float32))
+
+
+def _small_sint4_problem(oracle, seed=5, M=6, K=256, N=10, r=8):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    X[:, rng.choice(K, 3, replace=False)] *= 15
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    L = (rng.standard_normal((N, r)) * 1e-3).astype(np.float32)
+    R = (rng.standard_normal((r, K)) * 1e-3).astype(np.float32)
+    pk = oracle.pack_int(W, L, R, 64, 8, sint4_blocks=True)
+    act = oracle.quantize_act_int(X, pk, 8)
+    out = oracle.fwd_int(pk, act, want_acc=True)
+    return X, W, L, R, pk, act, out
+
+
+def test_sint4_block_forward_against_exact_rationals(oracle):
+    X, W, L, R, pk, act, out = _small_sint4_problem(oracle)
+    M, K = X.shape
+    N, G = pk.N, K // 64
+    # both operands of the main product carry one FP16 scale per block of 64 along K
+    assert act.sx.shape == (M, G) and pk.sw.shape == (N, G)
+    for a in (act.sx, pk.sw):
+        assert np.array_equal(a, a.astype(np.float16).astype(np.float32))
+    # the codes are those of the block quantiser applied row by row (to X, and to the residual P)
+    for m in range(M):
+        q, s = oracle.quant_sint4(X[m])
+        assert np.array_equal(q, act.xq[m]) and np.array_equal(s, act.sx[m])
+    q, s = oracle.quant_sint4(pk.P[3])
+    assert np.array_equal(q, pk.pq[3]) and np.array_equal(s, pk.sw[3])
+    # the branch is the per-token / per-row branch of the plain INT path, bit for bit
+    pk0 = oracle.pack_int(W, L, R, 64, 8)
+    act0 = oracle.quantize_act_int(X, pk0, 8)
+    assert np.array_equal(pk.lq, pk0.lq) and np.array_equal(pk.rq, pk0.rq) and np.array_equal(pk.P, pk0.P)
+    assert np.array_equal(act.tq, act0.tq) and np.array_equal(act.st, act0.st) and np.array_equal(act.xb, act0.xb)
+    # integer contractions are textbook matrix products per block
+    xq = act.xq.astype(np.int64).reshape(M, G, 64)
+    pq = pk.pq.astype(np.int64).reshape(N, G, 64)
+    assert np.array_equal(out.acc, np.einsum("mgk,ngk->mng", xq, pq))
+    # y32 = sum_g acc * sx * sw + branch, exact up to the fp32 roundings of the G + 3 operations
+    for m in range(M):
+        for n in range(N):
+            terms = [Fraction(int(out.acc[m, n, g])) * Fraction(float(act.sx[m, g])) * Fraction(float(pk.sw[n, g]))
+                     for g in range(G)]
+            br = Fraction(int(out.acc2[m, n])) * Fraction(float(act.st[m])) * Fraction(float(pk.sl[n]))
+            mag = float(sum(abs(t) for t in terms) + abs(br))
+            assert abs(float(sum(terms) + br) - float(out.y32[m, n])) <= (G + 4) * 2 ** -24 * mag
+            assert abs(float(sum(terms)) - float(out.ymain[m, n])) <= (G + 1) * 2 ** -24 * mag
+    # a single block (K = 64) and no branch: y32 is the correctly rounded acc * (sx * sw), no other rounding
+    pk1 = oracle.pack_int(W[:, :64], None, None, 64, 8, sint4_blocks=True)
+    act1 = oracle.quantize_act_int(X[:, :64], pk1, 8)
+    o1 = oracle.fwd_int(pk1, act1, want_acc=True)
+    p = (act1.sx[:, 0][:, None].astype(np.float64) * pk1.sw[:, 0][None, :].astype(np.float64))   # exact in fp64 and in fp32
+    assert np.array_equal(p.astype(np.float32).astype(np.float64), p)
+    want = (o1.acc[:, :, 0].astype(np.float64) * p).astype(np.float32)                         # one rounding
+    assert np.array_equal(o1.y32, want)
+    # finer scales help: with outlier channels the block-scaled main product is closer to X P^T than the per-token one
+    ref = X.astype(np.float64) @ pk.P.astype(np.float64).T
+    out0 = oracle.fwd_int(pk0, act0)
+    e_blk = np.abs(out.ymain - ref).mean()
+    e_tok = np.abs(out0.ymain - ref).mean()
+    assert e_blk < e_tok
+
 # --------------------------------------------------------------------------------------
 # whole INT path
 # --------------------------------------------------------------------------------------
