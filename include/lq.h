@@ -16,6 +16,10 @@
  *         activations one fp32 scale per token.  Q2 = signed INT8 / INT6 / INT4 with one
  *         scale per token (activations, intermediate) or per row of L / R (weights).
  *         Integer accumulation, fp32 dequantisation.
+ *         With main_a_group = 64 (and main_w_group = 64) both operands of the main product use the
+ *         literal SINT4 block format of App. A.3: blocks of 64 values along K, one FP16 scale per
+ *         block, s = fp16(amax / 7) kept inside [2^-24, 65504], codes clamp(rne(v * fl(1 / s))), and
+ *         Y = sum_g acc_g * (sx[m,g] * sw[n,g]) + branch.  The branch keeps its per-token scales.
  *   MX  : Q1 = MXFP4 (E2M1 elements, blocks of 32 along K, E8M0 scale, App. A.3) for both
  *         operands; Q2 = FP8 E4M3 with one fp32 scale per token / per row, or (all-MX setting of
  *         the mixed-precision tables, Section 4.3) MXFP8e4 / MXFP6e2: E4M3 / E2M3 elements in blocks of 32 along
@@ -82,7 +86,7 @@ typedef struct {
     int32_t main_w;                  /* lq_fmt: LQ_INT4 | LQ_MXFP4_E2M1                          */
     int32_t main_a;                  /* lq_fmt: must equal main_w                                 */
     int32_t main_w_group;            /* INT: 64 | 128 values along K per weight scale; MX, MXI: 32 */
-    int32_t main_a_group;            /* INT: 0 = one scale per token; MX, MXI: 32                 */
+    int32_t main_a_group;            /* INT: 0 = one scale per token, 64 = SINT4 blocks (needs main_w_group 64); MX, MXI: 32 */
     int32_t br_w;                    /* lq_fmt of Q2(L), Q2(R): INT8|INT6|INT4; MX: FP8 | MXFP8 | MXFP6; MXI: MXINT8 | MXINT4 */
     int32_t br_a;                    /* lq_fmt of Q2(X), Q2(X R^T): INT8|INT6; MX: = br_w; MXI: MXINT8 */
     int32_t residual_from_quantized; /* 1: P = W - deq(Q2 L) deq(Q2 R) (Fig. 1); 0: P = W - L R  */
@@ -116,7 +120,7 @@ typedef struct {
    byte, pe / xe the E8M0 bytes (N x K/32, M x K/32), lq / rq / tq E4M3 bytes. */
 typedef struct {
     int8_t  *pq;    /* N x K                                                                   */
-    float   *sw;    /* N x (K / main_w_group)     (INT)                                        */
+    float   *sw;    /* N x (K / main_w_group)     (INT; FP16-valued with main_a_group = 64)      */
     uint8_t *pe;    /* N x (K / 32)               (MX)                                         */
     int8_t  *lq;    /* N x r                                                                   */
     float   *sl;    /* N                                                                       */
@@ -128,7 +132,7 @@ typedef struct {
 
 typedef struct {
     int8_t  *xq;    /* M x K                                                                   */
-    float   *sx;    /* M                          (INT)                                        */
+    float   *sx;    /* M                          (INT);  M x (K / 64) with main_a_group = 64    */
     uint8_t *xe;    /* M x (K / 32)               (MX)                                         */
     int8_t  *tq;    /* M x r                                                                   */
     float   *st;    /* M                                                                       */

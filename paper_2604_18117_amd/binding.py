@@ -93,9 +93,11 @@ def raw():
 
 def make_config(N: int, K: int, rank: int, family: str = "int", group: int = 64, br_w_bits: int = 8,
                 br_a_bits: int = 8, x_dtype: str = "bf16", residual_from_quantized: bool = True,
-                smooth: bool = False) -> lq_config:
+                smooth: bool = False, a_group: int = 0) -> lq_config:
+    """a_group (INT family): 0 = one main activation scale per token; 64 = SINT4 blocks (FP16 scale per 64
+    values along K) for both operands of the main product."""
     if family == "int":
-        return lq_config(N, K, rank, LQ_INT4, LQ_INT4, group, 0, _INT_FMT[br_w_bits], _INT_FMT[br_a_bits],
+        return lq_config(N, K, rank, LQ_INT4, LQ_INT4, group, a_group, _INT_FMT[br_w_bits], _INT_FMT[br_a_bits],
                          1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32,
                          LQ_FLAG_SMOOTH if smooth else 0)
     if smooth:
@@ -112,7 +114,7 @@ def make_config(N: int, K: int, rank: int, family: str = "int", group: int = 64,
 
 def config_for_layer(layer, smooth: bool = False) -> lq_config:
     return make_config(layer.N, layer.K, layer.r, layer.family, layer.g, layer.br_w_bits, layer.br_a_bits,
-                       layer.x_dtype, smooth=smooth)
+                       layer.x_dtype, smooth=smooth, a_group=layer.a_group)
 
 
 def _stream() -> int:
@@ -266,7 +268,7 @@ def lq_unpack_act(cfg: lq_config, act: torch.Tensor, M: int) -> ActView:
     K, r = cfg.K, cfg.rank
     mx = cfg.main_w in (LQ_MXFP4_E2M1, LQ_MXINT4)
     v = ActView(torch.zeros((M, K), dtype=torch.int8, device=dev),
-                None if mx else torch.zeros(M, dtype=torch.float32, device=dev),
+                None if mx else torch.zeros((M, K // 64) if cfg.main_a_group == 64 else M, dtype=torch.float32, device=dev),
                 torch.zeros((M, K // 32), dtype=torch.uint8, device=dev) if mx else None,
                 torch.zeros((M, max(r, 1)), dtype=torch.int8, device=dev),
                 torch.zeros(M, dtype=torch.float32, device=dev),

@@ -4,6 +4,8 @@
 //   sxb = amax/qa,    xb = rne(x * qa/amax)         branch codes, kept in registers only
 //   accT = xb . rq^T  (int8 MFMA, int32)            skinny contraction with Q2(R)
 //   T = (float(accT) * sxb) * sr ;  st = max|T|/qa ;  tq = rne(T * qa/max|T|)
+// SINT4 blocks (App. A.3; template flag GA): the main codes take one FP16 scale per 64-chunk of K instead
+// of one scale per token, sx[m,g] = fp16(amax_g / 7), codes clamp(rne(x * fl(1 / sx))); the branch is unchanged.
 //
 // Decomposition: a workgroup of 4 wavefronts owns 16 token rows; lane l of every wavefront
 // works on row l%16 and on the 16-value quarter l/16 of each 64-deep K chunk, which is
@@ -27,6 +29,8 @@ struct ActParams {
     const float* sr;
     uint8_t* xq;
     float* sx;
+    uint32_t* sxg;  // SINT4 blocks: FP16 bits of the block scales (sxg_index), tiles128 = 128-row tiles
+    int tiles128, Mp;
     int8_t* tq;
     float* st;
     int8_t* dbg_xb;
@@ -117,7 +121,7 @@ __device__ __forceinline__ void scales(float amax, float qmax, float* s, float* 
 __device__ __forceinline__ uint32_t rne_bits(float u) { return __float_as_uint(__fadd_rn(u, 12582912.0f)); }
 
 // BF16IN: element type of X; SM: smoothing variant (X times stored reciprocals, row held as fp32).
-template <bool BF16IN, int MAXC, int NJB, bool SM = false>
+template <bool BF16IN, int MAXC, int NJB, bool SM = false, bool GA = false>
 __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
 {
     constexpr bool BF16 = BF16IN && !SM;  // representation of the row in registers
@@ -187,7 +191,7 @@ __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
     scales(a, 7.0f, &s4, &inv4);
     scales(a, p.qa, &sb, &invb);
     if (wave == 0 && kq == 0) {
-        p.sx[row] = s4;
+        if constexpr (!GA) p.sx[row] = s4;
         s_sxb[r16] = sb;
         if (p.dbg_sxb && row_ok) p.dbg_sxb[row] = sb;
         if (p.r == 0) p.st[row] = 1.0f;
@@ -205,6 +209,31 @@ __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
         if (c < C64) {  // wave-uniform
             uint32_t pk[2] = {0u, 0u};
             uint32_t xb4[4] = {0u, 0u, 0u, 0u};
+            if constexpr (GA) {
+                // block scale of this 64-chunk: amax over the lane's 16 values, then over the row's 4 lanes
+                float ac = 0.f;
+                if constexpr (BF16) {
+                    us2 m2 = {0, 0};
+#pragma unroll
+                    for (int d = 0; d < 8; ++d)
+                        m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, xc[ci].w[d] & 0x7FFF7FFFu));
+                    const uint32_t mm = m2[0] > m2[1] ? m2[0] : m2[1];
+                    ac = __uint_as_float(mm << 16);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) ac = fmaxf(ac, fabsf(xc[ci].get(i)));
+                }
+                ac = fmaxf(ac, __shfl_xor(ac, 16, 64));
+                ac = fmaxf(ac, __shfl_xor(ac, 32, 64));
+                const uint32_t bits = sint4_scale(ac, &inv4);
+                if (kq == 0) {
+                    p.sxg[sxg_index(row, c, p.tiles128)] = bits;
+                    // row blocks of the last 128-row tile that do not exist: finite scales (the forward multiplies
+                    // them by zero)
+                    if (row + 32 >= p.Mp)
+                        for (int rr = row + 32; (rr >> 7) == (row >> 7); rr += 32) p.sxg[sxg_index(rr, c, p.tiles128)] = 0u;
+                }
+            }
             if constexpr (BF16) {
                 // Magnitudes: |x|*inv + 2^23 has the code in its low bits and 0x4B in its top byte;
                 // eight of them are summed at their nibble positions with shift-adds (the top
@@ -218,7 +247,9 @@ __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         const float x = xc[ci].get(8 * h + e);
-                        const uint32_t mb = __float_as_uint(__fadd_rn(__fmul_rn(fabsf(x), inv4), 8388608.0f));
+                        float um = __fmul_rn(fabsf(x), inv4);
+                        if constexpr (GA) um = fminf(um, 7.0f);  // the stored scale may be smaller than amax / 7
+                        const uint32_t mb = __float_as_uint(__fadd_rn(um, 8388608.0f));
                         const int sh = e < 4 ? 8 * e : 8 * ((e - 5) & 3) + 4;
                         acc += mb << sh;
                         tb[e] = rne_bits(__fmul_rn(x, invb));
@@ -239,7 +270,9 @@ __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
                 for (int i = 0; i < 16; ++i) {
                     // main codes: magnitude from |x|, sign from x
                     const float x = xc[ci].get(i);
-                    const uint32_t m = __float_as_uint(__fadd_rn(__fmul_rn(fabsf(x), inv4), 8388608.0f)) & 7u;
+                    float um = __fmul_rn(fabsf(x), inv4);
+                    if constexpr (GA) um = fminf(um, 7.0f);
+                    const uint32_t m = __float_as_uint(__fadd_rn(um, 8388608.0f)) & 7u;
                     const uint32_t sgn = __float_as_uint(x) >> 31;
                     pk[i >> 3] |= nib_put(i & 7, sgn, m);
                     const uint32_t b = rne_bits(__fmul_rn(x, invb)) & 0xFFu;
@@ -310,23 +343,29 @@ __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
     }
 }
 
-template <bool BF16, int MAXC, int NJB, bool SM>
+template <bool BF16, int MAXC, int NJB, bool SM, bool GA>
 static hipError_t launch_one(const ActParams& p, int64_t Mp, hipStream_t s)
 {
-    hipLaunchKernelGGL((act_int_kernel<BF16, MAXC, NJB, SM>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((act_int_kernel<BF16, MAXC, NJB, SM, GA>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
     return hipGetLastError();
+}
+
+template <bool BF16, int MAXC, bool SM, bool GA>
+static hipError_t launch_rank2(const ActParams& p, int64_t Mp, hipStream_t s)
+{
+    switch (p.r) {
+        case 0: return launch_one<BF16, MAXC, 0, SM, GA>(p, Mp, s);
+        case 16: return launch_one<BF16, MAXC, 1, SM, GA>(p, Mp, s);
+        case 32: return launch_one<BF16, MAXC, 2, SM, GA>(p, Mp, s);
+        case 64: return launch_one<BF16, MAXC, 4, SM, GA>(p, Mp, s);
+        default: return launch_one<BF16, MAXC, 8, SM, GA>(p, Mp, s);
+    }
 }
 
 template <bool BF16, int MAXC, bool SM = false>
 static hipError_t launch_rank(const ActParams& p, int64_t Mp, hipStream_t s)
 {
-    switch (p.r) {
-        case 0: return launch_one<BF16, MAXC, 0, SM>(p, Mp, s);
-        case 16: return launch_one<BF16, MAXC, 1, SM>(p, Mp, s);
-        case 32: return launch_one<BF16, MAXC, 2, SM>(p, Mp, s);
-        case 64: return launch_one<BF16, MAXC, 4, SM>(p, Mp, s);
-        default: return launch_one<BF16, MAXC, 8, SM>(p, Mp, s);
-    }
+    return p.sxg ? launch_rank2<BF16, MAXC, SM, true>(p, Mp, s) : launch_rank2<BF16, MAXC, SM, false>(p, Mp, s);
 }
 
 hipError_t launch_quantize_act_int(const Dims& d, int x_dtype, const uint8_t* packed, const void* X,
@@ -348,6 +387,9 @@ hipError_t launch_quantize_act_int(const Dims& d, int x_dtype, const uint8_t* pa
     p.sr = (const float*)(packed + pl.off_sr);
     p.xq = act + al.off_xq;
     p.sx = (float*)(act + al.off_sx);
+    p.sxg = d.ga ? (uint32_t*)(act + al.off_sx) : nullptr;
+    p.tiles128 = (int)((al.Mp + 127) / 128);
+    p.Mp = (int)al.Mp;
     p.tq = (int8_t*)(act + al.off_tq);
     p.st = (float*)(act + al.off_st);
     p.dbg_xb = dbg ? dbg->xb : nullptr;

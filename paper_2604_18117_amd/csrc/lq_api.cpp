@@ -32,13 +32,15 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
     d->rp = (r + 31) / 32 * 32;
     d->C64 = (int)(cfg->K / 64);
     d->smooth = (cfg->flags & LQ_FLAG_SMOOTH) != 0;
-    d->mx = d->mxb = d->mxi = false;
+    d->mx = d->mxb = d->mxi = d->ga = false;
     d->bw_bits = d->mxb_elem = 0;
     if (cfg->main_w == LQ_INT4) {
         if (cfg->main_a != LQ_INT4) return LQ_ERR_UNSUPPORTED;
         if (cfg->main_w_group != 64 && cfg->main_w_group != 128) return LQ_ERR_SHAPE;
         if (cfg->K % cfg->main_w_group != 0) return LQ_ERR_SHAPE;
-        if (cfg->main_a_group != 0) return LQ_ERR_UNSUPPORTED;
+        if (cfg->main_a_group != 0 && cfg->main_a_group != 64) return LQ_ERR_UNSUPPORTED;
+        if (cfg->main_a_group == 64 && cfg->main_w_group != 64) return LQ_ERR_UNSUPPORTED;  // one block size for both operands
+        d->ga = cfg->main_a_group == 64;
         if (r == 96) return LQ_ERR_SHAPE;  // rank 96 (a 6-bit budget of 512 bits per channel, padded) only with block-scaled branches
         const int qw = int_qmax(cfg->br_w), qa = int_qmax(cfg->br_a);
         if (qw == 0 || qa == 0 || cfg->br_a == LQ_INT4) return LQ_ERR_UNSUPPORTED;
@@ -113,7 +115,9 @@ ActLayout act_layout(const Dims& d, int64_t M)
     al.off_xq = o;
     o = align256(o + (size_t)al.Mp * d.K / 2);
     al.off_sx = o;
-    o = align256(o + ((d.mx || d.mxi) ? (size_t)(al.Mp / 32) * ((d.C64 + 3) / 4) * 256 : (size_t)al.Mp * 4));
+    o = align256(o + ((d.mx || d.mxi) ? (size_t)(al.Mp / 32) * ((d.C64 + 3) / 4) * 256
+                      : d.ga          ? (size_t)d.G * ((al.Mp + 127) / 128) * 512
+                                      : (size_t)al.Mp * 4));
     al.off_tq = o;
     o = align256(o + (size_t)al.Mp * d.rp * (d.mxi ? 2 : 1));
     al.off_st = o;

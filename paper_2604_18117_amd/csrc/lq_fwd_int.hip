@@ -11,6 +11,14 @@
 // accumulator exactly and the per-group dequantisation is ONE fp32 FMA per output (no
 // int->float conversion); the factor 2^18 is folded into the stored weight scales.
 //
+// SINT4 blocks for both operands (template flag GA; App. A.3: one FP16 scale per 64 values): the dequantisation
+// factor of an output and a K block is sx[m,g] * sw[n,g].  The 32 x 32 tile of these products comes from the
+// matrix core as well: one v_mfma_f32_32x32x16_f16 whose A operand holds the token scales of the tile's four
+// row blocks at k = 0, 2, 4, 6 (a lane's 16-byte load as it stands) and whose B operand holds the channel
+// scale at the k of the wanted row block and zeros elsewhere; a product of two FP16 numbers is exact in fp32.
+// The per-group dequantisation therefore stays ONE FMA per output, t = fma(acc, P, t); the factor 2^18 of the
+// FP8-subnormal trick is applied once at the end (t * 2^18 is exact).
+//
 // Work decomposition: a workgroup of 4 wavefronts computes a 128 x 256 tile of Y (64 x 256 for
 // the half tiles at the tail of the grid); each wavefront owns 128 x 64 (4 x 2 MFMA tiles of
 // 32 x 32, 128 fp32 running sums per lane).  Activation codes go global -> registers -> (nibble
@@ -33,6 +41,8 @@ struct FwdParams {
     const float* st;
     const uint8_t* pq;
     const float* swT;
+    const uint32_t* sxg;  // SINT4 blocks: FP16 bits of the token block scales, [G][tiles128][32][4]
+    int tiles128;
     const int8_t* lq;
     const float* sl;
     uint16_t* Y;
@@ -74,9 +84,11 @@ constexpr int lds_bytes()
 // only 128 valid channels, where two of four side-by-side wavefronts would idle through the loop.
 // NRB = 4 (full tile) or
 // 2 (half tile, used for the tail of the grid).  NK = 32-deep chunks of the padded rank: 0|1|2|4.
-template <int GC, int NK, int NRB, bool DBG, bool SPLIT = false>
+template <int GC, int NK, int NRB, bool DBG, bool SPLIT = false, bool GA = false>
 __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const int rb0, const int tile_n)
 {
+    static_assert(!GA || GC == 1, "SINT4 blocks are 64 deep");
+    typedef _Float16 v8h __attribute__((ext_vector_type(8)));
     constexpr int SPW = 1;                      // row blocks staged per wavefront
     constexpr int STAGES = (GC == 1) ? 2 : 1;   // register sets of the global-load pipeline
     constexpr int NT = NRB * 2;                 // 32 x 32 MFMA tiles per wavefront and step
@@ -146,6 +158,22 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         }
     };
 
+    // SINT4 blocks: the token scales of step s are used straight from the register set they were loaded into
+    // (as the A operand of the scale-product MFMA); the set is refilled for step s + 2 at the end of step s.
+    struct SStage { v4i sx; };
+    const uint32_t* sxg_base = nullptr;
+    if constexpr (GA) sxg_base = p.sxg + ((size_t)(rbw >> 2) * 32 + l32) * 4;
+    auto load_s = [&](SStage& sc, int step) {
+        if constexpr (GA) {
+            const int st = step < G ? step : G - 1;
+            v4i v = *(const v4i*)(sxg_base + (size_t)st * p.tiles128 * 128);
+            if constexpr (NRB == 2) {  // half tiles own row blocks 0,1 or 2,3 of the 128-row tile: bring them to 0,1
+                if (rbw & 2) v = v4i{v[2], v[3], v[0], v[1]};
+            }
+            sc.sx = v;
+        }
+    };
+
     v16f t[NRB][2];
 #pragma unroll
     for (int a = 0; a < NRB; ++a)
@@ -156,6 +184,7 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
 
     v8i bu[GC][2];   // expanded weight operands of the current step
     float sw[2];     // their scales
+    const uint64_t half_mask = 0xFFFFFFFF00000000ull;
     auto expand_b = [&](const BStage& b) {
 #pragma unroll
         for (int cbi = 0; cbi < 2; ++cbi) {
@@ -163,7 +192,10 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
             for (int cc = 0; cc < GC; ++cc) bu[cc][cbi] = expand8(b.v[cc][cbi]);
             // a real move: keeps `sw` in a register of its own, so that the next load can land
             // in b.sw directly (a coalesced copy would force a wait on that fresh load)
-            asm volatile("v_mov_b32 %0, %1" : "=v"(sw[cbi]) : "v"(b.sw[cbi]));
+            if constexpr (GA)  // FP16 bits in the lanes of K half 0, zero in the others (they hold k = 8..15 of the scale MFMA)
+                asm volatile("v_cndmask_b32 %0, %1, 0, %2" : "=v"(sw[cbi]) : "v"(b.sw[cbi]), "s"(half_mask));
+            else
+                asm volatile("v_mov_b32 %0, %1" : "=v"(sw[cbi]) : "v"(b.sw[cbi]));
         }
     };
 
@@ -172,7 +204,7 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     // (loaded two steps ago).  During the step the data of step s+1 is expanded (activations
     // into the other LDS buffer, weights in registers) in the shadow of MFMAs already in
     // flight, and the loads for step s+3 are issued into `a`/`b`.
-    auto do_step = [&](int s, AStage& a, BStage& b) {
+    auto do_step = [&](int s, AStage& a, BStage& b, SStage& sc) {
         const int buf = s & 1;
         {
             auto lds_a = [&](int rbi, int cc) -> v8i {
@@ -199,6 +231,13 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
                 const int rbi = j >> 1, cbi = j & 1;
+                v16f P;
+                if constexpr (GA) {  // scale products of this tile; issued ahead of the next main MFMA
+                    v4i bsel = {0, 0, 0, 0};
+                    bsel[rbi] = __float_as_int(swc[cbi]);
+                    P = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, sc.sx), __builtin_bit_cast(v8h, bsel),
+                                                               v16f{0}, 0, 0, 0);
+                }
                 if (j + 1 < NT) {
                     const int nrbi = (j + 1) >> 1, ncbi = (j + 1) & 1;
                     dd[(j + 1) & 1] = tile_mfma(af[nrbi & 1], ncbi);
@@ -214,10 +253,12 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
                 if (j == NT - 1) {  // the last MFMA of the step is in flight: bu is free
                     expand_b(b);
                     load_b(b, s + 1 + STAGES);
+                    load_s(sc, s + 2);  // ... and so is this step's scale set
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) t[rbi][cbi][i] = __builtin_fmaf(dd[j & 1][i], swc[cbi], t[rbi][cbi][i]);
+                for (int i = 0; i < 16; ++i)
+                    t[rbi][cbi][i] = __builtin_fmaf(dd[j & 1][i], GA ? P[i] : swc[cbi], t[rbi][cbi][i]);
                 if (DBG) {
                     if (p.dbg_acc && active) {
 #pragma unroll
@@ -239,6 +280,9 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     if constexpr (STAGES == 2) {
         AStage a0, a1;
         BStage b0, b1;
+        SStage s0, s1;
+        load_s(s0, 0);
+        load_s(s1, 1);
         load_a(a0, 0);
         load_b(b0, 0);
         store_a(a0, 0);
@@ -258,13 +302,14 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         // last column or row block of a partial tile) works on clamped operands, stores nothing.
         int s = 0;
         for (; s + 1 < G; s += 2) {
-            do_step(s, a0, b0);
-            do_step(s + 1, a1, b1);
+            do_step(s, a0, b0, s0);
+            do_step(s + 1, a1, b1, s1);
         }
-        if (s < G) do_step(s, a0, b0);
+        if (s < G) do_step(s, a0, b0, s0);
     } else {
         AStage a0;
         BStage b0;
+        SStage s0;  // (unused: 128-deep groups have no block-scaled variant)
         load_a(a0, 0);
         load_b(b0, 0);
         store_a(a0, 0);
@@ -275,7 +320,7 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         load_b(b0, 1);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        for (int s = 0; s < G; ++s) do_step(s, a0, b0);
+        for (int s = 0; s < G; ++s) do_step(s, a0, b0, s0);
     }
 
     // ---- epilogue: rank-r expansion, scales, sum, bf16 -------------------------------------
@@ -316,7 +361,7 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         rb = rb < p.nrb ? rb : p.nrb - 1;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            sxv[q] = *(const v4f*)(p.sx + rb * 32 + 8 * q + 4 * half);
+            if constexpr (!GA) sxv[q] = *(const v4f*)(p.sx + rb * 32 + 8 * q + 4 * half);
             stv[q] = *(const v4f*)(p.st + rb * 32 + 8 * q + 4 * half);
         }
     };
@@ -345,7 +390,9 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const float ybr = __fmul_rn(__fmul_rn((float)a2[cbi][i], stv[i >> 2][i & 3]), slv[cbi]);
-                y[cbi][i] = __builtin_fmaf(sxv[i >> 2][i & 3], t[rbi][cbi][i], ybr);
+                // SINT4 blocks: t carries the factor 2^-18 of the subnormal codes; scaling it back is exact
+                y[cbi][i] = GA ? __builtin_fmaf(t[rbi][cbi][i], 262144.0f, ybr)
+                               : __builtin_fmaf(sxv[i >> 2][i & 3], t[rbi][cbi][i], ybr);
             }
         if (rbi + 1 < NRB) load_scales(rbi + 1);
 #pragma unroll
@@ -393,7 +440,7 @@ __device__ __forceinline__ int xcd_order(int b, int n)
     return xcd * per + (xcd < rem ? xcd : rem) + loc;
 }
 
-template <int GC, int NK, bool DBG>
+template <int GC, int NK, bool DBG, bool GA = false>
 __global__ __launch_bounds__(NW * 64, 2) void fwd_int_kernel(FwdParams p)
 {
     __shared__ __attribute__((aligned(16))) uint8_t lds[lds_bytes<GC>()];
@@ -402,16 +449,16 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_int_kernel(FwdParams p)
         const int tile = xcd_order(b, p.n_full);
         const int tile_m = tile / p.tilesN, tile_n = tile - tile_m * p.tilesN;
         if (p.split_last && tile_n == p.tilesN - 1)
-            fwd_tile<GC, NK, 2, DBG, true>(p, lds, tile_m * 4, tile_n);
+            fwd_tile<GC, NK, 2, DBG, true, GA>(p, lds, tile_m * 4, tile_n);
         else
-            fwd_tile<GC, NK, 4, DBG>(p, lds, tile_m * 4, tile_n);
+            fwd_tile<GC, NK, 4, DBG, false, GA>(p, lds, tile_m * 4, tile_n);
     } else {
         const int hh = xcd_order(b - p.n_full, 2 * (p.tilesM * p.tilesN - p.n_full));
         const int tile = p.n_full + (hh >> 1);
         const int tile_m = tile / p.tilesN, tile_n = tile - tile_m * p.tilesN;
         const int rb0 = tile_m * 4 + (hh & 1) * 2;
         if (rb0 >= p.nrb) return;  // lower half of a partial last row tile: nothing to do
-        fwd_tile<GC, NK, 2, DBG>(p, lds, rb0, tile_n);
+        fwd_tile<GC, NK, 2, DBG, false, GA>(p, lds, rb0, tile_n);
     }
 }
 
@@ -429,7 +476,7 @@ static int workgroup_slots()
     return cached[dev];
 }
 
-template <int GC, int NK, bool DBG>
+template <int GC, int NK, bool DBG, bool GA = false>
 static hipError_t launch_cfg(const FwdParams& p0, hipStream_t s)
 {
     FwdParams p = p0;
@@ -446,18 +493,18 @@ static hipError_t launch_cfg(const FwdParams& p0, hipStream_t s)
     p.n_full = n_full;
     p.split_last = (p.N & 255) == 128;
     dim3 grid((unsigned)(n_full + 2 * (tiles - n_full))), block(NW * 64);
-    hipLaunchKernelGGL((fwd_int_kernel<GC, NK, DBG>), grid, block, 0, s, p);
+    hipLaunchKernelGGL((fwd_int_kernel<GC, NK, DBG, GA>), grid, block, 0, s, p);
     return hipGetLastError();
 }
 
-template <int GC, bool DBG>
+template <int GC, bool DBG, bool GA = false>
 static hipError_t launch_rank(int nk, const FwdParams& p, hipStream_t s)
 {
     switch (nk) {
-        case 0: return launch_cfg<GC, 0, DBG>(p, s);
-        case 1: return launch_cfg<GC, 1, DBG>(p, s);
-        case 2: return launch_cfg<GC, 2, DBG>(p, s);
-        default: return launch_cfg<GC, 4, DBG>(p, s);
+        case 0: return launch_cfg<GC, 0, DBG, GA>(p, s);
+        case 1: return launch_cfg<GC, 1, DBG, GA>(p, s);
+        case 2: return launch_cfg<GC, 2, DBG, GA>(p, s);
+        default: return launch_cfg<GC, 4, DBG, GA>(p, s);
     }
 }
 
@@ -473,6 +520,8 @@ hipError_t launch_fwd_int(const Dims& d, const uint8_t* packed, const uint8_t* a
     p.st = (const float*)(act + al.off_st);
     p.pq = packed + pl.off_pq;
     p.swT = (const float*)(packed + pl.off_sw);
+    p.sxg = (const uint32_t*)(act + al.off_sx);
+    p.tiles128 = (int)((al.Mp + 127) / 128);
     p.lq = (const int8_t*)(packed + pl.off_lq);
     p.sl = (const float*)(packed + pl.off_sl);
     p.Y = Y;
@@ -489,6 +538,7 @@ hipError_t launch_fwd_int(const Dims& d, const uint8_t* packed, const uint8_t* a
     p.dbg_y32 = dbg ? dbg->y32 : nullptr;
     const bool want_dbg = dbg && (dbg->acc || dbg->acc2 || dbg->y32);
     const int nk = d.rp >> 5;  // 0 | 1 | 2 | 4 (the rank is one of 0, 16, 32, 64, 128)
+    if (d.ga) return want_dbg ? launch_rank<1, true, true>(nk, p, s) : launch_rank<1, false, true>(nk, p, s);
     if (d.g == 64) {
         return want_dbg ? launch_rank<1, true>(nk, p, s) : launch_rank<1, false>(nk, p, s);
     } else {

@@ -63,6 +63,7 @@ struct Dims {
     int mxb_elem; // block-scaled FP branch: 8 = E4M3 (MXFP8e4), 6 = E2M3 (MXFP6e2); 0 otherwise
     bool mxi;     // MXI family: MXINT4 main product, MXINT8 / MXINT4 branch (then mx is false)
     int bw_bits;  // MXI: width of the branch weight format (8 | 4)
+    bool ga;      // INT family with SINT4 blocks for both main operands (main_a_group = 64): FP16 scales per 64 values
     bool smooth;  // LQ_FLAG_SMOOTH: the activation kernel multiplies X by the stored reciprocals of gamma
     int qmax_bw;  // INT branch weight qmax
     int qmax_ba;  // INT branch activation qmax
@@ -70,7 +71,7 @@ struct Dims {
 
 struct PackedLayout {
     size_t off_pq;   // main codes, fragment order, N*K/2 bytes
-    size_t off_sw;   // INT: [G][N] fp32, pre-multiplied by 2^18;  MX: E8M0 bytes
+    size_t off_sw;   // INT: [G][N] fp32, pre-multiplied by 2^18 (SINT4 blocks: FP16 bits in a dword);  MX: E8M0 bytes
     size_t off_lq;   // [N][rp] int8 (zero padded) / E4M3 bytes
     size_t off_sl;   // [N] fp32
     size_t off_rq;   // branch R codes in the activation kernel's operand order, r*K bytes
@@ -82,7 +83,7 @@ struct PackedLayout {
 struct ActLayout {
     int64_t Mp;      // M rounded up to 32
     size_t off_xq;   // main codes, fragment order, Mp*K/2 bytes
-    size_t off_sx;   // INT: [Mp] fp32;  MX: E8M0 bytes
+    size_t off_sx;   // INT: [Mp] fp32 (SINT4 blocks: [G][Mp/128 rounded up][32][4] dwords of FP16 bits, sxg_index);  MX: E8M0 bytes
     size_t off_tq;   // [Mp][rp] int8 / E4M3
     size_t off_st;   // [Mp] fp32
     size_t total;
@@ -189,6 +190,33 @@ __device__ __forceinline__ float e2m3_value(uint32_t c)  // 1 sign, 2 exponent (
     const int e = (int)(c >> 3) & 3, m = (int)c & 7;
     const float mag = e ? ldexpf(1.0f + 0.125f * (float)m, e - 1) : 0.125f * (float)m;
     return (c & 32u) ? -mag : mag;
+}
+
+// SINT4 block scale (App. A.3): the FP16 number nearest to amax / 7, kept inside [2^-24, 65504]; 1 for an
+// all-zero block.  *inv is the correctly rounded fp32 reciprocal of the stored scale.
+__device__ __forceinline__ uint32_t sint4_scale(float amax, float* inv)
+{
+    if (amax == 0.0f) {
+        *inv = 1.0f;
+        return 0x3C00u;
+    }
+    const _Float16 h = (_Float16)fminf(__fdiv_rn(amax, 7.0f), 65504.0f);  // round to nearest even
+    uint32_t bits = (uint32_t)__builtin_bit_cast(uint16_t, h);
+    float f = (float)h;
+    if (f < 5.9604644775390625e-08f) {
+        f = 5.9604644775390625e-08f;
+        bits = 1u;
+    }
+    *inv = __fdiv_rn(1.0f, f);
+    return bits;
+}
+__device__ __forceinline__ float f16_bits_value(uint32_t bits) { return (float)__builtin_bit_cast(_Float16, (uint16_t)bits); }
+
+// dword index of the block scale of token `row`, K block g: the forward reads the scales of the four 32-row
+// blocks of a 128-row tile as one 16-byte operand per lane
+__device__ __forceinline__ size_t sxg_index(int row, int g, int tiles128)
+{
+    return ((size_t)((size_t)g * tiles128 + (row >> 7)) * 32 + (row & 31)) * 4 + ((row >> 5) & 3);
 }
 
 // fp32 -> bf16 bits, round to nearest even (finite inputs)

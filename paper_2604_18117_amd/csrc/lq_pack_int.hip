@@ -1,7 +1,8 @@
 // Offline packing for the INT family (paper Fig. 1 caption and Eq. 5):
 //   Q2(R), Q2(L) with one scale per row; P = W - deq(Q2 L) deq(Q2 R) accumulated in fp64 and
 //   rounded once to fp32; Q1(P) = INT4 with one fp32 scale per group of g values along K
-//   (SINT4-style blocks, App. A.3).  Also the inverse views used by tests.
+//   (SINT4-style blocks, App. A.3), or the literal SINT4 blocks: 64 values, FP16 scale.  Also the inverse
+//   views used by tests.
 // Quantiser: s = amax / qmax, code = rne(v * (qmax / amax)), symmetric range, all-zero -> s = 1.
 #include "lq_internal.h"
 
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(256) void pack_p_kernel(const float* W, const float
                                                      int N, int K, int r, int rp, int from_q,
                                                      const int8_t* lq, const float* sl,
                                                      const int8_t* rq, const float* sr,
-                                                     uint8_t* pq, float* swT)
+                                                     uint8_t* pq, float* swT, int ga)
 {
     const int lane = threadIdx.x & 63;
     const int G = K / (64 * GC), C64 = K >> 6;
@@ -116,8 +117,13 @@ __global__ __launch_bounds__(256) void pack_p_kernel(const float* W, const float
     }
     a = wave_max(a);
     float s, inv;
-    scale_pair(a, 7.0f, &s, &inv);
-    if (lane == 0) swT[(size_t)gi * N + n] = ldexpf(s, 18);
+    if (ga) {  // FP16 scale, stored as its bits; codes against the stored scale
+        const uint32_t bits = sint4_scale(a, &inv);
+        if (lane == 0) ((uint32_t*)swT)[(size_t)gi * N + n] = bits;
+    } else {
+        scale_pair(a, 7.0f, &s, &inv);
+        if (lane == 0) swT[(size_t)gi * N + n] = ldexpf(s, 18);
+    }
 #pragma unroll
     for (int cc = 0; cc < GC; ++cc) {
         const int k = (gi * GC + cc) * 64 + lane;
@@ -170,16 +176,16 @@ hipError_t launch_pack_int(const Dims& d, int from_q, const float* W, const floa
     const unsigned blocks = (unsigned)((waves + 3) / 4);
     if (d.g == 64)
         hipLaunchKernelGGL(pack_p_kernel<1>, dim3(blocks), dim3(256), 0, s, W, L, R, N, K, d.r, d.rp, from_q, lq,
-                           sl, rq, sr, pq, swT);
+                           sl, rq, sr, pq, swT, d.ga ? 1 : 0);
     else
         hipLaunchKernelGGL(pack_p_kernel<2>, dim3(blocks), dim3(256), 0, s, W, L, R, N, K, d.r, d.rp, from_q, lq,
-                           sl, rq, sr, pq, swT);
+                           sl, rq, sr, pq, swT, 0);
     return hipGetLastError();
 }
 
 // ---- plain views ----------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void unpack_w_kernel(const uint8_t* packed, PackedLayout pl, int N, int K,
-                                                       int r, int rp, int g, lq_weights_view out)
+                                                       int r, int rp, int g, int ga, lq_weights_view out)
 {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     const int C64 = K >> 6, G = K / g;
@@ -192,7 +198,8 @@ __global__ __launch_bounds__(256) void unpack_w_kernel(const uint8_t* packed, Pa
     }
     if (idx < (size_t)N * G && out.sw) {
         const int n = (int)(idx / G), gi = (int)(idx % G);
-        out.sw[idx] = ldexpf(((const float*)(packed + pl.off_sw))[(size_t)gi * N + n], -18);
+        out.sw[idx] = ga ? f16_bits_value(((const uint32_t*)(packed + pl.off_sw))[(size_t)gi * N + n])
+                         : ldexpf(((const float*)(packed + pl.off_sw))[(size_t)gi * N + n], -18);
     }
     if (idx < (size_t)N * r && out.lq) {
         const int n = (int)(idx / r), j = (int)(idx % r);
@@ -212,12 +219,12 @@ hipError_t launch_unpack_weights_int(const Dims& d, const uint8_t* packed, const
     const PackedLayout pl = packed_layout(d);
     const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * d.K;
     hipLaunchKernelGGL(unpack_w_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, packed, pl, (int)d.N,
-                       (int)d.K, d.r, d.rp, d.g, *out);
+                       (int)d.K, d.r, d.rp, d.g, d.ga ? 1 : 0, *out);
     return hipGetLastError();
 }
 
 __global__ __launch_bounds__(256) void unpack_a_kernel(const uint8_t* act, ActLayout al, int M, int K, int r,
-                                                       int rp, lq_act_view out)
+                                                       int rp, int ga, lq_act_view out)
 {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     const int C64 = K >> 6;
@@ -226,7 +233,14 @@ __global__ __launch_bounds__(256) void unpack_a_kernel(const uint8_t* act, ActLa
         const uint32_t w = *(const uint32_t*)(act + al.off_xq + frag_offset(m, k, C64));
         out.xq[idx] = (int8_t)nib_get(w, k & 7);
     }
-    if (idx < (size_t)M && out.sx) out.sx[idx] = ((const float*)(act + al.off_sx))[idx];
+    if (ga) {
+        if (idx < (size_t)M * C64 && out.sx) {
+            const int m = (int)(idx / C64), gi = (int)(idx % C64);
+            out.sx[idx] = f16_bits_value(((const uint32_t*)(act + al.off_sx))[sxg_index(m, gi, (int)((al.Mp + 127) / 128))]);
+        }
+    } else if (idx < (size_t)M && out.sx) {
+        out.sx[idx] = ((const float*)(act + al.off_sx))[idx];
+    }
     if (idx < (size_t)M && out.st) out.st[idx] = ((const float*)(act + al.off_st))[idx];
     if (idx < (size_t)M * r && out.tq) {
         const int m = (int)(idx / r), j = (int)(idx % r);
@@ -240,7 +254,7 @@ hipError_t launch_unpack_act_int(const Dims& d, const uint8_t* act, int64_t M, c
     const ActLayout al = act_layout(d, M);
     const size_t n = (size_t)M * (d.K > d.r ? d.K : d.r);
     hipLaunchKernelGGL(unpack_a_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, act, al, (int)M,
-                       (int)d.K, d.r, d.rp, *out);
+                       (int)d.K, d.r, d.rp, d.ga ? 1 : 0, *out);
     return hipGetLastError();
 }
 

@@ -38,6 +38,7 @@ class Layer:
     w_std: float = 0.02
     lr_std: float = 1e-3
     seed: int = 0
+    a_group: int = 0       # INT family: 0 = one main activation scale per token; 64 = SINT4 blocks for both main operands
 
 
 def _n_out(K: int) -> int:
@@ -85,8 +86,13 @@ CFG5B6 = [replace(l, name="c5b6" + l.name[2:], family="mxb", r=64, br_w_bits=6, 
 CFG5I = [replace(l, name="c5i" + l.name[2:], family="mxi", r=64) for l in CFG5]
 CFG5I4 = [replace(l, name="c5i4" + l.name[2:], family="mxi", r=128, br_w_bits=4) for l in CFG5]
 
+# Configuration 2 and the 2240-wide QKV layer with the literal SINT4 blocks (FP16 scale per 64 values along K) for the
+# activations as well as the weights.
+CFG2S = [replace(CFG2[0], name="c2s_qkv", a_group=64)]
+CFG4S = [replace(CFG4[0], name="c4s_qkv", a_group=64)]
+
 CONFIGS: Dict[str, List[Layer]] = {"c1": CFG1, "c2": CFG2, "c3": CFG3, "c4": CFG4, "c5": CFG5, "c5b": CFG5B, "c5b6": CFG5B6,
-                                   "c5i": CFG5I, "c5i4": CFG5I4}
+                                   "c5i": CFG5I, "c5i4": CFG5I4, "c2s": CFG2S, "c4s": CFG4S}
 LAYERS: Dict[str, Layer] = {l.name: l for ls in CONFIGS.values() for l in ls}
 
 

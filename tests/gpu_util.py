@@ -55,7 +55,8 @@ def run_gpu(layer, X, W, L, R, debug=True, debug_acc=True):
 
 
 def run_oracle_int(oracle, layer, X, W, L, R, want_acc=True):
-    pk = oracle.pack_int(W, L if layer.r else None, R if layer.r else None, layer.g, layer.br_w_bits)
+    pk = oracle.pack_int(W, L if layer.r else None, R if layer.r else None, layer.g, layer.br_w_bits,
+                         sint4_blocks=layer.a_group == 64)
     act = oracle.quantize_act_int(X, pk, layer.br_a_bits)
     out = oracle.fwd_int(pk, act, want_acc=want_acc)
     return pk, act, out

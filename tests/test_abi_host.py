@@ -73,8 +73,26 @@ def test_unsupported_combinations(lq):
     cfg.flags = 2                   # unknown flag bits are rejected
     assert lq.raw().lq_packed_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
     cfg = _cfg(lq)
-    cfg.main_a_group = 64           # per-token-group activations are reserved
+    cfg.main_a_group = 32           # INT activations: one scale per token, or SINT4 blocks of 64
     assert lq.raw().lq_packed_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+
+
+def test_sint4_block_contract(lq):
+    raw = lq.raw()
+    n0, n1 = C.c_size_t(0), C.c_size_t(0)
+    cfg = _cfg(lq)
+    cfg.main_a_group = 64           # SINT4 blocks for both main operands: one block size for both
+    assert raw.lq_packed_sizes(C.byref(cfg), C.byref(n1)) == lq.LQ_OK
+    assert raw.lq_packed_sizes(C.byref(_cfg(lq)), C.byref(n0)) == lq.LQ_OK
+    assert n0.value == n1.value     # a weight block scale takes a dword either way
+    cfg.main_w_group = 128
+    assert raw.lq_packed_sizes(C.byref(cfg), C.byref(n1)) == lq.LQ_ERR_UNSUPPORTED
+    # activation blob: K/64 scales per token (in whole 128-token tiles) instead of one
+    cfg = _cfg(lq, K=256)
+    cfg.main_a_group = 64
+    assert raw.lq_act_sizes(C.byref(cfg), 100, C.byref(n1)) == lq.LQ_OK
+    assert raw.lq_act_sizes(C.byref(_cfg(lq, K=256)), 100, C.byref(n0)) == lq.LQ_OK
+    assert n1.value - n0.value == 4 * 128 * 4 - 128 * 4
 
 
 def test_mx_family_contract(lq):

@@ -131,6 +131,10 @@ def test_strided_x_and_determinism(oracle):
 
 @pytest.mark.parametrize("name", ["c2_qkv", "c3_fc1", "c3_fc2", "c4_qkv", "c4_expand"])
 def test_full_size_sampled_rows(oracle, name):
+    _full_size_sampled(oracle, name)
+
+
+def _full_size_sampled(oracle, name):
     """Full-size layer in the launch configuration the bench times; the oracle recomputes a
     sample of token rows (rows are independent through the whole path)."""
     layer = wl.LAYERS[name]
@@ -191,3 +195,53 @@ def test_fused_smoothing(oracle, M, K, N, r, xd):
     assert np.array_equal(n(fdbg.y32), out.y32)
     assert np.array_equal(bf16_to_bits(Y), out.Y)
     assert not np.array_equal(act.xq, act0.xq)                   # the smoothing did change the codes
+
+
+# ---- SINT4 blocks for both operands of the main product (App. A.3: 64 values, one FP16 scale) ------------------------
+
+SINT4_SMALL = [
+    # M (ragged), K, N, r, bw, ba, x_dtype
+    (300, 256, 320, 16, 8, 8, "bf16"),
+    (77, 192, 64, 32, 8, 8, "f32"),
+    (513, 384, 576, 64, 6, 6, "bf16"),
+    (97, 1152, 128, 128, 4, 8, "bf16"),      # 97 tokens: a last 128-row tile with one real row block
+    (64, 128, 64, 0, 8, 8, "bf16"),
+    (1, 64, 64, 16, 8, 8, "f32"),
+]
+
+
+@pytest.mark.parametrize("M,K,N,r,bw,ba,xd", SINT4_SMALL)
+def test_sint4_blocks_small_shapes_bit_exact(oracle, M, K, N, r, bw, ba, xd):
+    layer = wl.Layer("t", M, K, N, r, "int", 64, bw, ba, xd, outlier_scale=15.0, n_outliers=max(1, K // 100), seed=M + K,
+                     a_group=64)
+    X, W, L, R = wl.make_inputs(layer)
+    g = _compare_all(oracle, layer, X, W, L, R)
+    assert g.av.sx.shape == (M, K // 64)
+
+
+@pytest.mark.parametrize("M,N", [(2000, 2304), (2100, 2176)])
+def test_sint4_blocks_full_tiles_bit_exact(oracle, M, N):
+    """Full 128 x 256 tiles, a ragged last row tile, and (second case) a last tile column of 128 channels."""
+    layer = wl.Layer("t", M, 256, N, 32, "int", 64, 8, 8, "bf16", outlier_scale=15.0, n_outliers=2, seed=M, a_group=64)
+    X, W, L, R = wl.make_inputs(layer)
+    _compare_all(oracle, layer, X, W, L, R)
+
+
+def test_sint4_blocks_degenerate_and_extreme_scales(oracle):
+    layer = wl.Layer("t", 70, 256, 64, 16, "int", 64, 8, 8, "f32", seed=4, a_group=64)
+    X, W, L, R = wl.make_inputs(layer)
+    X[3] = 0.0                    # an all-zero token: every block scale is 1
+    X[5, :] = 0.0
+    X[5, 70] = -2.0               # a one-hot token: three all-zero blocks
+    X[7, :64] *= 1e-9             # block scale below the FP16 range: clamped to 2^-24, codes flush or clamp
+    X[8, 64:128] *= 3e5           # block scale above the FP16 range: clamped to 65504, codes saturate
+    X[9, 128:192] = 2.0 ** -26    # amax / 7 rounds to zero in FP16
+    W[2] = 0.0
+    W[6, :64] *= 1e-7
+    _compare_all(oracle, layer, X, W, L, R)
+    _compare_all(oracle, layer, np.zeros_like(X), W, L, R)
+
+
+@pytest.mark.parametrize("name", ["c2s_qkv", "c4s_qkv"])
+def test_sint4_blocks_full_size_sampled_rows(oracle, name):
+    _full_size_sampled(oracle, name)
