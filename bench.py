@@ -148,7 +148,9 @@ def main():
     if mx:
         scale_bytes = (layer.M + layer.N) * (layer.K // 32) + (0 if mxi else rp // 32 if mxb else 4) * (layer.M + layer.N)
     else:
-        scale_bytes = 4 * layer.N * (layer.K // layer.g) + 4 * (2 * layer.M + layer.N)
+        # (SINT4 blocks: an FP16 scale per 64 values of either operand, counted at the 4 bytes the layouts store)
+        scale_bytes = 4 * layer.N * (layer.K // layer.g) + 4 * (2 * layer.M + layer.N) + \
+            (4 * layer.M * (layer.K // 64) if layer.a_group == 64 else 0)
     fwd_bytes = (layer.M + layer.N) * layer.K / 2 + scale_bytes + (layer.M + layer.N) * rp + 2.0 * layer.M * layer.N
     t_mfma = fwd_ops / (peak * 1e12)
     t_hbm = fwd_bytes / 8.0e12
@@ -161,7 +163,8 @@ def main():
         "dtype": "mxint4" if mxi else "mxfp4" if mx else "int4",
         "data": "synthetic",
         "config": {"workload": layer.name, "M": layer.M, "K": layer.K, "N": layer.N, "rank": layer.r,
-                   "main": "W4A4 MXINT4 block 32" if mxi else "W4A4 MXFP4 block 32" if mx else f"W4A4 INT4 g{layer.g}",
+                   "main": "W4A4 MXINT4 block 32" if mxi else "W4A4 MXFP4 block 32" if mx else
+                           "W4A4 SINT4 blocks of 64, FP16 scales" if layer.a_group == 64 else f"W4A4 INT4 g{layer.g}",
                    "branch": f"W{layer.br_w_bits}A8 MXINT block 32" if mxi else ("W6A6 MXFP6e2 block 32" if layer.br_w_bits == 6 else "W8A8 MXFP8e4 block 32") if mxb else "W8A8 FP8 E4M3" if mx else f"W{layer.br_w_bits}A{layer.br_a_bits}",
                    "x_dtype": layer.x_dtype, "buffer_sets": nsets,
                    "arithmetic": ("int4 codes as FP8 subnormals with E8M0 block scales on the scaled FP8 MFMA, "
@@ -197,7 +200,7 @@ def main():
             pk = lq_ref.pack_mx(W, L, R)
             run_rows = lambda n_rows: lq_ref.fwd_mx(pk, lq_ref.quantize_act_mx(X[:n_rows], pk))
         else:
-            pk = lq_ref.pack_int(W, L, R, layer.g, layer.br_w_bits)
+            pk = lq_ref.pack_int(W, L, R, layer.g, layer.br_w_bits, sint4_blocks=layer.a_group == 64)
             run_rows = lambda n_rows: lq_ref.fwd_int(pk, lq_ref.quantize_act_int(X[:n_rows], pk, layer.br_a_bits))
         probe = 16
         t = time.perf_counter()

@@ -115,6 +115,7 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     // Every wavefront stages one row block; with a half tile the upper two stage (clamped)
     // blocks that are not read.
     const uint32_t lane16 = (uint32_t)lane * 16u;
+    const uint32_t l32x4 = (uint32_t)l32 * 4u, l32x16 = (uint32_t)l32 * 16u;
     const uint8_t* xq_base[SPW];
 #pragma unroll
     for (int i = 0; i < SPW; ++i) {
@@ -128,13 +129,20 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
 
     struct AStage { v4i v[SPW][GC]; };
     struct BStage { v4i v[GC][2]; float sw[2]; };
+    // SINT4-block variant: registers are scarce, so a stream's address is kept as a wave-uniform base in
+    // scalar registers plus the one 32-bit lane offset all streams share (the opaque asm stops the compiler
+    // from folding the lane offset into a 64-bit vector base per stream).
+    auto uni = [](const uint8_t* q) -> const uint8_t* {
+        if constexpr (GA) asm volatile("" : "+s"(q));
+        return q;
+    };
     auto load_a = [&](AStage& a, int step) {
         const int st = step < G ? step : G - 1;
 #pragma unroll
         for (int i = 0; i < SPW; ++i)
 #pragma unroll
             for (int cc = 0; cc < GC; ++cc)
-                a.v[i][cc] = *(const v4i*)(xq_base[i] + (size_t)(st * GC + cc) * 1024 + lane16);
+                a.v[i][cc] = *(const v4i*)(uni(xq_base[i] + (size_t)(st * GC + cc) * 1024) + lane16);
     };
     auto store_a = [&](const AStage& a, int buf) {
 #pragma unroll
@@ -153,8 +161,11 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         for (int cbi = 0; cbi < 2; ++cbi) {
 #pragma unroll
             for (int cc = 0; cc < GC; ++cc)
-                b.v[cc][cbi] = *(const v4i*)(pq_base[cbi] + (size_t)(st * GC + cc) * 1024 + lane16);
-            b.sw[cbi] = sw_base[(size_t)st * p.N + cbi * 32 + l32];
+                b.v[cc][cbi] = *(const v4i*)(uni(pq_base[cbi] + (size_t)(st * GC + cc) * 1024) + lane16);
+            if constexpr (GA)
+                b.sw[cbi] = *(const float*)(uni((const uint8_t*)(sw_base + (size_t)st * p.N + cbi * 32)) + l32x4);
+            else
+                b.sw[cbi] = sw_base[(size_t)st * p.N + cbi * 32 + l32];
         }
     };
 
@@ -162,11 +173,11 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     // (as the A operand of the scale-product MFMA); the set is refilled for step s + 2 at the end of step s.
     struct SStage { v4i sx; };
     const uint32_t* sxg_base = nullptr;
-    if constexpr (GA) sxg_base = p.sxg + ((size_t)(rbw >> 2) * 32 + l32) * 4;
+    if constexpr (GA) sxg_base = p.sxg + (size_t)(rbw >> 2) * 128;
     auto load_s = [&](SStage& sc, int step) {
         if constexpr (GA) {
             const int st = step < G ? step : G - 1;
-            v4i v = *(const v4i*)(sxg_base + (size_t)st * p.tiles128 * 128);
+            v4i v = *(const v4i*)(uni((const uint8_t*)(sxg_base + (size_t)st * p.tiles128 * 128)) + l32x16);
             if constexpr (NRB == 2) {  // half tiles own row blocks 0,1 or 2,3 of the 128-row tile: bring them to 0,1
                 if (rbw & 2) v = v4i{v[2], v[3], v[0], v[1]};
             }
@@ -220,7 +231,10 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
                     d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(af[cc], bu[cc][cbi], d, 0, 0, 0, 0, 0, 0);
                 return d;
             };
-            v8i af[2][GC];
+            // operand of the current row block; double-buffered unless registers are scarce (the next block's
+            // read is issued after the last MFMA that uses the current one, so one buffer is enough)
+            constexpr int AFB = GA ? 1 : 2;
+            v8i af[AFB][GC];
             v16f dd[2];
             const float swc[2] = {sw[0], sw[1]};
 #pragma unroll
@@ -240,11 +254,11 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
                 }
                 if (j + 1 < NT) {
                     const int nrbi = (j + 1) >> 1, ncbi = (j + 1) & 1;
-                    dd[(j + 1) & 1] = tile_mfma(af[nrbi & 1], ncbi);
+                    dd[(j + 1) & 1] = tile_mfma(af[nrbi % AFB], ncbi);
                 }
                 if (cbi == 0 && rbi + 1 < NRB) {  // operand of the next row block, one tile ahead
 #pragma unroll
-                    for (int cc = 0; cc < GC; ++cc) af[(rbi + 1) & 1][cc] = lds_a(rbi + 1, cc);
+                    for (int cc = 0; cc < GC; ++cc) af[(rbi + 1) % AFB][cc] = lds_a(rbi + 1, cc);
                 }
                 if (j == 0) {  // fills the pipeline start-up bubble
                     store_a(a, buf ^ 1);
