@@ -71,6 +71,7 @@ constexpr int NW = WN;
 constexpr int RBT = 4;                         // 32-row blocks staged per workgroup (LDS slots)
 constexpr int EPI_ROW = 144;                   // bytes per staged output row (128 + pad: no bank conflicts)
 constexpr int EPI_WAVE = 32 * EPI_ROW;         // one 32 x 64 bf16 block per wavefront
+constexpr int GA_MAXG = 72;                    // SINT4-block variant: K <= 4608 (the tile's token scales sit in LDS)
 template <int GC>
 constexpr int lds_bytes()
 {
@@ -129,20 +130,30 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
 
     struct AStage { v4i v[SPW][GC]; };
     struct BStage { v4i v[GC][2]; float sw[2]; };
-    // SINT4-block variant: registers are scarce, so a stream's address is kept as a wave-uniform base in
-    // scalar registers plus the one 32-bit lane offset all streams share (the opaque asm stops the compiler
-    // from folding the lane offset into a 64-bit vector base per stream).
-    auto uni = [](const uint8_t* q) -> const uint8_t* {
-        if constexpr (GA) asm volatile("" : "+s"(q));
-        return q;
-    };
+    // SINT4-block variant: registers are scarce, so its streams are read with buffer loads: a wave-uniform
+    // descriptor and step offset in scalar registers plus the one 32-bit lane offset all streams share,
+    // instead of a 64-bit vector address per stream.  Each descriptor spans exactly the bytes its stream
+    // may touch (a read past it would return zeros).
+    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    constexpr int RSRC_FLAGS = 0x00020000;
+    __amdgpu_buffer_rsrc_t rs_xq, rs_pq[2], rs_sw;
+    if constexpr (GA) {
+        static_assert(SPW == 1, "one staged row block per wavefront");
+        rs_xq = __builtin_amdgcn_make_buffer_rsrc((void*)xq_base[0], 0, C64 * 1024, RSRC_FLAGS);
+        rs_pq[0] = __builtin_amdgcn_make_buffer_rsrc((void*)pq_base[0], 0, C64 * 1024, RSRC_FLAGS);
+        rs_pq[1] = __builtin_amdgcn_make_buffer_rsrc((void*)pq_base[1], 0, C64 * 1024, RSRC_FLAGS);
+        rs_sw = __builtin_amdgcn_make_buffer_rsrc((void*)sw_base, 0, (G * p.N - cbw * 32) * 4, RSRC_FLAGS);
+    }
     auto load_a = [&](AStage& a, int step) {
         const int st = step < G ? step : G - 1;
 #pragma unroll
         for (int i = 0; i < SPW; ++i)
 #pragma unroll
             for (int cc = 0; cc < GC; ++cc)
-                a.v[i][cc] = *(const v4i*)(uni(xq_base[i] + (size_t)(st * GC + cc) * 1024) + lane16);
+                if constexpr (GA)
+                    a.v[i][cc] = __builtin_bit_cast(v4i, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs_xq, lane16, st * 1024, 0));
+                else
+                    a.v[i][cc] = *(const v4i*)(xq_base[i] + (size_t)(st * GC + cc) * 1024 + lane16);
     };
     auto store_a = [&](const AStage& a, int buf) {
 #pragma unroll
@@ -161,23 +172,31 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         for (int cbi = 0; cbi < 2; ++cbi) {
 #pragma unroll
             for (int cc = 0; cc < GC; ++cc)
-                b.v[cc][cbi] = *(const v4i*)(uni(pq_base[cbi] + (size_t)(st * GC + cc) * 1024) + lane16);
+                if constexpr (GA)
+                    b.v[cc][cbi] = __builtin_bit_cast(v4i, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs_pq[cbi], lane16, st * 1024, 0));
+                else
+                    b.v[cc][cbi] = *(const v4i*)(pq_base[cbi] + (size_t)(st * GC + cc) * 1024 + lane16);
             if constexpr (GA)
-                b.sw[cbi] = *(const float*)(uni((const uint8_t*)(sw_base + (size_t)st * p.N + cbi * 32)) + l32x4);
+                b.sw[cbi] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_sw, l32x4 + cbi * 128, st * p.N * 4, 0));
             else
                 b.sw[cbi] = sw_base[(size_t)st * p.N + cbi * 32 + l32];
         }
     };
 
-    // SINT4 blocks: the token scales of step s are used straight from the register set they were loaded into
-    // (as the A operand of the scale-product MFMA); the set is refilled for step s + 2 at the end of step s.
+    // SINT4 blocks: the token scales of the whole 128-row tile (G x 512 bytes, [g][row % 32][row block]) are
+    // copied to LDS once; each step reads its 16 bytes per lane from there, one step ahead, into the register
+    // set that serves as the A operand of the scale-product MFMAs.
     struct SStage { v4i sx; };
-    const uint32_t* sxg_base = nullptr;
-    if constexpr (GA) sxg_base = p.sxg + (size_t)(rbw >> 2) * 128;
+    uint8_t* lds_sx = lds + lds_bytes<GC>();
+    if constexpr (GA) {
+        const uint32_t* src = p.sxg + (size_t)(rbw >> 2) * 128;
+        for (int i = tid; i < G * 32; i += NW * 64)
+            *(v4i*)(lds_sx + (size_t)i * 16) = *(const v4i*)(src + ((size_t)(i >> 5) * p.tiles128 * 32 + (i & 31)) * 4);
+    }
     auto load_s = [&](SStage& sc, int step) {
         if constexpr (GA) {
             const int st = step < G ? step : G - 1;
-            v4i v = *(const v4i*)(uni((const uint8_t*)(sxg_base + (size_t)st * p.tiles128 * 128)) + l32x16);
+            v4i v = *(const v4i*)(lds_sx + st * 512 + l32x16);
             if constexpr (NRB == 2) {  // half tiles own row blocks 0,1 or 2,3 of the 128-row tile: bring them to 0,1
                 if (rbw & 2) v = v4i{v[2], v[3], v[0], v[1]};
             }
@@ -267,7 +286,7 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
                 if (j == NT - 1) {  // the last MFMA of the step is in flight: bu is free
                     expand_b(b);
                     load_b(b, s + 1 + STAGES);
-                    load_s(sc, s + 2);  // ... and so is this step's scale set
+                    load_s(sc, s + 1);  // ... and so is this step's scale set
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -294,9 +313,7 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     if constexpr (STAGES == 2) {
         AStage a0, a1;
         BStage b0, b1;
-        SStage s0, s1;
-        load_s(s0, 0);
-        load_s(s1, 1);
+        SStage s0;
         load_a(a0, 0);
         load_b(b0, 0);
         store_a(a0, 0);
@@ -312,12 +329,13 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         load_b(b1, 2);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
+        load_s(s0, 0);
         // Every wavefront runs the same branch-free loop; one without valid output (past the
         // last column or row block of a partial tile) works on clamped operands, stores nothing.
         int s = 0;
         for (; s + 1 < G; s += 2) {
             do_step(s, a0, b0, s0);
-            do_step(s + 1, a1, b1, s1);
+            do_step(s + 1, a1, b1, s0);
         }
         if (s < G) do_step(s, a0, b0, s0);
     } else {
@@ -457,7 +475,7 @@ __device__ __forceinline__ int xcd_order(int b, int n)
 template <int GC, int NK, bool DBG, bool GA = false>
 __global__ __launch_bounds__(NW * 64, 2) void fwd_int_kernel(FwdParams p)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[lds_bytes<GC>()];
+    __shared__ __attribute__((aligned(16))) uint8_t lds[lds_bytes<GC>() + (GA ? GA_MAXG * 512 : 0)];
     const int b = blockIdx.x;
     if (b < p.n_full) {
         const int tile = xcd_order(b, p.n_full);
