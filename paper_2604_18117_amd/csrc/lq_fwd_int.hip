@@ -215,6 +215,7 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     v8i bu[GC][2];   // expanded weight operands of the current step
     float sw[2];     // their scales
     const uint64_t half_mask = 0xFFFFFFFF00000000ull;
+    v4i bsel = {0, 0, 0, 0};
     auto expand_b = [&](const BStage& b) {
 #pragma unroll
         for (int cbi = 0; cbi < 2; ++cbi) {
@@ -266,8 +267,11 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
                 const int rbi = j >> 1, cbi = j & 1;
                 v16f P;
                 if constexpr (GA) {  // scale products of this tile; issued ahead of the next main MFMA
-                    v4i bsel = {0, 0, 0, 0};
+                    // B operand: the channel scale at the k of this row block, zeros elsewhere; kept in one
+                    // register set across tiles and steps, so a tile costs one or two moves
+                    if (cbi == 0) bsel[(rbi + NRB - 1) % NRB] = 0;
                     bsel[rbi] = __float_as_int(swc[cbi]);
+                    asm volatile("" : "+v"(bsel));  // opaque: keeps the set in place instead of rebuilding it per tile
                     P = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, sc.sx), __builtin_bit_cast(v8h, bsel),
                                                                v16f{0}, 0, 0, 0);
                 }

@@ -12,11 +12,13 @@ from tests.gpu_util import to_dev_x
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("family,g,bits", [("int", 64, 8), ("int", 128, 8), ("mx", 32, 8), ("mxb", 32, 8), ("mxb", 32, 6),
-                                           ("mxi", 32, 8)])
+@pytest.mark.parametrize("family,g,bits", [("int", 64, 8), ("int", 128, 8), ("sint4", 64, 8), ("mx", 32, 8), ("mxb", 32, 8),
+                                           ("mxb", 32, 6), ("mxi", 32, 8)])
 def test_graph_replays_match_eager(family, g, bits):
+    ag = 64 if family == "sint4" else 0      # "sint4": INT family with SINT4 blocks for both main operands
+    family = "int" if ag else family
     layer = wl.Layer("t", 700, 512, 640, 32, family, g, bits, 8 if family == "mxi" else bits, "bf16", outlier_scale=10.0,
-                     n_outliers=4, seed=11)
+                     n_outliers=4, seed=11, a_group=ag)
     X, W, L, R = wl.make_inputs(layer)
     cfg = lq.config_for_layer(layer)
     packed = lq.lq_pack_weights(cfg, torch.from_numpy(W).cuda(), torch.from_numpy(L).cuda(), torch.from_numpy(R).cuda())
@@ -58,10 +60,13 @@ def test_graph_replays_match_eager(family, g, bits):
         assert torch.equal(y2.view(torch.int16), eager[(i + 1) % 3].view(torch.int16))
 
 
-@pytest.mark.parametrize("family,bits", [("mx", 8), ("mxb", 8), ("mxb", 6), ("mxi", 8), ("mxi", 4)])
+@pytest.mark.parametrize("family,bits", [("mx", 8), ("mxb", 8), ("mxb", 6), ("mxi", 8), ("mxi", 4), ("sint4", 8)])
 def test_strided_views_and_determinism(family, bits):
     """X and Y as column slices of wider tensors (row strides beyond K and N); repeated calls give identical bits."""
-    layer = wl.Layer("t", 130, 384, 192, 32, family, 32, bits, 8 if family == "mxi" else bits, "bf16", seed=13)
+    ag = 64 if family == "sint4" else 0
+    family = "int" if ag else family
+    layer = wl.Layer("t", 130, 384, 192, 32, family, 64 if ag else 32, bits, 8 if family == "mxi" else bits, "bf16", seed=13,
+                     a_group=ag)
     X, W, L, R = wl.make_inputs(layer)
     cfg = lq.config_for_layer(layer)
     packed = lq.lq_pack_weights(cfg, torch.from_numpy(W).cuda(), torch.from_numpy(L).cuda(), torch.from_numpy(R).cuda())

@@ -158,15 +158,17 @@ def _full_size_sampled(oracle, name):
     assert np.array_equal(Yb, out.Y)
 
 
-@pytest.mark.parametrize("M,K,N,r,xd", [(200, 1152, 320, 32, "bf16"), (77, 2304, 64, 16, "f32"), (33, 256, 64, 0, "bf16")])
-def test_fused_smoothing(oracle, M, K, N, r, xd):
+@pytest.mark.parametrize("M,K,N,r,xd,ag", [(200, 1152, 320, 32, "bf16", 0), (77, 2304, 64, 16, "f32", 0), (33, 256, 64, 0, "bf16", 0),
+                                              (200, 1152, 320, 32, "bf16", 64), (77, 2304, 64, 16, "f32", 64)])
+def test_fused_smoothing(oracle, M, K, N, r, xd, ag):
     """Activation smoothing (Section 3.4; App. A.1) fused into the activation kernel: the GPU is given the raw X
-    and the smoothing vector; the oracle quantises the smoothed input.  Everything bit-exact as for the plain path."""
+    and the smoothing vector; the oracle quantises the smoothed input.  Everything bit-exact as for the plain path.
+    ag = 64: together with SINT4 blocks for the main operands (the paper's literal SINT4 setting)."""
     import torch
     from paper_2604_18117_amd import binding as lq
     from tests.gpu_util import to_dev_x
     layer = wl.shrink(wl.LAYERS["c2_qkv"], M=M, K=K, N=N, r=r)
-    layer = wl.Layer(**{**layer.__dict__, "x_dtype": xd, "seed": M + K})
+    layer = wl.Layer(**{**layer.__dict__, "x_dtype": xd, "seed": M + K, "a_group": ag})
     X, W, L, R = wl.make_inputs(layer)
     gamma = wl.smoothing_vector(X, W)
     Ws = (W.astype(np.float64) * gamma).astype(np.float32)       # the caller folds gamma into W before packing
@@ -176,7 +178,7 @@ def test_fused_smoothing(oracle, M, K, N, r, xd):
     Xd = to_dev_x(X, xd)
     # before lq_set_smoothing the blob holds reciprocals 1: the plain path
     a0 = lq.lq_quantize_act(cfg, packed, Xd)
-    pk = oracle.pack_int(Ws, L if r else None, R if r else None, layer.g, layer.br_w_bits)
+    pk = oracle.pack_int(Ws, L if r else None, R if r else None, layer.g, layer.br_w_bits, sint4_blocks=ag == 64)
     act0 = oracle.quantize_act_int(X, pk, layer.br_a_bits)
     assert np.array_equal(n(lq.lq_unpack_act(cfg, a0, M).xq), act0.xq)
     lq.lq_set_smoothing(cfg, packed, torch.from_numpy(gamma).cuda())
