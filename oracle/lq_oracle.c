@@ -33,6 +33,9 @@
  *          int4 and int8" elements, blocks of 32, E8M0 scale; the integer rows of the
  *          mixed-precision tables, Section 4.3); fp64 accumulate, one rounding.
  *
+ * Besides the forward, lqo_calib_step is one Adam step of the data-free optimisation of the factors
+ * (Eq. 4, App. B.2), the step that produces the L and R the forward consumes.
+ *
  * Readings of points the paper leaves open (all "parity unpinned" by the paper; the tests
  * pin self-consistency only):
  *   - "round to nearest" = ties to even;
@@ -964,6 +967,102 @@ LQO_API void lqo_fwd_mxb6(int64_t M, int64_t N, int64_t K, int r, const uint8_t 
         free(vx);
     }
     free(vw);
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* Data-free calibration of the low-rank factors (Section 3.2, Eq. 4; App. B.2)           */
+/* ------------------------------------------------------------------------------------ */
+
+/* One Adam step on   loss(L, R) = mean_{n,k} ( Q1(W + L R) - W - L R )^2   (Eq. 4 with the Mean Squared
+   Error loss).  Orientation as everywhere here: W is N x K, L is N x r, R is r x K (the paper's
+   W^T, R^T, L^T); Q1 quantises W + L R along K in groups of g (fp32 scales) or in SINT4 blocks.
+   Readings:
+     - the point V = W + L R at which Q1 is evaluated is an fp32 number: v = W[n,k], then
+       v = fma(L[n,j], R[j,k], v) for ascending j (the quantised codes depend on V's rounding, so the
+       arithmetic type of this decision is fixed: fp32, this order);
+     - E = deq(Q1(V)) - V with deq = code * scale, both in fp32;
+     - App. B.2: the rounding has zero derivative, so d loss / d(L R) = -2 E / (N K), and
+       grad_L = -2/(N K) E R^T, grad_R = -2/(N K) L^T E  (accumulated in fp64 here, ascending index,
+       rounded once to fp32);
+     - Adam as published: m = b1 m + (1-b1) g, v = b2 v + (1-b2) g^2, bias-corrected by 1-b1^t and
+       1-b2^t (t = step, counted from 1), p -= lr * mhat / (sqrt(vhat) + eps); no weight decay.  State is
+       stored in fp32; one step's arithmetic is done in fp64 and rounded once per stored value.
+   In/out: L, R, mL, vL, mR, vR.  Out (each optional): E N x K, gL N x r, gR r x K, *loss (before the
+   update). */
+LQO_API void lqo_calib_step(int64_t N, int64_t K, int r, int g, int sint4_blocks, const float *W, float *L,
+                            float *R, float *mL, float *vL, float *mR, float *vR, int step, double lr,
+                            double b1, double b2, double eps, float *E_out, float *gL_out, float *gR_out,
+                            double *loss_out)
+{
+    const int64_t G = K / g;
+    float *E = (float *)malloc(sizeof(float) * (size_t)(N * K));
+    float *gL = (float *)malloc(sizeof(float) * (size_t)(N * (r > 0 ? r : 1)));
+    float *gR = (float *)malloc(sizeof(float) * (size_t)((r > 0 ? r : 1) * K));
+    const double c = -2.0 / ((double)N * (double)K);
+
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        float *V = (float *)malloc(sizeof(float) * (size_t)K);
+        int8_t *q = (int8_t *)malloc((size_t)K);
+        float *sc = (float *)malloc(sizeof(float) * (size_t)G);
+        for (int64_t k = 0; k < K; ++k) {
+            float v = W[n * K + k];
+            for (int j = 0; j < r; ++j) v = fmaf(L[n * r + j], R[(int64_t)j * K + k], v);
+            V[k] = v;
+        }
+        if (sint4_blocks)
+            lqo_quant_sint4(V, K, q, sc);
+        else
+            for (int64_t gi = 0; gi < G; ++gi) lqo_quant_int(V + gi * g, g, 7, q + gi * g, &sc[gi]);
+        for (int64_t k = 0; k < K; ++k) {
+            float deq = (float)q[k] * sc[k / g];
+            E[n * K + k] = deq - V[k];
+        }
+        free(V);
+        free(q);
+        free(sc);
+    }
+    double loss = 0.0;
+    for (int64_t i = 0; i < N * K; ++i) loss += (double)E[i] * (double)E[i];
+    loss /= (double)N * (double)K;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int j = 0; j < r; ++j) {
+            double a = 0.0;
+            for (int64_t k = 0; k < K; ++k) a += (double)E[n * K + k] * (double)R[(int64_t)j * K + k];
+            gL[n * r + j] = (float)(c * a);
+        }
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < K; ++k)
+        for (int j = 0; j < r; ++j) {
+            double a = 0.0;
+            for (int64_t n = 0; n < N; ++n) a += (double)L[n * r + j] * (double)E[n * K + k];
+            gR[(int64_t)j * K + k] = (float)(c * a);
+        }
+
+    const double c1 = 1.0 - pow(b1, (double)step), c2 = 1.0 - pow(b2, (double)step);
+    for (int pass = 0; pass < 2; ++pass) {
+        float *p = pass ? R : L, *m = pass ? mR : mL, *v = pass ? vR : vL;
+        const float *gr = pass ? gR : gL;
+        const int64_t cnt = pass ? (int64_t)r * K : N * r;
+        for (int64_t i = 0; i < cnt; ++i) {
+            double gd = (double)gr[i];
+            double mm = b1 * (double)m[i] + (1.0 - b1) * gd;
+            double vv = b2 * (double)v[i] + (1.0 - b2) * gd * gd;
+            m[i] = (float)mm;
+            v[i] = (float)vv;
+            double upd = lr * (mm / c1) / (sqrt(vv / c2) + eps);
+            p[i] = (float)((double)p[i] - upd);
+        }
+    }
+    if (E_out) memcpy(E_out, E, sizeof(float) * (size_t)(N * K));
+    if (gL_out) memcpy(gL_out, gL, sizeof(float) * (size_t)(N * r));
+    if (gR_out) memcpy(gR_out, gR, sizeof(float) * (size_t)(r * K));
+    if (loss_out) *loss_out = loss;
+    free(E);
+    free(gL);
+    free(gR);
 }
 
 LQO_API int lqo_num_threads(void)

@@ -500,3 +500,50 @@ def fwd_mxi(pk: PackedMxi, act: ActMxi) -> FwdOut:
                       _p(act.xe), _p(pk.pq), _p(pk.pe), _p(act.tq), _p(act.te), _p(pk.lq), _p(pk.le),
                       _p(out.ymain), _p(out.ybr), _p(out.y32), _p(out.Y))
     return out
+
+
+# ---------------------------------------------------------------------------------------
+# data-free calibration of the factors (Eq. 4, App. B.2)
+# ---------------------------------------------------------------------------------------
+
+@dataclass
+class CalibState:
+    """fp32 state of the optimisation: factors (paper's sign: Q1(W + L R) - W ~ L R) and Adam moments."""
+    L: np.ndarray
+    R: np.ndarray
+    mL: np.ndarray
+    vL: np.ndarray
+    mR: np.ndarray
+    vR: np.ndarray
+    step: int = 0
+
+
+def calib_init(L, R) -> CalibState:
+    L, R = _f32(L).copy(), _f32(R).copy()
+    return CalibState(L, R, np.zeros_like(L), np.zeros_like(L), np.zeros_like(R), np.zeros_like(R), 0)
+
+
+@dataclass
+class CalibOut:
+    loss: float          # mean squared error before this step's update
+    E: np.ndarray        # N x K  deq(Q1(W + L R)) - (W + L R)
+    gL: np.ndarray       # N x r
+    gR: np.ndarray       # r x K
+
+
+def calib_step(W, st: CalibState, g: int = 64, sint4_blocks: bool = False, lr: float = 1e-4, beta1: float = 0.9,
+               beta2: float = 0.999, eps: float = 1e-8) -> CalibOut:
+    """One Adam step; updates `st` in place and returns the loss / error / gradients it was computed from."""
+    W = _f32(W)
+    N, K = W.shape
+    r = st.L.shape[1]
+    assert st.L.shape == (N, r) and st.R.shape == (r, K) and K % g == 0
+    st.step += 1
+    out = CalibOut(0.0, np.empty((N, K), np.float32), np.empty((N, r), np.float32), np.empty((r, K), np.float32))
+    loss = C.c_double(0.0)
+    lib().lqo_calib_step(C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(g), C.c_int(1 if sint4_blocks else 0), _p(W),
+                         _p(st.L), _p(st.R), _p(st.mL), _p(st.vL), _p(st.mR), _p(st.vR), C.c_int(st.step),
+                         C.c_double(lr), C.c_double(beta1), C.c_double(beta2), C.c_double(eps), _p(out.E), _p(out.gL),
+                         _p(out.gR), C.byref(loss))
+    out.loss = float(loss.value)
+    return out

@@ -359,6 +359,112 @@ def test_sint4_block_forward_against_exact_rationals(oracle):
     e_tok = np.abs(out0.ymain - ref).mean()
     assert e_blk < e_tok
 
+
+# --------------------------------------------------------------------------------------
+# data-free calibration of the factors (Section 3.2, Eq. 4; App. B.2)
+# --------------------------------------------------------------------------------------
+
+def _calib_problem(oracle, seed=31, N=48, K=256, r=8):
+    rng = np.random.default_rng(seed)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    U, S, Vt = np.linalg.svd(W.astype(np.float64), full_matrices=False)
+    L0 = (U[:, :r] * np.sqrt(S[:r])).astype(np.float32)           # best rank-r approximation W ~ L0 R0 (Section 3.2)
+    R0 = (np.sqrt(S[:r])[:, None] * Vt[:r]).astype(np.float32)
+    return W, -L0, R0                                             # the paper starts from L = -L0, R = R0
+
+
+@pytest.mark.parametrize("g,sint4", [(64, False), (128, False), (64, True)])
+def test_calib_error_and_gradients(oracle, g, sint4):
+    W, L, R = _calib_problem(oracle)
+    N, K = W.shape
+    st = oracle.calib_init(L, R)
+    out = oracle.calib_step(W, st, g, sint4_blocks=sint4)
+    V = W.astype(np.float64) + L.astype(np.float64) @ R.astype(np.float64)
+    # E = Q1(V) - V: E + V sits on the 4-bit grid of its group (integer code in [-7, 7] times the group scale)
+    for n in (0, 7, N - 1):
+        for gi in range(K // g):
+            sl = slice(gi * g, (gi + 1) * g)
+            if sint4:
+                scale = float(np.float16(np.abs(V[n, sl]).max() / 7))
+                tol = 2 ** -10
+            else:
+                scale = np.abs(V[n, sl]).max() / 7
+                tol = 1e-5
+            codes = (out.E[n, sl] + V[n, sl]) / scale
+            assert np.all(np.abs(codes - np.rint(codes)) <= 7 * tol + 1e-4) and np.abs(np.rint(codes)).max() == 7
+            assert np.all(np.abs(out.E[n, sl]) <= scale * (0.5 + 8 * tol))
+    # loss = mean of E^2 (Mean Squared Error)
+    assert abs(out.loss - np.mean(out.E.astype(np.float64) ** 2)) <= 1e-12 * out.loss
+    # App. B.2: grad_L = -2/(NK) E R^T, grad_R = -2/(NK) L^T E  (numpy's matmul as the independent routine)
+    gL = -2.0 / (N * K) * out.E.astype(np.float64) @ R.astype(np.float64).T
+    gR = -2.0 / (N * K) * L.astype(np.float64).T @ out.E.astype(np.float64)
+    assert np.allclose(out.gL, gL, rtol=1e-6, atol=1e-7 * np.abs(gL).max())
+    assert np.allclose(out.gR, gR, rtol=1e-6, atol=1e-7 * np.abs(gR).max())
+    # ... which is the gradient of mean((C - L R)^2) with the quantised target C = Q1(W + L R) - W held fixed
+    # (the rounding has zero derivative): central differences on a few entries
+    Cq = out.E.astype(np.float64) + L.astype(np.float64) @ R.astype(np.float64)
+    f = lambda Lm, Rm: np.mean((Cq - Lm @ Rm) ** 2)
+    Ld, Rd = L.astype(np.float64), R.astype(np.float64)
+    for (i, j) in ((0, 0), (5, 3), (N - 1, 7)):
+        h = 1e-6
+        Lp, Lm_ = Ld.copy(), Ld.copy()
+        Lp[i, j] += h
+        Lm_[i, j] -= h
+        assert abs((f(Lp, Rd) - f(Lm_, Rd)) / (2 * h) - gL[i, j]) <= 1e-6 * np.abs(gL).max() + 1e-12
+    for (j, k) in ((0, 0), (3, 100), (7, K - 1)):
+        h = 1e-6
+        Rp, Rm_ = Rd.copy(), Rd.copy()
+        Rp[j, k] += h
+        Rm_[j, k] -= h
+        assert abs((f(Ld, Rp) - f(Ld, Rm_)) / (2 * h) - gR[j, k]) <= 1e-6 * np.abs(gR).max() + 1e-12
+
+
+def test_calib_adam_matches_library_optimizer(oracle):
+    # the update rule against torch.optim.Adam fed with the oracle's own gradients, over several steps
+    torch = pytest.importorskip("torch")
+    W, L, R = _calib_problem(oracle, seed=32)
+    st = oracle.calib_init(L, R)
+    Lt = torch.tensor(L, dtype=torch.float64, requires_grad=True)
+    Rt = torch.tensor(R, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adam([Lt, Rt], lr=1e-3, betas=(0.9, 0.999), eps=1e-8)
+    for step in range(4):
+        out = oracle.calib_step(W, st, 64, lr=1e-3)
+        Lt.grad = torch.tensor(out.gL, dtype=torch.float64)
+        Rt.grad = torch.tensor(out.gR, dtype=torch.float64)
+        opt.step()
+        # fp32 storage of the state on the oracle's side: a few ulps of the parameter per step
+        assert np.allclose(st.L, Lt.detach().numpy(), rtol=0, atol=4e-7 * (step + 1) * np.abs(L).max())
+        assert np.allclose(st.R, Rt.detach().numpy(), rtol=0, atol=4e-7 * (step + 1) * np.abs(R).max())
+    # closed form of Adam's first step (mhat = g, vhat = g^2): p -= lr g / (|g| + eps); with the mean-squared-error scaling
+    # the gradients of such a layer are of the order of eps, so eps is not negligible here
+    st1 = oracle.calib_init(L, R)
+    out = oracle.calib_step(W, st1, 64, lr=1e-3)
+    gd = out.gL.astype(np.float64)
+    want = L.astype(np.float64) - 1e-3 * gd / (np.abs(gd) + 1e-8)
+    assert np.allclose(st1.L, want, rtol=0, atol=2e-7 * np.abs(L).max())
+    assert 1e-9 < np.abs(gd).max() < 1e-5
+
+
+def test_calib_fixed_point_and_descent(oracle):
+    # Section 3.2: a point of the quantiser's image is a fixed point: E = 0, zero gradients, nothing moves
+    W, L, R = _calib_problem(oracle, seed=33)
+    # a weight on the 4-bit grid of its groups: scale 0.25 (amax 1.75 = 7 * 0.25), codes 7, 2, -3, 0
+    Wfix = np.zeros_like(W)
+    Wfix[:, 0], Wfix[:, 1], Wfix[:, 2] = 1.75, 0.5, -0.75
+    Wfix[:, 64:128] = Wfix[:, :64] * np.float32(2.0 ** -5)
+    st = oracle.calib_init(np.zeros_like(L), R)
+    out = oracle.calib_step(Wfix, st, 64)
+    assert not out.E.any() and not out.gL.any() and not out.gR.any() and out.loss == 0.0
+    assert not st.L.any() and np.array_equal(st.R, R)
+    # descent on a seeded synthetic weight: the optimisation lowers the loss of the SVD initialisation (Section 3.2)
+    st = oracle.calib_init(L, R)
+    losses = [oracle.calib_step(W, st, 64, lr=1e-4).loss for _ in range(120)]
+    assert losses[-1] < 0.9 * losses[0]
+    assert sum(b <= a * (1 + 1e-3) for a, b in zip(losses, losses[1:])) >= 0.9 * (len(losses) - 1)
+    # the SVD initialisation itself beats no compensation: Q(W - L0 R0) + L0 R0 is closer to W than Q(W)
+    z = oracle.calib_init(np.zeros_like(L), np.zeros_like(R))
+    assert losses[0] < oracle.calib_step(W, z, 64).loss
+
 # --------------------------------------------------------------------------------------
 # whole INT path
 # --------------------------------------------------------------------------------------
