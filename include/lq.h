@@ -185,6 +185,47 @@ lq_status lq_unpack_weights(const lq_config *cfg, const void *packed, const lq_w
 lq_status lq_unpack_act(const lq_config *cfg, const void *act, int64_t M, const lq_act_view *out,
                         void *stream);
 
+/* ---- Data-free calibration of the factors (Section 3.2, Eq. 4; gradients of App. B.2) --------------------------
+   The step that produces the L and R the forward consumes: gradient descent with Adam on
+       loss(L, R) = mean over N x K of ( Q1(W + L R) - W - L R )^2 ,
+   the rounding treated as having zero derivative, so that grad_L = -2/(N K) E R^T and grad_R = -2/(N K) L^T E with
+   E = Q1(W + L R) - W - L R.  Q1 is cfg's main weight quantiser; INT family only (LQ_ERR_UNSUPPORTED otherwise);
+   rank >= 16.  W + L R is formed in fp32 (W, then one fused multiply-add per rank index, ascending).
+   Sign: the factors follow the paper, Q1(W + L R) - W ~ L R, and the paper starts them at L = -L0, R = R0 with L0 R0
+   the best rank-r approximation of W (an input here: the singular value decomposition is the caller's).  lq_pack_weights
+   forms W - L' R', so it takes L' = -L, R' = R.
+   The state blob is device memory owned by the caller (256-byte aligned, at least state_bytes); it holds the factors,
+   Adam's two moments, the last step's gradients and error matrix.  A step is four kernel launches, no atomics, no
+   allocation; results are reproducible bit for bit. */
+typedef struct {
+    float lr;      /* the paper uses 1e-4 for INT formats (App. A.2)                  */
+    float beta1;   /* Adam as published: 0.9, 0.999, 1e-8; bias-corrected, no decay   */
+    float beta2;
+    float eps;
+} lq_adam;
+
+typedef struct {   /* plain row-major fp32 device arrays; any member may be NULL */
+    float *L, *R;        /* N x r, r x K   current factors                              */
+    float *mL, *vL;      /* N x r          Adam moments of L                            */
+    float *mR, *vR;      /* r x K          Adam moments of R                            */
+    float *gL, *gR;      /* gradients used by the last step                              */
+    float *E;            /* N x K          Q1(W + L R) - (W + L R) of the last step      */
+} lq_calib_view;
+
+lq_status lq_calib_sizes(const lq_config *cfg, size_t *state_bytes);
+
+/* Start an optimisation: copies L (N x r) and R (r x K), device fp32 dense, into the state and zeroes the moments. */
+lq_status lq_calib_init(const lq_config *cfg, const float *L, const float *R, void *state, size_t state_bytes,
+                        void *stream);
+
+/* One Adam step.  W: device, N x K fp32 dense.  step: 1 for the first step after lq_calib_init, then 2, 3, ... (it
+   sets the bias correction).  loss: device, one float, receives the loss BEFORE this step's update; may be NULL. */
+lq_status lq_calib_step(const lq_config *cfg, const float *W, void *state, size_t state_bytes, int32_t step,
+                        const lq_adam *adam, float *loss, void *stream);
+
+/* Copy parts of the state out (device to device). */
+lq_status lq_calib_unpack(const lq_config *cfg, const void *state, const lq_calib_view *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -53,9 +53,23 @@ class lq_act_view(C.Structure):
                 ("st", C.c_void_p), ("te", C.c_void_p)]
 
 
-EXPORTS = ["lq_status_string", "lq_packed_sizes", "lq_pack_weights", "lq_set_smoothing", "lq_act_sizes", "lq_quantize_act",
-           "lq_linear_lowrank_fwd", "lq_unpack_weights", "lq_unpack_act"]
+class lq_adam(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float)]
 
+
+class lq_calib_view(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("L", "R", "mL", "vL", "mR", "vR", "gL", "gR", "E")]
+
+
+EXPORTS = ["lq_status_string", "lq_packed_sizes", "lq_pack_weights", "lq_set_smoothing", "lq_act_sizes", "lq_quantize_act",
+           "lq_linear_lowrank_fwd", "lq_unpack_weights", "lq_unpack_act", "lq_calib_sizes", "lq_calib_init", "lq_calib_step",
+           "lq_calib_unpack"]
+
+_lib.lq_calib_sizes.argtypes = [C.POINTER(lq_config), C.POINTER(C.c_size_t)]
+_lib.lq_calib_init.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.lq_calib_step.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.POINTER(lq_adam),
+                               C.c_void_p, C.c_void_p]
+_lib.lq_calib_unpack.argtypes = [C.POINTER(lq_config), C.c_void_p, C.POINTER(lq_calib_view), C.c_void_p]
 _lib.lq_status_string.restype = C.c_char_p
 _lib.lq_status_string.argtypes = [C.c_int]
 _lib.lq_packed_sizes.argtypes = [C.POINTER(lq_config), C.POINTER(C.c_size_t)]
@@ -278,3 +292,42 @@ def lq_unpack_act(cfg: lq_config, act: torch.Tensor, M: int) -> ActView:
                        v.te.data_ptr())
     _check(_lib.lq_unpack_act(C.byref(cfg), _ptr(act), M, C.byref(view), C.c_void_p(_stream())), "lq_unpack_act")
     return v
+
+
+# ---- data-free calibration of the factors (argument marshalling only) -------------------------------------------------
+
+def lq_calib_sizes(cfg: lq_config) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.lq_calib_sizes(C.byref(cfg), C.byref(n)), "lq_calib_sizes")
+    return int(n.value)
+
+
+def lq_calib_init(cfg: lq_config, L: torch.Tensor, R: torch.Tensor, state: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """L (N x r), R (r x K): fp32 CUDA, contiguous (paper's sign: Q1(W + L R) - W ~ L R).  Returns the state blob."""
+    for t in (L, R):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+    if state is None:
+        state = torch.empty(lq_calib_sizes(cfg), dtype=torch.uint8, device=L.device)
+    _check(_lib.lq_calib_init(C.byref(cfg), _ptr(L), _ptr(R), _ptr(state), state.numel(), C.c_void_p(_stream())),
+           "lq_calib_init")
+    return state
+
+
+def lq_calib_step(cfg: lq_config, W: torch.Tensor, state: torch.Tensor, step: int, lr: float = 1e-4, beta1: float = 0.9,
+                  beta2: float = 0.999, eps: float = 1e-8, loss: Optional[torch.Tensor] = None) -> None:
+    """One Adam step (step counts from 1); `loss`: optional 1-element fp32 CUDA tensor that receives the loss before the update."""
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous()
+    ad = lq_adam(lr, beta1, beta2, eps)
+    _check(_lib.lq_calib_step(C.byref(cfg), _ptr(W), _ptr(state), state.numel(), step, C.byref(ad), _ptr(loss),
+                              C.c_void_p(_stream())), "lq_calib_step")
+
+
+def lq_calib_unpack(cfg: lq_config, state: torch.Tensor, names=("L", "R")) -> dict:
+    """Copies of the named parts of the state: L, R, mL, vL, mR, vR, gL, gR, E."""
+    N, K, r = cfg.N, cfg.K, cfg.rank
+    shapes = {"L": (N, r), "R": (r, K), "mL": (N, r), "vL": (N, r), "mR": (r, K), "vR": (r, K), "gL": (N, r), "gR": (r, K),
+              "E": (N, K)}
+    out = {k: torch.empty(shapes[k], dtype=torch.float32, device=state.device) for k in names}
+    view = lq_calib_view(**{k: (out[k].data_ptr() if k in out else None) for k in shapes})
+    _check(_lib.lq_calib_unpack(C.byref(cfg), _ptr(state), C.byref(view), C.c_void_p(_stream())), "lq_calib_unpack")
+    return out

@@ -268,4 +268,60 @@ lq_status lq_unpack_act(const lq_config* cfg, const void* act, int64_t M, const 
     return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }
 
+static lq_status calib_dims(const lq_config* cfg, Dims* d)
+{
+    lq_status st = make_dims(cfg, d);
+    if (st != LQ_OK) return st;
+    if (d->mx || d->mxi) return LQ_ERR_UNSUPPORTED;  // the calibration step knows the INT family's main quantiser
+    if (d->r < 16) return LQ_ERR_SHAPE;
+    return LQ_OK;
+}
+
+lq_status lq_calib_sizes(const lq_config* cfg, size_t* state_bytes)
+{
+    if (!cfg || !state_bytes) return LQ_ERR_NULL;
+    Dims d;
+    lq_status st = calib_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    *state_bytes = calib_layout(d).total;
+    return LQ_OK;
+}
+
+lq_status lq_calib_init(const lq_config* cfg, const float* L, const float* R, void* state, size_t state_bytes, void* stream)
+{
+    Dims d;
+    lq_status st = calib_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!L || !R || !state) return LQ_ERR_NULL;
+    if (!aligned(state, 256) || !aligned(L, 16) || !aligned(R, 16)) return LQ_ERR_ALIGN;
+    if (state_bytes < calib_layout(d).total) return LQ_ERR_BUFFER_TOO_SMALL;
+    return launch_calib_init(d, L, R, (uint8_t*)state, (hipStream_t)stream) == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
+lq_status lq_calib_step(const lq_config* cfg, const float* W, void* state, size_t state_bytes, int32_t step,
+                        const lq_adam* adam, float* loss, void* stream)
+{
+    Dims d;
+    lq_status st = calib_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!W || !state || !adam) return LQ_ERR_NULL;
+    if (step < 1) return LQ_ERR_SHAPE;
+    if (!(adam->lr > 0.f) || !(adam->beta1 >= 0.f && adam->beta1 < 1.f) || !(adam->beta2 >= 0.f && adam->beta2 < 1.f) ||
+        !(adam->eps > 0.f))
+        return LQ_ERR_UNSUPPORTED;
+    if (!aligned(state, 256) || !aligned(W, 16) || (loss && !aligned(loss, 4))) return LQ_ERR_ALIGN;
+    if (state_bytes < calib_layout(d).total) return LQ_ERR_BUFFER_TOO_SMALL;
+    return launch_calib_step(d, W, (uint8_t*)state, step, adam, loss, (hipStream_t)stream) == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
+lq_status lq_calib_unpack(const lq_config* cfg, const void* state, const lq_calib_view* out, void* stream)
+{
+    Dims d;
+    lq_status st = calib_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!state || !out) return LQ_ERR_NULL;
+    if (!aligned(state, 256)) return LQ_ERR_ALIGN;
+    return launch_calib_unpack(d, (const uint8_t*)state, out, (hipStream_t)stream) == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
 }  // extern "C"

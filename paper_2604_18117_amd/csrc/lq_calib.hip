@@ -1,0 +1,292 @@
+// Data-free calibration of the low-rank factors (Section 3.2, Eq. 4; gradients of App. B.2): one Adam step on
+//     loss(L, R) = mean ( Q1(W + L R) - W - L R )^2
+// for the INT family's main quantiser Q1 (INT4 in groups of 64 | 128 along K with fp32 scales, or SINT4 blocks with
+// FP16 scales).  Four launches per step:
+//   calib_err_kernel   V = W + L R (fp32 FMA chain over ascending j), E = deq(Q1(V)) - V, partial sums of E^2
+//   gemm_nt_kernel     grad_L = -2/(N K) E R^T      (fp32 MFMA, contraction split over the wavefronts of a workgroup)
+//   gemm_tn_kernel     grad_R = -2/(N K) L^T E
+//   calib_adam_kernel  Adam update of L and R, loss = sum of the partials / (N K)
+// No atomics: every sum has a fixed order, so a step is reproducible bit for bit.
+#include "lq_internal.h"
+
+namespace lq {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+CalibLayout calib_layout(const Dims& d)
+{
+    CalibLayout cl;
+    const size_t nl = (size_t)d.N * d.r * 4, nr = (size_t)d.r * d.K * 4;
+    size_t o = 0;
+    cl.off_L = o;  o = align256(o + nl);
+    cl.off_R = o;  o = align256(o + nr);
+    cl.off_mL = o; o = align256(o + nl);
+    cl.off_vL = o; o = align256(o + nl);
+    cl.off_mR = o; o = align256(o + nr);
+    cl.off_vR = o; o = align256(o + nr);
+    cl.off_gL = o; o = align256(o + nl);
+    cl.off_gR = o; o = align256(o + nr);
+    cl.off_E = o;  o = align256(o + (size_t)d.N * d.K * 4);
+    cl.n_lp = (int)(d.N / 16) * 4;  // one partial per wavefront of calib_err_kernel
+    cl.off_lp = o; o = align256(o + (size_t)cl.n_lp * 4);
+    cl.total = o;
+    return cl;
+}
+
+__device__ __forceinline__ float wave_max_f(float v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum_f(float v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = __fadd_rn(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// A workgroup owns 16 rows of W; its 4 wavefronts take the K groups round-robin; lane = column within a 64-chunk.
+// The 16 x r block of L sits in LDS (uniform-address reads broadcast), the r values of R for the lane's column(s)
+// stream through registers four rows of R at a time.
+template <int GC, bool SINT4>
+__global__ __launch_bounds__(256) void calib_err_kernel(const float* W, const float* L, const float* R, float* E, float* lp,
+                                                        int N, int K, int r)
+{
+    extern __shared__ __attribute__((aligned(16))) float sL[];  // [16][r]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n0 = blockIdx.x * 16;
+    for (int i = tid * 4; i < 16 * r; i += 256 * 4) *(v4f*)&sL[i] = *(const v4f*)&L[(size_t)n0 * r + i];
+    __syncthreads();
+    const int G = K / (64 * GC);
+    float lsum = 0.f;
+    for (int g = wave; g < G; g += 4) {
+        const int col0 = g * GC * 64 + lane;
+        float v[16][GC];
+#pragma unroll
+        for (int row = 0; row < 16; ++row)
+#pragma unroll
+            for (int c = 0; c < GC; ++c) v[row][c] = W[(size_t)(n0 + row) * K + col0 + c * 64];
+        for (int j = 0; j < r; j += 4) {
+            float rj[4][GC];
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                for (int c = 0; c < GC; ++c) rj[jj][c] = R[(size_t)(j + jj) * K + col0 + c * 64];
+#pragma unroll
+            for (int row = 0; row < 16; ++row) {
+                const v4f l4 = *(const v4f*)&sL[row * r + j];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                    for (int c = 0; c < GC; ++c) v[row][c] = __builtin_fmaf(l4[jj], rj[jj][c], v[row][c]);
+            }
+        }
+#pragma unroll
+        for (int row = 0; row < 16; ++row) {
+            float a = 0.f;
+#pragma unroll
+            for (int c = 0; c < GC; ++c) a = fmaxf(a, fabsf(v[row][c]));
+            a = wave_max_f(a);
+            float s, inv;
+            if constexpr (SINT4) {
+                s = f16_bits_value(sint4_scale(a, &inv));
+            } else if (a == 0.0f) {
+                s = 1.0f;
+                inv = 1.0f;
+            } else {
+                s = __fdiv_rn(a, 7.0f);
+                inv = __fdiv_rn(7.0f, a);
+            }
+#pragma unroll
+            for (int c = 0; c < GC; ++c) {
+                float q = rintf(__fmul_rn(v[row][c], inv));
+                q = fminf(fmaxf(q, -7.0f), 7.0f);
+                const float e = __fsub_rn(__fmul_rn(q, s), v[row][c]);
+                E[(size_t)(n0 + row) * K + col0 + c * 64] = e;
+                lsum = __fadd_rn(lsum, __fmul_rn(e, e));
+            }
+        }
+    }
+    lsum = wave_sum_f(lsum);
+    if (lane == 0) lp[blockIdx.x * 4 + wave] = lsum;
+}
+
+// C[m][n] = scale * sum_k A[m][k] B[n][k]   (both operands with the contraction index contiguous).  One 16 x 16 tile
+// of C per workgroup; wavefront w takes the 16-deep k slices w, w + WAVES, ...; partial tiles are summed through
+// LDS in wavefront order.  v_mfma_f32_16x16x4_f32: lane l supplies A[row l%16][k slot l/16] and B[col l%16][k slot
+// l/16]; a lane's 16-byte load holds four consecutive k, which feed four MFMAs (the k order inside a slice is
+// permuted the same way for both operands).
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_nt_kernel(const float* A, int lda, const float* B, int ldb, float* C, int ldc,
+                                                            int tilesN, int Kc, float scale)
+{
+    __shared__ __attribute__((aligned(16))) float s_acc[WAVES][64][4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = lane & 15, q = lane >> 4;
+    const int m0 = (blockIdx.x / tilesN) * 16, n0 = (blockIdx.x % tilesN) * 16;
+    v4f acc = {0.f, 0.f, 0.f, 0.f};
+    const float* ap = A + (size_t)(m0 + row) * lda + 4 * q;
+    const float* bp = B + (size_t)(n0 + row) * ldb + 4 * q;
+    for (int kk = wave * 16; kk < Kc; kk += WAVES * 16) {
+        const v4f a4 = *(const v4f*)(ap + kk);
+        const v4f b4 = *(const v4f*)(bp + kk);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[i], b4[i], acc, 0, 0, 0);
+    }
+    *(v4f*)&s_acc[wave][lane][0] = acc;
+    __syncthreads();
+    if (wave != 0) return;
+    v4f s = *(const v4f*)&s_acc[0][lane][0];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) {
+        const v4f o = *(const v4f*)&s_acc[w][lane][0];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s[i] = __fadd_rn(s[i], o[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) C[(size_t)(m0 + 4 * q + i) * ldc + n0 + row] = __fmul_rn(scale, s[i]);
+}
+
+// C[m][n] = scale * sum_k A[k][m] B[k][n]   (the contraction index is the row index of both operands).
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_tn_kernel(const float* A, int lda, const float* B, int ldb, float* C, int ldc,
+                                                            int tilesN, int Kc, float scale)
+{
+    __shared__ __attribute__((aligned(16))) float s_acc[WAVES][64][4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = lane & 15, q = lane >> 4;
+    const int m0 = (blockIdx.x / tilesN) * 16, n0 = (blockIdx.x % tilesN) * 16;
+    v4f acc = {0.f, 0.f, 0.f, 0.f};
+    for (int kk = wave * 16; kk < Kc; kk += WAVES * 16) {
+        float a4[4], b4[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a4[i] = A[(size_t)(kk + 4 * q + i) * lda + m0 + row];
+            b4[i] = B[(size_t)(kk + 4 * q + i) * ldb + n0 + row];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[i], b4[i], acc, 0, 0, 0);
+    }
+    *(v4f*)&s_acc[wave][lane][0] = acc;
+    __syncthreads();
+    if (wave != 0) return;
+    v4f s = *(const v4f*)&s_acc[0][lane][0];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) {
+        const v4f o = *(const v4f*)&s_acc[w][lane][0];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s[i] = __fadd_rn(s[i], o[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) C[(size_t)(m0 + 4 * q + i) * ldc + n0 + row] = __fmul_rn(scale, s[i]);
+}
+
+struct AdamParams {
+    float lr, b1, b2, eps, ic1, ic2;  // ic = 1 / (1 - beta^t)
+};
+
+// One thread per parameter: the N x r values of L, then the r x K values of R.  The first wavefront of block 0 also
+// sums the loss partials (lane-strided, then a fixed shuffle tree).
+__global__ __launch_bounds__(256) void calib_adam_kernel(float* L, float* mL, float* vL, const float* gL, size_t nL, float* R,
+                                                         float* mR, float* vR, const float* gR, size_t nR, AdamParams a,
+                                                         const float* lp, int n_lp, float inv_count, float* loss)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx < nL + nR) {
+        const bool isL = idx < nL;
+        const size_t i = isL ? idx : idx - nL;
+        float* p = isL ? L : R;
+        float* m = isL ? mL : mR;
+        float* v = isL ? vL : vR;
+        const float g = isL ? gL[i] : gR[i];
+        const float mm = __fadd_rn(__fmul_rn(a.b1, m[i]), __fmul_rn(1.0f - a.b1, g));
+        const float vv = __fadd_rn(__fmul_rn(a.b2, v[i]), __fmul_rn(1.0f - a.b2, __fmul_rn(g, g)));
+        m[i] = mm;
+        v[i] = vv;
+        const float den = __fadd_rn(__fsqrt_rn(__fmul_rn(vv, a.ic2)), a.eps);
+        p[i] = __fsub_rn(p[i], __fdiv_rn(__fmul_rn(a.lr, __fmul_rn(mm, a.ic1)), den));
+    }
+    if (loss && blockIdx.x == 0 && threadIdx.x < 64) {
+        float s = 0.f;
+        for (int i = threadIdx.x; i < n_lp; i += 64) s = __fadd_rn(s, lp[i]);
+        s = wave_sum_f(s);
+        if (threadIdx.x == 0) *loss = __fmul_rn(s, inv_count);
+    }
+}
+
+__global__ __launch_bounds__(256) void calib_zero_kernel(float* p, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+
+hipError_t launch_calib_init(const Dims& d, const float* L, const float* R, uint8_t* state, hipStream_t s)
+{
+    const CalibLayout cl = calib_layout(d);
+    const size_t nl = (size_t)d.N * d.r * 4, nr = (size_t)d.r * d.K * 4;
+    hipError_t e = hipMemcpyAsync(state + cl.off_L, L, nl, hipMemcpyDeviceToDevice, s);
+    if (e != hipSuccess) return e;
+    e = hipMemcpyAsync(state + cl.off_R, R, nr, hipMemcpyDeviceToDevice, s);
+    if (e != hipSuccess) return e;
+    // moments start at zero (one contiguous range: mL, vL, mR, vR); a kernel, so that the call can be captured in a graph
+    const size_t nz = (cl.off_gL - cl.off_mL) / 4;
+    hipLaunchKernelGGL(calib_zero_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, s, (float*)(state + cl.off_mL), nz);
+    return hipGetLastError();
+}
+
+hipError_t launch_calib_step(const Dims& d, const float* W, uint8_t* state, int step, const lq_adam* ad, float* loss,
+                             hipStream_t s)
+{
+    const CalibLayout cl = calib_layout(d);
+    float* L = (float*)(state + cl.off_L);
+    float* R = (float*)(state + cl.off_R);
+    float* gL = (float*)(state + cl.off_gL);
+    float* gR = (float*)(state + cl.off_gR);
+    float* E = (float*)(state + cl.off_E);
+    float* lp = (float*)(state + cl.off_lp);
+    const int N = (int)d.N, K = (int)d.K, r = d.r;
+    const unsigned lds = (unsigned)(16 * r * sizeof(float));
+    const dim3 grid((unsigned)(N / 16)), block(256);
+    if (d.ga)
+        hipLaunchKernelGGL((calib_err_kernel<1, true>), grid, block, lds, s, W, L, R, E, lp, N, K, r);
+    else if (d.g == 64)
+        hipLaunchKernelGGL((calib_err_kernel<1, false>), grid, block, lds, s, W, L, R, E, lp, N, K, r);
+    else
+        hipLaunchKernelGGL((calib_err_kernel<2, false>), grid, block, lds, s, W, L, R, E, lp, N, K, r);
+    const float cg = (float)(-2.0 / ((double)N * (double)K));
+    // grad_L (N x r) = cg * E (N x K) . R^T       contraction over K
+    hipLaunchKernelGGL((gemm_nt_kernel<4>), dim3((unsigned)((N / 16) * (r / 16))), dim3(256), 0, s, E, K, R, K, gL, r, r / 16, K, cg);
+    // grad_R (r x K) = cg * L^T (r x N) . E (N x K)   contraction over N
+    hipLaunchKernelGGL((gemm_tn_kernel<16>), dim3((unsigned)((r / 16) * (K / 16))), dim3(1024), 0, s, L, r, E, K, gR, K, K / 16, N, cg);
+    AdamParams a;
+    a.lr = ad->lr;
+    a.b1 = ad->beta1;
+    a.b2 = ad->beta2;
+    a.eps = ad->eps;
+    a.ic1 = (float)(1.0 / (1.0 - pow((double)ad->beta1, (double)step)));
+    a.ic2 = (float)(1.0 / (1.0 - pow((double)ad->beta2, (double)step)));
+    const size_t nL = (size_t)N * r, nR = (size_t)r * K;
+    hipLaunchKernelGGL(calib_adam_kernel, dim3((unsigned)((nL + nR + 255) / 256)), dim3(256), 0, s, L, (float*)(state + cl.off_mL),
+                       (float*)(state + cl.off_vL), gL, nL, R, (float*)(state + cl.off_mR), (float*)(state + cl.off_vR), gR, nR,
+                       a, lp, cl.n_lp, (float)(1.0 / ((double)N * (double)K)), loss);
+    return hipGetLastError();
+}
+
+hipError_t launch_calib_unpack(const Dims& d, const uint8_t* state, const lq_calib_view* out, hipStream_t s)
+{
+    const CalibLayout cl = calib_layout(d);
+    const size_t nl = (size_t)d.N * d.r * 4, nr = (size_t)d.r * d.K * 4;
+    struct { float* dst; size_t off, bytes; } parts[] = {
+        {out->L, cl.off_L, nl},   {out->R, cl.off_R, nr},   {out->mL, cl.off_mL, nl}, {out->vL, cl.off_vL, nl},
+        {out->mR, cl.off_mR, nr}, {out->vR, cl.off_vR, nr}, {out->gL, cl.off_gL, nl}, {out->gR, cl.off_gR, nr},
+        {out->E, cl.off_E, (size_t)d.N * d.K * 4}};
+    for (auto& p : parts) {
+        if (!p.dst) continue;
+        hipError_t e = hipMemcpyAsync(p.dst, state + p.off, p.bytes, hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace lq

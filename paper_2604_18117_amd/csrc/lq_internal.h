@@ -140,6 +140,22 @@ hipError_t launch_quantize_act_mxi(const Dims& d, int x_dtype, const uint8_t* pa
 hipError_t launch_fwd_mxi(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M,
                           uint16_t* Y, int64_t ldy, const lq_fwd_debug* dbg, hipStream_t s);
 
+// Calibration state (lq_calib.hip): plain row-major fp32 sections, each 256-byte aligned.
+struct CalibLayout {
+    size_t off_L, off_R;       // factors, N x r and r x K
+    size_t off_mL, off_vL, off_mR, off_vR;  // Adam moments (contiguous, in this order)
+    size_t off_gL, off_gR;     // gradients of the last step
+    size_t off_E;              // N x K  deq(Q1(W + L R)) - (W + L R) of the last step
+    size_t off_lp;             // partial sums of E^2, one per wavefront
+    int n_lp;
+    size_t total;
+};
+CalibLayout calib_layout(const Dims& d);
+hipError_t launch_calib_init(const Dims& d, const float* L, const float* R, uint8_t* state, hipStream_t s);
+hipError_t launch_calib_step(const Dims& d, const float* W, uint8_t* state, int step, const lq_adam* ad, float* loss,
+                             hipStream_t s);
+hipError_t launch_calib_unpack(const Dims& d, const uint8_t* state, const lq_calib_view* out, hipStream_t s);
+
 // ---- device helpers ----------------------------------------------------------------------
 #if defined(__HIPCC__)
 __device__ __forceinline__ uint32_t nib_lo(uint32_t p) { return p & 0x87878787u; }

@@ -211,3 +211,33 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "single-GPU" in r.stderr
+
+
+def test_calibration_contract(lq):
+    raw = lq.raw()
+    n = C.c_size_t(0)
+    cfg = _cfg(lq)                                 # N 128, K 256, rank 32
+    assert raw.lq_calib_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_OK
+    # factors, two moments and a gradient per factor, the N x K error matrix, a loss partial per wavefront
+    nl, nr = 128 * 32 * 4, 32 * 256 * 4
+    parts = [nl, nr, nl, nl, nr, nr, nl, nr, 128 * 256 * 4, 128 // 16 * 4 * 4]
+    assert n.value == sum((x + 255) // 256 * 256 for x in parts)
+    assert raw.lq_calib_sizes(C.byref(_cfg(lq, family="mx")), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    assert raw.lq_calib_sizes(C.byref(_cfg(lq, family="mxi")), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    assert raw.lq_calib_sizes(C.byref(_cfg(lq, rank=0)), C.byref(n)) == lq.LQ_ERR_SHAPE
+    good, odd = C.c_void_p(1 << 20), C.c_void_p((1 << 20) + 4)
+    sb = lq.lq_calib_sizes(cfg)
+    ad = lq.lq_adam(1e-4, 0.9, 0.999, 1e-8)
+    assert raw.lq_calib_init(C.byref(cfg), None, good, good, sb, None) == lq.LQ_ERR_NULL
+    assert raw.lq_calib_init(C.byref(cfg), good, good, odd, sb, None) == lq.LQ_ERR_ALIGN
+    assert raw.lq_calib_init(C.byref(cfg), good, good, good, sb - 1, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert raw.lq_calib_step(C.byref(cfg), None, good, sb, 1, C.byref(ad), None, None) == lq.LQ_ERR_NULL
+    assert raw.lq_calib_step(C.byref(cfg), good, good, sb, 1, None, None, None) == lq.LQ_ERR_NULL
+    assert raw.lq_calib_step(C.byref(cfg), good, good, sb, 0, C.byref(ad), None, None) == lq.LQ_ERR_SHAPE
+    assert raw.lq_calib_step(C.byref(cfg), good, good, sb - 1, 1, C.byref(ad), None, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert raw.lq_calib_step(C.byref(cfg), good, odd, sb, 1, C.byref(ad), None, None) == lq.LQ_ERR_ALIGN
+    bad = lq.lq_adam(1e-4, 1.0, 0.999, 1e-8)       # beta1 must be below 1
+    assert raw.lq_calib_step(C.byref(cfg), good, good, sb, 1, C.byref(bad), None, None) == lq.LQ_ERR_UNSUPPORTED
+    bad = lq.lq_adam(0.0, 0.9, 0.999, 1e-8)
+    assert raw.lq_calib_step(C.byref(cfg), good, good, sb, 1, C.byref(bad), None, None) == lq.LQ_ERR_UNSUPPORTED
+    assert raw.lq_calib_unpack(C.byref(cfg), good, None, None) == lq.LQ_ERR_NULL
