@@ -30,6 +30,55 @@ def layer_ops(l):
     return 2.0 * l.M * l.N * l.K + 2.0 * l.M * l.r * l.K + 2.0 * l.M * l.N * l.r
 
 
+def bench_calib(args, layer, np, torch, lq, wl):
+    """K Adam steps of the factor optimisation (Eq. 4) on the layer's weight shape, SVD-free synthetic start
+    (the start does not change the work per step).  value = steps per second; the error kernel's roofline is HBM:
+    it reads W and writes the error matrix, 8 bytes per weight."""
+    assert layer.family == "int", "the calibration step covers the INT family's main quantiser"
+    _, W, L, R = wl.make_inputs(layer)
+    cfg = lq.config_for_layer(layer)
+    Wd = torch.from_numpy(W).cuda()
+    scale = np.float32(10.0)                       # factors of the size an SVD start would have
+    state = lq.lq_calib_init(cfg, torch.from_numpy(L * scale).cuda(), torch.from_numpy(R * scale).cuda())
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    t = 0
+    t_ramp = time.perf_counter()
+    while time.perf_counter() - t_ramp < args.ramp_seconds:
+        for _ in range(50):
+            t += 1
+            lq.lq_calib_step(cfg, Wd, state, t, loss=loss)
+        torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        t += 1
+        lq.lq_calib_step(cfg, Wd, state, t, loss=loss)
+    torch.cuda.synchronize()
+    K = args.steps
+    t0 = time.perf_counter()
+    for _ in range(K):
+        t += 1
+        lq.lq_calib_step(cfg, Wd, state, t, loss=loss)
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / K
+    N, Kd, r = layer.N, layer.K, layer.r
+    flops = 3 * 2.0 * N * Kd * r                   # W + L R, E R^T, L^T E
+    hbm = 8.0 * N * Kd                             # error kernel: W in, E out
+    out = {"metric": "data-free calibration (Eq. 4) Adam steps per second", "value": round(1e3 / ms_step, 1), "unit": "steps/s",
+           "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": round(ms_step, 5), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": layer.name + "_calib", "N": N, "K": Kd, "rank": r,
+                      "main": "SINT4 blocks" if layer.a_group == 64 else f"INT4 g{layer.g}", "launches_per_step": 4},
+           "work_per_step": {"flops": flops, "hbm_bytes_error_kernel": hbm, "loss": float(loss.item())}}
+    if args.oracle_seconds > 0:
+        from oracle import lq_ref
+        st = lq_ref.calib_init(L * scale, R * scale)
+        t0 = time.perf_counter()
+        lq_ref.calib_step(W, st, layer.g, sint4_blocks=layer.a_group == 64)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(1.0 / dt, 3), "unit": "steps/s", "cores": lq_ref.num_threads(), "kind": "oracle",
+                               "sample": "one full step of the same layer"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -41,6 +90,9 @@ def main():
     ap.add_argument("--workload", default="c2_qkv", help="layer name from workloads.LAYERS")
     ap.add_argument("--oracle-seconds", type=float, default=15.0, help="CPU budget of the oracle leg (0 = skip)")
     ap.add_argument("--sets", type=int, default=4, help="distinct buffer sets rotated through")
+    ap.add_argument("--calib", action="store_true",
+                    help="time the data-free calibration step (lq_calib_step) on the workload's weight shape instead "
+                         "of the per-call path; prints its own JSON line")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
                     help="only run a plain device-to-device copy of BYTES (calibrates the HBM byte counters)")
     args = ap.parse_args()
@@ -67,6 +119,8 @@ def main():
         print(json.dumps({"copy_probe_bytes": args.copy_probe, "copies": 3}))
         return
     layer = wl.LAYERS[args.workload]
+    if args.calib:
+        return bench_calib(args, layer, np, torch, lq, wl)
     X, W, L, R = wl.make_inputs(layer)
     cfg = lq.config_for_layer(layer)
     M = layer.M

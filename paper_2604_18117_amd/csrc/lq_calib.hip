@@ -27,17 +27,31 @@ CalibLayout calib_layout(const Dims& d)
     cl.off_gL = o; o = align256(o + nl);
     cl.off_gR = o; o = align256(o + nr);
     cl.off_E = o;  o = align256(o + (size_t)d.N * d.K * 4);
-    cl.n_lp = (int)(d.N / 16) * 4;  // one partial per wavefront of calib_err_kernel
+    cl.n_lp = (int)(d.N / 16) * ((d.G + 3) / 4) * 4;  // one partial per wavefront of calib_err_kernel
     cl.off_lp = o; o = align256(o + (size_t)cl.n_lp * 4);
     cl.total = o;
     return cl;
 }
 
+// Maximum over the 64 lanes, returned in every lane: four cross-lane steps inside each row of 16 lanes on the
+// vector ALU's data-parallel-primitive path (no LDS traffic), then the four row results through scalar registers.
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float v)
+{
+    const int o = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false);
+    return fmaxf(v, __int_as_float(o));
+}
 __device__ __forceinline__ float wave_max_f(float v)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
+    v = dpp_max<0xB1>(v);   // quad_perm [1,0,3,2]
+    v = dpp_max<0x4E>(v);   // quad_perm [2,3,0,1]
+    v = dpp_max<0x141>(v);  // row_half_mirror
+    v = dpp_max<0x140>(v);  // row_mirror
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 __device__ __forceinline__ float wave_sum_f(float v)
 {
@@ -46,40 +60,46 @@ __device__ __forceinline__ float wave_sum_f(float v)
     return v;
 }
 
-// A workgroup owns 16 rows of W; its 4 wavefronts take the K groups round-robin; lane = column within a 64-chunk.
+// A workgroup owns 16 rows of W and four consecutive K groups, one per wavefront; lane = column within a 64-chunk.
 // The 16 x r block of L sits in LDS (uniform-address reads broadcast), the r values of R for the lane's column(s)
-// stream through registers four rows of R at a time.
+// stream through registers four rows of R at a time.  Many small workgroups: the loop is a chain of L2 round
+// trips, hidden by occupancy.
 template <int GC, bool SINT4>
 __global__ __launch_bounds__(256) void calib_err_kernel(const float* W, const float* L, const float* R, float* E, float* lp,
                                                         int N, int K, int r)
 {
     extern __shared__ __attribute__((aligned(16))) float sL[];  // [16][r]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n0 = blockIdx.x * 16;
+    const int G = K / (64 * GC), GQ = (G + 3) / 4;
+    const int n0 = (blockIdx.x / GQ) * 16;
     for (int i = tid * 4; i < 16 * r; i += 256 * 4) *(v4f*)&sL[i] = *(const v4f*)&L[(size_t)n0 * r + i];
     __syncthreads();
-    const int G = K / (64 * GC);
     float lsum = 0.f;
-    for (int g = wave; g < G; g += 4) {
+    const int g = (blockIdx.x % GQ) * 4 + wave;
+    if (g < G) {
         const int col0 = g * GC * 64 + lane;
         float v[16][GC];
 #pragma unroll
         for (int row = 0; row < 16; ++row)
 #pragma unroll
             for (int c = 0; c < GC; ++c) v[row][c] = W[(size_t)(n0 + row) * K + col0 + c * 64];
-        for (int j = 0; j < r; j += 4) {
-            float rj[4][GC];
+        // 16 rows of R at a time: all their loads are in flight together (one L2 round trip per 16 rank indices)
+        for (int j = 0; j < r; j += 16) {
+            float rj[16][GC];
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
+            for (int jj = 0; jj < 16; ++jj)
 #pragma unroll
                 for (int c = 0; c < GC; ++c) rj[jj][c] = R[(size_t)(j + jj) * K + col0 + c * 64];
 #pragma unroll
             for (int row = 0; row < 16; ++row) {
-                const v4f l4 = *(const v4f*)&sL[row * r + j];
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj)
+                for (int j4 = 0; j4 < 16; j4 += 4) {
+                    const v4f l4 = *(const v4f*)&sL[row * r + j + j4];
 #pragma unroll
-                    for (int c = 0; c < GC; ++c) v[row][c] = __builtin_fmaf(l4[jj], rj[jj][c], v[row][c]);
+                    for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                        for (int c = 0; c < GC; ++c) v[row][c] = __builtin_fmaf(l4[jj], rj[j4 + jj][c], v[row][c]);
+                }
             }
         }
 #pragma unroll
@@ -91,12 +111,10 @@ __global__ __launch_bounds__(256) void calib_err_kernel(const float* W, const fl
             float s, inv;
             if constexpr (SINT4) {
                 s = f16_bits_value(sint4_scale(a, &inv));
-            } else if (a == 0.0f) {
-                s = 1.0f;
-                inv = 1.0f;
-            } else {
-                s = __fdiv_rn(a, 7.0f);
-                inv = __fdiv_rn(7.0f, a);
+            } else {  // branch-free: an all-zero group takes scale 1
+                const float sd = __fdiv_rn(a, 7.0f), id = __fdiv_rn(7.0f, a);
+                s = a == 0.0f ? 1.0f : sd;
+                inv = a == 0.0f ? 1.0f : id;
             }
 #pragma unroll
             for (int c = 0; c < GC; ++c) {
@@ -128,6 +146,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nt_kernel(const float* A, int
     v4f acc = {0.f, 0.f, 0.f, 0.f};
     const float* ap = A + (size_t)(m0 + row) * lda + 4 * q;
     const float* bp = B + (size_t)(n0 + row) * ldb + 4 * q;
+#pragma unroll 4
     for (int kk = wave * 16; kk < Kc; kk += WAVES * 16) {
         const v4f a4 = *(const v4f*)(ap + kk);
         const v4f b4 = *(const v4f*)(bp + kk);
@@ -158,6 +177,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tn_kernel(const float* A, int
     const int row = lane & 15, q = lane >> 4;
     const int m0 = (blockIdx.x / tilesN) * 16, n0 = (blockIdx.x % tilesN) * 16;
     v4f acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
     for (int kk = wave * 16; kk < Kc; kk += WAVES * 16) {
         float a4[4], b4[4];
 #pragma unroll
@@ -186,8 +206,8 @@ struct AdamParams {
     float lr, b1, b2, eps, ic1, ic2;  // ic = 1 / (1 - beta^t)
 };
 
-// One thread per parameter: the N x r values of L, then the r x K values of R.  The first wavefront of block 0 also
-// sums the loss partials (lane-strided, then a fixed shuffle tree).
+// One thread per parameter: the N x r values of L, then the r x K values of R.  Block 0 also sums the loss partials
+// (thread-strided, a fixed shuffle tree per wavefront, then the four wavefronts in order).
 __global__ __launch_bounds__(256) void calib_adam_kernel(float* L, float* mL, float* vL, const float* gL, size_t nL, float* R,
                                                          float* mR, float* vR, const float* gR, size_t nR, AdamParams a,
                                                          const float* lp, int n_lp, float inv_count, float* loss)
@@ -207,11 +227,16 @@ __global__ __launch_bounds__(256) void calib_adam_kernel(float* L, float* mL, fl
         const float den = __fadd_rn(__fsqrt_rn(__fmul_rn(vv, a.ic2)), a.eps);
         p[i] = __fsub_rn(p[i], __fdiv_rn(__fmul_rn(a.lr, __fmul_rn(mm, a.ic1)), den));
     }
-    if (loss && blockIdx.x == 0 && threadIdx.x < 64) {
+    if (loss && blockIdx.x == 0) {  // block-uniform
+        __shared__ float s_part[4];
         float s = 0.f;
-        for (int i = threadIdx.x; i < n_lp; i += 64) s = __fadd_rn(s, lp[i]);
+#pragma unroll 8
+        for (int i = threadIdx.x; i < n_lp; i += 256) s = __fadd_rn(s, lp[i]);
         s = wave_sum_f(s);
-        if (threadIdx.x == 0) *loss = __fmul_rn(s, inv_count);
+        if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = s;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            *loss = __fmul_rn(__fadd_rn(__fadd_rn(s_part[0], s_part[1]), __fadd_rn(s_part[2], s_part[3])), inv_count);
     }
 }
 
@@ -247,7 +272,7 @@ hipError_t launch_calib_step(const Dims& d, const float* W, uint8_t* state, int 
     float* lp = (float*)(state + cl.off_lp);
     const int N = (int)d.N, K = (int)d.K, r = d.r;
     const unsigned lds = (unsigned)(16 * r * sizeof(float));
-    const dim3 grid((unsigned)(N / 16)), block(256);
+    const dim3 grid((unsigned)((N / 16) * ((d.G + 3) / 4))), block(256);
     if (d.ga)
         hipLaunchKernelGGL((calib_err_kernel<1, true>), grid, block, lds, s, W, L, R, E, lp, N, K, r);
     else if (d.g == 64)
@@ -256,7 +281,7 @@ hipError_t launch_calib_step(const Dims& d, const float* W, uint8_t* state, int 
         hipLaunchKernelGGL((calib_err_kernel<2, false>), grid, block, lds, s, W, L, R, E, lp, N, K, r);
     const float cg = (float)(-2.0 / ((double)N * (double)K));
     // grad_L (N x r) = cg * E (N x K) . R^T       contraction over K
-    hipLaunchKernelGGL((gemm_nt_kernel<4>), dim3((unsigned)((N / 16) * (r / 16))), dim3(256), 0, s, E, K, R, K, gL, r, r / 16, K, cg);
+    hipLaunchKernelGGL((gemm_nt_kernel<8>), dim3((unsigned)((N / 16) * (r / 16))), dim3(512), 0, s, E, K, R, K, gL, r, r / 16, K, cg);
     // grad_R (r x K) = cg * L^T (r x N) . E (N x K)   contraction over N
     hipLaunchKernelGGL((gemm_tn_kernel<16>), dim3((unsigned)((r / 16) * (K / 16))), dim3(1024), 0, s, L, r, E, K, gR, K, K / 16, N, cg);
     AdamParams a;

@@ -220,7 +220,7 @@ def test_calibration_contract(lq):
     assert raw.lq_calib_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_OK
     # factors, two moments and a gradient per factor, the N x K error matrix, a loss partial per wavefront
     nl, nr = 128 * 32 * 4, 32 * 256 * 4
-    parts = [nl, nr, nl, nl, nr, nr, nl, nr, 128 * 256 * 4, 128 // 16 * 4 * 4]
+    parts = [nl, nr, nl, nl, nr, nr, nl, nr, 128 * 256 * 4, 128 // 16 * 1 * 4 * 4]   # K 256: 4 groups = one workgroup column
     assert n.value == sum((x + 255) // 256 * 256 for x in parts)
     assert raw.lq_calib_sizes(C.byref(_cfg(lq, family="mx")), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
     assert raw.lq_calib_sizes(C.byref(_cfg(lq, family="mxi")), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
