@@ -189,8 +189,8 @@ lq_status lq_unpack_act(const lq_config *cfg, const void *act, int64_t M, const 
    The step that produces the L and R the forward consumes: gradient descent with Adam on
        loss(L, R) = mean over N x K of ( Q1(W + L R) - W - L R )^2 ,
    the rounding treated as having zero derivative, so that grad_L = -2/(N K) E R^T and grad_R = -2/(N K) L^T E with
-   E = Q1(W + L R) - W - L R.  Q1 is cfg's main weight quantiser; INT family only (LQ_ERR_UNSUPPORTED otherwise);
-   rank >= 16.  W + L R is formed in fp32 (W, then one fused multiply-add per rank index, ascending).
+   E = Q1(W + L R) - W - L R.  Q1 is cfg's main weight quantiser (INT4 groups, SINT4 blocks, MXFP4 or MXINT4; the
+   branch formats of cfg play no part); rank >= 16.  W + L R is formed in fp32 (W, then one fused multiply-add per rank index, ascending).
    Sign: the factors follow the paper, Q1(W + L R) - W ~ L R, and the paper starts them at L = -L0, R = R0 with L0 R0
    the best rank-r approximation of W (an input here: the singular value decomposition is the caller's).  lq_pack_weights
    forms W - L' R', so it takes L' = -L, R' = R.

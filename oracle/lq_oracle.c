@@ -975,7 +975,8 @@ LQO_API void lqo_fwd_mxb6(int64_t M, int64_t N, int64_t K, int r, const uint8_t 
 
 /* One Adam step on   loss(L, R) = mean_{n,k} ( Q1(W + L R) - W - L R )^2   (Eq. 4 with the Mean Squared
    Error loss).  Orientation as everywhere here: W is N x K, L is N x r, R is r x K (the paper's
-   W^T, R^T, L^T); Q1 quantises W + L R along K in groups of g (fp32 scales) or in SINT4 blocks.
+   W^T, R^T, L^T); Q1 quantises W + L R along K: q1 = 0 INT4 in groups of g with fp32 scales, 1 SINT4 blocks,
+   2 MXFP4, 3 MXINT4 (blocks of 32, E8M0 scale; g is ignored for 1..3).
    Readings:
      - the point V = W + L R at which Q1 is evaluated is an fp32 number: v = W[n,k], then
        v = fma(L[n,j], R[j,k], v) for ascending j (the quantised codes depend on V's rounding, so the
@@ -989,11 +990,13 @@ LQO_API void lqo_fwd_mxb6(int64_t M, int64_t N, int64_t K, int r, const uint8_t 
        stored in fp32; one step's arithmetic is done in fp64 and rounded once per stored value.
    In/out: L, R, mL, vL, mR, vR.  Out (each optional): E N x K, gL N x r, gR r x K, *loss (before the
    update). */
-LQO_API void lqo_calib_step(int64_t N, int64_t K, int r, int g, int sint4_blocks, const float *W, float *L,
+LQO_API void lqo_calib_step(int64_t N, int64_t K, int r, int g, int q1, const float *W, float *L,
                             float *R, float *mL, float *vL, float *mR, float *vR, int step, double lr,
                             double b1, double b2, double eps, float *E_out, float *gL_out, float *gR_out,
                             double *loss_out)
 {
+    if (q1 == 1) g = 64;
+    if (q1 >= 2) g = 32;
     const int64_t G = K / g;
     float *E = (float *)malloc(sizeof(float) * (size_t)(N * K));
     float *gL = (float *)malloc(sizeof(float) * (size_t)(N * (r > 0 ? r : 1)));
@@ -1010,13 +1013,27 @@ LQO_API void lqo_calib_step(int64_t N, int64_t K, int r, int g, int sint4_blocks
             for (int j = 0; j < r; ++j) v = fmaf(L[n * r + j], R[(int64_t)j * K + k], v);
             V[k] = v;
         }
-        if (sint4_blocks)
-            lqo_quant_sint4(V, K, q, sc);
-        else
-            for (int64_t gi = 0; gi < G; ++gi) lqo_quant_int(V + gi * g, g, 7, q + gi * g, &sc[gi]);
-        for (int64_t k = 0; k < K; ++k) {
-            float deq = (float)q[k] * sc[k / g];
-            E[n * K + k] = deq - V[k];
+        if (q1 >= 2) { /* element value times the block's power of two: exact in fp32 */
+            uint8_t *eb = (uint8_t *)malloc((size_t)G);
+            if (q1 == 2)
+                lqo_quant_mxfp4(V, K, (uint8_t *)q, eb);
+            else
+                lqo_quant_mxint(V, K, 4, q, eb);
+            for (int64_t k = 0; k < K; ++k) {
+                float deq = q1 == 2 ? lqo_e2m1_decode((uint8_t)q[k]) * (float)lqo_e8m0_decode(eb[k / 32])
+                                    : (float)mxint_value(q[k], eb[k / 32], 4);
+                E[n * K + k] = deq - V[k];
+            }
+            free(eb);
+        } else {
+            if (q1 == 1)
+                lqo_quant_sint4(V, K, q, sc);
+            else
+                for (int64_t gi = 0; gi < G; ++gi) lqo_quant_int(V + gi * g, g, 7, q + gi * g, &sc[gi]);
+            for (int64_t k = 0; k < K; ++k) {
+                float deq = (float)q[k] * sc[k / g];
+                E[n * K + k] = deq - V[k];
+            }
         }
         free(V);
         free(q);

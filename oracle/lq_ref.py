@@ -531,9 +531,16 @@ class CalibOut:
     gR: np.ndarray       # r x K
 
 
+Q1_KINDS = {"int": 0, "sint4": 1, "mxfp4": 2, "mxint4": 3}
+
+
 def calib_step(W, st: CalibState, g: int = 64, sint4_blocks: bool = False, lr: float = 1e-4, beta1: float = 0.9,
-               beta2: float = 0.999, eps: float = 1e-8) -> CalibOut:
-    """One Adam step; updates `st` in place and returns the loss / error / gradients it was computed from."""
+               beta2: float = 0.999, eps: float = 1e-8, q1: Optional[str] = None) -> CalibOut:
+    """One Adam step; updates `st` in place and returns the loss / error / gradients it was computed from.
+    q1: main quantiser, "int" (groups of g, fp32 scales; the default), "sint4", "mxfp4" or "mxint4"."""
+    kind = Q1_KINDS[q1] if q1 is not None else (1 if sint4_blocks else 0)
+    if kind:
+        g = 64 if kind == 1 else 32
     W = _f32(W)
     N, K = W.shape
     r = st.L.shape[1]
@@ -541,7 +548,7 @@ def calib_step(W, st: CalibState, g: int = 64, sint4_blocks: bool = False, lr: f
     st.step += 1
     out = CalibOut(0.0, np.empty((N, K), np.float32), np.empty((N, r), np.float32), np.empty((r, K), np.float32))
     loss = C.c_double(0.0)
-    lib().lqo_calib_step(C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(g), C.c_int(1 if sint4_blocks else 0), _p(W),
+    lib().lqo_calib_step(C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(g), C.c_int(kind), _p(W),
                          _p(st.L), _p(st.R), _p(st.mL), _p(st.vL), _p(st.mR), _p(st.vR), C.c_int(st.step),
                          C.c_double(lr), C.c_double(beta1), C.c_double(beta2), C.c_double(eps), _p(out.E), _p(out.gL),
                          _p(out.gR), C.byref(loss))

@@ -161,9 +161,11 @@ def lq_act_sizes(cfg: lq_config, M: int) -> int:
 def lq_pack_weights(cfg: lq_config, W: torch.Tensor, L: Optional[torch.Tensor], R: Optional[torch.Tensor],
                     packed: Optional[torch.Tensor] = None) -> torch.Tensor:
     """W (N x K), L (N x r), R (r x K): fp32 CUDA tensors, contiguous.  Returns the packed blob."""
-    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous()
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and tuple(W.shape) == (cfg.N, cfg.K)
     for t in (L, R):
         assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous())
+    if cfg.rank:  # the library reads N x r and r x K values: the tensors must hold them
+        assert tuple(L.shape) == (cfg.N, cfg.rank) and tuple(R.shape) == (cfg.rank, cfg.K), "factor shapes must match cfg"
     if packed is None:
         packed = torch.empty(lq_packed_sizes(cfg), dtype=torch.uint8, device=W.device)
     _check(_lib.lq_pack_weights(C.byref(cfg), _ptr(W), _ptr(L), _ptr(R), _ptr(packed), packed.numel(),
@@ -184,8 +186,9 @@ def lq_quantize_act(cfg: lq_config, packed: torch.Tensor, X: torch.Tensor, act: 
                     debug: bool = False):
     """X: M x K CUDA tensor (fp32 or bf16, row stride may exceed K).  Returns the activation blob
     (and the parity taps when debug=True)."""
-    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1 and X.shape[1] == cfg.K
     assert X.dtype == (torch.bfloat16 if cfg.x_dtype == LQ_BF16 else torch.float32)
+    assert packed is None or packed.numel() >= lq_packed_sizes(cfg)
     M = X.shape[0]
     if act is None:
         act = torch.empty(lq_act_sizes(cfg, M), dtype=torch.uint8, device=X.device)
@@ -306,6 +309,7 @@ def lq_calib_init(cfg: lq_config, L: torch.Tensor, R: torch.Tensor, state: Optio
     """L (N x r), R (r x K): fp32 CUDA, contiguous (paper's sign: Q1(W + L R) - W ~ L R).  Returns the state blob."""
     for t in (L, R):
         assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+    assert tuple(L.shape) == (cfg.N, cfg.rank) and tuple(R.shape) == (cfg.rank, cfg.K), "factor shapes must match cfg"
     if state is None:
         state = torch.empty(lq_calib_sizes(cfg), dtype=torch.uint8, device=L.device)
     _check(_lib.lq_calib_init(C.byref(cfg), _ptr(L), _ptr(R), _ptr(state), state.numel(), C.c_void_p(_stream())),
@@ -316,7 +320,7 @@ def lq_calib_init(cfg: lq_config, L: torch.Tensor, R: torch.Tensor, state: Optio
 def lq_calib_step(cfg: lq_config, W: torch.Tensor, state: torch.Tensor, step: int, lr: float = 1e-4, beta1: float = 0.9,
                   beta2: float = 0.999, eps: float = 1e-8, loss: Optional[torch.Tensor] = None) -> None:
     """One Adam step (step counts from 1); `loss`: optional 1-element fp32 CUDA tensor that receives the loss before the update."""
-    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous()
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and tuple(W.shape) == (cfg.N, cfg.K)
     ad = lq_adam(lr, beta1, beta2, eps)
     _check(_lib.lq_calib_step(C.byref(cfg), _ptr(W), _ptr(state), state.numel(), step, C.byref(ad), _ptr(loss),
                               C.c_void_p(_stream())), "lq_calib_step")

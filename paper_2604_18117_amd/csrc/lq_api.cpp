@@ -272,7 +272,6 @@ static lq_status calib_dims(const lq_config* cfg, Dims* d)
 {
     lq_status st = make_dims(cfg, d);
     if (st != LQ_OK) return st;
-    if (d->mx || d->mxi) return LQ_ERR_UNSUPPORTED;  // the calibration step knows the INT family's main quantiser
     if (d->r < 16) return LQ_ERR_SHAPE;
     return LQ_OK;
 }

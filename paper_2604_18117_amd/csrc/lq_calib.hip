@@ -1,7 +1,7 @@
 // Data-free calibration of the low-rank factors (Section 3.2, Eq. 4; gradients of App. B.2): one Adam step on
 //     loss(L, R) = mean ( Q1(W + L R) - W - L R )^2
-// for the INT family's main quantiser Q1 (INT4 in groups of 64 | 128 along K with fp32 scales, or SINT4 blocks with
-// FP16 scales).  Four launches per step:
+// for the main quantiser Q1 of the configuration: INT4 in groups of 64 | 128 along K with fp32 scales, SINT4 blocks with
+// FP16 scales, MXFP4 or MXINT4 (blocks of 32, E8M0 scale).  Four launches per step:
 //   calib_err_kernel   V = W + L R (fp32 FMA chain over ascending j), E = deq(Q1(V)) - V, partial sums of E^2
 //   gemm_nt_kernel     grad_L = -2/(N K) E R^T      (fp32 MFMA, contraction split over the wavefronts of a workgroup)
 //   gemm_tn_kernel     grad_R = -2/(N K) L^T E
@@ -12,6 +12,9 @@
 namespace lq {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+
+// column groups a wavefront of calib_err_kernel owns one of: the INT scale groups, or 64-chunks (two MX blocks)
+static int calib_groups(const Dims& d) { return (d.mx || d.mxi) ? d.C64 : d.G; }
 
 CalibLayout calib_layout(const Dims& d)
 {
@@ -27,7 +30,7 @@ CalibLayout calib_layout(const Dims& d)
     cl.off_gL = o; o = align256(o + nl);
     cl.off_gR = o; o = align256(o + nr);
     cl.off_E = o;  o = align256(o + (size_t)d.N * d.K * 4);
-    cl.n_lp = (int)(d.N / 16) * ((d.G + 3) / 4) * 4;  // one partial per wavefront of calib_err_kernel
+    cl.n_lp = (int)(d.N / 16) * ((calib_groups(d) + 3) / 4) * 4;  // one partial per wavefront of calib_err_kernel
     cl.off_lp = o; o = align256(o + (size_t)cl.n_lp * 4);
     cl.total = o;
     return cl;
@@ -41,7 +44,9 @@ __device__ __forceinline__ float dpp_max(float v)
     const int o = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false);
     return fmaxf(v, __int_as_float(o));
 }
-__device__ __forceinline__ float wave_max_f(float v)
+// HALF = false: maximum over the wavefront; HALF = true: over the lane's half (lanes 0..31 | 32..63 = one MX block)
+template <bool HALF>
+__device__ __forceinline__ float wave_max_f(float v, int lane)
 {
     v = dpp_max<0xB1>(v);   // quad_perm [1,0,3,2]
     v = dpp_max<0x4E>(v);   // quad_perm [2,3,0,1]
@@ -51,7 +56,30 @@ __device__ __forceinline__ float wave_max_f(float v)
     const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
     const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
     const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    if constexpr (HALF) return lane < 32 ? fmaxf(r0, r1) : fmaxf(r2, r3);
     return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
+// MX block scales and elements (App. A.3), the arithmetic of the MX pack kernels:
+// MXFP4: scale byte floor(log2 amax) - 2 + 127 clamped at 0; E2M1 element by the hardware converter (nearest even, saturating)
+__device__ __forceinline__ uint32_t mxfp4_scale_byte(float amax)
+{
+    const int e = (int)((__float_as_uint(amax) >> 23) & 0xFFu) - 2;
+    return (amax == 0.0f || e < 0) ? 0u : (uint32_t)e;
+}
+__device__ __forceinline__ float e8m0_as_float(uint32_t E) { return E ? __uint_as_float(E << 23) : __uint_as_float(0x00400000u); }
+__device__ __forceinline__ float e2m1_value(uint32_t c)  // 1 sign, 2 exponent (bias 1), 1 mantissa bit
+{
+    const uint32_t m = c & 7u;
+    const float mag = m < 2u ? 0.5f * (float)m : ldexpf(1.0f + 0.5f * (float)(m & 1u), (int)(m >> 1) - 1);
+    return (c & 8u) ? -mag : mag;
+}
+// MXINT4: shared exponent = the fp32 exponent field of amax; code = clamp(rne(v 2^(2 - s)), -7, 7), value = code 2^(s - 2)
+__device__ __forceinline__ float mxint4_round(float v, uint32_t field)
+{
+    const int s = (int)field - 127;
+    const float q = fminf(fmaxf(rintf(ldexpf(v, 2 - s)), -7.0f), 7.0f);
+    return ldexpf(q, s - 2);
 }
 __device__ __forceinline__ float wave_sum_f(float v)
 {
@@ -64,7 +92,8 @@ __device__ __forceinline__ float wave_sum_f(float v)
 // The 16 x r block of L sits in LDS (uniform-address reads broadcast), the r values of R for the lane's column(s)
 // stream through registers four rows of R at a time.  Many small workgroups: the loop is a chain of L2 round
 // trips, hidden by occupancy.
-template <int GC, bool SINT4>
+// Q: 0 INT4 groups of 64 * GC (fp32 scale), 1 SINT4 blocks, 2 MXFP4, 3 MXINT4 (1..3: GC = 1; 2, 3: two blocks of 32 per wavefront).
+template <int GC, int Q>
 __global__ __launch_bounds__(256) void calib_err_kernel(const float* W, const float* L, const float* R, float* E, float* lp,
                                                         int N, int K, int r)
 {
@@ -107,20 +136,35 @@ __global__ __launch_bounds__(256) void calib_err_kernel(const float* W, const fl
             float a = 0.f;
 #pragma unroll
             for (int c = 0; c < GC; ++c) a = fmaxf(a, fabsf(v[row][c]));
-            a = wave_max_f(a);
-            float s, inv;
-            if constexpr (SINT4) {
+            a = wave_max_f<(Q >= 2)>(a, lane);
+            float s = 1.0f, inv = 1.0f;
+            uint32_t eb = 0u;
+            if constexpr (Q == 1) {
                 s = f16_bits_value(sint4_scale(a, &inv));
-            } else {  // branch-free: an all-zero group takes scale 1
+            } else if constexpr (Q == 0) {  // branch-free: an all-zero group takes scale 1
                 const float sd = __fdiv_rn(a, 7.0f), id = __fdiv_rn(7.0f, a);
                 s = a == 0.0f ? 1.0f : sd;
                 inv = a == 0.0f ? 1.0f : id;
+            } else if constexpr (Q == 2) {
+                eb = mxfp4_scale_byte(a);
+                s = e8m0_as_float(eb);
+            } else {
+                eb = (__float_as_uint(a) >> 23) & 0xFFu;
             }
 #pragma unroll
             for (int c = 0; c < GC; ++c) {
-                float q = rintf(__fmul_rn(v[row][c], inv));
-                q = fminf(fmaxf(q, -7.0f), 7.0f);
-                const float e = __fsub_rn(__fmul_rn(q, s), v[row][c]);
+                float deq;
+                if constexpr (Q <= 1) {
+                    float q = rintf(__fmul_rn(v[row][c], inv));
+                    q = fminf(fmaxf(q, -7.0f), 7.0f);
+                    deq = __fmul_rn(q, s);
+                } else if constexpr (Q == 2) {
+                    const uint32_t code = a != 0.0f ? (__builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, v[row][c], 0.0f, s, 0) & 0xFu) : 0u;
+                    deq = __fmul_rn(e2m1_value(code), s);
+                } else {
+                    deq = mxint4_round(v[row][c], eb);
+                }
+                const float e = __fsub_rn(deq, v[row][c]);
                 E[(size_t)(n0 + row) * K + col0 + c * 64] = e;
                 lsum = __fadd_rn(lsum, __fmul_rn(e, e));
             }
@@ -272,13 +316,17 @@ hipError_t launch_calib_step(const Dims& d, const float* W, uint8_t* state, int 
     float* lp = (float*)(state + cl.off_lp);
     const int N = (int)d.N, K = (int)d.K, r = d.r;
     const unsigned lds = (unsigned)(16 * r * sizeof(float));
-    const dim3 grid((unsigned)((N / 16) * ((d.G + 3) / 4))), block(256);
-    if (d.ga)
-        hipLaunchKernelGGL((calib_err_kernel<1, true>), grid, block, lds, s, W, L, R, E, lp, N, K, r);
+    const dim3 grid((unsigned)((N / 16) * ((calib_groups(d) + 3) / 4))), block(256);
+    if (d.mxi)
+        hipLaunchKernelGGL((calib_err_kernel<1, 3>), grid, block, lds, s, W, L, R, E, lp, N, K, r);
+    else if (d.mx)
+        hipLaunchKernelGGL((calib_err_kernel<1, 2>), grid, block, lds, s, W, L, R, E, lp, N, K, r);
+    else if (d.ga)
+        hipLaunchKernelGGL((calib_err_kernel<1, 1>), grid, block, lds, s, W, L, R, E, lp, N, K, r);
     else if (d.g == 64)
-        hipLaunchKernelGGL((calib_err_kernel<1, false>), grid, block, lds, s, W, L, R, E, lp, N, K, r);
+        hipLaunchKernelGGL((calib_err_kernel<1, 0>), grid, block, lds, s, W, L, R, E, lp, N, K, r);
     else
-        hipLaunchKernelGGL((calib_err_kernel<2, false>), grid, block, lds, s, W, L, R, E, lp, N, K, r);
+        hipLaunchKernelGGL((calib_err_kernel<2, 0>), grid, block, lds, s, W, L, R, E, lp, N, K, r);
     const float cg = (float)(-2.0 / ((double)N * (double)K));
     // grad_L (N x r) = cg * E (N x K) . R^T       contraction over K
     hipLaunchKernelGGL((gemm_nt_kernel<8>), dim3((unsigned)((N / 16) * (r / 16))), dim3(512), 0, s, E, K, R, K, gL, r, r / 16, K, cg);

@@ -222,8 +222,9 @@ def test_calibration_contract(lq):
     nl, nr = 128 * 32 * 4, 32 * 256 * 4
     parts = [nl, nr, nl, nl, nr, nr, nl, nr, 128 * 256 * 4, 128 // 16 * 1 * 4 * 4]   # K 256: 4 groups = one workgroup column
     assert n.value == sum((x + 255) // 256 * 256 for x in parts)
-    assert raw.lq_calib_sizes(C.byref(_cfg(lq, family="mx")), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
-    assert raw.lq_calib_sizes(C.byref(_cfg(lq, family="mxi")), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    for fam in ("mx", "mxi"):                       # K 256 = four 64-chunks: the same workgroup grid, the same size
+        m = C.c_size_t(0)
+        assert raw.lq_calib_sizes(C.byref(_cfg(lq, family=fam)), C.byref(m)) == lq.LQ_OK and m.value == n.value
     assert raw.lq_calib_sizes(C.byref(_cfg(lq, rank=0)), C.byref(n)) == lq.LQ_ERR_SHAPE
     good, odd = C.c_void_p(1 << 20), C.c_void_p((1 << 20) + 4)
     sb = lq.lq_calib_sizes(cfg)

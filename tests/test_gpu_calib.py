@@ -24,7 +24,15 @@ def _problem(N, K, r, seed):
 
 
 def _cfg(N, K, r, g, sint4):
+    if g == 32:                                   # sint4 names the MX main format here: "mxfp4" | "mxint4"
+        return lq.make_config(N, K, r, "mx" if sint4 == "mxfp4" else "mxi", 32, 8, 8)
     return lq.make_config(N, K, r, "int", g, 8, 8, a_group=64 if sint4 else 0)
+
+
+def _orc_step(oracle, W, st, g, sint4, lr):
+    if g == 32:
+        return oracle.calib_step(W, st, q1=sint4, lr=lr)
+    return oracle.calib_step(W, st, g, sint4_blocks=sint4, lr=lr)
 
 
 def _n(t):
@@ -36,7 +44,7 @@ def _check_step(oracle, cfg, W, Wd, state, st, step, lr, g, sint4):
     L_before, R_before = st.L.copy(), st.R.copy()
     loss = torch.zeros(1, dtype=torch.float32, device="cuda")
     lq.lq_calib_step(cfg, Wd, state, step, lr=lr, loss=loss)
-    out = oracle.calib_step(W, st, g, sint4_blocks=sint4, lr=lr)
+    out = _orc_step(oracle, W, st, g, sint4, lr)
     got = lq.lq_calib_unpack(cfg, state, ("L", "R", "gL", "gR", "E"))
     torch.cuda.synchronize()
     N, K = W.shape
@@ -47,7 +55,8 @@ def _check_step(oracle, cfg, W, Wd, state, st, step, lr, g, sint4):
 
 
 @pytest.mark.parametrize("N,K,r,g,sint4", [(128, 256, 16, 64, False), (192, 384, 32, 128, False), (64, 1152, 64, 64, True),
-                                           (320, 128, 128, 64, False)])
+                                           (320, 128, 128, 64, False), (128, 384, 32, 32, "mxfp4"), (192, 256, 64, 32, "mxint4"),
+                                           (128, 1152, 96, 32, "mxint4")])
 def test_first_step_matches_oracle(oracle, N, K, r, g, sint4):
     W, L, R = _problem(N, K, r, seed=N + K)
     cfg = _cfg(N, K, r, g, sint4)
@@ -76,20 +85,21 @@ def test_first_step_matches_oracle(oracle, N, K, r, g, sint4):
     assert np.allclose(_n(a["mL"]), 0.1 * _n(a["gL"]), rtol=1e-6, atol=0)   # first moments after one step: (1 - beta1) g
 
 
-def test_trajectory_matches_oracle(oracle):
-    N, K, r, g = 128, 256, 16, 64
+@pytest.mark.parametrize("g,kind,lr", [(64, False, 1e-4), (32, "mxfp4", 1e-3)])
+def test_trajectory_matches_oracle(oracle, g, kind, lr):
+    N, K, r = 128, 256, 16
     W, L, R = _problem(N, K, r, seed=5)
-    cfg = _cfg(N, K, r, g, False)
+    cfg = _cfg(N, K, r, g, kind)
     Wd = torch.from_numpy(W).cuda()
     state = lq.lq_calib_init(cfg, torch.from_numpy(L).cuda(), torch.from_numpy(R).cuda())
     st = oracle.calib_init(L, R)
-    lr, steps = 1e-4, 40
+    steps = 40
     loss = torch.zeros(1, dtype=torch.float32, device="cuda")
     lg, lo = [], []
     for t in range(1, steps + 1):
         lq.lq_calib_step(cfg, Wd, state, t, lr=lr, loss=loss)
         lg.append(float(loss.item()))
-        lo.append(oracle.calib_step(W, st, g, lr=lr).loss)
+        lo.append(_orc_step(oracle, W, st, g, kind, lr).loss)
     assert np.allclose(lg, lo, rtol=1e-3)
     assert lg[-1] < 0.97 * lg[0]                                 # the optimisation lowers the loss of the SVD start
     got = lq.lq_calib_unpack(cfg, state)

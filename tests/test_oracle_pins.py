@@ -373,6 +373,35 @@ def _calib_problem(oracle, seed=31, N=48, K=256, r=8):
     return W, -L0, R0                                             # the paper starts from L = -L0, R = R0
 
 
+@pytest.mark.parametrize("q1", ["mxfp4", "mxint4"])
+def test_calib_error_mx_quantisers(oracle, q1):
+    # E = Q1(V) - V for the block-32 / E8M0 formats: E + V is an element value times the block's power of two, the
+    # one the (already pinned) block quantiser picks for the fp32 V
+    W, L, R = _calib_problem(oracle)
+    N, K = W.shape
+    st = oracle.calib_init(L, R)
+    out = oracle.calib_step(W, st, q1=q1)
+    V = W.astype(np.float64) + L.astype(np.float64) @ R.astype(np.float64)
+    grid = np.array(sorted(set(abs(v) for v in oracle.e2m1_decode(np.arange(16))))) if q1 == "mxfp4" else np.arange(8) / 4.0
+    for n in (0, 11, N - 1):
+        for b in range(K // 32):
+            sl = slice(32 * b, 32 * b + 32)
+            e = np.floor(np.log2(np.abs(V[n, sl]).max())) - (2 if q1 == "mxfp4" else 0)
+            units = (out.E[n, sl] + V[n, sl]) / 2.0 ** e           # in element units
+            near = grid[np.abs(np.abs(units)[:, None] - grid[None, :]).argmin(axis=1)]
+            assert np.all(np.abs(np.abs(units) - near) <= 1e-5), (n, b)
+            step_max = 2.0 if q1 == "mxfp4" else 0.25              # widest gap of the element grid (4 -> 6; 1/4)
+            top = 6.0 if q1 == "mxfp4" else 1.75
+            inside = np.abs(V[n, sl]) / 2.0 ** e <= top
+            assert np.all(np.abs(out.E[n, sl][inside]) / 2.0 ** e <= step_max / 2 + 1e-5)
+    assert abs(out.loss - np.mean(out.E.astype(np.float64) ** 2)) <= 1e-12 * out.loss
+    gL = -2.0 / (N * K) * out.E.astype(np.float64) @ R.astype(np.float64).T
+    assert np.allclose(out.gL, gL, rtol=1e-6, atol=1e-7 * np.abs(gL).max())
+    # descent also holds for these formats
+    losses = [out.loss] + [oracle.calib_step(W, st, q1=q1, lr=1e-3).loss for _ in range(60)]
+    assert losses[-1] < 0.97 * losses[0]
+
+
 @pytest.mark.parametrize("g,sint4", [(64, False), (128, False), (64, True)])
 def test_calib_error_and_gradients(oracle, g, sint4):
     W, L, R = _calib_problem(oracle)
