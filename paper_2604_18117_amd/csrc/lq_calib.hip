@@ -3,9 +3,9 @@
 // for the main quantiser Q1 of the configuration: INT4 in groups of 64 | 128 along K with fp32 scales, SINT4 blocks with
 // FP16 scales, MXFP4 or MXINT4 (blocks of 32, E8M0 scale).  Four launches per step:
 //   calib_err_kernel   V = W + L R (fp32 FMA chain over ascending j), E = deq(Q1(V)) - V, partial sums of E^2
-//   gemm_nt_kernel     grad_L = -2/(N K) E R^T      (fp32 MFMA, contraction split over the wavefronts of a workgroup)
-//   gemm_tn_kernel     grad_R = -2/(N K) L^T E
-//   calib_adam_kernel  Adam update of L and R, loss = sum of the partials / (N K)
+//   calib_grad_l_kernel  grad_L = -2/(N K) E R^T      (fp32 MFMA, contraction split over the wavefronts of a workgroup)
+//   calib_grad_r_kernel  partials of L^T E over row ranges
+//   calib_adam_kernel    grad_R = -2/(N K) * (sum of the partials), Adam update of L and R, loss = sum of its partials / (N K)
 // No atomics: every sum has a fixed order, so a step is reproducible bit for bit.
 #include "lq_internal.h"
 
@@ -15,6 +15,20 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 // column groups a wavefront of calib_err_kernel owns one of: the INT scale groups, or 64-chunks (two MX blocks)
 static int calib_groups(const Dims& d) { return (d.mx || d.mxi) ? d.C64 : d.G; }
+
+// Row ranges the contraction of grad_R = L^T E is split into (each range a multiple of 16 rows): enough workgroups
+// (K / 32 per range) to fill the device, at most 16 ranges.
+static int calib_splits(const Dims& d)
+{
+    const int blocks = (int)(d.N / 16), per = (int)(d.K / 32);
+    int best = 1;
+    for (int s = 1; s <= 16; ++s) {
+        if (blocks % s) continue;
+        best = s;
+        if (s * per >= 256) break;
+    }
+    return best;
+}
 
 CalibLayout calib_layout(const Dims& d)
 {
@@ -32,6 +46,7 @@ CalibLayout calib_layout(const Dims& d)
     cl.off_E = o;  o = align256(o + (size_t)d.N * d.K * 4);
     cl.n_lp = (int)(d.N / 16) * ((calib_groups(d) + 3) / 4) * 4;  // one partial per wavefront of calib_err_kernel
     cl.off_lp = o; o = align256(o + (size_t)cl.n_lp * 4);
+    cl.off_gRp = o; o = align256(o + (size_t)calib_splits(d) * nr);
     cl.total = o;
     return cl;
 }
@@ -131,20 +146,37 @@ __global__ __launch_bounds__(256) void calib_err_kernel(const float* W, const fl
                 }
             }
         }
+        float amax[16];
 #pragma unroll
         for (int row = 0; row < 16; ++row) {
             float a = 0.f;
 #pragma unroll
             for (int c = 0; c < GC; ++c) a = fmaxf(a, fabsf(v[row][c]));
-            a = wave_max_f<(Q >= 2)>(a, lane);
+            amax[row] = wave_max_f<(Q >= 2)>(a, lane);
+        }
+        // INT / SINT4 scales need correctly rounded divisions: done once for the 16 rows (lane l works on row l % 16,
+        // the rows then read their pair back through scalar registers) instead of once per row by all lanes
+        float sv = 1.0f, iv = 1.0f;
+        if constexpr (Q <= 1) {
+            float am = amax[0];
+#pragma unroll
+            for (int row = 1; row < 16; ++row) am = (lane & 15) == row ? amax[row] : am;
+            if constexpr (Q == 1) {
+                sv = f16_bits_value(sint4_scale(am, &iv));
+            } else {  // branch-free: an all-zero group takes scale 1
+                const float sd = __fdiv_rn(am, 7.0f), id = __fdiv_rn(7.0f, am);
+                sv = am == 0.0f ? 1.0f : sd;
+                iv = am == 0.0f ? 1.0f : id;
+            }
+        }
+#pragma unroll
+        for (int row = 0; row < 16; ++row) {
+            const float a = amax[row];
             float s = 1.0f, inv = 1.0f;
             uint32_t eb = 0u;
-            if constexpr (Q == 1) {
-                s = f16_bits_value(sint4_scale(a, &inv));
-            } else if constexpr (Q == 0) {  // branch-free: an all-zero group takes scale 1
-                const float sd = __fdiv_rn(a, 7.0f), id = __fdiv_rn(7.0f, a);
-                s = a == 0.0f ? 1.0f : sd;
-                inv = a == 0.0f ? 1.0f : id;
+            if constexpr (Q <= 1) {
+                s = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sv), row));
+                inv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(iv), row));
             } else if constexpr (Q == 2) {
                 eb = mxfp4_scale_byte(a);
                 s = e8m0_as_float(eb);
@@ -174,76 +206,107 @@ __global__ __launch_bounds__(256) void calib_err_kernel(const float* W, const fl
     if (lane == 0) lp[blockIdx.x * 4 + wave] = lsum;
 }
 
-// C[m][n] = scale * sum_k A[m][k] B[n][k]   (both operands with the contraction index contiguous).  One 16 x 16 tile
-// of C per workgroup; wavefront w takes the 16-deep k slices w, w + WAVES, ...; partial tiles are summed through
-// LDS in wavefront order.  v_mfma_f32_16x16x4_f32: lane l supplies A[row l%16][k slot l/16] and B[col l%16][k slot
-// l/16]; a lane's 16-byte load holds four consecutive k, which feed four MFMAs (the k order inside a slice is
-// permuted the same way for both operands).
-template <int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void gemm_nt_kernel(const float* A, int lda, const float* B, int ldb, float* C, int ldc,
-                                                            int tilesN, int Kc, float scale)
+// Gradient products on v_mfma_f32_16x16x4_f32 (fp32 in, fp32 accumulate): lane l supplies A[row l%16][k slot l/16] and
+// B[col l%16][k slot l/16]; the four values a lane holds per 16-deep slice feed four MFMAs (the k order inside a slice
+// is permuted the same way for both operands).  The contraction is split over the wavefronts of a workgroup (slices
+// w, w + WAVES, ...) and the partial tiles are summed through LDS in wavefront order.  NT = r / 16.
+//
+// grad_L = scale * E R^T: a workgroup owns 16 rows of E and all r columns, so E is read once.
+template <int NT>
+__global__ __launch_bounds__(512) void calib_grad_l_kernel(const float* E, const float* R, float* gL, int K, float scale)
 {
-    __shared__ __attribute__((aligned(16))) float s_acc[WAVES][64][4];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int WAVES = 8;
+    __shared__ __attribute__((aligned(16))) float s_acc[WAVES][NT][64][4];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int row = lane & 15, q = lane >> 4;
-    const int m0 = (blockIdx.x / tilesN) * 16, n0 = (blockIdx.x % tilesN) * 16;
-    v4f acc = {0.f, 0.f, 0.f, 0.f};
-    const float* ap = A + (size_t)(m0 + row) * lda + 4 * q;
-    const float* bp = B + (size_t)(n0 + row) * ldb + 4 * q;
-#pragma unroll 4
-    for (int kk = wave * 16; kk < Kc; kk += WAVES * 16) {
+    const int m0 = blockIdx.x * 16;
+    v4f acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
+    const float* ap = E + (size_t)(m0 + row) * K + 4 * q;
+    const float* bp = R + (size_t)row * K + 4 * q;
+#pragma unroll 2
+    for (int kk = wave * 16; kk < K; kk += WAVES * 16) {
         const v4f a4 = *(const v4f*)(ap + kk);
-        const v4f b4 = *(const v4f*)(bp + kk);
+        v4f b4[NT];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[i], b4[i], acc, 0, 0, 0);
+        for (int t = 0; t < NT; ++t) b4[t] = *(const v4f*)(bp + (size_t)t * 16 * K + kk);
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[i], b4[t][i], acc[t], 0, 0, 0);
     }
-    *(v4f*)&s_acc[wave][lane][0] = acc;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) *(v4f*)&s_acc[wave][t][lane][0] = acc[t];
     __syncthreads();
-    if (wave != 0) return;
-    v4f s = *(const v4f*)&s_acc[0][lane][0];
+    // wavefront w finishes tiles w, w + WAVES, ...
+    for (int t = wave; t < NT; t += WAVES) {
+        v4f s = *(const v4f*)&s_acc[0][t][lane][0];
 #pragma unroll
-    for (int w = 1; w < WAVES; ++w) {
-        const v4f o = *(const v4f*)&s_acc[w][lane][0];
+        for (int w = 1; w < WAVES; ++w) {
+            const v4f o = *(const v4f*)&s_acc[w][t][lane][0];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) s[i] = __fadd_rn(s[i], o[i]);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) C[(size_t)(m0 + 4 * q + i) * ldc + n0 + row] = __fmul_rn(scale, s[i]);
-}
-
-// C[m][n] = scale * sum_k A[k][m] B[k][n]   (the contraction index is the row index of both operands).
-template <int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void gemm_tn_kernel(const float* A, int lda, const float* B, int ldb, float* C, int ldc,
-                                                            int tilesN, int Kc, float scale)
-{
-    __shared__ __attribute__((aligned(16))) float s_acc[WAVES][64][4];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int row = lane & 15, q = lane >> 4;
-    const int m0 = (blockIdx.x / tilesN) * 16, n0 = (blockIdx.x % tilesN) * 16;
-    v4f acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-    for (int kk = wave * 16; kk < Kc; kk += WAVES * 16) {
-        float a4[4], b4[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            a4[i] = A[(size_t)(kk + 4 * q + i) * lda + m0 + row];
-            b4[i] = B[(size_t)(kk + 4 * q + i) * ldb + n0 + row];
+            for (int i = 0; i < 4; ++i) s[i] = __fadd_rn(s[i], o[i]);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[i], b4[i], acc, 0, 0, 0);
+        for (int i = 0; i < 4; ++i) gL[(size_t)(m0 + 4 * q + i) * (NT * 16) + t * 16 + row] = __fmul_rn(scale, s[i]);
     }
-    *(v4f*)&s_acc[wave][lane][0] = acc;
+}
+
+// Partial grad_R = L^T E over a range of rows: a workgroup owns 32 columns of E (whole 128-byte lines per row), all r
+// rows of the result, and the rows [split * rows_per, (split + 1) * rows_per) of the contraction; the partial goes to
+// part[split][r][K] and the Adam kernel adds the splits in order (and applies the scale).
+template <int NT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void calib_grad_r_kernel(const float* L, const float* E, float* part, int K, int rows_per)
+{
+    constexpr int r = NT * 16;
+    __shared__ __attribute__((aligned(16))) float s_acc[WAVES][NT * 2][64][4];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int row = lane & 15, q = lane >> 4;
+    const int ct = K >> 5;
+    const int n0 = ((int)blockIdx.x % ct) * 32, split = (int)blockIdx.x / ct;
+    const size_t base = (size_t)split * rows_per;
+    v4f acc[NT][2];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t][0] = acc[t][1] = v4f{0.f, 0.f, 0.f, 0.f};
+    const float* ap = L + (base + 4 * q) * r + row;
+    const float* bp = E + (base + 4 * q) * K + n0 + row;
+#pragma unroll 2
+    for (int kk = wave * 16; kk < rows_per; kk += WAVES * 16) {
+        float a4[NT][4], b4[2][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) a4[t][i] = ap[(size_t)(kk + i) * r + t * 16];
+            b4[0][i] = bp[(size_t)(kk + i) * K];
+            b4[1][i] = bp[(size_t)(kk + i) * K + 16];
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[t][h] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[t][i], b4[h][i], acc[t][h], 0, 0, 0);
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) *(v4f*)&s_acc[wave][t * 2 + h][lane][0] = acc[t][h];
     __syncthreads();
-    if (wave != 0) return;
-    v4f s = *(const v4f*)&s_acc[0][lane][0];
+    for (int th = wave; th < NT * 2; th += WAVES) {
+        v4f s = *(const v4f*)&s_acc[0][th][lane][0];
 #pragma unroll
-    for (int w = 1; w < WAVES; ++w) {
-        const v4f o = *(const v4f*)&s_acc[w][lane][0];
+        for (int w = 1; w < WAVES; ++w) {
+            const v4f o = *(const v4f*)&s_acc[w][th][lane][0];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) s[i] = __fadd_rn(s[i], o[i]);
+            for (int i = 0; i < 4; ++i) s[i] = __fadd_rn(s[i], o[i]);
+        }
+        const int t = th >> 1, h = th & 1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) part[((size_t)split * r + t * 16 + 4 * q + i) * K + n0 + h * 16 + row] = s[i];
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) C[(size_t)(m0 + 4 * q + i) * ldc + n0 + row] = __fmul_rn(scale, s[i]);
 }
 
 struct AdamParams {
@@ -253,8 +316,9 @@ struct AdamParams {
 // One thread per parameter: the N x r values of L, then the r x K values of R.  Block 0 also sums the loss partials
 // (thread-strided, a fixed shuffle tree per wavefront, then the four wavefronts in order).
 __global__ __launch_bounds__(256) void calib_adam_kernel(float* L, float* mL, float* vL, const float* gL, size_t nL, float* R,
-                                                         float* mR, float* vR, const float* gR, size_t nR, AdamParams a,
-                                                         const float* lp, int n_lp, float inv_count, float* loss)
+                                                         float* mR, float* vR, float* gR, const float* gR_part, int splits,
+                                                         float gscale, size_t nR, AdamParams a, const float* lp, int n_lp,
+                                                         float inv_count, float* loss)
 {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx < nL + nR) {
@@ -263,7 +327,15 @@ __global__ __launch_bounds__(256) void calib_adam_kernel(float* L, float* mL, fl
         float* p = isL ? L : R;
         float* m = isL ? mL : mR;
         float* v = isL ? vL : vR;
-        const float g = isL ? gL[i] : gR[i];
+        float g;
+        if (isL) {
+            g = gL[i];
+        } else {  // grad_R: the row-range partials in order, then the scale
+            float sum = gR_part[i];
+            for (int sp = 1; sp < splits; ++sp) sum = __fadd_rn(sum, gR_part[(size_t)sp * nR + i]);
+            g = __fmul_rn(gscale, sum);
+            gR[i] = g;
+        }
         const float mm = __fadd_rn(__fmul_rn(a.b1, m[i]), __fmul_rn(1.0f - a.b1, g));
         const float vv = __fadd_rn(__fmul_rn(a.b2, v[i]), __fmul_rn(1.0f - a.b2, __fmul_rn(g, g)));
         m[i] = mm;
@@ -328,10 +400,26 @@ hipError_t launch_calib_step(const Dims& d, const float* W, uint8_t* state, int 
     else
         hipLaunchKernelGGL((calib_err_kernel<2, 0>), grid, block, lds, s, W, L, R, E, lp, N, K, r);
     const float cg = (float)(-2.0 / ((double)N * (double)K));
-    // grad_L (N x r) = cg * E (N x K) . R^T       contraction over K
-    hipLaunchKernelGGL((gemm_nt_kernel<8>), dim3((unsigned)((N / 16) * (r / 16))), dim3(512), 0, s, E, K, R, K, gL, r, r / 16, K, cg);
-    // grad_R (r x K) = cg * L^T (r x N) . E (N x K)   contraction over N
-    hipLaunchKernelGGL((gemm_tn_kernel<16>), dim3((unsigned)((r / 16) * (K / 16))), dim3(1024), 0, s, L, r, E, K, gR, K, K / 16, N, cg);
+    // grad_L (N x r): one workgroup per 16 rows of E
+    const dim3 gl_grid((unsigned)(N / 16)), gl_block(512);
+    switch (r >> 4) {
+        case 1: hipLaunchKernelGGL((calib_grad_l_kernel<1>), gl_grid, gl_block, 0, s, E, R, gL, K, cg); break;
+        case 2: hipLaunchKernelGGL((calib_grad_l_kernel<2>), gl_grid, gl_block, 0, s, E, R, gL, K, cg); break;
+        case 4: hipLaunchKernelGGL((calib_grad_l_kernel<4>), gl_grid, gl_block, 0, s, E, R, gL, K, cg); break;
+        case 6: hipLaunchKernelGGL((calib_grad_l_kernel<6>), gl_grid, gl_block, 0, s, E, R, gL, K, cg); break;
+        default: hipLaunchKernelGGL((calib_grad_l_kernel<8>), gl_grid, gl_block, 0, s, E, R, gL, K, cg); break;
+    }
+    // grad_R (r x K): partials over row ranges
+    const int splits = calib_splits(d), rows_per = N / splits;
+    float* gRp = (float*)(state + cl.off_gRp);
+    const dim3 gr_grid((unsigned)((K / 32) * splits));
+    switch (r >> 4) {
+        case 1: hipLaunchKernelGGL((calib_grad_r_kernel<1, 8>), gr_grid, dim3(512), 0, s, L, E, gRp, K, rows_per); break;
+        case 2: hipLaunchKernelGGL((calib_grad_r_kernel<2, 8>), gr_grid, dim3(512), 0, s, L, E, gRp, K, rows_per); break;
+        case 4: hipLaunchKernelGGL((calib_grad_r_kernel<4, 8>), gr_grid, dim3(512), 0, s, L, E, gRp, K, rows_per); break;
+        case 6: hipLaunchKernelGGL((calib_grad_r_kernel<6, 4>), gr_grid, dim3(256), 0, s, L, E, gRp, K, rows_per); break;
+        default: hipLaunchKernelGGL((calib_grad_r_kernel<8, 4>), gr_grid, dim3(256), 0, s, L, E, gRp, K, rows_per); break;
+    }
     AdamParams a;
     a.lr = ad->lr;
     a.b1 = ad->beta1;
@@ -341,8 +429,8 @@ hipError_t launch_calib_step(const Dims& d, const float* W, uint8_t* state, int 
     a.ic2 = (float)(1.0 / (1.0 - pow((double)ad->beta2, (double)step)));
     const size_t nL = (size_t)N * r, nR = (size_t)r * K;
     hipLaunchKernelGGL(calib_adam_kernel, dim3((unsigned)((nL + nR + 255) / 256)), dim3(256), 0, s, L, (float*)(state + cl.off_mL),
-                       (float*)(state + cl.off_vL), gL, nL, R, (float*)(state + cl.off_mR), (float*)(state + cl.off_vR), gR, nR,
-                       a, lp, cl.n_lp, (float)(1.0 / ((double)N * (double)K)), loss);
+                       (float*)(state + cl.off_vL), gL, nL, R, (float*)(state + cl.off_mR), (float*)(state + cl.off_vR), gR, gRp,
+                       splits, cg, nR, a, lp, cl.n_lp, (float)(1.0 / ((double)N * (double)K)), loss);
     return hipGetLastError();
 }
 

@@ -148,6 +148,7 @@ struct CalibLayout {
     size_t off_E;              // N x K  deq(Q1(W + L R)) - (W + L R) of the last step
     size_t off_lp;             // partial sums of E^2, one per wavefront
     int n_lp;
+    size_t off_gRp;            // partials of L^T E over row ranges, [range][r][K]
     size_t total;
 };
 CalibLayout calib_layout(const Dims& d);

@@ -218,9 +218,9 @@ def test_calibration_contract(lq):
     n = C.c_size_t(0)
     cfg = _cfg(lq)                                 # N 128, K 256, rank 32
     assert raw.lq_calib_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_OK
-    # factors, two moments and a gradient per factor, the N x K error matrix, a loss partial per wavefront
+    # factors, two moments and a gradient per factor, the N x K error matrix, a loss partial per wavefront, partials of grad_R
     nl, nr = 128 * 32 * 4, 32 * 256 * 4
-    parts = [nl, nr, nl, nl, nr, nr, nl, nr, 128 * 256 * 4, 128 // 16 * 1 * 4 * 4]   # K 256: 4 groups = one workgroup column
+    parts = [nl, nr, nl, nl, nr, nr, nl, nr, 128 * 256 * 4, 128 // 16 * 1 * 4 * 4, 8 * nr]   # K 256: 4 groups = one workgroup column; grad_R partials over 8 row ranges
     assert n.value == sum((x + 255) // 256 * 256 for x in parts)
     for fam in ("mx", "mxi"):                       # K 256 = four 64-chunks: the same workgroup grid, the same size
         m = C.c_size_t(0)
