@@ -247,3 +247,25 @@ def test_sint4_blocks_degenerate_and_extreme_scales(oracle):
 @pytest.mark.parametrize("name", ["c2s_qkv", "c4s_qkv"])
 def test_sint4_blocks_full_size_sampled_rows(oracle, name):
     _full_size_sampled(oracle, name)
+
+
+def test_seeded_shape_sweep_bit_exact(oracle):
+    """Seeded sweep over small shapes around the tile edges (32-row blocks, 128-row tiles, 64- and 256-column tiles),
+    ranks, group sizes, branch widths, input types and both main scale granularities."""
+    rng = np.random.default_rng(2024)
+    edge_M = [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 257]
+    for it in range(14):
+        M = int(rng.choice(edge_M))
+        K = 64 * int(rng.integers(1, 9))
+        N = 64 * int(rng.integers(1, 10))
+        r = int(rng.choice([0, 16, 32, 64, 128]))
+        ag = int(rng.choice([0, 64]))
+        g = 64 if ag or K % 128 else int(rng.choice([64, 128]))
+        bw, ba = [(8, 8), (6, 6), (4, 8)][int(rng.integers(0, 3))]
+        xd = "bf16" if rng.integers(0, 2) else "f32"
+        layer = wl.Layer("t", M, K, N, r, "int", g, bw, ba, xd, outlier_scale=12.0, n_outliers=1, seed=100 + it, a_group=ag)
+        X, W, L, R = wl.make_inputs(layer)
+        try:
+            _compare_all(oracle, layer, X, W, L, R)
+        except AssertionError as e:
+            raise AssertionError(f"shape M={M} K={K} N={N} r={r} g={g} ag={ag} bw={bw} ba={ba} {xd}: {e}") from e

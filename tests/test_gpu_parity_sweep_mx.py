@@ -1,0 +1,37 @@
+"""Seeded sweeps over small shapes around the tile edges for the block-scaled families (MX, MXB, MXI), each compared by
+its family's own parity routine (codes and scale bytes bit-exact, floating-point results to the family's bound)."""
+import numpy as np
+import pytest
+
+from paper_2604_18117_amd import workloads as wl
+from tests import test_gpu_parity_mx as t_mx
+from tests import test_gpu_parity_mxb as t_mxb
+from tests import test_gpu_parity_mxi as t_mxi
+
+pytestmark = pytest.mark.gpu
+
+EDGE_M = [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 257]
+
+
+@pytest.mark.parametrize("family", ["mx", "mxb8", "mxb6", "mxi8", "mxi4"])
+def test_seeded_shape_sweep(oracle, family):
+    rng = np.random.default_rng(sum(map(ord, family)))
+    for it in range(8):
+        M = int(rng.choice(EDGE_M))
+        K = 128 * int(rng.integers(1, 6)) if not family.startswith("mxi") else 64 * int(rng.integers(1, 10))
+        N = 64 * int(rng.integers(1, 10))
+        xd = "bf16" if rng.integers(0, 2) else "f32"
+        if family == "mx":
+            r = int(rng.choice([0, 16, 32, 64, 128]))
+            layer, cmp = wl.Layer("t", M, K, N, r, "mx", 32, 8, 8, xd, seed=200 + it), t_mx._compare
+        elif family.startswith("mxb"):
+            r, e = int(rng.choice([0, 32, 64, 96, 128])), int(family[-1])
+            layer, cmp = wl.Layer("t", M, K, N, r, "mxb", 32, e, e, xd, seed=200 + it), t_mxb._compare
+        else:
+            r, bw = int(rng.choice([0, 32, 64, 96, 128])), int(family[-1])
+            layer, cmp = wl.Layer("t", M, K, N, r, "mxi", 32, bw, 8, xd, seed=200 + it), t_mxi._compare
+        X, W, L, R = wl.make_inputs(layer)
+        try:
+            cmp(oracle, layer, X, W, L, R)
+        except AssertionError as e:
+            raise AssertionError(f"{family}: M={M} K={K} N={N} r={r} {xd}: {e}") from e
