@@ -226,7 +226,6 @@ __global__ __launch_bounds__(512) void calib_grad_l_kernel(const float* E, const
     for (int t = 0; t < NT; ++t) acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
     const float* ap = E + (size_t)(m0 + row) * K + 4 * q;
     const float* bp = R + (size_t)row * K + 4 * q;
-#pragma unroll 2
     for (int kk = wave * 16; kk < K; kk += WAVES * 16) {
         const v4f a4 = *(const v4f*)(ap + kk);
         v4f b4[NT];
@@ -273,7 +272,6 @@ __global__ __launch_bounds__(WAVES * 64) void calib_grad_r_kernel(const float* L
     for (int t = 0; t < NT; ++t) acc[t][0] = acc[t][1] = v4f{0.f, 0.f, 0.f, 0.f};
     const float* ap = L + (base + 4 * q) * r + row;
     const float* bp = E + (base + 4 * q) * K + n0 + row;
-#pragma unroll 2
     for (int kk = wave * 16; kk < rows_per; kk += WAVES * 16) {
         float a4[NT][4], b4[2][4];
 #pragma unroll

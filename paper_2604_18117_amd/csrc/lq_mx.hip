@@ -261,7 +261,8 @@ hipError_t launch_pack_mx(const Dims& d, int from_q, const float* W, const float
         if (lq_bytes) hipLaunchKernelGGL(mx_fill_kernel, dim3((unsigned)((lq_bytes + 255) / 256)), dim3(256), 0, s, l8, lq_bytes, (uint8_t)0);
         hipLaunchKernelGGL(mx_fill_kernel, dim3((unsigned)((le_bytes + 255) / 256)), dim3(256), 0, s, (uint8_t*)sl, le_bytes, (uint8_t)127);
         if (d.r > 0 && d.mxb_elem == 6) {
-            launch_pack_rows_mx6(d, L, R, packed, s);
+            const hipError_t e = launch_pack_rows_mx6(d, L, R, packed, s);
+            if (e != hipSuccess) return e;
         } else if (d.r > 0) {
             const size_t nr = (size_t)d.r * (K / 32), nl = (size_t)N * (d.r / 32);
             hipLaunchKernelGGL(mxb_pack_rows_kernel, dim3((unsigned)((nr + 255) / 256)), dim3(256), 0, s, R, d.r, K, 0, d.r, d.rp, r8, (uint8_t*)sr);

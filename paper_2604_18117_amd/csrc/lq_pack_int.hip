@@ -171,7 +171,10 @@ hipError_t launch_pack_int(const Dims& d, int from_q, const float* W, const floa
         hipLaunchKernelGGL(pack_l_kernel, dim3((N + 255) / 256), dim3(256), 0, s, (const float*)nullptr, N, 0, 0,
                            1.0f, lq, sl);
     }
-    if (d.smooth) launch_set_smoothing(d, nullptr, packed, s);
+    if (d.smooth) {
+        const hipError_t e = launch_set_smoothing(d, nullptr, packed, s);
+        if (e != hipSuccess) return e;
+    }
     const size_t waves = (size_t)N * d.G;
     const unsigned blocks = (unsigned)((waves + 3) / 4);
     if (d.g == 64)
