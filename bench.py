@@ -34,7 +34,6 @@ def bench_calib(args, layer, np, torch, lq, wl):
     """K Adam steps of the factor optimisation (Eq. 4) on the layer's weight shape, SVD-free synthetic start
     (the start does not change the work per step).  value = steps per second; the error kernel's roofline is HBM:
     it reads W and writes the error matrix, 8 bytes per weight."""
-    assert layer.family == "int", "the calibration step covers the INT family's main quantiser"
     _, W, L, R = wl.make_inputs(layer)
     cfg = lq.config_for_layer(layer)
     Wd = torch.from_numpy(W).cuda()
@@ -66,13 +65,16 @@ def bench_calib(args, layer, np, torch, lq, wl):
            "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": round(ms_step, 5), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": layer.name + "_calib", "N": N, "K": Kd, "rank": r,
-                      "main": "SINT4 blocks" if layer.a_group == 64 else f"INT4 g{layer.g}", "launches_per_step": 4},
+                      "main": {"mx": "MXFP4", "mxb": "MXFP4", "mxi": "MXINT4"}.get(
+                          layer.family, "SINT4 blocks" if layer.a_group == 64 else f"INT4 g{layer.g}"),
+                      "launches_per_step": 4},
            "work_per_step": {"flops": flops, "hbm_bytes_error_kernel": hbm, "loss": float(loss.item())}}
     if args.oracle_seconds > 0:
         from oracle import lq_ref
         st = lq_ref.calib_init(L * scale, R * scale)
         t0 = time.perf_counter()
-        lq_ref.calib_step(W, st, layer.g, sint4_blocks=layer.a_group == 64)
+        q1 = {"mx": "mxfp4", "mxb": "mxfp4", "mxi": "mxint4"}.get(layer.family, "sint4" if layer.a_group == 64 else "int")
+        lq_ref.calib_step(W, st, layer.g, q1=q1)
         dt = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(1.0 / dt, 3), "unit": "steps/s", "cores": lq_ref.num_threads(), "kind": "oracle",
                                "sample": "one full step of the same layer"}

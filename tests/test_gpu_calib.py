@@ -144,3 +144,37 @@ def test_calibrated_factors_feed_the_forward(oracle):
     # the residual the pack step quantises is W + L R (fp64 sum rounded once there, an fp32 chain in the calibration)
     V = W.astype(np.float64) + Lc.astype(np.float64) @ Rc.astype(np.float64)
     assert np.allclose(pk.P, V, rtol=0, atol=1e-6 * np.abs(V).max())
+
+
+def test_step_in_a_hip_graph(oracle):
+    """A step is four kernel launches and nothing else, so it can be captured; the step number (bias correction) is a
+    launch argument, so replays repeat that step number: compared with eager calls at the same number."""
+    N, K, r, g = 128, 256, 16, 64
+    W, L, R = _problem(N, K, r, seed=12)
+    cfg = _cfg(N, K, r, g, False)
+    Wd = torch.from_numpy(W).cuda()
+    Ld, Rd = torch.from_numpy(L).cuda(), torch.from_numpy(R).cuda()
+    eager = lq.lq_calib_init(cfg, Ld, Rd)
+    loss_e = torch.zeros(1, dtype=torch.float32, device="cuda")
+    for _ in range(5):
+        lq.lq_calib_step(cfg, Wd, eager, 3, loss=loss_e)
+    torch.cuda.synchronize()
+    state = lq.lq_calib_init(cfg, Ld, Rd)
+    loss_g = torch.zeros(1, dtype=torch.float32, device="cuda")
+    graph = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=s):
+        lq.lq_calib_step(cfg, Wd, state, 3, loss=loss_g)
+    for rep in range(5):
+        graph.replay()
+        torch.cuda.synchronize()
+        _ = lq.lq_calib_unpack(cfg, eager, ("L",))          # eager work of the library between replays
+        torch.cuda.synchronize()
+    names = ("L", "R", "mL", "vL", "mR", "vR", "gL", "gR", "E")
+    a, b = lq.lq_calib_unpack(cfg, eager, names), lq.lq_calib_unpack(cfg, state, names)
+    torch.cuda.synchronize()
+    for k in names:
+        assert torch.equal(a[k], b[k]), k
+    assert loss_e.item() == loss_g.item()
