@@ -114,15 +114,14 @@ def make_config(N: int, K: int, rank: int, family: str = "int", group: int = 64,
         return lq_config(N, K, rank, LQ_INT4, LQ_INT4, group, a_group, _INT_FMT[br_w_bits], _INT_FMT[br_a_bits],
                          1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32,
                          LQ_FLAG_SMOOTH if smooth else 0)
-    if smooth:
-        raise ValueError("smoothing is fused into the INT family only")
+    fl = LQ_FLAG_SMOOTH if smooth else 0
     if family in ("mx", "mxb"):  # "mxb": block-scaled branch (MXFP8e4, or MXFP6e2 at 6 bits) instead of fp32-scaled E4M3
         br = (LQ_MXFP6_E2M3 if br_w_bits == 6 else LQ_MXFP8_E4M3) if family == "mxb" else LQ_FP8_E4M3
         return lq_config(N, K, rank, LQ_MXFP4_E2M1, LQ_MXFP4_E2M1, 32, 32, br, br,
-                         1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32, 0)
+                         1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32, fl)
     if family == "mxi":          # MXINT4 main; MXINT8 branch activations; MXINT8 or MXINT4 branch weights
         return lq_config(N, K, rank, LQ_MXINT4, LQ_MXINT4, 32, 32, LQ_MXINT8 if br_w_bits == 8 else LQ_MXINT4, LQ_MXINT8,
-                         1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32, 0)
+                         1 if residual_from_quantized else 0, LQ_BF16 if x_dtype == "bf16" else LQ_F32, fl)
     raise ValueError(family)
 
 

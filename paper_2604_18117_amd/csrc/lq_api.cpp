@@ -52,8 +52,6 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         d->g = cfg->main_w_group;
         d->qmax_bw = qw;
         d->qmax_ba = qa;
-    } else if (d->smooth) {
-        return LQ_ERR_UNSUPPORTED;  // smoothing is fused into the INT family's activation kernel only
     } else if (cfg->main_w == LQ_MXFP4_E2M1) {
         if (cfg->main_a != LQ_MXFP4_E2M1) return LQ_ERR_UNSUPPORTED;
         if (cfg->main_w_group != 32 || cfg->main_a_group != 32) return LQ_ERR_SHAPE;
@@ -63,6 +61,7 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         if (cfg->K % 128 != 0) return LQ_ERR_SHAPE;  // the MX forward stages K in steps of 128
         d->mxb = cfg->br_w != LQ_FP8_E4M3;
         if (!d->mxb && r == 96) return LQ_ERR_SHAPE;
+        if (!d->mxb && d->smooth && cfg->K > 2304) return LQ_ERR_UNSUPPORTED;  // row-resident kernel: the smoothed row is fp32
         d->mxb_elem = cfg->br_w == LQ_MXFP8_E4M3 ? 8 : cfg->br_w == LQ_MXFP6_E2M3 ? 6 : 0;
         if (d->mxb && r % 32 != 0) return LQ_ERR_SHAPE;  // whole blocks of 32 along the rank
         d->mx = true;

@@ -236,6 +236,43 @@ __device__ __forceinline__ size_t sxg_index(int row, int g, int tiles128)
     return ((size_t)((size_t)g * tiles128 + (row >> 7)) * 32 + (row & 31)) * 4 + ((row >> 5) & 3);
 }
 
+// Activation smoothing (Section 3.4; App. A.1) fused into an activation kernel: NV (16 | 32) consecutive values of X
+// (bf16 or fp32 source) times the stored reciprocals of the smoothing vector, as fp32 (zeros if !ok).  A product of a
+// bf16 value and an fp32 reciprocal is not a bf16 number, so smoothing kernels hold X as fp32.
+template <bool BF16IN, int NV>
+__device__ __forceinline__ void smooth_load(float (&out)[NV], const void* X, size_t elem, const float* rg, bool ok)
+{
+    typedef int v4i_ __attribute__((ext_vector_type(4)));
+    float raw[NV];
+    if constexpr (BF16IN) {
+#pragma unroll
+        for (int q = 0; q < NV / 8; ++q) {
+            v4i_ a = {0, 0, 0, 0};
+            if (ok) a = ((const v4i_*)((const uint16_t*)X + elem))[q];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                raw[8 * q + 2 * d] = __uint_as_float((uint32_t)a[d] << 16);
+                raw[8 * q + 2 * d + 1] = __uint_as_float((uint32_t)a[d] & 0xFFFF0000u);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < NV / 4; ++q) {
+            v4i_ a = {0, 0, 0, 0};
+            if (ok) a = ((const v4i_*)((const float*)X + elem))[q];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) raw[4 * q + d] = __int_as_float(a[d]);
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < NV / 4; ++q) {
+        v4i_ g = {0, 0, 0, 0};
+        if (ok) g = ((const v4i_*)rg)[q];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) out[4 * q + d] = __fmul_rn(raw[4 * q + d], __int_as_float(g[d]));
+    }
+}
+
 // fp32 -> bf16 bits, round to nearest even (finite inputs)
 __device__ __forceinline__ uint32_t bf16_bits(float f)
 {

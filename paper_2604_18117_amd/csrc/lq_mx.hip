@@ -255,6 +255,10 @@ hipError_t launch_pack_mx(const Dims& d, int from_q, const float* W, const float
     const size_t pe_bytes = (size_t)(N / 32) * ((d.C64 + 3) / 4) * 256;
     hipLaunchKernelGGL(mx_fill_kernel, dim3((unsigned)((pe_bytes + 255) / 256)), dim3(256), 0, s, packed + pl.off_sw,
                        pe_bytes, (uint8_t)127);
+    if (d.smooth) {  // reciprocals of the smoothing vector start at 1
+        const hipError_t e = launch_set_smoothing(d, nullptr, packed, s);
+        if (e != hipSuccess) return e;
+    }
     if (d.mxb) {
         // padding of the rank to 64: zero codes, scale 2^0
         const size_t lq_bytes = (size_t)N * d.rp, le_bytes = (size_t)N * 8;
@@ -381,6 +385,7 @@ struct MxActParams {
     int8_t* dbg_xb;
     float* dbg_sxb;
     float* dbg_T;
+    const float* rg;  // reciprocals of the smoothing vector (smoothing variant only)
 };
 
 template <bool BF16>
@@ -422,9 +427,11 @@ struct MxChunk<false> {
     __device__ __forceinline__ float get(int i) const { return v[i]; }
 };
 
-template <bool BF16, int MAXC, int NJB>
+// BF16IN: element type of X; SM: smoothing variant (X times the stored reciprocals, held as fp32).
+template <bool BF16IN, int MAXC, int NJB, bool SM = false>
 __global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
 {
+    constexpr bool BF16 = BF16IN && !SM;  // representation of the row in registers
     __shared__ float s_amax[4][16];
     __shared__ float s_sxb[16];
     __shared__ float s_acc[4][NJB > 0 ? NJB : 1][64][4];
@@ -439,7 +446,11 @@ __global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
 #pragma unroll
     for (int ci = 0; ci < MAXC; ++ci) {
         const int c = wave + 4 * ci;
-        xc[ci].load(p.X, (size_t)row * p.ldx + (size_t)c * 64 + kq * 16, row_ok && c < C64);
+        const size_t koff = (size_t)c * 64 + kq * 16;
+        if constexpr (SM)
+            smooth_load<BF16IN, 16>(xc[ci].v, p.X, (size_t)row * p.ldx + koff, p.rg + koff, row_ok && c < C64);
+        else
+            xc[ci].load(p.X, (size_t)row * p.ldx + koff, row_ok && c < C64);
     }
 
     // Operands that do not depend on X are requested now (their latency overlaps the load of X):
@@ -581,21 +592,21 @@ __global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
     }
 }
 
-template <bool BF16, int MAXC, int NJB>
+template <bool BF16, int MAXC, int NJB, bool SM>
 static hipError_t mx_act_launch(const MxActParams& p, int64_t Mp, hipStream_t s)
 {
-    hipLaunchKernelGGL((mx_act_kernel<BF16, MAXC, NJB>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((mx_act_kernel<BF16, MAXC, NJB, SM>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
     return hipGetLastError();
 }
-template <bool BF16, int MAXC>
+template <bool BF16, int MAXC, bool SM = false>
 static hipError_t mx_act_rank(const MxActParams& p, int64_t Mp, hipStream_t s)
 {
     switch (p.r) {
-        case 0: return mx_act_launch<BF16, MAXC, 0>(p, Mp, s);
-        case 16: return mx_act_launch<BF16, MAXC, 1>(p, Mp, s);
-        case 32: return mx_act_launch<BF16, MAXC, 2>(p, Mp, s);
-        case 64: return mx_act_launch<BF16, MAXC, 4>(p, Mp, s);
-        default: return mx_act_launch<BF16, MAXC, 8>(p, Mp, s);
+        case 0: return mx_act_launch<BF16, MAXC, 0, SM>(p, Mp, s);
+        case 16: return mx_act_launch<BF16, MAXC, 1, SM>(p, Mp, s);
+        case 32: return mx_act_launch<BF16, MAXC, 2, SM>(p, Mp, s);
+        case 64: return mx_act_launch<BF16, MAXC, 4, SM>(p, Mp, s);
+        default: return mx_act_launch<BF16, MAXC, 8, SM>(p, Mp, s);
     }
 }
 
@@ -628,6 +639,11 @@ hipError_t launch_quantize_act_mx(const Dims& d, int x_dtype, const uint8_t* pac
     p.dbg_sxb = dbg ? dbg->sxb : nullptr;
     p.dbg_T = dbg ? dbg->T : nullptr;
     const int maxc = (d.C64 + 3) / 4;
+    p.rg = d.smooth ? (const float*)(packed + pl.off_rg) : nullptr;
+    if (d.smooth) {  // K <= 2304: the smoothed row is held as fp32, at most 9 chunks per wavefront
+        if (x_dtype == LQ_BF16) return maxc <= 5 ? mx_act_rank<true, 5, true>(p, al.Mp, s) : mx_act_rank<true, 9, true>(p, al.Mp, s);
+        return maxc <= 5 ? mx_act_rank<false, 5, true>(p, al.Mp, s) : mx_act_rank<false, 9, true>(p, al.Mp, s);
+    }
     if (x_dtype == LQ_BF16) {
         if (maxc <= 5) return mx_act_rank<true, 5>(p, al.Mp, s);
         if (maxc <= 9) return mx_act_rank<true, 9>(p, al.Mp, s);
@@ -657,11 +673,14 @@ struct MxbActParams {
     int8_t* dbg_xb;
     uint8_t* dbg_xbe;
     float* dbg_T;
+    const float* rg;  // reciprocals of the smoothing vector (smoothing variant only)
 };
 
-template <bool BF16, int NJB>
+// BF16IN: element type of X; SM: smoothing variant (X times the stored reciprocals, held as fp32).
+template <bool BF16IN, int NJB, bool SM = false>
 __global__ __launch_bounds__(256) void mxb_act_kernel(MxbActParams p)
 {
+    constexpr bool BF16 = BF16IN && !SM;  // representation of a chunk in registers
     constexpr int NJA = NJB > 0 ? NJB : 1;
     constexpr int PF = 2;  // 128-chunks in flight per wavefront: no scale spans more than a block, the row is streamed
     __shared__ float s_acc[4][NJA][64][4];
@@ -674,11 +693,16 @@ __global__ __launch_bounds__(256) void mxb_act_kernel(MxbActParams p)
 
     const int nmy = (C128 - wave + 3) >> 2;  // chunks of this wavefront: c = wave + 4 * ci, ci < nmy
     MxChunk<BF16> xh[PF][2];
+    auto load_x = [&](MxChunk<BF16>& ch, size_t koff, bool ok) {
+        if constexpr (SM)
+            smooth_load<BF16IN, 16>(ch.v, p.X, (size_t)row * p.ldx + koff, p.rg + koff, ok);
+        else
+            ch.load(p.X, (size_t)row * p.ldx + koff, ok);
+    };
 #pragma unroll
     for (int i = 0; i < PF; ++i)
 #pragma unroll
-        for (int hh = 0; hh < 2; ++hh)
-            xh[i][hh].load(p.X, (size_t)row * p.ldx + (size_t)(wave + 4 * i) * 128 + hh * 64 + q * 16, row_ok && i < nmy);
+        for (int hh = 0; hh < 2; ++hh) load_x(xh[i][hh], (size_t)(wave + 4 * i) * 128 + hh * 64 + q * 16, row_ok && i < nmy);
     // R fragments and their scale dwords: first chunk now, later ones one chunk ahead
     v8i bvs[2][NJA];
     int bss[2][NJA];
@@ -762,7 +786,7 @@ __global__ __launch_bounds__(256) void mxb_act_kernel(MxbActParams p)
         // refill the slot with the chunk PF positions further on
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh)
-            xh[sl][hh].load(p.X, (size_t)row * p.ldx + (size_t)(c + 4 * PF) * 128 + hh * 64 + q * 16, row_ok && ci + PF < nmy);
+            load_x(xh[sl][hh], (size_t)(c + 4 * PF) * 128 + hh * 64 + q * 16, row_ok && ci + PF < nmy);
     }
     }
     {   // padding 64-chunks of the last quad (at most one 128-chunk per wavefront): valid E8M0 bytes (2^0)
@@ -823,22 +847,27 @@ __global__ __launch_bounds__(256) void mxb_act_kernel(MxbActParams p)
     }
 }
 
-template <bool BF16, int NJB>
+template <bool BF16, int NJB, bool SM>
 static hipError_t mxb_act_launch(const MxbActParams& p, int64_t Mp, hipStream_t s)
 {
-    hipLaunchKernelGGL((mxb_act_kernel<BF16, NJB>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((mxb_act_kernel<BF16, NJB, SM>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
     return hipGetLastError();
+}
+template <bool BF16, bool SM>
+static hipError_t mxb_act_rank2(const MxbActParams& p, int64_t Mp, hipStream_t s)
+{
+    switch (p.r) {
+        case 0: return mxb_act_launch<BF16, 0, SM>(p, Mp, s);
+        case 32: return mxb_act_launch<BF16, 2, SM>(p, Mp, s);
+        case 64: return mxb_act_launch<BF16, 4, SM>(p, Mp, s);
+        case 96: return mxb_act_launch<BF16, 6, SM>(p, Mp, s);
+        default: return mxb_act_launch<BF16, 8, SM>(p, Mp, s);
+    }
 }
 template <bool BF16>
 static hipError_t mxb_act_rank(const MxbActParams& p, int64_t Mp, hipStream_t s)
 {
-    switch (p.r) {
-        case 0: return mxb_act_launch<BF16, 0>(p, Mp, s);
-        case 32: return mxb_act_launch<BF16, 2>(p, Mp, s);
-        case 64: return mxb_act_launch<BF16, 4>(p, Mp, s);
-        case 96: return mxb_act_launch<BF16, 6>(p, Mp, s);
-        default: return mxb_act_launch<BF16, 8>(p, Mp, s);
-    }
+    return p.rg ? mxb_act_rank2<BF16, true>(p, Mp, s) : mxb_act_rank2<BF16, false>(p, Mp, s);
 }
 
 static hipError_t launch_quantize_act_mxb(const Dims& d, int x_dtype, const uint8_t* packed, const void* X, int64_t M,
@@ -865,6 +894,7 @@ static hipError_t launch_quantize_act_mxb(const Dims& d, int x_dtype, const uint
     p.dbg_xb = dbg ? dbg->xb : nullptr;
     p.dbg_xbe = dbg ? dbg->xbe : nullptr;
     p.dbg_T = dbg ? dbg->T : nullptr;
+    p.rg = d.smooth ? (const float*)(packed + pl.off_rg) : nullptr;
     return x_dtype == LQ_BF16 ? mxb_act_rank<true>(p, al.Mp, s) : mxb_act_rank<false>(p, al.Mp, s);
 }
 

@@ -211,6 +211,7 @@ struct Mx6ActParams {
     int8_t* dbg_xb;
     uint8_t* dbg_xbe;
     float* dbg_T;
+    const float* rg;  // reciprocals of the smoothing vector (smoothing variant only)
 };
 
 template <bool BF16>
@@ -248,9 +249,11 @@ struct Mx6Block<false> {  // 32 fp32 values
     __device__ __forceinline__ float get(int i) const { return v[i]; }
 };
 
-template <bool BF16, int NJB>
+// BF16IN: element type of X; SM: smoothing variant (X times the stored reciprocals, held as fp32).
+template <bool BF16IN, int NJB, bool SM = false>
 __global__ __launch_bounds__(256) void mx6_act_kernel(Mx6ActParams p)
 {
+    constexpr bool BF16 = BF16IN && !SM;  // representation of a block in registers
     constexpr int NJA = NJB > 0 ? NJB : 1;
     constexpr int PF = 2;  // 128-chunks in flight per wavefront
     __shared__ float s_acc[4][NJA][64][4];
@@ -264,9 +267,14 @@ __global__ __launch_bounds__(256) void mx6_act_kernel(Mx6ActParams p)
     const int nmy = (C128 - wave + 3) >> 2;  // chunks of this wavefront: c = wave + 4 * ci, ci < nmy
 
     Mx6Block<BF16> xb[PF];
+    auto load_x = [&](Mx6Block<BF16>& blk, size_t koff, bool ok) {
+        if constexpr (SM)
+            smooth_load<BF16IN, 32>(blk.v, p.X, (size_t)row * p.ldx + koff, p.rg + koff, ok);
+        else
+            blk.load(p.X, (size_t)row * p.ldx + koff, ok);
+    };
 #pragma unroll
-    for (int i = 0; i < PF; ++i)
-        xb[i].load(p.X, (size_t)row * p.ldx + (size_t)(wave + 4 * i) * 128 + q * 32, row_ok && i < nmy);
+    for (int i = 0; i < PF; ++i) load_x(xb[i], (size_t)(wave + 4 * i) * 128 + q * 32, row_ok && i < nmy);
     v8i bvs[2][NJA];
     int bss[2][NJA];
     auto load_r = [&](int slot, int ci) {
@@ -348,7 +356,7 @@ __global__ __launch_bounds__(256) void mx6_act_kernel(Mx6ActParams p)
                                                                                 bss[sl & 1][jb]);
                 }
             }
-            xb[sl].load(p.X, (size_t)row * p.ldx + (size_t)(c + 4 * PF) * 128 + q * 32, row_ok && ci + PF < nmy);
+            load_x(xb[sl], (size_t)(c + 4 * PF) * 128 + q * 32, row_ok && ci + PF < nmy);
         }
     }
     {   // padding 64-chunks of the last quad (at most one 128-chunk per wavefront): valid E8M0 bytes (2^0)
@@ -407,22 +415,27 @@ __global__ __launch_bounds__(256) void mx6_act_kernel(Mx6ActParams p)
     }
 }
 
-template <bool BF16, int NJB>
+template <bool BF16, int NJB, bool SM>
 static hipError_t mx6_act_launch(const Mx6ActParams& p, int64_t Mp, hipStream_t s)
 {
-    hipLaunchKernelGGL((mx6_act_kernel<BF16, NJB>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((mx6_act_kernel<BF16, NJB, SM>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
     return hipGetLastError();
+}
+template <bool BF16, bool SM>
+static hipError_t mx6_act_rank2(const Mx6ActParams& p, int64_t Mp, hipStream_t s)
+{
+    switch (p.r) {
+        case 0: return mx6_act_launch<BF16, 0, SM>(p, Mp, s);
+        case 32: return mx6_act_launch<BF16, 2, SM>(p, Mp, s);
+        case 64: return mx6_act_launch<BF16, 4, SM>(p, Mp, s);
+        case 96: return mx6_act_launch<BF16, 6, SM>(p, Mp, s);
+        default: return mx6_act_launch<BF16, 8, SM>(p, Mp, s);
+    }
 }
 template <bool BF16>
 static hipError_t mx6_act_rank(const Mx6ActParams& p, int64_t Mp, hipStream_t s)
 {
-    switch (p.r) {
-        case 0: return mx6_act_launch<BF16, 0>(p, Mp, s);
-        case 32: return mx6_act_launch<BF16, 2>(p, Mp, s);
-        case 64: return mx6_act_launch<BF16, 4>(p, Mp, s);
-        case 96: return mx6_act_launch<BF16, 6>(p, Mp, s);
-        default: return mx6_act_launch<BF16, 8>(p, Mp, s);
-    }
+    return p.rg ? mx6_act_rank2<BF16, true>(p, Mp, s) : mx6_act_rank2<BF16, false>(p, Mp, s);
 }
 
 hipError_t launch_quantize_act_mx6(const Dims& d, int x_dtype, const uint8_t* packed, const void* X, int64_t M,
@@ -449,6 +462,7 @@ hipError_t launch_quantize_act_mx6(const Dims& d, int x_dtype, const uint8_t* pa
     p.dbg_xb = dbg ? dbg->xb : nullptr;
     p.dbg_xbe = dbg ? dbg->xbe : nullptr;
     p.dbg_T = dbg ? dbg->T : nullptr;
+    p.rg = d.smooth ? (const float*)(packed + pl.off_rg) : nullptr;
     return x_dtype == LQ_BF16 ? mx6_act_rank<true>(p, al.Mp, s) : mx6_act_rank<false>(p, al.Mp, s);
 }
 

@@ -164,6 +164,10 @@ hipError_t launch_pack_mxi(const Dims& d, int from_q, const float* W, const floa
     const int N = (int)d.N, K = (int)d.K;
     // scale bytes of the padding chunks of the last quad: 2^0
     const size_t pe_bytes = (size_t)(N / 32) * ((d.C64 + 3) / 4) * 256;
+    if (d.smooth) {  // reciprocals of the smoothing vector start at 1
+        const hipError_t e = launch_set_smoothing(d, nullptr, packed, s);
+        if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL(mxi_fill_kernel, dim3((unsigned)((pe_bytes + 255) / 256)), dim3(256), 0, s, pp.pe, pe_bytes,
                        (uint8_t)127);
     if (d.r > 0) {
@@ -271,6 +275,7 @@ struct MxiActParams {
     int8_t* dbg_xb;
     uint8_t* dbg_xbe;
     float* dbg_T;
+    const float* rg;  // reciprocals of the smoothing vector (smoothing variant only)
 };
 
 template <bool BF16>
@@ -328,9 +333,11 @@ __device__ __forceinline__ uint32_t bf16_pair(float lo, float hi)  // upper halv
     return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
 }
 
-template <bool BF16, int NJB>
+// BF16IN: element type of X; SM: smoothing variant (X times the stored reciprocals, held as fp32).
+template <bool BF16IN, int NJB, bool SM = false>
 __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
 {
+    constexpr bool BF16 = BF16IN && !SM;  // representation of a chunk in registers
     constexpr int NJA = NJB > 0 ? NJB : 1;
     constexpr int PF = 2;  // 64-chunks in flight per wavefront (measured: 2 beats 4, 6, 8 -- fewer registers, more resident workgroups)
     __shared__ float s_acc[4][NJA][64][4];
@@ -345,9 +352,14 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
     // No scale spans more than a block of 32, so the row is streamed: PF chunks are in flight, a slot
     // is refilled as soon as its chunk has been coded.
     MxiChunk<BF16> xc[PF];
+    auto load_x = [&](MxiChunk<BF16>& ch, size_t koff, bool ok) {
+        if constexpr (SM)
+            smooth_load<BF16IN, 16>(ch.v, p.X, (size_t)row * p.ldx + koff, p.rg + koff, ok);
+        else
+            ch.load(p.X, (size_t)row * p.ldx + koff, ok);
+    };
 #pragma unroll
-    for (int i = 0; i < PF; ++i)
-        xc[i].load(p.X, (size_t)row * p.ldx + (size_t)(wave + 4 * i) * 64 + kq * 16, row_ok && i < nmy);
+    for (int i = 0; i < PF; ++i) load_x(xc[i], (size_t)(wave + 4 * i) * 64 + kq * 16, row_ok && i < nmy);
     // dequantised R fragments (bf16): first chunk now, later ones one chunk ahead
     v4i bvs[2][NJA][2];
     auto load_r = [&](int slot, int ci) {
@@ -447,7 +459,7 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
             }
         }
         // refill the slot with the chunk PF positions further on
-        xc[sl].load(p.X, (size_t)row * p.ldx + (size_t)(c + 4 * PF) * 64 + kq * 16, row_ok && ci + PF < nmy);
+        load_x(xc[sl], (size_t)(c + 4 * PF) * 64 + kq * 16, row_ok && ci + PF < nmy);
     }
     }
     {   // padding chunk of the last quad (at most one per wavefront): its scale bytes must be valid E8M0 values (2^0)
@@ -500,22 +512,27 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
     }
 }
 
-template <bool BF16, int NJB>
+template <bool BF16, int NJB, bool SM>
 static hipError_t mxi_act_launch(const MxiActParams& p, int64_t Mp, hipStream_t s)
 {
-    hipLaunchKernelGGL((mxi_act_kernel<BF16, NJB>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((mxi_act_kernel<BF16, NJB, SM>), dim3((unsigned)(Mp / 16)), dim3(256), 0, s, p);
     return hipGetLastError();
+}
+template <bool BF16, bool SM>
+static hipError_t mxi_act_rank2(const MxiActParams& p, int64_t Mp, hipStream_t s)
+{
+    switch (p.r) {
+        case 0: return mxi_act_launch<BF16, 0, SM>(p, Mp, s);
+        case 32: return mxi_act_launch<BF16, 2, SM>(p, Mp, s);
+        case 64: return mxi_act_launch<BF16, 4, SM>(p, Mp, s);
+        case 96: return mxi_act_launch<BF16, 6, SM>(p, Mp, s);
+        default: return mxi_act_launch<BF16, 8, SM>(p, Mp, s);
+    }
 }
 template <bool BF16>
 static hipError_t mxi_act_rank(const MxiActParams& p, int64_t Mp, hipStream_t s)
 {
-    switch (p.r) {
-        case 0: return mxi_act_launch<BF16, 0>(p, Mp, s);
-        case 32: return mxi_act_launch<BF16, 2>(p, Mp, s);
-        case 64: return mxi_act_launch<BF16, 4>(p, Mp, s);
-        case 96: return mxi_act_launch<BF16, 6>(p, Mp, s);
-        default: return mxi_act_launch<BF16, 8>(p, Mp, s);
-    }
+    return p.rg ? mxi_act_rank2<BF16, true>(p, Mp, s) : mxi_act_rank2<BF16, false>(p, Mp, s);
 }
 
 hipError_t launch_quantize_act_mxi(const Dims& d, int x_dtype, const uint8_t* packed, const void* X, int64_t M,
@@ -540,6 +557,7 @@ hipError_t launch_quantize_act_mxi(const Dims& d, int x_dtype, const uint8_t* pa
     p.dbg_xb = dbg ? dbg->xb : nullptr;
     p.dbg_xbe = dbg ? dbg->xbe : nullptr;
     p.dbg_T = dbg ? dbg->T : nullptr;
+    p.rg = d.smooth ? (const float*)(packed + pl.off_rg) : nullptr;
     return x_dtype == LQ_BF16 ? mxi_act_rank<true>(p, al.Mp, s) : mxi_act_rank<false>(p, al.Mp, s);
 }
 

@@ -30,14 +30,18 @@ class GpuRun:
     fdbg: object = None
 
 
-def run_gpu(layer, X, W, L, R, debug=True, debug_acc=True):
+def run_gpu(layer, X, W, L, R, debug=True, debug_acc=True, gamma=None):
+    """gamma: smoothing vector (K fp32 values): the layer is packed with fused smoothing and the activation kernel
+    divides X by it."""
     from paper_2604_18117_amd import binding as lq
-    cfg = lq.config_for_layer(layer)
+    cfg = lq.config_for_layer(layer, smooth=gamma is not None)
     Wd = torch.from_numpy(W).cuda()
     Ld = torch.from_numpy(L).cuda() if layer.r else None
     Rd = torch.from_numpy(R).cuda() if layer.r else None
     Xd = to_dev_x(X, layer.x_dtype)
     packed = lq.lq_pack_weights(cfg, Wd, Ld, Rd)
+    if gamma is not None:
+        lq.lq_set_smoothing(cfg, packed, torch.from_numpy(np.ascontiguousarray(gamma, np.float32)).cuda())
     M = X.shape[0]
     if debug and layer.family in ("mx", "mxb", "mxi"):
         debug_acc = False

@@ -204,12 +204,16 @@ def test_smoothing_contract(lq):
     # the activation kernel needs the blob even without a branch
     sm0 = lq.make_config(128, 256, 0, smooth=True)
     assert raw.lq_quantize_act(C.byref(sm0), None, good, 64, 256, good, 1 << 20, None, None) == lq.LQ_ERR_NULL
-    # the smoothed row is held as fp32: K <= 2304; fused into the INT family only
+    # kernels that keep the row in registers hold the smoothed row as fp32: K <= 2304 (INT family, MXFP4 with the
+    # fp32-scaled FP8 branch); the streamed kernels of the block-scaled branches have no such limit
     big = lq.make_config(128, 4608, 32, smooth=True)
     assert raw.lq_packed_sizes(C.byref(big), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
-    mx = lq.make_config(128, 256, 32, "mx")
-    mx.flags = lq.LQ_FLAG_SMOOTH
-    assert raw.lq_packed_sizes(C.byref(mx), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    assert raw.lq_packed_sizes(C.byref(lq.make_config(128, 4608, 32, "mx", smooth=True)), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    for fam, bits in (("mx", 8), ("mxb", 8), ("mxb", 6), ("mxi", 8), ("mxi", 4)):
+        K = 2304 if fam == "mx" else 4608
+        a, b = lq.make_config(128, K, 32, fam, 32, bits, 8, smooth=True), lq.make_config(128, K, 32, fam, 32, bits, 8)
+        assert a.flags == lq.LQ_FLAG_SMOOTH
+        assert lq.lq_packed_sizes(a) == lq.lq_packed_sizes(b) + K * 4
 
 
 def test_bench_refuses_more_than_one_gpu():

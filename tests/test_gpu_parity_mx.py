@@ -29,10 +29,12 @@ def _run_oracle(oracle, layer, X, W, L, R):
     return pk, act
 
 
-def _compare(oracle, layer, X, W, L, R, rows=None):
+def _compare(oracle, layer, X, W, L, R, rows=None, gamma=None):
     """rows: None = compare everything, else the sampled token rows (oracle sees only those)."""
-    g = run_gpu(layer, X, W, L, R, debug=True, debug_acc=False)
+    g = run_gpu(layer, X, W, L, R, debug=True, debug_acc=False, gamma=gamma)
     Xo = X if rows is None else X[rows]
+    if gamma is not None:                       # fused smoothing: the oracle quantises the smoothed input
+        Xo = oracle.smooth(Xo, gamma)
     sel = slice(None) if rows is None else rows
     pk, act = _run_oracle(oracle, layer, Xo, W, L, R)
     f8 = _e4m3_table(oracle)
@@ -92,7 +94,7 @@ def _compare(oracle, layer, X, W, L, R, rows=None):
     assert flips.mean() <= 2e-3, f"bf16 flip rate {flips.mean()}"
     assert np.all(rel[~flips] <= 2e-3)
     assert np.all(rel[flips] <= 2.0 ** -7 * 1.01)      # a flip is exactly one bf16 ulp
-    g2 = run_gpu(layer, X, W, L, R, debug=False)
+    g2 = run_gpu(layer, X, W, L, R, debug=False, gamma=gamma)
     assert torch.equal(g2.Y, g.Y)
     return g
 

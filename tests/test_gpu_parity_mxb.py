@@ -22,9 +22,11 @@ pytestmark = pytest.mark.gpu
 E2M1 = np.array([0, .5, 1, 1.5, 2, 3, 4, 6, -0., -.5, -1, -1.5, -2, -3, -4, -6], np.float32)
 
 
-def _compare(oracle, layer, X, W, L, R, rows=None):
-    g = run_gpu(layer, X, W, L, R, debug=True, debug_acc=False)
+def _compare(oracle, layer, X, W, L, R, rows=None, gamma=None):
+    g = run_gpu(layer, X, W, L, R, debug=True, debug_acc=False, gamma=gamma)
     Xo = X if rows is None else X[rows]
+    if gamma is not None:                       # fused smoothing: the oracle quantises the smoothed input
+        Xo = oracle.smooth(Xo, gamma)
     sel = slice(None) if rows is None else rows
     r = layer.r
     elem = layer.br_w_bits                      # 8: E4M3 elements; 6: E2M3 elements
@@ -93,7 +95,7 @@ def _compare(oracle, layer, X, W, L, R, rows=None):
     assert flips.mean() <= 2e-3, f"bf16 flip rate {flips.mean()}"
     assert np.all(rel[~flips] <= 2e-3)
     assert np.all(rel[flips] <= 2.0 ** -7 * 1.01)
-    g2 = run_gpu(layer, X, W, L, R, debug=False)
+    g2 = run_gpu(layer, X, W, L, R, debug=False, gamma=gamma)
     assert torch.equal(g2.Y, g.Y)
     return g
 

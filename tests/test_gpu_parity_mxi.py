@@ -26,9 +26,11 @@ def _vals(oracle, codes, ebytes, bits):
     return (np.abs(codes.astype(np.float64)).reshape(rows, -1, 32) * oracle.mxint_scale(ebytes, bits)[:, :, None]).reshape(rows, -1)
 
 
-def _compare(oracle, layer, X, W, L, R, rows=None, exact=False):
-    g = run_gpu(layer, X, W, L, R, debug=True, debug_acc=False)
+def _compare(oracle, layer, X, W, L, R, rows=None, exact=False, gamma=None):
+    g = run_gpu(layer, X, W, L, R, debug=True, debug_acc=False, gamma=gamma)
     Xo = X if rows is None else X[rows]
+    if gamma is not None:                       # fused smoothing: the oracle quantises the smoothed input
+        Xo = oracle.smooth(Xo, gamma)
     sel = slice(None) if rows is None else rows
     r, bw = layer.r, layer.br_w_bits
     pk = oracle.pack_mxi(W, L if r else None, R if r else None, bw)
@@ -91,7 +93,7 @@ def _compare(oracle, layer, X, W, L, R, rows=None, exact=False):
     assert flips.mean() <= 2e-3, f"bf16 flip rate {flips.mean()}"
     assert np.all(rel[~flips] <= 2e-3)
     assert np.all(rel[flips] <= 2.0 ** -7 * 1.01)
-    g2 = run_gpu(layer, X, W, L, R, debug=False)
+    g2 = run_gpu(layer, X, W, L, R, debug=False, gamma=gamma)
     assert torch.equal(g2.Y, g.Y)
     return g
 

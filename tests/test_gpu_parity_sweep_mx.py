@@ -35,3 +35,28 @@ def test_seeded_shape_sweep(oracle, family):
             cmp(oracle, layer, X, W, L, R)
         except AssertionError as e:
             raise AssertionError(f"{family}: M={M} K={K} N={N} r={r} {xd}: {e}") from e
+
+
+@pytest.mark.parametrize("family", ["mx", "mxb8", "mxb6", "mxi8", "mxi4"])
+@pytest.mark.parametrize("M,K,N,r,xd", [(200, 1152, 320, 32, "bf16"), (77, 2304, 64, 64, "f32"), (33, 256, 64, 0, "bf16")])
+def test_fused_smoothing(oracle, family, M, K, N, r, xd):
+    """Activation smoothing (Section 3.4; App. A.1) fused into the MX families' activation kernels: the GPU gets the raw X
+    and the smoothing vector, the oracle quantises the smoothed input; same bars as without smoothing."""
+    base = wl.shrink(wl.LAYERS["c2_qkv"], M=M, K=K, N=N, r=r)           # outlier channels for the vector to tame
+    kw = dict(base.__dict__, x_dtype=xd, seed=M + K, g=32)
+    if family == "mx":
+        layer, cmp = wl.Layer(**dict(kw, family="mx", br_w_bits=8, br_a_bits=8)), t_mx._compare
+    elif family.startswith("mxb"):
+        e = int(family[-1])
+        layer, cmp = wl.Layer(**dict(kw, family="mxb", br_w_bits=e, br_a_bits=e)), t_mxb._compare
+    else:
+        layer, cmp = wl.Layer(**dict(kw, family="mxi", br_w_bits=int(family[-1]), br_a_bits=8)), t_mxi._compare
+    X, W, L, R = wl.make_inputs(layer)
+    gamma = wl.smoothing_vector(X, W)
+    Ws = (W.astype(np.float64) * gamma).astype(np.float32)            # the caller folds gamma into W before packing
+    cmp(oracle, layer, X, Ws, L, R, gamma=gamma)
+    # the vector did change the codes: the unsmoothed run differs
+    from tests.gpu_util import n, run_gpu
+    a = run_gpu(layer, X, Ws, L, R, debug=True, debug_acc=False)
+    b = run_gpu(layer, X, Ws, L, R, debug=True, debug_acc=False, gamma=gamma)
+    assert not np.array_equal(n(a.av.xq), n(b.av.xq))
