@@ -11,7 +11,9 @@
 // works on row l%16 and on the 16-value quarter l/16 of each 64-deep K chunk, which is
 // exactly the A-operand layout of v_mfma_i32_16x16x64_i8.  The 64-chunks of K are dealt
 // round-robin to the 4 wavefronts, so a whole row block lives in registers between the
-// amax pass and the quantisation pass: X is read from HBM once.
+// amax pass and the quantisation pass: X is read from HBM once.  Rows too long for that (MAXC = 0) are
+// streamed twice through a two-chunk ring instead: once for the amax, once for the codes (the second read
+// comes from the caches: a workgroup's 16 rows are at most a few hundred KB).
 #include "lq_internal.h"
 
 namespace lq {
@@ -136,16 +138,20 @@ __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
     const int C64 = p.C64;
     constexpr int njb = NJB;  // rank / 16
 
-    XChunk<BF16> xc[MAXC];
-#pragma unroll
-    for (int ci = 0; ci < MAXC; ++ci) {
+    constexpr bool STREAM = MAXC == 0;
+    constexpr int NS = STREAM ? 2 : MAXC;            // chunk slots in registers
+    const int nmy = (C64 - wave + 3) >> 2;           // chunks of this wavefront: c = wave + 4 * ci, ci < nmy
+    XChunk<BF16> xc[NS];
+    auto load_x = [&](XChunk<BF16>& ch, int ci) {
         const int c = wave + 4 * ci;
+        const size_t koff = (size_t)c * 64 + kq * 16;
         if constexpr (SM)
-            load_smoothed<BF16IN>(xc[ci], p.X, (size_t)row * p.ldx + (size_t)c * 64 + kq * 16,
-                                  p.rg + (size_t)(c < C64 ? c : 0) * 64 + kq * 16, row_ok && c < C64);
+            load_smoothed<BF16IN>(ch, p.X, (size_t)row * p.ldx + koff, p.rg + (c < C64 ? koff : 0), row_ok && c < C64);
         else
-            xc[ci].load(p.X, (size_t)row * p.ldx + (size_t)c * 64 + kq * 16, row_ok && c < C64);
-    }
+            ch.load(p.X, (size_t)row * p.ldx + koff, row_ok && c < C64);
+    };
+#pragma unroll
+    for (int ci = 0; ci < NS; ++ci) load_x(xc[ci], ci);
 
     // Operands that do not depend on X are requested now, so that their latency overlaps the
     // load of X: the Q2(R) fragments of this wavefront's first chunk (later chunks are fetched one
@@ -165,21 +171,34 @@ __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
 
     // ---- per-row amax -------------------------------------------------------------------
     float a = 0.f;
-    if constexpr (BF16) {
-        // |bf16| is monotonic in its low 15 bits: packed unsigned 16-bit max, two values per op
-        us2 m2 = {0, 0};
+    us2 m2 = {0, 0};  // |bf16| is monotonic in its low 15 bits: packed unsigned 16-bit max, two values per op
+    auto amax_chunk = [&](const XChunk<BF16>& ch) {
+        if constexpr (BF16) {
 #pragma unroll
-        for (int ci = 0; ci < MAXC; ++ci)
+            for (int d = 0; d < 8; ++d) m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, ch.w[d] & 0x7FFF7FFFu));
+        } else {
 #pragma unroll
-            for (int d = 0; d < 8; ++d)
-                m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, xc[ci].w[d] & 0x7FFF7FFFu));
-        const uint32_t mm = m2[0] > m2[1] ? m2[0] : m2[1];
-        a = __uint_as_float(mm << 16);
+            for (int i = 0; i < 16; ++i) a = fmaxf(a, fabsf(ch.get(i)));
+        }
+    };
+    if constexpr (STREAM) {
+        for (int ci0 = 0; ci0 < nmy; ci0 += 2) {
+#pragma unroll
+            for (int sl = 0; sl < 2; ++sl) {
+                amax_chunk(xc[sl]);               // (a slot past the end holds zeros)
+                load_x(xc[sl], ci0 + sl + 2);
+            }
+        }
+        // second pass: the ring starts over
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl) load_x(xc[sl], sl);
     } else {
 #pragma unroll
-        for (int ci = 0; ci < MAXC; ++ci)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) a = fmaxf(a, fabsf(xc[ci].get(i)));
+        for (int ci = 0; ci < NS; ++ci) amax_chunk(xc[ci]);
+    }
+    if constexpr (BF16) {
+        const uint32_t mm = m2[0] > m2[1] ? m2[0] : m2[1];
+        a = __uint_as_float(mm << 16);
     }
     a = fmaxf(a, __shfl_xor(a, 16, 64));
     a = fmaxf(a, __shfl_xor(a, 32, 64));
@@ -202,93 +221,107 @@ __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
     for (int jb = 0; jb < NJB; ++jb) acc[jb] = v4i{0, 0, 0, 0};
 
     const int rb = row >> 5;
-#pragma unroll
-    for (int ci = 0; ci < MAXC; ++ci) {
-        const int c = wave + 4 * ci;
-        if (ci + 1 < MAXC) load_rq(bv[(ci + 1) & 1], ci + 1);
-        if (c < C64) {  // wave-uniform
-            uint32_t pk[2] = {0u, 0u};
-            uint32_t xb4[4] = {0u, 0u, 0u, 0u};
-            if constexpr (GA) {
-                // block scale of this 64-chunk: amax over the lane's 16 values, then over the row's 4 lanes
-                float ac = 0.f;
-                if constexpr (BF16) {
-                    us2 m2 = {0, 0};
-#pragma unroll
-                    for (int d = 0; d < 8; ++d)
-                        m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, xc[ci].w[d] & 0x7FFF7FFFu));
-                    const uint32_t mm = m2[0] > m2[1] ? m2[0] : m2[1];
-                    ac = __uint_as_float(mm << 16);
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) ac = fmaxf(ac, fabsf(xc[ci].get(i)));
-                }
-                ac = fmaxf(ac, __shfl_xor(ac, 16, 64));
-                ac = fmaxf(ac, __shfl_xor(ac, 32, 64));
-                const uint32_t bits = sint4_scale(ac, &inv4);
-                if (kq == 0) {
-                    p.sxg[sxg_index(row, c, p.tiles128)] = bits;
-                    // row blocks of the last 128-row tile that do not exist: finite scales (the forward multiplies
-                    // them by zero)
-                    if (row + 32 >= p.Mp)
-                        for (int rr = row + 32; (rr >> 7) == (row >> 7); rr += 32) p.sxg[sxg_index(rr, c, p.tiles128)] = 0u;
-                }
-            }
+    // one 64-chunk: main codes (and the block scale with SINT4 blocks), branch codes, skinny contraction
+    auto code_chunk = [&](const XChunk<BF16>& ch, const int c, const int bslot) {
+        uint32_t pk[2] = {0u, 0u};
+        uint32_t xb4[4] = {0u, 0u, 0u, 0u};
+        if constexpr (GA) {
+            // block scale of this 64-chunk: amax over the lane's 16 values, then over the row's 4 lanes
+            float ac = 0.f;
             if constexpr (BF16) {
-                // Magnitudes: |x|*inv + 2^23 has the code in its low bits and 0x4B in its top byte;
-                // eight of them are summed at their nibble positions with shift-adds (the top
-                // bytes shifted by 0 and 4 add up to the constant removed first, the others leave
-                // the dword).  Signs: the high bytes of four bf16 values are gathered with one
-                // byte permute.  Branch codes: low bytes of x*invb + 1.5*2^23, gathered likewise.
+                us2 m2 = {0, 0};
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    uint32_t acc = 0u - 0xFB000000u;
-                    uint32_t tb[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float x = xc[ci].get(8 * h + e);
-                        float um = __fmul_rn(fabsf(x), inv4);
-                        if constexpr (GA) um = fminf(um, 7.0f);  // the stored scale may be smaller than amax / 7
-                        const uint32_t mb = __float_as_uint(__fadd_rn(um, 8388608.0f));
-                        const int sh = e < 4 ? 8 * e : 8 * ((e - 5) & 3) + 4;
-                        acc += mb << sh;
-                        tb[e] = rne_bits(__fmul_rn(x, invb));
-                    }
-                    const uint32_t* w = &xc[ci].w[4 * h];
-                    const uint32_t s03 = __builtin_amdgcn_perm(w[1], w[0], 0x07050301u);
-                    const uint32_t s47 = __builtin_amdgcn_perm(w[3], w[2], 0x07050301u);
-                    pk[h] = acc | (s03 & 0x80808080u) | ((s47 >> 4) & 0x08080808u);
-#pragma unroll
-                    for (int q = 0; q < 2; ++q) {
-                        const uint32_t p01 = __builtin_amdgcn_perm(tb[4 * q + 1], tb[4 * q], 0x0c0c0400u);
-                        const uint32_t p23 = __builtin_amdgcn_perm(tb[4 * q + 3], tb[4 * q + 2], 0x0c0c0400u);
-                        xb4[2 * h + q] = __builtin_amdgcn_perm(p23, p01, 0x05040100u);
-                    }
-                }
+                for (int d = 0; d < 8; ++d)
+                    m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, ch.w[d] & 0x7FFF7FFFu));
+                const uint32_t mm = m2[0] > m2[1] ? m2[0] : m2[1];
+                ac = __uint_as_float(mm << 16);
             } else {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    // main codes: magnitude from |x|, sign from x
-                    const float x = xc[ci].get(i);
+                for (int i = 0; i < 16; ++i) ac = fmaxf(ac, fabsf(ch.get(i)));
+            }
+            ac = fmaxf(ac, __shfl_xor(ac, 16, 64));
+            ac = fmaxf(ac, __shfl_xor(ac, 32, 64));
+            const uint32_t bits = sint4_scale(ac, &inv4);
+            if (kq == 0) {
+                p.sxg[sxg_index(row, c, p.tiles128)] = bits;
+                // row blocks of the last 128-row tile that do not exist: finite scales (the forward multiplies
+                // them by zero)
+                if (row + 32 >= p.Mp)
+                    for (int rr = row + 32; (rr >> 7) == (row >> 7); rr += 32) p.sxg[sxg_index(rr, c, p.tiles128)] = 0u;
+            }
+        }
+        if constexpr (BF16) {
+            // Magnitudes: |x|*inv + 2^23 has the code in its low bits and 0x4B in its top byte;
+            // eight of them are summed at their nibble positions with shift-adds (the top
+            // bytes shifted by 0 and 4 add up to the constant removed first, the others leave
+            // the dword).  Signs: the high bytes of four bf16 values are gathered with one
+            // byte permute.  Branch codes: low bytes of x*invb + 1.5*2^23, gathered likewise.
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                uint32_t acc = 0u - 0xFB000000u;
+                uint32_t tb[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float x = ch.get(8 * h + e);
                     float um = __fmul_rn(fabsf(x), inv4);
-                    if constexpr (GA) um = fminf(um, 7.0f);
-                    const uint32_t m = __float_as_uint(__fadd_rn(um, 8388608.0f)) & 7u;
-                    const uint32_t sgn = __float_as_uint(x) >> 31;
-                    pk[i >> 3] |= nib_put(i & 7, sgn, m);
-                    const uint32_t b = rne_bits(__fmul_rn(x, invb)) & 0xFFu;
-                    xb4[i >> 2] |= b << (8 * (i & 3));
+                    if constexpr (GA) um = fminf(um, 7.0f);  // the stored scale may be smaller than amax / 7
+                    const uint32_t mb = __float_as_uint(__fadd_rn(um, 8388608.0f));
+                    const int sh = e < 4 ? 8 * e : 8 * ((e - 5) & 3) + 4;
+                    acc += mb << sh;
+                    tb[e] = rne_bits(__fmul_rn(x, invb));
+                }
+                const uint32_t* w = &ch.w[4 * h];
+                const uint32_t s03 = __builtin_amdgcn_perm(w[1], w[0], 0x07050301u);
+                const uint32_t s47 = __builtin_amdgcn_perm(w[3], w[2], 0x07050301u);
+                pk[h] = acc | (s03 & 0x80808080u) | ((s47 >> 4) & 0x08080808u);
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const uint32_t p01 = __builtin_amdgcn_perm(tb[4 * q + 1], tb[4 * q], 0x0c0c0400u);
+                    const uint32_t p23 = __builtin_amdgcn_perm(tb[4 * q + 3], tb[4 * q + 2], 0x0c0c0400u);
+                    xb4[2 * h + q] = __builtin_amdgcn_perm(p23, p01, 0x05040100u);
                 }
             }
-            uint8_t* dst = p.xq + ((size_t)((size_t)rb * C64 + c) * 64 + (row & 31) + 32 * (kq >> 1)) * 16 + (kq & 1) * 8;
-            *(uint2*)dst = make_uint2(pk[0], pk[1]);
-            if (p.dbg_xb && row_ok)
-                *(v4i*)(p.dbg_xb + (size_t)row * p.K + c * 64 + kq * 16) = v4i{(int)xb4[0], (int)xb4[1], (int)xb4[2], (int)xb4[3]};
-            if (njb > 0) {
-                const v4i av = {(int)xb4[0], (int)xb4[1], (int)xb4[2], (int)xb4[3]};
+        } else {
 #pragma unroll
-                for (int jb = 0; jb < NJB; ++jb)
-                    acc[jb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bv[ci & 1][jb], acc[jb], 0, 0, 0);
+            for (int i = 0; i < 16; ++i) {
+                // main codes: magnitude from |x|, sign from x
+                const float x = ch.get(i);
+                float um = __fmul_rn(fabsf(x), inv4);
+                if constexpr (GA) um = fminf(um, 7.0f);
+                const uint32_t m = __float_as_uint(__fadd_rn(um, 8388608.0f)) & 7u;
+                const uint32_t sgn = __float_as_uint(x) >> 31;
+                pk[i >> 3] |= nib_put(i & 7, sgn, m);
+                const uint32_t b = rne_bits(__fmul_rn(x, invb)) & 0xFFu;
+                xb4[i >> 2] |= b << (8 * (i & 3));
             }
+        }
+        uint8_t* dst = p.xq + ((size_t)((size_t)rb * C64 + c) * 64 + (row & 31) + 32 * (kq >> 1)) * 16 + (kq & 1) * 8;
+        *(uint2*)dst = make_uint2(pk[0], pk[1]);
+        if (p.dbg_xb && row_ok)
+            *(v4i*)(p.dbg_xb + (size_t)row * p.K + c * 64 + kq * 16) = v4i{(int)xb4[0], (int)xb4[1], (int)xb4[2], (int)xb4[3]};
+        if (njb > 0) {
+            const v4i av = {(int)xb4[0], (int)xb4[1], (int)xb4[2], (int)xb4[3]};
+#pragma unroll
+            for (int jb = 0; jb < NJB; ++jb)
+                acc[jb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bv[bslot][jb], acc[jb], 0, 0, 0);
+        }
+    };
+    if constexpr (STREAM) {
+        for (int ci0 = 0; ci0 < nmy; ci0 += 2) {
+#pragma unroll
+            for (int sl = 0; sl < 2; ++sl) {
+                const int ci = ci0 + sl, c = wave + 4 * ci;
+                load_rq(bv[(sl + 1) & 1], ci + 1);
+                if (c < C64) code_chunk(xc[sl], c, sl);  // wave-uniform
+                load_x(xc[sl], ci + 2);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int ci = 0; ci < NS; ++ci) {
+            const int c = wave + 4 * ci;
+            if (ci + 1 < NS) load_rq(bv[(ci + 1) & 1], ci + 1);
+            if (c < C64) code_chunk(xc[ci], c, ci & 1);  // wave-uniform
         }
     }
     if (njb == 0) return;
@@ -398,17 +431,22 @@ hipError_t launch_quantize_act_int(const Dims& d, int x_dtype, const uint8_t* pa
     p.dbg_T = dbg ? dbg->T : nullptr;
     p.rg = (const float*)(packed + pl.off_rg);
     const int maxc = (d.C64 + 3) / 4;
-    if (d.smooth) {  // K <= 2304: at most 9 chunks per wavefront
-        if (x_dtype == LQ_BF16) return maxc <= 5 ? launch_rank<true, 5, true>(p, al.Mp, s) : launch_rank<true, 9, true>(p, al.Mp, s);
-        return maxc <= 5 ? launch_rank<false, 5, true>(p, al.Mp, s) : launch_rank<false, 9, true>(p, al.Mp, s);
+    // MAXC = 0: the streamed kernel, for rows that do not fit in registers (fp32 representation: beyond 9 chunks per
+    // wavefront, K > 2304; bf16: beyond 18, K > 4608)
+    if (d.smooth) {
+        if (x_dtype == LQ_BF16)
+            return maxc <= 5 ? launch_rank<true, 5, true>(p, al.Mp, s) : maxc <= 9 ? launch_rank<true, 9, true>(p, al.Mp, s) : launch_rank<true, 0, true>(p, al.Mp, s);
+        return maxc <= 5 ? launch_rank<false, 5, true>(p, al.Mp, s) : maxc <= 9 ? launch_rank<false, 9, true>(p, al.Mp, s) : launch_rank<false, 0, true>(p, al.Mp, s);
     }
     if (x_dtype == LQ_BF16) {
         if (maxc <= 5) return launch_rank<true, 5>(p, al.Mp, s);
         if (maxc <= 9) return launch_rank<true, 9>(p, al.Mp, s);
-        return launch_rank<true, 18>(p, al.Mp, s);
+        if (maxc <= 18) return launch_rank<true, 18>(p, al.Mp, s);
+        return launch_rank<true, 0>(p, al.Mp, s);
     }
     if (maxc <= 5) return launch_rank<false, 5>(p, al.Mp, s);
-    return launch_rank<false, 9>(p, al.Mp, s);
+    if (maxc <= 9) return launch_rank<false, 9>(p, al.Mp, s);
+    return launch_rank<false, 0>(p, al.Mp, s);
 }
 
 }  // namespace lq

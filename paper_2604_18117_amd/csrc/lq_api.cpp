@@ -47,7 +47,6 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         if (r == 96) return LQ_ERR_SHAPE;  // rank 96 (a 6-bit budget of 512 bits per channel, padded) only with block-scaled branches
         const int qw = int_qmax(cfg->br_w), qa = int_qmax(cfg->br_a);
         if (qw == 0 || qa == 0 || cfg->br_a == LQ_INT4) return LQ_ERR_UNSUPPORTED;
-        if (d->smooth && cfg->K > 2304) return LQ_ERR_UNSUPPORTED;  // the smoothed row is held as fp32
         d->mx = false;
         d->g = cfg->main_w_group;
         d->qmax_bw = qw;
@@ -213,8 +212,8 @@ lq_status lq_quantize_act(const lq_config* cfg, const void* packed, const void* 
         return LQ_ERR_ALIGN;
     if (act_bytes < act_layout(d, M).total) return LQ_ERR_BUFFER_TOO_SMALL;
     const int maxc = (d.C64 + 3) / 4;
-    if (!d.mxi && !d.mxb && maxc > (cfg->x_dtype == LQ_BF16 ? 18 : 9))
-        return LQ_ERR_UNSUPPORTED;  // K beyond the register-resident row
+    if (d.mx && !d.mxb && maxc > (cfg->x_dtype == LQ_BF16 ? 18 : 9))
+        return LQ_ERR_UNSUPPORTED;  // MXFP4 with the fp32-scaled FP8 branch: K beyond the register-resident row
     hipError_t e = d.mxi ? launch_quantize_act_mxi(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,
                                                    (hipStream_t)stream)
                    : d.mx ? launch_quantize_act_mx(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,

@@ -269,3 +269,27 @@ def test_seeded_shape_sweep_bit_exact(oracle):
             _compare_all(oracle, layer, X, W, L, R)
         except AssertionError as e:
             raise AssertionError(f"shape M={M} K={K} N={N} r={r} g={g} ag={ag} bw={bw} ba={ba} {xd}: {e}") from e
+
+
+@pytest.mark.parametrize("M,K,N,r,xd,ag,sm", [(40, 5632, 64, 32, "bf16", 0, False),    # a 5600-wide input padded to 64s
+                                               (33, 2368, 64, 16, "f32", 0, False),     # fp32 rows beyond 2304
+                                               (50, 4672, 128, 64, "bf16", 0, True),    # smoothing on a long row
+                                               (20, 3072, 64, 32, "f32", 64, True),     # ... with SINT4 blocks
+                                               (17, 8192, 64, 128, "bf16", 0, False)])
+def test_long_rows_are_streamed(oracle, M, K, N, r, xd, ag, sm):
+    """Rows that do not fit the register-resident kernel go through the two-pass streamed one: same bits."""
+    import torch
+    from paper_2604_18117_amd import binding as lq
+    from tests.gpu_util import to_dev_x
+    layer = wl.Layer("t", M, K, N, r, "int", 64, 8, 8, xd, outlier_scale=15.0, n_outliers=8, seed=K, a_group=ag)
+    X, W, L, R = wl.make_inputs(layer)
+    if not sm:
+        _compare_all(oracle, layer, X, W, L, R)
+        return
+    gamma = wl.smoothing_vector(X, W)
+    g = run_gpu(layer, X, W, L, R, debug=True, debug_acc=False, gamma=gamma)
+    pk, act, out = run_oracle_int(oracle, layer, oracle.smooth(X, gamma), W, L, R, want_acc=False)
+    assert np.array_equal(n(g.av.xq), act.xq) and np.array_equal(n(g.av.sx), act.sx)
+    assert np.array_equal(n(g.adbg.xb), act.xb) and np.array_equal(n(g.adbg.accT), act.accT)
+    assert np.array_equal(n(g.av.tq), act.tq) and np.array_equal(n(g.av.st), act.st)
+    assert np.array_equal(n(g.fdbg.y32), out.y32) and np.array_equal(bf16_to_bits(g.Y), out.Y)
