@@ -97,8 +97,7 @@ typedef struct {
 /* Activation smoothing (Section 3.4; App. A.1): the activation kernel multiplies channel k of X by
    1 / gamma[k] before anything else, for both branches (the caller has folded gamma into the columns of
    W before calibration and packing).  All families; gamma is set with lq_set_smoothing after
-   lq_pack_weights.  With this flag K <= 2304 for MXFP4 with the fp32-scaled FP8 branch (its kernel keeps the
-   row, then as fp32, in registers); the other families have no limit. */
+   lq_pack_weights. */
 #define LQ_FLAG_SMOOTH 1
 
 /* Optional parity taps.  Every member may be NULL.  Device pointers, plain row-major. */

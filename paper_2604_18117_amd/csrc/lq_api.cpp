@@ -60,7 +60,6 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         if (cfg->K % 128 != 0) return LQ_ERR_SHAPE;  // the MX forward stages K in steps of 128
         d->mxb = cfg->br_w != LQ_FP8_E4M3;
         if (!d->mxb && r == 96) return LQ_ERR_SHAPE;
-        if (!d->mxb && d->smooth && cfg->K > 2304) return LQ_ERR_UNSUPPORTED;  // row-resident kernel: the smoothed row is fp32
         d->mxb_elem = cfg->br_w == LQ_MXFP8_E4M3 ? 8 : cfg->br_w == LQ_MXFP6_E2M3 ? 6 : 0;
         if (d->mxb && r % 32 != 0) return LQ_ERR_SHAPE;  // whole blocks of 32 along the rank
         d->mx = true;
@@ -211,9 +210,6 @@ lq_status lq_quantize_act(const lq_config* cfg, const void* packed, const void* 
     if (!aligned(X, 16) || (ldx * es) % 16 != 0 || !aligned(act, 256) || (packed && !aligned(packed, 256)))
         return LQ_ERR_ALIGN;
     if (act_bytes < act_layout(d, M).total) return LQ_ERR_BUFFER_TOO_SMALL;
-    const int maxc = (d.C64 + 3) / 4;
-    if (d.mx && !d.mxb && maxc > (cfg->x_dtype == LQ_BF16 ? 18 : 9))
-        return LQ_ERR_UNSUPPORTED;  // MXFP4 with the fp32-scaled FP8 branch: K beyond the register-resident row
     hipError_t e = d.mxi ? launch_quantize_act_mxi(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,
                                                    (hipStream_t)stream)
                    : d.mx ? launch_quantize_act_mx(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,

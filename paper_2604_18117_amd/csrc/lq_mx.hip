@@ -442,16 +442,22 @@ __global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
     const bool row_ok = row < p.M;
     const int C64 = p.C64;
 
-    MxChunk<BF16> xc[MAXC];
-#pragma unroll
-    for (int ci = 0; ci < MAXC; ++ci) {
+    // MAXC = 0: rows too long for the registers are streamed twice through a two-chunk ring (amax pass, coding pass;
+    // the second read comes from the caches)
+    constexpr bool STREAM = MAXC == 0;
+    constexpr int NS = STREAM ? 2 : MAXC;   // chunk slots in registers
+    const int nmy = (C64 - wave + 3) >> 2;  // chunks of this wavefront: c = wave + 4 * ci, ci < nmy
+    MxChunk<BF16> xc[NS];
+    auto load_x = [&](MxChunk<BF16>& ch, int ci) {
         const int c = wave + 4 * ci;
         const size_t koff = (size_t)c * 64 + kq * 16;
         if constexpr (SM)
-            smooth_load<BF16IN, 16>(xc[ci].v, p.X, (size_t)row * p.ldx + koff, p.rg + koff, row_ok && c < C64);
+            smooth_load<BF16IN, 16>(ch.v, p.X, (size_t)row * p.ldx + koff, p.rg + koff, row_ok && c < C64);
         else
-            xc[ci].load(p.X, (size_t)row * p.ldx + koff, row_ok && c < C64);
-    }
+            ch.load(p.X, (size_t)row * p.ldx + koff, row_ok && c < C64);
+    };
+#pragma unroll
+    for (int ci = 0; ci < NS; ++ci) load_x(xc[ci], ci);
 
     // Operands that do not depend on X are requested now (their latency overlaps the load of X):
     // the Q2(R) fragments of the first chunk (later ones one chunk ahead, in the loop), R's scales.
@@ -468,25 +474,40 @@ __global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
 #pragma unroll
     for (int jb = 0; jb < NJB; ++jb) srj[jb] = p.sr[jb * 16 + r16];
 
-    // amax of the lane's 16 values per chunk (reused for the block scale) and of the whole row
-    float a16[MAXC];
-    float a = 0.f;
-#pragma unroll
-    for (int ci = 0; ci < MAXC; ++ci) {
-        float m = 0.f;
+    // amax of the lane's 16 values per chunk (kept for the block scale when the row is resident) and of the whole row
+    auto amax16 = [&](const MxChunk<BF16>& ch) -> float {
         if constexpr (BF16) {
             // |bf16| is monotonic in its low 15 bits: packed unsigned 16-bit max, two values per op
             us2 m2 = {0, 0};
 #pragma unroll
-            for (int d = 0; d < 8; ++d) m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, xc[ci].w[d] & 0x7FFF7FFFu));
+            for (int d = 0; d < 8; ++d) m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, ch.w[d] & 0x7FFF7FFFu));
             const uint32_t mm = m2[0] > m2[1] ? m2[0] : m2[1];
-            m = __uint_as_float(mm << 16);
+            return __uint_as_float(mm << 16);
         } else {
+            float m = 0.f;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(xc[ci].get(i)));
+            for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(ch.get(i)));
+            return m;
         }
-        a16[ci] = m;
-        a = fmaxf(a, m);
+    };
+    float a16[NS];
+    float a = 0.f;
+    if constexpr (STREAM) {
+        for (int ci0 = 0; ci0 < nmy; ci0 += 2) {
+#pragma unroll
+            for (int sl = 0; sl < 2; ++sl) {
+                a = fmaxf(a, amax16(xc[sl]));  // (a slot past the end holds zeros)
+                load_x(xc[sl], ci0 + sl + 2);
+            }
+        }
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl) load_x(xc[sl], sl);  // second pass: the ring starts over
+    } else {
+#pragma unroll
+        for (int ci = 0; ci < NS; ++ci) {
+            a16[ci] = amax16(xc[ci]);
+            a = fmaxf(a, a16[ci]);
+        }
     }
     a = fmaxf(a, __shfl_xor(a, 16, 64));
     a = fmaxf(a, __shfl_xor(a, 32, 64));
@@ -505,46 +526,62 @@ __global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
 #pragma unroll
     for (int jb = 0; jb < NJB; ++jb) acc[jb] = v4f{0.f, 0.f, 0.f, 0.f};
 
-#pragma unroll
-    for (int ci = 0; ci < MAXC; ++ci) {
-        const int c = wave + 4 * ci;
-        if (ci + 1 < MAXC) load_r8(bvs[(ci + 1) & 1], ci + 1);
-        if (c < C64) {  // wave-uniform
-            // MXFP4: block of 32 = this lane's 16 values and its neighbour's (kq ^ 1)
-            const float ab = fmaxf(a16[ci], __shfl_xor(a16[ci], 16, 64));
-            const uint32_t E = e8m0_of(ab);
-            const float sc = e8m0_value(E);
-            uint32_t pk[2] = {0u, 0u};
-            uint32_t x8[4];
-#define LQ_CVT4(J) pk[(J) >> 2] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(pk[(J) >> 2], xc[ci].get(2 * (J)), xc[ci].get(2 * (J) + 1), sc, (J) & 3)
-            if (ab != 0.0f) {
-                LQ_CVT4(0); LQ_CVT4(1); LQ_CVT4(2); LQ_CVT4(3); LQ_CVT4(4); LQ_CVT4(5); LQ_CVT4(6); LQ_CVT4(7);
-            }
+    // one 64-chunk: MXFP4 codes and block scales, FP8 branch codes, skinny contraction (am: amax of the lane's 16 values)
+    auto code_chunk = [&](const MxChunk<BF16>& ch, const int c, const float am, const int bslot) {
+        // MXFP4: block of 32 = this lane's 16 values and its neighbour's (kq ^ 1)
+        const float ab = fmaxf(am, __shfl_xor(am, 16, 64));
+        const uint32_t E = e8m0_of(ab);
+        const float sc = e8m0_value(E);
+        uint32_t pk[2] = {0u, 0u};
+        uint32_t x8[4];
+#define LQ_CVT4(J) pk[(J) >> 2] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(pk[(J) >> 2], ch.get(2 * (J)), ch.get(2 * (J) + 1), sc, (J) & 3)
+        if (ab != 0.0f) {
+            LQ_CVT4(0); LQ_CVT4(1); LQ_CVT4(2); LQ_CVT4(3); LQ_CVT4(4); LQ_CVT4(5); LQ_CVT4(6); LQ_CVT4(7);
+        }
 #undef LQ_CVT4
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                x8[q] = fp8_quad(__fmul_rn(xc[ci].get(4 * q), invb), __fmul_rn(xc[ci].get(4 * q + 1), invb),
-                                 __fmul_rn(xc[ci].get(4 * q + 2), invb), __fmul_rn(xc[ci].get(4 * q + 3), invb));
-            uint8_t* dst = p.xc + ((size_t)((size_t)(row >> 5) * C64 + c) * 64 + (row & 31) + 32 * (kq >> 1)) * 16 + (kq & 1) * 8;
-            *(uint2*)dst = make_uint2(pk[0], pk[1]);
-            if ((kq & 1) == 0) p.xe[mx_scale_offset(row, c, kq >> 1, p.CQ)] = (uint8_t)E;
-            if (p.dbg_xb && row_ok)
-                *(v4i*)(p.dbg_xb + (size_t)row * p.K + c * 64 + kq * 16) = v4i{(int)x8[0], (int)x8[1], (int)x8[2], (int)x8[3]};
-            if (NJB > 0) {
-                const long alo = (long)(((unsigned long)x8[1] << 32) | x8[0]);
-                const long ahi = (long)(((unsigned long)x8[3] << 32) | x8[2]);
+        for (int q = 0; q < 4; ++q)
+            x8[q] = fp8_quad(__fmul_rn(ch.get(4 * q), invb), __fmul_rn(ch.get(4 * q + 1), invb),
+                             __fmul_rn(ch.get(4 * q + 2), invb), __fmul_rn(ch.get(4 * q + 3), invb));
+        uint8_t* dst = p.xc + ((size_t)((size_t)(row >> 5) * C64 + c) * 64 + (row & 31) + 32 * (kq >> 1)) * 16 + (kq & 1) * 8;
+        *(uint2*)dst = make_uint2(pk[0], pk[1]);
+        if ((kq & 1) == 0) p.xe[mx_scale_offset(row, c, kq >> 1, p.CQ)] = (uint8_t)E;
+        if (p.dbg_xb && row_ok)
+            *(v4i*)(p.dbg_xb + (size_t)row * p.K + c * 64 + kq * 16) = v4i{(int)x8[0], (int)x8[1], (int)x8[2], (int)x8[3]};
+        if (NJB > 0) {
+            const long alo = (long)(((unsigned long)x8[1] << 32) | x8[0]);
+            const long ahi = (long)(((unsigned long)x8[3] << 32) | x8[2]);
 #pragma unroll
-                for (int jb = 0; jb < NJB; ++jb) {
-                    const v4i bv = bvs[ci & 1][jb];
-                    const long blo = (long)(((unsigned long)(uint32_t)bv[1] << 32) | (uint32_t)bv[0]);
-                    const long bhi = (long)(((unsigned long)(uint32_t)bv[3] << 32) | (uint32_t)bv[2]);
-                    acc[jb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(alo, blo, acc[jb], 0, 0, 0);
-                    acc[jb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(ahi, bhi, acc[jb], 0, 0, 0);
-                }
+            for (int jb = 0; jb < NJB; ++jb) {
+                const v4i bv = bvs[bslot][jb];
+                const long blo = (long)(((unsigned long)(uint32_t)bv[1] << 32) | (uint32_t)bv[0]);
+                const long bhi = (long)(((unsigned long)(uint32_t)bv[3] << 32) | (uint32_t)bv[2]);
+                acc[jb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(alo, blo, acc[jb], 0, 0, 0);
+                acc[jb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(ahi, bhi, acc[jb], 0, 0, 0);
             }
-        } else if (c < 4 * p.CQ) {
-            // padding chunk of the last quad: its scale bytes must be valid E8M0 values (2^0)
-            if ((kq & 1) == 0) p.xe[mx_scale_offset(row, c, kq >> 1, p.CQ)] = (uint8_t)127;
+        }
+    };
+    auto pad_chunk = [&](const int c) {  // padding chunk of the last quad: its scale bytes must be valid E8M0 values (2^0)
+        if (c >= C64 && c < 4 * p.CQ && (kq & 1) == 0) p.xe[mx_scale_offset(row, c, kq >> 1, p.CQ)] = (uint8_t)127;
+    };
+    if constexpr (STREAM) {
+        for (int ci0 = 0; ci0 < nmy; ci0 += 2) {
+#pragma unroll
+            for (int sl = 0; sl < 2; ++sl) {
+                const int ci = ci0 + sl, c = wave + 4 * ci;
+                load_r8(bvs[(sl + 1) & 1], ci + 1);
+                if (c < C64) code_chunk(xc[sl], c, amax16(xc[sl]), sl);  // wave-uniform
+                load_x(xc[sl], ci + 2);
+            }
+        }
+        pad_chunk(wave + 4 * nmy);
+    } else {
+#pragma unroll
+        for (int ci = 0; ci < NS; ++ci) {
+            const int c = wave + 4 * ci;
+            if (ci + 1 < NS) load_r8(bvs[(ci + 1) & 1], ci + 1);
+            if (c < C64) code_chunk(xc[ci], c, a16[ci], ci & 1);  // wave-uniform
+            else pad_chunk(c);
         }
     }
     if (NJB == 0) return;
@@ -640,17 +677,21 @@ hipError_t launch_quantize_act_mx(const Dims& d, int x_dtype, const uint8_t* pac
     p.dbg_T = dbg ? dbg->T : nullptr;
     const int maxc = (d.C64 + 3) / 4;
     p.rg = d.smooth ? (const float*)(packed + pl.off_rg) : nullptr;
-    if (d.smooth) {  // K <= 2304: the smoothed row is held as fp32, at most 9 chunks per wavefront
-        if (x_dtype == LQ_BF16) return maxc <= 5 ? mx_act_rank<true, 5, true>(p, al.Mp, s) : mx_act_rank<true, 9, true>(p, al.Mp, s);
-        return maxc <= 5 ? mx_act_rank<false, 5, true>(p, al.Mp, s) : mx_act_rank<false, 9, true>(p, al.Mp, s);
+    // MAXC = 0: the streamed form, for rows that do not fit in registers (fp32 representation: K > 2304; bf16: K > 4608)
+    if (d.smooth) {
+        if (x_dtype == LQ_BF16)
+            return maxc <= 5 ? mx_act_rank<true, 5, true>(p, al.Mp, s) : maxc <= 9 ? mx_act_rank<true, 9, true>(p, al.Mp, s) : mx_act_rank<true, 0, true>(p, al.Mp, s);
+        return maxc <= 5 ? mx_act_rank<false, 5, true>(p, al.Mp, s) : maxc <= 9 ? mx_act_rank<false, 9, true>(p, al.Mp, s) : mx_act_rank<false, 0, true>(p, al.Mp, s);
     }
     if (x_dtype == LQ_BF16) {
         if (maxc <= 5) return mx_act_rank<true, 5>(p, al.Mp, s);
         if (maxc <= 9) return mx_act_rank<true, 9>(p, al.Mp, s);
-        return mx_act_rank<true, 18>(p, al.Mp, s);
+        if (maxc <= 18) return mx_act_rank<true, 18>(p, al.Mp, s);
+        return mx_act_rank<true, 0>(p, al.Mp, s);
     }
     if (maxc <= 5) return mx_act_rank<false, 5>(p, al.Mp, s);
-    return mx_act_rank<false, 9>(p, al.Mp, s);
+    if (maxc <= 9) return mx_act_rank<false, 9>(p, al.Mp, s);
+    return mx_act_rank<false, 0>(p, al.Mp, s);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -149,12 +149,12 @@ def test_argument_errors_before_any_launch(lq):
     assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, good, 64, odd, 128, None, None) == lq.LQ_ERR_ALIGN
     assert raw.lq_unpack_weights(C.byref(cfg), None, None, None) == lq.LQ_ERR_NULL
     assert raw.lq_unpack_act(C.byref(cfg), good, 0, None, None) == lq.LQ_ERR_NULL
-    # K beyond the register-resident row of the activation kernel: only MXFP4 with the fp32-scaled FP8 branch has no
-    # streamed kernel (the INT family streams long rows twice; a wrong row stride is still caught first)
-    big = _cfg(lq, K=8192, family="mx")
-    assert raw.lq_quantize_act(C.byref(big), good, good, 64, 8192, good, 1 << 30, None, None) == lq.LQ_ERR_UNSUPPORTED
-    big = _cfg(lq, K=8192)
-    assert raw.lq_quantize_act(C.byref(big), good, good, 64, 8000, good, 1 << 30, None, None) == lq.LQ_ERR_SHAPE
+    # K beyond the register-resident row of the activation kernels is accepted (long rows are streamed); a wrong row
+    # stride is still caught first
+    for fam in ("int", "mx"):
+        big = _cfg(lq, K=8192, family=fam, group=64 if fam == "int" else 32)
+        assert raw.lq_act_sizes(C.byref(big), 64, C.byref(C.c_size_t(0))) == lq.LQ_OK
+        assert raw.lq_quantize_act(C.byref(big), good, good, 64, 8000, good, 1 << 30, None, None) == lq.LQ_ERR_SHAPE
 
 
 def test_mxi_contract(lq):
@@ -205,12 +205,10 @@ def test_smoothing_contract(lq):
     # the activation kernel needs the blob even without a branch
     sm0 = lq.make_config(128, 256, 0, smooth=True)
     assert raw.lq_quantize_act(C.byref(sm0), None, good, 64, 256, good, 1 << 20, None, None) == lq.LQ_ERR_NULL
-    # the one kernel without a streamed form keeps the smoothed row as fp32 in registers: K <= 2304 for MXFP4 with the
-    # fp32-scaled FP8 branch; every other family streams long rows
+    # no K limit with smoothing either (long rows are streamed)
     assert raw.lq_packed_sizes(C.byref(lq.make_config(128, 4608, 32, smooth=True)), C.byref(n)) == lq.LQ_OK
-    assert raw.lq_packed_sizes(C.byref(lq.make_config(128, 4608, 32, "mx", smooth=True)), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
     for fam, bits in (("mx", 8), ("mxb", 8), ("mxb", 6), ("mxi", 8), ("mxi", 4)):
-        K = 2304 if fam == "mx" else 4608
+        K = 4608
         a, b = lq.make_config(128, K, 32, fam, 32, bits, 8, smooth=True), lq.make_config(128, K, 32, fam, 32, bits, 8)
         assert a.flags == lq.LQ_FLAG_SMOOTH
         assert lq.lq_packed_sizes(a) == lq.lq_packed_sizes(b) + K * 4

@@ -148,3 +148,12 @@ def test_full_size_sampled_rows(oracle, name):
     rng = np.random.default_rng(1)
     rows = np.sort(np.concatenate([[0, layer.M - 1], rng.choice(layer.M, 14, replace=False)]))
     _compare(oracle, layer, X, W, L, R, rows=rows)
+
+
+@pytest.mark.parametrize("M,K,N,r,xd,sm", [(40, 5632, 64, 32, "bf16", False), (33, 2432, 64, 16, "f32", False),
+                                            (50, 4736, 128, 64, "bf16", True), (17, 8192, 64, 128, "bf16", False)])
+def test_long_rows_are_streamed(oracle, M, K, N, r, xd, sm):
+    """Rows that do not fit the register-resident activation kernel go through the two-pass streamed form."""
+    layer = wl.Layer("t", M, K, N, r, "mx", 32, 8, 8, xd, outlier_scale=10.0, n_outliers=8, seed=K)
+    X, W, L, R = wl.make_inputs(layer)
+    _compare(oracle, layer, X, W, L, R, gamma=wl.smoothing_vector(X, W) if sm else None)
