@@ -19,7 +19,7 @@
  *         With main_a_group = 64 (and main_w_group = 64) both operands of the main product use the
  *         literal SINT4 block format of App. A.3: blocks of 64 values along K, one FP16 scale per
  *         block, s = fp16(amax / 7) kept inside [2^-24, 65504], codes clamp(rne(v * fl(1 / s))), and
- *         Y = sum_g acc_g * (sx[m,g] * sw[n,g]) + branch.  The branch keeps its per-token scales.  K <= 4608.
+ *         Y = sum_g acc_g * (sx[m,g] * sw[n,g]) + branch.  The branch keeps its per-token scales.  K <= 5632.
  *   MX  : Q1 = MXFP4 (E2M1 elements, blocks of 32 along K, E8M0 scale, App. A.3) for both
  *         operands; Q2 = FP8 E4M3 with one fp32 scale per token / per row, or (all-MX setting of
  *         the mixed-precision tables, Section 4.3) MXFP8e4 / MXFP6e2: E4M3 / E2M3 elements in blocks of 32 along

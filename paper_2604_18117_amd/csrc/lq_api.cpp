@@ -41,7 +41,7 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         if (cfg->main_a_group != 0 && cfg->main_a_group != 64) return LQ_ERR_UNSUPPORTED;
         if (cfg->main_a_group == 64 && cfg->main_w_group != 64) return LQ_ERR_UNSUPPORTED;  // one block size for both operands
         d->ga = cfg->main_a_group == 64;
-        if (d->ga && cfg->K > 4608) return LQ_ERR_UNSUPPORTED;  // the forward keeps a tile's token block scales in LDS
+        if (d->ga && cfg->K > 5632) return LQ_ERR_UNSUPPORTED;  // the forward keeps a tile's token block scales in LDS
         // ... and addresses the channel block scales with 32-bit byte offsets
         if (d->ga && cfg->N * (cfg->K / 64) * 4 >= ((int64_t)1 << 31)) return LQ_ERR_UNSUPPORTED;
         if (r == 96) return LQ_ERR_SHAPE;  // rank 96 (a 6-bit budget of 512 bits per channel, padded) only with block-scaled branches

@@ -71,7 +71,7 @@ constexpr int NW = WN;
 constexpr int RBT = 4;                         // 32-row blocks staged per workgroup (LDS slots)
 constexpr int EPI_ROW = 144;                   // bytes per staged output row (128 + pad: no bank conflicts)
 constexpr int EPI_WAVE = 32 * EPI_ROW;         // one 32 x 64 bf16 block per wavefront
-constexpr int GA_MAXG = 72;                    // SINT4-block variant: K <= 4608 (the tile's token scales sit in LDS)
+constexpr int GA_MAXG = 88;                    // SINT4-block variant: K <= 5632 (the tile's token scales sit in LDS: 44 KB)
 template <int GC>
 constexpr int lds_bytes()
 {

@@ -87,8 +87,8 @@ def test_sint4_block_contract(lq):
     assert n0.value == n1.value     # a weight block scale takes a dword either way
     cfg.main_w_group = 128
     assert raw.lq_packed_sizes(C.byref(cfg), C.byref(n1)) == lq.LQ_ERR_UNSUPPORTED
-    cfg = _cfg(lq, K=4672)
-    cfg.main_a_group = 64           # K beyond 4608: the forward's LDS copy of a tile's token scales would not fit
+    cfg = _cfg(lq, K=5696)
+    cfg.main_a_group = 64           # K beyond 5632: the forward's LDS copy of a tile's token scales would not fit
     assert raw.lq_packed_sizes(C.byref(cfg), C.byref(n1)) == lq.LQ_ERR_UNSUPPORTED
     cfg = _cfg(lq, N=1 << 24, K=4608)
     cfg.main_a_group = 64           # 2^24 channels x 72 blocks x 4 bytes: beyond the 32-bit offsets of the scale stream

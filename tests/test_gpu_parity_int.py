@@ -275,7 +275,8 @@ def test_seeded_shape_sweep_bit_exact(oracle):
                                                (33, 2368, 64, 16, "f32", 0, False),     # fp32 rows beyond 2304
                                                (50, 4672, 128, 64, "bf16", 0, True),    # smoothing on a long row
                                                (20, 3072, 64, 32, "f32", 64, True),     # ... with SINT4 blocks
-                                               (17, 8192, 64, 128, "bf16", 0, False)])
+                                               (17, 8192, 64, 128, "bf16", 0, False),
+                                               (150, 5632, 320, 32, "bf16", 64, False)])  # SINT4 blocks at their largest K
 def test_long_rows_are_streamed(oracle, M, K, N, r, xd, ag, sm):
     """Rows that do not fit the register-resident kernel go through the two-pass streamed one: same bits."""
     import torch
