@@ -40,7 +40,8 @@
  *     return value; a failed launch returns LQ_ERR_DEVICE.  Nothing throws.
  *   - Inputs must be finite (NaN / Inf give undefined codes).
  *   - Shape contract: K % 64 == 0, K % main_w_group == 0, N % 64 == 0,
- *     rank in {0,16,32,64,128} ({0,32,64,96,128} with a block-scaled branch), 1 <= M,
+ *     rank in {0,16,32,64,96,128} ({0,32,64,96,128} with a block-scaled branch, {0,16,32,64,128} with the fp32-scaled
+ *     FP8 branch), 1 <= M,
  *     row strides >= row lengths; MX family: K % 128 == 0.
  *   - Calls are deterministic: no atomics, no split-K; repeated calls give identical bits.
  */

@@ -391,6 +391,7 @@ static hipError_t launch_rank2(const ActParams& p, int64_t Mp, hipStream_t s)
         case 16: return launch_one<BF16, MAXC, 1, SM, GA>(p, Mp, s);
         case 32: return launch_one<BF16, MAXC, 2, SM, GA>(p, Mp, s);
         case 64: return launch_one<BF16, MAXC, 4, SM, GA>(p, Mp, s);
+        case 96: return launch_one<BF16, MAXC, 6, SM, GA>(p, Mp, s);
         default: return launch_one<BF16, MAXC, 8, SM, GA>(p, Mp, s);
     }
 }

@@ -44,7 +44,6 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         if (d->ga && cfg->K > 5632) return LQ_ERR_UNSUPPORTED;  // the forward keeps a tile's token block scales in LDS
         // ... and addresses the channel block scales with 32-bit byte offsets
         if (d->ga && cfg->N * (cfg->K / 64) * 4 >= ((int64_t)1 << 31)) return LQ_ERR_UNSUPPORTED;
-        if (r == 96) return LQ_ERR_SHAPE;  // rank 96 (a 6-bit budget of 512 bits per channel, padded) only with block-scaled branches
         const int qw = int_qmax(cfg->br_w), qa = int_qmax(cfg->br_a);
         if (qw == 0 || qa == 0 || cfg->br_a == LQ_INT4) return LQ_ERR_UNSUPPORTED;
         d->mx = false;

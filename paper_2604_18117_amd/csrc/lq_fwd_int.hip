@@ -84,7 +84,7 @@ constexpr int lds_bytes()
 // (NRB = 2): they are arranged 2 x 2 over a 128 x 128 tile, used for a last tile column that has
 // only 128 valid channels, where two of four side-by-side wavefronts would idle through the loop.
 // NRB = 4 (full tile) or
-// 2 (half tile, used for the tail of the grid).  NK = 32-deep chunks of the padded rank: 0|1|2|4.
+// 2 (half tile, used for the tail of the grid).  NK = 32-deep chunks of the padded rank: 0|1|2|3|4.
 template <int GC, int NK, int NRB, bool DBG, bool SPLIT = false, bool GA = false>
 __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const int rb0, const int tile_n)
 {
@@ -540,6 +540,7 @@ static hipError_t launch_rank(int nk, const FwdParams& p, hipStream_t s)
         case 0: return launch_cfg<GC, 0, DBG, GA>(p, s);
         case 1: return launch_cfg<GC, 1, DBG, GA>(p, s);
         case 2: return launch_cfg<GC, 2, DBG, GA>(p, s);
+        case 3: return launch_cfg<GC, 3, DBG, GA>(p, s);
         default: return launch_cfg<GC, 4, DBG, GA>(p, s);
     }
 }
@@ -573,7 +574,7 @@ hipError_t launch_fwd_int(const Dims& d, const uint8_t* packed, const uint8_t* a
     p.dbg_acc2 = dbg ? dbg->acc2 : nullptr;
     p.dbg_y32 = dbg ? dbg->y32 : nullptr;
     const bool want_dbg = dbg && (dbg->acc || dbg->acc2 || dbg->y32);
-    const int nk = d.rp >> 5;  // 0 | 1 | 2 | 4 (the rank is one of 0, 16, 32, 64, 128)
+    const int nk = d.rp >> 5;  // 0 | 1 | 2 | 3 | 4 (the rank is one of 0, 16, 32, 64, 96, 128)
     if (d.ga) return want_dbg ? launch_rank<1, true, true>(nk, p, s) : launch_rank<1, false, true>(nk, p, s);
     if (d.g == 64) {
         return want_dbg ? launch_rank<1, true>(nk, p, s) : launch_rank<1, false>(nk, p, s);

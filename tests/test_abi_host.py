@@ -180,13 +180,13 @@ def test_mxi_contract(lq):
     assert raw.lq_act_sizes(C.byref(big), 64, C.byref(n)) == lq.LQ_OK
 
 
-def test_rank_96_only_with_block_scaled_branches(lq):
+def test_rank_96(lq):
+    # rank 96 = the 6-bit point of a 512-bit budget (rank 85) padded; not with the fp32-scaled FP8 branch (8-bit only)
     n = C.c_size_t(0)
     raw = lq.raw()
-    for fam, kw in (("mxb", {}), ("mxb", dict(br_w_bits=6)), ("mxi", {})):
+    for fam, kw in (("mxb", {}), ("mxb", dict(br_w_bits=6)), ("mxi", {}), ("int", dict(br_w_bits=6, br_a_bits=6))):
         assert raw.lq_packed_sizes(C.byref(_cfg(lq, family=fam, rank=96, **kw)), C.byref(n)) == lq.LQ_OK
-    for fam in ("int", "mx"):
-        assert raw.lq_packed_sizes(C.byref(_cfg(lq, family=fam, rank=96)), C.byref(n)) == lq.LQ_ERR_SHAPE
+    assert raw.lq_packed_sizes(C.byref(_cfg(lq, family="mx", rank=96)), C.byref(n)) == lq.LQ_ERR_SHAPE
 
 
 def test_smoothing_contract(lq):

@@ -63,6 +63,8 @@ SMALL = [
     (33, 640, 192, 128, 128, 8, 8, "bf16"),
     (64, 128, 64, 0, 64, 8, 8, "bf16"),
     (1, 64, 64, 16, 64, 8, 8, "f32"),
+    (200, 448, 320, 96, 64, 6, 6, "bf16"),    # rank 96: the 6-bit point of a 512-bit budget (85) padded
+    (90, 256, 128, 96, 128, 6, 6, "f32"),
 ]
 
 
@@ -209,6 +211,7 @@ SINT4_SMALL = [
     (97, 1152, 128, 128, 4, 8, "bf16"),      # 97 tokens: a last 128-row tile with one real row block
     (64, 128, 64, 0, 8, 8, "bf16"),
     (1, 64, 64, 16, 8, 8, "f32"),
+    (130, 320, 192, 96, 6, 6, "bf16"),
 ]
 
 
