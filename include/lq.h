@@ -42,7 +42,7 @@
  *   - Shape contract: K % 64 == 0, K % main_w_group == 0, N % 64 == 0,
  *     rank in {0,16,32,64,96,128} ({0,32,64,96,128} with a block-scaled branch, {0,16,32,64,128} with the fp32-scaled
  *     FP8 branch), 1 <= M,
- *     row strides >= row lengths; MX family: K % 128 == 0.
+ *     row strides >= row lengths.
  *   - Calls are deterministic: no atomics, no split-K; repeated calls give identical bits.
  */
 #ifndef LQ_H

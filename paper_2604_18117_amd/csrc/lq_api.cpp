@@ -27,7 +27,7 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
     if (cfg->x_dtype != LQ_F32 && cfg->x_dtype != LQ_BF16) return LQ_ERR_UNSUPPORTED;
     if (cfg->residual_from_quantized != 0 && cfg->residual_from_quantized != 1) return LQ_ERR_UNSUPPORTED;
     d->N = cfg->N;
-    d->K = cfg->K;
+    d->K = d->Ks = cfg->K;
     d->r = r;
     d->rp = (r + 31) / 32 * 32;
     d->C64 = (int)(cfg->K / 64);
@@ -56,7 +56,10 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         if (cfg->br_w != cfg->br_a ||
             (cfg->br_w != LQ_FP8_E4M3 && cfg->br_w != LQ_MXFP8_E4M3 && cfg->br_w != LQ_MXFP6_E2M3))
             return LQ_ERR_UNSUPPORTED;
-        if (cfg->K % 128 != 0) return LQ_ERR_SHAPE;  // the MX forward stages K in steps of 128
+        // the MX forward stages K in steps of 128: an odd number of 64-chunks is padded inside the blobs with one chunk
+        // of zero codes (pack and activation kernels write it; sources and views keep the caller's K)
+        d->K = (cfg->K + 127) / 128 * 128;
+        d->C64 = (int)(d->K / 64);
         d->mxb = cfg->br_w != LQ_FP8_E4M3;
         if (!d->mxb && r == 96) return LQ_ERR_SHAPE;
         d->mxb_elem = cfg->br_w == LQ_MXFP8_E4M3 ? 8 : cfg->br_w == LQ_MXFP6_E2M3 ? 6 : 0;
@@ -204,7 +207,7 @@ lq_status lq_quantize_act(const lq_config* cfg, const void* packed, const void* 
     if (st != LQ_OK) return st;
     if (!X || !act) return LQ_ERR_NULL;
     if ((d.r > 0 || d.smooth) && !packed) return LQ_ERR_NULL;
-    if (M < 1 || M > (1 << 24) || ldx < d.K) return LQ_ERR_SHAPE;
+    if (M < 1 || M > (1 << 24) || ldx < d.Ks) return LQ_ERR_SHAPE;
     const size_t es = cfg->x_dtype == LQ_BF16 ? 2 : 4;
     if (!aligned(X, 16) || (ldx * es) % 16 != 0 || !aligned(act, 256) || (packed && !aligned(packed, 256)))
         return LQ_ERR_ALIGN;
@@ -268,6 +271,10 @@ static lq_status calib_dims(const lq_config* cfg, Dims* d)
     lq_status st = make_dims(cfg, d);
     if (st != LQ_OK) return st;
     if (d->r < 16) return LQ_ERR_SHAPE;
+    // the calibration works on the caller's W (N x K), not on packed layouts
+    d->K = d->Ks;
+    d->C64 = (int)(d->K / 64);
+    d->G = (int)(d->K / d->g);
     return LQ_OK;
 }
 

@@ -52,7 +52,8 @@ namespace lq {
 // ---------------------------------------------------------------------------------------
 
 struct Dims {
-    int64_t N, K;
+    int64_t N, K;   // MX family (MXFP4 main): K is the layout's K, the caller's K rounded up to 128 (the forward stages 128)
+    int64_t Ks;     // the caller's K: row length of W, R and X and of the plain views (= K outside the MX family)
     int r;        // rank
     int rp;       // rank padded to a multiple of 32 (0 if r == 0)
     int g;        // main weight group (64 | 128; MX: 32)

@@ -132,12 +132,13 @@ __global__ __launch_bounds__(256) void mx_fill_kernel(uint8_t* p, size_t n, uint
     if (i < n) p[i] = v;
 }
 
-__global__ __launch_bounds__(256) void mx_pack_r_kernel(const float* R, int K, int r, uint8_t* r8, float* sr)
+// Ks: row length of the source; K: row length of the layout (Ks rounded up to 128, the rest zero codes)
+__global__ __launch_bounds__(256) void mx_pack_r_kernel(const float* R, int Ks, int K, int r, uint8_t* r8, float* sr)
 {
     __shared__ float red[4];
     const int j = blockIdx.x, tid = threadIdx.x;
     float a = 0.f;
-    for (int k = tid; k < K; k += 256) a = fmaxf(a, fabsf(R[(size_t)j * K + k]));
+    for (int k = tid; k < Ks; k += 256) a = fmaxf(a, fabsf(R[(size_t)j * Ks + k]));
     a = wmax64(a);
     if ((tid & 63) == 0) red[tid >> 6] = a;
     __syncthreads();
@@ -145,7 +146,8 @@ __global__ __launch_bounds__(256) void mx_pack_r_kernel(const float* R, int K, i
     float s, inv;
     fp8_scales(a, &s, &inv);
     if (tid == 0) sr[j] = s;
-    for (int k = tid; k < K; k += 256) r8[mx_rq_offset(j, k, r)] = (uint8_t)fp8_byte(__fmul_rn(R[(size_t)j * K + k], inv));
+    for (int k = tid; k < K; k += 256)
+        r8[mx_rq_offset(j, k, r)] = k < Ks ? (uint8_t)fp8_byte(__fmul_rn(R[(size_t)j * Ks + k], inv)) : (uint8_t)0;
 }
 
 __global__ __launch_bounds__(256) void mx_pack_l_kernel(const float* L, int N, int r, int rp, uint8_t* l8, float* sl)
@@ -163,20 +165,23 @@ __global__ __launch_bounds__(256) void mx_pack_l_kernel(const float* L, int N, i
 
 // MXFP8e4 factors: one thread per (row, block of 32).  mode 0: rows of R, blocks along K, into the
 // activation kernel's operand order; mode 1: rows of L, blocks along the rank, into the forward's.
-__global__ __launch_bounds__(256) void mxb_pack_rows_kernel(const float* A, int rows, int len, int mode, int r, int rp,
-                                                            uint8_t* codes, uint8_t* scales)
+// (src_len: row length of the source; len: of the layout, a multiple of 128 for R: blocks past the source are zero)
+__global__ __launch_bounds__(256) void mxb_pack_rows_kernel(const float* A, int rows, int len, int src_len, int mode, int r,
+                                                            int rp, uint8_t* codes, uint8_t* scales)
 {
     const int nb = len >> 5;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (size_t)rows * nb) return;
     const int row = (int)(idx / nb), b = (int)(idx % nb);
-    const float* v = A + (size_t)row * len + 32 * b;
+    const bool in_src = 32 * b < src_len;
+    const float* v = A + (size_t)row * src_len + 32 * b;
     float a = 0.f;
-    for (int i = 0; i < 32; ++i) a = fmaxf(a, fabsf(v[i]));
+    if (in_src)
+        for (int i = 0; i < 32; ++i) a = fmaxf(a, fabsf(v[i]));
     const uint32_t E = e8m0_of_fp8(a);
     const float inv = e8m0_inverse(E);
     for (int i = 0; i < 32; ++i) {
-        const uint8_t c = (uint8_t)fp8_byte(__fmul_rn(v[i], inv));
+        const uint8_t c = in_src ? (uint8_t)fp8_byte(__fmul_rn(v[i], inv)) : (uint8_t)0;
         if (mode == 0)
             codes[mxb_rq_offset(row, 32 * b + i, r)] = c;
         else
@@ -190,18 +195,19 @@ __global__ __launch_bounds__(256) void mxb_pack_rows_kernel(const float* A, int 
 
 // one wavefront per (n, 64-chunk): lane = k % 64, two blocks of 32.  from_q: 0 = unquantised factors,
 // 1 = E4M3 codes with fp32 row scales, 2 = MXFP8e4 codes with E8M0 block scales (sl, sr hold le, re).
-__global__ __launch_bounds__(256) void mx_pack_p_kernel(const float* W, const float* L, const float* R, int N, int K,
+__global__ __launch_bounds__(256) void mx_pack_p_kernel(const float* W, const float* L, const float* R, int N, int Ks, int K,
                                                         int r, int rp, int from_q, const uint8_t* l8, const float* sl,
                                                         const uint8_t* r8, const float* sr, uint8_t* pc, uint8_t* pe)
 {
     const int lane = threadIdx.x & 63;
-    const int C64 = K >> 6, CQ = (C64 + 3) >> 2;
+    const int C64 = K >> 6, CQ = (C64 + 3) >> 2;  // layout chunks; a chunk past the source row (k >= Ks) is all zero
     const size_t wid = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (wid >= (size_t)N * C64) return;
     const int n = (int)(wid / C64), c = (int)(wid % C64);
     const int k = c * 64 + lane;
     double d = 0.0;
-    for (int j = 0; j < r; ++j) {
+    const int rr = k < Ks ? r : 0;
+    for (int j = 0; j < rr; ++j) {
         if (from_q == 3) {  // MXFP6e2 factors
             const uint8_t* le = (const uint8_t*)sl;
             const uint8_t* re = (const uint8_t*)sr;
@@ -224,11 +230,11 @@ __global__ __launch_bounds__(256) void mx_pack_p_kernel(const float* W, const fl
             rh = __fmul_rn(fp8_value(r8[mx_rq_offset(j, k, r)]), sr[j]);
         } else {
             lh = L[(size_t)n * r + j];
-            rh = R[(size_t)j * K + k];
+            rh = R[(size_t)j * Ks + k];
         }
         d = fma((double)lh, (double)rh, d);
     }
-    const float P = (float)((double)W[(size_t)n * K + k] - d);
+    const float P = k < Ks ? (float)((double)W[(size_t)n * Ks + k] - d) : 0.0f;
     float a = fabsf(P);
 #pragma unroll
     for (int o = 16; o >= 1; o >>= 1) a = fmaxf(a, __shfl_xor(a, o, 64));  // amax of the 32-block (half wave)
@@ -251,7 +257,7 @@ hipError_t launch_pack_mx(const Dims& d, int from_q, const float* W, const float
     float* sl = (float*)(packed + pl.off_sl);
     uint8_t* r8 = packed + pl.off_rq;
     float* sr = (float*)(packed + pl.off_sr);
-    const int N = (int)d.N, K = (int)d.K;
+    const int N = (int)d.N, K = (int)d.K, Ks = (int)d.Ks;
     const size_t pe_bytes = (size_t)(N / 32) * ((d.C64 + 3) / 4) * 256;
     hipLaunchKernelGGL(mx_fill_kernel, dim3((unsigned)((pe_bytes + 255) / 256)), dim3(256), 0, s, packed + pl.off_sw,
                        pe_bytes, (uint8_t)127);
@@ -269,16 +275,16 @@ hipError_t launch_pack_mx(const Dims& d, int from_q, const float* W, const float
             if (e != hipSuccess) return e;
         } else if (d.r > 0) {
             const size_t nr = (size_t)d.r * (K / 32), nl = (size_t)N * (d.r / 32);
-            hipLaunchKernelGGL(mxb_pack_rows_kernel, dim3((unsigned)((nr + 255) / 256)), dim3(256), 0, s, R, d.r, K, 0, d.r, d.rp, r8, (uint8_t*)sr);
-            hipLaunchKernelGGL(mxb_pack_rows_kernel, dim3((unsigned)((nl + 255) / 256)), dim3(256), 0, s, L, N, d.r, 1, d.r, d.rp, l8, (uint8_t*)sl);
+            hipLaunchKernelGGL(mxb_pack_rows_kernel, dim3((unsigned)((nr + 255) / 256)), dim3(256), 0, s, R, d.r, K, Ks, 0, d.r, d.rp, r8, (uint8_t*)sr);
+            hipLaunchKernelGGL(mxb_pack_rows_kernel, dim3((unsigned)((nl + 255) / 256)), dim3(256), 0, s, L, N, d.r, d.r, 1, d.r, d.rp, l8, (uint8_t*)sl);
         }
     } else {
-        if (d.r > 0) hipLaunchKernelGGL(mx_pack_r_kernel, dim3(d.r), dim3(256), 0, s, R, K, d.r, r8, sr);
+        if (d.r > 0) hipLaunchKernelGGL(mx_pack_r_kernel, dim3(d.r), dim3(256), 0, s, R, Ks, K, d.r, r8, sr);
         hipLaunchKernelGGL(mx_pack_l_kernel, dim3((N + 255) / 256), dim3(256), 0, s, d.r > 0 ? L : (const float*)nullptr, N,
                            d.r, d.rp, l8, sl);
     }
     const size_t waves = (size_t)N * d.C64;
-    hipLaunchKernelGGL(mx_pack_p_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, W, L, R, N, K, d.r, d.rp,
+    hipLaunchKernelGGL(mx_pack_p_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, W, L, R, N, Ks, K, d.r, d.rp,
                        (from_q && d.mxb) ? (d.mxb_elem == 6 ? 3 : 2) : from_q, l8, sl, r8, sr, packed + pl.off_pq, packed + pl.off_sw);
     return hipGetLastError();
 }
@@ -286,11 +292,11 @@ hipError_t launch_pack_mx(const Dims& d, int from_q, const float* W, const float
 // ---------------------------------------------------------------------------------------------
 // plain views
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void mx_unpack_w_kernel(const uint8_t* packed, PackedLayout pl, int N, int K, int r,
+__global__ __launch_bounds__(256) void mx_unpack_w_kernel(const uint8_t* packed, PackedLayout pl, int N, int K, int C64, int r,
                                                           int rp, int mxb, lq_weights_view out)
 {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const int C64 = K >> 6, CQ = (C64 + 3) >> 2, B = K >> 5;
+    const int CQ = (C64 + 3) >> 2, B = K >> 5;  // K: the caller's (views); C64: chunks of the layout
     if (idx < (size_t)N * K && out.pq) {
         const int n = (int)(idx / K), k = (int)(idx % K);
         const uint32_t w = *(const uint32_t*)(packed + pl.off_pq + mx_code_offset(n, k, C64));
@@ -327,17 +333,17 @@ hipError_t launch_unpack_weights_mx(const Dims& d, const uint8_t* packed, const 
 {
     if (d.mxb_elem == 6) return launch_unpack_weights_mx6(d, packed, out, s);
     const PackedLayout pl = packed_layout(d);
-    const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * d.K;
+    const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * d.Ks;
     hipLaunchKernelGGL(mx_unpack_w_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, packed, pl, (int)d.N,
-                       (int)d.K, d.r, d.rp, d.mxb ? 1 : 0, *out);
+                       (int)d.Ks, d.C64, d.r, d.rp, d.mxb ? 1 : 0, *out);
     return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void mx_unpack_a_kernel(const uint8_t* act, ActLayout al, int M, int K, int r, int rp,
+__global__ __launch_bounds__(256) void mx_unpack_a_kernel(const uint8_t* act, ActLayout al, int M, int K, int C64, int r, int rp,
                                                           int mxb, lq_act_view out)
 {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const int C64 = K >> 6, CQ = (C64 + 3) >> 2, B = K >> 5;
+    const int CQ = (C64 + 3) >> 2, B = K >> 5;
     if (idx < (size_t)M * K && out.xq) {
         const int m = (int)(idx / K), k = (int)(idx % K);
         const uint32_t w = *(const uint32_t*)(act + al.off_xq + mx_code_offset(m, k, C64));
@@ -362,9 +368,9 @@ hipError_t launch_unpack_act_mx(const Dims& d, const uint8_t* act, int64_t M, co
 {
     if (d.mxb_elem == 6) return launch_unpack_act_mx6(d, act, M, out, s);
     const ActLayout al = act_layout(d, M);
-    const size_t n = (size_t)M * (d.K > d.r ? d.K : d.r);
+    const size_t n = (size_t)M * (d.Ks > d.r ? d.Ks : d.r);
     hipLaunchKernelGGL(mx_unpack_a_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, act, al, (int)M,
-                       (int)d.K, d.r, d.rp, d.mxb ? 1 : 0, *out);
+                       (int)d.Ks, d.C64, d.r, d.rp, d.mxb ? 1 : 0, *out);
     return hipGetLastError();
 }
 
@@ -375,7 +381,7 @@ hipError_t launch_unpack_act_mx(const Dims& d, const uint8_t* act, int64_t M, co
 struct MxActParams {
     const void* X;
     int64_t ldx;
-    int M, K, C64, CQ, r, rp;
+    int M, K, C64, C64s, CQ, r, rp;  // K, C64s: the caller's row length and its 64-chunks; C64: chunks of the layout
     const uint8_t* r8;
     const float* sr;
     uint8_t* xc;
@@ -451,10 +457,11 @@ __global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
     auto load_x = [&](MxChunk<BF16>& ch, int ci) {
         const int c = wave + 4 * ci;
         const size_t koff = (size_t)c * 64 + kq * 16;
+        const bool ok = row_ok && c < p.C64s;  // (a chunk of the layout past the row is coded from zeros)
         if constexpr (SM)
-            smooth_load<BF16IN, 16>(ch.v, p.X, (size_t)row * p.ldx + koff, p.rg + koff, row_ok && c < C64);
+            smooth_load<BF16IN, 16>(ch.v, p.X, (size_t)row * p.ldx + koff, p.rg + koff, ok);
         else
-            ch.load(p.X, (size_t)row * p.ldx + koff, row_ok && c < C64);
+            ch.load(p.X, (size_t)row * p.ldx + koff, ok);
     };
 #pragma unroll
     for (int ci = 0; ci < NS; ++ci) load_x(xc[ci], ci);
@@ -546,7 +553,7 @@ __global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
         uint8_t* dst = p.xc + ((size_t)((size_t)(row >> 5) * C64 + c) * 64 + (row & 31) + 32 * (kq >> 1)) * 16 + (kq & 1) * 8;
         *(uint2*)dst = make_uint2(pk[0], pk[1]);
         if ((kq & 1) == 0) p.xe[mx_scale_offset(row, c, kq >> 1, p.CQ)] = (uint8_t)E;
-        if (p.dbg_xb && row_ok)
+        if (p.dbg_xb && row_ok && c < p.C64s)
             *(v4i*)(p.dbg_xb + (size_t)row * p.K + c * 64 + kq * 16) = v4i{(int)x8[0], (int)x8[1], (int)x8[2], (int)x8[3]};
         if (NJB > 0) {
             const long alo = (long)(((unsigned long)x8[1] << 32) | x8[0]);
@@ -661,8 +668,9 @@ hipError_t launch_quantize_act_mx(const Dims& d, int x_dtype, const uint8_t* pac
     p.X = X;
     p.ldx = ldx;
     p.M = (int)M;
-    p.K = (int)d.K;
+    p.K = (int)d.Ks;
     p.C64 = d.C64;
+    p.C64s = (int)(d.Ks / 64);
     p.CQ = (d.C64 + 3) / 4;
     p.r = d.r;
     p.rp = d.rp;
@@ -704,7 +712,7 @@ hipError_t launch_quantize_act_mx(const Dims& d, int x_dtype, const uint8_t* pac
 struct MxbActParams {
     const void* X;
     int64_t ldx;
-    int M, K, C64, CQ, C128, r, rp;
+    int M, K, C64, C64s, CQ, C128, r, rp;  // K, C64s: the caller's row length and its 64-chunks; C64, C128: of the layout
     const uint8_t* r8;
     const uint8_t* re;
     uint8_t* xc;
@@ -743,7 +751,8 @@ __global__ __launch_bounds__(256) void mxb_act_kernel(MxbActParams p)
 #pragma unroll
     for (int i = 0; i < PF; ++i)
 #pragma unroll
-        for (int hh = 0; hh < 2; ++hh) load_x(xh[i][hh], (size_t)(wave + 4 * i) * 128 + hh * 64 + q * 16, row_ok && i < nmy);
+        for (int hh = 0; hh < 2; ++hh)
+            load_x(xh[i][hh], (size_t)(wave + 4 * i) * 128 + hh * 64 + q * 16, row_ok && 2 * (wave + 4 * i) + hh < p.C64s);
     // R fragments and their scale dwords: first chunk now, later ones one chunk ahead
     v8i bvs[2][NJA];
     int bss[2][NJA];
@@ -807,10 +816,10 @@ __global__ __launch_bounds__(256) void mxb_act_kernel(MxbActParams p)
                 for (int g = 0; g < 4; ++g)
                     x8[4 * hh + g] = fp8_quad(__fmul_rn(xc.get(4 * g), inv8), __fmul_rn(xc.get(4 * g + 1), inv8),
                                               __fmul_rn(xc.get(4 * g + 2), inv8), __fmul_rn(xc.get(4 * g + 3), inv8));
-                if (p.dbg_xb && row_ok)
+                if (p.dbg_xb && row_ok && c64 < p.C64s)
                     *(v4i*)(p.dbg_xb + (size_t)row * p.K + (size_t)c * 128 + hh * 64 + q * 16) =
                         v4i{(int)x8[4 * hh], (int)x8[4 * hh + 1], (int)x8[4 * hh + 2], (int)x8[4 * hh + 3]};
-                if (p.dbg_xbe && row_ok && (q & 1) == 0) p.dbg_xbe[(size_t)row * (p.K >> 5) + 4 * c + 2 * hh + (q >> 1)] = (uint8_t)E8;
+                if (p.dbg_xbe && row_ok && c64 < p.C64s && (q & 1) == 0) p.dbg_xbe[(size_t)row * (p.K >> 5) + 4 * c + 2 * hh + (q >> 1)] = (uint8_t)E8;
             }
             if (NJB > 0) {
                 // lane q knows blocks (q>>1) [first half] and 2+(q>>1) [second half]; it must supply block q
@@ -827,7 +836,7 @@ __global__ __launch_bounds__(256) void mxb_act_kernel(MxbActParams p)
         // refill the slot with the chunk PF positions further on
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh)
-            load_x(xh[sl][hh], (size_t)(c + 4 * PF) * 128 + hh * 64 + q * 16, row_ok && ci + PF < nmy);
+            load_x(xh[sl][hh], (size_t)(c + 4 * PF) * 128 + hh * 64 + q * 16, row_ok && 2 * (c + 4 * PF) + hh < p.C64s);
     }
     }
     {   // padding 64-chunks of the last quad (at most one 128-chunk per wavefront): valid E8M0 bytes (2^0)
@@ -920,8 +929,9 @@ static hipError_t launch_quantize_act_mxb(const Dims& d, int x_dtype, const uint
     p.X = X;
     p.ldx = ldx;
     p.M = (int)M;
-    p.K = (int)d.K;
+    p.K = (int)d.Ks;
     p.C64 = d.C64;
+    p.C64s = (int)(d.Ks / 64);
     p.CQ = (d.C64 + 3) / 4;
     p.C128 = d.C64 / 2;
     p.r = d.r;

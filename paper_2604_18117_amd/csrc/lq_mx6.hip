@@ -74,8 +74,9 @@ __device__ __forceinline__ v6u fp6_block_from_bf16(v32bf h, float sc)
 // ---------------------------------------------------------------------------------------------
 // offline packing of the factors: one thread per (row, block of 32)
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void mx6_pack_rows_kernel(const float* A, int rows, int len, int mode, int r, int rp,
-                                                            uint8_t* slots, uint8_t* scales)
+// (src_len: row length of the source; len: of the layout, a multiple of 128 for R: blocks past the source are zero)
+__global__ __launch_bounds__(256) void mx6_pack_rows_kernel(const float* A, int rows, int len, int src_len, int mode, int r,
+                                                            int rp, uint8_t* slots, uint8_t* scales)
 {
     const int nb = len >> 5;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(256) void mx6_pack_rows_kernel(const float* A, int 
     float v[32];
     float a = 0.f;
     for (int i = 0; i < 32; ++i) {
-        v[i] = A[(size_t)row * len + 32 * b + i];
+        v[i] = 32 * b < src_len ? A[(size_t)row * src_len + 32 * b + i] : 0.0f;
         a = fmaxf(a, fabsf(v[i]));
     }
     const uint32_t E = m6_e8m0_of(a);
@@ -107,9 +108,9 @@ hipError_t launch_pack_rows_mx6(const Dims& d, const float* L, const float* R, u
     if (d.r == 0) return hipSuccess;
     const int N = (int)d.N, K = (int)d.K;
     const size_t nr = (size_t)d.r * (K / 32), nl = (size_t)N * (d.r / 32);
-    hipLaunchKernelGGL(mx6_pack_rows_kernel, dim3((unsigned)((nr + 255) / 256)), dim3(256), 0, s, R, d.r, K, 0, d.r, d.rp,
+    hipLaunchKernelGGL(mx6_pack_rows_kernel, dim3((unsigned)((nr + 255) / 256)), dim3(256), 0, s, R, d.r, K, (int)d.Ks, 0, d.r, d.rp,
                        packed + pl.off_rq, packed + pl.off_sr);
-    hipLaunchKernelGGL(mx6_pack_rows_kernel, dim3((unsigned)((nl + 255) / 256)), dim3(256), 0, s, L, N, d.r, 1, d.r, d.rp,
+    hipLaunchKernelGGL(mx6_pack_rows_kernel, dim3((unsigned)((nl + 255) / 256)), dim3(256), 0, s, L, N, d.r, d.r, 1, d.r, d.rp,
                        packed + pl.off_lq, packed + pl.off_sl);
     return hipGetLastError();
 }
@@ -117,11 +118,11 @@ hipError_t launch_pack_rows_mx6(const Dims& d, const float* L, const float* R, u
 // ---------------------------------------------------------------------------------------------
 // plain views
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void mx6_unpack_w_kernel(const uint8_t* packed, PackedLayout pl, int N, int K, int r, int rp,
-                                                           lq_weights_view out)
+__global__ __launch_bounds__(256) void mx6_unpack_w_kernel(const uint8_t* packed, PackedLayout pl, int N, int K, int C64, int r,
+                                                           int rp, lq_weights_view out)
 {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const int C64 = K >> 6, CQ = (C64 + 3) >> 2, B = K >> 5, BR = r >> 5;
+    const int CQ = (C64 + 3) >> 2, B = K >> 5, BR = r >> 5;  // K: the caller's (views); C64: chunks of the layout
     if (idx < (size_t)N * K && out.pq) {
         const int n = (int)(idx / K), k = (int)(idx % K);
         const uint32_t w = *(const uint32_t*)(packed + pl.off_pq + m6_code_offset(n, k, C64));
@@ -152,17 +153,17 @@ __global__ __launch_bounds__(256) void mx6_unpack_w_kernel(const uint8_t* packed
 hipError_t launch_unpack_weights_mx6(const Dims& d, const uint8_t* packed, const lq_weights_view* out, hipStream_t s)
 {
     const PackedLayout pl = packed_layout(d);
-    const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * d.K;
-    hipLaunchKernelGGL(mx6_unpack_w_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, packed, pl, (int)d.N, (int)d.K,
-                       d.r, d.rp, *out);
+    const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * d.Ks;
+    hipLaunchKernelGGL(mx6_unpack_w_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, packed, pl, (int)d.N, (int)d.Ks,
+                       d.C64, d.r, d.rp, *out);
     return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void mx6_unpack_a_kernel(const uint8_t* act, ActLayout al, int M, int K, int r, int rp,
+__global__ __launch_bounds__(256) void mx6_unpack_a_kernel(const uint8_t* act, ActLayout al, int M, int K, int C64, int r, int rp,
                                                            lq_act_view out)
 {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const int C64 = K >> 6, CQ = (C64 + 3) >> 2, B = K >> 5, BR = r >> 5;
+    const int CQ = (C64 + 3) >> 2, B = K >> 5, BR = r >> 5;
     if (idx < (size_t)M * K && out.xq) {
         const int m = (int)(idx / K), k = (int)(idx % K);
         const uint32_t w = *(const uint32_t*)(act + al.off_xq + m6_code_offset(m, k, C64));
@@ -185,9 +186,9 @@ __global__ __launch_bounds__(256) void mx6_unpack_a_kernel(const uint8_t* act, A
 hipError_t launch_unpack_act_mx6(const Dims& d, const uint8_t* act, int64_t M, const lq_act_view* out, hipStream_t s)
 {
     const ActLayout al = act_layout(d, M);
-    const size_t n = (size_t)M * (d.K > d.r ? d.K : d.r);
-    hipLaunchKernelGGL(mx6_unpack_a_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, act, al, (int)M, (int)d.K,
-                       d.r, d.rp, *out);
+    const size_t n = (size_t)M * (d.Ks > d.r ? d.Ks : d.r);
+    hipLaunchKernelGGL(mx6_unpack_a_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, act, al, (int)M, (int)d.Ks,
+                       d.C64, d.r, d.rp, *out);
     return hipGetLastError();
 }
 
@@ -201,7 +202,7 @@ hipError_t launch_unpack_act_mx6(const Dims& d, const uint8_t* act, int64_t M, c
 struct Mx6ActParams {
     const void* X;
     int64_t ldx;
-    int M, K, C64, CQ, C128, r, rp;
+    int M, K, C64, C64s, CQ, C128, r, rp;  // K, C64s: the caller's row length and its 64-chunks; C64, C128: of the layout
     const uint8_t* rs;   // R slots
     const uint8_t* re;   // R scale dwords
     uint8_t* xc;
@@ -274,7 +275,7 @@ __global__ __launch_bounds__(256) void mx6_act_kernel(Mx6ActParams p)
             blk.load(p.X, (size_t)row * p.ldx + koff, ok);
     };
 #pragma unroll
-    for (int i = 0; i < PF; ++i) load_x(xb[i], (size_t)(wave + 4 * i) * 128 + q * 32, row_ok && i < nmy);
+    for (int i = 0; i < PF; ++i) load_x(xb[i], (size_t)(wave + 4 * i) * 128 + q * 32, row_ok && 4 * (wave + 4 * i) + q < 2 * p.C64s);
     v8i bvs[2][NJA];
     int bss[2][NJA];
     auto load_r = [&](int slot, int ci) {
@@ -343,12 +344,12 @@ __global__ __launch_bounds__(256) void mx6_act_kernel(Mx6ActParams p)
                 *(v4i*)dst = v4i{(int)pk[0], (int)pk[1], (int)pk[2], (int)pk[3]};
                 p.xe[m6_scale_offset(row, c64, q & 1, p.CQ)] = (uint8_t)E;
                 if (NJB > 0) {
-                    if (p.dbg_xb && row_ok) {
+                    if (p.dbg_xb && row_ok && c64 < p.C64s) {
                         uint32_t cw[8] = {c6[0], c6[1], c6[2], c6[3], c6[4], c6[5], 0u, 0u};
                         int8_t* o = p.dbg_xb + (size_t)row * p.K + (size_t)c * 128 + q * 32;
                         for (int i = 0; i < 32; ++i) o[i] = (int8_t)fp6_get((const uint8_t*)cw, i);
                     }
-                    if (p.dbg_xbe && row_ok) p.dbg_xbe[(size_t)row * (p.K >> 5) + 4 * c + q] = (uint8_t)E;
+                    if (p.dbg_xbe && row_ok && c64 < p.C64s) p.dbg_xbe[(size_t)row * (p.K >> 5) + 4 * c + q] = (uint8_t)E;
                     const v8i a8 = {(int)c6[0], (int)c6[1], (int)c6[2], (int)c6[3], (int)c6[4], (int)c6[5], 0, 0};
 #pragma unroll
                     for (int jb = 0; jb < NJB; ++jb)
@@ -356,7 +357,7 @@ __global__ __launch_bounds__(256) void mx6_act_kernel(Mx6ActParams p)
                                                                                 bss[sl & 1][jb]);
                 }
             }
-            load_x(xb[sl], (size_t)(c + 4 * PF) * 128 + q * 32, row_ok && ci + PF < nmy);
+            load_x(xb[sl], (size_t)(c + 4 * PF) * 128 + q * 32, row_ok && 4 * (c + 4 * PF) + q < 2 * p.C64s);
         }
     }
     {   // padding 64-chunks of the last quad (at most one 128-chunk per wavefront): valid E8M0 bytes (2^0)
@@ -447,8 +448,9 @@ hipError_t launch_quantize_act_mx6(const Dims& d, int x_dtype, const uint8_t* pa
     p.X = X;
     p.ldx = ldx;
     p.M = (int)M;
-    p.K = (int)d.K;
+    p.K = (int)d.Ks;
     p.C64 = d.C64;
+    p.C64s = (int)(d.Ks / 64);
     p.CQ = (d.C64 + 3) / 4;
     p.C128 = d.C64 / 2;
     p.r = d.r;

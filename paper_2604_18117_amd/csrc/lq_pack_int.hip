@@ -137,16 +137,16 @@ __global__ __launch_bounds__(256) void pack_p_kernel(const float* W, const float
 }
 
 // reciprocals of the smoothing vector (gamma == nullptr: ones)
-__global__ __launch_bounds__(256) void smooth_recip_kernel(const float* gamma, int K, float* rg)
+__global__ __launch_bounds__(256) void smooth_recip_kernel(const float* gamma, int Ks, int K, float* rg)
 {
     const int k = blockIdx.x * 256 + threadIdx.x;
-    if (k < K) rg[k] = gamma ? __fdiv_rn(1.0f, gamma[k]) : 1.0f;
+    if (k < K) rg[k] = (gamma && k < Ks) ? __fdiv_rn(1.0f, gamma[k]) : 1.0f;  // (k >= Ks: layout padding)
 }
 
 hipError_t launch_set_smoothing(const Dims& d, const float* gamma, uint8_t* packed, hipStream_t s)
 {
     const PackedLayout pl = packed_layout(d);
-    hipLaunchKernelGGL(smooth_recip_kernel, dim3((unsigned)((d.K + 255) / 256)), dim3(256), 0, s, gamma, (int)d.K,
+    hipLaunchKernelGGL(smooth_recip_kernel, dim3((unsigned)((d.K + 255) / 256)), dim3(256), 0, s, gamma, (int)d.Ks, (int)d.K,
                        (float*)(packed + pl.off_rg));
     return hipGetLastError();
 }

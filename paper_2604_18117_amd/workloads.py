@@ -91,8 +91,12 @@ CFG5I4 = [replace(l, name="c5i4" + l.name[2:], family="mxi", r=128, br_w_bits=4)
 CFG2S = [replace(CFG2[0], name="c2s_qkv", a_group=64)]
 CFG4S = [replace(CFG4[0], name="c4s_qkv", a_group=64)]
 
+# The 2240-wide QKV projection in the all-MX setting (2240 = 35 x 64: one padding chunk inside the blobs).
+CFG4M = [Layer("c4m_qkv", 8192, 2240, 6720, 64, "mxb", 32, 8, 8, "bf16", outlier_scale=25.0, n_outliers=_n_out(2240),
+               w_std=0.015)]
+
 CONFIGS: Dict[str, List[Layer]] = {"c1": CFG1, "c2": CFG2, "c3": CFG3, "c4": CFG4, "c5": CFG5, "c5b": CFG5B, "c5b6": CFG5B6,
-                                   "c5i": CFG5I, "c5i4": CFG5I4, "c2s": CFG2S, "c4s": CFG4S}
+                                   "c5i": CFG5I, "c5i4": CFG5I4, "c2s": CFG2S, "c4s": CFG4S, "c4m": CFG4M}
 LAYERS: Dict[str, Layer] = {l.name: l for ls in CONFIGS.values() for l in ls}
 
 

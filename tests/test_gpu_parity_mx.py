@@ -104,6 +104,8 @@ SMALL = [
     (300, 256, 320, 32, "bf16"),
     (77, 384, 64, 16, "f32"),
     (130, 1152, 192, 64, "bf16"),
+    (100, 2240, 128, 64, "bf16"),     # 35 chunks of 64: the 2240-wide transformer; one padding chunk in the layouts
+    (70, 192, 64, 32, "f32"),
     (64, 128, 64, 0, "bf16"),
     (33, 640, 128, 128, "bf16"),
     (1, 128, 64, 32, "f32"),

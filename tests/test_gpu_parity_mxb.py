@@ -105,6 +105,8 @@ SMALL = [
     (300, 256, 320, 32, "bf16"),
     (77, 384, 64, 32, "f32"),
     (130, 1152, 192, 64, "bf16"),
+    (100, 2240, 128, 64, "bf16"),     # 35 chunks of 64: the 2240-wide transformer; one padding chunk in the layouts
+    (70, 192, 64, 32, "f32"),
     (64, 128, 64, 0, "bf16"),
     (33, 640, 128, 128, "bf16"),
     (1, 128, 64, 32, "f32"),
@@ -155,7 +157,7 @@ def test_wide_dynamic_range_blocks(oracle, elem):
     _compare(oracle, layer, wl.round_to_bf16(X), W, L, R)
 
 
-@pytest.mark.parametrize("name", ["c5b_qkv", "c5b_fc2", "c5b6_qkv", "c5b6_fc2"])
+@pytest.mark.parametrize("name", ["c5b_qkv", "c5b_fc2", "c5b6_qkv", "c5b6_fc2", "c4m_qkv"])
 def test_full_size_sampled_rows(oracle, name):
     layer = wl.LAYERS[name]
     X, W, L, R = wl.make_inputs(layer)
