@@ -360,8 +360,10 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
     };
 #pragma unroll
     for (int i = 0; i < PF; ++i) load_x(xc[i], (size_t)(wave + 4 * i) * 64 + kq * 16, row_ok && i < nmy);
-    // dequantised R fragments (bf16): first chunk now, later ones one chunk ahead
-    v4i bvs[2][NJA][2];
+    // dequantised R fragments (bf16): first chunk now, later ones one chunk ahead.  Two register sets up to rank 64; one
+    // above (refilled right after the chunk's MFMAs): a second set of 64 or more registers would halve the occupancy
+    constexpr int RB = NJB > 4 ? 1 : 2;
+    v4i bvs[RB][NJA][2];
     auto load_r = [&](int slot, int ci) {
         int c = wave + 4 * ci;
         c = c < C64 ? c : C64 - 1;  // clamped: a fragment past the end is fetched but not used
@@ -382,7 +384,7 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
     for (int sl = 0; sl < PF; ++sl) {
         const int ci = base + sl;
         const int c = wave + 4 * ci;
-        load_r((sl + 1) & 1, ci + 1);
+        if constexpr (RB == 2) load_r((sl + 1) & 1, ci + 1);
         if (ci < nmy) {  // wave-uniform
             float m = 0.f;
             if constexpr (BF16) {
@@ -455,9 +457,10 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
 #pragma unroll
                     for (int u = 0; u < 2; ++u)
                         acc[jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, au[u]),
-                                                                         __builtin_bit_cast(v8bf, bvs[sl & 1][jb][u]), acc[jb], 0, 0, 0);
+                                                                         __builtin_bit_cast(v8bf, bvs[sl % RB][jb][u]), acc[jb], 0, 0, 0);
             }
         }
+        if constexpr (RB == 1) load_r(0, ci + 1);
         // refill the slot with the chunk PF positions further on
         load_x(xc[sl], (size_t)(c + 4 * PF) * 64 + kq * 16, row_ok && ci + PF < nmy);
     }
