@@ -49,6 +49,7 @@ struct FwdParams {
     int64_t ldy;
     int M, N, G, C64, rp, nrb;
     int tilesM, tilesN, n_full;
+    int panel;       // column tiles per panel of the tile order (panel_tile)
     int split_last;  // the last tile column has exactly 128 valid channels: run it 2 x 2
     int32_t* dbg_acc;
     int32_t* dbg_acc2;
@@ -483,7 +484,8 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_int_kernel(FwdParams p)
     const int b = blockIdx.x;
     if (b < p.n_full) {
         const int tile = xcd_order(b, p.n_full);
-        const int tile_m = tile / p.tilesN, tile_n = tile - tile_m * p.tilesN;
+        int tile_m, tile_n;
+        panel_tile(tile, p.tilesM, p.tilesN, p.panel, tile_m, tile_n);
         if (p.split_last && tile_n == p.tilesN - 1)
             fwd_tile<GC, NK, 2, DBG, true, GA>(p, lds, tile_m * 4, tile_n);
         else
@@ -491,7 +493,8 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_int_kernel(FwdParams p)
     } else {
         const int hh = xcd_order(b - p.n_full, 2 * (p.tilesM * p.tilesN - p.n_full));
         const int tile = p.n_full + (hh >> 1);
-        const int tile_m = tile / p.tilesN, tile_n = tile - tile_m * p.tilesN;
+        int tile_m, tile_n;
+        panel_tile(tile, p.tilesM, p.tilesN, p.panel, tile_m, tile_n);
         const int rb0 = tile_m * 4 + (hh & 1) * 2;
         if (rb0 >= p.nrb) return;  // lower half of a partial last row tile: nothing to do
         fwd_tile<GC, NK, 2, DBG, false, GA>(p, lds, rb0, tile_n);
@@ -528,6 +531,7 @@ static hipError_t launch_cfg(const FwdParams& p0, hipStream_t s)
     if (4 * (tiles - n_full) > slots) n_full = tiles;
     p.n_full = n_full;
     p.split_last = (p.N & 255) == 128;
+    p.panel = panel_width(p.tilesN, p.C64);
     dim3 grid((unsigned)(n_full + 2 * (tiles - n_full))), block(NW * 64);
     hipLaunchKernelGGL((fwd_int_kernel<GC, NK, DBG, GA>), grid, block, 0, s, p);
     return hipGetLastError();
@@ -570,6 +574,7 @@ hipError_t launch_fwd_int(const Dims& d, const uint8_t* packed, const uint8_t* a
     p.rp = d.rp;
     p.nrb = (int)(al.Mp / 32);
     p.tilesM = p.tilesN = p.n_full = p.split_last = 0;
+    p.panel = 1;
     p.dbg_acc = dbg ? dbg->acc : nullptr;
     p.dbg_acc2 = dbg ? dbg->acc2 : nullptr;
     p.dbg_y32 = dbg ? dbg->y32 : nullptr;

@@ -577,7 +577,7 @@ struct MxiFwdParams {
     uint16_t* Y;
     int64_t ldy;
     int M, N, C64, CQ, nrb;
-    int tilesM, tilesN;
+    int tilesM, tilesN, panel;
     float* dbg_y32;
 };
 
@@ -611,7 +611,8 @@ __global__ __launch_bounds__(256, 2) void mxi_fwd_kernel(MxiFwdParams p)
     const int per = tiles >> 3, rem = tiles & 7;
     const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
     const int tile = xcd * per + (xcd < rem ? xcd : rem) + loc;
-    const int tile_m = tile / p.tilesN, tile_n = tile - tile_m * p.tilesN;
+    int tile_m, tile_n;
+    panel_tile(tile, p.tilesM, p.tilesN, p.panel, tile_m, tile_n);
     const int rb0 = tile_m * RBT;
     const int cb0 = tile_n * 8 + wave * 2;
     const bool active = (cb0 * 32 < p.N) && (rb0 < p.nrb);
@@ -838,6 +839,7 @@ hipError_t launch_fwd_mxi(const Dims& d, const uint8_t* packed, const uint8_t* a
     p.nrb = (int)(al.Mp / 32);
     p.tilesM = (p.nrb + 3) / 4;
     p.tilesN = (p.N + 255) / 256;
+    p.panel = panel_width(p.tilesN, p.C64);
     p.dbg_y32 = dbg ? dbg->y32 : nullptr;
     switch (d.rp >> 4) {
         case 0: mxi_fwd_launch<0>(p, s); break;
