@@ -45,16 +45,19 @@ def run_gpu(layer, X, W, L, R, debug=True, debug_acc=True, gamma=None):
     M = X.shape[0]
     if debug and layer.family in ("mx", "mxb", "mxi"):
         debug_acc = False
+    # the output starts as a bit pattern the path never produces (a NaN): a tile the grid skipped would keep it
+    Y0 = torch.full((M, layer.N), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)
     if debug:
         act, adbg = lq.lq_quantize_act(cfg, packed, Xd, debug=True)
-        Y, fdbg = lq.lq_linear_lowrank_fwd(cfg, packed, act, M, debug=True, debug_acc=debug_acc)
+        Y, fdbg = lq.lq_linear_lowrank_fwd(cfg, packed, act, M, Y=Y0, debug=True, debug_acc=debug_acc)
         out = GpuRun(cfg, packed, act, Y, lq.lq_unpack_weights(cfg, packed), lq.lq_unpack_act(cfg, act, M),
                      adbg, fdbg)
     else:
         act = lq.lq_quantize_act(cfg, packed, Xd)
-        Y = lq.lq_linear_lowrank_fwd(cfg, packed, act, M)
+        Y = lq.lq_linear_lowrank_fwd(cfg, packed, act, M, Y=Y0)
         out = GpuRun(cfg, packed, act, Y)
     torch.cuda.synchronize()
+    assert not bool((Y.view(torch.int16) == -1).any()), "an output element was never written"
     return out
 
 
