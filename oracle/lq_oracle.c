@@ -34,7 +34,8 @@
  *          mixed-precision tables, Section 4.3); fp64 accumulate, one rounding.
  *
  * Besides the forward, lqo_calib_step is one Adam step of the data-free optimisation of the factors
- * (Eq. 4, App. B.2), the step that produces the L and R the forward consumes.
+ * (Eq. 4, App. B.2), the step that produces the L and R the forward consumes, and lqo_rot_step one step
+ * of the rotation search of Section 3.3 (Eq. 6-7) that follows it.
  *
  * Readings of points the paper leaves open (all "parity unpinned" by the paper; the tests
  * pin self-consistency only):
@@ -1080,6 +1081,169 @@ LQO_API void lqo_calib_step(int64_t N, int64_t K, int r, int g, int q1, const fl
     free(E);
     free(gL);
     free(gR);
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* Rotation of the factors before they are quantised (Section 3.3, Eq. 6-7)               */
+/* ------------------------------------------------------------------------------------ */
+
+/* One step of the search for an orthogonal r x r matrix Omega that makes L Omega and Omega^T R easier
+   to quantise with Q2 (the product L R is unchanged: Omega Omega^T = I).  Orientation as everywhere
+   here: L is N x r, R is r x K.  Eq. 7 with the Mean Squared Error loss of Eq. 4:
+       loss(Omega) = mean_{n,j} ( Q2(Z1) - Z1 )^2 + mean_{j,k} ( Q2(Z2) - Z2 )^2 ,
+       Z1 = L Omega (N x r),  Z2 = Omega^T R (r x K).
+   Q2 here: symmetric integers of qmax, one scale per row of Z1 (per output channel) and per row of Z2
+   (per rank index), the granularity the packing step uses for Q2(L) and Q2(R).
+   Readings (the paper names the loss, a learning rate and the optimiser family only):
+     - Z1, Z2 are fp32 numbers, each a chain z = fma(a_i, b_i, z) over the rank index i ascending from
+       z = 0 (the codes depend on their rounding, so the arithmetic of this decision is fixed);
+     - E = deq(Q2(Z)) - Z in fp32, deq = code * scale;
+     - the rounding has zero derivative, as in App. B.2, so with E1, E2 held fixed
+           G = d loss / d Omega = -2/(N r) L^T E1 - 2/(r K) R E2^T          (r x r),
+       accumulated in fp64, times grad_scale (1 = the loss as printed), rounded once to fp32;
+     - the optimiser is the Cayley SGD with momentum of the work the paper cites for it (Li et al. 2020,
+       Algorithm 1), with X = Omega and the Frobenius norm:
+           M  <- beta M - G
+           Wh <- M X^T - 1/2 X (X^T M X^T);   W <- Wh - Wh^T;   M <- W X
+           alpha <- min(lr, 2 q / (||W|| + eps))
+           Y <- X + alpha M;  s times:  Y <- X + alpha/2 W (X + Y);   X <- Y
+       done in fp64 from the fp32 state and rounded once per stored value.
+   In/out: Omega, Mom (r x r).  Out (each optional): E1 N x r, E2 r x K, G r x r, *loss (before the update). */
+LQO_API void lqo_rot_step(int64_t N, int64_t K, int r, int qmax, const float *L, const float *R, float *Omega,
+                          float *Mom, double lr, double beta, double eps, double q, int s, double grad_scale,
+                          float *E1_out, float *E2_out, float *G_out, double *loss_out)
+{
+    float *E1 = (float *)malloc(sizeof(float) * (size_t)(N * r));
+    float *E2 = (float *)malloc(sizeof(float) * (size_t)(r * K));
+    const int rr = r * r;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        float *z = (float *)malloc(sizeof(float) * (size_t)r);
+        int8_t *c = (int8_t *)malloc((size_t)r);
+        float sc;
+        for (int j = 0; j < r; ++j) {
+            float v = 0.0f;
+            for (int i = 0; i < r; ++i) v = fmaf(L[n * r + i], Omega[i * r + j], v);
+            z[j] = v;
+        }
+        lqo_quant_int(z, r, qmax, c, &sc);
+        for (int j = 0; j < r; ++j) E1[n * r + j] = (float)c[j] * sc - z[j];
+        free(z);
+        free(c);
+    }
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < r; ++j) {
+        float *z = (float *)malloc(sizeof(float) * (size_t)K);
+        int8_t *c = (int8_t *)malloc((size_t)K);
+        float sc;
+        for (int64_t k = 0; k < K; ++k) {
+            float v = 0.0f;
+            for (int i = 0; i < r; ++i) v = fmaf(Omega[i * r + j], R[(int64_t)i * K + k], v);
+            z[k] = v;
+        }
+        lqo_quant_int(z, K, qmax, c, &sc);
+        for (int64_t k = 0; k < K; ++k) E2[(int64_t)j * K + k] = (float)c[k] * sc - z[k];
+        free(z);
+        free(c);
+    }
+    double l1 = 0.0, l2 = 0.0;
+    for (int64_t i = 0; i < N * r; ++i) l1 += (double)E1[i] * (double)E1[i];
+    for (int64_t i = 0; i < (int64_t)r * K; ++i) l2 += (double)E2[i] * (double)E2[i];
+    const double loss = l1 / ((double)N * r) + l2 / ((double)r * (double)K);
+
+    double *G = (double *)malloc(sizeof(double) * (size_t)rr);
+    const double c1 = -2.0 / ((double)N * r), c2 = -2.0 / ((double)r * (double)K);
+    for (int i = 0; i < r; ++i)
+        for (int j = 0; j < r; ++j) {
+            double a = 0.0, b = 0.0;
+            for (int64_t n = 0; n < N; ++n) a += (double)L[n * r + i] * (double)E1[n * r + j];
+            for (int64_t k = 0; k < K; ++k) b += (double)R[(int64_t)i * K + k] * (double)E2[(int64_t)j * K + k];
+            G[i * r + j] = (double)(float)(grad_scale * (c1 * a + c2 * b));
+        }
+
+    /* Cayley SGD with momentum; all r x r, row-major */
+    double *X = (double *)malloc(sizeof(double) * (size_t)rr * 7);
+    double *M = X + rr, *A = M + rr, *B = A + rr, *Wh = B + rr, *W = Wh + rr, *Y = W + rr;
+    for (int i = 0; i < rr; ++i) {
+        X[i] = (double)Omega[i];
+        M[i] = beta * (double)Mom[i] - G[i];
+    }
+    for (int i = 0; i < r; ++i)      /* A = M X^T */
+        for (int j = 0; j < r; ++j) {
+            double a = 0.0;
+            for (int k = 0; k < r; ++k) a += M[i * r + k] * X[j * r + k];
+            A[i * r + j] = a;
+        }
+    for (int i = 0; i < r; ++i)      /* B = X^T A = X^T M X^T */
+        for (int j = 0; j < r; ++j) {
+            double a = 0.0;
+            for (int k = 0; k < r; ++k) a += X[k * r + i] * A[k * r + j];
+            B[i * r + j] = a;
+        }
+    for (int i = 0; i < r; ++i)      /* Wh = A - 1/2 X B */
+        for (int j = 0; j < r; ++j) {
+            double a = 0.0;
+            for (int k = 0; k < r; ++k) a += X[i * r + k] * B[k * r + j];
+            Wh[i * r + j] = A[i * r + j] - 0.5 * a;
+        }
+    double nrm = 0.0;
+    for (int i = 0; i < r; ++i)
+        for (int j = 0; j < r; ++j) {
+            W[i * r + j] = Wh[i * r + j] - Wh[j * r + i];
+            nrm += W[i * r + j] * W[i * r + j];
+        }
+    nrm = sqrt(nrm);
+    for (int i = 0; i < r; ++i)      /* M = W X */
+        for (int j = 0; j < r; ++j) {
+            double a = 0.0;
+            for (int k = 0; k < r; ++k) a += W[i * r + k] * X[k * r + j];
+            M[i * r + j] = a;
+        }
+    double alpha = 2.0 * q / (nrm + eps);
+    if (lr < alpha) alpha = lr;
+    for (int i = 0; i < rr; ++i) Y[i] = X[i] + alpha * M[i];
+    for (int it = 0; it < s; ++it) {
+        for (int i = 0; i < rr; ++i) A[i] = X[i] + Y[i];
+        for (int i = 0; i < r; ++i)
+            for (int j = 0; j < r; ++j) {
+                double a = 0.0;
+                for (int k = 0; k < r; ++k) a += W[i * r + k] * A[k * r + j];
+                B[i * r + j] = X[i * r + j] + 0.5 * alpha * a;
+            }
+        for (int i = 0; i < rr; ++i) Y[i] = B[i];
+    }
+    for (int i = 0; i < rr; ++i) {
+        Omega[i] = (float)Y[i];
+        Mom[i] = (float)M[i];
+    }
+    if (E1_out) memcpy(E1_out, E1, sizeof(float) * (size_t)(N * r));
+    if (E2_out) memcpy(E2_out, E2, sizeof(float) * (size_t)(r * K));
+    if (G_out)
+        for (int i = 0; i < rr; ++i) G_out[i] = (float)G[i];
+    if (loss_out) *loss_out = loss;
+    free(X);
+    free(G);
+    free(E1);
+    free(E2);
+}
+
+/* The rotated factors the packing step then takes: Lr = L Omega, Rr = Omega^T R, the same fp32 chains as above. */
+LQO_API void lqo_rot_apply(int64_t N, int64_t K, int r, const float *L, const float *R, const float *Omega,
+                           float *Lr, float *Rr)
+{
+    for (int64_t n = 0; n < N; ++n)
+        for (int j = 0; j < r; ++j) {
+            float v = 0.0f;
+            for (int i = 0; i < r; ++i) v = fmaf(L[n * r + i], Omega[i * r + j], v);
+            Lr[n * r + j] = v;
+        }
+    for (int j = 0; j < r; ++j)
+        for (int64_t k = 0; k < K; ++k) {
+            float v = 0.0f;
+            for (int i = 0; i < r; ++i) v = fmaf(Omega[i * r + j], R[(int64_t)i * K + k], v);
+            Rr[(int64_t)j * K + k] = v;
+        }
 }
 
 LQO_API int lqo_num_threads(void)

@@ -554,3 +554,53 @@ def calib_step(W, st: CalibState, g: int = 64, sint4_blocks: bool = False, lr: f
                          _p(out.gR), C.byref(loss))
     out.loss = float(loss.value)
     return out
+
+
+# ---------------------------------------------------------------------------------------
+# rotation of the factors before quantisation (Section 3.3, Eq. 6-7)
+# ---------------------------------------------------------------------------------------
+
+@dataclass
+class RotState:
+    """fp32 state of the rotation search: the orthogonal matrix and the optimiser's momentum."""
+    Omega: np.ndarray
+    Mom: np.ndarray
+
+
+def rot_init(r: int, Omega=None, Mom=None) -> RotState:
+    return RotState(np.eye(r, dtype=np.float32) if Omega is None else _f32(Omega).copy(),
+                    np.zeros((r, r), np.float32) if Mom is None else _f32(Mom).copy())
+
+
+@dataclass
+class RotOut:
+    loss: float          # Eq. 7 before this step's update
+    E1: np.ndarray       # N x r   deq(Q2(L Omega)) - L Omega
+    E2: np.ndarray       # r x K   deq(Q2(Omega^T R)) - Omega^T R
+    G: np.ndarray        # r x r   Euclidean gradient used by the step
+
+
+def rot_step(L, R, st: RotState, bits: int = 8, lr: float = 0.5, beta: float = 0.9, eps: float = 1e-8, q: float = 0.5,
+             s: int = 2, grad_scale: float = 1.0) -> RotOut:
+    """One Cayley-SGD step on Omega; updates `st` in place.  bits: width of Q2 (per-row symmetric integers)."""
+    L, R = _f32(L), _f32(R)
+    N, r = L.shape
+    K = R.shape[1]
+    assert R.shape[0] == r and st.Omega.shape == (r, r) and st.Mom.shape == (r, r)
+    out = RotOut(0.0, np.empty((N, r), np.float32), np.empty((r, K), np.float32), np.empty((r, r), np.float32))
+    loss = C.c_double(0.0)
+    lib().lqo_rot_step(C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(2 ** (bits - 1) - 1), _p(L), _p(R), _p(st.Omega),
+                       _p(st.Mom), C.c_double(lr), C.c_double(beta), C.c_double(eps), C.c_double(q), C.c_int(s),
+                       C.c_double(grad_scale), _p(out.E1), _p(out.E2), _p(out.G), C.byref(loss))
+    out.loss = float(loss.value)
+    return out
+
+
+def rot_apply(L, R, Omega):
+    """(L Omega, Omega^T R) in the fp32 arithmetic the loss quantises."""
+    L, R, Omega = _f32(L), _f32(R), _f32(Omega)
+    N, r = L.shape
+    K = R.shape[1]
+    Lr, Rr = np.empty((N, r), np.float32), np.empty((r, K), np.float32)
+    lib().lqo_rot_apply(C.c_int64(N), C.c_int64(K), C.c_int(r), _p(L), _p(R), _p(Omega), _p(Lr), _p(Rr))
+    return Lr, Rr

@@ -1140,3 +1140,124 @@ def test_workload_generator_is_seeded():
     X = a[0]
     assert np.array_equal(wl.round_to_bf16(X), X)
     assert [x.shape for x in a] == [(16, 128), (64, 128), (64, 16), (16, 128)]
+
+
+# ---- rotation search (Section 3.3, Eq. 6-7) -----------------------------------------------------------------------
+def _rot_case(seed, N=96, K=160, r=16, outlier=8.0):
+    rng = np.random.default_rng(seed)
+    L = rng.standard_normal((N, r)).astype(np.float32) * 0.05
+    R = rng.standard_normal((r, K)).astype(np.float32) * 0.05
+    L[:, 3] *= outlier
+    R[5, :] *= outlier
+    X0 = np.linalg.qr(rng.standard_normal((r, r)))[0].astype(np.float32)
+    return L, R, X0
+
+
+def test_rot_errors_are_roundings_of_the_rotated_factors(oracle):
+    """Eq. 7's two terms: E1, E2 are the errors of a per-row integer quantiser applied to L Omega and Omega^T R: every
+    entry within half a step of its row, every reconstructed value an integer multiple of the step within the code
+    range, the row maximum exact; the loss is the sum of the two mean squares."""
+    L, R, X0 = _rot_case(1)
+    for bits in (8, 6, 4):
+        qmax = 2 ** (bits - 1) - 1
+        st = oracle.rot_init(16, X0)
+        out = oracle.rot_step(L, R, st, bits=bits, lr=0.0)
+        for Z, E in ((L.astype(np.float64) @ X0, out.E1), (X0.T.astype(np.float64) @ R, out.E2)):
+            step = np.abs(Z).max(axis=1, keepdims=True) / qmax
+            assert np.all(np.abs(E) <= 0.5 * step * (1 + 1e-5) + 1e-9)
+            codes = (Z + E) / step
+            assert np.all(np.abs(codes - np.rint(codes)) < 1e-3) and np.abs(np.rint(codes)).max() == qmax
+        assert out.loss == pytest.approx(np.mean(out.E1.astype(np.float64) ** 2) + np.mean(out.E2.astype(np.float64) ** 2), rel=1e-12)
+        assert np.array_equal(st.Omega, X0)          # a zero learning rate moves nothing
+
+
+def test_rot_gradient_is_the_gradient_of_the_loss_with_the_codes_held(oracle):
+    """App. B.2's convention applied to Eq. 7: with the quantised values C1, C2 held fixed the loss is the quadratic
+    mean((C1 - L Omega)^2) + mean((C2 - Omega^T R)^2); its central differences give G entry by entry."""
+    L, R, X0 = _rot_case(2)
+    st = oracle.rot_init(16, X0)
+    out = oracle.rot_step(L, R, st, bits=4, lr=0.0, grad_scale=3.0)
+    L64, R64, X64 = L.astype(np.float64), R.astype(np.float64), X0.astype(np.float64)
+    C1, C2 = L64 @ X64 + out.E1, X64.T @ R64 + out.E2
+
+    def f(X):
+        return np.mean((C1 - L64 @ X) ** 2) + np.mean((C2 - X.T @ R64) ** 2)
+
+    h = 1e-4
+    for (i, j) in [(0, 0), (3, 5), (5, 3), (15, 2), (7, 7)]:
+        D = np.zeros((16, 16))
+        D[i, j] = h
+        fd = (f(X64 + D) - f(X64 - D)) / (2 * h)       # exact for a quadratic, up to rounding
+        assert 3.0 * fd == pytest.approx(float(out.G[i, j]), rel=2e-4, abs=1e-9)
+
+
+@pytest.mark.parametrize("s,beta", [(2, 0.0), (6, 0.0), (3, 0.9)])
+def test_rot_update_is_the_cayley_transform_of_the_projected_momentum(oracle, s, beta):
+    """The published iteration converges to the closed-form Cayley transform (I - a/2 W)^-1 (I + a/2 W) X of the
+    skew-symmetric W built from the momentum; after s passes the distance is at most a^s * 2 a^2 / (1 - a) * ||X||
+    with a = ||alpha W / 2||_2.  A wrong sign, a dropped 1/2 or a transposed operand leaves an error of order a."""
+    L, R, X0 = _rot_case(3)
+    rng = np.random.default_rng(4)
+    M0 = (rng.standard_normal((16, 16)) * 1e-3).astype(np.float32)
+    st = oracle.rot_init(16, X0, M0)
+    lr, scale = 0.5, 2500.0
+    out = oracle.rot_step(L, R, st, bits=4, lr=lr, beta=beta, s=s, grad_scale=scale)
+    X = X0.astype(np.float64)
+    M = beta * M0.astype(np.float64) - out.G.astype(np.float64)
+    Wh = M @ X.T - 0.5 * X @ (X.T @ M @ X.T)
+    W = Wh - Wh.T
+    assert np.allclose(W, -W.T)
+    alpha = min(lr, 1.0 / (np.linalg.norm(W) + 1e-8))
+    a = np.linalg.norm(alpha * W / 2, 2)
+    assert 0.01 < a < 0.5                                 # the case exercises the iteration, inside its contraction region
+    I = np.eye(16)
+    Ystar = np.linalg.solve(I - alpha / 2 * W, (I + alpha / 2 * W) @ X)
+    bound = a ** s * 2 * a * a / (1 - a) * np.linalg.norm(X) + 1e-6
+    assert np.linalg.norm(st.Omega - Ystar) <= bound
+    if s == 6:
+        assert np.abs(st.Omega - Ystar).max() < 2e-7      # fp32 storage is all that is left
+    # the stored momentum is the projected one, W X: tangent to the orthogonal group at X
+    assert np.allclose(st.Mom, W @ X, rtol=1e-5, atol=1e-9)
+    T = st.Mom.astype(np.float64) @ X.T
+    assert np.abs(T + T.T).max() < 1e-6 * max(1.0, np.abs(T).max())
+    # the transform of an orthogonal matrix is orthogonal
+    assert np.abs(Ystar.T @ Ystar - I).max() < 1e-5
+    assert np.abs(st.Omega.astype(np.float64).T @ st.Omega - I).max() < 4 * bound + 1e-5
+
+
+def test_rot_step_limiter_and_descent(oracle):
+    """The step length is min(lr, 2q / (||W|| + eps)): a huge gradient cannot leave the contraction region (the update
+    stays near-orthogonal), and a small step goes downhill on the loss with the codes held (sign of the update)."""
+    L, R, X0 = _rot_case(5)
+    st = oracle.rot_init(16, X0)
+    oracle.rot_step(L, R, st, bits=4, lr=0.5, beta=0.0, s=2, grad_scale=1e6)
+    assert np.abs(st.Omega.astype(np.float64).T @ st.Omega - np.eye(16)).max() < 0.3   # a = q = 0.5: bounded, not exploded
+    st = oracle.rot_init(16, X0)
+    out = oracle.rot_step(L, R, st, bits=4, lr=1e-3, beta=0.0, s=2, grad_scale=100.0)
+    L64, R64, X64 = L.astype(np.float64), R.astype(np.float64), X0.astype(np.float64)
+    C1, C2 = L64 @ X64 + out.E1, X64.T @ R64 + out.E2
+    f = lambda X: np.mean((C1 - L64 @ X) ** 2) + np.mean((C2 - X.T @ R64) ** 2)
+    assert f(st.Omega.astype(np.float64)) < f(X64)
+
+
+def test_rot_lossless_factors_are_a_fixed_point_and_apply_keeps_the_product(oracle):
+    """Factors already on the integer grid of their rows (row maximum = qmax steps) have zero error at Omega = I: loss 0,
+    gradient 0, Omega and the momentum stay exactly where they were.  Applying an orthogonal Omega leaves L R unchanged
+    up to fp32 rounding and equals the plain matrix products."""
+    rng = np.random.default_rng(6)
+    r, N, K = 16, 40, 96
+    L = rng.integers(-127, 128, (N, r)).astype(np.float32)
+    R = rng.integers(-127, 128, (r, K)).astype(np.float32)
+    L[:, 0] = 127.0
+    R[:, 1] = -127.0
+    L *= np.float32(2.0 ** -9)
+    R *= np.float32(2.0 ** -7)
+    st = oracle.rot_init(r)
+    out = oracle.rot_step(L, R, st, bits=8, lr=0.5)
+    assert out.loss == 0.0 and not out.G.any() and not out.E1.any() and not out.E2.any()
+    assert np.array_equal(st.Omega, np.eye(r, dtype=np.float32)) and not st.Mom.any()
+    L2, R2, X0 = _rot_case(7)
+    Lr, Rr = oracle.rot_apply(L2, R2, X0)
+    assert np.allclose(Lr, L2.astype(np.float64) @ X0, rtol=0, atol=1e-6)
+    assert np.allclose(Rr, X0.T.astype(np.float64) @ R2, rtol=0, atol=1e-6)
+    assert np.allclose(Lr.astype(np.float64) @ Rr, L2.astype(np.float64) @ R2, rtol=0, atol=2e-6)
