@@ -227,6 +227,58 @@ lq_status lq_calib_step(const lq_config *cfg, const float *W, void *state, size_
 /* Copy parts of the state out (device to device). */
 lq_status lq_calib_unpack(const lq_config *cfg, const void *state, const lq_calib_view *out, void *stream);
 
+/* ---- Rotation of the calibrated factors before they are quantised (Section 3.3, Eq. 6-7) -----------------------
+   Search for an orthogonal r x r matrix Omega that lowers
+       loss(Omega) = mean over N x r of ( Q2(L Omega) - L Omega )^2 + mean over r x K of ( Q2(Omega^T R) - Omega^T R )^2 ,
+   the product (L Omega)(Omega^T R) = L R unchanged.  INT family only (anything else: LQ_ERR_UNSUPPORTED): Q2 is the
+   symmetric integer format cfg->br_w with one scale per row of L Omega and per row of Omega^T R, as lq_pack_weights
+   quantises L and R; rank >= 16.  Both products are fp32 fused-multiply-add chains over the rank index, ascending
+   from zero.  The rounding is treated as having zero derivative (App. B.2), so
+       G = -2/(N r) L^T E1 - 2/(r K) R E2^T ,   E1 = Q2(L Omega) - L Omega,  E2 = Q2(Omega^T R) - Omega^T R ,
+   times grad_scale.  The update is the Cayley SGD with momentum of the work the paper cites for it (Li et al. 2020,
+   Algorithm 1; X = Omega, Frobenius norm):
+       M <- beta M - G;  Wh <- M X^T - 1/2 X (X^T M X^T);  W <- Wh - Wh^T;  M <- W X;
+       alpha <- min(lr, 2 q / (||W|| + eps));  Y <- X + alpha M;  s times: Y <- X + alpha/2 W (X + Y);  X <- Y.
+   The paper gives the learning rate (0.5; 0.1 for the mixed-precision study; 500 steps; App. A.2) and nothing else of
+   the optimiser: beta, q, s and eps are the cited algorithm's (0.9, 0.5, 2, 1e-8).  With the mean-squared-error loss
+   as printed the gradient of a layer-sized problem is of the order of 1e-7 and a step of 0.5 moves Omega by as much;
+   grad_scale (1 = as printed) is the caller's handle on that.
+   The state blob is device memory owned by the caller (256-byte aligned, at least state_bytes).  A step is five kernel
+   launches, no atomics, no allocation; results are reproducible bit for bit. */
+typedef struct {
+    float lr;          /* 0.5 (App. A.2)                                                  */
+    float beta;        /* momentum, in [0, 1)                                            */
+    float eps;         /* > 0                                                            */
+    float q;           /* in (0, 1): alpha ||W|| / 2 stays at or below it                */
+    int32_t s;         /* fixed-point passes of the Cayley transform, 0 .. 16            */
+    float grad_scale;  /* > 0                                                            */
+} lq_cayley;
+
+typedef struct {   /* plain row-major fp32 device arrays; any member may be NULL */
+    float *Omega, *Mom, *G;  /* r x r: the rotation, the momentum, the gradient used by the last step */
+    float *E1;               /* N x r  Q2(L Omega) - L Omega of the last step                         */
+    float *E2;               /* r x K  Q2(Omega^T R) - Omega^T R of the last step                     */
+} lq_rot_view;
+
+lq_status lq_rot_sizes(const lq_config *cfg, size_t *state_bytes);
+
+/* Start a search.  Omega0, Mom0: device, r x r fp32 dense, or NULL for the identity / zero. */
+lq_status lq_rot_init(const lq_config *cfg, const float *Omega0, const float *Mom0, void *state, size_t state_bytes,
+                      void *stream);
+
+/* One step.  L: device, N x r; R: device, r x K; fp32 dense, not modified.  loss: device, one float, receives the loss
+   BEFORE this step's update; may be NULL. */
+lq_status lq_rot_step(const lq_config *cfg, const float *L, const float *R, void *state, size_t state_bytes,
+                      const lq_cayley *opt, float *loss, void *stream);
+
+/* The rotated factors lq_pack_weights then takes: Lr = L Omega (N x r), Rr = Omega^T R (r x K), device fp32 dense, the
+   same fp32 chains the loss quantises.  Lr, Rr must not overlap L, R. */
+lq_status lq_rot_apply(const lq_config *cfg, const float *L, const float *R, const void *state, float *Lr, float *Rr,
+                       void *stream);
+
+/* Copy parts of the state out (device to device). */
+lq_status lq_rot_unpack(const lq_config *cfg, const void *state, const lq_rot_view *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

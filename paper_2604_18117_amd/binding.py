@@ -61,15 +61,30 @@ class lq_calib_view(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in ("L", "R", "mL", "vL", "mR", "vR", "gL", "gR", "E")]
 
 
+class lq_cayley(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta", C.c_float), ("eps", C.c_float), ("q", C.c_float), ("s", C.c_int32),
+                ("grad_scale", C.c_float)]
+
+
+class lq_rot_view(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("Omega", "Mom", "G", "E1", "E2")]
+
+
 EXPORTS = ["lq_status_string", "lq_packed_sizes", "lq_pack_weights", "lq_set_smoothing", "lq_act_sizes", "lq_quantize_act",
            "lq_linear_lowrank_fwd", "lq_unpack_weights", "lq_unpack_act", "lq_calib_sizes", "lq_calib_init", "lq_calib_step",
-           "lq_calib_unpack"]
+           "lq_calib_unpack", "lq_rot_sizes", "lq_rot_init", "lq_rot_step", "lq_rot_apply", "lq_rot_unpack"]
 
 _lib.lq_calib_sizes.argtypes = [C.POINTER(lq_config), C.POINTER(C.c_size_t)]
 _lib.lq_calib_init.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.lq_calib_step.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.POINTER(lq_adam),
                                C.c_void_p, C.c_void_p]
 _lib.lq_calib_unpack.argtypes = [C.POINTER(lq_config), C.c_void_p, C.POINTER(lq_calib_view), C.c_void_p]
+_lib.lq_rot_sizes.argtypes = [C.POINTER(lq_config), C.POINTER(C.c_size_t)]
+_lib.lq_rot_init.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.lq_rot_step.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.POINTER(lq_cayley),
+                             C.c_void_p, C.c_void_p]
+_lib.lq_rot_apply.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.lq_rot_unpack.argtypes = [C.POINTER(lq_config), C.c_void_p, C.POINTER(lq_rot_view), C.c_void_p]
 _lib.lq_status_string.restype = C.c_char_p
 _lib.lq_status_string.argtypes = [C.c_int]
 _lib.lq_packed_sizes.argtypes = [C.POINTER(lq_config), C.POINTER(C.c_size_t)]
@@ -333,4 +348,59 @@ def lq_calib_unpack(cfg: lq_config, state: torch.Tensor, names=("L", "R")) -> di
     out = {k: torch.empty(shapes[k], dtype=torch.float32, device=state.device) for k in names}
     view = lq_calib_view(**{k: (out[k].data_ptr() if k in out else None) for k in shapes})
     _check(_lib.lq_calib_unpack(C.byref(cfg), _ptr(state), C.byref(view), C.c_void_p(_stream())), "lq_calib_unpack")
+    return out
+
+
+# ---- rotation of the calibrated factors (argument marshalling only) ---------------------------------------------------
+
+def lq_rot_sizes(cfg: lq_config) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.lq_rot_sizes(C.byref(cfg), C.byref(n)), "lq_rot_sizes")
+    return int(n.value)
+
+
+def _check_factors(cfg: lq_config, L: torch.Tensor, R: torch.Tensor) -> None:
+    for t in (L, R):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+    assert tuple(L.shape) == (cfg.N, cfg.rank) and tuple(R.shape) == (cfg.rank, cfg.K), "factor shapes must match cfg"
+
+
+def lq_rot_init(cfg: lq_config, Omega0: Optional[torch.Tensor] = None, Mom0: Optional[torch.Tensor] = None,
+                state: Optional[torch.Tensor] = None, device="cuda") -> torch.Tensor:
+    """Omega0, Mom0: r x r fp32 CUDA, contiguous, or None for the identity / zero.  Returns the state blob."""
+    for t in (Omega0, Mom0):
+        assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == (cfg.rank, cfg.rank))
+    if state is None:
+        state = torch.empty(lq_rot_sizes(cfg), dtype=torch.uint8, device=device)
+    _check(_lib.lq_rot_init(C.byref(cfg), _ptr(Omega0), _ptr(Mom0), _ptr(state), state.numel(), C.c_void_p(_stream())),
+           "lq_rot_init")
+    return state
+
+
+def lq_rot_step(cfg: lq_config, L: torch.Tensor, R: torch.Tensor, state: torch.Tensor, lr: float = 0.5, beta: float = 0.9,
+                eps: float = 1e-8, q: float = 0.5, s: int = 2, grad_scale: float = 1.0,
+                loss: Optional[torch.Tensor] = None) -> None:
+    """One Cayley-SGD step on Omega; `loss`: optional 1-element fp32 CUDA tensor that receives the loss before the update."""
+    _check_factors(cfg, L, R)
+    opt = lq_cayley(lr, beta, eps, q, s, grad_scale)
+    _check(_lib.lq_rot_step(C.byref(cfg), _ptr(L), _ptr(R), _ptr(state), state.numel(), C.byref(opt), _ptr(loss),
+                            C.c_void_p(_stream())), "lq_rot_step")
+
+
+def lq_rot_apply(cfg: lq_config, L: torch.Tensor, R: torch.Tensor, state: torch.Tensor):
+    """(L Omega, Omega^T R) as new fp32 tensors, for lq_pack_weights."""
+    _check_factors(cfg, L, R)
+    Lr, Rr = torch.empty_like(L), torch.empty_like(R)
+    _check(_lib.lq_rot_apply(C.byref(cfg), _ptr(L), _ptr(R), _ptr(state), _ptr(Lr), _ptr(Rr), C.c_void_p(_stream())),
+           "lq_rot_apply")
+    return Lr, Rr
+
+
+def lq_rot_unpack(cfg: lq_config, state: torch.Tensor, names=("Omega",)) -> dict:
+    """Copies of the named parts of the state: Omega, Mom, G, E1, E2."""
+    N, K, r = cfg.N, cfg.K, cfg.rank
+    shapes = {"Omega": (r, r), "Mom": (r, r), "G": (r, r), "E1": (N, r), "E2": (r, K)}
+    out = {k: torch.empty(shapes[k], dtype=torch.float32, device=state.device) for k in names}
+    view = lq_rot_view(**{k: (out[k].data_ptr() if k in out else None) for k in shapes})
+    _check(_lib.lq_rot_unpack(C.byref(cfg), _ptr(state), C.byref(view), C.c_void_p(_stream())), "lq_rot_unpack")
     return out

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["lq_api.cpp", "lq_pack_int.hip", "lq_act_int.hip", "lq_fwd_int.hip", "lq_mx.hip", "lq_mx6.hip", "lq_mxi.hip", "lq_calib.hip"]
+SOURCES = ["lq_api.cpp", "lq_pack_int.hip", "lq_act_int.hip", "lq_fwd_int.hip", "lq_mx.hip", "lq_mx6.hip", "lq_mxi.hip", "lq_calib.hip", "lq_rot.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-ffp-contract=off",
          "-fno-fast-math", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"), "-I", CSRC]

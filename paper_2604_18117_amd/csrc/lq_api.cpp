@@ -325,4 +325,72 @@ lq_status lq_calib_unpack(const lq_config* cfg, const void* state, const lq_cali
     return launch_calib_unpack(d, (const uint8_t*)state, out, (hipStream_t)stream) == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }
 
+static lq_status rot_dims(const lq_config* cfg, Dims* d)
+{
+    lq_status st = make_dims(cfg, d);
+    if (st != LQ_OK) return st;
+    if (d->mx || d->mxi) return LQ_ERR_UNSUPPORTED;  // per-row integer Q2 only
+    if (d->r < 16) return LQ_ERR_SHAPE;
+    if ((int64_t)d->r * d->K * 4 >= ((int64_t)1 << 31)) return LQ_ERR_UNSUPPORTED;  // R is read with 32-bit byte offsets
+    return LQ_OK;
+}
+
+lq_status lq_rot_sizes(const lq_config* cfg, size_t* state_bytes)
+{
+    if (!cfg || !state_bytes) return LQ_ERR_NULL;
+    Dims d;
+    lq_status st = rot_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    *state_bytes = rot_layout(d).total;
+    return LQ_OK;
+}
+
+lq_status lq_rot_init(const lq_config* cfg, const float* Omega0, const float* Mom0, void* state, size_t state_bytes,
+                      void* stream)
+{
+    Dims d;
+    lq_status st = rot_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!state) return LQ_ERR_NULL;
+    if (!aligned(state, 256) || !aligned(Omega0, 4) || !aligned(Mom0, 4)) return LQ_ERR_ALIGN;
+    if (state_bytes < rot_layout(d).total) return LQ_ERR_BUFFER_TOO_SMALL;
+    return launch_rot_init(d, Omega0, Mom0, (uint8_t*)state, (hipStream_t)stream) == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
+lq_status lq_rot_step(const lq_config* cfg, const float* L, const float* R, void* state, size_t state_bytes,
+                      const lq_cayley* opt, float* loss, void* stream)
+{
+    Dims d;
+    lq_status st = rot_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!L || !R || !state || !opt) return LQ_ERR_NULL;
+    if (!(opt->lr > 0.f) || !(opt->beta >= 0.f && opt->beta < 1.f) || !(opt->eps > 0.f) || !(opt->q > 0.f && opt->q < 1.f) ||
+        opt->s < 0 || opt->s > 16 || !(opt->grad_scale > 0.f))
+        return LQ_ERR_UNSUPPORTED;
+    if (!aligned(state, 256) || !aligned(L, 16) || !aligned(R, 16) || (loss && !aligned(loss, 4))) return LQ_ERR_ALIGN;
+    if (state_bytes < rot_layout(d).total) return LQ_ERR_BUFFER_TOO_SMALL;
+    return launch_rot_step(d, L, R, (uint8_t*)state, opt, loss, (hipStream_t)stream) == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
+lq_status lq_rot_apply(const lq_config* cfg, const float* L, const float* R, const void* state, float* Lr, float* Rr,
+                       void* stream)
+{
+    Dims d;
+    lq_status st = rot_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!L || !R || !state || !Lr || !Rr) return LQ_ERR_NULL;
+    if (!aligned(state, 256) || !aligned(L, 16) || !aligned(R, 16) || !aligned(Lr, 16) || !aligned(Rr, 16)) return LQ_ERR_ALIGN;
+    return launch_rot_apply(d, L, R, (const uint8_t*)state, Lr, Rr, (hipStream_t)stream) == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
+lq_status lq_rot_unpack(const lq_config* cfg, const void* state, const lq_rot_view* out, void* stream)
+{
+    Dims d;
+    lq_status st = rot_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!state || !out) return LQ_ERR_NULL;
+    if (!aligned(state, 256)) return LQ_ERR_ALIGN;
+    return launch_rot_unpack(d, (const uint8_t*)state, out, (hipStream_t)stream) == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
 }  // extern "C"

@@ -158,6 +158,24 @@ hipError_t launch_calib_step(const Dims& d, const float* W, uint8_t* state, int 
                              hipStream_t s);
 hipError_t launch_calib_unpack(const Dims& d, const uint8_t* state, const lq_calib_view* out, hipStream_t s);
 
+struct RotLayout {
+    size_t off_X, off_M, off_G;  // Omega, momentum, gradient of the last step (r x r each)
+    size_t off_E1, off_E2;       // N x r and r x K quantisation errors of the rotated factors (last step)
+    size_t off_ax;               // per-wavefront row maxima of Omega^T R, [4 * nkb][r]
+    size_t off_lp;               // partial sums of E1^2 (nlb), then of E2^2 (r * nkb)
+    size_t off_gp;               // partials of the gradient, [workgroup][r][r]
+    size_t off_tmp;              // scratch matrices of the update
+    int nlb, nkb, n_lp;
+    size_t total;
+};
+RotLayout rot_layout(const Dims& d);
+hipError_t launch_rot_init(const Dims& d, const float* Omega0, const float* Mom0, uint8_t* state, hipStream_t s);
+hipError_t launch_rot_step(const Dims& d, const float* L, const float* R, uint8_t* state, const lq_cayley* cs, float* loss,
+                           hipStream_t s);
+hipError_t launch_rot_apply(const Dims& d, const float* L, const float* R, const uint8_t* state, float* Lr, float* Rr,
+                            hipStream_t s);
+hipError_t launch_rot_unpack(const Dims& d, const uint8_t* state, const lq_rot_view* out, hipStream_t s);
+
 // Tile order of the forward kernels: panels of `panel` tile columns (256 channels each), row-major inside a panel; the
 // last panel may be narrower.  The workgroups resident on an XCD at one time then share few weight column blocks: with
 // all tile columns in flight at once, the weight codes of a wide layer (7.5 MB at 2240 x 6720) do not stay in the XCD's

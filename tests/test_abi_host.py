@@ -217,6 +217,39 @@ def test_smoothing_contract(lq):
         assert lq.lq_packed_sizes(a) == lq.lq_packed_sizes(b) + K * 4
 
 
+def test_rotation_contract(lq):
+    raw = lq.raw()
+    n = C.c_size_t(0)
+    good = C.c_void_p(1 << 20)
+    cfg = lq.make_config(128, 256, 32)
+    assert raw.lq_rot_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_OK
+    r, N, K = 32, 128, 256
+    # Omega, momentum, gradient, E1, E2, row maxima, loss partials, 64 gradient partials, 5 scratch matrices (256-byte aligned each)
+    a256 = lambda x: (x + 255) // 256 * 256
+    want = 3 * a256(r * r * 4) + a256(N * r * 4) + a256(r * K * 4) + a256(1 * 4 * r * 4) + a256((1 + r * 1) * 4) + \
+        a256(64 * r * r * 4) + a256(5 * r * r * 4)
+    assert n.value == want
+    opt = lq.lq_cayley(0.5, 0.9, 1e-8, 0.5, 2, 1.0)
+    sb = n.value
+    assert raw.lq_rot_init(C.byref(cfg), None, None, None, sb, None) == lq.LQ_ERR_NULL
+    assert raw.lq_rot_init(C.byref(cfg), None, None, good, sb - 1, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert raw.lq_rot_init(C.byref(cfg), None, None, C.c_void_p((1 << 20) + 64), sb, None) == lq.LQ_ERR_ALIGN
+    assert raw.lq_rot_step(C.byref(cfg), None, good, good, sb, C.byref(opt), None, None) == lq.LQ_ERR_NULL
+    assert raw.lq_rot_step(C.byref(cfg), good, good, good, sb, None, None, None) == lq.LQ_ERR_NULL
+    assert raw.lq_rot_step(C.byref(cfg), good, C.c_void_p((1 << 20) + 4), good, sb, C.byref(opt), None, None) == lq.LQ_ERR_ALIGN
+    assert raw.lq_rot_step(C.byref(cfg), good, good, good, sb - 1, C.byref(opt), None, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    for bad in (lq.lq_cayley(0.0, 0.9, 1e-8, 0.5, 2, 1.0), lq.lq_cayley(0.5, 1.0, 1e-8, 0.5, 2, 1.0), lq.lq_cayley(0.5, 0.9, 0.0, 0.5, 2, 1.0),
+                lq.lq_cayley(0.5, 0.9, 1e-8, 1.0, 2, 1.0), lq.lq_cayley(0.5, 0.9, 1e-8, 0.5, 17, 1.0), lq.lq_cayley(0.5, 0.9, 1e-8, 0.5, -1, 1.0),
+                lq.lq_cayley(0.5, 0.9, 1e-8, 0.5, 2, 0.0)):
+        assert raw.lq_rot_step(C.byref(cfg), good, good, good, sb, C.byref(bad), None, None) == lq.LQ_ERR_UNSUPPORTED
+    assert raw.lq_rot_apply(C.byref(cfg), good, good, good, None, good, None) == lq.LQ_ERR_NULL
+    assert raw.lq_rot_unpack(C.byref(cfg), good, None, None) == lq.LQ_ERR_NULL
+    # integer per-row Q2 only; a branch to rotate
+    for fam in ("mx", "mxb", "mxi"):
+        assert raw.lq_rot_sizes(C.byref(lq.make_config(128, 256, 32, fam, 32)), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    assert raw.lq_rot_sizes(C.byref(lq.make_config(128, 256, 0)), C.byref(n)) == lq.LQ_ERR_SHAPE
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
