@@ -81,6 +81,47 @@ def bench_calib(args, layer, np, torch, lq, wl):
     print(json.dumps(out))
 
 
+def bench_rot(args, layer, np, torch, lq, wl):
+    """K steps of the rotation search (Section 3.3, Eq. 6-7) on the layer's factor shapes.  value = steps per second."""
+    _, _, L, R = wl.make_inputs(layer)
+    cfg = lq.config_for_layer(layer)
+    scale = np.float32(10.0)
+    Ld, Rd = torch.from_numpy(L * scale).cuda(), torch.from_numpy(R * scale).cuda()
+    state = lq.lq_rot_init(cfg)
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    opt = dict(lr=0.5, beta=0.9, s=2, grad_scale=1.0)
+    t_ramp = time.perf_counter()
+    while time.perf_counter() - t_ramp < args.ramp_seconds:
+        for _ in range(50):
+            lq.lq_rot_step(cfg, Ld, Rd, state, loss=loss, **opt)
+        torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        lq.lq_rot_step(cfg, Ld, Rd, state, loss=loss, **opt)
+    torch.cuda.synchronize()
+    K = args.steps
+    t0 = time.perf_counter()
+    for _ in range(K):
+        lq.lq_rot_step(cfg, Ld, Rd, state, loss=loss, **opt)
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / K
+    N, Kd, r = layer.N, layer.K, layer.r
+    out = {"metric": "rotation search (Eq. 7) Cayley-SGD steps per second", "value": round(1e3 / ms_step, 1), "unit": "steps/s",
+           "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": round(ms_step, 5), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": layer.name + "_rot", "N": N, "K": Kd, "rank": r, "q2_bits": layer.br_w_bits,
+                      "launches_per_step": 5},
+           "work_per_step": {"flops": 2.0 * (2 * 2 + 1) * (N + Kd) * r * r + 2.0 * 8 * r ** 3, "loss": float(loss.item())}}
+    if args.oracle_seconds > 0:
+        from oracle import lq_ref
+        st = lq_ref.rot_init(r)
+        t0 = time.perf_counter()
+        lq_ref.rot_step(L * scale, R * scale, st, bits=layer.br_w_bits)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(1.0 / dt, 3), "unit": "steps/s", "cores": lq_ref.num_threads(), "kind": "oracle",
+                               "sample": "one full step of the same layer"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -95,6 +136,8 @@ def main():
     ap.add_argument("--calib", action="store_true",
                     help="time the data-free calibration step (lq_calib_step) on the workload's weight shape instead "
                          "of the per-call path; prints its own JSON line")
+    ap.add_argument("--rot", action="store_true",
+                    help="time the rotation search step (lq_rot_step) on the workload's factor shapes; prints its own JSON line")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
                     help="only run a plain device-to-device copy of BYTES (calibrates the HBM byte counters)")
     args = ap.parse_args()
@@ -123,6 +166,8 @@ def main():
     layer = wl.LAYERS[args.workload]
     if args.calib:
         return bench_calib(args, layer, np, torch, lq, wl)
+    if args.rot:
+        return bench_rot(args, layer, np, torch, lq, wl)
     X, W, L, R = wl.make_inputs(layer)
     cfg = lq.config_for_layer(layer)
     M = layer.M

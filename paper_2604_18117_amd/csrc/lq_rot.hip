@@ -20,7 +20,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int ROT_TPB = 256;
 constexpr int ROT_GRAD_WGS = 64;   // slices the two contractions of the gradient are dealt to
-constexpr int ROT_TMP = 5;         // r x r scratch matrices of the update kernel
+constexpr int ROT_TMP = 4;         // r x r scratch matrices of the update kernel
 
 RotLayout rot_layout(const Dims& d)
 {
@@ -283,18 +283,38 @@ struct RotStepParams {
     int s;
 };
 
-// The update, one workgroup of 1024 threads.  Every phase reads matrices that earlier phases wrote to global memory;
-// __syncthreads orders those accesses within the workgroup.
+// The update, one workgroup of 1024 threads.  Five r x r work matrices; as many as fit sit in a 60 KB LDS pool (all five
+// and Omega up to rank 32, three at rank 64, one at rank 96), the rest in the state's scratch area in global memory:
+// the code addresses both through generic pointers.  Every phase reads what earlier phases wrote; __syncthreads orders
+// those accesses within the workgroup.
+// ALL_LDS (rank <= 32): everything sits in the pool and the compiler sees plain LDS addresses.
+constexpr int ROT_POOL = 15360;  // floats
+template <bool ALL_LDS>
 __global__ __launch_bounds__(1024) void rot_cayley_kernel(RotStepParams p)
 {
+    __shared__ __attribute__((aligned(16))) float pool[ROT_POOL];
     __shared__ double red[16];
     __shared__ float bc;
     const int r = p.r, rr = r * r, tid = threadIdx.x;
-    float* T0 = p.tmp;            // beta M - G
-    float* T1 = T0 + rr;          // A = T0 X^T, later Y
-    float* T2 = T1 + rr;          // B = X^T A, later X + Y
-    float* T3 = T2 + rr;          // Wh, later the next Y
-    float* W = T3 + rr;
+    __builtin_assume(r % 16 == 0 && r >= 16);  // the dot products below are unrolled 16 deep: their loads go out together
+    // priority: W (read by every product of the second half), then the operands of the passes, then Omega
+    float *W, *T1, *T2, *T4, *Xl;
+    if constexpr (ALL_LDS) {
+        W = pool;
+        T1 = pool + rr;
+        T2 = pool + 2 * rr;
+        T4 = pool + 3 * rr;
+        Xl = pool + 4 * rr;
+    } else {
+        const int fit = ROT_POOL / rr;
+        W = 0 < fit ? pool : p.tmp;
+        T1 = 1 < fit ? pool + rr : p.tmp + rr;
+        T2 = 2 < fit ? pool + 2 * rr : p.tmp + 2 * rr;
+        T4 = 3 < fit ? pool + 3 * rr : p.tmp + 3 * rr;
+        Xl = 4 < fit ? pool + 4 * rr : p.X;
+    }
+    // W: first beta M - G, then Wh, then W = Wh - Wh^T in place;  T1: A = (beta M - G) X^T, later Y;
+    // T2: X^T (for A), B = X^T A, later X + Y;  T4: the next Y
     auto block_sum = [&](double v) -> double {
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
@@ -315,39 +335,49 @@ __global__ __launch_bounds__(1024) void rot_cayley_kernel(RotStepParams p)
     }
     for (int e = tid; e < rr; e += 1024) {
         double g = 0.0;
-        for (int w = 0; w < p.nparts; ++w) g += (double)p.gp[(size_t)w * rr + e];
+#pragma unroll 16
+        for (int w = 0; w < ROT_GRAD_WGS; ++w) g += (double)p.gp[(size_t)w * rr + e];  // 16 loads in flight at a time
         const float gf = (float)((double)p.grad_scale * g);
         p.G[e] = gf;
-        T0[e] = p.beta * p.M[e] - gf;
+        W[e] = p.beta * p.M[e] - gf;
+        const float x = p.X[e];
+        if (ALL_LDS || Xl != p.X) Xl[e] = x;
+        const int i = e / r, j = e - i * r;
+        T2[j * r + i] = x;  // X^T: the product below then reads rows, not columns (in LDS a column read is a 32-way bank conflict)
     }
     __syncthreads();
-    for (int e = tid; e < rr; e += 1024) {  // A = T0 X^T
+    for (int e = tid; e < rr; e += 1024) {  // A = (beta M - G) X^T
         const int i = e / r, j = e - i * r;
         float a = 0.f;
-        for (int k = 0; k < r; ++k) a = __builtin_fmaf(T0[i * r + k], p.X[j * r + k], a);
+#pragma unroll 16
+        for (int k = 0; k < r; ++k) a = __builtin_fmaf(W[i * r + k], T2[k * r + j], a);
         T1[e] = a;
     }
     __syncthreads();
     for (int e = tid; e < rr; e += 1024) {  // B = X^T A
         const int i = e / r, j = e - i * r;
         float a = 0.f;
-        for (int k = 0; k < r; ++k) a = __builtin_fmaf(p.X[k * r + i], T1[k * r + j], a);
+#pragma unroll 16
+        for (int k = 0; k < r; ++k) a = __builtin_fmaf(Xl[k * r + i], T1[k * r + j], a);
         T2[e] = a;
     }
     __syncthreads();
     for (int e = tid; e < rr; e += 1024) {  // Wh = A - 1/2 X B
         const int i = e / r, j = e - i * r;
         float a = 0.f;
-        for (int k = 0; k < r; ++k) a = __builtin_fmaf(p.X[i * r + k], T2[k * r + j], a);
-        T3[e] = T1[e] - 0.5f * a;
+#pragma unroll 16
+        for (int k = 0; k < r; ++k) a = __builtin_fmaf(Xl[i * r + k], T2[k * r + j], a);
+        W[e] = T1[e] - 0.5f * a;
     }
     __syncthreads();
     double n2 = 0.0;
-    for (int e = tid; e < rr; e += 1024) {  // W = Wh - Wh^T
+    for (int e = tid; e < rr; e += 1024) {  // W = Wh - Wh^T, each pair (i, j), (j, i) by the thread of its upper entry
         const int i = e / r, j = e - i * r;
-        const float w = T3[e] - T3[j * r + i];
+        if (i > j) continue;
+        const float w = W[e] - W[j * r + i];
         W[e] = w;
-        n2 += (double)w * (double)w;
+        W[j * r + i] = -w;
+        if (i < j) n2 += 2.0 * (double)w * (double)w;
     }
     const double nrm2 = block_sum(n2);      // (its barriers also order W's stores before the reads below)
     if (tid == 0) {
@@ -359,21 +389,23 @@ __global__ __launch_bounds__(1024) void rot_cayley_kernel(RotStepParams p)
     for (int e = tid; e < rr; e += 1024) {  // M = W X;  Y = X + alpha M
         const int i = e / r, j = e - i * r;
         float a = 0.f;
-        for (int k = 0; k < r; ++k) a = __builtin_fmaf(W[i * r + k], p.X[k * r + j], a);
+#pragma unroll 16
+        for (int k = 0; k < r; ++k) a = __builtin_fmaf(W[i * r + k], Xl[k * r + j], a);
         p.M[e] = a;
-        T1[e] = __builtin_fmaf(alpha, a, p.X[e]);
+        T1[e] = __builtin_fmaf(alpha, a, Xl[e]);
     }
     float* Y = T1;
-    float* Yn = T3;
+    float* Yn = T4;
     for (int it = 0; it < p.s; ++it) {      // Y <- X + alpha/2 W (X + Y)
         __syncthreads();
-        for (int e = tid; e < rr; e += 1024) T2[e] = p.X[e] + Y[e];
+        for (int e = tid; e < rr; e += 1024) T2[e] = Xl[e] + Y[e];
         __syncthreads();
         for (int e = tid; e < rr; e += 1024) {
             const int i = e / r, j = e - i * r;
             float a = 0.f;
-            for (int k = 0; k < r; ++k) a = __builtin_fmaf(W[i * r + k], T2[k * r + j], a);
-            Yn[e] = __builtin_fmaf(0.5f * alpha, a, p.X[e]);
+    #pragma unroll 16
+        for (int k = 0; k < r; ++k) a = __builtin_fmaf(W[i * r + k], T2[k * r + j], a);
+            Yn[e] = __builtin_fmaf(0.5f * alpha, a, Xl[e]);
         }
         float* t = Y;
         Y = Yn;
@@ -467,7 +499,10 @@ hipError_t launch_rot_step(const Dims& d, const float* L, const float* Rm, uint8
     p.q = cs->q;
     p.grad_scale = cs->grad_scale;
     p.s = cs->s;
-    hipLaunchKernelGGL(rot_cayley_kernel, dim3(1), dim3(1024), 0, s, p);
+    if (5 * r * r <= ROT_POOL)
+        hipLaunchKernelGGL(rot_cayley_kernel<true>, dim3(1), dim3(1024), 0, s, p);
+    else
+        hipLaunchKernelGGL(rot_cayley_kernel<false>, dim3(1), dim3(1024), 0, s, p);
     return hipGetLastError();
 }
 

@@ -65,6 +65,14 @@ def test_one_step_matches_the_oracle(oracle, N, K, r, bits):
     _compare_step(oracle, lq, N, K, r, bits, seed=N + K + r, lr=0.5, beta=0.9, s=2, grad_scale=2500.0)
 
 
+@pytest.mark.parametrize("name,bits", [("c2_qkv", 8), ("c4_qkv", 6), ("c3_fc2", 4)])
+def test_full_size_layers(oracle, name, bits):
+    """The factor shapes of the benchmark layers (3456 x 32 / 32 x 1152, 6720 x 64 / 64 x 2240, 1152 x 32 / 32 x 4608)."""
+    from paper_2604_18117_amd import binding as lq
+    l = wl.LAYERS[name]
+    _compare_step(oracle, lq, l.N, l.K, l.r, bits, seed=7, lr=0.5, beta=0.9, s=2, grad_scale=20000.0)
+
+
 def test_defaults_identity_start_and_more_passes(oracle):
     """lq_rot_init without matrices starts at the identity with zero momentum; the paper's learning rate with the loss as
     printed (grad_scale 1); s = 5 passes; beta = 0."""
