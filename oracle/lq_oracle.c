@@ -1092,8 +1092,10 @@ LQO_API void lqo_calib_step(int64_t N, int64_t K, int r, int g, int q1, const fl
    here: L is N x r, R is r x K.  Eq. 7 with the Mean Squared Error loss of Eq. 4:
        loss(Omega) = mean_{n,j} ( Q2(Z1) - Z1 )^2 + mean_{j,k} ( Q2(Z2) - Z2 )^2 ,
        Z1 = L Omega (N x r),  Z2 = Omega^T R (r x K).
-   Q2 here: symmetric integers of qmax, one scale per row of Z1 (per output channel) and per row of Z2
-   (per rank index), the granularity the packing step uses for Q2(L) and Q2(R).
+   Q2 is the format the packing step applies to L and R, along the rows of Z1 (per output channel, r values)
+   and of Z2 (per rank index, K values): q2 = 0 symmetric integers of qmax = qparam with one fp32 scale per
+   row; 1 FP8 E4M3 with one fp32 scale per row; 2 MXFP8e4, 3 MXFP6e2, 4 MXINT of qparam bits (blocks of 32
+   along the row, E8M0 scale; r and K multiples of 32).
    Readings (the paper names the loss, a learning rate and the optimiser family only):
      - Z1, Z2 are fp32 numbers, each a chain z = fma(a_i, b_i, z) over the rank index i ascending from
        z = 0 (the codes depend on their rounding, so the arithmetic of this decision is fixed);
@@ -1109,7 +1111,38 @@ LQO_API void lqo_calib_step(int64_t N, int64_t K, int r, int g, int q1, const fl
            Y <- X + alpha M;  s times:  Y <- X + alpha/2 W (X + Y);   X <- Y
        done in fp64 from the fp32 state and rounded once per stored value.
    In/out: Omega, Mom (r x r).  Out (each optional): E1 N x r, E2 r x K, G r x r, *loss (before the update). */
-LQO_API void lqo_rot_step(int64_t N, int64_t K, int r, int qmax, const float *L, const float *R, float *Omega,
+static void rot_quant_err(const float *z, int64_t n, int q2, int qparam, float *e)
+{
+    uint8_t *c = (uint8_t *)malloc((size_t)n);
+    uint8_t *eb = (uint8_t *)malloc((size_t)(n / 32 + 1));
+    float sc;
+    switch (q2) {
+    case 0:
+        lqo_quant_int(z, n, qparam, (int8_t *)c, &sc);
+        for (int64_t i = 0; i < n; ++i) e[i] = (float)((int8_t *)c)[i] * sc - z[i];
+        break;
+    case 1:
+        lqo_quant_fp8(z, n, c, &sc);
+        for (int64_t i = 0; i < n; ++i) e[i] = lqo_e4m3_decode(c[i]) * sc - z[i];
+        break;
+    case 2:
+        lqo_quant_mxfp8(z, n, c, eb);
+        for (int64_t i = 0; i < n; ++i) e[i] = (float)mxfp8_value(c[i], eb[i / 32]) - z[i];
+        break;
+    case 3:
+        lqo_quant_mxfp6(z, n, c, eb);
+        for (int64_t i = 0; i < n; ++i) e[i] = (float)mxfp6_value(c[i], eb[i / 32]) - z[i];
+        break;
+    default:
+        lqo_quant_mxint(z, n, qparam, (int8_t *)c, eb);
+        for (int64_t i = 0; i < n; ++i) e[i] = (float)mxint_value(((int8_t *)c)[i], eb[i / 32], qparam) - z[i];
+        break;
+    }
+    free(c);
+    free(eb);
+}
+
+LQO_API void lqo_rot_step(int64_t N, int64_t K, int r, int q2, int qparam, const float *L, const float *R, float *Omega,
                           float *Mom, double lr, double beta, double eps, double q, int s, double grad_scale,
                           float *E1_out, float *E2_out, float *G_out, double *loss_out)
 {
@@ -1120,32 +1153,24 @@ LQO_API void lqo_rot_step(int64_t N, int64_t K, int r, int qmax, const float *L,
 #pragma omp parallel for schedule(static)
     for (int64_t n = 0; n < N; ++n) {
         float *z = (float *)malloc(sizeof(float) * (size_t)r);
-        int8_t *c = (int8_t *)malloc((size_t)r);
-        float sc;
         for (int j = 0; j < r; ++j) {
             float v = 0.0f;
             for (int i = 0; i < r; ++i) v = fmaf(L[n * r + i], Omega[i * r + j], v);
             z[j] = v;
         }
-        lqo_quant_int(z, r, qmax, c, &sc);
-        for (int j = 0; j < r; ++j) E1[n * r + j] = (float)c[j] * sc - z[j];
+        rot_quant_err(z, r, q2, qparam, E1 + n * r);
         free(z);
-        free(c);
     }
 #pragma omp parallel for schedule(static)
     for (int j = 0; j < r; ++j) {
         float *z = (float *)malloc(sizeof(float) * (size_t)K);
-        int8_t *c = (int8_t *)malloc((size_t)K);
-        float sc;
         for (int64_t k = 0; k < K; ++k) {
             float v = 0.0f;
             for (int i = 0; i < r; ++i) v = fmaf(Omega[i * r + j], R[(int64_t)i * K + k], v);
             z[k] = v;
         }
-        lqo_quant_int(z, K, qmax, c, &sc);
-        for (int64_t k = 0; k < K; ++k) E2[(int64_t)j * K + k] = (float)c[k] * sc - z[k];
+        rot_quant_err(z, K, q2, qparam, E2 + (int64_t)j * K);
         free(z);
-        free(c);
     }
     double l1 = 0.0, l2 = 0.0;
     for (int64_t i = 0; i < N * r; ++i) l1 += (double)E1[i] * (double)E1[i];

@@ -580,16 +580,22 @@ class RotOut:
     G: np.ndarray        # r x r   Euclidean gradient used by the step
 
 
+Q2_KINDS = {"int": 0, "fp8": 1, "mxfp8": 2, "mxfp6": 3, "mxint": 4}
+
+
 def rot_step(L, R, st: RotState, bits: int = 8, lr: float = 0.5, beta: float = 0.9, eps: float = 1e-8, q: float = 0.5,
-             s: int = 2, grad_scale: float = 1.0) -> RotOut:
-    """One Cayley-SGD step on Omega; updates `st` in place.  bits: width of Q2 (per-row symmetric integers)."""
+             s: int = 2, grad_scale: float = 1.0, q2: str = "int") -> RotOut:
+    """One Cayley-SGD step on Omega; updates `st` in place.  q2: the format of Q2 ("int": per-row symmetric integers of
+    `bits`; "fp8": E4M3 with a per-row fp32 scale; "mxfp8", "mxfp6", "mxint" (of `bits`): blocks of 32 along the row)."""
     L, R = _f32(L), _f32(R)
     N, r = L.shape
     K = R.shape[1]
     assert R.shape[0] == r and st.Omega.shape == (r, r) and st.Mom.shape == (r, r)
     out = RotOut(0.0, np.empty((N, r), np.float32), np.empty((r, K), np.float32), np.empty((r, r), np.float32))
     loss = C.c_double(0.0)
-    lib().lqo_rot_step(C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(2 ** (bits - 1) - 1), _p(L), _p(R), _p(st.Omega),
+    kind = Q2_KINDS[q2]
+    lib().lqo_rot_step(C.c_int64(N), C.c_int64(K), C.c_int(r), C.c_int(kind), C.c_int(2 ** (bits - 1) - 1 if kind == 0 else bits),
+                       _p(L), _p(R), _p(st.Omega),
                        _p(st.Mom), C.c_double(lr), C.c_double(beta), C.c_double(eps), C.c_double(q), C.c_int(s),
                        C.c_double(grad_scale), _p(out.E1), _p(out.E2), _p(out.G), C.byref(loss))
     out.loss = float(loss.value)

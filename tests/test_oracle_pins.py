@@ -1261,3 +1261,43 @@ def test_rot_lossless_factors_are_a_fixed_point_and_apply_keeps_the_product(orac
     assert np.allclose(Lr, L2.astype(np.float64) @ X0, rtol=0, atol=1e-6)
     assert np.allclose(Rr, X0.T.astype(np.float64) @ R2, rtol=0, atol=1e-6)
     assert np.allclose(Lr.astype(np.float64) @ Rr, L2.astype(np.float64) @ R2, rtol=0, atol=2e-6)
+
+
+@pytest.mark.parametrize("q2,bits,half_ulp", [("fp8", 8, 2.0 ** -4), ("mxfp8", 8, 2.0 ** -4), ("mxfp6", 6, 2.0 ** -4), ("mxint", 8, None),
+                                              ("mxint", 4, None)])
+def test_rot_errors_with_mx_branch_formats(oracle, q2, bits, half_ulp):
+    """Eq. 7 with the MX branch formats as Q2 (App. A.3): every reconstructed value Z + E is a representable number of
+    its block (or row) and E is no larger than half the local spacing.  Floating-point elements: relative error at most
+    2^-(m+1) (m = 3 mantissa bits) above the format's smallest normal, and the largest element of a block is exact to
+    that bound; MXINT: multiples of the block step 2^(floor(log2 amax) - (bits - 2)), at most half a step off, except a
+    value rounding to 2^(bits-1) steps, which saturates (a full step at most)."""
+    L, R, X0 = _rot_case(8, N=64, K=128, r=32)
+    st = oracle.rot_init(32, X0)
+    out = oracle.rot_step(L, R, st, bits=bits, lr=0.0, q2=q2)
+    for Z, E in ((L.astype(np.float64) @ X0, out.E1), (X0.T.astype(np.float64) @ R, out.E2)):
+        Zb, Eb = Z.reshape(Z.shape[0], -1, 32), E.astype(np.float64).reshape(Z.shape[0], -1, 32)
+        amax = np.abs(Zb).max(axis=2, keepdims=True) if q2 != "fp8" else np.abs(Z).max(axis=1).reshape(-1, 1, 1)
+        if q2 == "mxint":
+            step = 2.0 ** (np.floor(np.log2(amax)) - (bits - 2))
+            codes = (Zb + Eb) / step
+            assert np.all(np.abs(codes - np.rint(codes)) < 1e-3) and np.abs(np.rint(codes)).max() <= 2 ** (bits - 1) - 1
+            assert np.all(np.abs(Eb) <= step * (1 + 1e-5))
+            inside = np.abs(Zb) / step <= 2 ** (bits - 1) - 1
+            assert np.all(np.abs(Eb)[inside] <= (0.5 * step * np.ones_like(Eb))[inside] * (1 + 1e-5) + 1e-12)
+        else:
+            # elements far enough above the subnormal range of the scaled format: relative error <= 2^-4 (3 mantissa bits)
+            big = np.abs(Zb) >= amax * 2.0 ** -5
+            if q2 != "fp8":   # block formats: elements above the largest code of the scaled format saturate to it
+                top = (448.0 if q2 == "mxfp8" else 7.5) * 2.0 ** (np.floor(np.log2(amax)) - (8 if q2 == "mxfp8" else 2))
+                sat = np.abs(Zb) > top
+                assert np.allclose(np.abs(Zb + Eb)[sat], (top * np.ones_like(Zb))[sat], rtol=1e-6)
+                big &= ~sat
+            assert np.all(np.abs(Eb)[big] <= half_ulp * np.abs(Zb)[big] * (1 + 1e-5))
+            assert np.all(np.abs(Eb) <= 2 * half_ulp * amax * (1 + 1e-5))
+            # the reconstructed values have at most 4 significant bits
+            v = np.abs(Zb + Eb)[big]
+            m, _ = np.frexp(v if q2 != "fp8" else v / (amax * np.ones_like(Zb))[big] * 448.0)
+            if q2 != "fp8":
+                assert np.all(np.abs(m * 16 - np.rint(m * 16)) < 1e-4)
+    assert out.loss == pytest.approx(np.mean(out.E1.astype(np.float64) ** 2) + np.mean(out.E2.astype(np.float64) ** 2), rel=1e-12)
+    assert out.loss > 0
