@@ -230,9 +230,10 @@ lq_status lq_calib_unpack(const lq_config *cfg, const void *state, const lq_cali
 /* ---- Rotation of the calibrated factors before they are quantised (Section 3.3, Eq. 6-7) -----------------------
    Search for an orthogonal r x r matrix Omega that lowers
        loss(Omega) = mean over N x r of ( Q2(L Omega) - L Omega )^2 + mean over r x K of ( Q2(Omega^T R) - Omega^T R )^2 ,
-   the product (L Omega)(Omega^T R) = L R unchanged.  INT family only (anything else: LQ_ERR_UNSUPPORTED): Q2 is the
-   symmetric integer format cfg->br_w with one scale per row of L Omega and per row of Omega^T R, as lq_pack_weights
-   quantises L and R; rank >= 16.  Both products are fp32 fused-multiply-add chains over the rank index, ascending
+   the product (L Omega)(Omega^T R) = L R unchanged.  Q2 is the branch weight format cfg->br_w along the rows of L Omega
+   and of Omega^T R, as lq_pack_weights quantises L and R: symmetric integers (INT family) or FP8 E4M3 (MX family with
+   the fp32-scaled branch) with one fp32 scale per row, or MXFP8e4 / MXFP6e2 / MXINT8 / MXINT4 blocks of 32 along the row
+   with E8M0 scales; rank >= 16.  The main formats of cfg play no part.  Both products are fp32 fused-multiply-add chains over the rank index, ascending
    from zero.  The rounding is treated as having zero derivative (App. B.2), so
        G = -2/(N r) L^T E1 - 2/(r K) R E2^T ,   E1 = Q2(L Omega) - L Omega,  E2 = Q2(Omega^T R) - Omega^T R ,
    times grad_scale.  The update is the Cayley SGD with momentum of the work the paper cites for it (Li et al. 2020,
@@ -244,7 +245,7 @@ lq_status lq_calib_unpack(const lq_config *cfg, const void *state, const lq_cali
    as printed the gradient of a layer-sized problem is of the order of 1e-7 and a step of 0.5 moves Omega by as much;
    grad_scale (1 = as printed) is the caller's handle on that.
    The state blob is device memory owned by the caller (256-byte aligned, at least state_bytes).  A step is five kernel
-   launches, no atomics, no allocation; results are reproducible bit for bit. */
+   launches (four with block-scaled formats), no atomics, no allocation; results are reproducible bit for bit. */
 typedef struct {
     float lr;          /* 0.5 (App. A.2)                                                  */
     float beta;        /* momentum, in [0, 1)                                            */

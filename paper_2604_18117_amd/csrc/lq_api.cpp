@@ -329,8 +329,11 @@ static lq_status rot_dims(const lq_config* cfg, Dims* d)
 {
     lq_status st = make_dims(cfg, d);
     if (st != LQ_OK) return st;
-    if (d->mx || d->mxi) return LQ_ERR_UNSUPPORTED;  // per-row integer Q2 only
     if (d->r < 16) return LQ_ERR_SHAPE;
+    // the search works on the caller's factors (N x r, r x K), not on packed layouts
+    d->K = d->Ks;
+    d->C64 = (int)(d->K / 64);
+    d->G = (int)(d->K / d->g);
     if ((int64_t)d->r * d->K * 4 >= ((int64_t)1 << 31)) return LQ_ERR_UNSUPPORTED;  // R is read with 32-bit byte offsets
     return LQ_OK;
 }

@@ -1,15 +1,16 @@
 // Rotation search for the low-rank factors (Section 3.3, Eq. 6-7): one step on an orthogonal r x r matrix Omega that
 // lowers the error of quantising L Omega and Omega^T R with Q2, the product L R unchanged.
 //     loss(Omega) = mean ( Q2(Z1) - Z1 )^2 + mean ( Q2(Z2) - Z2 )^2,   Z1 = L Omega (N x r),  Z2 = Omega^T R (r x K)
-// Q2: symmetric integers of the branch weight width, one scale per row of Z1 and per row of Z2 (the granularity
-// lq_pack_weights uses for Q2(L) and Q2(R)).  Z1 and Z2 are fp32 chains z = fma(a_i, b_i, z) over the rank index
+// Q2: the branch weight format of the configuration along the rows of Z1 and Z2, as lq_pack_weights applies it to L and R:
+// symmetric integers or FP8 E4M3 with one fp32 scale per row, or MXFP8e4 / MXFP6e2 / MXINT blocks of 32 with E8M0 scales.  Z1 and Z2 are fp32 chains z = fma(a_i, b_i, z) over the rank index
 // ascending (the codes depend on their rounding); the rounding has zero derivative (App. B.2), so
 //     G = -2/(N r) L^T E1 - 2/(r K) R E2^T
 // and the update is the Cayley SGD with momentum of the work the paper cites for it (Li et al. 2020, Algorithm 1).
 // Five launches per step, no atomics, every sum in a fixed order:
 //   rot_zl_kernel     one thread per row of L: Z1 row twice (row maximum, then codes), E1, partial sums of E1^2
 //   rot_zr_kernel     one thread per column of R: the column of Z2 (stored in E2's place), per-wavefront row maxima
-//   rot_qr_kernel     E2 = deq(Q2(Z2)) - Z2 in place, partial sums of E2^2
+//   rot_qr_kernel     E2 = deq(Q2(Z2)) - Z2 in place, partial sums of E2^2 (row-scaled Q2 only: with block scales
+//                     rot_zr_kernel forms E2 itself and a step is four launches)
 //   rot_grad_kernel   partials of L^T E1 and R E2^T over strided 16-deep slices of N and K
 //   rot_cayley_kernel one workgroup: G, loss, momentum, the skew-symmetric W, step length, the fixed-point passes
 #include "lq_internal.h"
@@ -74,22 +75,78 @@ __device__ __forceinline__ float rot_block_sum(float v, float* red)
     return red[0] + red[1] + red[2] + red[3];
 }
 
-// Per-row integer quantiser of lq_pack_weights: scale amax / qmax, codes against qmax / amax, ties to even, clamped.
-__device__ __forceinline__ void rot_scale(float amax, float qmax, float& s, float& inv)
+// Q2, the format lq_pack_weights gives L and R (App. A.3).  Row kinds carry one fp32 scale per row: 0 symmetric integers
+// of qmax, 1 FP8 E4M3 (largest magnitude 448).  Block kinds carry an E8M0 scale per 32 values along the row: 2 MXFP8e4,
+// 3 MXFP6e2, 4 MXINT of `bits`.
+struct RotQ {
+    int kind;
+    float top;  // row kinds: qmax or 448
+    int bits;   // MXINT
+};
+
+// Maximum over the lane's half of the wavefront (lanes 0..31 | 32..63 = one block of 32 columns).
+__device__ __forceinline__ float rot_half_max(float v, int lane)
+{
+    v = rot_dpp_max<0xB1>(v);
+    v = rot_dpp_max<0x4E>(v);
+    v = rot_dpp_max<0x141>(v);
+    v = rot_dpp_max<0x140>(v);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return lane < 32 ? fmaxf(r0, r1) : fmaxf(r2, r3);
+}
+
+// Row kinds: scale amax / top, codes against top / amax (an all-zero row: scale 1).
+__device__ __forceinline__ void rot_scale(float amax, float top, float& s, float& inv)
 {
     if (amax == 0.f) {
         s = 1.f;
         inv = 1.f;
     } else {
-        s = amax / qmax;
-        inv = qmax / amax;
+        s = amax / top;
+        inv = top / amax;
     }
 }
-__device__ __forceinline__ float rot_err(float z, float s, float inv, float qmax)
+__device__ __forceinline__ float rot_fp8_value(float u)  // nearest E4M3 number (ties to even), saturating at 448
 {
-    float c = rintf(z * inv);
+    u = fminf(fmaxf(u, -448.f), 448.f);  // the converter returns NaN above 464
+    const int code = __builtin_amdgcn_cvt_pk_fp8_f32(u, u, 0, false) & 0xFF;
+    return __builtin_amdgcn_cvt_f32_fp8(code, 0);
+}
+__device__ __forceinline__ float rot_err(float z, float s, float inv, const RotQ& q)
+{
+    if (q.kind == 0) {
+        float c = rintf(z * inv);
+        c = fminf(fmaxf(c, -q.top), q.top);
+        return c * s - z;
+    }
+    return rot_fp8_value(z * inv) * s - z;
+}
+
+// Block kinds: the shared exponent floor(log2 amax) - (largest element exponent: 8 for E4M3, 2 for E2M3, 0 for MXINT),
+// kept in [-127, 127]; an all-zero block: -127.
+__device__ __forceinline__ int rot_block_exp(float amax, const RotQ& q)
+{
+    if (amax == 0.f) return -127;
+    const int e = __builtin_amdgcn_frexp_expf(amax) - 1 - (q.kind == 2 ? 8 : q.kind == 3 ? 2 : 0);
+    return e < -127 ? -127 : e > 127 ? 127 : e;
+}
+__device__ __forceinline__ float rot_err_block(float z, int e, const RotQ& q)
+{
+    if (q.kind == 2) return __builtin_ldexpf(rot_fp8_value(__builtin_ldexpf(z, -e)), e) - z;
+    if (q.kind == 3) {  // E2M3: spacing 1/8 below 2, 1/4 below 4, 1/2 up to the largest magnitude 7.5
+        const float m = fminf(fabsf(__builtin_ldexpf(z, -e)), 7.5f);
+        const float step = m < 2.f ? 0.125f : m < 4.f ? 0.25f : 0.5f;
+        const float v = fminf(rintf(m / step) * step, 7.5f);
+        return __builtin_copysignf(__builtin_ldexpf(v, e), z) - z;
+    }
+    const int frac = q.bits - 2;
+    const float qmax = (float)((1 << (q.bits - 1)) - 1);
+    float c = rintf(__builtin_ldexpf(z, frac - e));
     c = fminf(fmaxf(c, -qmax), qmax);
-    return c * s - z;
+    return __builtin_ldexpf(c, e - frac) - z;
 }
 
 // Four neighbouring entries of a row of Z: z[c] = sum_i reg[i] * Om[i][j + c], each an fma chain over ascending i.
@@ -111,7 +168,7 @@ __device__ __forceinline__ v4f rot_chain4(const float (&reg)[R], const float* om
 // One thread per row n of L.  OUTZ: write Z1 = L Omega itself (the rotated factor) instead of its quantisation error.
 template <int R, bool OUTZ>
 __global__ __launch_bounds__(ROT_TPB) void rot_zl_kernel(const float* __restrict__ L, const float* __restrict__ X, int N,
-                                                        float qmax, float* __restrict__ out, float* __restrict__ lp)
+                                                        RotQ q, float* __restrict__ out, float* __restrict__ lp)
 {
     extern __shared__ __attribute__((aligned(16))) float om[];
     __shared__ float red[4];
@@ -133,37 +190,51 @@ __global__ __launch_bounds__(ROT_TPB) void rot_zl_kernel(const float* __restrict
             if (ok) *(v4f*)(out + (size_t)n * R + j) = z;
         }
     } else {
-        float amax = 0.f;
+        // one scale per row (row kinds) or per 32 columns (block kinds): span by span, the chains run twice
+        const int span = (q.kind <= 1 || R < 32) ? R : 32;  // (block formats come with ranks that are multiples of 32)
 #pragma unroll 1
-        for (int j = 0; j < R; j += 4) {
-            const v4f z = rot_chain4<R>(reg, om, j);
-            amax = fmaxf(fmaxf(amax, fmaxf(fabsf(z[0]), fabsf(z[1]))), fmaxf(fabsf(z[2]), fabsf(z[3])));
-        }
-        float s, inv;
-        rot_scale(amax, qmax, s, inv);
+        for (int j0 = 0; j0 < R; j0 += span) {
+            float amax = 0.f;
 #pragma unroll 1
-        for (int j = 0; j < R; j += 4) {
-            const v4f z = rot_chain4<R>(reg, om, j);  // the same chains: the same bits as in the first pass
-            v4f e;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                e[c] = rot_err(z[c], s, inv, qmax);
-                sq = __builtin_fmaf(e[c], e[c], sq);
+            for (int j = j0; j < j0 + span; j += 4) {
+                const v4f z = rot_chain4<R>(reg, om, j);
+                amax = fmaxf(fmaxf(amax, fmaxf(fabsf(z[0]), fabsf(z[1]))), fmaxf(fabsf(z[2]), fabsf(z[3])));
             }
-            if (ok) *(v4f*)(out + (size_t)n * R + j) = e;
+            float s = 1.f, inv = 1.f;
+            int eb = 0;
+            if (q.kind <= 1)
+                rot_scale(amax, q.top, s, inv);
+            else
+                eb = rot_block_exp(amax, q);
+#pragma unroll 1
+            for (int j = j0; j < j0 + span; j += 4) {
+                const v4f z = rot_chain4<R>(reg, om, j);  // the same chains: the same bits as in the first pass
+                v4f e;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    e[c] = q.kind <= 1 ? rot_err(z[c], s, inv, q) : rot_err_block(z[c], eb, q);
+                    sq = __builtin_fmaf(e[c], e[c], sq);
+                }
+                if (ok) *(v4f*)(out + (size_t)n * R + j) = e;
+            }
         }
         const float tot = rot_block_sum(ok ? sq : 0.f, red);
         if (threadIdx.x == 0) lp[blockIdx.x] = tot;
     }
 }
 
-// One thread per column k of R: the column of Z2 = Omega^T R, written to out[j][k]; OUTZ = false also leaves the
-// maximum magnitude of every row j over the wavefront's 64 columns in ax[4 * block + wavefront][j].
+// One thread per column k of R: the column of Z2 = Omega^T R.  OUTZ: written to out[j][k] as it is.  Otherwise, row kinds
+// of Q2: Z2 is written and the maximum magnitude of every row j over the wavefront's 64 columns is left in
+// ax[4 * block + wavefront][j] (rot_qr_kernel finishes the job); block kinds: a block is 32 lanes of one row, so the error
+// is formed here, written to out, and its squares are summed into lp[block].
 template <int R, bool OUTZ>
 __global__ __launch_bounds__(ROT_TPB) void rot_zr_kernel(const float* __restrict__ Rm, const float* __restrict__ X, int K,
-                                                        float* __restrict__ out, float* __restrict__ ax)
+                                                        RotQ q, float* __restrict__ out, float* __restrict__ ax,
+                                                        float* __restrict__ lp)
 {
     extern __shared__ __attribute__((aligned(16))) float om[];
+    __shared__ float red[4];
+    float sq = 0.f;
     for (int i = threadIdx.x; i < R * R; i += ROT_TPB) om[i] = X[i];
     __syncthreads();
     const int k = blockIdx.x * ROT_TPB + threadIdx.x;
@@ -181,29 +252,42 @@ __global__ __launch_bounds__(ROT_TPB) void rot_zr_kernel(const float* __restrict
         const v4f z = rot_chain4<R>(reg, om, j);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (ok) out[(size_t)(j + c) * K + k] = z[c];
+            float o = z[c];
             if constexpr (!OUTZ) {
-                const float m = rot_wave_max(ok ? fabsf(z[c]) : 0.f);
-                if (lane == 0) ax[(size_t)(blockIdx.x * 4 + wave) * R + j + c] = m;
+                if (q.kind <= 1) {
+                    const float m = rot_wave_max(ok ? fabsf(z[c]) : 0.f);
+                    if (lane == 0) ax[(size_t)(blockIdx.x * 4 + wave) * R + j + c] = m;
+                } else {
+                    const int eb = rot_block_exp(rot_half_max(ok ? fabsf(z[c]) : 0.f, lane), q);
+                    o = rot_err_block(z[c], eb, q);
+                    if (ok) sq = __builtin_fmaf(o, o, sq);
+                }
             }
+            if (ok) out[(size_t)(j + c) * K + k] = o;
+        }
+    }
+    if constexpr (!OUTZ) {
+        if (q.kind > 1) {  // (uniform over the grid)
+            const float tot = rot_block_sum(sq, red);
+            if (threadIdx.x == 0) lp[blockIdx.x] = tot;
         }
     }
 }
 
 // E2 = deq(Q2(Z2)) - Z2 in place; grid (column blocks, r).
 __global__ __launch_bounds__(ROT_TPB) void rot_qr_kernel(float* __restrict__ E2, const float* __restrict__ ax, int K, int r,
-                                                        int nparts, float qmax, float* __restrict__ lp)
+                                                        int nparts, RotQ q, float* __restrict__ lp)
 {
     __shared__ float red[4];
     const int j = blockIdx.y;
     float amax = 0.f;
     for (int p = 0; p < nparts; ++p) amax = fmaxf(amax, ax[(size_t)p * r + j]);
     float s, inv;
-    rot_scale(amax, qmax, s, inv);
+    rot_scale(amax, q.top, s, inv);
     const int k = blockIdx.x * ROT_TPB + threadIdx.x;
     float sq = 0.f;
     if (k < K) {
-        const float e = rot_err(E2[(size_t)j * K + k], s, inv, qmax);
+        const float e = rot_err(E2[(size_t)j * K + k], s, inv, q);
         E2[(size_t)j * K + k] = e;
         sq = e * e;
     }
@@ -431,29 +515,40 @@ hipError_t launch_rot_init(const Dims& d, const float* Omega0, const float* Mom0
     return hipGetLastError();
 }
 
+// Q2 of the configuration: the branch weight format.
+static RotQ rot_q2(const Dims& d)
+{
+    RotQ q;
+    q.kind = d.mxi ? 4 : d.mxb ? (d.mxb_elem == 8 ? 2 : 3) : d.mx ? 1 : 0;
+    q.top = q.kind == 0 ? (float)d.qmax_bw : 448.f;
+    q.bits = d.mxi ? d.bw_bits : 0;
+    return q;
+}
+
 template <int R, bool OUTZ>
-static void rot_launch_z(const Dims& d, const RotLayout& rl, const float* L, const float* Rm, const float* X, float* o1,
-                         float* o2, float* ax, float* lp, hipStream_t s)
+static void rot_launch_z(const Dims& d, const RotLayout& rl, const RotQ& q, const float* L, const float* Rm, const float* X,
+                         float* o1, float* o2, float* ax, float* lp, hipStream_t s)
 {
     const size_t lds = (size_t)R * R * 4;
     if constexpr (R == 128) {  // Omega alone fills the 64 KB a launch may use without asking for more
         (void)hipFuncSetAttribute((const void*)rot_zl_kernel<R, OUTZ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         (void)hipFuncSetAttribute((const void*)rot_zr_kernel<R, OUTZ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     }
-    hipLaunchKernelGGL((rot_zl_kernel<R, OUTZ>), dim3(rl.nlb), dim3(ROT_TPB), lds, s, L, X, (int)d.N, (float)d.qmax_bw, o1, lp);
-    hipLaunchKernelGGL((rot_zr_kernel<R, OUTZ>), dim3(rl.nkb), dim3(ROT_TPB), lds, s, Rm, X, (int)d.K, o2, ax);
+    hipLaunchKernelGGL((rot_zl_kernel<R, OUTZ>), dim3(rl.nlb), dim3(ROT_TPB), lds, s, L, X, (int)d.N, q, o1, lp);
+    hipLaunchKernelGGL((rot_zr_kernel<R, OUTZ>), dim3(rl.nkb), dim3(ROT_TPB), lds, s, Rm, X, (int)d.K, q, o2, ax,
+                       lp ? lp + rl.nlb : nullptr);
 }
 
 template <bool OUTZ>
-static void rot_dispatch_z(const Dims& d, const RotLayout& rl, const float* L, const float* Rm, const float* X, float* o1,
-                           float* o2, float* ax, float* lp, hipStream_t s)
+static void rot_dispatch_z(const Dims& d, const RotLayout& rl, const RotQ& q, const float* L, const float* Rm, const float* X,
+                           float* o1, float* o2, float* ax, float* lp, hipStream_t s)
 {
     switch (d.r) {
-        case 16: rot_launch_z<16, OUTZ>(d, rl, L, Rm, X, o1, o2, ax, lp, s); break;
-        case 32: rot_launch_z<32, OUTZ>(d, rl, L, Rm, X, o1, o2, ax, lp, s); break;
-        case 64: rot_launch_z<64, OUTZ>(d, rl, L, Rm, X, o1, o2, ax, lp, s); break;
-        case 96: rot_launch_z<96, OUTZ>(d, rl, L, Rm, X, o1, o2, ax, lp, s); break;
-        default: rot_launch_z<128, OUTZ>(d, rl, L, Rm, X, o1, o2, ax, lp, s); break;
+        case 16: rot_launch_z<16, OUTZ>(d, rl, q, L, Rm, X, o1, o2, ax, lp, s); break;
+        case 32: rot_launch_z<32, OUTZ>(d, rl, q, L, Rm, X, o1, o2, ax, lp, s); break;
+        case 64: rot_launch_z<64, OUTZ>(d, rl, q, L, Rm, X, o1, o2, ax, lp, s); break;
+        case 96: rot_launch_z<96, OUTZ>(d, rl, q, L, Rm, X, o1, o2, ax, lp, s); break;
+        default: rot_launch_z<128, OUTZ>(d, rl, q, L, Rm, X, o1, o2, ax, lp, s); break;
     }
 }
 
@@ -468,9 +563,10 @@ hipError_t launch_rot_step(const Dims& d, const float* L, const float* Rm, uint8
     float* lp = (float*)(state + rl.off_lp);
     float* gp = (float*)(state + rl.off_gp);
     const int N = (int)d.N, K = (int)d.K, r = d.r;
-    rot_dispatch_z<false>(d, rl, L, Rm, X, E1, E2, ax, lp, s);
-    hipLaunchKernelGGL(rot_qr_kernel, dim3(rl.nkb, r), dim3(ROT_TPB), 0, s, E2, ax, K, r, rl.nkb * 4, (float)d.qmax_bw,
-                       lp + rl.nlb);
+    const RotQ q = rot_q2(d);
+    rot_dispatch_z<false>(d, rl, q, L, Rm, X, E1, E2, ax, lp, s);
+    if (q.kind <= 1)
+        hipLaunchKernelGGL(rot_qr_kernel, dim3(rl.nkb, r), dim3(ROT_TPB), 0, s, E2, ax, K, r, rl.nkb * 4, q, lp + rl.nlb);
     const float c1 = (float)(-2.0 / ((double)N * r)), c2 = (float)(-2.0 / ((double)r * K));
     switch (r >> 4) {
         case 1: hipLaunchKernelGGL(rot_grad_kernel<1>, dim3(ROT_GRAD_WGS), dim3(ROT_TPB), 0, s, L, E1, Rm, E2, N, K, c1, c2, gp); break;
@@ -489,7 +585,7 @@ hipError_t launch_rot_step(const Dims& d, const float* L, const float* Rm, uint8
     p.loss = loss;
     p.r = r;
     p.nlb = rl.nlb;
-    p.n_lp = rl.n_lp;
+    p.n_lp = q.kind <= 1 ? rl.n_lp : rl.nlb + rl.nkb;
     p.nparts = ROT_GRAD_WGS;
     p.inv1 = (float)(1.0 / ((double)N * r));
     p.inv2 = (float)(1.0 / ((double)r * K));
@@ -510,7 +606,7 @@ hipError_t launch_rot_apply(const Dims& d, const float* L, const float* Rm, cons
                             hipStream_t s)
 {
     const RotLayout rl = rot_layout(d);
-    rot_dispatch_z<true>(d, rl, L, Rm, (const float*)(state + rl.off_X), Lr, Rr, nullptr, nullptr, s);
+    rot_dispatch_z<true>(d, rl, rot_q2(d), L, Rm, (const float*)(state + rl.off_X), Lr, Rr, nullptr, nullptr, s);
     return hipGetLastError();
 }
 

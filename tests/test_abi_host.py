@@ -244,9 +244,12 @@ def test_rotation_contract(lq):
         assert raw.lq_rot_step(C.byref(cfg), good, good, good, sb, C.byref(bad), None, None) == lq.LQ_ERR_UNSUPPORTED
     assert raw.lq_rot_apply(C.byref(cfg), good, good, good, None, good, None) == lq.LQ_ERR_NULL
     assert raw.lq_rot_unpack(C.byref(cfg), good, None, None) == lq.LQ_ERR_NULL
-    # integer per-row Q2 only; a branch to rotate
+    # every family's branch format; the state is sized by the caller's K (2240 = 35 chunks of 64, padded only inside packed blobs)
     for fam in ("mx", "mxb", "mxi"):
-        assert raw.lq_rot_sizes(C.byref(lq.make_config(128, 256, 32, fam, 32)), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+        assert raw.lq_rot_sizes(C.byref(lq.make_config(128, 256, 32, fam, 32)), C.byref(n)) == lq.LQ_OK and n.value == want
+    a, b = lq.lq_rot_sizes(lq.make_config(128, 2240, 32, "mxb", 32)), lq.lq_rot_sizes(lq.make_config(128, 2240, 32))
+    assert a == b
+    # a branch to rotate
     assert raw.lq_rot_sizes(C.byref(lq.make_config(128, 256, 0)), C.byref(n)) == lq.LQ_ERR_SHAPE
 
 

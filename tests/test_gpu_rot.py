@@ -24,26 +24,31 @@ def _case(N, K, r, seed, outlier=8.0):
     return L, R, X0, M0
 
 
-def _cfg(lq, N, K, r, bits):
-    return lq.make_config(N, K, r, "int", 64, bits, 8)
+FAMILY = {"int": "int", "fp8": "mx", "mxfp8": "mxb", "mxfp6": "mxb", "mxint": "mxi"}
+
+
+def _cfg(lq, N, K, r, bits, q2="int"):
+    if q2 == "int":
+        return lq.make_config(N, K, r, "int", 64, bits, 8)
+    return lq.make_config(N, K, r, FAMILY[q2], 32, bits, 8)
 
 
 def _d(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def _compare_step(oracle, lq, N, K, r, bits, seed, X0=None, M0=None, **opt):
+def _compare_step(oracle, lq, N, K, r, bits, seed, X0=None, M0=None, q2="int", **opt):
     L, R, Xr, Mr = _case(N, K, r, seed)
     X0 = Xr if X0 is None else X0
     M0 = Mr if M0 is None else M0
-    cfg = _cfg(lq, N, K, r, bits)
+    cfg = _cfg(lq, N, K, r, bits, q2)
     Ld, Rd = _d(L), _d(R)
     state = lq.lq_rot_init(cfg, _d(X0), _d(M0))
     loss = torch.zeros(1, dtype=torch.float32, device="cuda")
     lq.lq_rot_step(cfg, Ld, Rd, state, loss=loss, **opt)
     got = {k: v.cpu().numpy() for k, v in lq.lq_rot_unpack(cfg, state, ("Omega", "Mom", "G", "E1", "E2")).items()}
     st = oracle.rot_init(r, X0, M0)
-    ref = oracle.rot_step(L, R, st, bits=bits, **opt)
+    ref = oracle.rot_step(L, R, st, bits=bits, q2=q2, **opt)
     assert np.array_equal(got["E1"], ref.E1), "E1 differs"
     assert np.array_equal(got["E2"], ref.E2), "E2 differs"
     assert float(loss.item()) == pytest.approx(ref.loss, rel=1e-5)
@@ -71,6 +76,18 @@ def test_full_size_layers(oracle, name, bits):
     from paper_2604_18117_amd import binding as lq
     l = wl.LAYERS[name]
     _compare_step(oracle, lq, l.N, l.K, l.r, bits, seed=7, lr=0.5, beta=0.9, s=2, grad_scale=20000.0)
+
+
+@pytest.mark.parametrize("q2,bits", [("fp8", 8), ("mxfp8", 8), ("mxfp6", 6), ("mxint", 8), ("mxint", 4)])
+@pytest.mark.parametrize("N,K,r", [(320, 448, 32), (192, 2240, 64), (576, 1344, 128), (1152, 1152, 96)])
+def test_mx_branch_formats_as_q2(oracle, q2, bits, N, K, r):
+    """Q2 = the branch weight format of the MX families: E4M3 with a per-row fp32 scale (config 5), MXFP8e4, MXFP6e2, MXINT8
+    and MXINT4 blocks of 32 along the rows of L Omega and Omega^T R.  K = 2240 is 35 chunks of 64 (the search works on
+    the caller's K, not the padded layout); K = 448 and 1344 end inside a 256-column workgroup."""
+    from paper_2604_18117_amd import binding as lq
+    if q2 == "fp8" and r == 96:
+        pytest.skip("rank 96 is not a rank of the fp32-scaled FP8 branch")
+    _compare_step(oracle, lq, N, K, r, bits, seed=N + r, q2=q2, lr=0.5, beta=0.9, s=2, grad_scale=2500.0)
 
 
 def test_defaults_identity_start_and_more_passes(oracle):
