@@ -41,7 +41,7 @@
  *   - Inputs must be finite (NaN / Inf give undefined codes).
  *   - Shape contract: K % 64 == 0, K % main_w_group == 0, N % 64 == 0,
  *     rank in {0,16,32,64,96,128} ({0,32,64,96,128} with a block-scaled branch, {0,16,32,64,128} with the fp32-scaled
- *     FP8 branch), 1 <= M,
+ *     FP8 branch), 0 <= M <= 2^24 (M = 0, an empty batch: LQ_OK, nothing is launched and no pointer is looked at),
  *     row strides >= row lengths.
  *   - Calls are deterministic: no atomics, no split-K; repeated calls give identical bits.
  */

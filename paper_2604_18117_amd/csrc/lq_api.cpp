@@ -164,7 +164,7 @@ lq_status lq_act_sizes(const lq_config* cfg, int64_t M, size_t* act_bytes)
     Dims d;
     lq_status st = make_dims(cfg, &d);
     if (st != LQ_OK) return st;
-    if (M < 1 || M > (1 << 24)) return LQ_ERR_SHAPE;
+    if (M < 0 || M > (1 << 24)) return LQ_ERR_SHAPE;
     *act_bytes = act_layout(d, M).total;
     return LQ_OK;
 }
@@ -205,6 +205,7 @@ lq_status lq_quantize_act(const lq_config* cfg, const void* packed, const void* 
     Dims d;
     lq_status st = make_dims(cfg, &d);
     if (st != LQ_OK) return st;
+    if (M == 0) return LQ_OK;  // an empty batch: nothing to do, no launch, the pointers are not looked at
     if (!X || !act) return LQ_ERR_NULL;
     if ((d.r > 0 || d.smooth) && !packed) return LQ_ERR_NULL;
     if (M < 1 || M > (1 << 24) || ldx < d.Ks) return LQ_ERR_SHAPE;
@@ -227,6 +228,7 @@ lq_status lq_linear_lowrank_fwd(const lq_config* cfg, const void* packed, const 
     Dims d;
     lq_status st = make_dims(cfg, &d);
     if (st != LQ_OK) return st;
+    if (M == 0) return LQ_OK;  // an empty batch
     if (!packed || !act || !Y) return LQ_ERR_NULL;
     if (M < 1 || M > (1 << 24) || ldy < d.N) return LQ_ERR_SHAPE;
     if (!aligned(packed, 256) || !aligned(act, 256) || !aligned(Y, 16) || (ldy & 7)) return LQ_ERR_ALIGN;
@@ -257,6 +259,7 @@ lq_status lq_unpack_act(const lq_config* cfg, const void* act, int64_t M, const 
     Dims d;
     lq_status st = make_dims(cfg, &d);
     if (st != LQ_OK) return st;
+    if (M == 0) return LQ_OK;  // an empty batch
     if (!act || !out) return LQ_ERR_NULL;
     if (M < 1 || M > (1 << 24)) return LQ_ERR_SHAPE;
     if (!aligned(act, 256)) return LQ_ERR_ALIGN;

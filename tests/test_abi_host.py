@@ -141,7 +141,14 @@ def test_argument_errors_before_any_launch(lq):
     assert raw.lq_pack_weights(C.byref(cfg), good, good, good, good, pb - 1, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
     assert raw.lq_quantize_act(C.byref(cfg), good, None, 64, 256, good, ab, None, None) == lq.LQ_ERR_NULL
     assert raw.lq_quantize_act(C.byref(cfg), None, good, 64, 256, good, ab, None, None) == lq.LQ_ERR_NULL
-    assert raw.lq_quantize_act(C.byref(cfg), good, good, 0, 256, good, ab, None, None) == lq.LQ_ERR_SHAPE
+    assert raw.lq_quantize_act(C.byref(cfg), good, good, -1, 256, good, ab, None, None) == lq.LQ_ERR_SHAPE
+    # an empty batch is a successful no-op on every per-call entry point: nothing launched, pointers not examined
+    assert raw.lq_quantize_act(C.byref(cfg), None, None, 0, 256, None, 0, None, None) == lq.LQ_OK
+    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), None, None, 0, None, 128, None, None) == lq.LQ_OK
+    assert raw.lq_unpack_act(C.byref(cfg), None, 0, None, None) == lq.LQ_OK
+    zero = C.c_size_t(99)
+    assert raw.lq_act_sizes(C.byref(cfg), 0, C.byref(zero)) == lq.LQ_OK and zero.value == 0
+    assert raw.lq_act_sizes(C.byref(cfg), -1, C.byref(zero)) == lq.LQ_ERR_SHAPE
     assert raw.lq_quantize_act(C.byref(cfg), good, good, 64, 255, good, ab, None, None) == lq.LQ_ERR_SHAPE
     assert raw.lq_quantize_act(C.byref(cfg), good, good, 64, 260, good, ab, None, None) == lq.LQ_ERR_ALIGN
     assert raw.lq_quantize_act(C.byref(cfg), good, odd, 64, 256, good, ab, None, None) == lq.LQ_ERR_ALIGN
@@ -151,7 +158,7 @@ def test_argument_errors_before_any_launch(lq):
     assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, good, 64, good, 132, None, None) == lq.LQ_ERR_ALIGN
     assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, good, 64, odd, 128, None, None) == lq.LQ_ERR_ALIGN
     assert raw.lq_unpack_weights(C.byref(cfg), None, None, None) == lq.LQ_ERR_NULL
-    assert raw.lq_unpack_act(C.byref(cfg), good, 0, None, None) == lq.LQ_ERR_NULL
+    assert raw.lq_unpack_act(C.byref(cfg), good, 64, None, None) == lq.LQ_ERR_NULL
     # K beyond the register-resident row of the activation kernels is accepted (long rows are streamed); a wrong row
     # stride is still caught first
     for fam in ("int", "mx"):

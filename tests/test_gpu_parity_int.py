@@ -297,3 +297,25 @@ def test_long_rows_are_streamed(oracle, M, K, N, r, xd, ag, sm):
     assert np.array_equal(n(g.adbg.xb), act.xb) and np.array_equal(n(g.adbg.accT), act.accT)
     assert np.array_equal(n(g.av.tq), act.tq) and np.array_equal(n(g.av.st), act.st)
     assert np.array_equal(n(g.fdbg.y32), out.y32) and np.array_equal(bf16_to_bits(g.Y), out.Y)
+
+
+@pytest.mark.parametrize("family", ["int", "mx", "mxb", "mxi"])
+def test_empty_batch_is_a_no_op(oracle, family):
+    """M = 0 on every per-call entry point: LQ_OK, empty results, nothing launched (the stream stays usable)."""
+    from paper_2604_18117_amd import binding as lq
+    N, K, r = 128, 256, 32
+    cfg = lq.make_config(N, K, r, family, 64 if family == "int" else 32)
+    rng = np.random.default_rng(0)
+    W = torch.from_numpy((rng.standard_normal((N, K)) * 0.02).astype(np.float32)).cuda()
+    L = torch.from_numpy((rng.standard_normal((N, r)) * 0.01).astype(np.float32)).cuda()
+    R = torch.from_numpy((rng.standard_normal((r, K)) * 0.01).astype(np.float32)).cuda()
+    packed = lq.lq_pack_weights(cfg, W, L, R)
+    X = torch.empty((0, K), dtype=torch.bfloat16, device="cuda")
+    act = lq.lq_quantize_act(cfg, packed, X)
+    Y = lq.lq_linear_lowrank_fwd(cfg, packed, act, 0)
+    torch.cuda.synchronize()
+    assert tuple(Y.shape) == (0, N)
+    X1 = torch.ones((8, K), dtype=torch.bfloat16, device="cuda")      # and the next, non-empty call works
+    Y1 = lq.lq_linear_lowrank_fwd(cfg, packed, lq.lq_quantize_act(cfg, packed, X1), 8)
+    torch.cuda.synchronize()
+    assert tuple(Y1.shape) == (8, N) and bool(torch.isfinite(Y1.float()).all())
