@@ -531,8 +531,15 @@ static void rot_launch_z(const Dims& d, const RotLayout& rl, const RotQ& q, cons
 {
     const size_t lds = (size_t)R * R * 4;
     if constexpr (R == 128) {  // Omega alone fills the 64 KB a launch may use without asking for more
-        (void)hipFuncSetAttribute((const void*)rot_zl_kernel<R, OUTZ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        (void)hipFuncSetAttribute((const void*)rot_zr_kernel<R, OUTZ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        // once per device and kernel pair, so that later calls (which a caller may capture in a graph) only launch
+        static bool asked[64] = {false};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+        if (!asked[dev]) {
+            (void)hipFuncSetAttribute((const void*)rot_zl_kernel<R, OUTZ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            (void)hipFuncSetAttribute((const void*)rot_zr_kernel<R, OUTZ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            asked[dev] = true;
+        }
     }
     hipLaunchKernelGGL((rot_zl_kernel<R, OUTZ>), dim3(rl.nlb), dim3(ROT_TPB), lds, s, L, X, (int)d.N, q, o1, lp);
     hipLaunchKernelGGL((rot_zr_kernel<R, OUTZ>), dim3(rl.nkb), dim3(ROT_TPB), lds, s, Rm, X, (int)d.K, q, o2, ax,
