@@ -333,7 +333,7 @@ hipError_t launch_unpack_weights_mx(const Dims& d, const uint8_t* packed, const 
 {
     if (d.mxb_elem == 6) return launch_unpack_weights_mx6(d, packed, out, s);
     const PackedLayout pl = packed_layout(d);
-    const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * d.Ks;
+    const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * (d.Ks > d.r ? d.Ks : d.r);  // covers N x K, r x K and N x r
     hipLaunchKernelGGL(mx_unpack_w_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, packed, pl, (int)d.N,
                        (int)d.Ks, d.C64, d.r, d.rp, d.mxb ? 1 : 0, *out);
     return hipGetLastError();
@@ -1152,7 +1152,7 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
 #pragma unroll
     for (int cbi = 0; cbi < 2; ++cbi) {
         const int col = (cb0 + cbi) * 32 + l32;
-        if (!BLK) slv[cbi] = p.sl[col];
+        if (!BLK && NK > 0) slv[cbi] = p.sl[col];
 #pragma unroll
         for (int kk = 0; kk < NKF; ++kk) lf[cbi][kk] = *(const v8i*)(p.l8 + (size_t)col * p.rp + kk * 64 + half * 32);
     }
@@ -1169,7 +1169,7 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
         for (int kk = 0; kk < NKF; ++kk) tf[kk] = *(const v8i*)(p.tq8 + (size_t)(rb * 32 + l32) * p.rp + kk * 64 + half * 32);
     };
     auto load_scales = [&](int rbi) {
-        if (BLK) return;
+        if (BLK || NK == 0) return;  // no fp32-scaled branch: its scale sections may hold anything
         int rb = rb0 + rbi;
         rb = rb < p.nrb ? rb : p.nrb - 1;
 #pragma unroll
@@ -1201,6 +1201,8 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
             for (int i = 0; i < 16; ++i) {
                 if (BLK) {
                     y[cbi][i] = t[rbi][cbi][i];
+                } else if (NK == 0) {  // rank 0: the branch term is +0, whatever the (unused, possibly unwritten) scales hold
+                    y[cbi][i] = __fadd_rn(t[rbi][cbi][i], 0.f);
                 } else {
                     const float ybr = __fmul_rn(__fmul_rn(a2[cbi][i], stv[i >> 2][i & 3]), slv[cbi]);
                     y[cbi][i] = __fadd_rn(t[rbi][cbi][i], ybr);

@@ -153,7 +153,7 @@ __global__ __launch_bounds__(256) void mx6_unpack_w_kernel(const uint8_t* packed
 hipError_t launch_unpack_weights_mx6(const Dims& d, const uint8_t* packed, const lq_weights_view* out, hipStream_t s)
 {
     const PackedLayout pl = packed_layout(d);
-    const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * d.Ks;
+    const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * (d.Ks > d.r ? d.Ks : d.r);  // covers N x K, r x K and N x r
     hipLaunchKernelGGL(mx6_unpack_w_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, packed, pl, (int)d.N, (int)d.Ks,
                        d.C64, d.r, d.rp, *out);
     return hipGetLastError();

@@ -220,7 +220,7 @@ __global__ __launch_bounds__(256) void mxi_unpack_w_kernel(MxiPackedPtrs pp, int
 hipError_t launch_unpack_weights_mxi(const Dims& d, const uint8_t* packed, const lq_weights_view* out, hipStream_t s)
 {
     const MxiPackedPtrs pp = mxi_packed_ptrs(d, const_cast<uint8_t*>(packed));
-    const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * d.K;
+    const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * (d.K > d.r ? d.K : d.r);  // covers N x K, r x K and N x r
     hipLaunchKernelGGL(mxi_unpack_w_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, pp, (int)d.N, (int)d.K,
                        d.r, d.rp, d.bw_bits, *out);
     return hipGetLastError();

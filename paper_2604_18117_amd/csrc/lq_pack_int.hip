@@ -220,7 +220,7 @@ hipError_t launch_unpack_weights_int(const Dims& d, const uint8_t* packed, const
                                      hipStream_t s)
 {
     const PackedLayout pl = packed_layout(d);
-    const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * d.K;
+    const size_t n = (size_t)(d.N > d.r ? d.N : d.r) * (d.K > d.r ? d.K : d.r);  // covers N x K, r x K and N x r
     hipLaunchKernelGGL(unpack_w_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, packed, pl, (int)d.N,
                        (int)d.K, d.r, d.rp, d.g, d.ga ? 1 : 0, *out);
     return hipGetLastError();

@@ -39,7 +39,9 @@ def run_gpu(layer, X, W, L, R, debug=True, debug_acc=True, gamma=None):
     Ld = torch.from_numpy(L).cuda() if layer.r else None
     Rd = torch.from_numpy(R).cuda() if layer.r else None
     Xd = to_dev_x(X, layer.x_dtype)
-    packed = lq.lq_pack_weights(cfg, Wd, Ld, Rd)
+    # both blobs start as 0xFF bytes (NaN patterns as floats): a kernel that reads a section nobody wrote (e.g. branch
+    # scales at rank 0) then shows up as NaN instead of passing on memory that happened to be zero
+    packed = lq.lq_pack_weights(cfg, Wd, Ld, Rd, packed=torch.full((lq.lq_packed_sizes(cfg),), 0xFF, dtype=torch.uint8, device="cuda"))
     if gamma is not None:
         lq.lq_set_smoothing(cfg, packed, torch.from_numpy(np.ascontiguousarray(gamma, np.float32)).cuda())
     M = X.shape[0]
@@ -47,13 +49,14 @@ def run_gpu(layer, X, W, L, R, debug=True, debug_acc=True, gamma=None):
         debug_acc = False
     # the output starts as a bit pattern the path never produces (a NaN): a tile the grid skipped would keep it
     Y0 = torch.full((M, layer.N), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+    act0 = torch.full((lq.lq_act_sizes(cfg, M),), 0xFF, dtype=torch.uint8, device="cuda")
     if debug:
-        act, adbg = lq.lq_quantize_act(cfg, packed, Xd, debug=True)
+        act, adbg = lq.lq_quantize_act(cfg, packed, Xd, act=act0, debug=True)
         Y, fdbg = lq.lq_linear_lowrank_fwd(cfg, packed, act, M, Y=Y0, debug=True, debug_acc=debug_acc)
         out = GpuRun(cfg, packed, act, Y, lq.lq_unpack_weights(cfg, packed), lq.lq_unpack_act(cfg, act, M),
                      adbg, fdbg)
     else:
-        act = lq.lq_quantize_act(cfg, packed, Xd)
+        act = lq.lq_quantize_act(cfg, packed, Xd, act=act0)
         Y = lq.lq_linear_lowrank_fwd(cfg, packed, act, M, Y=Y0)
         out = GpuRun(cfg, packed, act, Y)
     torch.cuda.synchronize()

@@ -65,6 +65,8 @@ SMALL = [
     (1, 64, 64, 16, 64, 8, 8, "f32"),
     (200, 448, 320, 96, 64, 6, 6, "bf16"),    # rank 96: the 6-bit point of a 512-bit budget (85) padded
     (90, 256, 128, 96, 128, 6, 6, "f32"),
+    (50, 64, 128, 128, 64, 8, 8, "bf16"),    # rank > K: the factor views are larger than N x K
+    (33, 64, 192, 96, 64, 6, 6, "f32"),
 ]
 
 

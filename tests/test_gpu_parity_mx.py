@@ -63,7 +63,7 @@ def _compare(oracle, layer, X, W, L, R, rows=None, gamma=None):
         assert np.allclose(st_gpu, act.st, rtol=2e-4, atol=0), "st"
         diff = tq_gpu != act.tq8
         diff &= ~(((tq_gpu & 0x7F) == 0) & ((act.tq8 & 0x7F) == 0))
-        assert diff.mean() <= 1e-2, f"tq8 mismatch rate {diff.mean()}"
+        assert diff.sum() <= max(1, 1e-2 * diff.size), f"tq8 mismatch rate {diff.mean()}"  # (one code may differ on a tiny sample; the rounding check below is the bar)
         # every GPU code is a correct E4M3 rounding of a value within the accumulation bound of the
         # oracle's T: |deq - T| <= half the local code spacing (in units of st) + bound
         u = np.abs(act.T.astype(np.float64)) / st_gpu[:, None]
@@ -109,6 +109,8 @@ SMALL = [
     (64, 128, 64, 0, "bf16"),
     (33, 640, 128, 128, "bf16"),
     (1, 128, 64, 32, "f32"),
+    (33, 64, 576, 128, "bf16"),       # rank > K: the factor views are larger than N x K
+    (255, 192, 256, 0, "f32"),        # rank 0: no branch section of either blob is read
 ]
 
 

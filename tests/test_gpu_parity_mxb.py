@@ -58,7 +58,7 @@ def _compare(oracle, layer, X, W, L, R, rows=None, gamma=None):
         assert np.all(np.abs(T_gpu - act.T) <= tb), f"T max excess {np.max(np.abs(T_gpu - act.T) / tb)}"
         # block exponents: equal except where a block's amax sits within the bound of a power of two
         ediff = te_gpu != act.te
-        assert ediff.mean() <= 1e-2, f"te mismatch rate {ediff.mean()}"
+        assert ediff.sum() <= max(1, 1e-2 * ediff.size), f"te mismatch rate {ediff.mean()}"  # (one code may differ on a tiny sample; the rounding check below is the bar)
         assert np.all(np.abs(te_gpu.astype(int) - act.te.astype(int)) <= 1)
         # every GPU element is a correct saturating E4M3 rounding, under the GPU's block scale, of a
         # value within the accumulation bound of the oracle's T
@@ -70,7 +70,7 @@ def _compare(oracle, layer, X, W, L, R, rows=None, gamma=None):
         assert np.all(np.abs(deq - act.T) <= sc * half + tb), "tq8 is not a block rounding of T"
         same = ~ediff.repeat(32, axis=1)
         diff = (f8[tq_gpu] != f8[act.tq8]) & same
-        assert diff.mean() <= 1e-2, f"tq8 mismatch rate {diff.mean()}"
+        assert diff.sum() <= max(1, 1e-2 * diff.size), f"tq8 mismatch rate {diff.mean()}"  # (one code may differ on a tiny sample; the rounding check below is the bar)
     # ---- forward: the oracle is fed the GPU's re-quantised intermediate
     act_g = dataclasses.replace(act, tq8=np.ascontiguousarray(tq_gpu), te=np.ascontiguousarray(te_gpu))
     out = oracle.fwd_mxb(pk, act_g)
@@ -111,6 +111,9 @@ SMALL = [
     (33, 640, 128, 128, "bf16"),
     (1, 128, 64, 32, "f32"),
     (50, 256, 64, 96, "bf16"),     # a 6-bit budget of 512 bits per channel gives rank 85: padded to three blocks of 32
+    (31, 64, 768, 96, "bf16"),     # rank > K: the factor views are larger than N x K
+    (255, 192, 256, 0, "f32"),     # rank 0: no branch section of either blob is read (they may hold anything)
+    (128, 384, 1344, 0, "f32"),
 ]
 
 

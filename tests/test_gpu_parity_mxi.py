@@ -56,7 +56,7 @@ def _compare(oracle, layer, X, W, L, R, rows=None, exact=False, gamma=None):
         tb = 2.0 ** -13 * (_vals(oracle, act.xb, act.xbe, 8) @ _vals(oracle, pk.rq, pk.re, bw).T) + 1e-300
         assert np.all(np.abs(T_gpu - act.T) <= tb), f"T max excess {np.max(np.abs(T_gpu - act.T) / tb)}"
         ediff = te_gpu != act.te
-        assert ediff.mean() <= 1e-2, f"te mismatch rate {ediff.mean()}"
+        assert ediff.sum() <= max(1, 1e-2 * ediff.size), f"te mismatch rate {ediff.mean()}"  # (one code may differ on a tiny sample; the rounding check below is the bar)
         assert np.all(np.abs(te_gpu.astype(int) - act.te.astype(int)) <= 1)
         # every GPU element is a correct saturating rounding, on the GPU's block grid, of a value within
         # the accumulation bound of the oracle's T
@@ -68,7 +68,7 @@ def _compare(oracle, layer, X, W, L, R, rows=None, exact=False, gamma=None):
         assert np.all(np.abs(deq - act.T) <= step * half + tb), "tq is not a block rounding of T"
         same = ~ediff.repeat(32, axis=1)
         diff = (tq_gpu != act.tq) & same
-        assert diff.mean() <= 1e-2, f"tq mismatch rate {diff.mean()}"
+        assert diff.sum() <= max(1, 1e-2 * diff.size), f"tq mismatch rate {diff.mean()}"  # (one code may differ on a tiny sample; the rounding check below is the bar)
         if exact:
             assert np.array_equal(T_gpu, act.T) and np.array_equal(tq_gpu, act.tq) and np.array_equal(te_gpu, act.te)
     # ---- forward: the oracle is fed the GPU's re-quantised intermediate
@@ -110,6 +110,9 @@ SMALL = [
     (40, 5120, 64, 32, 8, "bf16"),      # K beyond what the row-resident activation kernels of the other families take
     (18, 2368, 64, 64, 4, "f32"),
     (50, 256, 64, 96, 8, "bf16"),
+    (97, 64, 384, 128, 8, "bf16"),      # rank > K: the factor views are larger than N x K
+    (15, 64, 320, 96, 4, "f32"),
+    (255, 192, 256, 0, 8, "f32"),       # rank 0: no branch section of either blob is read
 ]
 
 
