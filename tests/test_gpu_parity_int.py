@@ -259,11 +259,11 @@ def test_seeded_shape_sweep_bit_exact(oracle):
     ranks, group sizes, branch widths, input types and both main scale granularities."""
     rng = np.random.default_rng(2024)
     edge_M = [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 257]
-    for it in range(14):
+    for it in range(40):
         M = int(rng.choice(edge_M))
-        K = 64 * int(rng.integers(1, 9))
-        N = 64 * int(rng.integers(1, 10))
-        r = int(rng.choice([0, 16, 32, 64, 128]))
+        K = 64 * int(rng.integers(1, 9))      # K = 64 with ranks 96 and 128 included: factor views larger than N x K
+        N = 64 * int(rng.integers(1, 10)) if it % 8 else 64 * int(rng.integers(10, 40))
+        r = int(rng.choice([0, 16, 32, 64, 96, 128]))
         ag = int(rng.choice([0, 64]))
         g = 64 if ag or K % 128 else int(rng.choice([64, 128]))
         bw, ba = [(8, 8), (6, 6), (4, 8)][int(rng.integers(0, 3))]

@@ -16,10 +16,10 @@ EDGE_M = [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 257]
 @pytest.mark.parametrize("family", ["mx", "mxb8", "mxb6", "mxi8", "mxi4"])
 def test_seeded_shape_sweep(oracle, family):
     rng = np.random.default_rng(sum(map(ord, family)))
-    for it in range(8):
+    for it in range(20):
         M = int(rng.choice(EDGE_M))
         K = 64 * int(rng.integers(1, 12))        # odd multiples of 64 included (padded to whole 128-stages inside the blobs)
-        N = 64 * int(rng.integers(1, 10))
+        N = 64 * int(rng.integers(1, 10)) if it % 8 else 64 * int(rng.integers(10, 40))
         xd = "bf16" if rng.integers(0, 2) else "f32"
         if family == "mx":
             r = int(rng.choice([0, 16, 32, 64, 128]))
