@@ -1,0 +1,532 @@
+// Rotation search for the low-rank factors (Section 3.3, Eq. 6-7): one step on an orthogonal r x r matrix Omega that
+// lowers the error of quantising L Omega and Omega^T R with Q2, the product L R unchanged.
+//     loss(Omega) = mean ( Q2(Z1) - Z1 )^2 + mean ( Q2(Z2) - Z2 )^2,   Z1 = L Omega (N x r),  Z2 = Omega^T R (r x K)
+// Q2: symmetric integers of the branch weight width, one scale per row of Z1 and per row of Z2 (the granularity
+// lq_pack_weights uses for Q2(L) and Q2(R)).  Z1 and Z2 are fp32 chains z = fma(a_i, b_i, z) over the rank index
+// ascending (the codes depend on their rounding); the rounding has zero derivative (App. B.2), so
+//     G = -2/(N r) L^T E1 - 2/(r K) R E2^T
+// and the update is the Cayley SGD with momentum of the work the paper cites for it (Li et al. 2020, Algorithm 1).
+// Five launches per step, no atomics, every sum in a fixed order:
+//   rot_zl_kernel     one thread per row of L: Z1 row twice (row maximum, then codes), E1, partial sums of E1^2
+//   rot_zr_kernel     one thread per column of R: the column of Z2 (stored in E2's place), per-wavefront row maxima
+//   rot_qr_kernel     E2 = deq(Q2(Z2)) - Z2 in place, partial sums of E2^2
+//   rot_grad_kernel   partials of L^T E1 and R E2^T over strided 16-deep slices of N and K
+//   rot_cayley_kernel one workgroup: G, loss, momentum, the skew-symmetric W, step length, the fixed-point passes
+#include "lq_internal.h"
+
+namespace lq {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int ROT_TPB = 256;
+constexpr int ROT_GRAD_WGS = 64;   // slices the two contractions of the gradient are dealt to
+constexpr int ROT_TMP = 4;         // r x r scratch matrices of the update kernel
+
+RotLayout rot_layout(const Dims& d)
+{
+    RotLayout rl;
+    const size_t rr = (size_t)d.r * d.r * 4;
+    rl.nlb = (int)((d.N + ROT_TPB - 1) / ROT_TPB);
+    rl.nkb = (int)((d.K + ROT_TPB - 1) / ROT_TPB);
+    size_t o = 0;
+    rl.off_X = o;   o = align256(o + rr);
+    rl.off_M = o;   o = align256(o + rr);
+    rl.off_G = o;   o = align256(o + rr);
+    rl.off_E1 = o;  o = align256(o + (size_t)d.N * d.r * 4);
+    rl.off_E2 = o;  o = align256(o + (size_t)d.r * d.K * 4);
+    rl.off_ax = o;  o = align256(o + (size_t)rl.nkb * 4 * d.r * 4);
+    rl.n_lp = rl.nlb + d.r * rl.nkb;
+    rl.off_lp = o;  o = align256(o + (size_t)rl.n_lp * 4);
+    rl.off_gp = o;  o = align256(o + (size_t)ROT_GRAD_WGS * rr);
+    rl.off_tmp = o; o = align256(o + (size_t)ROT_TMP * rr);
+    rl.total = o;
+    return rl;
+}
+
+// Maximum over the 64 lanes (in every lane) on the data-parallel-primitive path.
+template <int CTRL>
+__device__ __forceinline__ float rot_dpp_max(float v)
+{
+    const int o = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false);
+    return fmaxf(v, __int_as_float(o));
+}
+__device__ __forceinline__ float rot_wave_max(float v)
+{
+    v = rot_dpp_max<0xB1>(v);   // quad_perm [1,0,3,2]
+    v = rot_dpp_max<0x4E>(v);   // quad_perm [2,3,0,1]
+    v = rot_dpp_max<0x141>(v);  // row_half_mirror
+    v = rot_dpp_max<0x140>(v);  // row_mirror
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
+// Sum over the workgroup (256 threads), valid in thread 0.
+__device__ __forceinline__ float rot_block_sum(float v, float* red)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
+    const int tid = threadIdx.x;
+    if ((tid & 63) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+
+// Per-row integer quantiser of lq_pack_weights: scale amax / qmax, codes against qmax / amax, ties to even, clamped.
+__device__ __forceinline__ void rot_scale(float amax, float qmax, float& s, float& inv)
+{
+    if (amax == 0.f) {
+        s = 1.f;
+        inv = 1.f;
+    } else {
+        s = amax / qmax;
+        inv = qmax / amax;
+    }
+}
+__device__ __forceinline__ float rot_err(float z, float s, float inv, float qmax)
+{
+    float c = rintf(z * inv);
+    c = fminf(fmaxf(c, -qmax), qmax);
+    return c * s - z;
+}
+
+// Four neighbouring entries of a row of Z: z[c] = sum_i reg[i] * Om[i][j + c], each an fma chain over ascending i.
+template <int R>
+__device__ __forceinline__ v4f rot_chain4(const float (&reg)[R], const float* om, int j)
+{
+    v4f z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        const v4f w = *(const v4f*)(om + i * R + j);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) z[c] = __builtin_fmaf(reg[i], w[c], z[c]);
+        // keeps the compiler from hoisting all R reads of Omega to the top (4 registers each)
+        if ((i & 7) == 7) asm volatile("" ::: "memory");
+    }
+    return z;
+}
+
+// One thread per row n of L.  OUTZ: write Z1 = L Omega itself (the rotated factor) instead of its quantisation error.
+template <int R, bool OUTZ>
+__global__ __launch_bounds__(ROT_TPB) void rot_zl_kernel(const float* __restrict__ L, const float* __restrict__ X, int N,
+                                                        float qmax, float* __restrict__ out, float* __restrict__ lp)
+{
+    extern __shared__ __attribute__((aligned(16))) float om[];
+    __shared__ float red[4];
+    for (int i = threadIdx.x; i < R * R; i += ROT_TPB) om[i] = X[i];
+    __syncthreads();
+    const int n = blockIdx.x * ROT_TPB + threadIdx.x;
+    const bool ok = n < N;
+    float reg[R];
+#pragma unroll
+    for (int i = 0; i < R; i += 4) {
+        const v4f v = ok ? *(const v4f*)(L + (size_t)n * R + i) : v4f{0.f, 0.f, 0.f, 0.f};
+        reg[i] = v[0]; reg[i + 1] = v[1]; reg[i + 2] = v[2]; reg[i + 3] = v[3];
+    }
+    float sq = 0.f;
+    if constexpr (OUTZ) {
+#pragma unroll 1
+        for (int j = 0; j < R; j += 4) {
+            const v4f z = rot_chain4<R>(reg, om, j);
+            if (ok) *(v4f*)(out + (size_t)n * R + j) = z;
+        }
+    } else {
+        float amax = 0.f;
+#pragma unroll 1
+        for (int j = 0; j < R; j += 4) {
+            const v4f z = rot_chain4<R>(reg, om, j);
+            amax = fmaxf(fmaxf(amax, fmaxf(fabsf(z[0]), fabsf(z[1]))), fmaxf(fabsf(z[2]), fabsf(z[3])));
+        }
+        float s, inv;
+        rot_scale(amax, qmax, s, inv);
+#pragma unroll 1
+        for (int j = 0; j < R; j += 4) {
+            const v4f z = rot_chain4<R>(reg, om, j);  // the same chains: the same bits as in the first pass
+            v4f e;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                e[c] = rot_err(z[c], s, inv, qmax);
+                sq = __builtin_fmaf(e[c], e[c], sq);
+            }
+            if (ok) *(v4f*)(out + (size_t)n * R + j) = e;
+        }
+        const float tot = rot_block_sum(ok ? sq : 0.f, red);
+        if (threadIdx.x == 0) lp[blockIdx.x] = tot;
+    }
+}
+
+// One thread per column k of R: the column of Z2 = Omega^T R, written to out[j][k]; OUTZ = false also leaves the
+// maximum magnitude of every row j over the wavefront's 64 columns in ax[4 * block + wavefront][j].
+template <int R, bool OUTZ>
+__global__ __launch_bounds__(ROT_TPB) void rot_zr_kernel(const float* __restrict__ Rm, const float* __restrict__ X, int K,
+                                                        float* __restrict__ out, float* __restrict__ ax)
+{
+    extern __shared__ __attribute__((aligned(16))) float om[];
+    for (int i = threadIdx.x; i < R * R; i += ROT_TPB) om[i] = X[i];
+    __syncthreads();
+    const int k = blockIdx.x * ROT_TPB + threadIdx.x;
+    const bool ok = k < K;
+    float reg[R];
+    // buffer loads: the row offset i * K travels in a scalar register, so the R loads share one vector offset instead
+    // of holding a 64-bit vector address each; a column past K reads finite in-range data of the next row (zeros past
+    // the end of the descriptor), and nothing computed from it is stored or enters a maximum
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)Rm, 0, R * K * 4, 0x00020000);
+#pragma unroll
+    for (int i = 0; i < R; ++i) reg[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, k * 4, i * K * 4, 0));
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll 1
+    for (int j = 0; j < R; j += 4) {
+        const v4f z = rot_chain4<R>(reg, om, j);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (ok) out[(size_t)(j + c) * K + k] = z[c];
+            if constexpr (!OUTZ) {
+                const float m = rot_wave_max(ok ? fabsf(z[c]) : 0.f);
+                if (lane == 0) ax[(size_t)(blockIdx.x * 4 + wave) * R + j + c] = m;
+            }
+        }
+    }
+}
+
+// E2 = deq(Q2(Z2)) - Z2 in place; grid (column blocks, r).
+__global__ __launch_bounds__(ROT_TPB) void rot_qr_kernel(float* __restrict__ E2, const float* __restrict__ ax, int K, int r,
+                                                        int nparts, float qmax, float* __restrict__ lp)
+{
+    __shared__ float red[4];
+    const int j = blockIdx.y;
+    float amax = 0.f;
+    for (int p = 0; p < nparts; ++p) amax = fmaxf(amax, ax[(size_t)p * r + j]);
+    float s, inv;
+    rot_scale(amax, qmax, s, inv);
+    const int k = blockIdx.x * ROT_TPB + threadIdx.x;
+    float sq = 0.f;
+    if (k < K) {
+        const float e = rot_err(E2[(size_t)j * K + k], s, inv, qmax);
+        E2[(size_t)j * K + k] = e;
+        sq = e * e;
+    }
+    const float tot = rot_block_sum(sq, red);
+    if (threadIdx.x == 0) lp[(size_t)j * gridDim.x + blockIdx.x] = tot;
+}
+
+// Partials of  c1 L^T E1 + c2 R E2^T  (r x r): workgroup w takes the 16-deep slices w, w + gridDim.x, ... of the
+// contraction over N, then of the one over K.  Thread (ty, tx) of 16 x 16 owns entries (ty + 16 a, tx + 16 b).
+template <int T>
+__global__ __launch_bounds__(ROT_TPB) void rot_grad_kernel(const float* __restrict__ L, const float* __restrict__ E1,
+                                                          const float* __restrict__ Rm, const float* __restrict__ E2, int N,
+                                                          int K, float c1, float c2, float* __restrict__ gp)
+{
+    constexpr int R = 16 * T;
+    __shared__ float As[16][R];
+    __shared__ float Bs[16][R];
+    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+    float acc[T][T];
+#pragma unroll
+    for (int a = 0; a < T; ++a)
+#pragma unroll
+        for (int b = 0; b < T; ++b) acc[a][b] = 0.f;
+    auto contract = [&]() {
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            float av[T], bv[T];
+#pragma unroll
+            for (int a = 0; a < T; ++a) av[a] = As[kk][ty + 16 * a];
+#pragma unroll
+            for (int b = 0; b < T; ++b) bv[b] = Bs[kk][tx + 16 * b];
+#pragma unroll
+            for (int a = 0; a < T; ++a)
+#pragma unroll
+                for (int b = 0; b < T; ++b) acc[a][b] = __builtin_fmaf(av[a], bv[b], acc[a][b]);
+        }
+    };
+    for (int n0 = blockIdx.x * 16; n0 < N; n0 += gridDim.x * 16) {  // rows n0 .. n0+15 of L and E1 (zero past N)
+        __syncthreads();
+        for (int e = tid; e < 16 * R; e += ROT_TPB) {
+            const int rr = e / R, i = e - rr * R;
+            const bool ok = n0 + rr < N;
+            As[rr][i] = ok ? L[(size_t)(n0 + rr) * R + i] : 0.f;
+            Bs[rr][i] = ok ? c1 * E1[(size_t)(n0 + rr) * R + i] : 0.f;
+        }
+        __syncthreads();
+        contract();
+    }
+    for (int k0 = blockIdx.x * 16; k0 < K; k0 += gridDim.x * 16) {  // columns k0 .. k0+15 of R and E2 (K is a multiple of 64)
+        __syncthreads();
+        for (int e = tid; e < 16 * R; e += ROT_TPB) {
+            const int i = e >> 4, kk = e & 15;
+            As[kk][i] = Rm[(size_t)i * K + k0 + kk];
+            Bs[kk][i] = c2 * E2[(size_t)i * K + k0 + kk];
+        }
+        __syncthreads();
+        contract();
+    }
+    float* o = gp + (size_t)blockIdx.x * R * R;
+#pragma unroll
+    for (int a = 0; a < T; ++a)
+#pragma unroll
+        for (int b = 0; b < T; ++b) o[(ty + 16 * a) * R + tx + 16 * b] = acc[a][b];
+}
+
+struct RotStepParams {
+    float* X;          // Omega
+    float* M;          // momentum
+    float* G;          // gradient of this step
+    const float* gp;   // its partials
+    const float* lp;   // partial sums of E1^2 (nlb) then of E2^2
+    float* tmp;        // ROT_TMP scratch matrices
+    float* loss;       // may be null
+    int r, nlb, n_lp, nparts;
+    float inv1, inv2;  // 1 / (N r), 1 / (r K)
+    float lr, beta, eps, q, grad_scale;
+    int s;
+};
+
+// The update, one workgroup of 1024 threads.  Five r x r work matrices; as many as fit sit in a 60 KB LDS pool (all five
+// and Omega up to rank 32, three at rank 64, one at rank 96), the rest in the state's scratch area in global memory:
+// the code addresses both through generic pointers.  Every phase reads what earlier phases wrote; __syncthreads orders
+// those accesses within the workgroup.
+// ALL_LDS (rank <= 32): everything sits in the pool and the compiler sees plain LDS addresses.
+constexpr int ROT_POOL = 15360;  // floats
+template <bool ALL_LDS>
+__global__ __launch_bounds__(1024) void rot_cayley_kernel(RotStepParams p)
+{
+    __shared__ __attribute__((aligned(16))) float pool[ROT_POOL];
+    __shared__ double red[16];
+    __shared__ float bc;
+    const int r = p.r, rr = r * r, tid = threadIdx.x;
+    __builtin_assume(r % 16 == 0 && r >= 16);  // the dot products below are unrolled 16 deep: their loads go out together
+    // priority: W (read by every product of the second half), then the operands of the passes, then Omega
+    float *W, *T1, *T2, *T4, *Xl;
+    if constexpr (ALL_LDS) {
+        W = pool;
+        T1 = pool + rr;
+        T2 = pool + 2 * rr;
+        T4 = pool + 3 * rr;
+        Xl = pool + 4 * rr;
+    } else {
+        const int fit = ROT_POOL / rr;
+        W = 0 < fit ? pool : p.tmp;
+        T1 = 1 < fit ? pool + rr : p.tmp + rr;
+        T2 = 2 < fit ? pool + 2 * rr : p.tmp + 2 * rr;
+        T4 = 3 < fit ? pool + 3 * rr : p.tmp + 3 * rr;
+        Xl = 4 < fit ? pool + 4 * rr : p.X;
+    }
+    // W: first beta M - G, then Wh, then W = Wh - Wh^T in place;  T1: A = (beta M - G) X^T, later Y;
+    // T2: X^T (for A), B = X^T A, later X + Y;  T4: the next Y
+    auto block_sum = [&](double v) -> double {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
+        __syncthreads();
+        if ((tid & 63) == 0) red[tid >> 6] = v;
+        __syncthreads();
+        double t = 0.0;
+        for (int w = 0; w < 16; ++w) t += red[w];
+        return t;
+    };
+    // loss (before the update) and gradient from their partials
+    {
+        double a = 0.0, b = 0.0;
+        for (int i = tid; i < p.nlb; i += 1024) a += (double)p.lp[i];
+        for (int i = p.nlb + tid; i < p.n_lp; i += 1024) b += (double)p.lp[i];
+        const double ta = block_sum(a), tb = block_sum(b);
+        if (tid == 0 && p.loss) *p.loss = (float)(ta * (double)p.inv1 + tb * (double)p.inv2);
+    }
+    for (int e = tid; e < rr; e += 1024) {
+        double g = 0.0;
+#pragma unroll 16
+        for (int w = 0; w < ROT_GRAD_WGS; ++w) g += (double)p.gp[(size_t)w * rr + e];  // 16 loads in flight at a time
+        const float gf = (float)((double)p.grad_scale * g);
+        p.G[e] = gf;
+        W[e] = p.beta * p.M[e] - gf;
+        const float x = p.X[e];
+        if (ALL_LDS || Xl != p.X) Xl[e] = x;
+        const int i = e / r, j = e - i * r;
+        T2[j * r + i] = x;  // X^T: the product below then reads rows, not columns (in LDS a column read is a 32-way bank conflict)
+    }
+    __syncthreads();
+    for (int e = tid; e < rr; e += 1024) {  // A = (beta M - G) X^T
+        const int i = e / r, j = e - i * r;
+        float a = 0.f;
+#pragma unroll 16
+        for (int k = 0; k < r; ++k) a = __builtin_fmaf(W[i * r + k], T2[k * r + j], a);
+        T1[e] = a;
+    }
+    __syncthreads();
+    for (int e = tid; e < rr; e += 1024) {  // B = X^T A
+        const int i = e / r, j = e - i * r;
+        float a = 0.f;
+#pragma unroll 16
+        for (int k = 0; k < r; ++k) a = __builtin_fmaf(Xl[k * r + i], T1[k * r + j], a);
+        T2[e] = a;
+    }
+    __syncthreads();
+    for (int e = tid; e < rr; e += 1024) {  // Wh = A - 1/2 X B
+        const int i = e / r, j = e - i * r;
+        float a = 0.f;
+#pragma unroll 16
+        for (int k = 0; k < r; ++k) a = __builtin_fmaf(Xl[i * r + k], T2[k * r + j], a);
+        W[e] = T1[e] - 0.5f * a;
+    }
+    __syncthreads();
+    double n2 = 0.0;
+    for (int e = tid; e < rr; e += 1024) {  // W = Wh - Wh^T, each pair (i, j), (j, i) by the thread of its upper entry
+        const int i = e / r, j = e - i * r;
+        if (i > j) continue;
+        const float w = W[e] - W[j * r + i];
+        W[e] = w;
+        W[j * r + i] = -w;
+        if (i < j) n2 += 2.0 * (double)w * (double)w;
+    }
+    const double nrm2 = block_sum(n2);      // (its barriers also order W's stores before the reads below)
+    if (tid == 0) {
+        const float lim = 2.f * p.q / ((float)sqrt(nrm2) + p.eps);
+        bc = p.lr < lim ? p.lr : lim;
+    }
+    __syncthreads();
+    const float alpha = bc;
+    for (int e = tid; e < rr; e += 1024) {  // M = W X;  Y = X + alpha M
+        const int i = e / r, j = e - i * r;
+        float a = 0.f;
+#pragma unroll 16
+        for (int k = 0; k < r; ++k) a = __builtin_fmaf(W[i * r + k], Xl[k * r + j], a);
+        p.M[e] = a;
+        T1[e] = __builtin_fmaf(alpha, a, Xl[e]);
+    }
+    float* Y = T1;
+    float* Yn = T4;
+    for (int it = 0; it < p.s; ++it) {      // Y <- X + alpha/2 W (X + Y)
+        __syncthreads();
+        for (int e = tid; e < rr; e += 1024) T2[e] = Xl[e] + Y[e];
+        __syncthreads();
+        for (int e = tid; e < rr; e += 1024) {
+            const int i = e / r, j = e - i * r;
+            float a = 0.f;
+    #pragma unroll 16
+        for (int k = 0; k < r; ++k) a = __builtin_fmaf(W[i * r + k], T2[k * r + j], a);
+            Yn[e] = __builtin_fmaf(0.5f * alpha, a, Xl[e]);
+        }
+        float* t = Y;
+        Y = Yn;
+        Yn = t;
+    }
+    __syncthreads();
+    for (int e = tid; e < rr; e += 1024) p.X[e] = Y[e];
+}
+
+__global__ __launch_bounds__(ROT_TPB) void rot_init_kernel(float* X, float* M, const float* X0, const float* M0, int r)
+{
+    const int e = blockIdx.x * ROT_TPB + threadIdx.x;
+    if (e >= r * r) return;
+    X[e] = X0 ? X0[e] : (e / r == e % r ? 1.f : 0.f);
+    M[e] = M0 ? M0[e] : 0.f;
+}
+
+hipError_t launch_rot_init(const Dims& d, const float* Omega0, const float* Mom0, uint8_t* state, hipStream_t s)
+{
+    const RotLayout rl = rot_layout(d);
+    hipLaunchKernelGGL(rot_init_kernel, dim3((d.r * d.r + ROT_TPB - 1) / ROT_TPB), dim3(ROT_TPB), 0, s,
+                       (float*)(state + rl.off_X), (float*)(state + rl.off_M), Omega0, Mom0, d.r);
+    return hipGetLastError();
+}
+
+template <int R, bool OUTZ>
+static void rot_launch_z(const Dims& d, const RotLayout& rl, const float* L, const float* Rm, const float* X, float* o1,
+                         float* o2, float* ax, float* lp, hipStream_t s)
+{
+    const size_t lds = (size_t)R * R * 4;
+    if constexpr (R == 128) {  // Omega alone fills the 64 KB a launch may use without asking for more
+        (void)hipFuncSetAttribute((const void*)rot_zl_kernel<R, OUTZ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        (void)hipFuncSetAttribute((const void*)rot_zr_kernel<R, OUTZ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    }
+    hipLaunchKernelGGL((rot_zl_kernel<R, OUTZ>), dim3(rl.nlb), dim3(ROT_TPB), lds, s, L, X, (int)d.N, (float)d.qmax_bw, o1, lp);
+    hipLaunchKernelGGL((rot_zr_kernel<R, OUTZ>), dim3(rl.nkb), dim3(ROT_TPB), lds, s, Rm, X, (int)d.K, o2, ax);
+}
+
+template <bool OUTZ>
+static void rot_dispatch_z(const Dims& d, const RotLayout& rl, const float* L, const float* Rm, const float* X, float* o1,
+                           float* o2, float* ax, float* lp, hipStream_t s)
+{
+    switch (d.r) {
+        case 16: rot_launch_z<16, OUTZ>(d, rl, L, Rm, X, o1, o2, ax, lp, s); break;
+        case 32: rot_launch_z<32, OUTZ>(d, rl, L, Rm, X, o1, o2, ax, lp, s); break;
+        case 64: rot_launch_z<64, OUTZ>(d, rl, L, Rm, X, o1, o2, ax, lp, s); break;
+        case 96: rot_launch_z<96, OUTZ>(d, rl, L, Rm, X, o1, o2, ax, lp, s); break;
+        default: rot_launch_z<128, OUTZ>(d, rl, L, Rm, X, o1, o2, ax, lp, s); break;
+    }
+}
+
+hipError_t launch_rot_step(const Dims& d, const float* L, const float* Rm, uint8_t* state, const lq_cayley* cs, float* loss,
+                           hipStream_t s)
+{
+    const RotLayout rl = rot_layout(d);
+    float* X = (float*)(state + rl.off_X);
+    float* E1 = (float*)(state + rl.off_E1);
+    float* E2 = (float*)(state + rl.off_E2);
+    float* ax = (float*)(state + rl.off_ax);
+    float* lp = (float*)(state + rl.off_lp);
+    float* gp = (float*)(state + rl.off_gp);
+    const int N = (int)d.N, K = (int)d.K, r = d.r;
+    rot_dispatch_z<false>(d, rl, L, Rm, X, E1, E2, ax, lp, s);
+    hipLaunchKernelGGL(rot_qr_kernel, dim3(rl.nkb, r), dim3(ROT_TPB), 0, s, E2, ax, K, r, rl.nkb * 4, (float)d.qmax_bw,
+                       lp + rl.nlb);
+    const float c1 = (float)(-2.0 / ((double)N * r)), c2 = (float)(-2.0 / ((double)r * K));
+    switch (r >> 4) {
+        case 1: hipLaunchKernelGGL(rot_grad_kernel<1>, dim3(ROT_GRAD_WGS), dim3(ROT_TPB), 0, s, L, E1, Rm, E2, N, K, c1, c2, gp); break;
+        case 2: hipLaunchKernelGGL(rot_grad_kernel<2>, dim3(ROT_GRAD_WGS), dim3(ROT_TPB), 0, s, L, E1, Rm, E2, N, K, c1, c2, gp); break;
+        case 4: hipLaunchKernelGGL(rot_grad_kernel<4>, dim3(ROT_GRAD_WGS), dim3(ROT_TPB), 0, s, L, E1, Rm, E2, N, K, c1, c2, gp); break;
+        case 6: hipLaunchKernelGGL(rot_grad_kernel<6>, dim3(ROT_GRAD_WGS), dim3(ROT_TPB), 0, s, L, E1, Rm, E2, N, K, c1, c2, gp); break;
+        default: hipLaunchKernelGGL(rot_grad_kernel<8>, dim3(ROT_GRAD_WGS), dim3(ROT_TPB), 0, s, L, E1, Rm, E2, N, K, c1, c2, gp); break;
+    }
+    RotStepParams p;
+    p.X = X;
+    p.M = (float*)(state + rl.off_M);
+    p.G = (float*)(state + rl.off_G);
+    p.gp = gp;
+    p.lp = lp;
+    p.tmp = (float*)(state + rl.off_tmp);
+    p.loss = loss;
+    p.r = r;
+    p.nlb = rl.nlb;
+    p.n_lp = rl.n_lp;
+    p.nparts = ROT_GRAD_WGS;
+    p.inv1 = (float)(1.0 / ((double)N * r));
+    p.inv2 = (float)(1.0 / ((double)r * K));
+    p.lr = cs->lr;
+    p.beta = cs->beta;
+    p.eps = cs->eps;
+    p.q = cs->q;
+    p.grad_scale = cs->grad_scale;
+    p.s = cs->s;
+    if (5 * r * r <= ROT_POOL)
+        hipLaunchKernelGGL(rot_cayley_kernel<true>, dim3(1), dim3(1024), 0, s, p);
+    else
+        hipLaunchKernelGGL(rot_cayley_kernel<false>, dim3(1), dim3(1024), 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_rot_apply(const Dims& d, const float* L, const float* Rm, const uint8_t* state, float* Lr, float* Rr,
+                            hipStream_t s)
+{
+    const RotLayout rl = rot_layout(d);
+    rot_dispatch_z<true>(d, rl, L, Rm, (const float*)(state + rl.off_X), Lr, Rr, nullptr, nullptr, s);
+    return hipGetLastError();
+}
+
+hipError_t launch_rot_unpack(const Dims& d, const uint8_t* state, const lq_rot_view* out, hipStream_t s)
+{
+    const RotLayout rl = rot_layout(d);
+    const size_t rr = (size_t)d.r * d.r * 4;
+    struct { float* dst; size_t off, bytes; } parts[5] = {{out->Omega, rl.off_X, rr}, {out->Mom, rl.off_M, rr}, {out->G, rl.off_G, rr},
+                                                         {out->E1, rl.off_E1, (size_t)d.N * d.r * 4},
+                                                         {out->E2, rl.off_E2, (size_t)d.r * d.K * 4}};
+    for (auto& pt : parts) {
+        if (!pt.dst) continue;
+        const hipError_t e = hipMemcpyAsync(pt.dst, state + pt.off, pt.bytes, hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace lq

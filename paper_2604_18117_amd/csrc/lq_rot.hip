@@ -14,6 +14,7 @@
 //   rot_grad_kernel   partials of L^T E1 and R E2^T over strided 16-deep slices of N and K
 //   rot_cayley_kernel one workgroup: G, loss, momentum, the skew-symmetric W, step length, the fixed-point passes
 #include "lq_internal.h"
+#include <type_traits>
 
 namespace lq {
 
@@ -21,7 +22,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int ROT_TPB = 256;
 constexpr int ROT_GRAD_WGS = 64;   // slices the two contractions of the gradient are dealt to
-constexpr int ROT_TMP = 4;         // r x r scratch matrices of the update kernel
+constexpr int ROT_TMP = 3;         // r x r scratch matrices of the update kernel
 
 RotLayout rot_layout(const Dims& d)
 {
@@ -115,14 +116,16 @@ __device__ __forceinline__ float rot_fp8_value(float u)  // nearest E4M3 number 
     const int code = __builtin_amdgcn_cvt_pk_fp8_f32(u, u, 0, false) & 0xFF;
     return __builtin_amdgcn_cvt_f32_fp8(code, 0);
 }
-__device__ __forceinline__ float rot_err(float z, float s, float inv, const RotQ& q)
+template <int QK>  // 0: integers of qmax = top; 1: FP8 E4M3
+__device__ __forceinline__ float rot_err(float z, float s, float inv, float top)
 {
-    if (q.kind == 0) {
+    if constexpr (QK == 0) {
         float c = rintf(z * inv);
-        c = fminf(fmaxf(c, -q.top), q.top);
+        c = fminf(fmaxf(c, -top), top);
         return c * s - z;
+    } else {
+        return rot_fp8_value(z * inv) * s - z;
     }
-    return rot_fp8_value(z * inv) * s - z;
 }
 
 // Block kinds: the shared exponent floor(log2 amax) - (largest element exponent: 8 for E4M3, 2 for E2M3, 0 for MXINT),
@@ -159,17 +162,25 @@ __device__ __forceinline__ v4f rot_chain4(const float (&reg)[R], const float* om
         const v4f w = *(const v4f*)(om + i * R + j);
 #pragma unroll
         for (int c = 0; c < 4; ++c) z[c] = __builtin_fmaf(reg[i], w[c], z[c]);
-        // keeps the compiler from hoisting all R reads of Omega to the top (4 registers each)
-        if ((i & 7) == 7) asm volatile("" ::: "memory");
+        // Keeps the compiler from hoisting all R reads of Omega to the top (4 registers each): after every eight rows the
+        // column offset passes through an empty asm together with a chain value, so the next eight reads depend on it.
+        if ((i & 7) == 7) {
+            float z0 = z[0];
+            asm volatile("" : "+v"(j), "+v"(z0));
+            z[0] = z0;
+        }
     }
     return z;
 }
 
 // One thread per row n of L.  OUTZ: write Z1 = L Omega itself (the rotated factor) instead of its quantisation error.
-template <int R, bool OUTZ>
+// BLOCKQ: Q2 is one of the block kinds (a compile-time split: with the choice made at run time the row-scaled kernels, which
+// hold a whole row in registers, grew from 61 to 173 registers at rank 32 and spilled hundreds at rank 128).
+template <int R, bool OUTZ, int QK>
 __global__ __launch_bounds__(ROT_TPB) void rot_zl_kernel(const float* __restrict__ L, const float* __restrict__ X, int N,
-                                                        RotQ q, float* __restrict__ out, float* __restrict__ lp)
+                                                        int rrt, RotQ q, float* __restrict__ out, float* __restrict__ lp)
 {
+    constexpr bool BLOCKQ = QK == 2;
     extern __shared__ __attribute__((aligned(16))) float om[];
     __shared__ float red[4];
     for (int i = threadIdx.x; i < R * R; i += ROT_TPB) om[i] = X[i];
@@ -185,37 +196,53 @@ __global__ __launch_bounds__(ROT_TPB) void rot_zl_kernel(const float* __restrict
     float sq = 0.f;
     if constexpr (OUTZ) {
 #pragma unroll 1
-        for (int j = 0; j < R; j += 4) {
+        for (int j = 0; j < rrt; j += 4) {  // rrt = R, passed as an argument: a bound the compiler cannot unroll over
             const v4f z = rot_chain4<R>(reg, om, j);
             if (ok) *(v4f*)(out + (size_t)n * R + j) = z;
         }
     } else {
-        // one scale per row (row kinds) or per 32 columns (block kinds): span by span, the chains run twice
-        const int span = (q.kind <= 1 || R < 32) ? R : 32;  // (block formats come with ranks that are multiples of 32)
-#pragma unroll 1
-        for (int j0 = 0; j0 < R; j0 += span) {
+        if constexpr (!BLOCKQ) {  // one scale per row: the chains run twice, over the whole row
             float amax = 0.f;
 #pragma unroll 1
-            for (int j = j0; j < j0 + span; j += 4) {
+            for (int j = 0; j < R; j += 4) {
                 const v4f z = rot_chain4<R>(reg, om, j);
                 amax = fmaxf(fmaxf(amax, fmaxf(fabsf(z[0]), fabsf(z[1]))), fmaxf(fabsf(z[2]), fabsf(z[3])));
             }
-            float s = 1.f, inv = 1.f;
-            int eb = 0;
-            if (q.kind <= 1)
-                rot_scale(amax, q.top, s, inv);
-            else
-                eb = rot_block_exp(amax, q);
+            float s, inv;
+            rot_scale(amax, q.top, s, inv);
 #pragma unroll 1
-            for (int j = j0; j < j0 + span; j += 4) {
+            for (int j = 0; j < R; j += 4) {
                 const v4f z = rot_chain4<R>(reg, om, j);  // the same chains: the same bits as in the first pass
                 v4f e;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    e[c] = q.kind <= 1 ? rot_err(z[c], s, inv, q) : rot_err_block(z[c], eb, q);
+                    e[c] = rot_err<QK>(z[c], s, inv, q.top);
                     sq = __builtin_fmaf(e[c], e[c], sq);
                 }
                 if (ok) *(v4f*)(out + (size_t)n * R + j) = e;
+            }
+        } else {  // one scale per 32 columns: block by block, the chains run twice (ranks here are multiples of 32)
+            const int blk = rrt < 32 ? rrt : 32;  // 32; from an argument, so that the loops below stay loops
+#pragma unroll 1
+            for (int j0 = 0; j0 < rrt; j0 += blk) {
+                float amax = 0.f;
+#pragma unroll 1
+                for (int j = j0; j < j0 + blk; j += 4) {
+                    const v4f z = rot_chain4<R>(reg, om, j);
+                    amax = fmaxf(fmaxf(amax, fmaxf(fabsf(z[0]), fabsf(z[1]))), fmaxf(fabsf(z[2]), fabsf(z[3])));
+                }
+                const int eb = rot_block_exp(amax, q);
+#pragma unroll 1
+                for (int j = j0; j < j0 + blk; j += 4) {
+                    const v4f z = rot_chain4<R>(reg, om, j);
+                    v4f e;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        e[c] = rot_err_block(z[c], eb, q);
+                        sq = __builtin_fmaf(e[c], e[c], sq);
+                    }
+                    if (ok) *(v4f*)(out + (size_t)n * R + j) = e;
+                }
             }
         }
         const float tot = rot_block_sum(ok ? sq : 0.f, red);
@@ -227,11 +254,12 @@ __global__ __launch_bounds__(ROT_TPB) void rot_zl_kernel(const float* __restrict
 // of Q2: Z2 is written and the maximum magnitude of every row j over the wavefront's 64 columns is left in
 // ax[4 * block + wavefront][j] (rot_qr_kernel finishes the job); block kinds: a block is 32 lanes of one row, so the error
 // is formed here, written to out, and its squares are summed into lp[block].
-template <int R, bool OUTZ>
+template <int R, bool OUTZ, int QK>
 __global__ __launch_bounds__(ROT_TPB) void rot_zr_kernel(const float* __restrict__ Rm, const float* __restrict__ X, int K,
-                                                        RotQ q, float* __restrict__ out, float* __restrict__ ax,
+                                                        int rrt, RotQ q, float* __restrict__ out, float* __restrict__ ax,
                                                         float* __restrict__ lp)
 {
+    constexpr bool BLOCKQ = QK == 2;
     extern __shared__ __attribute__((aligned(16))) float om[];
     __shared__ float red[4];
     float sq = 0.f;
@@ -248,13 +276,13 @@ __global__ __launch_bounds__(ROT_TPB) void rot_zr_kernel(const float* __restrict
     for (int i = 0; i < R; ++i) reg[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, k * 4, i * K * 4, 0));
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll 1
-    for (int j = 0; j < R; j += 4) {
+    for (int j = 0; j < rrt; j += 4) {
         const v4f z = rot_chain4<R>(reg, om, j);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             float o = z[c];
             if constexpr (!OUTZ) {
-                if (q.kind <= 1) {
+                if constexpr (!BLOCKQ) {
                     const float m = rot_wave_max(ok ? fabsf(z[c]) : 0.f);
                     if (lane == 0) ax[(size_t)(blockIdx.x * 4 + wave) * R + j + c] = m;
                 } else {
@@ -266,11 +294,9 @@ __global__ __launch_bounds__(ROT_TPB) void rot_zr_kernel(const float* __restrict
             if (ok) out[(size_t)(j + c) * K + k] = o;
         }
     }
-    if constexpr (!OUTZ) {
-        if (q.kind > 1) {  // (uniform over the grid)
-            const float tot = rot_block_sum(sq, red);
-            if (threadIdx.x == 0) lp[blockIdx.x] = tot;
-        }
+    if constexpr (!OUTZ && BLOCKQ) {
+        const float tot = rot_block_sum(sq, red);
+        if (threadIdx.x == 0) lp[blockIdx.x] = tot;
     }
 }
 
@@ -287,7 +313,8 @@ __global__ __launch_bounds__(ROT_TPB) void rot_qr_kernel(float* __restrict__ E2,
     const int k = blockIdx.x * ROT_TPB + threadIdx.x;
     float sq = 0.f;
     if (k < K) {
-        const float e = rot_err(E2[(size_t)j * K + k], s, inv, q);
+        const float z = E2[(size_t)j * K + k];
+        const float e = q.kind == 0 ? rot_err<0>(z, s, inv, q.top) : rot_err<1>(z, s, inv, q.top);
         E2[(size_t)j * K + k] = e;
         sq = e * e;
     }
@@ -367,38 +394,39 @@ struct RotStepParams {
     int s;
 };
 
-// The update, one workgroup of 1024 threads.  Five r x r work matrices; as many as fit sit in a 60 KB LDS pool (all five
-// and Omega up to rank 32, three at rank 64, one at rank 96), the rest in the state's scratch area in global memory:
+// The update, one workgroup of 1024 threads.  Three r x r work matrices and Omega; as many as fit sit in a 60 KB LDS pool
+// (all four up to rank 32, three at rank 64, one at rank 96), the rest in the state's scratch area in global memory:
 // the code addresses both through generic pointers.  Every phase reads what earlier phases wrote; __syncthreads orders
 // those accesses within the workgroup.
+// T = entries per thread and dimension in the r-deep products: thread (ty, tx) of 32 x 32 owns entries (ty + 32 a, tx + 32 b),
+// so one k step loads T + T operands for T * T multiply-adds (rank 16 and 32: T = 1, 64: 2, 96: 3, 128: 4).
 // ALL_LDS (rank <= 32): everything sits in the pool and the compiler sees plain LDS addresses.
 constexpr int ROT_POOL = 15360;  // floats
-template <bool ALL_LDS>
+template <int T, bool ALL_LDS>
 __global__ __launch_bounds__(1024) void rot_cayley_kernel(RotStepParams p)
 {
     __shared__ __attribute__((aligned(16))) float pool[ROT_POOL];
     __shared__ double red[16];
     __shared__ float bc;
     const int r = p.r, rr = r * r, tid = threadIdx.x;
-    __builtin_assume(r % 16 == 0 && r >= 16);  // the dot products below are unrolled 16 deep: their loads go out together
+    const int ty = tid >> 5, tx = tid & 31;
+    __builtin_assume(r % 16 == 0 && r >= 16);
     // priority: W (read by every product of the second half), then the operands of the passes, then Omega
-    float *W, *T1, *T2, *T4, *Xl;
+    float *W, *T1, *T2, *Xl;
     if constexpr (ALL_LDS) {
         W = pool;
         T1 = pool + rr;
         T2 = pool + 2 * rr;
-        T4 = pool + 3 * rr;
-        Xl = pool + 4 * rr;
+        Xl = pool + 3 * rr;
     } else {
         const int fit = ROT_POOL / rr;
         W = 0 < fit ? pool : p.tmp;
         T1 = 1 < fit ? pool + rr : p.tmp + rr;
         T2 = 2 < fit ? pool + 2 * rr : p.tmp + 2 * rr;
-        T4 = 3 < fit ? pool + 3 * rr : p.tmp + 3 * rr;
-        Xl = 4 < fit ? pool + 4 * rr : p.X;
+        Xl = 3 < fit ? pool + 3 * rr : p.X;
     }
     // W: first beta M - G, then Wh, then W = Wh - Wh^T in place;  T1: A = (beta M - G) X^T, later Y;
-    // T2: X^T (for A), B = X^T A, later X + Y;  T4: the next Y
+    // T2: X^T (for A), B = X^T A, later X + Y
     auto block_sum = [&](double v) -> double {
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
@@ -408,6 +436,33 @@ __global__ __launch_bounds__(1024) void rot_cayley_kernel(RotStepParams p)
         double t = 0.0;
         for (int w = 0; w < 16; ++w) t += red[w];
         return t;
+    };
+    // C(i, j) = sum_k A(i, k) B(k, j), each entry an fma chain over ascending k; out(i, j, value) stores it
+    auto product = [&](auto A, auto B, auto out) {
+        float acc[T][T];
+#pragma unroll
+        for (int a = 0; a < T; ++a)
+#pragma unroll
+            for (int b = 0; b < T; ++b) acc[a][b] = 0.f;
+        const bool live = ty < r && tx < r;  // (rank 16 leaves three quarters of the workgroup idle)
+        if (live) {
+#pragma unroll 8
+            for (int k = 0; k < r; ++k) {
+                float av[T], bv[T];
+#pragma unroll
+                for (int a = 0; a < T; ++a) av[a] = A(ty + 32 * a, k);
+#pragma unroll
+                for (int b = 0; b < T; ++b) bv[b] = B(k, tx + 32 * b);
+#pragma unroll
+                for (int a = 0; a < T; ++a)
+#pragma unroll
+                    for (int b = 0; b < T; ++b) acc[a][b] = __builtin_fmaf(av[a], bv[b], acc[a][b]);
+            }
+#pragma unroll
+            for (int a = 0; a < T; ++a)
+#pragma unroll
+                for (int b = 0; b < T; ++b) out(ty + 32 * a, tx + 32 * b, acc[a][b]);
+        }
     };
     // loss (before the update) and gradient from their partials
     {
@@ -430,29 +485,14 @@ __global__ __launch_bounds__(1024) void rot_cayley_kernel(RotStepParams p)
         T2[j * r + i] = x;  // X^T: the product below then reads rows, not columns (in LDS a column read is a 32-way bank conflict)
     }
     __syncthreads();
-    for (int e = tid; e < rr; e += 1024) {  // A = (beta M - G) X^T
-        const int i = e / r, j = e - i * r;
-        float a = 0.f;
-#pragma unroll 16
-        for (int k = 0; k < r; ++k) a = __builtin_fmaf(W[i * r + k], T2[k * r + j], a);
-        T1[e] = a;
-    }
+    product([&](int i, int k) { return W[i * r + k]; }, [&](int k, int j) { return T2[k * r + j]; },
+            [&](int i, int j, float v) { T1[i * r + j] = v; });                       // A = (beta M - G) X^T
     __syncthreads();
-    for (int e = tid; e < rr; e += 1024) {  // B = X^T A
-        const int i = e / r, j = e - i * r;
-        float a = 0.f;
-#pragma unroll 16
-        for (int k = 0; k < r; ++k) a = __builtin_fmaf(Xl[k * r + i], T1[k * r + j], a);
-        T2[e] = a;
-    }
+    product([&](int i, int k) { return Xl[k * r + i]; }, [&](int k, int j) { return T1[k * r + j]; },
+            [&](int i, int j, float v) { T2[i * r + j] = v; });                       // B = X^T A
     __syncthreads();
-    for (int e = tid; e < rr; e += 1024) {  // Wh = A - 1/2 X B
-        const int i = e / r, j = e - i * r;
-        float a = 0.f;
-#pragma unroll 16
-        for (int k = 0; k < r; ++k) a = __builtin_fmaf(Xl[i * r + k], T2[k * r + j], a);
-        W[e] = T1[e] - 0.5f * a;
-    }
+    product([&](int i, int k) { return Xl[i * r + k]; }, [&](int k, int j) { return T2[k * r + j]; },
+            [&](int i, int j, float v) { W[i * r + j] = T1[i * r + j] - 0.5f * v; });  // Wh = A - 1/2 X B
     __syncthreads();
     double n2 = 0.0;
     for (int e = tid; e < rr; e += 1024) {  // W = Wh - Wh^T, each pair (i, j), (j, i) by the thread of its upper entry
@@ -470,33 +510,20 @@ __global__ __launch_bounds__(1024) void rot_cayley_kernel(RotStepParams p)
     }
     __syncthreads();
     const float alpha = bc;
-    for (int e = tid; e < rr; e += 1024) {  // M = W X;  Y = X + alpha M
-        const int i = e / r, j = e - i * r;
-        float a = 0.f;
-#pragma unroll 16
-        for (int k = 0; k < r; ++k) a = __builtin_fmaf(W[i * r + k], Xl[k * r + j], a);
-        p.M[e] = a;
-        T1[e] = __builtin_fmaf(alpha, a, Xl[e]);
-    }
-    float* Y = T1;
-    float* Yn = T4;
-    for (int it = 0; it < p.s; ++it) {      // Y <- X + alpha/2 W (X + Y)
+    product([&](int i, int k) { return W[i * r + k]; }, [&](int k, int j) { return Xl[k * r + j]; },
+            [&](int i, int j, float v) {                                               // M = W X;  Y = X + alpha M
+                p.M[i * r + j] = v;
+                T1[i * r + j] = __builtin_fmaf(alpha, v, Xl[i * r + j]);
+            });
+    for (int it = 0; it < p.s; ++it) {      // Y <- X + alpha/2 W (X + Y); Y is dead once X + Y is formed, so it is updated in place
         __syncthreads();
-        for (int e = tid; e < rr; e += 1024) T2[e] = Xl[e] + Y[e];
+        for (int e = tid; e < rr; e += 1024) T2[e] = Xl[e] + T1[e];
         __syncthreads();
-        for (int e = tid; e < rr; e += 1024) {
-            const int i = e / r, j = e - i * r;
-            float a = 0.f;
-    #pragma unroll 16
-        for (int k = 0; k < r; ++k) a = __builtin_fmaf(W[i * r + k], T2[k * r + j], a);
-            Yn[e] = __builtin_fmaf(0.5f * alpha, a, Xl[e]);
-        }
-        float* t = Y;
-        Y = Yn;
-        Yn = t;
+        product([&](int i, int k) { return W[i * r + k]; }, [&](int k, int j) { return T2[k * r + j]; },
+                [&](int i, int j, float v) { T1[i * r + j] = __builtin_fmaf(0.5f * alpha, v, Xl[i * r + j]); });
     }
     __syncthreads();
-    for (int e = tid; e < rr; e += 1024) p.X[e] = Y[e];
+    for (int e = tid; e < rr; e += 1024) p.X[e] = T1[e];
 }
 
 __global__ __launch_bounds__(ROT_TPB) void rot_init_kernel(float* X, float* M, const float* X0, const float* M0, int r)
@@ -530,20 +557,30 @@ static void rot_launch_z(const Dims& d, const RotLayout& rl, const RotQ& q, cons
                          float* o1, float* o2, float* ax, float* lp, hipStream_t s)
 {
     const size_t lds = (size_t)R * R * 4;
-    if constexpr (R == 128) {  // Omega alone fills the 64 KB a launch may use without asking for more
-        // once per device and kernel pair, so that later calls (which a caller may capture in a graph) only launch
-        static bool asked[64] = {false};
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
-        if (!asked[dev]) {
-            (void)hipFuncSetAttribute((const void*)rot_zl_kernel<R, OUTZ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            (void)hipFuncSetAttribute((const void*)rot_zr_kernel<R, OUTZ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            asked[dev] = true;
+    auto go = [&](auto qk) {
+        constexpr int BQ = decltype(qk)::value;
+        if constexpr (R == 128) {  // Omega alone fills the 64 KB a launch may use without asking for more
+            // once per device and kernel pair, so that later calls (which a caller may capture in a graph) only launch
+            static bool asked[64] = {false};
+            int dev = 0;
+            if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+            if (!asked[dev]) {
+                (void)hipFuncSetAttribute((const void*)rot_zl_kernel<R, OUTZ, BQ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                (void)hipFuncSetAttribute((const void*)rot_zr_kernel<R, OUTZ, BQ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                asked[dev] = true;
+            }
         }
-    }
-    hipLaunchKernelGGL((rot_zl_kernel<R, OUTZ>), dim3(rl.nlb), dim3(ROT_TPB), lds, s, L, X, (int)d.N, q, o1, lp);
-    hipLaunchKernelGGL((rot_zr_kernel<R, OUTZ>), dim3(rl.nkb), dim3(ROT_TPB), lds, s, Rm, X, (int)d.K, q, o2, ax,
-                       lp ? lp + rl.nlb : nullptr);
+        hipLaunchKernelGGL((rot_zl_kernel<R, OUTZ, BQ>), dim3(rl.nlb), dim3(ROT_TPB), lds, s, L, X, (int)d.N, R, q, o1, lp);
+        hipLaunchKernelGGL((rot_zr_kernel<R, OUTZ, BQ>), dim3(rl.nkb), dim3(ROT_TPB), lds, s, Rm, X, (int)d.K, R, q, o2, ax,
+                           lp ? lp + rl.nlb : nullptr);
+    };
+    // (the rotated factors themselves do not depend on Q2: one instantiation serves both)
+    if (OUTZ || q.kind == 0)
+        go(std::integral_constant<int, 0>{});
+    else if (q.kind == 1)
+        go(std::integral_constant<int, 1>{});
+    else if constexpr (R >= 32)
+        go(std::integral_constant<int, 2>{});
 }
 
 template <bool OUTZ>
@@ -602,10 +639,12 @@ hipError_t launch_rot_step(const Dims& d, const float* L, const float* Rm, uint8
     p.q = cs->q;
     p.grad_scale = cs->grad_scale;
     p.s = cs->s;
-    if (5 * r * r <= ROT_POOL)
-        hipLaunchKernelGGL(rot_cayley_kernel<true>, dim3(1), dim3(1024), 0, s, p);
-    else
-        hipLaunchKernelGGL(rot_cayley_kernel<false>, dim3(1), dim3(1024), 0, s, p);
+    switch ((r + 31) >> 5) {
+        case 1: hipLaunchKernelGGL((rot_cayley_kernel<1, true>), dim3(1), dim3(1024), 0, s, p); break;
+        case 2: hipLaunchKernelGGL((rot_cayley_kernel<2, false>), dim3(1), dim3(1024), 0, s, p); break;
+        case 3: hipLaunchKernelGGL((rot_cayley_kernel<3, false>), dim3(1), dim3(1024), 0, s, p); break;
+        default: hipLaunchKernelGGL((rot_cayley_kernel<4, false>), dim3(1), dim3(1024), 0, s, p); break;
+    }
     return hipGetLastError();
 }
 

@@ -231,10 +231,10 @@ def test_rotation_contract(lq):
     cfg = lq.make_config(128, 256, 32)
     assert raw.lq_rot_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_OK
     r, N, K = 32, 128, 256
-    # Omega, momentum, gradient, E1, E2, row maxima, loss partials, 64 gradient partials, 4 scratch matrices (256-byte aligned each)
+    # Omega, momentum, gradient, E1, E2, row maxima, loss partials, 64 gradient partials, 3 scratch matrices (256-byte aligned each)
     a256 = lambda x: (x + 255) // 256 * 256
     want = 3 * a256(r * r * 4) + a256(N * r * 4) + a256(r * K * 4) + a256(1 * 4 * r * 4) + a256((1 + r * 1) * 4) + \
-        a256(64 * r * r * 4) + a256(4 * r * r * 4)
+        a256(64 * r * r * 4) + a256(3 * r * r * 4)
     assert n.value == want
     opt = lq.lq_cayley(0.5, 0.9, 1e-8, 0.5, 2, 1.0)
     sb = n.value
