@@ -7,7 +7,8 @@
 //     G = -2/(N r) L^T E1 - 2/(r K) R E2^T
 // and the update is the Cayley SGD with momentum of the work the paper cites for it (Li et al. 2020, Algorithm 1).
 // Five launches per step, no atomics, every sum in a fixed order:
-//   rot_zl_kernel     one thread per row of L: Z1 row twice (row maximum, then codes), E1, partial sums of E1^2
+//   rot_zl_kernel     one thread per row of L: the row of Z1 in blocks of 32 columns (twice with a per-row scale: row
+//                     maximum, then codes), E1, partial sums of E1^2
 //   rot_zr_kernel     one thread per column of R: the column of Z2 (stored in E2's place), per-wavefront row maxima
 //   rot_qr_kernel     E2 = deq(Q2(Z2)) - Z2 in place, partial sums of E2^2 (row-scaled Q2 only: with block scales
 //                     rot_zr_kernel forms E2 itself and a step is four launches)
@@ -152,97 +153,95 @@ __device__ __forceinline__ float rot_err_block(float z, int e, const RotQ& q)
     return __builtin_ldexpf(c, e - frac) - z;
 }
 
-// Four neighbouring entries of a row of Z: z[c] = sum_i reg[i] * Om[i][j + c], each an fma chain over ascending i.
-template <int R>
-__device__ __forceinline__ v4f rot_chain4(const float (&reg)[R], const float* om, int j)
+// BW neighbouring entries of the thread's row (or column) of Z: z[c] = sum_i a(i) * Om[i][j0 + c], each an fma chain over
+// ascending i.  The rank index is the loop (four rows of Omega per turn, broadcast from LDS), the BW running sums are the
+// registers: the thread's own operand a(i) is read again for every block of columns (L1-resident) instead of being held,
+// so the register count does not grow with the rank (a first version that held the row spilled at ranks 96 and 128).
+template <int R, int BW, typename AOP>
+__device__ __forceinline__ void rot_chain_block(AOP a, const float* om, int j0, float (&z)[BW])
 {
-    v4f z = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < R; ++i) {
-        const v4f w = *(const v4f*)(om + i * R + j);
+    for (int c = 0; c < BW; ++c) z[c] = 0.f;
+    float av[4], an[4];
+    a(0, av);
+#pragma unroll 1
+    for (int i = 0; i < R; i += 4) {
+        a(i + 4 < R ? i + 4 : i, an);  // the next turn's operand, requested before this turn's arithmetic
 #pragma unroll
-        for (int c = 0; c < 4; ++c) z[c] = __builtin_fmaf(reg[i], w[c], z[c]);
-        // Keeps the compiler from hoisting all R reads of Omega to the top (4 registers each): after every eight rows the
-        // column offset passes through an empty asm together with a chain value, so the next eight reads depend on it.
-        if ((i & 7) == 7) {
-            float z0 = z[0];
-            asm volatile("" : "+v"(j), "+v"(z0));
-            z[0] = z0;
-        }
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int c = 0; c < BW; c += 4) {
+                const v4f w = *(const v4f*)(om + (i + u) * R + j0 + c);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) z[c + t] = __builtin_fmaf(av[u], w[t], z[c + t]);
+            }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) av[u] = an[u];
     }
-    return z;
 }
 
 // One thread per row n of L.  OUTZ: write Z1 = L Omega itself (the rotated factor) instead of its quantisation error.
-// BLOCKQ: Q2 is one of the block kinds (a compile-time split: with the choice made at run time the row-scaled kernels, which
-// hold a whole row in registers, grew from 61 to 173 registers at rank 32 and spilled hundreds at rank 128).
+// QK: 0 integer rows, 1 FP8 rows (one scale per row: the chains run twice, row maximum first), 2 block kinds (a block
+// of 32 columns is one pass of the chains).
 template <int R, bool OUTZ, int QK>
 __global__ __launch_bounds__(ROT_TPB) void rot_zl_kernel(const float* __restrict__ L, const float* __restrict__ X, int N,
-                                                        int rrt, RotQ q, float* __restrict__ out, float* __restrict__ lp)
+                                                        RotQ q, float* __restrict__ out, float* __restrict__ lp)
 {
-    constexpr bool BLOCKQ = QK == 2;
+    constexpr int BW = R < 32 ? R : 32;
     extern __shared__ __attribute__((aligned(16))) float om[];
     __shared__ float red[4];
     for (int i = threadIdx.x; i < R * R; i += ROT_TPB) om[i] = X[i];
     __syncthreads();
     const int n = blockIdx.x * ROT_TPB + threadIdx.x;
     const bool ok = n < N;
-    float reg[R];
-#pragma unroll
-    for (int i = 0; i < R; i += 4) {
-        const v4f v = ok ? *(const v4f*)(L + (size_t)n * R + i) : v4f{0.f, 0.f, 0.f, 0.f};
-        reg[i] = v[0]; reg[i + 1] = v[1]; reg[i + 2] = v[2]; reg[i + 3] = v[3];
-    }
+    const float* lrow = L + (size_t)(ok ? n : 0) * R;  // rows past N recompute row 0 and store nothing
+    auto aop = [&](int i, float (&av)[4]) {
+        const v4f v = *(const v4f*)(lrow + i);
+        av[0] = v[0]; av[1] = v[1]; av[2] = v[2]; av[3] = v[3];
+    };
+    float* orow = out + (size_t)(ok ? n : 0) * R;
+    float z[BW];
     float sq = 0.f;
     if constexpr (OUTZ) {
 #pragma unroll 1
-        for (int j = 0; j < rrt; j += 4) {  // rrt = R, passed as an argument: a bound the compiler cannot unroll over
-            const v4f z = rot_chain4<R>(reg, om, j);
-            if (ok) *(v4f*)(out + (size_t)n * R + j) = z;
+        for (int j0 = 0; j0 < R; j0 += BW) {
+            rot_chain_block<R, BW>(aop, om, j0, z);
+            if (ok) {
+#pragma unroll
+                for (int c = 0; c < BW; c += 4) *(v4f*)(orow + j0 + c) = v4f{z[c], z[c + 1], z[c + 2], z[c + 3]};
+            }
         }
     } else {
-        if constexpr (!BLOCKQ) {  // one scale per row: the chains run twice, over the whole row
+        float s = 1.f, inv = 1.f;
+        if constexpr (QK != 2) {
             float amax = 0.f;
 #pragma unroll 1
-            for (int j = 0; j < R; j += 4) {
-                const v4f z = rot_chain4<R>(reg, om, j);
-                amax = fmaxf(fmaxf(amax, fmaxf(fabsf(z[0]), fabsf(z[1]))), fmaxf(fabsf(z[2]), fabsf(z[3])));
+            for (int j0 = 0; j0 < R; j0 += BW) {
+                rot_chain_block<R, BW>(aop, om, j0, z);
+#pragma unroll
+                for (int c = 0; c < BW; ++c) amax = fmaxf(amax, fabsf(z[c]));
             }
-            float s, inv;
             rot_scale(amax, q.top, s, inv);
+        }
 #pragma unroll 1
-            for (int j = 0; j < R; j += 4) {
-                const v4f z = rot_chain4<R>(reg, om, j);  // the same chains: the same bits as in the first pass
-                v4f e;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    e[c] = rot_err<QK>(z[c], s, inv, q.top);
-                    sq = __builtin_fmaf(e[c], e[c], sq);
-                }
-                if (ok) *(v4f*)(out + (size_t)n * R + j) = e;
-            }
-        } else {  // one scale per 32 columns: block by block, the chains run twice (ranks here are multiples of 32)
-            const int blk = rrt < 32 ? rrt : 32;  // 32; from an argument, so that the loops below stay loops
-#pragma unroll 1
-            for (int j0 = 0; j0 < rrt; j0 += blk) {
+        for (int j0 = 0; j0 < R; j0 += BW) {
+            rot_chain_block<R, BW>(aop, om, j0, z);  // (row kinds: the same chains, the same bits as in the first pass)
+            int eb = 0;
+            if constexpr (QK == 2) {
                 float amax = 0.f;
-#pragma unroll 1
-                for (int j = j0; j < j0 + blk; j += 4) {
-                    const v4f z = rot_chain4<R>(reg, om, j);
-                    amax = fmaxf(fmaxf(amax, fmaxf(fabsf(z[0]), fabsf(z[1]))), fmaxf(fabsf(z[2]), fabsf(z[3])));
-                }
-                const int eb = rot_block_exp(amax, q);
-#pragma unroll 1
-                for (int j = j0; j < j0 + blk; j += 4) {
-                    const v4f z = rot_chain4<R>(reg, om, j);
-                    v4f e;
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        e[c] = rot_err_block(z[c], eb, q);
-                        sq = __builtin_fmaf(e[c], e[c], sq);
-                    }
-                    if (ok) *(v4f*)(out + (size_t)n * R + j) = e;
-                }
+                for (int c = 0; c < BW; ++c) amax = fmaxf(amax, fabsf(z[c]));
+                eb = rot_block_exp(amax, q);
+            }
+#pragma unroll
+            for (int c = 0; c < BW; ++c) {
+                if constexpr (QK == 2) z[c] = rot_err_block(z[c], eb, q);
+                else z[c] = rot_err<QK>(z[c], s, inv, q.top);
+                sq = __builtin_fmaf(z[c], z[c], sq);
+            }
+            if (ok) {
+#pragma unroll
+                for (int c = 0; c < BW; c += 4) *(v4f*)(orow + j0 + c) = v4f{z[c], z[c + 1], z[c + 2], z[c + 3]};
             }
         }
         const float tot = rot_block_sum(ok ? sq : 0.f, red);
@@ -256,45 +255,47 @@ __global__ __launch_bounds__(ROT_TPB) void rot_zl_kernel(const float* __restrict
 // is formed here, written to out, and its squares are summed into lp[block].
 template <int R, bool OUTZ, int QK>
 __global__ __launch_bounds__(ROT_TPB) void rot_zr_kernel(const float* __restrict__ Rm, const float* __restrict__ X, int K,
-                                                        int rrt, RotQ q, float* __restrict__ out, float* __restrict__ ax,
+                                                        RotQ q, float* __restrict__ out, float* __restrict__ ax,
                                                         float* __restrict__ lp)
 {
-    constexpr bool BLOCKQ = QK == 2;
+    constexpr int BW = R < 32 ? R : 32;
     extern __shared__ __attribute__((aligned(16))) float om[];
     __shared__ float red[4];
-    float sq = 0.f;
     for (int i = threadIdx.x; i < R * R; i += ROT_TPB) om[i] = X[i];
     __syncthreads();
     const int k = blockIdx.x * ROT_TPB + threadIdx.x;
     const bool ok = k < K;
-    float reg[R];
-    // buffer loads: the row offset i * K travels in a scalar register, so the R loads share one vector offset instead
-    // of holding a 64-bit vector address each; a column past K reads finite in-range data of the next row (zeros past
-    // the end of the descriptor), and nothing computed from it is stored or enters a maximum
+    // buffer loads: the row offset i * K travels in a scalar register and all loads share one vector offset; a column
+    // past K reads finite in-range data of the next row (zeros past the end of the descriptor), and nothing computed
+    // from it is stored or enters a maximum
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)Rm, 0, R * K * 4, 0x00020000);
+    auto aop = [&](int i, float (&av)[4]) {
 #pragma unroll
-    for (int i = 0; i < R; ++i) reg[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, k * 4, i * K * 4, 0));
+        for (int u = 0; u < 4; ++u) av[u] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, k * 4, (i + u) * K * 4, 0));
+    };
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    float z[BW];
+    float sq = 0.f;
 #pragma unroll 1
-    for (int j = 0; j < rrt; j += 4) {
-        const v4f z = rot_chain4<R>(reg, om, j);
+    for (int j0 = 0; j0 < R; j0 += BW) {
+        rot_chain_block<R, BW>(aop, om, j0, z);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
+        for (int c = 0; c < BW; ++c) {
             float o = z[c];
             if constexpr (!OUTZ) {
-                if constexpr (!BLOCKQ) {
-                    const float m = rot_wave_max(ok ? fabsf(z[c]) : 0.f);
-                    if (lane == 0) ax[(size_t)(blockIdx.x * 4 + wave) * R + j + c] = m;
+                if constexpr (QK != 2) {
+                    const float m = rot_wave_max(ok ? fabsf(o) : 0.f);
+                    if (lane == 0) ax[(size_t)(blockIdx.x * 4 + wave) * R + j0 + c] = m;
                 } else {
-                    const int eb = rot_block_exp(rot_half_max(ok ? fabsf(z[c]) : 0.f, lane), q);
-                    o = rot_err_block(z[c], eb, q);
+                    const int eb = rot_block_exp(rot_half_max(ok ? fabsf(o) : 0.f, lane), q);
+                    o = rot_err_block(o, eb, q);
                     if (ok) sq = __builtin_fmaf(o, o, sq);
                 }
             }
-            if (ok) out[(size_t)(j + c) * K + k] = o;
+            if (ok) out[(size_t)(j0 + c) * K + k] = o;
         }
     }
-    if constexpr (!OUTZ && BLOCKQ) {
+    if constexpr (!OUTZ && QK == 2) {
         const float tot = rot_block_sum(sq, red);
         if (threadIdx.x == 0) lp[blockIdx.x] = tot;
     }
@@ -570,8 +571,8 @@ static void rot_launch_z(const Dims& d, const RotLayout& rl, const RotQ& q, cons
                 asked[dev] = true;
             }
         }
-        hipLaunchKernelGGL((rot_zl_kernel<R, OUTZ, BQ>), dim3(rl.nlb), dim3(ROT_TPB), lds, s, L, X, (int)d.N, R, q, o1, lp);
-        hipLaunchKernelGGL((rot_zr_kernel<R, OUTZ, BQ>), dim3(rl.nkb), dim3(ROT_TPB), lds, s, Rm, X, (int)d.K, R, q, o2, ax,
+        hipLaunchKernelGGL((rot_zl_kernel<R, OUTZ, BQ>), dim3(rl.nlb), dim3(ROT_TPB), lds, s, L, X, (int)d.N, q, o1, lp);
+        hipLaunchKernelGGL((rot_zr_kernel<R, OUTZ, BQ>), dim3(rl.nkb), dim3(ROT_TPB), lds, s, Rm, X, (int)d.K, q, o2, ax,
                            lp ? lp + rl.nlb : nullptr);
     };
     // (the rotated factors themselves do not depend on Q2: one instantiation serves both)
