@@ -115,7 +115,8 @@ def bench_rot(args, layer, np, torch, lq, wl):
         from oracle import lq_ref
         st = lq_ref.rot_init(r)
         t0 = time.perf_counter()
-        lq_ref.rot_step(L * scale, R * scale, st, bits=layer.br_w_bits)
+        q2 = {"mx": "fp8", "mxi": "mxint"}.get(layer.family, ("mxfp6" if layer.br_w_bits == 6 else "mxfp8") if layer.family == "mxb" else "int")
+        lq_ref.rot_step(L * scale, R * scale, st, bits=layer.br_w_bits, q2=q2)
         dt = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(1.0 / dt, 3), "unit": "steps/s", "cores": lq_ref.num_threads(), "kind": "oracle",
                                "sample": "one full step of the same layer"}
