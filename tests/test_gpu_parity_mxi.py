@@ -90,7 +90,7 @@ def _compare(oracle, layer, X, W, L, R, rows=None, exact=False, gamma=None):
     tau = 1e-3 * np.sqrt(np.mean(out.y32.astype(np.float64) ** 2)) + 1e-300
     rel = np.abs(Yf - Yo) / np.maximum(np.abs(out.y32), tau)
     flips = Yb != out.Y
-    assert flips.mean() <= 2e-3, f"bf16 flip rate {flips.mean()}"
+    assert flips.sum() <= max(1, 2e-3 * flips.size), f"bf16 flip rate {flips.mean()}"  # (one flip is allowed on a tiny output)
     assert np.all(rel[~flips] <= 2e-3)
     assert np.all(rel[flips] <= 2.0 ** -7 * 1.01)
     g2 = run_gpu(layer, X, W, L, R, debug=False, gamma=gamma)
