@@ -151,7 +151,7 @@ def main():
     import torch
     from paper_2604_18117_amd import binding as lq
     from paper_2604_18117_amd import workloads as wl
-    from tests.gpu_util import to_dev_x
+    to_dev_x = wl.to_dev_x
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -315,7 +315,7 @@ def main():
         dt = time.perf_counter() - t
         cpu_tops = ops * (rows / M) / dt / 1e12
         # parity spot check of the bench's own launch against those rows
-        from tests.gpu_util import bf16_to_bits
+        bf16_to_bits = wl.bf16_to_bits
         lq.lq_quantize_act(cfg, packed, Xs[0], act=acts[0])
         lq.lq_linear_lowrank_fwd(cfg, packed, acts[0], M, Y=Ys[0])
         torch.cuda.synchronize()

@@ -151,12 +151,16 @@ def make_inputs(layer: Layer) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.nd
     return X, W, L, R
 
 
-def smoothing_vector(X: np.ndarray, W: np.ndarray, alpha: float = 0.5, beta: float = 0.5) -> np.ndarray:
-    """A per-channel smoothing vector for a layer's inputs, of the shape the paper's App. A.1 describes
-    (channel maximum of the activations to the power alpha over channel maximum of the weights to the
-    power beta), computed on the synthetic tensors themselves.  It is an INPUT of the path (the paper
-    calibrates it offline); channels that are all zero get 1."""
-    ax = np.abs(X).max(axis=0).astype(np.float64)
-    aw = np.abs(W).max(axis=0).astype(np.float64)
-    g = np.where((ax > 0) & (aw > 0), ax ** alpha / np.maximum(aw, 1e-30) ** beta, 1.0)
-    return g.astype(np.float32)
+def to_dev_x(X: np.ndarray, x_dtype: str):
+    """X as a device tensor of the layer's input type (marshalling only; torch is imported on use)."""
+    import torch
+    if x_dtype == "bf16":
+        bits = f32_to_bf16_bits(X).view(np.int16)
+        return torch.from_numpy(bits.copy()).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(X, np.float32)).cuda()
+
+
+def bf16_to_bits(t) -> np.ndarray:
+    """uint16 bit patterns of a bf16 device tensor, on the host."""
+    import torch
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)

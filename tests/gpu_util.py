@@ -7,15 +7,8 @@ import torch
 from paper_2604_18117_amd import workloads as wl
 
 
-def to_dev_x(X: np.ndarray, x_dtype: str) -> torch.Tensor:
-    if x_dtype == "bf16":
-        bits = wl.f32_to_bf16_bits(X).view(np.int16)
-        return torch.from_numpy(bits.copy()).cuda().view(torch.bfloat16)
-    return torch.from_numpy(np.ascontiguousarray(X, np.float32)).cuda()
-
-
-def bf16_to_bits(t: torch.Tensor) -> np.ndarray:
-    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+to_dev_x = wl.to_dev_x
+bf16_to_bits = wl.bf16_to_bits
 
 
 @dataclass

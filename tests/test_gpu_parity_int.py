@@ -9,6 +9,7 @@ import pytest
 import torch
 
 from paper_2604_18117_amd import workloads as wl
+from tests.smoothing import smoothing_vector
 from tests.gpu_util import bf16_to_bits, n, run_gpu, run_oracle_int
 
 pytestmark = pytest.mark.gpu
@@ -174,7 +175,7 @@ def test_fused_smoothing(oracle, M, K, N, r, xd, ag):
     layer = wl.shrink(wl.LAYERS["c2_qkv"], M=M, K=K, N=N, r=r)
     layer = wl.Layer(**{**layer.__dict__, "x_dtype": xd, "seed": M + K, "a_group": ag})
     X, W, L, R = wl.make_inputs(layer)
-    gamma = wl.smoothing_vector(X, W)
+    gamma = smoothing_vector(X, W)
     Ws = (W.astype(np.float64) * gamma).astype(np.float32)       # the caller folds gamma into W before packing
     cfg = lq.config_for_layer(layer, smooth=True)
     packed = lq.lq_pack_weights(cfg, torch.from_numpy(Ws).cuda(), torch.from_numpy(L).cuda() if r else None,
@@ -292,7 +293,7 @@ def test_long_rows_are_streamed(oracle, M, K, N, r, xd, ag, sm):
     if not sm:
         _compare_all(oracle, layer, X, W, L, R)
         return
-    gamma = wl.smoothing_vector(X, W)
+    gamma = smoothing_vector(X, W)
     g = run_gpu(layer, X, W, L, R, debug=True, debug_acc=False, gamma=gamma)
     pk, act, out = run_oracle_int(oracle, layer, oracle.smooth(X, gamma), W, L, R, want_acc=False)
     assert np.array_equal(n(g.av.xq), act.xq) and np.array_equal(n(g.av.sx), act.sx)

@@ -12,6 +12,7 @@ import pytest
 import torch
 
 from paper_2604_18117_amd import workloads as wl
+from tests.smoothing import smoothing_vector
 from tests.gpu_util import bf16_to_bits, n, run_gpu
 
 pytestmark = pytest.mark.gpu
@@ -160,4 +161,4 @@ def test_long_rows_are_streamed(oracle, M, K, N, r, xd, sm):
     """Rows that do not fit the register-resident activation kernel go through the two-pass streamed form."""
     layer = wl.Layer("t", M, K, N, r, "mx", 32, 8, 8, xd, outlier_scale=10.0, n_outliers=8, seed=K)
     X, W, L, R = wl.make_inputs(layer)
-    _compare(oracle, layer, X, W, L, R, gamma=wl.smoothing_vector(X, W) if sm else None)
+    _compare(oracle, layer, X, W, L, R, gamma=smoothing_vector(X, W) if sm else None)

@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 
 from paper_2604_18117_amd import workloads as wl
+from tests.smoothing import smoothing_vector
 from tests import test_gpu_parity_mx as t_mx
 from tests import test_gpu_parity_mxb as t_mxb
 from tests import test_gpu_parity_mxi as t_mxi
@@ -52,7 +53,7 @@ def test_fused_smoothing(oracle, family, M, K, N, r, xd):
     else:
         layer, cmp = wl.Layer(**dict(kw, family="mxi", br_w_bits=int(family[-1]), br_a_bits=8)), t_mxi._compare
     X, W, L, R = wl.make_inputs(layer)
-    gamma = wl.smoothing_vector(X, W)
+    gamma = smoothing_vector(X, W)
     Ws = (W.astype(np.float64) * gamma).astype(np.float32)            # the caller folds gamma into W before packing
     cmp(oracle, layer, X, Ws, L, R, gamma=gamma)
     # the vector did change the codes: the unsmoothed run differs

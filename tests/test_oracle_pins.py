@@ -12,6 +12,7 @@ import numpy as np
 import pytest
 
 from paper_2604_18117_amd import workloads as wl
+from tests.smoothing import smoothing_vector
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "ocp_mx_element_formats.txt")
 
@@ -1111,7 +1112,7 @@ def test_smoothing_is_a_reciprocal_multiply_and_tames_outlier_channels(oracle):
     out_cols = rng.choice(K, 4, replace=False)
     X[:, out_cols] *= 30                                   # the situation smoothing addresses
     W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
-    g = wl.smoothing_vector(X, W)
+    g = smoothing_vector(X, W)
     assert g.shape == (K,) and np.all(g > 0) and np.all(g[out_cols] > np.median(g) * 3)
     Xs = oracle.smooth(X, g)
     # correctly rounded reciprocal, one rounding for the product (exact rationals)
