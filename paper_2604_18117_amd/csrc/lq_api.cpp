@@ -42,8 +42,8 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         if (cfg->main_a_group == 64 && cfg->main_w_group != 64) return LQ_ERR_UNSUPPORTED;  // one block size for both operands
         d->ga = cfg->main_a_group == 64;
         if (d->ga && cfg->K > 5632) return LQ_ERR_UNSUPPORTED;  // the forward keeps a tile's token block scales in LDS
-        // ... and addresses the channel block scales with 32-bit byte offsets
-        if (d->ga && cfg->N * (cfg->K / 64) * 4 >= ((int64_t)1 << 31)) return LQ_ERR_UNSUPPORTED;
+        // the forward addresses the channel group scales with 32-bit byte offsets
+        if (cfg->N * (cfg->K / cfg->main_w_group) * 4 >= ((int64_t)1 << 31)) return LQ_ERR_UNSUPPORTED;
         const int qw = int_qmax(cfg->br_w), qa = int_qmax(cfg->br_a);
         if (qw == 0 || qa == 0 || cfg->br_a == LQ_INT4) return LQ_ERR_UNSUPPORTED;
         d->mx = false;
@@ -89,7 +89,7 @@ PackedLayout packed_layout(const Dims& d)
     PackedLayout pl;
     size_t o = 0;
     pl.off_pq = o;
-    o = align256(o + (size_t)d.N * d.K / 2);
+    o = align256(o + ((d.mx || d.mxi) ? (size_t)d.N * d.K / 2 : (size_t)d.N * d.K / 4 * 3));  // INT family: 6-bit fields
     pl.off_sw = o;
     o = align256(o + ((d.mx || d.mxi) ? (size_t)(d.N / 32) * ((d.C64 + 3) / 4) * 256 : (size_t)d.N * d.G * 4));
     pl.off_lq = o;
@@ -115,7 +115,7 @@ ActLayout act_layout(const Dims& d, int64_t M)
     al.Mp = (M + 31) / 32 * 32;
     size_t o = 0;
     al.off_xq = o;
-    o = align256(o + (size_t)al.Mp * d.K / 2);
+    o = align256(o + ((d.mx || d.mxi) ? (size_t)al.Mp * d.K / 2 : (size_t)al.Mp * d.K / 4 * 3));
     al.off_sx = o;
     o = align256(o + ((d.mx || d.mxi) ? (size_t)(al.Mp / 32) * ((d.C64 + 3) / 4) * 256
                       : d.ga          ? (size_t)d.G * ((al.Mp + 127) / 128) * 512

@@ -5,29 +5,30 @@
 //   acc2[m,n]  = sum_j tq[m,j] lq[n,j]                  int8 MFMA, int32
 //   y          = fma(sx[m], t, (float(acc2) * st[m]) * sl[n]);   Y = bf16_rne(y)
 //
-// The 4-bit codes are fed to the matrix cores as FP8-E4M3 subnormals (byte s0000mmm =
-// +-m * 2^-9): every product and every partial sum of a 64..128-deep group is an integer
-// multiple of 2^-18 below 2^13 * 2^-18, so the fp32 MFMA accumulator holds the integer
-// accumulator exactly and the per-group dequantisation is ONE fp32 FMA per output (no
-// int->float conversion); the factor 2^18 is folded into the stored weight scales.
+// The 4-bit codes are stored as 6-bit fields s00mmm = the E2M3 pattern of +-m/8 and go to the matrix
+// cores as they are (v_mfma_f32_32x32x64_f8f6f4 in FP6 mode): every product and every partial sum of a
+// 64..128-deep group is an integer multiple of 2^-6 below 2^13 * 2^-6, so the fp32 MFMA accumulator
+// holds the integer accumulator exactly and the per-group dequantisation is ONE fp32 FMA per output (no
+// int->float conversion, no operand expansion); the factor 2^6 is folded into the stored weight scales.
 //
 // SINT4 blocks for both operands (template flag GA; App. A.3: one FP16 scale per 64 values): the dequantisation
 // factor of an output and a K block is sx[m,g] * sw[n,g].  The 32 x 32 tile of these products comes from the
 // matrix core as well: one v_mfma_f32_32x32x16_f16 whose A operand holds the token scales of the tile's four
 // row blocks at k = 0, 2, 4, 6 (a lane's 16-byte load as it stands) and whose B operand holds the channel
 // scale at the k of the wanted row block and zeros elsewhere; a product of two FP16 numbers is exact in fp32.
-// The per-group dequantisation therefore stays ONE FMA per output, t = fma(acc, P, t); the factor 2^18 of the
-// FP8-subnormal trick is applied once at the end (t * 2^18 is exact).
+// The per-group dequantisation therefore stays ONE FMA per output, t = fma(acc, P, t); the factor 2^6 of the
+// code fields is applied once at the end (t * 2^6 is exact).
 //
 // Work decomposition: a workgroup of 4 wavefronts computes a 128 x 256 tile of Y (64 x 256 for
 // the half tiles at the tail of the grid); each wavefront owns 128 x 64 (4 x 2 MFMA tiles of
-// 32 x 32, 128 fp32 running sums per lane).  Activation codes go global -> registers -> (nibble
-// to byte) -> LDS once per workgroup; weight codes are read by each wavefront straight from
-// global memory in operand order (no other wavefront needs them) and expanded in registers.
+// 32 x 32, 128 fp32 running sums per lane).  Activation codes go global -> registers -> LDS once per
+// workgroup; weight codes are read by each wavefront straight from global memory in operand order (no
+// other wavefront needs them) into the registers the MFMAs read.
 #include "lq_internal.h"
 
 namespace lq {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
@@ -56,15 +57,12 @@ struct FwdParams {
     float* dbg_y32;
 };
 
-__device__ __forceinline__ v8i expand8(v4i p)
+// One lane's FP6 operand: 32 six-bit codes = 24 bytes = six dwords (loaded as the 16-byte and the 8-byte part of the layout).
+typedef int Op6 __attribute__((ext_vector_type(6)));
+__device__ __forceinline__ Op6 op6(v4i lo, v2i hi) { return Op6{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1]}; }
+__device__ __forceinline__ v8i op8(Op6 o)  // the builtin's operand type; FP6 mode reads the first six dwords
 {
-    v8i o;
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-        o[2 * d] = (int)nib_lo((uint32_t)p[d]);
-        o[2 * d + 1] = (int)nib_hi((uint32_t)p[d]);
-    }
-    return o;
+    return __builtin_shufflevector(o, o, 0, 1, 2, 3, 4, 5, -1, -1);
 }
 
 constexpr int WN = 4;                          // wavefronts per workgroup, side by side along N
@@ -76,8 +74,8 @@ constexpr int GA_MAXG = 88;                    // SINT4-block variant: K <= 5632
 template <int GC>
 constexpr int lds_bytes()
 {
-    // [buffer][chunk in group][row block][part][lane][16 B]
-    return 2 * GC * RBT * 2048 > NW * EPI_WAVE ? 2 * GC * RBT * 2048 : NW * EPI_WAVE;
+    // [buffer][chunk in group][row block][1536 B]
+    return 2 * GC * RBT * F6_CHUNK > NW * EPI_WAVE ? 2 * GC * RBT * F6_CHUNK : NW * EPI_WAVE;
 }
 
 // One output tile: rows rb0*32.., columns tile_n*256...  Each wavefront owns NRB row blocks x 64
@@ -91,8 +89,11 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
 {
     static_assert(!GA || GC == 1, "SINT4 blocks are 64 deep");
     typedef _Float16 v8h __attribute__((ext_vector_type(8)));
-    constexpr int SPW = 1;                      // row blocks staged per wavefront
-    constexpr int STAGES = (GC == 1) ? 2 : 1;   // register sets of the global-load pipeline
+    // Register sets of the weight stream: with 64-deep groups three sets rotate (a step's operands are requested two
+    // steps before their use: an L2 round trip is about as long as one step); 128-deep groups (a step twice as long)
+    // and the register-scarce SINT4-block variant use two sets, reloaded right after their last use.
+    constexpr int BSETS = (GC == 1 && !GA) ? 3 : 2;
+    constexpr int ASETS = (GC == 1) ? 2 : 1;    // register sets of the activation stream (on their way to LDS)
     constexpr int NT = NRB * 2;                 // 32 x 32 MFMA tiles per wavefront and step
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -109,78 +110,55 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     const int C64 = p.C64, G = p.G;
 
     // ---- operand streams -----------------------------------------------------------------
-    // Global loads run TWO steps ahead of their use (an L2 round trip is about as long as one
-    // step), in two alternating register sets per stream; the step loop is unrolled by two so
-    // that the sets are addressed statically.  Steps and row blocks are clamped instead of
-    // predicated: the loop body stays branch-free, and a clamped load only re-reads valid data
-    // that never reaches a stored output.
+    // Steps and row blocks are clamped instead of predicated: the loop body stays branch-free, and a
+    // clamped load only re-reads valid data that never reaches a stored output.
     // Every wavefront stages one row block; with a half tile the upper two stage (clamped)
     // blocks that are not read.
-    const uint32_t lane16 = (uint32_t)lane * 16u;
+    const uint32_t lane16 = (uint32_t)lane * 16u, lane8 = 1024u + (uint32_t)lane * 8u;
     const uint32_t l32x4 = (uint32_t)l32 * 4u, l32x16 = (uint32_t)l32 * 16u;
-    const uint8_t* xq_base[SPW];
-#pragma unroll
-    for (int i = 0; i < SPW; ++i) {
-        int rb = rb0 + wave * SPW + i;
-        rb = rb < p.nrb ? rb : p.nrb - 1;
-        xq_base[i] = p.xq + (size_t)rb * C64 * 1024;
-    }
+    int rbs = rb0 + wave;
+    rbs = rbs < p.nrb ? rbs : p.nrb - 1;
+    const uint8_t* xq_base = p.xq + (size_t)rbs * C64 * F6_CHUNK;
     const int cbw = (cb0 * 32 < p.N) ? cb0 : 0;  // wavefronts past the last column read block 0 (unused)
-    const uint8_t* pq_base[2] = {p.pq + (size_t)cbw * C64 * 1024, p.pq + (size_t)(cbw + 1) * C64 * 1024};
+    const uint8_t* pq_base[2] = {p.pq + (size_t)cbw * C64 * F6_CHUNK, p.pq + (size_t)(cbw + 1) * C64 * F6_CHUNK};
     const float* sw_base = p.swT + cbw * 32;
 
-    struct AStage { v4i v[SPW][GC]; };
-    struct BStage { v4i v[GC][2]; float sw[2]; };
-    // SINT4-block variant: registers are scarce, so its streams are read with buffer loads: a wave-uniform
-    // descriptor and step offset in scalar registers plus the one 32-bit lane offset all streams share,
-    // instead of a 64-bit vector address per stream.  Each descriptor spans exactly the bytes its stream
-    // may touch (a read past it would return zeros).
+    struct AStage { Op6 v[GC]; };
+    struct BStage { Op6 v[GC][2]; float sw[2]; };
+    // The streams are read with buffer loads: a wave-uniform descriptor and step offset in scalar registers plus
+    // the 32-bit lane offsets all streams share, instead of a 64-bit vector address per stream (registers are
+    // scarce).  Each descriptor spans exactly the bytes its stream may touch (a read past it would return zeros).
     typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    typedef unsigned int u2 __attribute__((ext_vector_type(2)));
     constexpr int RSRC_FLAGS = 0x00020000;
-    __amdgpu_buffer_rsrc_t rs_xq, rs_pq[2], rs_sw;
-    if constexpr (GA) {
-        static_assert(SPW == 1, "one staged row block per wavefront");
-        rs_xq = __builtin_amdgcn_make_buffer_rsrc((void*)xq_base[0], 0, C64 * 1024, RSRC_FLAGS);
-        rs_pq[0] = __builtin_amdgcn_make_buffer_rsrc((void*)pq_base[0], 0, C64 * 1024, RSRC_FLAGS);
-        rs_pq[1] = __builtin_amdgcn_make_buffer_rsrc((void*)pq_base[1], 0, C64 * 1024, RSRC_FLAGS);
-        rs_sw = __builtin_amdgcn_make_buffer_rsrc((void*)sw_base, 0, (G * p.N - cbw * 32) * 4, RSRC_FLAGS);
-    }
+    const __amdgpu_buffer_rsrc_t rs_xq = __builtin_amdgcn_make_buffer_rsrc((void*)xq_base, 0, C64 * F6_CHUNK, RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t rs_pq[2] = {__builtin_amdgcn_make_buffer_rsrc((void*)pq_base[0], 0, C64 * F6_CHUNK, RSRC_FLAGS),
+                                             __builtin_amdgcn_make_buffer_rsrc((void*)pq_base[1], 0, C64 * F6_CHUNK, RSRC_FLAGS)};
+    const __amdgpu_buffer_rsrc_t rs_sw = __builtin_amdgcn_make_buffer_rsrc((void*)sw_base, 0, (G * p.N - cbw * 32) * 4, RSRC_FLAGS);
+    auto load_op = [&](Op6& o, const __amdgpu_buffer_rsrc_t& rs, int chunk) {
+        o = op6(__builtin_bit_cast(v4i, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs, lane16, chunk * F6_CHUNK, 0)),
+                __builtin_bit_cast(v2i, (u2)__builtin_amdgcn_raw_buffer_load_b64(rs, lane8, chunk * F6_CHUNK, 0)));
+    };
     auto load_a = [&](AStage& a, int step) {
         const int st = step < G ? step : G - 1;
 #pragma unroll
-        for (int i = 0; i < SPW; ++i)
-#pragma unroll
-            for (int cc = 0; cc < GC; ++cc)
-                if constexpr (GA)
-                    a.v[i][cc] = __builtin_bit_cast(v4i, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs_xq, lane16, st * 1024, 0));
-                else
-                    a.v[i][cc] = *(const v4i*)(xq_base[i] + (size_t)(st * GC + cc) * 1024 + lane16);
+        for (int cc = 0; cc < GC; ++cc) load_op(a.v[cc], rs_xq, st * GC + cc);
     };
     auto store_a = [&](const AStage& a, int buf) {
 #pragma unroll
-        for (int i = 0; i < SPW; ++i)
-#pragma unroll
-            for (int cc = 0; cc < GC; ++cc) {
-                const v8i e = expand8(a.v[i][cc]);
-                uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wave * SPW + i) * 2048) + lane16;
-                *(v4i*)(base) = v4i{e[0], e[1], e[2], e[3]};
-                *(v4i*)(base + 1024) = v4i{e[4], e[5], e[6], e[7]};
-            }
+        for (int cc = 0; cc < GC; ++cc) {
+            uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wave) * F6_CHUNK);
+            *(v4i*)(base + lane16) = v4i{a.v[cc][0], a.v[cc][1], a.v[cc][2], a.v[cc][3]};
+            *(v2i*)(base + lane8) = v2i{a.v[cc][4], a.v[cc][5]};
+        }
     };
     auto load_b = [&](BStage& b, int step) {
         const int st = step < G ? step : G - 1;
 #pragma unroll
         for (int cbi = 0; cbi < 2; ++cbi) {
 #pragma unroll
-            for (int cc = 0; cc < GC; ++cc)
-                if constexpr (GA)
-                    b.v[cc][cbi] = __builtin_bit_cast(v4i, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs_pq[cbi], lane16, st * 1024, 0));
-                else
-                    b.v[cc][cbi] = *(const v4i*)(pq_base[cbi] + (size_t)(st * GC + cc) * 1024 + lane16);
-            if constexpr (GA)
-                b.sw[cbi] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_sw, l32x4 + cbi * 128, st * p.N * 4, 0));
-            else
-                b.sw[cbi] = sw_base[(size_t)st * p.N + cbi * 32 + l32];
+            for (int cc = 0; cc < GC; ++cc) load_op(b.v[cc][cbi], rs_pq[cbi], st * GC + cc);
+            b.sw[cbi] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_sw, l32x4 + cbi * 128, st * p.N * 4, 0));
         }
     };
 
@@ -213,151 +191,154 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
 #pragma unroll
             for (int i = 0; i < 16; ++i) t[a][b][i] = 0.f;
 
-    v8i bu[GC][2];   // expanded weight operands of the current step
-    float sw[2];     // their scales
     const uint64_t half_mask = 0xFFFFFFFF00000000ull;
     v4i bsel = {0, 0, 0, 0};
-    auto expand_b = [&](const BStage& b) {
-#pragma unroll
-        for (int cbi = 0; cbi < 2; ++cbi) {
-#pragma unroll
-            for (int cc = 0; cc < GC; ++cc) bu[cc][cbi] = expand8(b.v[cc][cbi]);
-            // a real move: keeps `sw` in a register of its own, so that the next load can land
-            // in b.sw directly (a coalesced copy would force a wait on that fresh load)
-            if constexpr (GA)  // FP16 bits in the lanes of K half 0, zero in the others (they hold k = 8..15 of the scale MFMA)
-                asm volatile("v_cndmask_b32 %0, %1, 0, %2" : "=v"(sw[cbi]) : "v"(b.sw[cbi]), "s"(half_mask));
-            else
-                asm volatile("v_mov_b32 %0, %1" : "=v"(sw[cbi]) : "v"(b.sw[cbi]));
-        }
-    };
 
-    // One step = one weight group.  On entry: LDS buffer s&1 holds the activation operands of
-    // step s, `bu`/`sw` the weight operands of step s, `a`/`b` the packed data of step s+1
-    // (loaded two steps ago).  During the step the data of step s+1 is expanded (activations
-    // into the other LDS buffer, weights in registers) in the shadow of MFMAs already in
-    // flight, and the loads for step s+3 are issued into `a`/`b`.
-    auto do_step = [&](int s, AStage& a, BStage& b, SStage& sc) {
+    // One step = one weight group.  On entry: LDS buffer s&1 holds the activation operands of step s, `bc` the
+    // weight operands and scales of step s, `a` the activation codes of step s+1 on their way to LDS.  During
+    // the step `a` goes to the other LDS buffer and is reloaded (two steps ahead with 64-deep groups), and the
+    // weight set `bl` is requested: the set that step s-1 read (three rotating sets), or `bc` itself after this
+    // step's last MFMA has been issued (two sets).
+    auto do_step = [&](int s, AStage& a, BStage& bc, BStage& bl, SStage& sc) {
         const int buf = s & 1;
-        {
-            auto lds_a = [&](int rbi, int cc) -> v8i {
-                const uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wm * NRB + rbi) * 2048) + lane16;
-                const v4i lo = *(const v4i*)(base);
-                const v4i hi = *(const v4i*)(base + 1024);
-                return v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-            };
-            auto tile_mfma = [&](const v8i (&af)[GC], int cbi) -> v16f {
-                v16f d = {0};
+        auto lds_a = [&](int rbi, int cc) -> v8i {
+            const uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wm * NRB + rbi) * F6_CHUNK);
+            return op8(op6(*(const v4i*)(base + lane16), *(const v2i*)(base + lane8)));
+        };
+        auto tile_mfma = [&](const v8i (&af)[GC], int cbi) -> v16f {
+            v16f d = {0};
 #pragma unroll
-                for (int cc = 0; cc < GC; ++cc)
-                    d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(af[cc], bu[cc][cbi], d, 0, 0, 0, 0, 0, 0);
-                return d;
-            };
-            // operand of the current row block; double-buffered unless registers are scarce (the next block's
-            // read is issued after the last MFMA that uses the current one, so one buffer is enough)
-            constexpr int AFB = GA ? 1 : 2;
-            v8i af[AFB][GC];
-            v16f dd[2];
-            const float swc[2] = {sw[0], sw[1]};
+            for (int cc = 0; cc < GC; ++cc)
+                d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(af[cc], op8(bc.v[cc][cbi]), d, 2, 2, 0, 0, 0, 0);
+            return d;
+        };
+        // operand of the current row block; double-buffered unless registers are scarce (the next block's
+        // read is issued after the last MFMA that uses the current one, so one buffer is enough)
+        constexpr int AFB = GA ? 1 : 2;
+        v8i af[AFB][GC];
+        v16f dd[2];
+        float swc[2];
+        if constexpr (GA) {  // FP16 bits in the lanes of K half 0, zero in the others (they hold k = 8..15 of the scale MFMA)
 #pragma unroll
-            for (int cc = 0; cc < GC; ++cc) af[0][cc] = lds_a(0, cc);
-            dd[0] = tile_mfma(af[0], 0);
-            // software pipeline over the 8 MFMA tiles: the matrix core works on tile j+1 while
-            // the vector ALU folds tile j into the running sums
+            for (int cbi = 0; cbi < 2; ++cbi)
+                asm volatile("v_cndmask_b32 %0, %1, 0, %2" : "=v"(swc[cbi]) : "v"(bc.sw[cbi]), "s"(half_mask));
+        } else {
+            swc[0] = bc.sw[0];
+            swc[1] = bc.sw[1];
+        }
+        if constexpr (BSETS == 3) load_b(bl, s + 2);
 #pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                const int rbi = j >> 1, cbi = j & 1;
-                v16f P;
-                if constexpr (GA) {  // scale products of this tile; issued ahead of the next main MFMA
-                    // B operand: the channel scale at the k of this row block, zeros elsewhere; kept in one
-                    // register set across tiles and steps, so a tile costs one or two moves
-                    if (cbi == 0) bsel[(rbi + NRB - 1) % NRB] = 0;
-                    bsel[rbi] = __float_as_int(swc[cbi]);
-                    asm volatile("" : "+v"(bsel));  // opaque: keeps the set in place instead of rebuilding it per tile
-                    P = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, sc.sx), __builtin_bit_cast(v8h, bsel),
-                                                               v16f{0}, 0, 0, 0);
-                }
-                if (j + 1 < NT) {
-                    const int nrbi = (j + 1) >> 1, ncbi = (j + 1) & 1;
-                    dd[(j + 1) & 1] = tile_mfma(af[nrbi % AFB], ncbi);
-                }
-                if (cbi == 0 && rbi + 1 < NRB) {  // operand of the next row block, one tile ahead
+        for (int cc = 0; cc < GC; ++cc) af[0][cc] = lds_a(0, cc);
+        dd[0] = tile_mfma(af[0], 0);
+        // software pipeline over the 8 MFMA tiles: the matrix core works on tile j+1 while
+        // the vector ALU folds tile j into the running sums
 #pragma unroll
-                    for (int cc = 0; cc < GC; ++cc) af[(rbi + 1) % AFB][cc] = lds_a(rbi + 1, cc);
-                }
-                if (j == 0) {  // fills the pipeline start-up bubble
-                    store_a(a, buf ^ 1);
-                    load_a(a, s + 1 + STAGES);
-                }
-                if (j == NT - 1) {  // the last MFMA of the step is in flight: bu is free
-                    expand_b(b);
-                    load_b(b, s + 1 + STAGES);
-                    load_s(sc, s + 1);  // ... and so is this step's scale set
-                }
-                __builtin_amdgcn_sched_barrier(0);
+        for (int j = 0; j < NT; ++j) {
+            const int rbi = j >> 1, cbi = j & 1;
+            v16f P;
+            if constexpr (GA) {  // scale products of this tile; issued ahead of the next main MFMA
+                // B operand: the channel scale at the k of this row block, zeros elsewhere; kept in one
+                // register set across tiles and steps, so a tile costs one or two moves
+                if (cbi == 0) bsel[(rbi + NRB - 1) % NRB] = 0;
+                bsel[rbi] = __float_as_int(swc[cbi]);
+                asm volatile("" : "+v"(bsel));  // opaque: keeps the set in place instead of rebuilding it per tile
+                P = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, sc.sx), __builtin_bit_cast(v8h, bsel),
+                                                           v16f{0}, 0, 0, 0);
+            }
+            if (j + 1 < NT) {
+                const int nrbi = (j + 1) >> 1, ncbi = (j + 1) & 1;
+                dd[(j + 1) & 1] = tile_mfma(af[nrbi % AFB], ncbi);
+            }
+            if (cbi == 0 && rbi + 1 < NRB) {  // operand of the next row block, one tile ahead
 #pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    t[rbi][cbi][i] = __builtin_fmaf(dd[j & 1][i], GA ? P[i] : swc[cbi], t[rbi][cbi][i]);
-                if (DBG) {
-                    if (p.dbg_acc && active) {
+                for (int cc = 0; cc < GC; ++cc) af[(rbi + 1) % AFB][cc] = lds_a(rbi + 1, cc);
+            }
+            if (j == 0) {  // fills the pipeline start-up bubble
+                store_a(a, buf ^ 1);
+                load_a(a, s + 1 + ASETS);
+            }
+            if (j == NT - 1) {  // the last MFMA of the step is in flight
+                if constexpr (BSETS == 2) load_b(bl, s + 2);  // (bl is bc: its operands have been read)
+                load_s(sc, s + 1);  // ... and so has this step's scale set
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const int row = (rbw + rbi) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-                            const int col = (cb0 + cbi) * 32 + l32;
-                            if (row < p.M)
-                                p.dbg_acc[((size_t)row * p.N + col) * G + s] = (int)(dd[j & 1][i] * 262144.0f);
-                        }
+            for (int i = 0; i < 16; ++i)
+                t[rbi][cbi][i] = __builtin_fmaf(dd[j & 1][i], GA ? P[i] : swc[cbi], t[rbi][cbi][i]);
+            if (DBG) {
+                if (p.dbg_acc && active) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int row = (rbw + rbi) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+                        const int col = (cb0 + cbi) * 32 + l32;
+                        if (row < p.M)
+                            p.dbg_acc[((size_t)row * p.N + col) * G + s] = (int)(dd[j & 1][i] * 64.0f);
                     }
                 }
-                __builtin_amdgcn_sched_barrier(0);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
     };
-    // Two register sets (loads two steps ahead) for 64-deep groups; for 128-deep groups a step
-    // is twice as long and one set (loads one step ahead) hides the latency with fewer registers.
-    if constexpr (STAGES == 2) {
+
+    // Every wavefront runs the same branch-free loop; one without valid output (past the
+    // last column or row block of a partial tile) works on clamped operands, stores nothing.
+    SStage s0;
+    if constexpr (BSETS == 3) {
         AStage a0, a1;
-        BStage b0, b1;
-        SStage s0;
+        BStage b0, b1, b2;
         load_a(a0, 0);
         load_b(b0, 0);
+        load_a(a1, 1);   // (goes to LDS during step 0)
+        load_b(b1, 1);
         store_a(a0, 0);
-        expand_b(b0);
-        // issue order = the loop's steady-state order (the wait counts are derived from it)
-        __builtin_amdgcn_sched_barrier(0);
-        load_a(a0, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        load_b(b0, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        load_a(a1, 2);
-        __builtin_amdgcn_sched_barrier(0);
-        load_b(b1, 2);
-        __builtin_amdgcn_sched_barrier(0);
+        load_a(a0, 2);   // (goes to LDS during step 1)
         __syncthreads();
         load_s(s0, 0);
-        // Every wavefront runs the same branch-free loop; one without valid output (past the
-        // last column or row block of a partial tile) works on clamped operands, stores nothing.
-        int s = 0;
-        for (; s + 1 < G; s += 2) {
-            do_step(s, a0, b0, s0);
-            do_step(s + 1, a1, b1, s0);
+        // step s reads weight set s % 3 and requests set (s + 2) % 3; activation set (s + 1) % 2 goes to LDS
+        for (int s = 0; s < G; s += 6) {
+            do_step(s, a1, b0, b2, s0);
+            if (s + 1 >= G) break;
+            do_step(s + 1, a0, b1, b0, s0);
+            if (s + 2 >= G) break;
+            do_step(s + 2, a1, b2, b1, s0);
+            if (s + 3 >= G) break;
+            do_step(s + 3, a0, b0, b2, s0);
+            if (s + 4 >= G) break;
+            do_step(s + 4, a1, b1, b0, s0);
+            if (s + 5 >= G) break;
+            do_step(s + 5, a0, b2, b1, s0);
         }
-        if (s < G) do_step(s, a0, b0, s0);
-    } else {
-        AStage a0;
-        BStage b0;
-        SStage s0;  // (unused: 128-deep groups have no block-scaled variant)
+    } else if constexpr (ASETS == 2) {  // SINT4 blocks: two weight sets
+        AStage a0, a1;
+        BStage b0, b1;
         load_a(a0, 0);
         load_b(b0, 0);
+        load_a(a1, 1);
+        load_b(b1, 1);
         store_a(a0, 0);
-        expand_b(b0);
-        __builtin_amdgcn_sched_barrier(0);
-        load_a(a0, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        load_b(b0, 1);
-        __builtin_amdgcn_sched_barrier(0);
+        load_a(a0, 2);
         __syncthreads();
-        for (int s = 0; s < G; ++s) do_step(s, a0, b0, s0);
+        load_s(s0, 0);
+        for (int s = 0; s < G; s += 2) {
+            do_step(s, a1, b0, b0, s0);
+            if (s + 1 >= G) break;
+            do_step(s + 1, a0, b1, b1, s0);
+        }
+    } else {  // 128-deep groups
+        AStage a0;
+        BStage b0, b1;
+        load_a(a0, 0);
+        load_b(b0, 0);
+        load_b(b1, 1);
+        store_a(a0, 0);
+        load_a(a0, 1);
+        __syncthreads();
+        for (int s = 0; s < G; s += 2) {
+            do_step(s, a0, b0, b0, s0);
+            if (s + 1 >= G) break;
+            do_step(s + 1, a0, b1, b1, s0);
+        }
     }
 
     // ---- epilogue: rank-r expansion, scales, sum, bf16 -------------------------------------
@@ -427,8 +408,8 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const float ybr = __fmul_rn(__fmul_rn((float)a2[cbi][i], stv[i >> 2][i & 3]), slv[cbi]);
-                // SINT4 blocks: t carries the factor 2^-18 of the subnormal codes; scaling it back is exact
-                y[cbi][i] = GA ? __builtin_fmaf(t[rbi][cbi][i], 262144.0f, ybr)
+                // SINT4 blocks: t carries the factor 2^-6 of the code fields; scaling it back is exact
+                y[cbi][i] = GA ? __builtin_fmaf(t[rbi][cbi][i], 64.0f, ybr)
                                : __builtin_fmaf(sxv[i >> 2][i & 3], t[rbi][cbi][i], ybr);
             }
         if (rbi + 1 < NRB) load_scales(rbi + 1);
@@ -523,15 +504,15 @@ static hipError_t launch_cfg(const FwdParams& p0, hipStream_t s)
     p.tilesN = (p.N + WN * 64 - 1) / (WN * 64);
     const int tiles = p.tilesM * p.tilesN;
     const int slots = workgroup_slots() & ~7;
-    // Full rounds of the grid use full tiles.  A half tile costs about 2/3 of a full one (the weight
-    // operands are expanded per wavefront either way), so splitting the remainder pays only while
+    // Full rounds of the grid use full tiles.  A half tile costs more than half of a full one (each wavefront
+    // reads its weight operands either way), so splitting the remainder pays only while
     // the halves still fit one per compute unit: measured +5 % on a 1152 -> 4608 layer (2.25 rounds),
     // nothing at 1.75 rounds, a loss at 0.6 rounds.
     int n_full = (tiles / slots) * slots;
     if (4 * (tiles - n_full) > slots) n_full = tiles;
     p.n_full = n_full;
     p.split_last = (p.N & 255) == 128;
-    p.panel = panel_width(p.tilesN, p.C64);
+    p.panel = panel_width(p.tilesN, p.C64, 48);
     dim3 grid((unsigned)(n_full + 2 * (tiles - n_full))), block(NW * 64);
     hipLaunchKernelGGL((fwd_int_kernel<GC, NK, DBG, GA>), grid, block, 0, s, p);
     return hipGetLastError();

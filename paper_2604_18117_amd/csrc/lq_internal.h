@@ -13,21 +13,28 @@ namespace lq {
 // ---------------------------------------------------------------------------------------
 // Device data layout (INT family).  All sections start 256-byte aligned.
 //
-// 4-bit codes are stored sign-magnitude, 8 codes c0..c7 per dword, such that two cheap
-// bit operations turn a dword into two dwords of FP8-E4M3 *subnormal* bytes  s0000mmm
-// (value +-m * 2^-9, exact for |m| <= 7):
+// The 4-bit main codes (weights pq, activations xq) are stored as 6-bit sign-magnitude fields
+// s00mmm, which are the E2M3 (FP6) bit patterns of +-m/8: the matrix core multiplies them in its
+// FP6 mode with no expansion step in the forward kernel (every product and every partial sum is an
+// integer multiple of 2^-6, exact in the fp32 accumulator).  A lane's v_mfma_f32_32x32x64_f8f6f4
+// FP6 operand is the 32 codes k = 32*half .. 32*half+31 of one row as 192 contiguous bits (code i at
+// bits 6i .. 6i+5), six dwords.
+//
+// "Fragment order" for a 64-deep K chunk and a block of 32 rows (tokens or out-channels), 1536 bytes:
+//     bytes    0..1023 : [lane = row%32 + 32*half][16 bytes = dwords 0..3 of the lane's operand]
+//     bytes 1024..1535 : [lane][8 bytes = dwords 4..5]
+// chunks ordered [block][chunk]; a lane reads its operand as one aligned 16-byte and one aligned
+// 8-byte load, each contiguous over the wavefront.
+//
+// The MXI family keeps 4-bit sign-magnitude nibbles, 8 codes c0..c7 per dword, such that two bit
+// operations turn a dword into two dwords of FP8-E4M3 *subnormal* bytes  s0000mmm (+-m * 2^-9):
 //     lo = p & 0x87878787          -> bytes of c0..c3
 //     hi = rotl(p, 4) & 0x87878787 -> bytes of c4..c7
 // i.e. for i in 0..3:  c_i   : sign at bit 8i+7, magnitude at bits 8i+2..8i
 //                      c_4+i : sign at bit 8i+3, magnitude at bits 8j+6..8j+4, j = (i-1)&3
 //
-// "Fragment order" for a 64-deep K chunk and a block of 32 rows (tokens or out-channels):
-//     [block][chunk][half = (k%64)/32][row % 32][16 bytes = 32 codes = dwords (k%32)/8]
-// so that lane l of a wavefront reads its v_mfma_f32_32x32x64_f8f6f4 operand (row l%32,
-// K half l/32) as one aligned 16-byte load at (block, chunk) base + 16*l.
-//
-// MX family: E2M1 codes in the same fragment order, code i of a lane's 32 in nibble i of its 16
-// bytes (the FP4 operand layout of v_mfma_scale_f32_32x32x64_f8f6f4).  E8M0 scales:
+// MX family: E2M1 codes as [block of 32 rows][64-chunk][lane = row%32 + 32*half][16 bytes], code i of a lane's
+// 32 in nibble i of its 16 bytes (the FP4 operand layout of v_mfma_scale_f32_32x32x64_f8f6f4).  E8M0 scales:
 //     [block of 32 rows][quad = chunk/4][lane = row%32 + 32*half][4 bytes = chunks 4q..4q+3]
 // so that a lane's scale operand for four consecutive chunks is one dword and the instruction's
 // op_sel picks the chunk's byte (padding bytes hold 127 = 2^0).  Branch codes are E4M3 bytes;
@@ -71,7 +78,7 @@ struct Dims {
 };
 
 struct PackedLayout {
-    size_t off_pq;   // main codes, fragment order, N*K/2 bytes
+    size_t off_pq;   // main codes, fragment order: INT family N*K*3/4 bytes (6-bit fields), MX families N*K/2
     size_t off_sw;   // INT: [G][N] fp32, pre-multiplied by 2^18 (SINT4 blocks: FP16 bits in a dword);  MX: E8M0 bytes
     size_t off_lq;   // [N][rp] int8 (zero padded) / E4M3 bytes
     size_t off_sl;   // [N] fp32
@@ -83,7 +90,7 @@ struct PackedLayout {
 
 struct ActLayout {
     int64_t Mp;      // M rounded up to 32
-    size_t off_xq;   // main codes, fragment order, Mp*K/2 bytes
+    size_t off_xq;   // main codes, fragment order: INT family Mp*K*3/4 bytes (6-bit fields), MX families Mp*K/2
     size_t off_sx;   // INT: [Mp] fp32 (SINT4 blocks: [G][Mp/128 rounded up][32][4] dwords of FP16 bits, sxg_index);  MX: E8M0 bytes
     size_t off_tq;   // [Mp][rp] int8 / E4M3
     size_t off_st;   // [Mp] fp32
@@ -180,10 +187,10 @@ hipError_t launch_rot_unpack(const Dims& d, const uint8_t* state, const lq_rot_v
 // last panel may be narrower.  The workgroups resident on an XCD at one time then share few weight column blocks: with
 // all tile columns in flight at once, the weight codes of a wide layer (7.5 MB at 2240 x 6720) do not stay in the XCD's
 // 4 MB L2 (measured: -5 % and -9 % on the 2240-wide layers, nothing on the 1152-wide ones, whose weights fit anyway).
-// Width: the 4-bit codes of a panel (256 x K/2 bytes per tile column) within about 2 MB.
-static inline int panel_width(int tilesN, int C64)
+// Width: the weight codes of a panel (256 channels x chunk_row_bytes per 64-chunk and tile column) within about 2 MB.
+static inline int panel_width(int tilesN, int C64, int chunk_row_bytes = 32)
 {
-    const int pw = (int)(((int64_t)2 << 20) / ((int64_t)256 * C64 * 32));
+    const int pw = (int)(((int64_t)2 << 20) / ((int64_t)256 * C64 * chunk_row_bytes));
     return pw < 1 ? 1 : pw > tilesN ? tilesN : pw;
 }
 
@@ -223,6 +230,31 @@ __device__ __forceinline__ int nib_get(uint32_t p, int e)
     const uint32_t b = (v >> (8 * (e & 3))) & 0xFFu;
     const int m = (int)(b & 7u);
     return (b & 0x80u) ? -m : m;
+}
+
+// ---- 6-bit main codes of the INT family (fragment order above) ----
+constexpr int F6_CHUNK = 1536;  // bytes of one (32-row block, 64-chunk)
+// byte offset, inside a chunk, of dword d (0..5) of lane `lane`'s operand
+__device__ __forceinline__ int f6_dword_offset(int lane, int d)
+{
+    return d < 4 ? lane * 16 + d * 4 : 1024 + lane * 8 + (d - 4) * 4;
+}
+__device__ __forceinline__ size_t f6_chunk_offset(int row, int k, int C64)
+{
+    return ((size_t)(row >> 5) * C64 + (k >> 6)) * F6_CHUNK;
+}
+// the 6-bit field of an integer code in [-7, 7]
+__device__ __forceinline__ uint32_t f6_field(int q) { return q < 0 ? (32u | (uint32_t)(-q)) : (uint32_t)q; }
+// code (row, k) of a section in fragment order, as a signed integer
+__device__ __forceinline__ int f6_get(const uint8_t* sec, int row, int k, int C64)
+{
+    const uint8_t* ch = sec + f6_chunk_offset(row, k, C64);
+    const int lane = (row & 31) + 32 * ((k & 63) >> 5), bit = 6 * (k & 31), d = bit >> 5, sh = bit & 31;
+    uint64_t v = *(const uint32_t*)(ch + f6_dword_offset(lane, d));
+    if (d < 5) v |= (uint64_t)(*(const uint32_t*)(ch + f6_dword_offset(lane, d + 1))) << 32;
+    const uint32_t c = (uint32_t)(v >> sh) & 63u;
+    const int m = (int)(c & 7u);
+    return (c & 32u) ? -m : m;
 }
 
 // ---- MXFP6e2 branch (E2M3 elements, blocks of 32, E8M0 scale): with 6-bit operands a lane of the scaled

@@ -41,13 +41,6 @@ __device__ __forceinline__ size_t rq_offset(int j, int k, int r)
     return ((size_t)((size_t)c * (r >> 4) + (j >> 4)) * 64 + (j & 15) + 16 * kq) * 16 + (k & 15);
 }
 
-// byte offset of the dword holding main code (n,k) in fragment order
-__device__ __forceinline__ size_t frag_offset(int row, int k, int C64)
-{
-    const int blk = row >> 5, c = k >> 6, half = (k & 63) >> 5, d = (k & 31) >> 3;
-    return ((size_t)((size_t)blk * C64 + c) * 64 + (row & 31) + 32 * half) * 16 + d * 4;
-}
-
 // ---- Q2(R): one workgroup per row j ------------------------------------------------------
 __global__ __launch_bounds__(256) void pack_r_kernel(const float* R, int K, int r, float qmax,
                                                      int8_t* rq, float* sr)
@@ -122,17 +115,25 @@ __global__ __launch_bounds__(256) void pack_p_kernel(const float* W, const float
         if (lane == 0) ((uint32_t*)swT)[(size_t)gi * N + n] = bits;
     } else {
         scale_pair(a, 7.0f, &s, &inv);
-        if (lane == 0) swT[(size_t)gi * N + n] = ldexpf(s, 18);
+        if (lane == 0) swT[(size_t)gi * N + n] = ldexpf(s, 6);
     }
 #pragma unroll
     for (int cc = 0; cc < GC; ++cc) {
         const int k = (gi * GC + cc) * 64 + lane;
         const int q = quant_code(P[cc], inv, 7.0f);
-        uint32_t w = nib_put(lane & 7, q < 0 ? 1u : 0u, (uint32_t)(q < 0 ? -q : q));
-        w |= __shfl_xor(w, 1, 64);
-        w |= __shfl_xor(w, 2, 64);
-        w |= __shfl_xor(w, 4, 64);
-        if ((lane & 7) == 0) *(uint32_t*)(pq + frag_offset(n, k, C64)) = w;
+        // 6-bit fields: lane (half = lane / 32, i = lane % 32) owns bits 6i .. 6i+5 of its half's 192-bit operand;
+        // the six dwords of a half are OR-reduced over its 32 lanes
+        const int i = lane & 31, bit = 6 * i;
+        const uint64_t v = (uint64_t)f6_field(q) << (bit & 31);
+        uint32_t mine = 0u;
+#pragma unroll
+        for (int dd = 0; dd < 6; ++dd) {
+            uint32_t w = (bit >> 5) == dd ? (uint32_t)v : (bit >> 5) + 1 == dd ? (uint32_t)(v >> 32) : 0u;
+#pragma unroll
+            for (int o = 16; o >= 1; o >>= 1) w |= __shfl_xor(w, o, 64);
+            if (i == dd) mine = w;
+        }
+        if (i < 6) *(uint32_t*)(pq + f6_chunk_offset(n, k, C64) + f6_dword_offset((n & 31) + 32 * (lane >> 5), i)) = mine;
     }
 }
 
@@ -195,14 +196,13 @@ __global__ __launch_bounds__(256) void unpack_w_kernel(const uint8_t* packed, Pa
     if (idx < (size_t)N * K) {
         const int n = (int)(idx / K), k = (int)(idx % K);
         if (out.pq) {
-            const uint32_t w = *(const uint32_t*)(packed + pl.off_pq + frag_offset(n, k, C64));
-            out.pq[idx] = (int8_t)nib_get(w, k & 7);
+            out.pq[idx] = (int8_t)f6_get(packed + pl.off_pq, n, k, C64);
         }
     }
     if (idx < (size_t)N * G && out.sw) {
         const int n = (int)(idx / G), gi = (int)(idx % G);
         out.sw[idx] = ga ? f16_bits_value(((const uint32_t*)(packed + pl.off_sw))[(size_t)gi * N + n])
-                         : ldexpf(((const float*)(packed + pl.off_sw))[(size_t)gi * N + n], -18);
+                         : ldexpf(((const float*)(packed + pl.off_sw))[(size_t)gi * N + n], -6);
     }
     if (idx < (size_t)N * r && out.lq) {
         const int n = (int)(idx / r), j = (int)(idx % r);
@@ -233,8 +233,7 @@ __global__ __launch_bounds__(256) void unpack_a_kernel(const uint8_t* act, ActLa
     const int C64 = K >> 6;
     if (idx < (size_t)M * K && out.xq) {
         const int m = (int)(idx / K), k = (int)(idx % K);
-        const uint32_t w = *(const uint32_t*)(act + al.off_xq + frag_offset(m, k, C64));
-        out.xq[idx] = (int8_t)nib_get(w, k & 7);
+        out.xq[idx] = (int8_t)f6_get(act + al.off_xq, m, k, C64);
     }
     if (ga) {
         if (idx < (size_t)M * C64 && out.sx) {

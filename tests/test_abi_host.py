@@ -34,11 +34,11 @@ def test_status_strings(lq):
 def test_sizes_follow_the_layout(lq):
     cfg = lq.make_config(3456, 1152, 32, "int", 64, 8, 8)
     pb = lq.lq_packed_sizes(cfg)
-    # codes N*K/2 + scales N*G*4 + lq N*32 + sl N*4 + rq r*K + sr r*4, each section 256-aligned
-    parts = [3456 * 1152 // 2, 3456 * 18 * 4, 3456 * 32, 3456 * 4, 32 * 1152, 32 * 4]
+    # codes N*K*6/8 (4-bit codes in 6-bit fields) + scales N*G*4 + lq N*32 + sl N*4 + rq r*K + sr r*4, each section 256-aligned
+    parts = [3456 * 1152 * 3 // 4, 3456 * 18 * 4, 3456 * 32, 3456 * 4, 32 * 1152, 32 * 4]
     assert pb == sum((x + 255) // 256 * 256 for x in parts)
     ab = lq.lq_act_sizes(cfg, 8192)
-    parts = [8192 * 1152 // 2, 8192 * 4, 8192 * 32, 8192 * 4]
+    parts = [8192 * 1152 * 3 // 4, 8192 * 4, 8192 * 32, 8192 * 4]
     assert ab == sum((x + 255) // 256 * 256 for x in parts)
     # M is padded to a multiple of 32 rows
     assert lq.lq_act_sizes(cfg, 1) == lq.lq_act_sizes(cfg, 32) < lq.lq_act_sizes(cfg, 33)

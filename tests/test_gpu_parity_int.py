@@ -108,6 +108,31 @@ def test_degenerate_inputs(oracle):
     _compare_all(oracle, layer, np.zeros_like(X), W, L, R)
 
 
+@pytest.mark.parametrize("xd,a_group", [("bf16", 0), ("f32", 0), ("bf16", 64), ("f32", 64)])
+def test_main_codes_on_exact_ties_and_tiny_values(oracle, xd, a_group):
+    """Rows whose scaled values x * (7 / amax) are exact half-integers (ties go to even), whole integers, values just
+    below and above a tie, values far below half a step (codes +0 / -0), and the extremes +-amax: the main codes come
+    from the hardware FP6 converter and must equal the oracle's nearest-even integers."""
+    layer = wl.Layer("t", 96, 256, 64, 16, "int", 64, 8, 8, xd, seed=11, a_group=a_group)
+    X, W, L, R = wl.make_inputs(layer)
+    rng = np.random.default_rng(4)
+    halves = (rng.integers(-14, 15, size=X.shape) * 0.5).astype(np.float32)          # multiples of 1/2 in [-7, 7]
+    for m in range(X.shape[0]):
+        scale = np.float32(2.0 ** (m % 9 - 4))
+        row = halves[m] * scale
+        if m % 3 == 1:   # one ulp (of the input type) to either side of the ties
+            eps = np.float32(2.0 ** -7 if xd == "bf16" else 2.0 ** -22)
+            row = row * (1 + eps * rng.choice([-1.0, 1.0], size=row.shape).astype(np.float32))
+        if m % 3 == 2:   # tiny magnitudes of both signs next to the extremes
+            row = (rng.standard_normal(row.shape) * 1e-6).astype(np.float32) * scale
+        for b in range(0, X.shape[1], 64):   # every block of 64 holds +-7 * scale, so block scales equal the row scale
+            row[b] = 7 * scale
+            row[b + 1] = -7 * scale
+        X[m] = row
+    X = wl.round_to_bf16(X) if xd == "bf16" else X
+    _compare_all(oracle, layer, X, W, L, R)
+
+
 def test_rank0_equals_plain_w4a4_on_gpu(oracle):
     layer = wl.Layer("t", 96, 256, 128, 32, "int", 64, 8, 8, "bf16", seed=9)
     X, W, L, R = wl.make_inputs(layer)
