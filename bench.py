@@ -4,9 +4,11 @@ linear layer with a quantized low-rank branch, on synthetic DiT-shaped layers, o
 
 A "step" is one pass of the whole per-call path (lq_quantize_act + lq_linear_lowrank_fwd)
 over one batch of M tokens already resident in HBM; weight packing is offline and untimed.
-Prints ONE JSON line: metric, value (whole-path TOPS), ms_per_step, the workload, a `roofline` object for
-the forward kernel (bound, achieved, peak, fraction, measured HBM traffic), an `act_kernel` object and a
-`cpu_baseline` object (the CPU oracle timed on the host cores on the same workload).
+Prints ONE JSON line.  Its top-level fields describe the headline workload (the largest layer, the 2240 -> 11200
+expansion on 8192 tokens): metric, value (whole-path TOPS), ms_per_step, a `roofline` object for the forward kernel
+(bound, achieved, peak, fraction, measured HBM traffic), an `act_kernel` object and a `cpu_baseline` object (the CPU
+oracle timed on the host cores on a row sample of the same workload).  `layers` holds the same per-kernel figures for
+every benchmark layer (the INT4 layers of both transformer shapes and the seven MX-format layers of one block).
 """
 import argparse
 import json
@@ -19,11 +21,14 @@ sys.path.insert(0, ROOT)
 
 # MI355X dense matrix peaks: FP8 / INT8 (the INT4 main product runs on the FP8 pipe) and FP4 (MXFP4)
 PEAK_MFMA_TFLOPS = {"int": 5033.0, "mx": 10066.0, "mxb": 10066.0, "mxi": 5033.0}
-# HBM bytes per forward launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/fwd_int_kernel_c2_qkv.md,
-# profiles/mx_fwd_kernel_c5_qkv.md),
-# each scaled by the factor a plain copy of known size gives (2.0 for FETCH_SIZE, 1.0 for WRITE_SIZE).
-MEASURED_TRAFFIC_BYTES = {"c2_qkv": 22004.6 * 1024 * 2.0 + 55296.0 * 1024 * 1.0,
-                          "c5_qkv": 42285.7 * 1024 * 2.0 + 110592.0 * 1024 * 1.0}
+# HBM bytes per forward launch from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch; the
+# commands and the raw figures are in profiles/hbm_traffic_forward_kernels.md), each scaled by the factor a plain copy
+# of known size gives for the same counter.  A workload without an entry reports "traffic": null.
+TRAFFIC_KIB = {}   # name -> (FETCH_SIZE KiB, WRITE_SIZE KiB) per forward dispatch
+TRAFFIC_SCALE = (2.0, 1.0)   # copy-kernel calibration of FETCH_SIZE and WRITE_SIZE
+HEADLINE = "c4_expand"
+BENCH_LAYERS = ["c2_qkv", "c3_fc1", "c3_fc2", "c4_qkv", "c4_expand", "c5_qkv", "c5_attn_out", "c5_cross_q", "c5_cross_kv",
+                "c5_cross_out", "c5_fc1", "c5_fc2"]
 
 
 def layer_ops(l):
@@ -123,52 +128,8 @@ def bench_rot(args, layer, np, torch, lq, wl):
     print(json.dumps(out))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--ramp-seconds", type=float, default=0.5,
-                    help="untimed run of the same step loop before the warm-up steps: the GPU leaves its idle "
-                         "clock state only after some 0.2 s of load (a cold 10 ms loop runs ~15 %% slower)")
-    ap.add_argument("--workload", default="c2_qkv", help="layer name from workloads.LAYERS")
-    ap.add_argument("--oracle-seconds", type=float, default=15.0, help="CPU budget of the oracle leg (0 = skip)")
-    ap.add_argument("--sets", type=int, default=4, help="distinct buffer sets rotated through")
-    ap.add_argument("--calib", action="store_true",
-                    help="time the data-free calibration step (lq_calib_step) on the workload's weight shape instead "
-                         "of the per-call path; prints its own JSON line")
-    ap.add_argument("--rot", action="store_true",
-                    help="time the rotation search step (lq_rot_step) on the workload's factor shapes; prints its own JSON line")
-    ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
-                    help="only run a plain device-to-device copy of BYTES (calibrates the HBM byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build is single-GPU (token rows are independent through the whole path, so it "
-              "would shard over tokens with no collective); run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
-    import torch
-    from paper_2604_18117_amd import binding as lq
-    from paper_2604_18117_amd import workloads as wl
-    to_dev_x = wl.to_dev_x
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    if args.copy_probe:
-        src = torch.empty(args.copy_probe, dtype=torch.uint8, device="cuda").random_(0, 255)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_probe_bytes": args.copy_probe, "copies": 3}))
-        return
-    layer = wl.LAYERS[args.workload]
-    if args.calib:
-        return bench_calib(args, layer, np, torch, lq, wl)
-    if args.rot:
-        return bench_rot(args, layer, np, torch, lq, wl)
+def measure_layer(args, layer, np, torch, lq, wl, keep=False):
+    """All timings of one layer.  Returns (result dict, context for the oracle leg or None)."""
     X, W, L, R = wl.make_inputs(layer)
     cfg = lq.config_for_layer(layer)
     M = layer.M
@@ -179,7 +140,7 @@ def main():
     Xs, acts, Ys = [], [], []
     for i in range(nsets):
         Xi = X if i == 0 else X[rng.permutation(M)]      # same distribution, different bytes
-        Xs.append(to_dev_x(Xi, layer.x_dtype))
+        Xs.append(wl.to_dev_x(Xi, layer.x_dtype))
         acts.append(torch.empty(lq.lq_act_sizes(cfg, M), dtype=torch.uint8, device="cuda"))
         Ys.append(torch.empty((M, layer.N), dtype=torch.bfloat16, device="cuda"))
 
@@ -190,7 +151,7 @@ def main():
 
     t_ramp = time.perf_counter()
     while time.perf_counter() - t_ramp < args.ramp_seconds:
-        for i in range(200):
+        for i in range(100):
             step(i)
         torch.cuda.synchronize()
     for i in range(args.warmup):
@@ -207,28 +168,27 @@ def main():
     t1 = time.perf_counter()
     ms_step = (t1 - t0) * 1e3 / K
 
-    # ---- per-kernel durations: the same K steps again with HIP events around each launch (on the
-    # stream the kernels run on).  Events between launches drain the queue, so this loop is slower
-    # than the timed region above and is not used for `value`.  An event pair also measures the
-    # dispatch latency of the launch it brackets; an empty pair, timed in the same loop, gives that
-    # overhead, which is subtracted.
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
+    # ---- per-kernel durations: HIP events (on the stream the kernels run on) around a run of KK launches of ONE
+    # kernel back to back; the mean includes the gap between two dependent dispatches, so it can only overstate a
+    # kernel's duration (rocprofv3's kernel-trace average of the same launches is the lower figure, profiles/).
+    KK = max(K, args.kernel_iters)
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    for i in range(nsets):
+        lq.lq_quantize_act(cfg, packed, Xs[i], act=acts[i])
     torch.cuda.synchronize()
-    for i in range(K):
-        k = i % nsets
-        ev[i][0].record()
-        lq.lq_quantize_act(cfg, packed, Xs[k], act=acts[k])
-        ev[i][1].record()
-        lq.lq_linear_lowrank_fwd(cfg, packed, acts[k], M, Y=Ys[k])
-        ev[i][2].record()
-        ev[i][3].record()
-        ev[i][4].record()
+    e[0].record()
+    for i in range(KK):
+        lq.lq_linear_lowrank_fwd(cfg, packed, acts[i % nsets], M, Y=Ys[i % nsets])
+    e[1].record()
     torch.cuda.synchronize()
-    empty_ms = float(np.median([e[3].elapsed_time(e[4]) for e in ev]))
-    act_raw_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
-    fwd_raw_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
-    act_ms = act_raw_ms - empty_ms
-    fwd_ms = fwd_raw_ms - empty_ms
+    e[2].record()
+    for i in range(KK):
+        lq.lq_quantize_act(cfg, packed, Xs[i % nsets], act=acts[i % nsets])
+    e[3].record()
+    torch.cuda.synchronize()
+    fwd_ms = e[0].elapsed_time(e[1]) / KK
+    act_ms = e[2].elapsed_time(e[3]) / KK
+
     ops = layer_ops(layer)
     fwd_ops = 2.0 * layer.M * layer.N * (layer.K + layer.r)
     tops = ops / (ms_step * 1e-3) / 1e12
@@ -257,13 +217,10 @@ def main():
     t_mfma = fwd_ops / (peak * 1e12)
     t_hbm = fwd_bytes / 8.0e12
     fwd_gbs = fwd_bytes / (fwd_ms * 1e-3) / 1e9
-    out = {
-        "metric": "fused W4A4+low-rank linear TOPS and % of MFMA roofline on MI355X",
-        "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": K, "warmup": args.warmup,
-        "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None,
+    kib = TRAFFIC_KIB.get(layer.name)
+    res = {
+        "value": round(tops, 2), "ms_per_step": round(ms_step, 5),
         "dtype": "mxint4" if mxi else "mxfp4" if mx else "int4",
-        "data": "synthetic",
         "config": {"workload": layer.name, "M": layer.M, "K": layer.K, "N": layer.N, "rank": layer.r,
                    "main": "W4A4 MXINT4 block 32" if mxi else "W4A4 MXFP4 block 32" if mx else
                            "W4A4 SINT4 blocks of 64, FP16 scales" if layer.a_group == 64 else f"W4A4 INT4 g{layer.g}",
@@ -272,7 +229,7 @@ def main():
                    "arithmetic": ("int4 codes as FP8 subnormals with E8M0 block scales on the scaled FP8 MFMA, "
                                   "bf16-exact MXINT branch, fp32 accumulate" if mxi else
                                   "e2m1 x e8m0 on the scaled FP4 MFMA, e4m3 branch, fp32 accumulate" if mx else
-                                  "int4 codes (exact, on the FP8 MFMA pipe), int8 branch, fp32 dequantisation")},
+                                  "int4 codes (exact; 6-bit E2M3 fields on the f8f6f4 MFMA), int8 branch, fp32 dequantisation")},
         # the bound is whichever of ops/peak and bytes/bandwidth is the longer time for this layer (the
         # K = 1152 MXFP4 layers write 2 bytes per 2*1152 ops at the FP4 rate: below the ridge)
         "roofline": ({"bound": "mfma", "achieved": round(fwd_tops, 2), "peak": peak, "unit": "TFLOP/s",
@@ -282,52 +239,146 @@ def main():
         "act_kernel": {"bound": "hbm", "avg_kernel_ms": round(act_ms, 5), "achieved": round(act_gbs, 1),
                        "peak": 8000.0, "unit": "GB/s", "frac": round(act_gbs / 8000.0, 4)},
     }
-
-    out["roofline"].update({
-        "kernel": "mxi_fwd_kernel" if mxi else "mx_fwd_kernel" if mx else "fwd_int_kernel", "traffic": MEASURED_TRAFFIC_BYTES.get(layer.name),
+    res["roofline"].update({
+        "kernel": "mxi_fwd_kernel" if mxi else "mx_fwd_kernel" if mx else "fwd_int_kernel",
+        "traffic": None if kib is None else (kib[0] * TRAFFIC_SCALE[0] + kib[1] * TRAFFIC_SCALE[1]) * 1024.0,
         "algorithmic_ops": fwd_ops, "algorithmic_bytes": fwd_bytes, "avg_kernel_ms": round(fwd_ms, 5),
-        "event_pair_ms": round(fwd_raw_ms, 5), "empty_event_pair_ms": round(empty_ms, 5),
+        "kernel_timing": f"HIP events around {KK} back-to-back launches, mean (includes the inter-dispatch gap)",
         "frac_of_mfma_peak": round(fwd_tops / peak, 4), "frac_of_hbm_peak": round(fwd_gbs / 8000.0, 4)})
+    if kib is None:
+        res["roofline"]["traffic_note"] = "no counter run recorded for this workload"
+    if not mx:
+        # the INT4 product is priced against the INT8 / FP8 dense peak (there is no 4-bit integer matrix instruction); the
+        # instruction that multiplies the 6-bit code fields has the FP6 peak, quoted beside it
+        res["roofline"]["frac_of_fp6_instruction_peak"] = round(fwd_tops / 10066.0, 4)
+    ctx = (X, W, L, R, cfg, packed, Xs, acts, Ys, ops) if keep else None
+    return res, ctx
 
-    # ---- CPU oracle leg (reported baseline only): bounded row sample of the same workload -----
-    if args.oracle_seconds > 0:
-        from oracle import lq_ref
-        if mxi:
-            pk = lq_ref.pack_mxi(W, L, R, layer.br_w_bits)
-            run_rows = lambda n_rows: lq_ref.fwd_mxi(pk, lq_ref.quantize_act_mxi(X[:n_rows], pk))
-        elif mxb:
-            pk = lq_ref.pack_mxb(W, L, R, elem=layer.br_w_bits)
-            run_rows = lambda n_rows: lq_ref.fwd_mxb(pk, lq_ref.quantize_act_mxb(X[:n_rows], pk))
-        elif mx:
-            pk = lq_ref.pack_mx(W, L, R)
-            run_rows = lambda n_rows: lq_ref.fwd_mx(pk, lq_ref.quantize_act_mx(X[:n_rows], pk))
-        else:
-            pk = lq_ref.pack_int(W, L, R, layer.g, layer.br_w_bits, sint4_blocks=layer.a_group == 64)
-            run_rows = lambda n_rows: lq_ref.fwd_int(pk, lq_ref.quantize_act_int(X[:n_rows], pk, layer.br_a_bits))
-        probe = 16
-        t = time.perf_counter()
-        run_rows(probe)
-        dt = time.perf_counter() - t
-        rows = int(max(probe, min(M, probe * args.oracle_seconds / max(dt, 1e-6))))
-        rows = max(16, rows // 16 * 16)
-        t = time.perf_counter()
-        o = run_rows(rows)
-        dt = time.perf_counter() - t
-        cpu_tops = ops * (rows / M) / dt / 1e12
-        # parity spot check of the bench's own launch against those rows
-        bf16_to_bits = wl.bf16_to_bits
-        lq.lq_quantize_act(cfg, packed, Xs[0], act=acts[0])
-        lq.lq_linear_lowrank_fwd(cfg, packed, acts[0], M, Y=Ys[0])
+
+def oracle_leg(args, layer, ctx, np, torch, lq, wl):
+    """CPU oracle (reported baseline only): bounded row sample of the same workload."""
+    from oracle import lq_ref
+    X, W, L, R, cfg, packed, Xs, acts, Ys, ops = ctx
+    M = layer.M
+    mx = layer.family in ("mx", "mxb", "mxi")
+    if layer.family == "mxi":
+        pk = lq_ref.pack_mxi(W, L, R, layer.br_w_bits)
+        run_rows = lambda n_rows: lq_ref.fwd_mxi(pk, lq_ref.quantize_act_mxi(X[:n_rows], pk))
+    elif layer.family == "mxb":
+        pk = lq_ref.pack_mxb(W, L, R, elem=layer.br_w_bits)
+        run_rows = lambda n_rows: lq_ref.fwd_mxb(pk, lq_ref.quantize_act_mxb(X[:n_rows], pk))
+    elif mx:
+        pk = lq_ref.pack_mx(W, L, R)
+        run_rows = lambda n_rows: lq_ref.fwd_mx(pk, lq_ref.quantize_act_mx(X[:n_rows], pk))
+    else:
+        pk = lq_ref.pack_int(W, L, R, layer.g, layer.br_w_bits, sint4_blocks=layer.a_group == 64)
+        run_rows = lambda n_rows: lq_ref.fwd_int(pk, lq_ref.quantize_act_int(X[:n_rows], pk, layer.br_a_bits))
+    probe = 16
+    t = time.perf_counter()
+    run_rows(probe)
+    dt = time.perf_counter() - t
+    rows = int(max(probe, min(M, probe * args.oracle_seconds / max(dt, 1e-6))))
+    rows = max(16, rows // 16 * 16)
+    t = time.perf_counter()
+    o = run_rows(rows)
+    dt = time.perf_counter() - t
+    cpu_tops = ops * (rows / M) / dt / 1e12
+    # parity spot check of the bench's own launch against those rows
+    lq.lq_quantize_act(cfg, packed, Xs[0], act=acts[0])
+    lq.lq_linear_lowrank_fwd(cfg, packed, acts[0], M, Y=Ys[0])
+    torch.cuda.synchronize()
+    gy = wl.bf16_to_bits(Ys[0][:rows])
+    out = {"value": round(cpu_tops, 5), "unit": "TOPS", "cores": lq_ref.num_threads(),
+           "kind": "oracle", "seconds": round(dt, 2),
+           "sample": f"first {rows} of {M} token rows of {layer.name}, activation step + forward, "
+                     f"scaled linearly in M"}
+    if mx:  # fp32 accumulation order differs from the oracle's fp64: one-ulp bf16 flips at rounding boundaries
+        out["gpu_rows_bf16_flip_rate"] = float(np.mean(gy != o.Y))
+    else:
+        out["gpu_rows_bit_exact"] = bool(np.array_equal(gy, o.Y))
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--ramp-seconds", type=float, default=0.5,
+                    help="untimed run of the same step loop before the warm-up steps: the GPU leaves its idle "
+                         "clock state only after some 0.2 s of load (a cold 10 ms loop runs ~15 %% slower)")
+    ap.add_argument("--workload", default=HEADLINE, help="headline layer (name from workloads.LAYERS)")
+    ap.add_argument("--layers", default="all",
+                    help="'all' = every benchmark layer in the `layers` array, 'none' = headline only, or a comma-separated list")
+    ap.add_argument("--kernel-iters", type=int, default=200,
+                    help="launches per kernel in the per-kernel timing runs (at least --steps)")
+    ap.add_argument("--oracle-seconds", type=float, default=15.0, help="CPU budget of the oracle leg (0 = skip)")
+    ap.add_argument("--sets", type=int, default=4, help="distinct buffer sets rotated through")
+    ap.add_argument("--calib", action="store_true",
+                    help="time the data-free calibration step (lq_calib_step) on the workload's weight shape instead "
+                         "of the per-call path; prints its own JSON line")
+    ap.add_argument("--rot", action="store_true",
+                    help="time the rotation search step (lq_rot_step) on the workload's factor shapes; prints its own JSON line")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
+                    help="only run a plain device-to-device copy of BYTES (calibrates the HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (token rows are independent through the whole path, so it "
+              "would shard over tokens with no collective); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2604_18117_amd import binding as lq
+    from paper_2604_18117_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.copy_probe:
+        src = torch.empty(args.copy_probe, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        gy = bf16_to_bits(Ys[0][:rows])
-        out["cpu_baseline"] = {"value": round(cpu_tops, 5), "unit": "TOPS", "cores": lq_ref.num_threads(),
-                               "kind": "oracle", "seconds": round(dt, 2),
-                               "sample": f"first {rows} of {M} token rows, activation step + forward, "
-                                         f"scaled linearly in M"}
-        if mx:  # fp32 accumulation order differs from the oracle's fp64: one-ulp bf16 flips at rounding boundaries
-            out["cpu_baseline"]["gpu_rows_bf16_flip_rate"] = float(np.mean(gy != o.Y))
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": args.copy_probe, "copies": 3}))
+        return
+    layer = wl.LAYERS[args.workload]
+    if args.calib:
+        return bench_calib(args, layer, np, torch, lq, wl)
+    if args.rot:
+        return bench_rot(args, layer, np, torch, lq, wl)
+
+    head, ctx = measure_layer(args, layer, np, torch, lq, wl, keep=args.oracle_seconds > 0)
+    out = {
+        "metric": "fused W4A4+low-rank linear TOPS and % of MFMA roofline on MI355X",
+        "value": head["value"], "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
+        "config": head["config"], "roofline": head["roofline"], "act_kernel": head["act_kernel"],
+    }
+    if args.oracle_seconds > 0:
+        out["cpu_baseline"] = oracle_leg(args, layer, ctx, np, torch, lq, wl)
+    del ctx
+    torch.cuda.empty_cache()
+    names = [] if args.layers == "none" else BENCH_LAYERS if args.layers == "all" else args.layers.split(",")
+    layers = []
+    for name in names:
+        if name == layer.name:
+            r = head
         else:
-            out["cpu_baseline"]["gpu_rows_bit_exact"] = bool(np.array_equal(gy, o.Y))
+            r, _ = measure_layer(args, wl.LAYERS[name], np, torch, lq, wl)
+            torch.cuda.empty_cache()
+        layers.append({"workload": name, "M": r["config"]["M"], "K": r["config"]["K"], "N": r["config"]["N"],
+                       "rank": r["config"]["rank"], "main": r["config"]["main"], "branch": r["config"]["branch"],
+                       "tops": r["value"], "ms_per_step": r["ms_per_step"], "bound": r["roofline"]["bound"],
+                       "frac": r["roofline"]["frac"], "avg_kernel_ms": r["roofline"]["avg_kernel_ms"],
+                       "frac_of_mfma_peak": r["roofline"]["frac_of_mfma_peak"],
+                       "frac_of_hbm_peak": r["roofline"]["frac_of_hbm_peak"], "traffic": r["roofline"]["traffic"],
+                       "act_kernel_ms": r["act_kernel"]["avg_kernel_ms"], "act_kernel_gbs": r["act_kernel"]["achieved"],
+                       "act_kernel_frac": r["act_kernel"]["frac"]})
+    if layers:
+        out["layers"] = layers
     print(json.dumps(out))
 
 
