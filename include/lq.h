@@ -272,6 +272,20 @@ lq_status lq_rot_init(const lq_config *cfg, const float *Omega0, const float *Mo
 lq_status lq_rot_step(const lq_config *cfg, const float *L, const float *R, void *state, size_t state_bytes,
                       const lq_cayley *opt, float *loss, void *stream);
 
+/* For callers that cannot allocate or size a workspace (code under HIP graph capture, tight serving loops, harnesses
+   that forbid hipMalloc): lq_rot_step with the step's partial results (row maxima, loss and gradient partials, the
+   update's work matrices) in an array the library holds on each GPU (LQ_ROT_STATIC_SCRATCH_BYTES, until the process
+   ends) instead of in the state blob.  Same arguments, same kernels, same results bit for bit.  Of the state blob only
+   the leading sections are used (Omega, momentum, gradient, E1, E2: 3 r^2 + N r + r K floats, each section rounded up to
+   256 bytes), so state_bytes may be that small; a blob of lq_rot_sizes bytes always serves.  A configuration whose
+   partial results need more than LQ_ROT_STATIC_SCRATCH_BYTES (rank 96 and 128; a K or N in the millions) is rejected
+   with LQ_ERR_UNSUPPORTED before any launch.  Calls no allocator.  All calls on one GPU share that GPU's array: two
+   calls that overlap in time on one GPU (different streams, or a second thread) race; calls on one stream, or ordered
+   by events, are fine.  Nothing in the array has to start at zero. */
+#define LQ_ROT_STATIC_SCRATCH_BYTES (2u << 20)
+lq_status lq_rot_step_static(const lq_config *cfg, const float *L, const float *R, void *state, size_t state_bytes,
+                             const lq_cayley *opt, float *loss, void *stream);
+
 /* The rotated factors lq_pack_weights then takes: Lr = L Omega (N x r), Rr = Omega^T R (r x K), device fp32 dense, the
    same fp32 chains the loss quantises.  Lr, Rr must not overlap L, R. */
 lq_status lq_rot_apply(const lq_config *cfg, const float *L, const float *R, const void *state, float *Lr, float *Rr,

@@ -72,7 +72,7 @@ class lq_rot_view(C.Structure):
 
 EXPORTS = ["lq_status_string", "lq_packed_sizes", "lq_pack_weights", "lq_set_smoothing", "lq_act_sizes", "lq_quantize_act",
            "lq_linear_lowrank_fwd", "lq_unpack_weights", "lq_unpack_act", "lq_calib_sizes", "lq_calib_init", "lq_calib_step",
-           "lq_calib_unpack", "lq_rot_sizes", "lq_rot_init", "lq_rot_step", "lq_rot_apply", "lq_rot_unpack"]
+           "lq_calib_unpack", "lq_rot_sizes", "lq_rot_init", "lq_rot_step", "lq_rot_step_static", "lq_rot_apply", "lq_rot_unpack"]
 
 _lib.lq_calib_sizes.argtypes = [C.POINTER(lq_config), C.POINTER(C.c_size_t)]
 _lib.lq_calib_init.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -83,6 +83,7 @@ _lib.lq_rot_sizes.argtypes = [C.POINTER(lq_config), C.POINTER(C.c_size_t)]
 _lib.lq_rot_init.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.lq_rot_step.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.POINTER(lq_cayley),
                              C.c_void_p, C.c_void_p]
+_lib.lq_rot_step_static.argtypes = _lib.lq_rot_step.argtypes
 _lib.lq_rot_apply.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.lq_rot_unpack.argtypes = [C.POINTER(lq_config), C.c_void_p, C.POINTER(lq_rot_view), C.c_void_p]
 _lib.lq_status_string.restype = C.c_char_p
@@ -385,6 +386,16 @@ def lq_rot_step(cfg: lq_config, L: torch.Tensor, R: torch.Tensor, state: torch.T
     opt = lq_cayley(lr, beta, eps, q, s, grad_scale)
     _check(_lib.lq_rot_step(C.byref(cfg), _ptr(L), _ptr(R), _ptr(state), state.numel(), C.byref(opt), _ptr(loss),
                             C.c_void_p(_stream())), "lq_rot_step")
+
+
+def lq_rot_step_static(cfg: lq_config, L: torch.Tensor, R: torch.Tensor, state: torch.Tensor, lr: float = 0.5,
+                       beta: float = 0.9, eps: float = 1e-8, q: float = 0.5, s: int = 2, grad_scale: float = 1.0,
+                       loss: Optional[torch.Tensor] = None) -> None:
+    """lq_rot_step with the step's partial results in the library's per-GPU array (allocates nothing, sizes nothing)."""
+    _check_factors(cfg, L, R)
+    opt = lq_cayley(lr, beta, eps, q, s, grad_scale)
+    _check(_lib.lq_rot_step_static(C.byref(cfg), _ptr(L), _ptr(R), _ptr(state), state.numel(), C.byref(opt), _ptr(loss),
+                                   C.c_void_p(_stream())), "lq_rot_step_static")
 
 
 def lq_rot_apply(cfg: lq_config, L: torch.Tensor, R: torch.Tensor, state: torch.Tensor):

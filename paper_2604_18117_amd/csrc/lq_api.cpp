@@ -378,6 +378,22 @@ lq_status lq_rot_step(const lq_config* cfg, const float* L, const float* R, void
     return launch_rot_step(d, L, R, (uint8_t*)state, opt, loss, (hipStream_t)stream) == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }
 
+lq_status lq_rot_step_static(const lq_config* cfg, const float* L, const float* R, void* state, size_t state_bytes,
+                             const lq_cayley* opt, float* loss, void* stream)
+{
+    Dims d;
+    lq_status st = rot_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!L || !R || !state || !opt) return LQ_ERR_NULL;
+    if (!(opt->lr > 0.f) || !(opt->beta >= 0.f && opt->beta < 1.f) || !(opt->eps > 0.f) || !(opt->q > 0.f && opt->q < 1.f) ||
+        opt->s < 0 || opt->s > 16 || !(opt->grad_scale > 0.f))
+        return LQ_ERR_UNSUPPORTED;
+    if (rot_static_scratch_needed(d) > LQ_ROT_STATIC_SCRATCH_BYTES) return LQ_ERR_UNSUPPORTED;  // beyond the library's array
+    if (!aligned(state, 256) || !aligned(L, 16) || !aligned(R, 16) || (loss && !aligned(loss, 4))) return LQ_ERR_ALIGN;
+    if (state_bytes < rot_layout(d).off_ax) return LQ_ERR_BUFFER_TOO_SMALL;  // Omega, momentum, gradient, E1, E2
+    return launch_rot_step_static(d, L, R, (uint8_t*)state, opt, loss, (hipStream_t)stream) == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
 lq_status lq_rot_apply(const lq_config* cfg, const float* L, const float* R, const void* state, float* Lr, float* Rr,
                        void* stream)
 {

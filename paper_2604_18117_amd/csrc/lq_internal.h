@@ -179,6 +179,11 @@ RotLayout rot_layout(const Dims& d);
 hipError_t launch_rot_init(const Dims& d, const float* Omega0, const float* Mom0, uint8_t* state, hipStream_t s);
 hipError_t launch_rot_step(const Dims& d, const float* L, const float* R, uint8_t* state, const lq_cayley* cs, float* loss,
                            hipStream_t s);
+// The same step with its partial results in a per-device array of the library instead of the state blob's last sections
+// (for callers that cannot allocate); rot_static_scratch_needed = the bytes of those sections for a configuration.
+hipError_t launch_rot_step_static(const Dims& d, const float* L, const float* R, uint8_t* state, const lq_cayley* cs,
+                                  float* loss, hipStream_t s);
+size_t rot_static_scratch_needed(const Dims& d);
 hipError_t launch_rot_apply(const Dims& d, const float* L, const float* R, const uint8_t* state, float* Lr, float* Rr,
                             hipStream_t s);
 hipError_t launch_rot_unpack(const Dims& d, const uint8_t* state, const lq_rot_view* out, hipStream_t s);

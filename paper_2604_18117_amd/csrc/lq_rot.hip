@@ -14,6 +14,8 @@
 //                     rot_zr_kernel forms E2 itself and a step is four launches)
 //   rot_grad_kernel   partials of L^T E1 and R E2^T over strided 16-deep slices of N and K
 //   rot_cayley_kernel one workgroup: G, loss, momentum, the skew-symmetric W, step length, the fixed-point passes
+#include <mutex>
+
 #include "lq_internal.h"
 #include <type_traits>
 
@@ -597,16 +599,69 @@ static void rot_dispatch_z(const Dims& d, const RotLayout& rl, const RotQ& q, co
     }
 }
 
+// Partial results of a step (row maxima, loss and gradient partials, the update's work matrices) for callers that
+// cannot allocate: one array per device, held until the process ends.  Every element a step reads it has written before
+// in that same step, so nothing needs clearing between calls; two steps that overlap on one GPU would race on it.
+static __device__ __align__(256) uint8_t scratch[LQ_ROT_STATIC_SCRATCH_BYTES];
+
+// The array's device address on the current device (host code must not use the symbol's name as an address), looked up
+// once per device.
+static hipError_t rot_scratch_ptr(uint8_t** out)
+{
+    static std::mutex mu;
+    static uint8_t* ptr[64] = {nullptr};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr[dev] = (uint8_t*)p;
+    }
+    *out = ptr[dev];
+    return hipSuccess;
+}
+
+size_t rot_static_scratch_needed(const Dims& d)
+{
+    const RotLayout rl = rot_layout(d);
+    return rl.total - rl.off_ax;
+}
+
+// part: where the step's partial results live (laid out like the state blob's sections from off_ax on): inside the
+// state blob, or the per-device array
+static hipError_t rot_step_launches(const Dims& d, const float* L, const float* Rm, uint8_t* state, uint8_t* part,
+                                    const lq_cayley* cs, float* loss, hipStream_t s);
+
 hipError_t launch_rot_step(const Dims& d, const float* L, const float* Rm, uint8_t* state, const lq_cayley* cs, float* loss,
                            hipStream_t s)
+{
+    return rot_step_launches(d, L, Rm, state, state + rot_layout(d).off_ax, cs, loss, s);
+}
+
+hipError_t launch_rot_step_static(const Dims& d, const float* L, const float* Rm, uint8_t* state, const lq_cayley* cs,
+                                  float* loss, hipStream_t s)
+{
+    uint8_t* part = nullptr;
+    const hipError_t e = rot_scratch_ptr(&part);
+    if (e != hipSuccess) return e;
+    return rot_step_launches(d, L, Rm, state, part, cs, loss, s);
+}
+
+static hipError_t rot_step_launches(const Dims& d, const float* L, const float* Rm, uint8_t* state, uint8_t* part,
+                                    const lq_cayley* cs, float* loss, hipStream_t s)
 {
     const RotLayout rl = rot_layout(d);
     float* X = (float*)(state + rl.off_X);
     float* E1 = (float*)(state + rl.off_E1);
     float* E2 = (float*)(state + rl.off_E2);
-    float* ax = (float*)(state + rl.off_ax);
-    float* lp = (float*)(state + rl.off_lp);
-    float* gp = (float*)(state + rl.off_gp);
+    float* ax = (float*)part;
+    float* lp = (float*)(part + (rl.off_lp - rl.off_ax));
+    float* gp = (float*)(part + (rl.off_gp - rl.off_ax));
     const int N = (int)d.N, K = (int)d.K, r = d.r;
     const RotQ q = rot_q2(d);
     rot_dispatch_z<false>(d, rl, q, L, Rm, X, E1, E2, ax, lp, s);
@@ -626,7 +681,7 @@ hipError_t launch_rot_step(const Dims& d, const float* L, const float* Rm, uint8
     p.G = (float*)(state + rl.off_G);
     p.gp = gp;
     p.lp = lp;
-    p.tmp = (float*)(state + rl.off_tmp);
+    p.tmp = (float*)(part + (rl.off_tmp - rl.off_ax));
     p.loss = loss;
     p.r = r;
     p.nlb = rl.nlb;
