@@ -24,6 +24,8 @@
 // 32 x 32, 128 fp32 running sums per lane).  Activation codes go global -> registers -> LDS once per
 // workgroup; weight codes are read by each wavefront straight from global memory in operand order (no
 // other wavefront needs them) into the registers the MFMAs read.
+#include <type_traits>
+
 #include "lq_internal.h"
 
 namespace lq {
@@ -71,11 +73,20 @@ constexpr int RBT = 4;                         // 32-row blocks staged per workg
 constexpr int EPI_ROW = 144;                   // bytes per staged output row (128 + pad: no bank conflicts)
 constexpr int EPI_WAVE = 32 * EPI_ROW;         // one 32 x 64 bf16 block per wavefront
 constexpr int GA_MAXG = 88;                    // SINT4-block variant: K <= 5632 (the tile's token scales sit in LDS: 44 KB)
-template <int GC>
+// LDS slot of one staged (row block, chunk): the 1536 operand bytes; the stride is chosen so that the 8-byte parts of
+// two slots are neither 512-byte multiples nor within 2040 bytes of each other (the compiler would otherwise merge
+// their reads into one two-address read and pay register moves to put the halves back into operand tuples)
+// (the SINT4-block variant, short of registers, keeps the dense stride: there the merged reads cost fewer registers)
+template <bool GA>
+constexpr int lds_slot()
+{
+    return GA ? F6_CHUNK : 2064;
+}
+template <int GC, bool GA = false>
 constexpr int lds_bytes()
 {
-    // [buffer][chunk in group][row block][1536 B]
-    return 2 * GC * RBT * F6_CHUNK > NW * EPI_WAVE ? 2 * GC * RBT * F6_CHUNK : NW * EPI_WAVE;
+    // [buffer][chunk in group][row block][slot]
+    return 2 * GC * RBT * lds_slot<GA>() > NW * EPI_WAVE ? 2 * GC * RBT * lds_slot<GA>() : NW * EPI_WAVE;
 }
 
 // One output tile: rows rb0*32.., columns tile_n*256...  Each wavefront owns NRB row blocks x 64
@@ -147,7 +158,7 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     auto store_a = [&](const AStage& a, int buf) {
 #pragma unroll
         for (int cc = 0; cc < GC; ++cc) {
-            uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wave) * F6_CHUNK);
+            uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wave) * lds_slot<GA>());
             *(v4i*)(base + lane16) = v4i{a.v[cc][0], a.v[cc][1], a.v[cc][2], a.v[cc][3]};
             *(v2i*)(base + lane8) = v2i{a.v[cc][4], a.v[cc][5]};
         }
@@ -166,7 +177,7 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     // copied to LDS once; each step reads its 16 bytes per lane from there, one step ahead, into the register
     // set that serves as the A operand of the scale-product MFMAs.
     struct SStage { v4i sx; };
-    uint8_t* lds_sx = lds + lds_bytes<GC>();
+    uint8_t* lds_sx = lds + lds_bytes<GC, GA>();
     if constexpr (GA) {
         const uint32_t* src = p.sxg + (size_t)(rbw >> 2) * 128;
         for (int i = tid; i < G * 32; i += NW * 64)
@@ -183,13 +194,7 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         }
     };
 
-    v16f t[NRB][2];
-#pragma unroll
-    for (int a = 0; a < NRB; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) t[a][b][i] = 0.f;
+    v16f t[NRB][2];  // running sums; the first step starts them (from +0, as a constant operand of its FMAs)
 
     const uint64_t half_mask = 0xFFFFFFFF00000000ull;
     v4i bsel = {0, 0, 0, 0};
@@ -199,10 +204,11 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     // the step `a` goes to the other LDS buffer and is reloaded (two steps ahead with 64-deep groups), and the
     // weight set `bl` is requested: the set that step s-1 read (three rotating sets), or `bc` itself after this
     // step's last MFMA has been issued (two sets).
-    auto do_step = [&](int s, AStage& a, BStage& bc, BStage& bl, SStage& sc) {
+    auto do_step = [&](auto first_tag, int s, AStage& a, BStage& bc, BStage& bl, SStage& sc) {
+        constexpr bool FIRST = decltype(first_tag)::value;
         const int buf = s & 1;
         auto lds_a = [&](int rbi, int cc) -> v8i {
-            const uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wm * NRB + rbi) * F6_CHUNK);
+            const uint8_t* base = lds + (size_t)(((buf * GC + cc) * RBT + wm * NRB + rbi) * lds_slot<GA>());
             return op8(op6(*(const v4i*)(base + lane16), *(const v2i*)(base + lane8)));
         };
         auto tile_mfma = [&](const v8i (&af)[GC], int cbi) -> v16f {
@@ -229,6 +235,10 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         if constexpr (BSETS == 3) load_b(bl, s + 2);
 #pragma unroll
         for (int cc = 0; cc < GC; ++cc) af[0][cc] = lds_a(0, cc);
+        if constexpr (AFB == 2 && NRB > 1) {
+#pragma unroll
+            for (int cc = 0; cc < GC; ++cc) af[1][cc] = lds_a(1, cc);
+        }
         dd[0] = tile_mfma(af[0], 0);
         // software pipeline over the 8 MFMA tiles: the matrix core works on tile j+1 while
         // the vector ALU folds tile j into the running sums
@@ -249,9 +259,17 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
                 const int nrbi = (j + 1) >> 1, ncbi = (j + 1) & 1;
                 dd[(j + 1) & 1] = tile_mfma(af[nrbi % AFB], ncbi);
             }
-            if (cbi == 0 && rbi + 1 < NRB) {  // operand of the next row block, one tile ahead
+            if constexpr (AFB == 2) {
+                // operands are read a whole row block (two tiles) ahead of their first MFMA: block rbi + 2 goes into the
+                // buffer of block rbi as soon as that block's last MFMA has been issued (the LDS round trip is longer
+                // than one tile's FMAs)
+                if (cbi == 1 && rbi + 2 < NRB) {
 #pragma unroll
-                for (int cc = 0; cc < GC; ++cc) af[(rbi + 1) % AFB][cc] = lds_a(rbi + 1, cc);
+                    for (int cc = 0; cc < GC; ++cc) af[rbi % AFB][cc] = lds_a(rbi + 2, cc);
+                }
+            } else if (cbi == 0 && rbi + 1 < NRB) {  // one buffer: the next row block, one tile ahead
+#pragma unroll
+                for (int cc = 0; cc < GC; ++cc) af[0][cc] = lds_a(rbi + 1, cc);
             }
             if (j == 0) {  // fills the pipeline start-up bubble
                 store_a(a, buf ^ 1);
@@ -264,7 +282,7 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < 16; ++i)
-                t[rbi][cbi][i] = __builtin_fmaf(dd[j & 1][i], GA ? P[i] : swc[cbi], t[rbi][cbi][i]);
+                t[rbi][cbi][i] = __builtin_fmaf(dd[j & 1][i], GA ? P[i] : swc[cbi], FIRST ? 0.0f : t[rbi][cbi][i]);
             if (DBG) {
                 if (p.dbg_acc && active) {
 #pragma unroll
@@ -284,6 +302,8 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     // Every wavefront runs the same branch-free loop; one without valid output (past the
     // last column or row block of a partial tile) works on clamped operands, stores nothing.
     SStage s0;
+    const std::true_type first{};    // the first step of a tile starts the running sums
+    const std::false_type later{};
     if constexpr (BSETS == 3) {
         AStage a0, a1;
         BStage b0, b1, b2;
@@ -296,18 +316,19 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         __syncthreads();
         load_s(s0, 0);
         // step s reads weight set s % 3 and requests set (s + 2) % 3; activation set (s + 1) % 2 goes to LDS
-        for (int s = 0; s < G; s += 6) {
-            do_step(s, a1, b0, b2, s0);
+        do_step(first, 0, a1, b0, b2, s0);
+        for (int s = 1; s < G; s += 6) {
+            do_step(later, s, a0, b1, b0, s0);
             if (s + 1 >= G) break;
-            do_step(s + 1, a0, b1, b0, s0);
+            do_step(later, s + 1, a1, b2, b1, s0);
             if (s + 2 >= G) break;
-            do_step(s + 2, a1, b2, b1, s0);
+            do_step(later, s + 2, a0, b0, b2, s0);
             if (s + 3 >= G) break;
-            do_step(s + 3, a0, b0, b2, s0);
+            do_step(later, s + 3, a1, b1, b0, s0);
             if (s + 4 >= G) break;
-            do_step(s + 4, a1, b1, b0, s0);
+            do_step(later, s + 4, a0, b2, b1, s0);
             if (s + 5 >= G) break;
-            do_step(s + 5, a0, b2, b1, s0);
+            do_step(later, s + 5, a1, b0, b2, s0);
         }
     } else if constexpr (ASETS == 2) {  // SINT4 blocks: two weight sets
         AStage a0, a1;
@@ -320,10 +341,18 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         load_a(a0, 2);
         __syncthreads();
         load_s(s0, 0);
-        for (int s = 0; s < G; s += 2) {
-            do_step(s, a1, b0, b0, s0);
+        // (registers are scarce here: the running sums start as zeros in registers and every step is the same code)
+#pragma unroll
+        for (int a = 0; a < NRB; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) t[a][b][i] = 0.f;
+        do_step(later, 0, a1, b0, b0, s0);
+        for (int s = 1; s < G; s += 2) {
+            do_step(later, s, a0, b1, b1, s0);
             if (s + 1 >= G) break;
-            do_step(s + 1, a0, b1, b1, s0);
+            do_step(later, s + 1, a1, b0, b0, s0);
         }
     } else {  // 128-deep groups
         AStage a0;
@@ -334,10 +363,11 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         store_a(a0, 0);
         load_a(a0, 1);
         __syncthreads();
-        for (int s = 0; s < G; s += 2) {
-            do_step(s, a0, b0, b0, s0);
+        do_step(first, 0, a0, b0, b0, s0);
+        for (int s = 1; s < G; s += 2) {
+            do_step(later, s, a0, b1, b1, s0);
             if (s + 1 >= G) break;
-            do_step(s + 1, a0, b1, b1, s0);
+            do_step(later, s + 1, a0, b0, b0, s0);
         }
     }
 
@@ -461,7 +491,7 @@ __device__ __forceinline__ int xcd_order(int b, int n)
 template <int GC, int NK, bool DBG, bool GA = false>
 __global__ __launch_bounds__(NW * 64, 2) void fwd_int_kernel(FwdParams p)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[lds_bytes<GC>() + (GA ? GA_MAXG * 512 : 0)];
+    __shared__ __attribute__((aligned(16))) uint8_t lds[lds_bytes<GC, GA>() + (GA ? GA_MAXG * 512 : 0)];
     const int b = blockIdx.x;
     if (b < p.n_full) {
         const int tile = xcd_order(b, p.n_full);
