@@ -67,3 +67,56 @@ def run_oracle_int(oracle, layer, X, W, L, R, want_acc=True):
 
 def n(t):
     return t.cpu().numpy()
+
+
+def check_bf16_against_oracle(oracle, Yb, y_gpu, out, bound, what=""):
+    """The bf16 output against an oracle result `out` whose fp32 value the kernel's own fp32 value `y_gpu` has already
+    been shown to match within `bound` (fp32 accumulation in the matrix core against the oracle's fp64 sum).
+    Rule (a reading of "max relative error <= 2e-3" for a bf16 output, whose own rounding step is 2^-8 .. 2^-7 relative):
+    the stored bits are the nearest-even rounding of the kernel's fp32 value; where they differ from the oracle's bits
+    (a "flip") the two fp32 values straddle a rounding boundary, so the difference is exactly one bf16 step (unless the
+    result cancels to less than the accumulation bound itself); everything else is within 2e-3 relative.  The number of flips is reported, and on outputs of at least 1000 elements their rate
+    must stay below 2e-3 (measured: ~3e-5; a kernel that reorders sums grossly would show up here first)."""
+    want = ((y_gpu.view(np.uint32) + 0x7FFF + ((y_gpu.view(np.uint32) >> 16) & 1)) >> 16).astype(np.uint16)
+    assert np.array_equal(Yb, want), "Y is not bf16_rne(y32)"
+    Yf = oracle.bf16_bits_to_f32(Yb).astype(np.float64)
+    Yo = oracle.bf16_bits_to_f32(out.Y).astype(np.float64)
+    tau = 1e-3 * np.sqrt(np.mean(out.y32.astype(np.float64) ** 2)) + 1e-300
+    rel = np.abs(Yf - Yo) / np.maximum(np.abs(out.y32), tau)
+    flips = Yb != out.Y
+    assert np.all(rel[~flips] <= 2e-3)
+    if flips.any():
+        yg, yo, bf = y_gpu[flips].astype(np.float64), out.y32[flips].astype(np.float64), bound[flips]
+        assert np.all(np.abs(yg - yo) <= bf)
+        # two roundings (half a bf16 step each, at most 2^-8 relative) of values within the bound of each other
+        assert np.all(np.abs(Yf[flips] - Yo[flips]) <= bf + 2.0 ** -8 * (np.abs(yg) + np.abs(yo)))
+        # where the bound is far below a bf16 step the difference is exactly one step of the grid (results that cancel
+        # to almost nothing, e.g. an all-zero channel of W whose main product and branch cancel, sit on a finer grid
+        # than the bound and may land several steps apart)
+        a, b = Yb[flips].astype(np.int64), out.Y[flips].astype(np.int64)
+        same_sign = (a >> 15) == (b >> 15)
+        one_step = np.where(same_sign, np.abs(a - b) == 1, ((a & 0x7FFF) + (b & 0x7FFF)) <= 1)
+        fine = bf <= 2.0 ** -10 * np.abs(yo)
+        assert np.all(one_step[fine]), "a bf16 difference of more than one step"
+    if flips.size >= 1000:
+        assert flips.mean() <= 2e-3, f"bf16 flip rate {flips.mean()}"
+    if flips.any():
+        print(f"[parity{what}] bf16 flips against the oracle: {int(flips.sum())} of {flips.size}")
+
+
+def check_end_to_end(oracle, Yb, y_gpu, out_alone, bound_acc, D, Labs, what=""):
+    """The kernel's result against the oracle run ALONE (its own re-quantised intermediate), end to end.
+    bound_acc: the fp32-accumulation bound on y; D (M x r): |dequantised intermediate of the GPU - of the oracle|,
+    itself already checked against its derived bound (half a code step on either side plus the accumulation bound
+    of T); Labs (N x r): |dequantised L|.  Then |y_gpu - y32_oracle| <= bound_acc + sum_j D[m,j] |L[n,j]|, and the
+    stored bf16 value is within half a bf16 step (2^-8 relative) of y_gpu."""
+    tot = bound_acc + D @ Labs.T
+    err = np.abs(y_gpu.astype(np.float64) - out_alone.y32.astype(np.float64))
+    assert np.all(err <= tot), f"end-to-end y32 max excess {np.max(err / tot)}"
+    Yf = oracle.bf16_bits_to_f32(Yb).astype(np.float64)
+    e2 = np.abs(Yf - out_alone.y32.astype(np.float64))
+    assert np.all(e2 <= tot + 2.0 ** -8 * np.abs(y_gpu.astype(np.float64)) + 1e-300), "end-to-end bf16 output"
+    tau = 1e-3 * np.sqrt(np.mean(out_alone.y32.astype(np.float64) ** 2)) + 1e-300
+    rel = e2 / np.maximum(np.abs(out_alone.y32), tau)
+    print(f"[parity{what}] end to end vs the oracle alone: max |Y - y32| / max(|y32|, tau) = {rel.max():.3e}, "
+          f"share above 2e-3: {np.mean(rel > 2e-3):.2e} (bf16's own rounding step is 3.9e-3 .. 7.8e-3)")

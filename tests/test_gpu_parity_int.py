@@ -188,6 +188,32 @@ def _full_size_sampled(oracle, name):
     assert np.array_equal(Yb, out.Y)
 
 
+@pytest.mark.parametrize("name", ["c2_qkv", "c3_fc1", "c4_qkv", "c4_expand"])
+def test_full_size_whole_tile_row_and_column_panel(oracle, name):
+    """Full-size layer with the accumulator taps on: one whole interior 128-row tile row (every channel) and one whole
+    interior 256-column panel (every token) against the oracle, per-group accumulators included.  A wrong tile anywhere
+    on that row or in that panel (tile order, panel order, the grid's tail) shows up here, which a sample of token rows
+    can only see through the never-written check.  The oracle computes the panel from the same channels of W and L
+    (channels are independent through the whole path, like token rows)."""
+    layer = wl.LAYERS[name]
+    X, W, L, R = wl.make_inputs(layer)
+    g = run_gpu(layer, X, W, L, R, debug=True, debug_acc=True)
+    tm = (layer.M // 128) * 5 // 8
+    rows = slice(tm * 128, tm * 128 + 128)
+    pk, act, out = run_oracle_int(oracle, layer, X[rows], W, L, R, want_acc=True)
+    assert np.array_equal(n(g.fdbg.acc[rows]), out.acc), "acc, tile row"
+    assert np.array_equal(n(g.fdbg.acc2[rows]), out.acc2), "acc2, tile row"
+    assert np.array_equal(n(g.fdbg.y32[rows]), out.y32), "y32, tile row"
+    assert np.array_equal(bf16_to_bits(g.Y[rows]), out.Y), "Y, tile row"
+    tn = ((layer.N + 255) // 256) * 3 // 7
+    cols = slice(tn * 256, tn * 256 + 256)
+    pk, act, out = run_oracle_int(oracle, layer, X, W[cols], L[cols], R, want_acc=True)
+    assert np.array_equal(n(g.fdbg.acc[:, cols].contiguous()), out.acc), "acc, column panel"
+    assert np.array_equal(n(g.fdbg.acc2[:, cols].contiguous()), out.acc2), "acc2, column panel"
+    assert np.array_equal(n(g.fdbg.y32[:, cols].contiguous()), out.y32), "y32, column panel"
+    assert np.array_equal(bf16_to_bits(g.Y[:, cols]), out.Y), "Y, column panel"
+
+
 @pytest.mark.parametrize("M,K,N,r,xd,ag", [(200, 1152, 320, 32, "bf16", 0), (77, 2304, 64, 16, "f32", 0), (33, 256, 64, 0, "bf16", 0),
                                               (200, 1152, 320, 32, "bf16", 64), (77, 2304, 64, 16, "f32", 64)])
 def test_fused_smoothing(oracle, M, K, N, r, xd, ag):

@@ -13,7 +13,7 @@ import torch
 
 from paper_2604_18117_amd import workloads as wl
 from tests.smoothing import smoothing_vector
-from tests.gpu_util import bf16_to_bits, n, run_gpu
+from tests.gpu_util import bf16_to_bits, check_bf16_against_oracle, check_end_to_end, n, run_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -64,7 +64,13 @@ def _compare(oracle, layer, X, W, L, R, rows=None, gamma=None):
         assert np.allclose(st_gpu, act.st, rtol=2e-4, atol=0), "st"
         diff = tq_gpu != act.tq8
         diff &= ~(((tq_gpu & 0x7F) == 0) & ((act.tq8 & 0x7F) == 0))
-        assert diff.sum() <= max(1, 1e-2 * diff.size), f"tq8 mismatch rate {diff.mean()}"  # (one code may differ on a tiny sample; the rounding check below is the bar)
+        # Re-quantised codes may differ from the oracle's only where T sits within the accumulation bound of a rounding
+        # boundary (where |T| is small against the sum of |terms| that bound can span more than one code step): the
+        # GPU's code must be a correct rounding of a value within the bound of the oracle's T (checked next, for every
+        # element), and the two dequantised intermediates lie within two half steps plus the bound of each other
+        # (checked with the end-to-end comparison below).  The count is reported.
+        if diff.any():
+            print(f"[parity mx] re-quantised codes that differ from the oracle's: {int(diff.sum())} of {diff.size}")
         # every GPU code is a correct E4M3 rounding of a value within the accumulation bound of the
         # oracle's T: |deq - T| <= half the local code spacing (in units of st) + bound
         u = np.abs(act.T.astype(np.float64)) / st_gpu[:, None]
@@ -82,19 +88,21 @@ def _compare(oracle, layer, X, W, L, R, rows=None, gamma=None):
     A = Xd.reshape(Xo.shape[0], -1) @ Wd.reshape(layer.N, -1).T          # sum of |terms| of the main product
     bound = 2.0 ** -15 * (A + np.abs(out.ybr)) + 1e-30
     assert np.all(np.abs(y_gpu - out.y32) <= bound), f"y32 max excess {np.max(np.abs(y_gpu - out.y32) / bound)}"
-    # bf16 output = nearest-even rounding of the kernel's own fp32 value ...
     Yb = bf16_to_bits(g.Y)[sel]
-    want = ((y_gpu.view(np.uint32) + 0x7FFF + ((y_gpu.view(np.uint32) >> 16) & 1)) >> 16).astype(np.uint16)
-    assert np.array_equal(Yb, want), "Y is not bf16_rne(y32)"
-    # ... and against the oracle: the stated 2e-3 bound on everything that is not a rounding-boundary flip
-    Yf = oracle.bf16_bits_to_f32(Yb).astype(np.float64)
-    Yo = oracle.bf16_bits_to_f32(out.Y).astype(np.float64)
-    tau = 1e-3 * np.sqrt(np.mean(out.y32.astype(np.float64) ** 2)) + 1e-30
-    rel = np.abs(Yf - Yo) / np.maximum(np.abs(out.y32), tau)
-    flips = Yb != out.Y
-    assert flips.sum() <= max(1, 2e-3 * flips.size), f"bf16 flip rate {flips.mean()}"  # (one flip is allowed on a tiny output)
-    assert np.all(rel[~flips] <= 2e-3)
-    assert np.all(rel[flips] <= 2.0 ** -7 * 1.01)      # a flip is exactly one bf16 ulp
+    check_bf16_against_oracle(oracle, Yb, y_gpu, out, bound, " mx")
+    # ---- end to end: the oracle alone (its own T, scale and codes)
+    if r:
+        out_alone = oracle.fwd_mx(pk, act)
+        deq_g = f8[tq_gpu].astype(np.float64) * st_gpu[:, None].astype(np.float64)
+        deq_o = f8[act.tq8].astype(np.float64) * act.st[:, None].astype(np.float64)
+        D = np.abs(deq_g - deq_o)
+        # both are roundings (half a local E4M3 step under their own per-token scale) of values within tb of each other
+        uo = np.abs(act.T.astype(np.float64)) / act.st[:, None]
+        step_o = np.exp2(np.maximum(np.floor(np.log2(np.maximum(uo, 2.0 ** -6))) - 3, -9))
+        assert np.all(D <= (st_gpu[:, None] * 0.5 * step + act.st[:, None] * 0.5 * step_o) * (1 + 1e-3)
+                      + 4e-4 * np.abs(act.T) + tb), "intermediates further apart than two half steps"
+        Labs = np.abs(f8[pk.l8].astype(np.float64)) * pk.sl[:, None].astype(np.float64)
+        check_end_to_end(oracle, Yb, y_gpu, out_alone, 2.0 ** -15 * (A + np.abs(out_alone.ybr)) + 1e-30, D, Labs, " mx")
     g2 = run_gpu(layer, X, W, L, R, debug=False, gamma=gamma)
     assert torch.equal(g2.Y, g.Y)
     return g

@@ -15,11 +15,14 @@ import pytest
 import torch
 
 from paper_2604_18117_amd import workloads as wl
-from tests.gpu_util import bf16_to_bits, n, run_gpu
+from tests.gpu_util import bf16_to_bits, check_bf16_against_oracle, check_end_to_end, n, run_gpu
 
 pytestmark = pytest.mark.gpu
 
 E2M1 = np.array([0, .5, 1, 1.5, 2, 3, 4, 6, -0., -.5, -1, -1.5, -2, -3, -4, -6], np.float32)
+# fp32 accumulation inside the 8-bit scaled matrix instruction against the oracle's fp64 sum: at most this fraction of the
+# sum of |terms| (measured worst case over every committed and swept case: 2^-14.9; the bar leaves a factor 1.9)
+ACC = 2.0 ** -14
 
 
 def _compare(oracle, layer, X, W, L, R, rows=None, gamma=None):
@@ -54,12 +57,18 @@ def _compare(oracle, layer, X, W, L, R, rows=None, gamma=None):
         T_gpu = n(g.adbg.T)[sel]
         xs = np.abs(f8[act.xb8].astype(np.float64).reshape(Mo, -1, 32)) * oracle.e8m0_decode(act.xbe)[:, :, None]
         rs = np.abs(f8[pk.r8].astype(np.float64).reshape(r, -1, 32)) * oracle.e8m0_decode(pk.re)[:, :, None]
-        tb = 2.0 ** -13 * (xs.reshape(Mo, -1) @ rs.reshape(r, -1).T) + 1e-300
+        tb = ACC * (xs.reshape(Mo, -1) @ rs.reshape(r, -1).T) + 1e-300
         assert np.all(np.abs(T_gpu - act.T) <= tb), f"T max excess {np.max(np.abs(T_gpu - act.T) / tb)}"
         # block exponents: equal except where a block's amax sits within the bound of a power of two
         ediff = te_gpu != act.te
-        assert ediff.sum() <= max(1, 1e-2 * ediff.size), f"te mismatch rate {ediff.mean()}"  # (one code may differ on a tiny sample; the rounding check below is the bar)
         assert np.all(np.abs(te_gpu.astype(int) - act.te.astype(int)) <= 1)
+        # a block exponent may differ only where the block's largest |T| sits within the bound of a power of two
+        if ediff.any():
+            bm = np.abs(act.T.astype(np.float64)).reshape(Mo, -1, 32)
+            amax, amax_b = bm.max(axis=2), np.take_along_axis(tb.reshape(Mo, -1, 32), bm.argmax(axis=2)[:, :, None], axis=2)[:, :, 0]
+            p2 = np.exp2(np.round(np.log2(np.maximum(amax, 1e-300))))
+            assert np.all(np.abs(amax - p2)[ediff] <= amax_b[ediff] * 1.0001), "block exponent differs away from a power of two"
+            print(f"[parity mxb] block exponents that differ from the oracle's: {int(ediff.sum())} of {ediff.size}")
         # every GPU element is a correct saturating E4M3 rounding, under the GPU's block scale, of a
         # value within the accumulation bound of the oracle's T
         sc = np.repeat(oracle.e8m0_decode(te_gpu), 32, axis=1)
@@ -70,7 +79,11 @@ def _compare(oracle, layer, X, W, L, R, rows=None, gamma=None):
         assert np.all(np.abs(deq - act.T) <= sc * half + tb), "tq8 is not a block rounding of T"
         same = ~ediff.repeat(32, axis=1)
         diff = (f8[tq_gpu] != f8[act.tq8]) & same
-        assert diff.sum() <= max(1, 1e-2 * diff.size), f"tq8 mismatch rate {diff.mean()}"  # (one code may differ on a tiny sample; the rounding check below is the bar)
+        # under equal block scales a code may differ from the oracle's only where T sits within the accumulation bound
+        # of a rounding boundary (the check above bounds every element; the end-to-end comparison below bounds the
+        # distance of the two dequantised intermediates).  The count is reported.
+        if diff.any():
+            print(f"[parity mxb] re-quantised codes that differ from the oracle's: {int(diff.sum())} of {diff.size}")
     # ---- forward: the oracle is fed the GPU's re-quantised intermediate
     act_g = dataclasses.replace(act, tq8=np.ascontiguousarray(tq_gpu), te=np.ascontiguousarray(te_gpu))
     out = oracle.fwd_mxb(pk, act_g)
@@ -82,19 +95,24 @@ def _compare(oracle, layer, X, W, L, R, rows=None, gamma=None):
         Td = np.abs(f8[tq_gpu].astype(np.float64).reshape(Mo, -1, 32)) * oracle.e8m0_decode(te_gpu)[:, :, None]
         Ld = np.abs(f8[pk.l8].astype(np.float64).reshape(layer.N, -1, 32)) * oracle.e8m0_decode(pk.le)[:, :, None]
         A = A + Td.reshape(Mo, -1) @ Ld.reshape(layer.N, -1).T
-    bound = 2.0 ** -13 * A + 1e-300
+    bound = ACC * A + 1e-300
     assert np.all(np.abs(y_gpu - out.y32) <= bound), f"y32 max excess {np.max(np.abs(y_gpu - out.y32) / bound)}"
     Yb = bf16_to_bits(g.Y)[sel]
-    want = ((y_gpu.view(np.uint32) + 0x7FFF + ((y_gpu.view(np.uint32) >> 16) & 1)) >> 16).astype(np.uint16)
-    assert np.array_equal(Yb, want), "Y is not bf16_rne(y32)"
-    Yf = oracle.bf16_bits_to_f32(Yb).astype(np.float64)
-    Yo = oracle.bf16_bits_to_f32(out.Y).astype(np.float64)
-    tau = 1e-3 * np.sqrt(np.mean(out.y32.astype(np.float64) ** 2)) + 1e-300
-    rel = np.abs(Yf - Yo) / np.maximum(np.abs(out.y32), tau)
-    flips = Yb != out.Y
-    assert flips.sum() <= max(1, 2e-3 * flips.size), f"bf16 flip rate {flips.mean()}"  # (one flip is allowed on a tiny output)
-    assert np.all(rel[~flips] <= 2e-3)
-    assert np.all(rel[flips] <= 2.0 ** -7 * 1.01)
+    check_bf16_against_oracle(oracle, Yb, y_gpu, out, bound, " mxb")
+    # ---- end to end: the oracle alone (its own T, block exponents and codes)
+    if r:
+        out_alone = oracle.fwd_mxb(pk, act)
+        sc_o = np.repeat(oracle.e8m0_decode(act.te), 32, axis=1)
+        deq_o = f8[act.tq8].astype(np.float64) * sc_o
+        D = np.abs(deq - deq_o)
+        uo = np.abs(act.T.astype(np.float64)) / sc_o
+        step_o = np.exp2(np.maximum(np.floor(np.log2(np.maximum(uo, 2.0 ** (min_exp - 1)))) - 3, min_exp))
+        half_o = np.where(uo > top, uo - top, 0.5 * step_o * (1 + 1e-6))
+        assert np.all(D <= sc * half + sc_o * half_o + tb), "intermediates further apart than two half steps"
+        Labs = (np.abs(f8[pk.l8].astype(np.float64).reshape(layer.N, -1, 32)) * oracle.e8m0_decode(pk.le)[:, :, None]).reshape(layer.N, -1)
+        To = (np.abs(deq_o).reshape(Mo, -1)) @ Labs.T
+        Am = Xd.reshape(Mo, -1) @ Wd.reshape(layer.N, -1).T
+        check_end_to_end(oracle, Yb, y_gpu, out_alone, ACC * (Am + To) + 1e-300, D, Labs, " mxb")
     g2 = run_gpu(layer, X, W, L, R, debug=False, gamma=gamma)
     assert torch.equal(g2.Y, g.Y)
     return g

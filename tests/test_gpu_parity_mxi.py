@@ -15,9 +15,13 @@ import pytest
 import torch
 
 from paper_2604_18117_amd import workloads as wl
-from tests.gpu_util import bf16_to_bits, n, run_gpu
+from tests.gpu_util import bf16_to_bits, check_bf16_against_oracle, check_end_to_end, n, run_gpu
 
 pytestmark = pytest.mark.gpu
+
+# fp32 accumulation inside the scaled / bf16 matrix instructions against the oracle's fp64 sum: at most this fraction of the
+# sum of |terms| (measured worst case over every committed and swept case: 2^-14.9; the bar leaves a factor 1.9)
+ACC = 2.0 ** -14
 
 
 def _vals(oracle, codes, ebytes, bits):
@@ -53,11 +57,17 @@ def _compare(oracle, layer, X, W, L, R, rows=None, exact=False, gamma=None):
         assert np.array_equal(n(g.adbg.xb)[sel], act.xb), "xb"
         assert np.array_equal(n(g.adbg.xbe)[sel], act.xbe), "xbe"
         T_gpu = n(g.adbg.T)[sel]
-        tb = 2.0 ** -13 * (_vals(oracle, act.xb, act.xbe, 8) @ _vals(oracle, pk.rq, pk.re, bw).T) + 1e-300
+        tb = ACC * (_vals(oracle, act.xb, act.xbe, 8) @ _vals(oracle, pk.rq, pk.re, bw).T) + 1e-300
         assert np.all(np.abs(T_gpu - act.T) <= tb), f"T max excess {np.max(np.abs(T_gpu - act.T) / tb)}"
         ediff = te_gpu != act.te
-        assert ediff.sum() <= max(1, 1e-2 * ediff.size), f"te mismatch rate {ediff.mean()}"  # (one code may differ on a tiny sample; the rounding check below is the bar)
         assert np.all(np.abs(te_gpu.astype(int) - act.te.astype(int)) <= 1)
+        # a block exponent may differ only where the block's largest |T| sits within the bound of a power of two
+        if ediff.any():
+            bm = np.abs(act.T.astype(np.float64)).reshape(Mo, -1, 32)
+            amax, amax_b = bm.max(axis=2), np.take_along_axis(tb.reshape(Mo, -1, 32), bm.argmax(axis=2)[:, :, None], axis=2)[:, :, 0]
+            p2 = np.exp2(np.round(np.log2(np.maximum(amax, 1e-300))))
+            assert np.all(np.abs(amax - p2)[ediff] <= amax_b[ediff] * 1.0001), "block exponent differs away from a power of two"
+            print(f"[parity mxi] block exponents that differ from the oracle's: {int(ediff.sum())} of {ediff.size}")
         # every GPU element is a correct saturating rounding, on the GPU's block grid, of a value within
         # the accumulation bound of the oracle's T
         step = np.repeat(oracle.mxint_scale(te_gpu, 8), 32, axis=1)
@@ -68,7 +78,11 @@ def _compare(oracle, layer, X, W, L, R, rows=None, exact=False, gamma=None):
         assert np.all(np.abs(deq - act.T) <= step * half + tb), "tq is not a block rounding of T"
         same = ~ediff.repeat(32, axis=1)
         diff = (tq_gpu != act.tq) & same
-        assert diff.sum() <= max(1, 1e-2 * diff.size), f"tq mismatch rate {diff.mean()}"  # (one code may differ on a tiny sample; the rounding check below is the bar)
+        # under equal block scales a code may differ from the oracle's only where T sits within the accumulation bound
+        # of a rounding boundary (the check above bounds every element; the end-to-end comparison below bounds the
+        # distance of the two dequantised intermediates).  The count is reported.
+        if diff.any():
+            print(f"[parity mxi] re-quantised codes that differ from the oracle's: {int(diff.sum())} of {diff.size}")
         if exact:
             assert np.array_equal(T_gpu, act.T) and np.array_equal(tq_gpu, act.tq) and np.array_equal(te_gpu, act.te)
     # ---- forward: the oracle is fed the GPU's re-quantised intermediate
@@ -78,21 +92,24 @@ def _compare(oracle, layer, X, W, L, R, rows=None, exact=False, gamma=None):
     A = _vals(oracle, act.xq, act.xe, 4) @ _vals(oracle, pk.pq, pk.pe, 4).T
     if r:
         A = A + _vals(oracle, tq_gpu, te_gpu, 8) @ _vals(oracle, pk.lq, pk.le, bw).T
-    bound = 2.0 ** -13 * A + 1e-300
+    bound = ACC * A + 1e-300
     assert np.all(np.abs(y_gpu - out.y32) <= bound), f"y32 max excess {np.max(np.abs(y_gpu - out.y32) / bound)}"
     if exact:
         assert np.array_equal(y_gpu, out.y32), "y32 (exactly representable partial sums)"
     Yb = bf16_to_bits(g.Y)[sel]
-    want = ((y_gpu.view(np.uint32) + 0x7FFF + ((y_gpu.view(np.uint32) >> 16) & 1)) >> 16).astype(np.uint16)
-    assert np.array_equal(Yb, want), "Y is not bf16_rne(y32)"
-    Yf = oracle.bf16_bits_to_f32(Yb).astype(np.float64)
-    Yo = oracle.bf16_bits_to_f32(out.Y).astype(np.float64)
-    tau = 1e-3 * np.sqrt(np.mean(out.y32.astype(np.float64) ** 2)) + 1e-300
-    rel = np.abs(Yf - Yo) / np.maximum(np.abs(out.y32), tau)
-    flips = Yb != out.Y
-    assert flips.sum() <= max(1, 2e-3 * flips.size), f"bf16 flip rate {flips.mean()}"  # (one flip is allowed on a tiny output)
-    assert np.all(rel[~flips] <= 2e-3)
-    assert np.all(rel[flips] <= 2.0 ** -7 * 1.01)
+    check_bf16_against_oracle(oracle, Yb, y_gpu, out, bound, " mxi")
+    # ---- end to end: the oracle alone (its own T, block exponents and codes)
+    if r:
+        out_alone = oracle.fwd_mxi(pk, act)
+        step_o = np.repeat(oracle.mxint_scale(act.te, 8), 32, axis=1)
+        deq_o = act.tq.astype(np.float64) * step_o
+        D = np.abs(deq - deq_o)
+        uo = np.abs(act.T.astype(np.float64)) / step_o
+        half_o = np.where(uo > 127.0, uo - 127.0, 0.5 * (1 + 1e-9))
+        assert np.all(D <= step * half + step_o * half_o + tb), "intermediates further apart than two half steps"
+        Labs = _vals(oracle, pk.lq, pk.le, bw)
+        Am = _vals(oracle, act.xq, act.xe, 4) @ _vals(oracle, pk.pq, pk.pe, 4).T
+        check_end_to_end(oracle, Yb, y_gpu, out_alone, ACC * (Am + np.abs(deq_o) @ Labs.T) + 1e-300, D, Labs, " mxi")
     g2 = run_gpu(layer, X, W, L, R, debug=False, gamma=gamma)
     assert torch.equal(g2.Y, g.Y)
     return g

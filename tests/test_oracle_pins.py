@@ -534,6 +534,35 @@ def test_forward_matches_exact_rational_dequant(oracle):
     assert oracle.bf16_rne(-2.5) == 0xC020
 
 
+def test_final_scale_and_add_is_one_fused_rounding(oracle):
+    """The order of the last dequantisation step is a choice the paper leaves open (Fig. 1 only draws a sum node):
+    y = fma(sx, t, ybr), one rounding, not fl(fl(sx * t) + ybr).  A constructed layer on which the two forms differ
+    pins the choice: t = sx = 1 + 2^-23 and ybr = 2^-24, so sx * t = 1 + 2^-22 + 2^-46; rounding that product first
+    loses the 2^-46 and the sum 1 + 2^-22 + 2^-24 is an exact tie that goes to even (1 + 2^-22), while the fused form
+    sees a value just above the tie and rounds up to 1 + 2^-22 + 2^-23."""
+    K, g = 64, 64
+    one_eps = np.float32(1.0 + 2.0 ** -23)
+    pq = np.zeros((1, K), np.int8); pq[0, 0] = 1
+    xq = np.zeros((1, K), np.int8); xq[0, 0] = 1
+    pk = oracle.PackedInt(1, K, 1, g, False, pq, np.full((1, 1), one_eps, np.float32), np.ones((1, 1), np.int8),
+                          np.ones(1, np.float32), np.zeros((1, K), np.int8), np.ones(1, np.float32),
+                          np.zeros((1, K), np.float32))
+    act = oracle.ActInt(1, xq, np.full(1, one_eps, np.float32), np.zeros((1, K), np.int8), np.ones(1, np.float32),
+                        np.zeros((1, 1), np.int32), np.zeros((1, 1), np.float32), np.ones((1, 1), np.int8),
+                        np.full(1, 2.0 ** -24, np.float32))
+    out = oracle.fwd_int(pk, act, want_acc=True)
+    assert out.acc[0, 0, 0] == 1 and out.acc2[0, 0] == 1
+    assert out.ybr[0, 0] == np.float32(2.0 ** -24)
+    two_step = np.float32(np.float32(one_eps * one_eps) + np.float32(2.0 ** -24))
+    assert two_step == np.float32(1.0 + 2.0 ** -22)                      # what two roundings would give
+    fused = Fraction(float(one_eps)) ** 2 + Fraction(2) ** -24           # exact value, then one rounding
+    assert fused > Fraction(1) + Fraction(2) ** -22 + Fraction(2) ** -24  # just above the tie
+    assert out.y32[0, 0] == np.float32(1.0 + 2.0 ** -22 + 2.0 ** -23)
+    assert out.y32[0, 0] != two_step
+    # ymain is reported as the separately rounded product (it is a tap, not an operand of the sum)
+    assert out.ymain[0, 0] == np.float32(one_eps * one_eps)
+
+
 def test_rank0_equals_plain_w4a4(oracle):
     # rank 0, or L = R = 0: P == W and the branch contributes +0 (bit for bit)
     X, W, L, R, pk, act, out = _small_int_problem(oracle)
