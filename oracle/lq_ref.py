@@ -492,6 +492,14 @@ def quantize_act_mxi(X, pk: PackedMxi) -> ActMxi:
     return out
 
 
+def handoff_mxi(Y_bits, pk_next: PackedMxi) -> ActMxi:
+    """Quantized hand-off between two linears (Section 4.5: activations move between layers in the MX formats instead
+    of 16 bits).  The reading taken: the next layer's activation codes are those of its own activation step applied to
+    the bf16 value this layer would have stored, Q(bf16_rne(y)) -- so a fused epilogue that emits codes instead of
+    bf16 changes no bit of the two-call path.  Y_bits: M x N uint16 (bf16 bits), N = pk_next.K."""
+    return quantize_act_mxi(bf16_bits_to_f32(np.asarray(Y_bits, np.uint16)), pk_next)
+
+
 def fwd_mxi(pk: PackedMxi, act: ActMxi) -> FwdOut:
     M, N, K, r = act.M, pk.N, pk.K, pk.r
     out = FwdOut(None, None, np.empty((M, N), np.float32), np.empty((M, N), np.float32),

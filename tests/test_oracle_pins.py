@@ -1331,3 +1331,54 @@ def test_rot_errors_with_mx_branch_formats(oracle, q2, bits, half_ulp):
                 assert np.all(np.abs(m * 16 - np.rint(m * 16)) < 1e-4)
     assert out.loss == pytest.approx(np.mean(out.E1.astype(np.float64) ** 2) + np.mean(out.E2.astype(np.float64) ** 2), rel=1e-12)
     assert out.loss > 0
+
+
+# ---------------------------------------------------------------------------------------
+# quantized hand-off between two linears (Section 4.5)
+# ---------------------------------------------------------------------------------------
+def _mxi_layer(oracle, rng, N, K, r, bw=8):
+    W = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    L = (rng.standard_normal((N, r)) * 0.02).astype(np.float32)
+    R = (rng.standard_normal((r, K)) * 0.02).astype(np.float32)
+    return oracle.pack_mxi(W, L, R, bw)
+
+
+def test_handoff_is_the_next_activation_step_on_the_bf16_output(oracle):
+    rng = np.random.default_rng(31)
+    M, K1, N1, N2, r = 9, 128, 192, 64, 32
+    pk1 = _mxi_layer(oracle, rng, N1, K1, r)
+    pk2 = _mxi_layer(oracle, rng, N2, N1, r)
+    X = rng.standard_normal((M, K1)).astype(np.float32)
+    out1 = oracle.fwd_mxi(pk1, oracle.quantize_act_mxi(X, pk1))
+    ho = oracle.handoff_mxi(out1.Y, pk2)
+    ref = oracle.quantize_act_mxi(oracle.bf16_bits_to_f32(out1.Y), pk2)
+    for f in ("xq", "xe", "xb", "xbe", "T", "tq", "te"):
+        assert np.array_equal(getattr(ho, f), getattr(ref, f)), f
+    # the second layer's output through the hand-off equals the two-call path bit for bit
+    assert np.array_equal(oracle.fwd_mxi(pk2, ho).Y, oracle.fwd_mxi(pk2, ref).Y)
+    # every hand-off scale and code belongs to 32 consecutive output channels of the producing layer: codes of one
+    # block do not move when any other column of Y changes (what makes a tile-local epilogue legal) ...
+    Y2 = out1.Y.copy()
+    Y2[:, 32:] = Y2[:, 32:][:, ::-1]
+    ho2 = oracle.handoff_mxi(Y2, pk2)
+    assert np.array_equal(ho2.xq[:, :32], ho.xq[:, :32]) and np.array_equal(ho2.xe[:, 0], ho.xe[:, 0])
+    assert np.array_equal(ho2.xb[:, :32], ho.xb[:, :32]) and np.array_equal(ho2.xbe[:, 0], ho.xbe[:, 0])
+    # ... while the skinny contraction of the next layer runs over the whole row
+    assert not np.array_equal(ho2.T, ho.T)
+
+
+def test_handoff_codes_come_from_the_bf16_value_not_from_the_fp32_sum(oracle):
+    """The reading pinned on a constructed row: a block whose largest value is 4 has MXINT8 step 1/16; the fp32 value
+    2^-5 + 2^-14 lies above the tie between codes 0 and 1, its bf16 rounding (a tie at spacing 2^-13, to even) is
+    exactly 2^-5, the tie itself, which goes to the even code 0."""
+    rng = np.random.default_rng(32)
+    pk2 = _mxi_layer(oracle, rng, 64, 64, 32)
+    y32 = np.zeros((1, 64), np.float32)
+    y32[0, 0] = 4.0
+    y32[0, 1] = np.float32(2.0 ** -5 + 2.0 ** -14)
+    ybits = np.array([[oracle.bf16_rne(float(v)) for v in y32[0]]], np.uint16)
+    assert oracle.bf16_bits_to_f32(ybits)[0, 1] == np.float32(2.0 ** -5)
+    from_bf16 = oracle.handoff_mxi(ybits, pk2)
+    from_f32 = oracle.quantize_act_mxi(y32, pk2)
+    assert from_bf16.xbe[0, 0] == 127 + 2 and from_bf16.xb[0, 0] == 64
+    assert from_f32.xb[0, 1] == 1 and from_bf16.xb[0, 1] == 0
