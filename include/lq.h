@@ -180,6 +180,34 @@ lq_status lq_linear_lowrank_fwd(const lq_config *cfg, const void *packed, const 
                                 int64_t M, void *Y, int64_t ldy, const lq_fwd_debug *dbg,
                                 void *stream);
 
+/* Quantized hand-off between two linear layers (Section 4.5, "Method Efficiency": with quantized branches the
+   activations that move between layers are in the 8-, 6- or 4-bit MX formats instead of 16 bits).  Built for the integer
+   MX family (main_w = main_a = LQ_MXINT4, br_a = LQ_MXINT8 in both configurations) and a consuming layer whose K is the
+   producing layer's N.  The paper does not say from which value the consumer's codes are taken, nor where an
+   element-wise operation between the two linears would sit; the reading taken: the codes are those of the consumer's
+   own activation step applied to the bf16 value the producer would have stored, Q(bf16_rne(y)), and nothing sits
+   between the two linears (an operation in between has to consume and produce codes itself).  The two calls below
+   therefore fill `act_next` with exactly the bytes lq_quantize_act(next_cfg, packed_next, Y) would have written,
+   without Y (2 bytes per value) ever being stored or re-read: the producer's epilogue emits the consumer's main codes
+   and block scales (0.5 + 1/32 bytes per value) straight into `act_next`, and its MXINT8 branch codes and scale bytes
+   (1 + 1/32 bytes per value) into `codes`; every one of these belongs to 32 consecutive output channels, which one
+   wavefront of the forward owns.  The consumer's skinny contraction runs over the whole row, so it stays a kernel of its
+   own that reads the codes: lq_branch_from_codes.
+     lq_handoff_sizes           bytes of the `codes` buffer for M tokens of the consuming layer.
+     lq_linear_lowrank_fwd_handoff   lq_linear_lowrank_fwd plus the hand-off.  Y may be NULL (nothing is stored then);
+                                with Y the bf16 output is written as well.  act_next: device, 256-byte aligned, at
+                                least lq_act_sizes(next_cfg, M) bytes; codes: device, 256-byte aligned.
+     lq_branch_from_codes       completes act_next (intermediate codes and scales of the consumer's branch) from `codes`;
+                                a no-op for a consumer of rank 0.
+   Errors as for the calls they extend; a configuration pair outside the family, or next_cfg->K != cfg->N:
+   LQ_ERR_UNSUPPORTED / LQ_ERR_SHAPE before any launch. */
+lq_status lq_handoff_sizes(const lq_config *next_cfg, int64_t M, size_t *codes_bytes);
+lq_status lq_linear_lowrank_fwd_handoff(const lq_config *cfg, const void *packed, const void *act, int64_t M, void *Y,
+                                        int64_t ldy, const lq_config *next_cfg, void *act_next, size_t act_next_bytes,
+                                        void *codes, size_t codes_bytes, void *stream);
+lq_status lq_branch_from_codes(const lq_config *next_cfg, const void *packed_next, const void *codes, size_t codes_bytes,
+                               int64_t M, void *act_next, size_t act_next_bytes, void *stream);
+
 /* Decode the opaque blobs into plain row-major arrays (test / inspection helpers). */
 lq_status lq_unpack_weights(const lq_config *cfg, const void *packed, const lq_weights_view *out,
                             void *stream);

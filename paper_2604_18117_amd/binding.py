@@ -71,7 +71,8 @@ class lq_rot_view(C.Structure):
 
 
 EXPORTS = ["lq_status_string", "lq_packed_sizes", "lq_pack_weights", "lq_set_smoothing", "lq_act_sizes", "lq_quantize_act",
-           "lq_linear_lowrank_fwd", "lq_unpack_weights", "lq_unpack_act", "lq_calib_sizes", "lq_calib_init", "lq_calib_step",
+           "lq_linear_lowrank_fwd", "lq_handoff_sizes", "lq_linear_lowrank_fwd_handoff", "lq_branch_from_codes",
+           "lq_unpack_weights", "lq_unpack_act", "lq_calib_sizes", "lq_calib_init", "lq_calib_step",
            "lq_calib_unpack", "lq_rot_sizes", "lq_rot_init", "lq_rot_step", "lq_rot_step_static", "lq_rot_apply", "lq_rot_unpack"]
 
 _lib.lq_calib_sizes.argtypes = [C.POINTER(lq_config), C.POINTER(C.c_size_t)]
@@ -97,6 +98,11 @@ _lib.lq_quantize_act.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C
                                  C.c_void_p, C.c_size_t, C.POINTER(lq_act_debug), C.c_void_p]
 _lib.lq_linear_lowrank_fwd.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                                        C.c_int64, C.POINTER(lq_fwd_debug), C.c_void_p]
+_lib.lq_handoff_sizes.argtypes = [C.POINTER(lq_config), C.c_int64, C.POINTER(C.c_size_t)]
+_lib.lq_linear_lowrank_fwd_handoff.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                               C.POINTER(lq_config), C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.lq_branch_from_codes.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_size_t, C.c_int64, C.c_void_p,
+                                      C.c_size_t, C.c_void_p]
 _lib.lq_unpack_weights.argtypes = [C.POINTER(lq_config), C.c_void_p, C.POINTER(lq_weights_view), C.c_void_p]
 _lib.lq_unpack_act.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_int64, C.POINTER(lq_act_view), C.c_void_p]
 
@@ -249,6 +255,37 @@ def lq_linear_lowrank_fwd(cfg: lq_config, packed: torch.Tensor, act: torch.Tenso
                                       C.byref(dbg) if dbg is not None else None, C.c_void_p(_stream())),
            "lq_linear_lowrank_fwd")
     return (Y, taps) if debug else Y
+
+
+def lq_handoff_sizes(next_cfg: lq_config, M: int) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.lq_handoff_sizes(C.byref(next_cfg), M, C.byref(n)), "lq_handoff_sizes")
+    return int(n.value)
+
+
+def lq_linear_lowrank_fwd_handoff(cfg: lq_config, packed: torch.Tensor, act: torch.Tensor, M: int, next_cfg: lq_config,
+                                  act_next: Optional[torch.Tensor] = None, codes: Optional[torch.Tensor] = None,
+                                  Y: Optional[torch.Tensor] = None):
+    """The forward plus the quantized hand-off to a next layer (K = this N).  Returns (act_next, codes); Y (M x N bf16)
+    is written only when given."""
+    if act_next is None:
+        act_next = torch.empty(lq_act_sizes(next_cfg, M), dtype=torch.uint8, device=act.device)
+    if codes is None:
+        codes = torch.empty(lq_handoff_sizes(next_cfg, M), dtype=torch.uint8, device=act.device)
+    if Y is not None:
+        assert Y.is_cuda and Y.dtype == torch.bfloat16 and Y.stride(1) == 1 and Y.shape == (M, cfg.N)
+    _check(_lib.lq_linear_lowrank_fwd_handoff(C.byref(cfg), _ptr(packed), _ptr(act), M, _ptr(Y), Y.stride(0) if Y is not None else 0,
+                                              C.byref(next_cfg), _ptr(act_next), act_next.numel(), _ptr(codes), codes.numel(),
+                                              C.c_void_p(_stream())), "lq_linear_lowrank_fwd_handoff")
+    return act_next, codes
+
+
+def lq_branch_from_codes(next_cfg: lq_config, packed_next: torch.Tensor, codes: torch.Tensor, M: int,
+                         act_next: torch.Tensor) -> torch.Tensor:
+    """Completes act_next (the consumer's intermediate codes and scales) from the hand-off codes."""
+    _check(_lib.lq_branch_from_codes(C.byref(next_cfg), _ptr(packed_next), _ptr(codes), codes.numel(), M, _ptr(act_next),
+                                     act_next.numel(), C.c_void_p(_stream())), "lq_branch_from_codes")
+    return act_next
 
 
 @dataclass

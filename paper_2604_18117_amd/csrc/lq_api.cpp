@@ -241,6 +241,69 @@ lq_status lq_linear_lowrank_fwd(const lq_config* cfg, const void* packed, const 
     return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }
 
+static lq_status handoff_dims(const lq_config* next_cfg, Dims* dn)
+{
+    lq_status st = make_dims(next_cfg, dn);
+    if (st != LQ_OK) return st;
+    if (!dn->mxi || dn->smooth) return LQ_ERR_UNSUPPORTED;  // integer MX family; smoothing has no place in a hand-off
+    return LQ_OK;
+}
+
+lq_status lq_handoff_sizes(const lq_config* next_cfg, int64_t M, size_t* codes_bytes)
+{
+    if (!next_cfg || !codes_bytes) return LQ_ERR_NULL;
+    Dims dn;
+    lq_status st = handoff_dims(next_cfg, &dn);
+    if (st != LQ_OK) return st;
+    if (M < 0 || M > (1 << 24)) return LQ_ERR_SHAPE;
+    *codes_bytes = handoff_total_bytes(dn, M);
+    return LQ_OK;
+}
+
+lq_status lq_linear_lowrank_fwd_handoff(const lq_config* cfg, const void* packed, const void* act, int64_t M, void* Y,
+                                        int64_t ldy, const lq_config* next_cfg, void* act_next, size_t act_next_bytes,
+                                        void* codes, size_t codes_bytes, void* stream)
+{
+    Dims d, dn;
+    lq_status st = make_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!next_cfg) return LQ_ERR_NULL;
+    st = handoff_dims(next_cfg, &dn);
+    if (st != LQ_OK) return st;
+    if (!d.mxi) return LQ_ERR_UNSUPPORTED;
+    if (dn.K != d.N) return LQ_ERR_SHAPE;
+    if (M == 0) return LQ_OK;  // an empty batch
+    if (!packed || !act || !act_next || !codes) return LQ_ERR_NULL;
+    if (M < 1 || M > (1 << 24) || (Y && ldy < d.N)) return LQ_ERR_SHAPE;
+    if (!aligned(packed, 256) || !aligned(act, 256) || !aligned(act_next, 256) || !aligned(codes, 256) ||
+        (Y && (!aligned(Y, 16) || (ldy & 7))))
+        return LQ_ERR_ALIGN;
+    if (act_next_bytes < act_layout(dn, M).total || codes_bytes < handoff_total_bytes(dn, M)) return LQ_ERR_BUFFER_TOO_SMALL;
+    return launch_fwd_handoff_mxi(d, (const uint8_t*)packed, (const uint8_t*)act, M, (uint16_t*)Y, Y ? ldy : d.N, dn,
+                                  (uint8_t*)act_next, (uint8_t*)codes, (hipStream_t)stream) == hipSuccess
+               ? LQ_OK
+               : LQ_ERR_DEVICE;
+}
+
+lq_status lq_branch_from_codes(const lq_config* next_cfg, const void* packed_next, const void* codes, size_t codes_bytes,
+                               int64_t M, void* act_next, size_t act_next_bytes, void* stream)
+{
+    Dims dn;
+    if (!next_cfg) return LQ_ERR_NULL;
+    lq_status st = handoff_dims(next_cfg, &dn);
+    if (st != LQ_OK) return st;
+    if (M == 0) return LQ_OK;
+    if (!codes || !act_next || (dn.r > 0 && !packed_next)) return LQ_ERR_NULL;
+    if (M < 1 || M > (1 << 24)) return LQ_ERR_SHAPE;
+    if (!aligned(codes, 256) || !aligned(act_next, 256) || (packed_next && !aligned(packed_next, 256))) return LQ_ERR_ALIGN;
+    if (act_next_bytes < act_layout(dn, M).total || codes_bytes < handoff_total_bytes(dn, M)) return LQ_ERR_BUFFER_TOO_SMALL;
+    if (dn.r == 0) return LQ_OK;
+    return launch_branch_from_codes_mxi(dn, (const uint8_t*)packed_next, (const uint8_t*)codes, M, (uint8_t*)act_next,
+                                        (hipStream_t)stream) == hipSuccess
+               ? LQ_OK
+               : LQ_ERR_DEVICE;
+}
+
 lq_status lq_unpack_weights(const lq_config* cfg, const void* packed, const lq_weights_view* out, void* stream)
 {
     Dims d;

@@ -148,6 +148,17 @@ hipError_t launch_quantize_act_mxi(const Dims& d, int x_dtype, const uint8_t* pa
 hipError_t launch_fwd_mxi(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M,
                           uint16_t* Y, int64_t ldy, const lq_fwd_debug* dbg, hipStream_t s);
 
+// Quantized hand-off between two MXINT layers (Section 4.5; lq_mxi.hip): the producing layer's forward also writes the
+// consuming layer's main codes and scales into its activation blob and its MXINT8 branch codes into a hand-off buffer
+// ([Mp][K] code bytes, then [Mp][K/32] E8M0 bytes, each section 256-byte aligned); the consuming layer's branch step then
+// runs from those codes.
+size_t handoff_codes_bytes(const Dims& next, int64_t M);
+size_t handoff_total_bytes(const Dims& next, int64_t M);
+hipError_t launch_fwd_handoff_mxi(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M, uint16_t* Y, int64_t ldy,
+                                  const Dims& next, uint8_t* act_next, uint8_t* codes, hipStream_t s);
+hipError_t launch_branch_from_codes_mxi(const Dims& d, const uint8_t* packed, const uint8_t* codes, int64_t M, uint8_t* act,
+                                        hipStream_t s);
+
 // Calibration state (lq_calib.hip): plain row-major fp32 sections, each 256-byte aligned.
 struct CalibLayout {
     size_t off_L, off_R;       // factors, N x r and r x K

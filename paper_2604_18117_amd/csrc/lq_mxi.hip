@@ -265,6 +265,8 @@ hipError_t launch_unpack_act_mxi(const Dims& d, const uint8_t* act, int64_t M, c
 // ---------------------------------------------------------------------------------------------
 struct MxiActParams {
     const void* X;
+    const int8_t* cb;    // from-codes variant: M x K MXINT8 codes of a quantized hand-off, row-major
+    const uint8_t* cbe;  // ... and their E8M0 bytes, M x K/32
     int64_t ldx;
     int M, K, C64, CQ, r, rp;
     const uint8_t* rv;
@@ -334,7 +336,10 @@ __device__ __forceinline__ uint32_t bf16_pair(float lo, float hi)  // upper halv
 }
 
 // BF16IN: element type of X; SM: smoothing variant (X times the stored reciprocals, held as fp32).
-template <bool BF16IN, int NJB, bool SM = false>
+// FROMC: the branch half of the step alone, from the MXINT8 codes of a quantized hand-off (the producing layer's
+// epilogue has already written this layer's main codes and scales): 16 code bytes and a scale byte replace the 16 values
+// of X, code * 2^(s-6) is the dequantised bf16 element; the contraction and the re-quantisation are the same code.
+template <bool BF16IN, int NJB, bool SM = false, bool FROMC = false>
 __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
 {
     constexpr bool BF16 = BF16IN && !SM;  // representation of a chunk in registers
@@ -353,7 +358,17 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
     // is refilled as soon as its chunk has been coded.
     MxiChunk<BF16> xc[PF];
     auto load_x = [&](MxiChunk<BF16>& ch, size_t koff, bool ok) {
-        if constexpr (SM)
+        if constexpr (FROMC) {  // 16 code bytes in w[0..3], the block's scale byte in w[4]
+            static_assert(!FROMC || (BF16IN && !SM), "the from-codes variant reuses the packed chunk registers");
+            v4i a = {0, 0, 0, 0};
+            uint32_t e = 0u;
+            if (ok) {
+                a = *(const v4i*)(p.cb + (size_t)row * p.K + koff);
+                e = p.cbe[(size_t)row * (p.K >> 5) + (koff >> 5)];
+            }
+            ch.w[0] = a[0]; ch.w[1] = a[1]; ch.w[2] = a[2]; ch.w[3] = a[3];
+            ch.w[4] = e;
+        } else if constexpr (SM)
             smooth_load<BF16IN, 16>(ch.v, p.X, (size_t)row * p.ldx + koff, p.rg + koff, ok);
         else
             ch.load(p.X, (size_t)row * p.ldx + koff, ok);
@@ -386,59 +401,71 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
         const int c = wave + 4 * ci;
         if constexpr (RB == 2) load_r((sl + 1) & 1, ci + 1);
         if (ci < nmy) {  // wave-uniform
-            float m = 0.f;
-            if constexpr (BF16) {
-                // |bf16| is monotonic in its low 15 bits: packed unsigned 16-bit max, two values per op
-                us2 m2 = {0, 0};
-#pragma unroll
-                for (int d = 0; d < 8; ++d) m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, xc[sl].w[d] & 0x7FFF7FFFu));
-                const uint32_t mm = m2[0] > m2[1] ? m2[0] : m2[1];
-                m = __uint_as_float(mm << 16);
+            uint32_t field;
+            if constexpr (FROMC) {
+                field = xc[sl].w[4];
             } else {
+                float m = 0.f;
+                if constexpr (BF16) {
+                    // |bf16| is monotonic in its low 15 bits: packed unsigned 16-bit max, two values per op
+                    us2 m2 = {0, 0};
 #pragma unroll
-                for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(xc[sl].get(i)));
-            }
-            const float ab = fmaxf(m, __shfl_xor(m, 16, 64));  // block of 32 = lanes kq, kq ^ 1
-            const uint32_t field = exp_field(ab);
-            // ---- main codes: MXINT4.  code = min(rne(|x| * 2^(2-s)), 7), sign kept apart
-            const float inv4 = field >= 2u ? __uint_as_float((256u - field) << 23) : 0.0f;  // 2^(2-s)
-            uint32_t pk[2] = {0u, 0u};
-            if constexpr (BF16) {
-                // |x|*inv + 2^23 has the code in its low bits and 0x4B in its top byte; eight of them
-                // are summed at their nibble positions (the top bytes shifted by 0 and 4 add up to the
-                // constant removed first, the others leave the dword); signs by one byte permute per four
+                    for (int d = 0; d < 8; ++d) m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, xc[sl].w[d] & 0x7FFF7FFFu));
+                    const uint32_t mm = m2[0] > m2[1] ? m2[0] : m2[1];
+                    m = __uint_as_float(mm << 16);
+                } else {
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    uint32_t sum = 0u - 0xFB000000u;
+                    for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(xc[sl].get(i)));
+                }
+                const float ab = fmaxf(m, __shfl_xor(m, 16, 64));  // block of 32 = lanes kq, kq ^ 1
+                field = exp_field(ab);
+                // ---- main codes: MXINT4.  code = min(rne(|x| * 2^(2-s)), 7), sign kept apart
+                const float inv4 = field >= 2u ? __uint_as_float((256u - field) << 23) : 0.0f;  // 2^(2-s)
+                uint32_t pk[2] = {0u, 0u};
+                if constexpr (BF16) {
+                    // |x|*inv + 2^23 has the code in its low bits and 0x4B in its top byte; eight of them
+                    // are summed at their nibble positions (the top bytes shifted by 0 and 4 add up to the
+                    // constant removed first, the others leave the dword); signs by one byte permute per four
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float x = xc[sl].get(8 * h + e);
-                        const uint32_t mb = __float_as_uint(__fadd_rn(fminf(__fmul_rn(fabsf(x), inv4), 7.0f), 8388608.0f));
-                        const int sh = e < 4 ? 8 * e : 8 * ((e - 5) & 3) + 4;
-                        sum += mb << sh;
+                    for (int h = 0; h < 2; ++h) {
+                        uint32_t sum = 0u - 0xFB000000u;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float x = xc[sl].get(8 * h + e);
+                            const uint32_t mb = __float_as_uint(__fadd_rn(fminf(__fmul_rn(fabsf(x), inv4), 7.0f), 8388608.0f));
+                            const int sh = e < 4 ? 8 * e : 8 * ((e - 5) & 3) + 4;
+                            sum += mb << sh;
+                        }
+                        const uint32_t* w = &xc[sl].w[4 * h];
+                        const uint32_t s03 = __builtin_amdgcn_perm(w[1], w[0], 0x07050301u);
+                        const uint32_t s47 = __builtin_amdgcn_perm(w[3], w[2], 0x07050301u);
+                        pk[h] = sum | (s03 & 0x80808080u) | ((s47 >> 4) & 0x08080808u);
                     }
-                    const uint32_t* w = &xc[sl].w[4 * h];
-                    const uint32_t s03 = __builtin_amdgcn_perm(w[1], w[0], 0x07050301u);
-                    const uint32_t s47 = __builtin_amdgcn_perm(w[3], w[2], 0x07050301u);
-                    pk[h] = sum | (s03 & 0x80808080u) | ((s47 >> 4) & 0x08080808u);
-                }
-            } else {
+                } else {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float x = xc[sl].get(i);
-                    const uint32_t mg = __float_as_uint(__fadd_rn(fminf(__fmul_rn(fabsf(x), inv4), 7.0f), 8388608.0f)) & 7u;
-                    pk[i >> 3] |= nib_put(i & 7, __float_as_uint(x) >> 31, mg);
+                    for (int i = 0; i < 16; ++i) {
+                        const float x = xc[sl].get(i);
+                        const uint32_t mg = __float_as_uint(__fadd_rn(fminf(__fmul_rn(fabsf(x), inv4), 7.0f), 8388608.0f)) & 7u;
+                        pk[i >> 3] |= nib_put(i & 7, __float_as_uint(x) >> 31, mg);
+                    }
                 }
+                // lane (row, kq): block kq>>1 of the chunk, K half-block h = kq&1 -> dwords 2*(kq>>1), +1 of lane (row, h)
+                uint8_t* dst = p.xq + ((size_t)((size_t)(row >> 5) * C64 + c) * 64 + (row & 31) + 32 * (kq & 1)) * 16 + (kq >> 1) * 8;
+                *(uint2*)dst = make_uint2(pk[0], pk[1]);
+                if ((kq & 1) == 0) p.xe[mxi_scale_offset(row, c, kq >> 1, p.CQ)] = (uint8_t)(field + 7u);
             }
-            // lane (row, kq): block kq>>1 of the chunk, K half-block h = kq&1 -> dwords 2*(kq>>1), +1 of lane (row, h)
-            uint8_t* dst = p.xq + ((size_t)((size_t)(row >> 5) * C64 + c) * 64 + (row & 31) + 32 * (kq & 1)) * 16 + (kq >> 1) * 8;
-            *(uint2*)dst = make_uint2(pk[0], pk[1]);
-            if ((kq & 1) == 0) p.xe[mxi_scale_offset(row, c, kq >> 1, p.CQ)] = (uint8_t)(field + 7u);
             if (NJB > 0) {
                 // ---- branch: MXINT8 of the same block, kept as dequantised bf16
                 float v8[16];
+                if constexpr (FROMC) {  // code * 2^(s-6): exact, at most 7 significant bits
+                    const float step = field >= 7u ? __uint_as_float((field - 6u) << 23) : 0.0f;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) v8[i] = mxint8_round(xc[sl].get(i), field);
+                    for (int i = 0; i < 16; ++i)
+                        v8[i] = __fmul_rn((float)(int)(int8_t)((xc[sl].w[i >> 2] >> (8 * (i & 3))) & 0xFFu), step);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) v8[i] = mxint8_round(xc[sl].get(i), field);
+                }
                 v4i au[2];
 #pragma unroll
                 for (int u = 0; u < 2; ++u)
@@ -465,7 +492,7 @@ __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
         load_x(xc[sl], (size_t)(c + 4 * PF) * 64 + kq * 16, row_ok && ci + PF < nmy);
     }
     }
-    {   // padding chunk of the last quad (at most one per wavefront): its scale bytes must be valid E8M0 values (2^0)
+    if constexpr (!FROMC) {   // padding chunk of the last quad (at most one per wavefront): its scale bytes must be valid E8M0 values (2^0)
         const int c = wave + 4 * nmy;
         if (c < 4 * p.CQ && (kq & 1) == 0) p.xe[mxi_scale_offset(row, c, kq >> 1, p.CQ)] = (uint8_t)127;
     }
@@ -538,6 +565,37 @@ static hipError_t mxi_act_rank(const MxiActParams& p, int64_t Mp, hipStream_t s)
     return p.rg ? mxi_act_rank2<BF16, true>(p, Mp, s) : mxi_act_rank2<BF16, false>(p, Mp, s);
 }
 
+// The branch half of the activation step from the codes of a quantized hand-off (see mxi_act_kernel, FROMC).
+hipError_t launch_branch_from_codes_mxi(const Dims& d, const uint8_t* packed, const uint8_t* codes, int64_t M, uint8_t* act,
+                                        hipStream_t s)
+{
+    const PackedLayout pl = packed_layout(d);
+    const ActLayout al = act_layout(d, M);
+    MxiActParams p = {};
+    p.cb = (const int8_t*)codes;
+    p.cbe = codes + handoff_codes_bytes(d, M);
+    p.M = (int)M;
+    p.K = (int)d.K;
+    p.C64 = d.C64;
+    p.CQ = (d.C64 + 3) / 4;
+    p.r = d.r;
+    p.rp = d.rp;
+    p.rv = packed + pl.off_rq;
+    p.xq = act + al.off_xq;
+    p.xe = act + al.off_sx;
+    p.tv = act + al.off_tq;
+    p.te = act + al.off_st;
+    const unsigned grid = (unsigned)(al.Mp / 16);
+    switch (d.r) {
+        case 32: hipLaunchKernelGGL((mxi_act_kernel<true, 2, false, true>), dim3(grid), dim3(256), 0, s, p); break;
+        case 64: hipLaunchKernelGGL((mxi_act_kernel<true, 4, false, true>), dim3(grid), dim3(256), 0, s, p); break;
+        case 96: hipLaunchKernelGGL((mxi_act_kernel<true, 6, false, true>), dim3(grid), dim3(256), 0, s, p); break;
+        case 128: hipLaunchKernelGGL((mxi_act_kernel<true, 8, false, true>), dim3(grid), dim3(256), 0, s, p); break;
+        default: break;  // rank 0: the next layer has no branch, its blob is complete after the producing layer's epilogue
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_quantize_act_mxi(const Dims& d, int x_dtype, const uint8_t* packed, const void* X, int64_t M,
                                    int64_t ldx, uint8_t* act, const lq_act_debug* dbg, hipStream_t s)
 {
@@ -545,6 +603,8 @@ hipError_t launch_quantize_act_mxi(const Dims& d, int x_dtype, const uint8_t* pa
     const ActLayout al = act_layout(d, M);
     MxiActParams p;
     p.X = X;
+    p.cb = nullptr;
+    p.cbe = nullptr;
     p.ldx = ldx;
     p.M = (int)M;
     p.K = (int)d.K;
@@ -579,6 +639,13 @@ struct MxiFwdParams {
     int M, N, C64, CQ, nrb;
     int tilesM, tilesN, panel;
     float* dbg_y32;
+    // quantized hand-off to a next MXINT layer whose K is this layer's N (HO variant): its main codes and scale bytes
+    // (sections of its activation blob) and its MXINT8 branch codes and scale bytes (row-major, for the from-codes step)
+    uint8_t* ho_xq;
+    uint8_t* ho_xe;
+    int8_t* ho_cb;
+    uint8_t* ho_cbe;
+    int ho_C64, ho_CQ;
 };
 
 __device__ __forceinline__ v8i mxi_expand8(v4i p)  // 32 nibbles -> 32 FP8 subnormal bytes
@@ -592,8 +659,9 @@ __device__ __forceinline__ v8i mxi_expand8(v4i p)  // 32 nibbles -> 32 FP8 subno
     return o;
 }
 
-// NK16 = 16-deep chunks of the rank: 0 | 2 | 4 | 6 | 8
-template <int NK16, bool DBG>
+// NK16 = 16-deep chunks of the rank: 0 | 2 | 4 | 6 | 8.  HO: quantized hand-off (Section 4.5): the epilogue also emits
+// the next layer's activation codes from the bf16 values it has just formed; Y itself is optional then.
+template <int NK16, bool DBG, bool HO = false>
 __global__ __launch_bounds__(256, 2) void mxi_fwd_kernel(MxiFwdParams p)
 {
     constexpr int RBT = 4;
@@ -800,9 +868,55 @@ __global__ __launch_bounds__(256, 2) void mxi_fwd_kernel(MxiFwdParams p)
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) ov[q] = *(const v4i*)(stage + (q * 8 + rd_row) * EPI_ROW + rd_seg * 16);
+        if constexpr (HO) {
+            // The lane holds 8 consecutive channels of one token as bf16; a block of 32 channels of the next layer's K
+            // axis is the 4 lanes that differ in the two low lane bits.  Codes as in the activation kernel: shared
+            // exponent from the block maximum, MXINT4 main codes (sign-magnitude nibbles), MXINT8 branch codes.
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int row = rbase + q * 8 + rd_row;
+                const uint32_t w[4] = {(uint32_t)ov[q][0], (uint32_t)ov[q][1], (uint32_t)ov[q][2], (uint32_t)ov[q][3]};
+                us2 m2 = {0, 0};
+#pragma unroll
+                for (int d = 0; d < 4; ++d) m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2, w[d] & 0x7FFF7FFFu));
+                uint32_t mm = m2[0] > m2[1] ? m2[0] : m2[1];
+                float am = __uint_as_float(mm << 16);
+                am = fmaxf(am, __shfl_xor(am, 1, 64));
+                am = fmaxf(am, __shfl_xor(am, 2, 64));
+                const uint32_t field = exp_field(am);
+                const float inv4 = field >= 2u ? __uint_as_float((256u - field) << 23) : 0.0f;   // 2^(2-s)
+                const float to8 = field >= 7u ? __uint_as_float((260u - field) << 23) : 0.0f;    // 2^(6-s)
+                uint32_t sum = 0u - 0xFB000000u, c8[2] = {0u, 0u};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float x = __uint_as_float((e & 1) ? (w[e >> 1] & 0xFFFF0000u) : (w[e >> 1] << 16));
+                    const uint32_t mb = __float_as_uint(__fadd_rn(fminf(__fmul_rn(fabsf(x), inv4), 7.0f), 8388608.0f));
+                    const int sh = e < 4 ? 8 * e : 8 * ((e - 5) & 3) + 4;
+                    sum += mb << sh;
+                    const int code = (int)__fmul_rn(mxint8_round(x, field), to8);   // exact: a multiple of one step
+                    c8[e >> 2] |= ((uint32_t)code & 0xFFu) << (8 * (e & 3));
+                }
+                const uint32_t s03 = __builtin_amdgcn_perm(w[1], w[0], 0x07050301u);
+                const uint32_t s47 = __builtin_amdgcn_perm(w[3], w[2], 0x07050301u);
+                const uint32_t pk = sum | (s03 & 0x80808080u) | ((s47 >> 4) & 0x08080808u);
+                if (row < p.nrb * 32) {
+                    const int k0 = cb0 * 32 + rd_seg * 8;   // this layer's channel = the next layer's k
+                    *(uint32_t*)(p.ho_xq + mxi_frag_offset(row, k0, p.ho_C64)) = pk;
+                    *(uint2*)(p.ho_cb + (size_t)row * p.N + k0) = make_uint2(c8[0], c8[1]);
+                    if ((rd_seg & 3) == 0) {
+                        p.ho_xe[mxi_scale_offset(row, k0 >> 6, (k0 >> 5) & 1, p.ho_CQ)] = (uint8_t)(field + 7u);
+                        p.ho_cbe[(size_t)row * (p.N >> 5) + (k0 >> 5)] = (uint8_t)field;
+                        // padding chunks of the next layer's last quad: valid E8M0 bytes (2^0), written by the wavefront
+                        // that owns the last real chunk
+                        if ((k0 >> 6) == p.ho_C64 - 1)
+                            for (int c = p.ho_C64; c < 4 * p.ho_CQ; ++c) p.ho_xe[mxi_scale_offset(row, c, (k0 >> 5) & 1, p.ho_CQ)] = (uint8_t)127;
+                    }
+                }
+            }
+        }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if (rbase + q * 8 + rd_row < p.M) *(v4i*)yptr = ov[q];
+            if ((!HO || p.Y) && rbase + q * 8 + rd_row < p.M) *(v4i*)yptr = ov[q];
             yptr += ystep;
         }
     }
@@ -812,18 +926,60 @@ template <int NK16>
 static void mxi_fwd_launch(const MxiFwdParams& p, hipStream_t s)
 {
     dim3 grid((unsigned)(p.tilesM * p.tilesN)), block(256);
-    if (p.dbg_y32)
+    if (p.ho_xq)
+        hipLaunchKernelGGL((mxi_fwd_kernel<NK16, false, true>), grid, block, 0, s, p);
+    else if (p.dbg_y32)
         hipLaunchKernelGGL((mxi_fwd_kernel<NK16, true>), grid, block, 0, s, p);
     else
         hipLaunchKernelGGL((mxi_fwd_kernel<NK16, false>), grid, block, 0, s, p);
 }
 
+static hipError_t fwd_mxi_launches(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M, uint16_t* Y, int64_t ldy,
+                                   const lq_fwd_debug* dbg, const Dims* next, uint8_t* act_next, uint8_t* codes, hipStream_t s);
+
 hipError_t launch_fwd_mxi(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M, uint16_t* Y, int64_t ldy,
                           const lq_fwd_debug* dbg, hipStream_t s)
+{
+    return fwd_mxi_launches(d, packed, act, M, Y, ldy, dbg, nullptr, nullptr, nullptr, s);
+}
+
+// Forward with the quantized hand-off: `next` is the consuming layer (K = this layer's N), act_next its activation blob
+// (main codes and scales are written here), codes the hand-off buffer of its branch codes.  Y may be null.
+hipError_t launch_fwd_handoff_mxi(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M, uint16_t* Y, int64_t ldy,
+                                  const Dims& next, uint8_t* act_next, uint8_t* codes, hipStream_t s)
+{
+    return fwd_mxi_launches(d, packed, act, M, Y, ldy, nullptr, &next, act_next, codes, s);
+}
+
+size_t handoff_codes_bytes(const Dims& next, int64_t M)
+{
+    const int64_t Mp = (M + 31) / 32 * 32;
+    return align256((size_t)Mp * next.K);
+}
+size_t handoff_total_bytes(const Dims& next, int64_t M)
+{
+    const int64_t Mp = (M + 31) / 32 * 32;
+    return handoff_codes_bytes(next, M) + align256((size_t)Mp * (next.K / 32));
+}
+
+static hipError_t fwd_mxi_launches(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M, uint16_t* Y, int64_t ldy,
+                                   const lq_fwd_debug* dbg, const Dims* next, uint8_t* act_next, uint8_t* codes, hipStream_t s)
 {
     const PackedLayout pl = packed_layout(d);
     const ActLayout al = act_layout(d, M);
     MxiFwdParams p;
+    p.ho_xq = p.ho_xe = p.ho_cbe = nullptr;
+    p.ho_cb = nullptr;
+    p.ho_C64 = p.ho_CQ = 0;
+    if (next) {
+        const ActLayout an = act_layout(*next, M);
+        p.ho_xq = act_next + an.off_xq;
+        p.ho_xe = act_next + an.off_sx;
+        p.ho_cb = (int8_t*)codes;
+        p.ho_cbe = codes + handoff_codes_bytes(*next, M);
+        p.ho_C64 = next->C64;
+        p.ho_CQ = (next->C64 + 3) / 4;
+    }
     p.xq = act + al.off_xq;
     p.xe = act + al.off_sx;
     p.tv = act + al.off_tq;

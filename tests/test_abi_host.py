@@ -296,3 +296,37 @@ def test_calibration_contract(lq):
     bad = lq.lq_adam(0.0, 0.9, 0.999, 1e-8)
     assert raw.lq_calib_step(C.byref(cfg), good, good, sb, 1, C.byref(bad), None, None) == lq.LQ_ERR_UNSUPPORTED
     assert raw.lq_calib_unpack(C.byref(cfg), good, None, None) == lq.LQ_ERR_NULL
+
+
+def test_handoff_contract(lq):
+    """Quantized hand-off: integer MX family on both sides, the consumer's K = the producer's N; every error is
+    reported before any launch (no GPU needed)."""
+    raw = lq.raw()
+    n = C.c_size_t(0)
+    prod = lq.make_config(320, 256, 32, "mxi", 32, 8, 8)
+    cons = lq.make_config(128, 320, 64, "mxi", 32, 8, 8)
+    assert raw.lq_handoff_sizes(C.byref(cons), 100, C.byref(n)) == lq.LQ_OK
+    al = lambda x: (x + 255) // 256 * 256
+    assert n.value == al(128 * 320) + al(128 * 10)          # Mp = 128 rows: one code byte per value, one scale byte per 32
+    assert raw.lq_handoff_sizes(C.byref(_cfg(lq)), 100, C.byref(n)) == lq.LQ_ERR_UNSUPPORTED        # INT family
+    assert raw.lq_handoff_sizes(C.byref(_cfg(lq, family="mx", K=256)), 100, C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
+    assert raw.lq_handoff_sizes(None, 100, C.byref(n)) == lq.LQ_ERR_NULL
+    fake = C.c_void_p(0x1000)     # aligned, never dereferenced: the checks below fail first
+    big = 1 << 40
+    call = lambda p, c, **kw: raw.lq_linear_lowrank_fwd_handoff(
+        C.byref(p), kw.get("packed", fake), fake, kw.get("M", 100), kw.get("Y", None), 0, C.byref(c), kw.get("act_next", fake),
+        kw.get("anb", big), kw.get("codes", fake), kw.get("cb", big), None)
+    assert call(prod, lq.make_config(128, 256, 64, "mxi", 32, 8, 8)) == lq.LQ_ERR_SHAPE          # K of the consumer != N
+    assert call(_cfg(lq, N=320), cons) == lq.LQ_ERR_UNSUPPORTED                                  # producer outside the family
+    assert call(prod, cons, packed=None) == lq.LQ_ERR_NULL
+    assert call(prod, cons, codes=None) == lq.LQ_ERR_NULL
+    assert call(prod, cons, act_next=C.c_void_p(0x1010)) == lq.LQ_ERR_ALIGN
+    assert call(prod, cons, anb=16) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert call(prod, cons, cb=16) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert call(prod, cons, M=0) == lq.LQ_OK                                                     # an empty batch
+    br = lambda c, **kw: raw.lq_branch_from_codes(C.byref(c), kw.get("packed", fake), kw.get("codes", fake), kw.get("cb", big),
+                                                  kw.get("M", 100), fake, kw.get("anb", big), None)
+    assert br(cons, packed=None) == lq.LQ_ERR_NULL
+    assert br(cons, cb=16) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert br(_cfg(lq)) == lq.LQ_ERR_UNSUPPORTED
+    assert br(lq.make_config(128, 320, 0, "mxi", 32, 8, 8), packed=None) == lq.LQ_OK             # rank 0: nothing to do
