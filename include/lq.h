@@ -62,8 +62,11 @@ typedef enum {
     LQ_ERR_UNSUPPORTED = 3,      /* format combination not implemented                   */
     LQ_ERR_ALIGN = 4,            /* a pointer or stride is not aligned as documented     */
     LQ_ERR_BUFFER_TOO_SMALL = 5, /* caller's buffer smaller than lq_*_sizes reports       */
-    LQ_ERR_DEVICE = 6            /* the HIP runtime rejected a launch                    */
+    LQ_ERR_DEVICE = 6,           /* the HIP runtime rejected a launch                    */
+    LQ_ERR_STALE_BLOB = 7        /* lq_verify_blob: the blob's header belongs to another configuration, token count or layout version */
 } lq_status;
+
+typedef enum { LQ_BLOB_PACKED = 1, LQ_BLOB_ACT = 2 } lq_blob_kind;
 
 typedef enum {
     LQ_INT4 = 0,
@@ -158,6 +161,15 @@ lq_status lq_pack_weights(const lq_config *cfg, const float *W, const float *L, 
    call the blob holds reciprocals 1.0 (lq_pack_weights writes them).  LQ_ERR_UNSUPPORTED without the flag. */
 lq_status lq_set_smoothing(const lq_config *cfg, const float *gamma, void *packed, size_t packed_bytes,
                            void *stream);
+
+/* Both blobs start with a 256-byte header (magic, layout version, kind, a hash of every field of the configuration, the
+   token count of an activation blob, N, K) that lq_pack_weights and the activation step write.  The per-call entry
+   points never read device memory on the host (that would put a synchronising copy on an asynchronous path), so they
+   cannot notice a blob that was packed under another configuration, written for another M, or produced by an older
+   layout: lq_verify_blob is the explicit check for callers that load blobs from elsewhere.  It copies the header to the
+   host and therefore SYNCHRONISES `stream`.  kind: lq_blob_kind; M: the token count for LQ_BLOB_ACT (ignored otherwise);
+   blob_bytes must cover the blob of that configuration (LQ_ERR_BUFFER_TOO_SMALL).  LQ_ERR_STALE_BLOB on a mismatch. */
+lq_status lq_verify_blob(const lq_config *cfg, int32_t kind, const void *blob, size_t blob_bytes, int64_t M, void *stream);
 
 /* Bytes of the activation blob for M tokens.  Host-only. */
 lq_status lq_act_sizes(const lq_config *cfg, int64_t M, size_t *act_bytes);

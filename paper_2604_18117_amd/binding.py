@@ -20,7 +20,8 @@ if not os.path.exists(_LIB_PATH):
 _lib = C.CDLL(_LIB_PATH)
 
 LQ_OK = 0
-LQ_ERR_NULL, LQ_ERR_SHAPE, LQ_ERR_UNSUPPORTED, LQ_ERR_ALIGN, LQ_ERR_BUFFER_TOO_SMALL, LQ_ERR_DEVICE = range(1, 7)
+LQ_ERR_NULL, LQ_ERR_SHAPE, LQ_ERR_UNSUPPORTED, LQ_ERR_ALIGN, LQ_ERR_BUFFER_TOO_SMALL, LQ_ERR_DEVICE, LQ_ERR_STALE_BLOB = range(1, 8)
+LQ_BLOB_PACKED, LQ_BLOB_ACT = 1, 2
 LQ_INT4, LQ_INT6, LQ_INT8, LQ_MXFP4_E2M1, LQ_FP8_E4M3, LQ_MXFP8_E4M3, LQ_MXINT4, LQ_MXINT8, LQ_MXFP6_E2M3 = range(9)
 LQ_F32, LQ_BF16 = 0, 1
 LQ_FLAG_SMOOTH = 1
@@ -70,7 +71,7 @@ class lq_rot_view(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in ("Omega", "Mom", "G", "E1", "E2")]
 
 
-EXPORTS = ["lq_status_string", "lq_packed_sizes", "lq_pack_weights", "lq_set_smoothing", "lq_act_sizes", "lq_quantize_act",
+EXPORTS = ["lq_status_string", "lq_packed_sizes", "lq_pack_weights", "lq_verify_blob", "lq_set_smoothing", "lq_act_sizes", "lq_quantize_act",
            "lq_linear_lowrank_fwd", "lq_handoff_sizes", "lq_linear_lowrank_fwd_handoff", "lq_branch_from_codes",
            "lq_unpack_weights", "lq_unpack_act", "lq_calib_sizes", "lq_calib_init", "lq_calib_step",
            "lq_calib_unpack", "lq_rot_sizes", "lq_rot_init", "lq_rot_step", "lq_rot_step_static", "lq_rot_apply", "lq_rot_unpack"]
@@ -93,6 +94,7 @@ _lib.lq_packed_sizes.argtypes = [C.POINTER(lq_config), C.POINTER(C.c_size_t)]
 _lib.lq_act_sizes.argtypes = [C.POINTER(lq_config), C.c_int64, C.POINTER(C.c_size_t)]
 _lib.lq_pack_weights.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_size_t, C.c_void_p]
+_lib.lq_verify_blob.argtypes = [C.POINTER(lq_config), C.c_int32, C.c_void_p, C.c_size_t, C.c_int64, C.c_void_p]
 _lib.lq_set_smoothing.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.lq_quantize_act.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
                                  C.c_void_p, C.c_size_t, C.POINTER(lq_act_debug), C.c_void_p]
@@ -171,6 +173,11 @@ def lq_set_smoothing(cfg: lq_config, packed: torch.Tensor, gamma: torch.Tensor) 
     assert gamma.is_cuda and gamma.dtype == torch.float32 and gamma.is_contiguous() and gamma.numel() == cfg.K
     _check(_lib.lq_set_smoothing(C.byref(cfg), _ptr(gamma), _ptr(packed), packed.numel(), C.c_void_p(_stream())),
            "lq_set_smoothing")
+
+
+def lq_verify_blob(cfg: lq_config, kind: int, blob: torch.Tensor, M: int = 0) -> None:
+    """Raises LqError(LQ_ERR_STALE_BLOB) when the blob's header does not belong to cfg (and M).  Synchronises the stream."""
+    _check(_lib.lq_verify_blob(C.byref(cfg), kind, _ptr(blob), blob.numel(), M, C.c_void_p(_stream())), "lq_verify_blob")
 
 
 def lq_act_sizes(cfg: lq_config, M: int) -> int:

@@ -39,6 +39,8 @@ struct ActParams {
     float* dbg_sxb;
     int32_t* dbg_accT;
     float* dbg_T;
+    BlobTag tag;        // header of the activation blob (written by the first workgroup)
+    uint32_t* tag_dst;
 };
 
 template <bool BF16>
@@ -150,6 +152,7 @@ __device__ __forceinline__ void f6_codes16(const float (&v)[16], uint32_t (&out)
 template <bool BF16IN, int MAXC, int NJB, bool SM = false, bool GA = false>
 __global__ __launch_bounds__(256) void act_int_kernel(ActParams p)
 {
+    write_tag(p.tag_dst, p.tag);
     constexpr bool BF16 = BF16IN && !SM;  // representation of the row in registers
     __shared__ float s_amax[4][16];
     __shared__ float s_sxb[16];
@@ -428,6 +431,8 @@ hipError_t launch_quantize_act_int(const Dims& d, int x_dtype, const uint8_t* pa
     const PackedLayout pl = packed_layout(d);
     const ActLayout al = act_layout(d, M);
     ActParams p;
+    p.tag = make_tag(d, LQ_BLOB_ACT, M);
+    p.tag_dst = (uint32_t*)act;
     p.X = X;
     p.ldx = ldx;
     p.M = (int)M;

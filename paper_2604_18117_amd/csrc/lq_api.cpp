@@ -81,13 +81,24 @@ lq_status make_dims(const lq_config* cfg, Dims* d)
         return LQ_ERR_UNSUPPORTED;
     }
     d->G = (int)(cfg->K / d->g);
+    {   // FNV-1a over the configuration's fields, in declaration order
+        const int64_t f[12] = {cfg->N, cfg->K, cfg->rank, cfg->main_w, cfg->main_a, cfg->main_w_group, cfg->main_a_group,
+                               cfg->br_w, cfg->br_a, cfg->residual_from_quantized, cfg->x_dtype, cfg->flags};
+        uint64_t h = 1469598103934665603ull;
+        for (int i = 0; i < 12; ++i)
+            for (int b = 0; b < 8; ++b) {
+                h ^= (uint64_t)((f[i] >> (8 * b)) & 0xFF);
+                h *= 1099511628211ull;
+            }
+        d->cfg_hash = h;
+    }
     return LQ_OK;
 }
 
 PackedLayout packed_layout(const Dims& d)
 {
     PackedLayout pl;
-    size_t o = 0;
+    size_t o = BLOB_HEADER;
     pl.off_pq = o;
     o = align256(o + ((d.mx || d.mxi) ? (size_t)d.N * d.K / 2 : (size_t)d.N * d.K / 4 * 3));  // INT family: 6-bit fields
     pl.off_sw = o;
@@ -113,7 +124,7 @@ ActLayout act_layout(const Dims& d, int64_t M)
 {
     ActLayout al;
     al.Mp = (M + 31) / 32 * 32;
-    size_t o = 0;
+    size_t o = BLOB_HEADER;
     al.off_xq = o;
     o = align256(o + ((d.mx || d.mxi) ? (size_t)al.Mp * d.K / 2 : (size_t)al.Mp * d.K / 4 * 3));
     al.off_sx = o;
@@ -144,6 +155,7 @@ const char* lq_status_string(lq_status s)
         case LQ_ERR_ALIGN: return "misaligned pointer or stride";
         case LQ_ERR_BUFFER_TOO_SMALL: return "buffer too small";
         case LQ_ERR_DEVICE: return "HIP launch failed";
+        case LQ_ERR_STALE_BLOB: return "blob header does not match the configuration";
     }
     return "unknown status";
 }
@@ -165,7 +177,7 @@ lq_status lq_act_sizes(const lq_config* cfg, int64_t M, size_t* act_bytes)
     lq_status st = make_dims(cfg, &d);
     if (st != LQ_OK) return st;
     if (M < 0 || M > (1 << 24)) return LQ_ERR_SHAPE;
-    *act_bytes = act_layout(d, M).total;
+    *act_bytes = M == 0 ? 0 : act_layout(d, M).total;  // (an empty batch needs no blob, not even the header)
     return LQ_OK;
 }
 
@@ -184,7 +196,28 @@ lq_status lq_pack_weights(const lq_config* cfg, const float* W, const float* L, 
     hipError_t e = d.mxi ? launch_pack_mxi(d, cfg->residual_from_quantized, W, L, R, (uint8_t*)packed, (hipStream_t)stream)
                    : d.mx ? launch_pack_mx(d, cfg->residual_from_quantized, W, L, R, (uint8_t*)packed, (hipStream_t)stream)
                         : launch_pack_int(d, cfg->residual_from_quantized, W, L, R, (uint8_t*)packed, (hipStream_t)stream);
+    if (e == hipSuccess) e = launch_write_tag((uint8_t*)packed, make_tag(d, LQ_BLOB_PACKED, 0), (hipStream_t)stream);
     return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
+}
+
+lq_status lq_verify_blob(const lq_config* cfg, int32_t kind, const void* blob, size_t blob_bytes, int64_t M, void* stream)
+{
+    Dims d;
+    lq_status st = make_dims(cfg, &d);
+    if (st != LQ_OK) return st;
+    if (!blob) return LQ_ERR_NULL;
+    if (kind != LQ_BLOB_PACKED && kind != LQ_BLOB_ACT) return LQ_ERR_UNSUPPORTED;
+    if (kind == LQ_BLOB_ACT && (M < 1 || M > (1 << 24))) return LQ_ERR_SHAPE;
+    if (!aligned(blob, 256)) return LQ_ERR_ALIGN;
+    const size_t need = kind == LQ_BLOB_PACKED ? packed_layout(d).total : act_layout(d, M).total;
+    if (blob_bytes < need) return LQ_ERR_BUFFER_TOO_SMALL;
+    BlobTag got;
+    if (hipMemcpyAsync(&got, blob, sizeof(got), hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess) return LQ_ERR_DEVICE;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return LQ_ERR_DEVICE;
+    const BlobTag want = make_tag(d, kind, kind == LQ_BLOB_ACT ? M : 0);
+    for (int i = 0; i < 8; ++i)
+        if (got.w[i] != want.w[i]) return LQ_ERR_STALE_BLOB;
+    return LQ_OK;
 }
 
 lq_status lq_set_smoothing(const lq_config* cfg, const float* gamma, void* packed, size_t packed_bytes, void* stream)

@@ -75,7 +75,30 @@ struct Dims {
     bool smooth;  // LQ_FLAG_SMOOTH: the activation kernel multiplies X by the stored reciprocals of gamma
     int qmax_bw;  // INT branch weight qmax
     int qmax_ba;  // INT branch activation qmax
+    uint64_t cfg_hash;  // of every field of the caller's lq_config (blob headers)
 };
+
+// Every blob starts with a 256-byte header: 8 dwords {magic, layout version, kind, configuration hash (2), M (activation
+// blobs; 0 otherwise), N, K}, the rest reserved.  lq_pack_weights and the activation kernels write it; lq_verify_blob
+// compares it with a configuration (a blob packed under one configuration and used under another is otherwise
+// undetectable: the per-call entry points never read device memory on the host).
+constexpr size_t BLOB_HEADER = 256;
+constexpr uint32_t BLOB_MAGIC = 0x4C515242u;   // "LQRB"
+constexpr uint32_t BLOB_VERSION = 2u;          // layout revision (6-bit code fields for the INT family)
+struct BlobTag { uint32_t w[8]; };
+static inline BlobTag make_tag(const Dims& d, int kind, int64_t M)
+{
+    BlobTag t;
+    t.w[0] = BLOB_MAGIC;
+    t.w[1] = BLOB_VERSION;
+    t.w[2] = (uint32_t)kind;
+    t.w[3] = (uint32_t)d.cfg_hash;
+    t.w[4] = (uint32_t)(d.cfg_hash >> 32);
+    t.w[5] = (uint32_t)M;
+    t.w[6] = (uint32_t)d.N;
+    t.w[7] = (uint32_t)d.Ks;
+    return t;
+}
 
 struct PackedLayout {
     size_t off_pq;   // main codes, fragment order: INT family N*K*3/4 bytes (6-bit fields), MX families N*K/2
@@ -210,8 +233,15 @@ static inline int panel_width(int tilesN, int C64, int chunk_row_bytes = 32)
     return pw < 1 ? 1 : pw > tilesN ? tilesN : pw;
 }
 
+hipError_t launch_write_tag(uint8_t* blob, const BlobTag& t, hipStream_t s);
+
 // ---- device helpers ----------------------------------------------------------------------
 #if defined(__HIPCC__)
+// header of an activation blob, written by the first workgroup of the kernel that fills the blob
+__device__ __forceinline__ void write_tag(uint32_t* dst, const BlobTag& t)
+{
+    if (blockIdx.x == 0 && threadIdx.x < 8) dst[threadIdx.x] = t.w[threadIdx.x];
+}
 __device__ __forceinline__ void panel_tile(int tile, int tilesM, int tilesN, int panel, int& tile_m, int& tile_n)
 {
     const int full = (tilesN / panel) * panel;  // columns in full panels

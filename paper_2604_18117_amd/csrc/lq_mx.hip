@@ -392,6 +392,8 @@ struct MxActParams {
     float* dbg_sxb;
     float* dbg_T;
     const float* rg;  // reciprocals of the smoothing vector (smoothing variant only)
+    BlobTag tag;        // header of the activation blob (written by the first workgroup)
+    uint32_t* tag_dst;
 };
 
 template <bool BF16>
@@ -437,6 +439,7 @@ struct MxChunk<false> {
 template <bool BF16IN, int MAXC, int NJB, bool SM = false>
 __global__ __launch_bounds__(256) void mx_act_kernel(MxActParams p)
 {
+    write_tag(p.tag_dst, p.tag);
     constexpr bool BF16 = BF16IN && !SM;  // representation of the row in registers
     __shared__ float s_amax[4][16];
     __shared__ float s_sxb[16];
@@ -665,6 +668,8 @@ hipError_t launch_quantize_act_mx(const Dims& d, int x_dtype, const uint8_t* pac
     const PackedLayout pl = packed_layout(d);
     const ActLayout al = act_layout(d, M);
     MxActParams p;
+    p.tag = make_tag(d, LQ_BLOB_ACT, M);
+    p.tag_dst = (uint32_t*)act;
     p.X = X;
     p.ldx = ldx;
     p.M = (int)M;
@@ -723,12 +728,15 @@ struct MxbActParams {
     uint8_t* dbg_xbe;
     float* dbg_T;
     const float* rg;  // reciprocals of the smoothing vector (smoothing variant only)
+    BlobTag tag;        // header of the activation blob (written by the first workgroup)
+    uint32_t* tag_dst;
 };
 
 // BF16IN: element type of X; SM: smoothing variant (X times the stored reciprocals, held as fp32).
 template <bool BF16IN, int NJB, bool SM = false>
 __global__ __launch_bounds__(256) void mxb_act_kernel(MxbActParams p)
 {
+    write_tag(p.tag_dst, p.tag);
     constexpr bool BF16 = BF16IN && !SM;  // representation of a chunk in registers
     constexpr int NJA = NJB > 0 ? NJB : 1;
     constexpr int PF = 2;  // 128-chunks in flight per wavefront: no scale spans more than a block, the row is streamed
@@ -926,6 +934,8 @@ static hipError_t launch_quantize_act_mxb(const Dims& d, int x_dtype, const uint
     const PackedLayout pl = packed_layout(d);
     const ActLayout al = act_layout(d, M);
     MxbActParams p;
+    p.tag = make_tag(d, LQ_BLOB_ACT, M);
+    p.tag_dst = (uint32_t*)act;
     p.X = X;
     p.ldx = ldx;
     p.M = (int)M;

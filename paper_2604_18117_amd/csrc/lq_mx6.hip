@@ -213,6 +213,8 @@ struct Mx6ActParams {
     uint8_t* dbg_xbe;
     float* dbg_T;
     const float* rg;  // reciprocals of the smoothing vector (smoothing variant only)
+    BlobTag tag;        // header of the activation blob (written by the first workgroup)
+    uint32_t* tag_dst;
 };
 
 template <bool BF16>
@@ -254,6 +256,7 @@ struct Mx6Block<false> {  // 32 fp32 values
 template <bool BF16IN, int NJB, bool SM = false>
 __global__ __launch_bounds__(256) void mx6_act_kernel(Mx6ActParams p)
 {
+    write_tag(p.tag_dst, p.tag);
     constexpr bool BF16 = BF16IN && !SM;  // representation of a block in registers
     constexpr int NJA = NJB > 0 ? NJB : 1;
     constexpr int PF = 2;  // 128-chunks in flight per wavefront
@@ -445,6 +448,8 @@ hipError_t launch_quantize_act_mx6(const Dims& d, int x_dtype, const uint8_t* pa
     const PackedLayout pl = packed_layout(d);
     const ActLayout al = act_layout(d, M);
     Mx6ActParams p;
+    p.tag = make_tag(d, LQ_BLOB_ACT, M);
+    p.tag_dst = (uint32_t*)act;
     p.X = X;
     p.ldx = ldx;
     p.M = (int)M;

@@ -278,6 +278,8 @@ struct MxiActParams {
     uint8_t* dbg_xbe;
     float* dbg_T;
     const float* rg;  // reciprocals of the smoothing vector (smoothing variant only)
+    BlobTag tag;        // header of the activation blob (written by the first workgroup)
+    uint32_t* tag_dst;
 };
 
 template <bool BF16>
@@ -342,6 +344,7 @@ __device__ __forceinline__ uint32_t bf16_pair(float lo, float hi)  // upper halv
 template <bool BF16IN, int NJB, bool SM = false, bool FROMC = false>
 __global__ __launch_bounds__(256) void mxi_act_kernel(MxiActParams p)
 {
+    write_tag(p.tag_dst, p.tag);
     constexpr bool BF16 = BF16IN && !SM;  // representation of a chunk in registers
     constexpr int NJA = NJB > 0 ? NJB : 1;
     constexpr int PF = 2;  // 64-chunks in flight per wavefront (measured: 2 beats 4, 6, 8 -- fewer registers, more resident workgroups)
@@ -572,6 +575,8 @@ hipError_t launch_branch_from_codes_mxi(const Dims& d, const uint8_t* packed, co
     const PackedLayout pl = packed_layout(d);
     const ActLayout al = act_layout(d, M);
     MxiActParams p = {};
+    p.tag = make_tag(d, LQ_BLOB_ACT, M);
+    p.tag_dst = (uint32_t*)act;
     p.cb = (const int8_t*)codes;
     p.cbe = codes + handoff_codes_bytes(d, M);
     p.M = (int)M;
@@ -602,6 +607,8 @@ hipError_t launch_quantize_act_mxi(const Dims& d, int x_dtype, const uint8_t* pa
     const PackedLayout pl = packed_layout(d);
     const ActLayout al = act_layout(d, M);
     MxiActParams p;
+    p.tag = make_tag(d, LQ_BLOB_ACT, M);
+    p.tag_dst = (uint32_t*)act;
     p.X = X;
     p.cb = nullptr;
     p.cbe = nullptr;
@@ -646,6 +653,8 @@ struct MxiFwdParams {
     int8_t* ho_cb;
     uint8_t* ho_cbe;
     int ho_C64, ho_CQ;
+    BlobTag ho_tag;      // header of the consumer's activation blob
+    uint32_t* ho_tag_dst;
 };
 
 __device__ __forceinline__ v8i mxi_expand8(v4i p)  // 32 nibbles -> 32 FP8 subnormal bytes
@@ -664,6 +673,7 @@ __device__ __forceinline__ v8i mxi_expand8(v4i p)  // 32 nibbles -> 32 FP8 subno
 template <int NK16, bool DBG, bool HO = false>
 __global__ __launch_bounds__(256, 2) void mxi_fwd_kernel(MxiFwdParams p)
 {
+    if constexpr (HO) write_tag(p.ho_tag_dst, p.ho_tag);
     constexpr int RBT = 4;
     constexpr int EPI_ROW = 144, EPI_WAVE = 32 * EPI_ROW;
     constexpr int LDS_MAIN = 2 * RBT * 2048;  // [buffer][row block][part][lane][16 B]
@@ -979,6 +989,8 @@ static hipError_t fwd_mxi_launches(const Dims& d, const uint8_t* packed, const u
         p.ho_cbe = codes + handoff_codes_bytes(*next, M);
         p.ho_C64 = next->C64;
         p.ho_CQ = (next->C64 + 3) / 4;
+        p.ho_tag = make_tag(*next, LQ_BLOB_ACT, M);
+        p.ho_tag_dst = (uint32_t*)act_next;
     }
     p.xq = act + al.off_xq;
     p.xe = act + al.off_sx;

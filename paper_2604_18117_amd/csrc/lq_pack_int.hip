@@ -137,6 +137,14 @@ __global__ __launch_bounds__(256) void pack_p_kernel(const float* W, const float
     }
 }
 
+// blob header (offline packing: a launch of its own; the activation kernels write theirs themselves)
+__global__ void write_tag_kernel(uint32_t* dst, BlobTag t) { write_tag(dst, t); }
+hipError_t launch_write_tag(uint8_t* blob, const BlobTag& t, hipStream_t s)
+{
+    hipLaunchKernelGGL(write_tag_kernel, dim3(1), dim3(64), 0, s, (uint32_t*)blob, t);
+    return hipGetLastError();
+}
+
 // reciprocals of the smoothing vector (gamma == nullptr: ones)
 __global__ __launch_bounds__(256) void smooth_recip_kernel(const float* gamma, int Ks, int K, float* rg)
 {

@@ -27,18 +27,18 @@ def test_exports_every_declared_symbol(lq):
 
 
 def test_status_strings(lq):
-    seen = {lq.lq_status_string(s) for s in range(7)}
-    assert len(seen) == 7 and "ok" in seen
+    seen = {lq.lq_status_string(s) for s in range(8)}
+    assert len(seen) == 8 and "ok" in seen
 
 
 def test_sizes_follow_the_layout(lq):
     cfg = lq.make_config(3456, 1152, 32, "int", 64, 8, 8)
     pb = lq.lq_packed_sizes(cfg)
-    # codes N*K*6/8 (4-bit codes in 6-bit fields) + scales N*G*4 + lq N*32 + sl N*4 + rq r*K + sr r*4, each section 256-aligned
-    parts = [3456 * 1152 * 3 // 4, 3456 * 18 * 4, 3456 * 32, 3456 * 4, 32 * 1152, 32 * 4]
+    # header 256 + codes N*K*6/8 (4-bit codes in 6-bit fields) + scales N*G*4 + lq N*32 + sl N*4 + rq r*K + sr r*4, each section 256-aligned
+    parts = [256, 3456 * 1152 * 3 // 4, 3456 * 18 * 4, 3456 * 32, 3456 * 4, 32 * 1152, 32 * 4]
     assert pb == sum((x + 255) // 256 * 256 for x in parts)
     ab = lq.lq_act_sizes(cfg, 8192)
-    parts = [8192 * 1152 * 3 // 4, 8192 * 4, 8192 * 32, 8192 * 4]
+    parts = [256, 8192 * 1152 * 3 // 4, 8192 * 4, 8192 * 32, 8192 * 4]
     assert ab == sum((x + 255) // 256 * 256 for x in parts)
     # M is padded to a multiple of 32 rows
     assert lq.lq_act_sizes(cfg, 1) == lq.lq_act_sizes(cfg, 32) < lq.lq_act_sizes(cfg, 33)
@@ -124,7 +124,7 @@ def test_mx_family_contract(lq):
     # codes N*K/2, E8M0 dwords per (32 rows, quad of 64-chunks, lane), lq N*64, one scale dword per
     # (channel, rank half), rq r*K, one scale dword per (128-chunk, 16 rank rows, lane) (+4)
     cfg = lq.make_config(3456, 1152, 32, "mxb")
-    parts = [3456 * 1152 // 2, 3456 // 32 * 5 * 256, 3456 * 64, 3456 * 8, 32 * 1152, 9 * 2 * 256 + 4]
+    parts = [256, 3456 * 1152 // 2, 3456 // 32 * 5 * 256, 3456 * 64, 3456 * 8, 32 * 1152, 9 * 2 * 256 + 4]
     assert lq.lq_packed_sizes(cfg) == sum((x + 255) // 256 * 256 for x in parts)
 
 
@@ -181,7 +181,7 @@ def test_mxi_contract(lq):
     assert raw.lq_packed_sizes(C.byref(cfg), C.byref(n)) == lq.LQ_ERR_UNSUPPORTED
     # 4-bit codes N*K/2, scale dwords per (32 rows, quad of chunks, lane), bf16 factors with one byte per block
     cfg = lq.make_config(3456, 1152, 64, "mxi")
-    parts = [3456 * 1152 // 2, 3456 // 32 * 5 * 256, 3456 * 64 * 2, 3456 * 2 + 4, 64 * 1152 * 2, 64 * 36 + 4]
+    parts = [256, 3456 * 1152 // 2, 3456 // 32 * 5 * 256, 3456 * 64 * 2, 3456 * 2 + 4, 64 * 1152 * 2, 64 * 36 + 4]
     assert lq.lq_packed_sizes(cfg) == sum((x + 255) // 256 * 256 for x in parts)
     # the block-local scales need no register-resident row: K is not limited
     good = C.c_void_p(1 << 20)
@@ -330,3 +330,15 @@ def test_handoff_contract(lq):
     assert br(cons, cb=16) == lq.LQ_ERR_BUFFER_TOO_SMALL
     assert br(_cfg(lq)) == lq.LQ_ERR_UNSUPPORTED
     assert br(lq.make_config(128, 320, 0, "mxi", 32, 8, 8), packed=None) == lq.LQ_OK             # rank 0: nothing to do
+
+
+def test_verify_blob_contract(lq):
+    raw = lq.raw()
+    cfg = _cfg(lq)
+    fake = C.c_void_p(0x1000)
+    assert raw.lq_verify_blob(C.byref(cfg), lq.LQ_BLOB_PACKED, None, 1 << 30, 0, None) == lq.LQ_ERR_NULL
+    assert raw.lq_verify_blob(C.byref(cfg), 3, fake, 1 << 30, 0, None) == lq.LQ_ERR_UNSUPPORTED
+    assert raw.lq_verify_blob(C.byref(cfg), lq.LQ_BLOB_ACT, fake, 1 << 30, 0, None) == lq.LQ_ERR_SHAPE
+    assert raw.lq_verify_blob(C.byref(cfg), lq.LQ_BLOB_PACKED, C.c_void_p(0x1008), 1 << 30, 0, None) == lq.LQ_ERR_ALIGN
+    assert raw.lq_verify_blob(C.byref(cfg), lq.LQ_BLOB_PACKED, fake, 64, 0, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert raw.lq_verify_blob(C.byref(_cfg(lq, N=100)), lq.LQ_BLOB_PACKED, fake, 1 << 30, 0, None) == lq.LQ_ERR_SHAPE
