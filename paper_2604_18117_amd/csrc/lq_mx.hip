@@ -986,9 +986,13 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
 {
     constexpr int WN = 4, RBT = 4;
     constexpr int EPI_ROW = 144, EPI_WAVE = 32 * EPI_ROW;
-    constexpr int LDS_MAIN = 2 * 2 * RBT * 1024;  // [buffer][chunk in stage][row block][lane][16 B]
+    constexpr int NBUF = 4;                          // LDS buffers of the activation stream (one stage each)
+    constexpr int LDS_MAIN = NBUF * 2 * RBT * 1024;  // [buffer][chunk in stage][row block][lane][16 B]
     constexpr int LDS_BYTES = LDS_MAIN > 4 * EPI_WAVE ? LDS_MAIN : 4 * EPI_WAVE;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES];
+    // + the tile's 128 per-token scales of the fp32-scaled branch (read back by every wavefront in the epilogue: an LDS
+    // broadcast read instead of sixteen 1 KB vector-memory loads per wavefront whose lanes all fetch the same 16 bytes)
+    __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES + RBT * 32 * 4];
+    float* lds_st = (float*)(lds + LDS_BYTES);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1027,31 +1031,35 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     // lane fewer).  Each descriptor spans exactly the bytes its stream may touch.
     typedef unsigned int u4 __attribute__((ext_vector_type(4)));
     constexpr int RSRC_FLAGS = 0x00020000;
-    const __amdgpu_buffer_rsrc_t rs_xc = __builtin_amdgcn_make_buffer_rsrc((void*)xc_base, 0, C64 * 1024, RSRC_FLAGS);
-    const __amdgpu_buffer_rsrc_t rs_pc[2] = {__builtin_amdgcn_make_buffer_rsrc((void*)pc_base[0], 0, C64 * 1024, RSRC_FLAGS),
-                                             __builtin_amdgcn_make_buffer_rsrc((void*)pc_base[1], 0, C64 * 1024, RSRC_FLAGS)};
     const __amdgpu_buffer_rsrc_t rs_pe[2] = {__builtin_amdgcn_make_buffer_rsrc((void*)pe_base[0], 0, CQ * 256, RSRC_FLAGS),
                                              __builtin_amdgcn_make_buffer_rsrc((void*)pe_base[1], 0, CQ * 256, RSRC_FLAGS)};
     __amdgpu_buffer_rsrc_t rs_xe[4];
 #pragma unroll
     for (int rbi = 0; rbi < 4; ++rbi) rs_xe[rbi] = __builtin_amdgcn_make_buffer_rsrc((void*)xe_base[rbi], 0, CQ * 256, RSRC_FLAGS);
+    // A load for a stage (or quad of chunks) past the end goes through a descriptor of zero bytes: every lane is out of
+    // range, nothing is fetched and the (unused) result is zero; the loop body stays branch-free.
     auto load_a = [&](AStage& a, int stage) {
-        const int st = stage < S ? stage : S - 1;
+        const bool ok = stage < S;
+        const int st = ok ? stage : S - 1;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)xc_base, 0, ok ? C64 * 1024 : 0, RSRC_FLAGS);
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc)
-            a.v[cc] = __builtin_bit_cast(v4i, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs_xc, lane16, (st * 2 + cc) * 1024, 0));
+            a.v[cc] = __builtin_bit_cast(v4i, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs, lane16, (st * 2 + cc) * 1024, 0));
     };
     auto store_a = [&](const AStage& a, int buf) {
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc) *(v4i*)(lds + (size_t)(((buf * 2 + cc) * RBT + wave) * 1024) + lane16) = a.v[cc];
     };
     auto load_b = [&](BStage& b, int stage) {
-        const int st = stage < S ? stage : S - 1;
+        const bool ok = stage < S;
+        const int st = ok ? stage : S - 1;
 #pragma unroll
-        for (int cbi = 0; cbi < 2; ++cbi)
+        for (int cbi = 0; cbi < 2; ++cbi) {
+            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)pc_base[cbi], 0, ok ? C64 * 1024 : 0, RSRC_FLAGS);
 #pragma unroll
             for (int cc = 0; cc < 2; ++cc)
-                b.v[cc][cbi] = __builtin_bit_cast(v4i, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs_pc[cbi], lane16, (st * 2 + cc) * 1024, 0));
+                b.v[cc][cbi] = __builtin_bit_cast(v4i, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs, lane16, (st * 2 + cc) * 1024, 0));
+        }
     };
     // scale dwords of one quad of chunks (= two stages)
     struct Scales { int a[4]; int b[2]; };
@@ -1071,35 +1079,42 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
 #pragma unroll
             for (int i = 0; i < 16; ++i) t[a][b][i] = 0.f;
 
-    // One stage = 128 values of K = two 64-chunks.  PAR (0|1) = parity of the stage inside its
-    // quad of chunks: the op_sel immediates are 2*PAR and 2*PAR+1.
-    auto do_stage = [&](auto par, int s, AStage& a, BStage& b, const Scales& sc) {
-        constexpr int PAR = decltype(par)::value;
-        const int buf = s & 1;
+    // One stage = 128 values of K = two 64-chunks = eight activation fragments (chunk, row block), each the A operand of
+    // two MFMAs.  P = stage index mod 4: LDS buffer P holds the stage's activation codes, buffer P+1 those of the next
+    // stage (written one stage earlier, so they are visible without a barrier in between), buffer P+2 receives stage
+    // s+2 during this one.  The fragments are read two ahead of their MFMAs into a ring of four register sets, across
+    // the stage boundary as well, so that a wavefront on its own keeps the matrix core busy (the barrier at the end of
+    // a stage orders LDS writes against reads two stages apart; nothing waits on it).  Loads past the last stage are
+    // issued through an empty descriptor: at K = 1152 they would be a sixth of the wavefront's vector-memory work.
+    // The op_sel immediates of the scale bytes are 2*(P&1) and 2*(P&1)+1.
+    v4i fr[4];
+    auto lds_frag = [&](int buf, int f) -> v4i {   // f = chunk * 4 + row block
+        return *(const v4i*)(lds + (size_t)((buf * 2 * RBT + f) * 1024) + lane16);
+    };
+    auto do_stage = [&](auto pc, int s, AStage& a, BStage& b, const Scales& sc) {
+        constexpr int P = decltype(pc)::value, PAR = P & 1;
 #pragma unroll
-        for (int cc = 0; cc < 2; ++cc) {
+        for (int f = 0; f < 8; ++f) {
+            const int cc = f >> 2, rbi = f & 3;
+            fr[(f + 2) & 3] = f + 2 < 8 ? lds_frag(P, f + 2) : lds_frag((P + 1) & 3, f + 2 - 8);
+            if (f == 0) store_a(a, (P + 2) & 3);
+            if (f == 1) load_a(a, s + 4);
+            const v4i av = fr[f & 3];
+            const v8i a8 = {av[0], av[1], av[2], av[3], 0, 0, 0, 0};
 #pragma unroll
-            for (int rbi = 0; rbi < 4; ++rbi) {
-                const v4i av = *(const v4i*)(lds + (size_t)(((buf * 2 + cc) * RBT + rbi) * 1024) + lane16);
-                const v8i a8 = {av[0], av[1], av[2], av[3], 0, 0, 0, 0};
-#pragma unroll
-                for (int cbi = 0; cbi < 2; ++cbi) {
-                    const v4i bq = b.v[cc][cbi];
-                    const v8i b8 = {bq[0], bq[1], bq[2], bq[3], 0, 0, 0, 0};
-                    if (cc == 0)
-                        t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, t[rbi][cbi], 4, 4, 2 * PAR,
-                                                                                     sc.a[rbi], 2 * PAR, sc.b[cbi]);
-                    else
-                        t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, t[rbi][cbi], 4, 4, 2 * PAR + 1,
-                                                                                     sc.a[rbi], 2 * PAR + 1, sc.b[cbi]);
-                }
+            for (int cbi = 0; cbi < 2; ++cbi) {
+                const v4i bq = b.v[cc][cbi];
+                const v8i b8 = {bq[0], bq[1], bq[2], bq[3], 0, 0, 0, 0};
+                if (cc == 0)
+                    t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, t[rbi][cbi], 4, 4, 2 * PAR,
+                                                                                 sc.a[rbi], 2 * PAR, sc.b[cbi]);
+                else
+                    t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, t[rbi][cbi], 4, 4, 2 * PAR + 1,
+                                                                                 sc.a[rbi], 2 * PAR + 1, sc.b[cbi]);
             }
-            if (cc == 0) {  // stage s+1 goes to the other LDS buffer while this one is being consumed
-                store_a(a, buf ^ 1);
-                load_a(a, s + 3);
-            }
+            if (f == 7) load_b(b, s + 2);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        load_b(b, s + 2);
         __syncthreads();
     };
 
@@ -1107,16 +1122,23 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     BStage b0, b1;
     Scales s0, s1;
     load_a(a0, 0);
+    load_a(a1, 1);
     load_b(b0, 0);
     load_s(s0, 0);
+    if constexpr (!BLK && NK > 0) {
+        if (lane < 32) lds_st[wave * 32 + lane] = p.st[rbs * 32 + lane];
+    }
     store_a(a0, 0);
+    store_a(a1, 1);
     __builtin_amdgcn_sched_barrier(0);
-    load_a(a0, 1);
+    load_a(a0, 2);
+    load_a(a1, 3);
     load_b(b1, 1);
-    load_a(a1, 2);
     load_s(s1, 1);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
+    fr[0] = lds_frag(0, 0);
+    fr[1] = lds_frag(0, 1);
 
     // stages come in groups of four (two quads of chunks): quad q uses scale set q & 1
     int s = 0;
@@ -1124,14 +1146,14 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
         do_stage(std::integral_constant<int, 0>{}, s, a0, b0, s0);
         do_stage(std::integral_constant<int, 1>{}, s + 1, a1, b1, s0);
         load_s(s0, (s >> 1) + 2);
-        do_stage(std::integral_constant<int, 0>{}, s + 2, a0, b0, s1);
-        do_stage(std::integral_constant<int, 1>{}, s + 3, a1, b1, s1);
+        do_stage(std::integral_constant<int, 2>{}, s + 2, a0, b0, s1);
+        do_stage(std::integral_constant<int, 3>{}, s + 3, a1, b1, s1);
         load_s(s1, (s >> 1) + 3);
     }
     if (s < S) {
         do_stage(std::integral_constant<int, 0>{}, s, a0, b0, s0);
         if (s + 1 < S) do_stage(std::integral_constant<int, 1>{}, s + 1, a1, b1, s0);
-        if (s + 2 < S) do_stage(std::integral_constant<int, 0>{}, s + 2, a0, b0, s1);
+        if (s + 2 < S) do_stage(std::integral_constant<int, 2>{}, s + 2, a0, b0, s1);
     }
 
     if (!active) return;
@@ -1197,8 +1219,9 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
         if (BLK || NK == 0) return;  // no fp32-scaled branch: its scale sections may hold anything
         int rb = rb0 + rbi;
         rb = rb < p.nrb ? rb : p.nrb - 1;
+        (void)rb;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) stv[q] = *(const v4f*)(p.st + rb * 32 + 8 * q + 4 * half);
+        for (int q = 0; q < 4; ++q) stv[q] = *(const v4f*)(lds_st + rbi * 32 + 8 * q + 4 * half);
     };
     load_tq(0);
     load_scales(0);
