@@ -178,19 +178,24 @@ lq_status lq_act_sizes(const lq_config *cfg, int64_t M, size_t *act_bytes);
    4-bit main codes and scales, quantises X for the branch, contracts it with Q2(R) and
    re-quantises the M x r result per token.
    X: device, M x K of cfg.x_dtype, row stride ldx elements (ldx >= K, ldx*elemsize % 16 == 0,
-   X 16-byte aligned).  `packed`: blob written by lq_pack_weights for the same cfg.
-   `act`: device, 256-byte aligned, at least act_bytes.  dbg may be NULL. */
-lq_status lq_quantize_act(const lq_config *cfg, const void *packed, const void *X, int64_t M,
-                          int64_t ldx, void *act, size_t act_bytes, const lq_act_debug *dbg,
+   X 16-byte aligned).  `packed`: blob written by lq_pack_weights for the same cfg, packed_bytes = the
+   bytes the caller holds there (LQ_ERR_BUFFER_TOO_SMALL below lq_packed_sizes; packed may be NULL, and
+   packed_bytes is then ignored, when rank == 0 and no smoothing is fused).
+   `act`: device, 256-byte aligned, at least lq_act_sizes(cfg, M) bytes.  dbg may be NULL. */
+lq_status lq_quantize_act(const lq_config *cfg, const void *packed, size_t packed_bytes, const void *X,
+                          int64_t M, int64_t ldx, void *act, size_t act_bytes, const lq_act_debug *dbg,
                           void *stream);
 
 /* Forward (Fig. 1): main 4-bit product with per-group dequantisation, rank-r expansion of the
    re-quantised intermediate, sum, bf16 rounding.
    Y: device, M x N bf16, row stride ldy elements (ldy >= N, ldy % 8 == 0, Y 16-byte aligned).
+   packed_bytes / act_bytes: the bytes the caller holds behind `packed` / `act`; a blob smaller than
+   lq_packed_sizes(cfg) / lq_act_sizes(cfg, M) is refused (LQ_ERR_BUFFER_TOO_SMALL) before any launch, so
+   that a blob sized for another configuration or token count is never read past its end.
    dbg may be NULL (production); with dbg the same kernel also writes the taps. */
-lq_status lq_linear_lowrank_fwd(const lq_config *cfg, const void *packed, const void *act,
-                                int64_t M, void *Y, int64_t ldy, const lq_fwd_debug *dbg,
-                                void *stream);
+lq_status lq_linear_lowrank_fwd(const lq_config *cfg, const void *packed, size_t packed_bytes,
+                                const void *act, size_t act_bytes, int64_t M, void *Y, int64_t ldy,
+                                const lq_fwd_debug *dbg, void *stream);
 
 /* Quantized hand-off between two linear layers (Section 4.5, "Method Efficiency": with quantized branches the
    activations that move between layers are in the 8-, 6- or 4-bit MX formats instead of 16 bits).  Built for the integer
@@ -214,11 +219,13 @@ lq_status lq_linear_lowrank_fwd(const lq_config *cfg, const void *packed, const 
    Errors as for the calls they extend; a configuration pair outside the family, or next_cfg->K != cfg->N:
    LQ_ERR_UNSUPPORTED / LQ_ERR_SHAPE before any launch. */
 lq_status lq_handoff_sizes(const lq_config *next_cfg, int64_t M, size_t *codes_bytes);
-lq_status lq_linear_lowrank_fwd_handoff(const lq_config *cfg, const void *packed, const void *act, int64_t M, void *Y,
-                                        int64_t ldy, const lq_config *next_cfg, void *act_next, size_t act_next_bytes,
-                                        void *codes, size_t codes_bytes, void *stream);
-lq_status lq_branch_from_codes(const lq_config *next_cfg, const void *packed_next, const void *codes, size_t codes_bytes,
-                               int64_t M, void *act_next, size_t act_next_bytes, void *stream);
+lq_status lq_linear_lowrank_fwd_handoff(const lq_config *cfg, const void *packed, size_t packed_bytes, const void *act,
+                                        size_t act_bytes, int64_t M, void *Y, int64_t ldy, const lq_config *next_cfg,
+                                        void *act_next, size_t act_next_bytes, void *codes, size_t codes_bytes,
+                                        void *stream);
+lq_status lq_branch_from_codes(const lq_config *next_cfg, const void *packed_next, size_t packed_next_bytes,
+                               const void *codes, size_t codes_bytes, int64_t M, void *act_next, size_t act_next_bytes,
+                               void *stream);
 
 /* Decode the opaque blobs into plain row-major arrays (test / inspection helpers). */
 lq_status lq_unpack_weights(const lq_config *cfg, const void *packed, const lq_weights_view *out,

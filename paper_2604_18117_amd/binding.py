@@ -96,15 +96,16 @@ _lib.lq_pack_weights.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C
                                  C.c_size_t, C.c_void_p]
 _lib.lq_verify_blob.argtypes = [C.POINTER(lq_config), C.c_int32, C.c_void_p, C.c_size_t, C.c_int64, C.c_void_p]
 _lib.lq_set_smoothing.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
-_lib.lq_quantize_act.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+_lib.lq_quantize_act.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_size_t, C.c_void_p, C.c_int64, C.c_int64,
                                  C.c_void_p, C.c_size_t, C.POINTER(lq_act_debug), C.c_void_p]
-_lib.lq_linear_lowrank_fwd.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
-                                       C.c_int64, C.POINTER(lq_fwd_debug), C.c_void_p]
+_lib.lq_linear_lowrank_fwd.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_int64,
+                                       C.c_void_p, C.c_int64, C.POINTER(lq_fwd_debug), C.c_void_p]
 _lib.lq_handoff_sizes.argtypes = [C.POINTER(lq_config), C.c_int64, C.POINTER(C.c_size_t)]
-_lib.lq_linear_lowrank_fwd_handoff.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
-                                               C.POINTER(lq_config), C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p]
-_lib.lq_branch_from_codes.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p, C.c_size_t, C.c_int64, C.c_void_p,
-                                      C.c_size_t, C.c_void_p]
+_lib.lq_linear_lowrank_fwd_handoff.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_int64,
+                                               C.c_void_p, C.c_int64, C.POINTER(lq_config), C.c_void_p, C.c_size_t, C.c_void_p,
+                                               C.c_size_t, C.c_void_p]
+_lib.lq_branch_from_codes.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_int64,
+                                      C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.lq_unpack_weights.argtypes = [C.POINTER(lq_config), C.c_void_p, C.POINTER(lq_weights_view), C.c_void_p]
 _lib.lq_unpack_act.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_int64, C.POINTER(lq_act_view), C.c_void_p]
 
@@ -231,7 +232,8 @@ def lq_quantize_act(cfg: lq_config, packed: torch.Tensor, X: torch.Tensor, act: 
                         torch.zeros((M, cfg.K // 32), dtype=torch.uint8, device=X.device))
         dbg = lq_act_debug(taps.xb.data_ptr(), taps.sxb.data_ptr(), taps.accT.data_ptr(), taps.T.data_ptr(),
                            taps.xbe.data_ptr())
-    _check(_lib.lq_quantize_act(C.byref(cfg), _ptr(packed), _ptr(X), M, X.stride(0), _ptr(act), act.numel(),
+    _check(_lib.lq_quantize_act(C.byref(cfg), _ptr(packed), 0 if packed is None else packed.numel(), _ptr(X), M, X.stride(0),
+                                _ptr(act), act.numel(),
                                 C.byref(dbg) if dbg is not None else None, C.c_void_p(_stream())),
            "lq_quantize_act")
     return (act, taps) if debug else act
@@ -258,7 +260,7 @@ def lq_linear_lowrank_fwd(cfg: lq_config, packed: torch.Tensor, act: torch.Tenso
                         torch.zeros((M, cfg.N), dtype=torch.int32, device=act.device),
                         torch.zeros((M, cfg.N), dtype=torch.float32, device=act.device))
         dbg = lq_fwd_debug(taps.acc.data_ptr() if debug_acc else None, taps.acc2.data_ptr(), taps.y32.data_ptr())
-    _check(_lib.lq_linear_lowrank_fwd(C.byref(cfg), _ptr(packed), _ptr(act), M, _ptr(Y), Y.stride(0),
+    _check(_lib.lq_linear_lowrank_fwd(C.byref(cfg), _ptr(packed), packed.numel(), _ptr(act), act.numel(), M, _ptr(Y), Y.stride(0),
                                       C.byref(dbg) if dbg is not None else None, C.c_void_p(_stream())),
            "lq_linear_lowrank_fwd")
     return (Y, taps) if debug else Y
@@ -281,7 +283,8 @@ def lq_linear_lowrank_fwd_handoff(cfg: lq_config, packed: torch.Tensor, act: tor
         codes = torch.empty(lq_handoff_sizes(next_cfg, M), dtype=torch.uint8, device=act.device)
     if Y is not None:
         assert Y.is_cuda and Y.dtype == torch.bfloat16 and Y.stride(1) == 1 and Y.shape == (M, cfg.N)
-    _check(_lib.lq_linear_lowrank_fwd_handoff(C.byref(cfg), _ptr(packed), _ptr(act), M, _ptr(Y), Y.stride(0) if Y is not None else 0,
+    _check(_lib.lq_linear_lowrank_fwd_handoff(C.byref(cfg), _ptr(packed), packed.numel(), _ptr(act), act.numel(), M, _ptr(Y),
+                                              Y.stride(0) if Y is not None else 0,
                                               C.byref(next_cfg), _ptr(act_next), act_next.numel(), _ptr(codes), codes.numel(),
                                               C.c_void_p(_stream())), "lq_linear_lowrank_fwd_handoff")
     return act_next, codes
@@ -290,7 +293,8 @@ def lq_linear_lowrank_fwd_handoff(cfg: lq_config, packed: torch.Tensor, act: tor
 def lq_branch_from_codes(next_cfg: lq_config, packed_next: torch.Tensor, codes: torch.Tensor, M: int,
                          act_next: torch.Tensor) -> torch.Tensor:
     """Completes act_next (the consumer's intermediate codes and scales) from the hand-off codes."""
-    _check(_lib.lq_branch_from_codes(C.byref(next_cfg), _ptr(packed_next), _ptr(codes), codes.numel(), M, _ptr(act_next),
+    _check(_lib.lq_branch_from_codes(C.byref(next_cfg), _ptr(packed_next), 0 if packed_next is None else packed_next.numel(),
+                                     _ptr(codes), codes.numel(), M, _ptr(act_next),
                                      act_next.numel(), C.c_void_p(_stream())), "lq_branch_from_codes")
     return act_next
 

@@ -232,8 +232,8 @@ lq_status lq_set_smoothing(const lq_config* cfg, const float* gamma, void* packe
     return launch_set_smoothing(d, gamma, (uint8_t*)packed, (hipStream_t)stream) == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }
 
-lq_status lq_quantize_act(const lq_config* cfg, const void* packed, const void* X, int64_t M, int64_t ldx,
-                          void* act, size_t act_bytes, const lq_act_debug* dbg, void* stream)
+lq_status lq_quantize_act(const lq_config* cfg, const void* packed, size_t packed_bytes, const void* X, int64_t M,
+                          int64_t ldx, void* act, size_t act_bytes, const lq_act_debug* dbg, void* stream)
 {
     Dims d;
     lq_status st = make_dims(cfg, &d);
@@ -245,7 +245,7 @@ lq_status lq_quantize_act(const lq_config* cfg, const void* packed, const void* 
     const size_t es = cfg->x_dtype == LQ_BF16 ? 2 : 4;
     if (!aligned(X, 16) || (ldx * es) % 16 != 0 || !aligned(act, 256) || (packed && !aligned(packed, 256)))
         return LQ_ERR_ALIGN;
-    if (act_bytes < act_layout(d, M).total) return LQ_ERR_BUFFER_TOO_SMALL;
+    if (act_bytes < act_layout(d, M).total || (packed && packed_bytes < packed_layout(d).total)) return LQ_ERR_BUFFER_TOO_SMALL;
     hipError_t e = d.mxi ? launch_quantize_act_mxi(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,
                                                    (hipStream_t)stream)
                    : d.mx ? launch_quantize_act_mx(d, cfg->x_dtype, (const uint8_t*)packed, X, M, ldx, (uint8_t*)act, dbg,
@@ -255,8 +255,8 @@ lq_status lq_quantize_act(const lq_config* cfg, const void* packed, const void* 
     return e == hipSuccess ? LQ_OK : LQ_ERR_DEVICE;
 }
 
-lq_status lq_linear_lowrank_fwd(const lq_config* cfg, const void* packed, const void* act, int64_t M, void* Y,
-                                int64_t ldy, const lq_fwd_debug* dbg, void* stream)
+lq_status lq_linear_lowrank_fwd(const lq_config* cfg, const void* packed, size_t packed_bytes, const void* act,
+                                size_t act_bytes, int64_t M, void* Y, int64_t ldy, const lq_fwd_debug* dbg, void* stream)
 {
     Dims d;
     lq_status st = make_dims(cfg, &d);
@@ -265,6 +265,7 @@ lq_status lq_linear_lowrank_fwd(const lq_config* cfg, const void* packed, const 
     if (!packed || !act || !Y) return LQ_ERR_NULL;
     if (M < 1 || M > (1 << 24) || ldy < d.N) return LQ_ERR_SHAPE;
     if (!aligned(packed, 256) || !aligned(act, 256) || !aligned(Y, 16) || (ldy & 7)) return LQ_ERR_ALIGN;
+    if (packed_bytes < packed_layout(d).total || act_bytes < act_layout(d, M).total) return LQ_ERR_BUFFER_TOO_SMALL;
     hipError_t e = d.mxi ? launch_fwd_mxi(d, (const uint8_t*)packed, (const uint8_t*)act, M, (uint16_t*)Y, ldy, dbg,
                                           (hipStream_t)stream)
                    : d.mx ? launch_fwd_mx(d, (const uint8_t*)packed, (const uint8_t*)act, M, (uint16_t*)Y, ldy, dbg,
@@ -293,9 +294,9 @@ lq_status lq_handoff_sizes(const lq_config* next_cfg, int64_t M, size_t* codes_b
     return LQ_OK;
 }
 
-lq_status lq_linear_lowrank_fwd_handoff(const lq_config* cfg, const void* packed, const void* act, int64_t M, void* Y,
-                                        int64_t ldy, const lq_config* next_cfg, void* act_next, size_t act_next_bytes,
-                                        void* codes, size_t codes_bytes, void* stream)
+lq_status lq_linear_lowrank_fwd_handoff(const lq_config* cfg, const void* packed, size_t packed_bytes, const void* act,
+                                        size_t act_bytes, int64_t M, void* Y, int64_t ldy, const lq_config* next_cfg,
+                                        void* act_next, size_t act_next_bytes, void* codes, size_t codes_bytes, void* stream)
 {
     Dims d, dn;
     lq_status st = make_dims(cfg, &d);
@@ -311,15 +312,18 @@ lq_status lq_linear_lowrank_fwd_handoff(const lq_config* cfg, const void* packed
     if (!aligned(packed, 256) || !aligned(act, 256) || !aligned(act_next, 256) || !aligned(codes, 256) ||
         (Y && (!aligned(Y, 16) || (ldy & 7))))
         return LQ_ERR_ALIGN;
-    if (act_next_bytes < act_layout(dn, M).total || codes_bytes < handoff_total_bytes(dn, M)) return LQ_ERR_BUFFER_TOO_SMALL;
+    if (act_next_bytes < act_layout(dn, M).total || codes_bytes < handoff_total_bytes(dn, M) ||
+        packed_bytes < packed_layout(d).total || act_bytes < act_layout(d, M).total)
+        return LQ_ERR_BUFFER_TOO_SMALL;
     return launch_fwd_handoff_mxi(d, (const uint8_t*)packed, (const uint8_t*)act, M, (uint16_t*)Y, Y ? ldy : d.N, dn,
                                   (uint8_t*)act_next, (uint8_t*)codes, (hipStream_t)stream) == hipSuccess
                ? LQ_OK
                : LQ_ERR_DEVICE;
 }
 
-lq_status lq_branch_from_codes(const lq_config* next_cfg, const void* packed_next, const void* codes, size_t codes_bytes,
-                               int64_t M, void* act_next, size_t act_next_bytes, void* stream)
+lq_status lq_branch_from_codes(const lq_config* next_cfg, const void* packed_next, size_t packed_next_bytes,
+                               const void* codes, size_t codes_bytes, int64_t M, void* act_next, size_t act_next_bytes,
+                               void* stream)
 {
     Dims dn;
     if (!next_cfg) return LQ_ERR_NULL;
@@ -329,7 +333,9 @@ lq_status lq_branch_from_codes(const lq_config* next_cfg, const void* packed_nex
     if (!codes || !act_next || (dn.r > 0 && !packed_next)) return LQ_ERR_NULL;
     if (M < 1 || M > (1 << 24)) return LQ_ERR_SHAPE;
     if (!aligned(codes, 256) || !aligned(act_next, 256) || (packed_next && !aligned(packed_next, 256))) return LQ_ERR_ALIGN;
-    if (act_next_bytes < act_layout(dn, M).total || codes_bytes < handoff_total_bytes(dn, M)) return LQ_ERR_BUFFER_TOO_SMALL;
+    if (act_next_bytes < act_layout(dn, M).total || codes_bytes < handoff_total_bytes(dn, M) ||
+        (packed_next && packed_next_bytes < packed_layout(dn).total))
+        return LQ_ERR_BUFFER_TOO_SMALL;
     if (dn.r == 0) return LQ_OK;
     return launch_branch_from_codes_mxi(dn, (const uint8_t*)packed_next, (const uint8_t*)codes, M, (uint8_t*)act_next,
                                         (hipStream_t)stream) == hipSuccess

@@ -139,24 +139,29 @@ def test_argument_errors_before_any_launch(lq):
     assert raw.lq_pack_weights(C.byref(cfg), good, None, good, good, pb, None) == lq.LQ_ERR_NULL
     assert raw.lq_pack_weights(C.byref(cfg), good, good, good, odd, pb, None) == lq.LQ_ERR_ALIGN
     assert raw.lq_pack_weights(C.byref(cfg), good, good, good, good, pb - 1, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
-    assert raw.lq_quantize_act(C.byref(cfg), good, None, 64, 256, good, ab, None, None) == lq.LQ_ERR_NULL
-    assert raw.lq_quantize_act(C.byref(cfg), None, good, 64, 256, good, ab, None, None) == lq.LQ_ERR_NULL
-    assert raw.lq_quantize_act(C.byref(cfg), good, good, -1, 256, good, ab, None, None) == lq.LQ_ERR_SHAPE
+    assert raw.lq_quantize_act(C.byref(cfg), good, pb, None, 64, 256, good, ab, None, None) == lq.LQ_ERR_NULL
+    assert raw.lq_quantize_act(C.byref(cfg), None, 0, good, 64, 256, good, ab, None, None) == lq.LQ_ERR_NULL
+    assert raw.lq_quantize_act(C.byref(cfg), good, pb, good, -1, 256, good, ab, None, None) == lq.LQ_ERR_SHAPE
     # an empty batch is a successful no-op on every per-call entry point: nothing launched, pointers not examined
-    assert raw.lq_quantize_act(C.byref(cfg), None, None, 0, 256, None, 0, None, None) == lq.LQ_OK
-    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), None, None, 0, None, 128, None, None) == lq.LQ_OK
+    assert raw.lq_quantize_act(C.byref(cfg), None, 0, None, 0, 256, None, 0, None, None) == lq.LQ_OK
+    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), None, 0, None, 0, 0, None, 128, None, None) == lq.LQ_OK
     assert raw.lq_unpack_act(C.byref(cfg), None, 0, None, None) == lq.LQ_OK
     zero = C.c_size_t(99)
     assert raw.lq_act_sizes(C.byref(cfg), 0, C.byref(zero)) == lq.LQ_OK and zero.value == 0
     assert raw.lq_act_sizes(C.byref(cfg), -1, C.byref(zero)) == lq.LQ_ERR_SHAPE
-    assert raw.lq_quantize_act(C.byref(cfg), good, good, 64, 255, good, ab, None, None) == lq.LQ_ERR_SHAPE
-    assert raw.lq_quantize_act(C.byref(cfg), good, good, 64, 260, good, ab, None, None) == lq.LQ_ERR_ALIGN
-    assert raw.lq_quantize_act(C.byref(cfg), good, odd, 64, 256, good, ab, None, None) == lq.LQ_ERR_ALIGN
-    assert raw.lq_quantize_act(C.byref(cfg), good, good, 64, 256, good, ab - 1, None, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
-    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, good, 64, None, 128, None, None) == lq.LQ_ERR_NULL
-    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, good, 64, good, 64, None, None) == lq.LQ_ERR_SHAPE
-    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, good, 64, good, 132, None, None) == lq.LQ_ERR_ALIGN
-    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, good, 64, odd, 128, None, None) == lq.LQ_ERR_ALIGN
+    assert raw.lq_quantize_act(C.byref(cfg), good, pb, good, 64, 255, good, ab, None, None) == lq.LQ_ERR_SHAPE
+    assert raw.lq_quantize_act(C.byref(cfg), good, pb, good, 64, 260, good, ab, None, None) == lq.LQ_ERR_ALIGN
+    assert raw.lq_quantize_act(C.byref(cfg), good, pb, odd, 64, 256, good, ab, None, None) == lq.LQ_ERR_ALIGN
+    assert raw.lq_quantize_act(C.byref(cfg), good, pb, good, 64, 256, good, ab - 1, None, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, pb, good, ab, 64, None, 128, None, None) == lq.LQ_ERR_NULL
+    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, pb, good, ab, 64, good, 64, None, None) == lq.LQ_ERR_SHAPE
+    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, pb, good, ab, 64, good, 132, None, None) == lq.LQ_ERR_ALIGN
+    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, pb, good, ab, 64, odd, 128, None, None) == lq.LQ_ERR_ALIGN
+    # a blob smaller than the configuration (or the token count) needs is refused before any launch
+    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, pb - 1, good, ab, 64, good, 128, None, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, pb, good, ab - 1, 64, good, 128, None, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, pb, good, lq.lq_act_sizes(cfg, 32), 64, good, 128, None, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert raw.lq_quantize_act(C.byref(cfg), good, pb - 1, good, 64, 256, good, ab, None, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
     assert raw.lq_unpack_weights(C.byref(cfg), None, None, None) == lq.LQ_ERR_NULL
     assert raw.lq_unpack_act(C.byref(cfg), good, 64, None, None) == lq.LQ_ERR_NULL
     # K beyond the register-resident row of the activation kernels is accepted (long rows are streamed); a wrong row
@@ -164,7 +169,7 @@ def test_argument_errors_before_any_launch(lq):
     for fam in ("int", "mx"):
         big = _cfg(lq, K=8192, family=fam, group=64 if fam == "int" else 32)
         assert raw.lq_act_sizes(C.byref(big), 64, C.byref(C.c_size_t(0))) == lq.LQ_OK
-        assert raw.lq_quantize_act(C.byref(big), good, good, 64, 8000, good, 1 << 30, None, None) == lq.LQ_ERR_SHAPE
+        assert raw.lq_quantize_act(C.byref(big), good, 1 << 40, good, 64, 8000, good, 1 << 30, None, None) == lq.LQ_ERR_SHAPE
 
 
 def test_mxi_contract(lq):
@@ -186,7 +191,7 @@ def test_mxi_contract(lq):
     # the block-local scales need no register-resident row: K is not limited
     good = C.c_void_p(1 << 20)
     big = _cfg(lq, family="mxi", K=8192)
-    assert raw.lq_quantize_act(C.byref(big), good, good, 64, 8000, good, 1 << 30, None, None) == lq.LQ_ERR_SHAPE
+    assert raw.lq_quantize_act(C.byref(big), good, 1 << 40, good, 64, 8000, good, 1 << 30, None, None) == lq.LQ_ERR_SHAPE
     assert raw.lq_act_sizes(C.byref(big), 64, C.byref(n)) == lq.LQ_OK
 
 
@@ -214,7 +219,7 @@ def test_smoothing_contract(lq):
     assert raw.lq_set_smoothing(C.byref(sm), good, C.c_void_p((1 << 20) + 8), pb, None) == lq.LQ_ERR_ALIGN
     # the activation kernel needs the blob even without a branch
     sm0 = lq.make_config(128, 256, 0, smooth=True)
-    assert raw.lq_quantize_act(C.byref(sm0), None, good, 64, 256, good, 1 << 20, None, None) == lq.LQ_ERR_NULL
+    assert raw.lq_quantize_act(C.byref(sm0), None, 0, good, 64, 256, good, 1 << 20, None, None) == lq.LQ_ERR_NULL
     # no K limit with smoothing either (long rows are streamed)
     assert raw.lq_packed_sizes(C.byref(lq.make_config(128, 4608, 32, smooth=True)), C.byref(n)) == lq.LQ_OK
     for fam, bits in (("mx", 8), ("mxb", 8), ("mxb", 6), ("mxi", 8), ("mxi", 4)):
@@ -314,8 +319,8 @@ def test_handoff_contract(lq):
     fake = C.c_void_p(0x1000)     # aligned, never dereferenced: the checks below fail first
     big = 1 << 40
     call = lambda p, c, **kw: raw.lq_linear_lowrank_fwd_handoff(
-        C.byref(p), kw.get("packed", fake), fake, kw.get("M", 100), kw.get("Y", None), 0, C.byref(c), kw.get("act_next", fake),
-        kw.get("anb", big), kw.get("codes", fake), kw.get("cb", big), None)
+        C.byref(p), kw.get("packed", fake), kw.get("pb", big), fake, kw.get("ab", big), kw.get("M", 100), kw.get("Y", None), 0,
+        C.byref(c), kw.get("act_next", fake), kw.get("anb", big), kw.get("codes", fake), kw.get("cb", big), None)
     assert call(prod, lq.make_config(128, 256, 64, "mxi", 32, 8, 8)) == lq.LQ_ERR_SHAPE          # K of the consumer != N
     assert call(_cfg(lq, N=320), cons) == lq.LQ_ERR_UNSUPPORTED                                  # producer outside the family
     assert call(prod, cons, packed=None) == lq.LQ_ERR_NULL
@@ -323,11 +328,14 @@ def test_handoff_contract(lq):
     assert call(prod, cons, act_next=C.c_void_p(0x1010)) == lq.LQ_ERR_ALIGN
     assert call(prod, cons, anb=16) == lq.LQ_ERR_BUFFER_TOO_SMALL
     assert call(prod, cons, cb=16) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert call(prod, cons, pb=lq.lq_packed_sizes(prod) - 1) == lq.LQ_ERR_BUFFER_TOO_SMALL       # the producer's own blobs
+    assert call(prod, cons, ab=lq.lq_act_sizes(prod, 100) - 1) == lq.LQ_ERR_BUFFER_TOO_SMALL
     assert call(prod, cons, M=0) == lq.LQ_OK                                                     # an empty batch
-    br = lambda c, **kw: raw.lq_branch_from_codes(C.byref(c), kw.get("packed", fake), kw.get("codes", fake), kw.get("cb", big),
-                                                  kw.get("M", 100), fake, kw.get("anb", big), None)
+    br = lambda c, **kw: raw.lq_branch_from_codes(C.byref(c), kw.get("packed", fake), kw.get("pb", big), kw.get("codes", fake),
+                                                  kw.get("cb", big), kw.get("M", 100), fake, kw.get("anb", big), None)
     assert br(cons, packed=None) == lq.LQ_ERR_NULL
     assert br(cons, cb=16) == lq.LQ_ERR_BUFFER_TOO_SMALL
+    assert br(cons, pb=64) == lq.LQ_ERR_BUFFER_TOO_SMALL
     assert br(_cfg(lq)) == lq.LQ_ERR_UNSUPPORTED
     assert br(lq.make_config(128, 320, 0, "mxi", 32, 8, 8), packed=None) == lq.LQ_OK             # rank 0: nothing to do
 

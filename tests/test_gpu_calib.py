@@ -123,6 +123,43 @@ def test_full_size_layer_first_step(oracle):
     assert np.abs(_n(got["L"]) - st.L).max() <= 2e-5 and np.abs(_n(got["R"]) - st.R).max() <= 2e-5
 
 
+def test_thousand_steps_from_the_svd_start_at_a_layer_shape(oracle):
+    """The optimisation as the paper runs it (Section 3.2; App. A.2: Adam, lr 1e-4, on the order of a thousand steps) on
+    the 1152 -> 3456 projection: start L = -L0, R = R0 from the best rank-32 approximation of W, 1000 steps on the GPU.
+    The loss of Eq. 4 falls well below that of the start and keeps falling (compared over windows: single steps jitter,
+    the rounding has no gradient); after the run the state is still the oracle's state: from the GPU's factors one more
+    step on both sides gives the same error matrix bit for bit, the same loss and gradients within the accumulation bound."""
+    N, K, r, g = 3456, 1152, 32, 64
+    W, L, R = _problem(N, K, r, seed=21)
+    cfg = _cfg(N, K, r, g, False)
+    Wd = torch.from_numpy(W).cuda()
+    state = lq.lq_calib_init(cfg, torch.from_numpy(L).cuda(), torch.from_numpy(R).cuda())
+    steps, lr = 1000, 1e-4
+    losses = torch.zeros(steps, dtype=torch.float32, device="cuda")
+    for t in range(1, steps + 1):
+        lq.lq_calib_step(cfg, Wd, state, t, lr=lr, loss=losses[t - 1:t])
+    torch.cuda.synchronize()
+    ls = _n(losses).astype(np.float64)
+    assert np.all(np.isfinite(ls)) and np.all(ls > 0)
+    w = ls.reshape(10, 100).mean(axis=1)
+    print("[calib] mean loss per 100 steps, relative to the start:", np.round(w / ls[0], 4))
+    assert w[-1] < 0.9 * ls[0], "1000 steps lower the loss of the SVD start by more than a tenth"
+    assert np.all(np.diff(w) < 0.002 * ls[0]), "the windowed loss does not rise"
+    got = lq.lq_calib_unpack(cfg, state, ("L", "R"))
+    torch.cuda.synchronize()
+    Lg, Rg = _n(got["L"]).copy(), _n(got["R"]).copy()
+    assert np.abs(Lg - L).max() > 10 * lr                         # the factors travelled
+    # one more step from these factors on both sides (fresh moments on both: step number 1)
+    st = oracle.calib_init(Lg, Rg)
+    state2 = lq.lq_calib_init(cfg, torch.from_numpy(Lg).cuda(), torch.from_numpy(Rg).cuda())
+    out, got2, loss, bL, bR = _check_step(oracle, cfg, W, Wd, state2, st, 1, lr, g, False)
+    assert np.array_equal(_n(got2["E"]), out.E)
+    assert abs(loss - out.loss) <= 1e-5 * out.loss
+    assert np.all(np.abs(_n(got2["gL"]) - out.gL) <= bL) and np.all(np.abs(_n(got2["gR"]) - out.gR) <= bR)
+    # the loss the optimiser reported last belongs to (almost) these factors: one step of lr 1e-4 apart
+    assert abs(out.loss - ls[-1]) <= 0.02 * ls[-1]
+
+
 def test_calibrated_factors_feed_the_forward(oracle):
     """End to end: optimise, hand -L and R to lq_pack_weights (it forms W - L' R'), and the packed main codes are
     Q1(W + L R) of the calibration, i.e. the residual whose rounding error the branch now carries."""
