@@ -16,7 +16,8 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "liblq_oracle.so")
+# (LQ_ORACLE_LIB: another build of the same source, e.g. the sanitizer-instrumented one the test suite runs the pins on)
+_LIB_PATH = os.environ.get("LQ_ORACLE_LIB") or os.path.join(_HERE, "liblq_oracle.so")
 _lib = None
 
 
