@@ -52,6 +52,7 @@ struct FwdParams {
     int64_t ldy;
     int M, N, G, C64, rp, nrb;
     int tilesM, tilesN, n_full;
+    int nrb_main;    // row blocks per tile in the region of whole tiles: 4, or 3 where that fills the device better
     int panel;       // column tiles per panel of the tile order (panel_tile)
     int split_last;  // the last tile column has exactly 128 valid channels: run it 2 x 2
     int32_t* dbg_acc;
@@ -299,8 +300,28 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         __syncthreads();
     };
 
-    // Every wavefront runs the same branch-free loop; one without valid output (past the
-    // last column or row block of a partial tile) works on clamped operands, stores nothing.
+    // A wavefront whose columns lie past N (the last tile column of a layer whose width is no multiple of 256) only
+    // stages its row block of the activation codes, barrier for barrier with the others: it issues no matrix or
+    // vector work that would compete with the wavefront it shares a SIMD with.
+    if (cb0 * 32 >= p.N) {  // wave-uniform
+        AStage x0, x1;
+        load_a(x0, 0);
+        load_a(x1, 1);
+        store_a(x0, 0);
+        __syncthreads();
+        for (int s = 0; s < G; s += 2) {  // step s: the codes of step s + 1 go to the other buffer
+            store_a(x1, (s & 1) ^ 1);
+            load_a(x0, s + 2);
+            __syncthreads();
+            if (s + 1 >= G) break;
+            store_a(x0, s & 1);
+            load_a(x1, s + 3);
+            __syncthreads();
+        }
+        return;
+    }
+    // Every other wavefront runs the same branch-free loop; one without valid output (past the last row block of a
+    // partial tile) works on clamped operands, stores nothing.
     SStage s0;
     const std::true_type first{};    // the first step of a tile starts the running sums
     const std::false_type later{};
@@ -499,6 +520,8 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_int_kernel(FwdParams p)
         panel_tile(tile, p.tilesM, p.tilesN, p.panel, tile_m, tile_n);
         if (p.split_last && tile_n == p.tilesN - 1)
             fwd_tile<GC, NK, 2, DBG, true, GA>(p, lds, tile_m * 4, tile_n);
+        else if (!GA && p.nrb_main == 3)
+            fwd_tile<GC, NK, 3, DBG, false, false>(p, lds, tile_m * 3, tile_n);
         else
             fwd_tile<GC, NK, 4, DBG, false, GA>(p, lds, tile_m * 4, tile_n);
     } else {
@@ -532,8 +555,32 @@ static hipError_t launch_cfg(const FwdParams& p0, hipStream_t s)
     FwdParams p = p0;
     p.tilesM = (p.nrb + 3) / 4;
     p.tilesN = (p.N + WN * 64 - 1) / (WN * 64);
-    const int tiles = p.tilesM * p.tilesN;
     const int slots = workgroup_slots() & ~7;
+    // Tile height.  Tiles of 96 rows instead of 128 when they fill the device better: a layer whose 128-row tiles
+    // number between one per compute unit and one per workgroup slot (the 4608 -> 1152 projection: 288 tiles on 512
+    // slots) leaves half the wavefront slots empty while the rest work two to a SIMD; 96-row tiles (430) put more of
+    // the chip to work for three quarters of the time each.  Estimated time of a layout: generations of the grid
+    // times (a fixed part + the tile's row blocks), a lone workgroup on a compute unit counted at 0.6.
+    {
+        auto est = [&](int h) {
+            const int t = ((p.nrb + h - 1) / h) * p.tilesN;
+            const double c = 1.0 + h;
+            if (t <= slots / 2) return 0.6 * c;
+            return (double)((t + slots - 1) / slots) * c;
+        };
+        const int t4 = p.tilesM * p.tilesN;
+        p.nrb_main = (!GA && t4 > slots / 2 && est(3) < 0.9 * est(4)) ? 3 : 4;
+    }
+    if (p.nrb_main == 3) {
+        p.tilesM = (p.nrb + 2) / 3;
+        p.n_full = p.tilesM * p.tilesN;
+        p.split_last = 0;   // (a last tile column of 128 channels: its two wavefronts past the end only stage)
+        p.panel = panel_width(p.tilesN, p.C64, 48);
+        dim3 grid((unsigned)p.n_full), block(NW * 64);
+        hipLaunchKernelGGL((fwd_int_kernel<GC, NK, DBG, GA>), grid, block, 0, s, p);
+        return hipGetLastError();
+    }
+    const int tiles = p.tilesM * p.tilesN;
     // Full rounds of the grid use full tiles.  A half tile costs more than half of a full one (each wavefront
     // reads its weight operands either way), so splitting the remainder pays only while
     // the halves still fit one per compute unit: measured +5 % on a 1152 -> 4608 layer (2.25 rounds),

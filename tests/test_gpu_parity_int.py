@@ -79,11 +79,16 @@ def test_small_shapes_bit_exact(oracle, M, K, N, r, g, bw, ba, xd):
 
 
 @pytest.mark.parametrize("M,K,N,r,g,bw,ba", [(2000, 128, 2304, 16, 64, 8, 8), (2100, 256, 2304, 32, 128, 4, 8),
-                                                 (2100, 128, 2176, 32, 64, 8, 8)])
+                                                 (2100, 128, 2176, 32, 64, 8, 8), (2100, 128, 2240, 32, 64, 8, 8),
+                                                 (4000, 128, 2304, 32, 64, 8, 8), (4100, 192, 2176, 64, 64, 6, 6),
+                                                 (4000, 256, 2240, 32, 128, 4, 8)])
 def test_full_tiles_bit_exact(oracle, M, K, N, r, g, bw, ba):
     """Large enough (more than a quarter of the device's workgroup slots) that the grid runs
     full 128 x 256 tiles, the small shapes above run as half tiles; ragged last row tile; the third
-    case has a last tile column with 128 valid channels (wavefronts arranged 2 x 2 there)."""
+    case has a last tile column with 128 valid channels (wavefronts arranged 2 x 2 there), the fourth one with 192 (its
+    fourth wavefront only stages).  The last three have between one 128-row tile per compute unit and one per workgroup
+    slot and therefore run as 96-row tiles (ragged last tile of one or two row blocks; last tile column of 128 or 192
+    channels, whose wavefronts past the end only stage; 64- and 128-deep groups)."""
     layer = wl.Layer("t", M, K, N, r, "int", g, bw, ba, "bf16", outlier_scale=15.0, n_outliers=2, seed=M + K)
     X, W, L, R = wl.make_inputs(layer)
     _compare_all(oracle, layer, X, W, L, R)
@@ -188,7 +193,7 @@ def _full_size_sampled(oracle, name):
     assert np.array_equal(Yb, out.Y)
 
 
-@pytest.mark.parametrize("name", ["c2_qkv", "c3_fc1", "c4_qkv", "c4_expand"])
+@pytest.mark.parametrize("name", ["c2_qkv", "c3_fc1", "c3_fc2", "c4_qkv", "c4_expand"])
 def test_full_size_whole_tile_row_and_column_panel(oracle, name):
     """Full-size layer with the accumulator taps on: one whole interior 128-row tile row (every channel) and one whole
     interior 256-column panel (every token) against the oracle, per-group accumulators included.  A wrong tile anywhere
