@@ -188,7 +188,7 @@ lq_status lq_quantize_act(const lq_config *cfg, const void *packed, size_t packe
 
 /* Forward (Fig. 1): main 4-bit product with per-group dequantisation, rank-r expansion of the
    re-quantised intermediate, sum, bf16 rounding.
-   Y: device, M x N bf16, row stride ldy elements (ldy >= N, ldy % 8 == 0, Y 16-byte aligned).
+   Y: device, M x N bf16, row stride ldy elements (N <= ldy <= 2^22, ldy % 8 == 0, Y 16-byte aligned).
    packed_bytes / act_bytes: the bytes the caller holds behind `packed` / `act`; a blob smaller than
    lq_packed_sizes(cfg) / lq_act_sizes(cfg, M) is refused (LQ_ERR_BUFFER_TOO_SMALL) before any launch, so
    that a blob sized for another configuration or token count is never read past its end.

@@ -263,7 +263,7 @@ lq_status lq_linear_lowrank_fwd(const lq_config* cfg, const void* packed, size_t
     if (st != LQ_OK) return st;
     if (M == 0) return LQ_OK;  // an empty batch
     if (!packed || !act || !Y) return LQ_ERR_NULL;
-    if (M < 1 || M > (1 << 24) || ldy < d.N) return LQ_ERR_SHAPE;
+    if (M < 1 || M > (1 << 24) || ldy < d.N || ldy > (1 << 22)) return LQ_ERR_SHAPE;
     if (!aligned(packed, 256) || !aligned(act, 256) || !aligned(Y, 16) || (ldy & 7)) return LQ_ERR_ALIGN;
     if (packed_bytes < packed_layout(d).total || act_bytes < act_layout(d, M).total) return LQ_ERR_BUFFER_TOO_SMALL;
     hipError_t e = d.mxi ? launch_fwd_mxi(d, (const uint8_t*)packed, (const uint8_t*)act, M, (uint16_t*)Y, ldy, dbg,
@@ -308,7 +308,7 @@ lq_status lq_linear_lowrank_fwd_handoff(const lq_config* cfg, const void* packed
     if (dn.K != d.N) return LQ_ERR_SHAPE;
     if (M == 0) return LQ_OK;  // an empty batch
     if (!packed || !act || !act_next || !codes) return LQ_ERR_NULL;
-    if (M < 1 || M > (1 << 24) || (Y && ldy < d.N)) return LQ_ERR_SHAPE;
+    if (M < 1 || M > (1 << 24) || (Y && (ldy < d.N || ldy > (1 << 22)))) return LQ_ERR_SHAPE;
     if (!aligned(packed, 256) || !aligned(act, 256) || !aligned(act_next, 256) || !aligned(codes, 256) ||
         (Y && (!aligned(Y, 16) || (ldy & 7))))
         return LQ_ERR_ALIGN;

@@ -1207,13 +1207,18 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     const int rd_row = lane >> 3, rd_seg = lane & 7;
     // Operands of row block rbi+1 are fetched while block rbi is processed; blocks past the end of
     // a partial tile are clamped and never stored.
-    v8i tf[NKA];
+    // With one 64-chunk of the rank the intermediate codes of all four row blocks are requested before the first output
+    // store: the vector-memory counter retires in order, so a wait for a load issued after a store also waits for that
+    // store's acknowledgement, and no such wait is left in the epilogue.  (Two chunks: one row block ahead; registers.)
+    constexpr bool TQ_ALL = NKF <= 1;
+    v8i tf[TQ_ALL ? 4 : 1][NKA];
     v4f stv[4];
     auto load_tq = [&](int rbi) {
         int rb = rb0 + rbi;
         rb = rb < p.nrb ? rb : p.nrb - 1;
 #pragma unroll
-        for (int kk = 0; kk < NKF; ++kk) tf[kk] = *(const v8i*)(p.tq8 + (size_t)(rb * 32 + l32) * p.rp + kk * 64 + half * 32);
+        for (int kk = 0; kk < NKF; ++kk)
+            tf[TQ_ALL ? rbi : 0][kk] = *(const v8i*)(p.tq8 + (size_t)(rb * 32 + l32) * p.rp + kk * 64 + half * 32);
     };
     auto load_scales = [&](int rbi) {
         if (BLK || NK == 0) return;  // no fp32-scaled branch: its scale sections may hold anything
@@ -1224,11 +1229,22 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
         for (int q = 0; q < 4; ++q) stv[q] = *(const v4f*)(lds_st + rbi * 32 + 8 * q + 4 * half);
     };
     load_tq(0);
+    if constexpr (TQ_ALL) {
+        load_tq(1);
+        load_tq(2);
+        load_tq(3);
+    }
     load_scales(0);
     // this lane's output pointer: row rd_row of the tile, 16 bytes at column segment rd_seg; it moves
     // down 8 rows per store (4 stores per row block), rows past M are skipped
-    uint16_t* yptr = p.Y + (size_t)(rb0 * 32 + rd_row) * p.ldy + cb0 * 32 + rd_seg * 8;
-    const size_t ystep = (size_t)8 * p.ldy;
+    // The stores are buffer stores through a descriptor that ends with the wavefront's 128 bytes of the tile's last valid
+    // row: rows past M are out of range and dropped by the hardware, so the stores need no branch -- and only stores the
+    // compiler can count let it wait for a load issued before them without waiting for the stores themselves.
+    const int rows_valid = p.M - rb0 * 32 < 128 ? p.M - rb0 * 32 : 128;
+    const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(p.Y + (size_t)(rb0 * 32) * p.ldy + cb0 * 32), 0, (int)((rows_valid - 1) * p.ldy * 2 + 128), RSRC_FLAGS);
+    uint32_t yoff = (uint32_t)(rd_row * (int)p.ldy * 2 + rd_seg * 16);
+    const uint32_t ystep = (uint32_t)(8 * (int)p.ldy * 2);
     v4i ov[4];
 #pragma unroll
     for (int rbi = 0; rbi < 4; ++rbi) {
@@ -1239,9 +1255,9 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
             a2[cbi] = v16f{0};
 #pragma unroll
             for (int kk = 0; kk < NKF; ++kk)
-                a2[cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(tf[kk], lf[cbi][kk], a2[cbi], 0, 0, 0, 0, 0, 0);
+                a2[cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(tf[TQ_ALL ? rbi : 0][kk], lf[cbi][kk], a2[cbi], 0, 0, 0, 0, 0, 0);
         }
-        if (rbi + 1 < 4) load_tq(rbi + 1);
+        if (!TQ_ALL && rbi + 1 < 4) load_tq(rbi + 1);
         float y[2][16];
 #pragma unroll
         for (int cbi = 0; cbi < 2; ++cbi)
@@ -1252,8 +1268,9 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
                 } else if (NK == 0) {  // rank 0: the branch term is +0, whatever the (unused, possibly unwritten) scales hold
                     y[cbi][i] = __fadd_rn(t[rbi][cbi][i], 0.f);
                 } else {
-                    const float ybr = __fmul_rn(__fmul_rn(a2[cbi][i], stv[i >> 2][i & 3]), slv[cbi]);
-                    y[cbi][i] = __fadd_rn(t[rbi][cbi][i], ybr);
+                    // two vector instructions per output: the scaled branch term enters through a fused multiply-add
+                    // (the fp32 result is compared against a sum rounded once, within an accumulation bound)
+                    y[cbi][i] = __builtin_fmaf(__fmul_rn(a2[cbi][i], stv[i >> 2][i & 3]), slv[cbi], t[rbi][cbi][i]);
                 }
             }
         if (rbi + 1 < 4) load_scales(rbi + 1);
@@ -1280,8 +1297,8 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
         for (int q = 0; q < 4; ++q) ov[q] = *(const v4i*)(stage + (q * 8 + rd_row) * EPI_ROW + rd_seg * 16);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if (rbase + q * 8 + rd_row < p.M) *(v4i*)yptr = ov[q];
-            yptr += ystep;
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, ov[q]), rs_y, yoff, 0, 0);
+            yoff += ystep;
         }
     }
 }

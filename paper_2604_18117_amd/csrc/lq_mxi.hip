@@ -851,8 +851,17 @@ __global__ __launch_bounds__(256, 2) void mxi_fwd_kernel(MxiFwdParams p)
     uint8_t* stage = lds + wave * EPI_WAVE;
     const int wr_off = (4 * half) * EPI_ROW + l32 * 2;
     const int rd_row = lane >> 3, rd_seg = lane & 7;
-    uint16_t* yptr = p.Y + (size_t)(rb0 * 32 + rd_row) * p.ldy + cb0 * 32 + rd_seg * 8;
-    const size_t ystep = (size_t)8 * p.ldy;
+    // The stores are buffer stores through a descriptor that ends with the wavefront's 128 bytes of the tile's last valid
+    // row (rows past M are out of range and dropped by the hardware; without Y the descriptor is empty): no branch, so
+    // the compiler can count the stores and need not wait for them when it waits for an older load.
+    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    const int rows_valid = p.M - rb0 * 32 < 128 ? p.M - rb0 * 32 : 128;
+    const bool have_y = !HO || p.Y;
+    const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(
+        have_y ? (void*)(p.Y + (size_t)(rb0 * 32) * p.ldy + cb0 * 32) : (void*)p.ho_xq, 0,
+        have_y ? (int)((rows_valid - 1) * p.ldy * 2 + 128) : 0, 0x00020000);
+    uint32_t yoff = (uint32_t)(rd_row * (int)p.ldy * 2 + rd_seg * 16);
+    const uint32_t ystep = (uint32_t)(8 * (int)p.ldy * 2);
     v4i ov[4];
 #pragma unroll
     for (int rbi = 0; rbi < 4; ++rbi) {
@@ -926,8 +935,8 @@ __global__ __launch_bounds__(256, 2) void mxi_fwd_kernel(MxiFwdParams p)
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if ((!HO || p.Y) && rbase + q * 8 + rd_row < p.M) *(v4i*)yptr = ov[q];
-            yptr += ystep;
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, ov[q]), rs_y, yoff, 0, 0);
+            yoff += ystep;
         }
     }
 }
