@@ -20,6 +20,7 @@
 
 namespace lq {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -985,14 +986,17 @@ template <int NK, bool DBG, bool BLK, int BFMT = 0>
 __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
 {
     constexpr int WN = 4, RBT = 4;
-    constexpr int EPI_ROW = 144, EPI_WAVE = 32 * EPI_ROW;
+    constexpr int EPI_ROW = 136, EPI_WAVE = 32 * EPI_ROW;
     constexpr int NBUF = 4;                          // LDS buffers of the activation stream (one stage each)
     constexpr int LDS_MAIN = NBUF * 2 * RBT * 1024;  // [buffer][chunk in stage][row block][lane][16 B]
     constexpr int LDS_BYTES = LDS_MAIN > 4 * EPI_WAVE ? LDS_MAIN : 4 * EPI_WAVE;
     // + the tile's 128 per-token scales of the fp32-scaled branch (read back by every wavefront in the epilogue: an LDS
     // broadcast read instead of sixteen 1 KB vector-memory loads per wavefront whose lanes all fetch the same 16 bytes)
-    __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES + RBT * 32 * 4];
+    // ... and the tile's 256 per-channel scales of that branch; both are small loads whose round trip would otherwise
+    // open the epilogue
+    __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES + RBT * 32 * 4 + WN * 64 * 4];
     float* lds_st = (float*)(lds + LDS_BYTES);
+    float* lds_sl = lds_st + RBT * 32;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1105,12 +1109,14 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
             for (int cbi = 0; cbi < 2; ++cbi) {
                 const v4i bq = b.v[cc][cbi];
                 const v8i b8 = {bq[0], bq[1], bq[2], bq[3], 0, 0, 0, 0};
+                // the weights are the first operand: a lane then holds one token and, per register quad, four
+                // consecutive channels (the epilogue packs them into 8-byte LDS writes)
                 if (cc == 0)
-                    t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, t[rbi][cbi], 4, 4, 2 * PAR,
-                                                                                 sc.a[rbi], 2 * PAR, sc.b[cbi]);
+                    t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b8, a8, t[rbi][cbi], 4, 4, 2 * PAR,
+                                                                                 sc.b[cbi], 2 * PAR, sc.a[rbi]);
                 else
-                    t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, t[rbi][cbi], 4, 4, 2 * PAR + 1,
-                                                                                 sc.a[rbi], 2 * PAR + 1, sc.b[cbi]);
+                    t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b8, a8, t[rbi][cbi], 4, 4, 2 * PAR + 1,
+                                                                                 sc.b[cbi], 2 * PAR + 1, sc.a[rbi]);
             }
             if (f == 7) load_b(b, s + 2);
             __builtin_amdgcn_sched_barrier(0);
@@ -1127,6 +1133,7 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     load_s(s0, 0);
     if constexpr (!BLK && NK > 0) {
         if (lane < 32) lds_st[wave * 32 + lane] = p.st[rbs * 32 + lane];
+        lds_sl[wave * 64 + lane] = p.sl[cbw * 32 + lane];
     }
     store_a(a0, 0);
     store_a(a1, 1);
@@ -1135,6 +1142,32 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     load_a(a1, 3);
     load_b(b1, 1);
     load_s(s1, 1);
+    // Operands of the epilogue's first matrix instructions (the branch's channel codes, the intermediate codes of the
+    // first row block) are requested here: asked for at the start of the epilogue, their round trip would open it.
+    constexpr int NKF = BLK ? 0 : NK;  // chunks of the fp32-scaled branch handled in the epilogue
+    constexpr int NKA = NKF > 0 ? NKF : 1;
+    constexpr bool TQ_ALL = NKF <= 1;
+    v8i lf[2][NKA];
+    v8i tf[TQ_ALL ? 4 : 1][NKA];
+    auto load_tq = [&](int rbi) {
+        int rb = rb0 + rbi;
+        rb = rb < p.nrb ? rb : p.nrb - 1;
+#pragma unroll
+        for (int kk = 0; kk < NKF; ++kk)
+            tf[TQ_ALL ? rbi : 0][kk] = *(const v8i*)(p.tq8 + (size_t)(rb * 32 + l32) * p.rp + kk * 64 + half * 32);
+    };
+    auto load_lf = [&]() {
+#pragma unroll
+        for (int cbi = 0; cbi < 2; ++cbi)
+#pragma unroll
+            for (int kk = 0; kk < NKF; ++kk)
+                lf[cbi][kk] = *(const v8i*)(p.l8 + (size_t)((cbw + cbi) * 32 + l32) * p.rp + kk * 64 + half * 32);
+    };
+    constexpr bool EARLY = NKF == 1;  // (two chunks: the registers are not there; the epilogue requests them itself)
+    if constexpr (EARLY) {
+        load_lf();
+        load_tq(0);
+    }
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
     fr[0] = lds_frag(0, 0);
@@ -1180,63 +1213,42 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
 #pragma unroll
                 for (int cbi = 0; cbi < 2; ++cbi) {
                     if (cc == 0)
-                        t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ta, lb[cbi], t[rbi][cbi], BFMT, BFMT, 0, tsc, 0, lsc[cbi]);
+                        t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(lb[cbi], ta, t[rbi][cbi], BFMT, BFMT, 0, lsc[cbi], 0, tsc);
                     else
-                        t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ta, lb[cbi], t[rbi][cbi], BFMT, BFMT, 1, tsc, 1, lsc[cbi]);
+                        t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(lb[cbi], ta, t[rbi][cbi], BFMT, BFMT, 1, lsc[cbi], 1, tsc);
                 }
             }
         }
     }
 
-    // ---- epilogue: FP8 rank-r expansion, scales, sum, bf16, transposed full-line stores -------
+    // ---- epilogue: FP8 rank-r expansion, scales, sum, bf16, full-line stores -------
+    // A lane holds token l32 of a row block and, in registers 4g .. 4g+3 of a 32 x 32 tile, channels 8g + 4 half + 0..3:
+    // four bf16 values = one 8-byte LDS write; the block is read back row-wise, 16 bytes per lane.
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     typedef float f32x2 __attribute__((ext_vector_type(2)));
-    constexpr int NKF = BLK ? 0 : NK;  // chunks of the fp32-scaled branch handled in this epilogue
-    constexpr int NKA = NKF > 0 ? NKF : 1;
     uint8_t* stage = lds + wave * EPI_WAVE;
-    float slv[2] = {0.f, 0.f};
-    v8i lf[2][NKA];
+    v4f slv[2][4];  // channel scales of the branch, in register order
 #pragma unroll
     for (int cbi = 0; cbi < 2; ++cbi) {
-        const int col = (cb0 + cbi) * 32 + l32;
-        if (!BLK && NK > 0) slv[cbi] = p.sl[col];
+        if (!BLK && NK > 0) {
 #pragma unroll
-        for (int kk = 0; kk < NKF; ++kk) lf[cbi][kk] = *(const v8i*)(p.l8 + (size_t)col * p.rp + kk * 64 + half * 32);
+            for (int g = 0; g < 4; ++g) slv[cbi][g] = *(const v4f*)(lds_sl + wave * 64 + cbi * 32 + 8 * g + 4 * half);
+        }
     }
-    const int wr_off = (4 * half) * EPI_ROW + l32 * 2;
+    const int wr_off = l32 * EPI_ROW + half * 8;
     const int rd_row = lane >> 3, rd_seg = lane & 7;
-    // Operands of row block rbi+1 are fetched while block rbi is processed; blocks past the end of
-    // a partial tile are clamped and never stored.
-    // With one 64-chunk of the rank the intermediate codes of all four row blocks are requested before the first output
-    // store: the vector-memory counter retires in order, so a wait for a load issued after a store also waits for that
-    // store's acknowledgement, and no such wait is left in the epilogue.  (Two chunks: one row block ahead; registers.)
-    constexpr bool TQ_ALL = NKF <= 1;
-    v8i tf[TQ_ALL ? 4 : 1][NKA];
-    v4f stv[4];
-    auto load_tq = [&](int rbi) {
-        int rb = rb0 + rbi;
-        rb = rb < p.nrb ? rb : p.nrb - 1;
-#pragma unroll
-        for (int kk = 0; kk < NKF; ++kk)
-            tf[TQ_ALL ? rbi : 0][kk] = *(const v8i*)(p.tq8 + (size_t)(rb * 32 + l32) * p.rp + kk * 64 + half * 32);
-    };
-    auto load_scales = [&](int rbi) {
-        if (BLK || NK == 0) return;  // no fp32-scaled branch: its scale sections may hold anything
-        int rb = rb0 + rbi;
-        rb = rb < p.nrb ? rb : p.nrb - 1;
-        (void)rb;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) stv[q] = *(const v4f*)(lds_st + rbi * 32 + 8 * q + 4 * half);
-    };
-    load_tq(0);
+    // With one 64-chunk of the rank the intermediate codes of the other three row blocks are requested before the first
+    // output store: the vector-memory counter retires in order, so a wait for a load issued after a store also waits for
+    // that store's acknowledgement, and no such wait is left in the epilogue.  (Two chunks: one row block ahead; registers.)
+    if constexpr (!EARLY) {
+        load_lf();
+        load_tq(0);
+    }
     if constexpr (TQ_ALL) {
         load_tq(1);
         load_tq(2);
         load_tq(3);
     }
-    load_scales(0);
-    // this lane's output pointer: row rd_row of the tile, 16 bytes at column segment rd_seg; it moves
-    // down 8 rows per store (4 stores per row block), rows past M are skipped
     // The stores are buffer stores through a descriptor that ends with the wavefront's 128 bytes of the tile's last valid
     // row: rows past M are out of range and dropped by the hardware, so the stores need no branch -- and only stores the
     // compiler can count let it wait for a load issued before them without waiting for the stores themselves.
@@ -1255,9 +1267,10 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
             a2[cbi] = v16f{0};
 #pragma unroll
             for (int kk = 0; kk < NKF; ++kk)
-                a2[cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(tf[TQ_ALL ? rbi : 0][kk], lf[cbi][kk], a2[cbi], 0, 0, 0, 0, 0, 0);
+                a2[cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(lf[cbi][kk], tf[TQ_ALL ? rbi : 0][kk], a2[cbi], 0, 0, 0, 0, 0, 0);
         }
         if (!TQ_ALL && rbi + 1 < 4) load_tq(rbi + 1);
+        const float stl = (!BLK && NK > 0) ? lds_st[rbi * 32 + l32] : 0.f;  // this lane's token
         float y[2][16];
 #pragma unroll
         for (int cbi = 0; cbi < 2; ++cbi)
@@ -1270,31 +1283,32 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
                 } else {
                     // two vector instructions per output: the scaled branch term enters through a fused multiply-add
                     // (the fp32 result is compared against a sum rounded once, within an accumulation bound)
-                    y[cbi][i] = __builtin_fmaf(__fmul_rn(a2[cbi][i], stv[i >> 2][i & 3]), slv[cbi], t[rbi][cbi][i]);
+                    y[cbi][i] = __builtin_fmaf(__fmul_rn(a2[cbi][i], stl), slv[cbi][i >> 2][i & 3], t[rbi][cbi][i]);
                 }
             }
-        if (rbi + 1 < 4) load_scales(rbi + 1);
 #pragma unroll
         for (int cbi = 0; cbi < 2; ++cbi) {
 #pragma unroll
-            for (int i = 0; i < 16; i += 2) {
-                const bf16x2 h = __builtin_convertvector(f32x2{y[cbi][i], y[cbi][i + 1]}, bf16x2);
-                const uint32_t w = __builtin_bit_cast(uint32_t, h);
-                const int o = wr_off + (8 * (i >> 2) + (i & 3)) * EPI_ROW + cbi * 64;
-                *(uint16_t*)(stage + o) = (uint16_t)(w & 0xFFFFu);
-                *(uint16_t*)(stage + o + EPI_ROW) = (uint16_t)(w >> 16);
+            for (int g = 0; g < 4; ++g) {
+                const bf16x2 h0 = __builtin_convertvector(f32x2{y[cbi][4 * g], y[cbi][4 * g + 1]}, bf16x2);
+                const bf16x2 h1 = __builtin_convertvector(f32x2{y[cbi][4 * g + 2], y[cbi][4 * g + 3]}, bf16x2);
+                *(v2i*)(stage + wr_off + cbi * 64 + g * 16) = v2i{__builtin_bit_cast(int, h0), __builtin_bit_cast(int, h1)};
             }
             if (DBG) {
-                const int col = (cb0 + cbi) * 32 + l32;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int row = rbase + 8 * (i >> 2) + 4 * half + (i & 3);
+                    const int row = rbase + l32;
+                    const int col = (cb0 + cbi) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
                     if (row < p.M && p.dbg_y32) p.dbg_y32[(size_t)row * p.N + col] = y[cbi][i];
                 }
             }
         }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) ov[q] = *(const v4i*)(stage + (q * 8 + rd_row) * EPI_ROW + rd_seg * 16);
+        for (int q = 0; q < 4; ++q) {
+            const uint8_t* src = stage + (q * 8 + rd_row) * EPI_ROW + rd_seg * 16;
+            const v2i lo = *(const v2i*)src, hi = *(const v2i*)(src + 8);
+            ov[q] = v4i{lo[0], lo[1], hi[0], hi[1]};
+        }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, ov[q]), rs_y, yoff, 0, 0);
