@@ -90,6 +90,22 @@ constexpr int lds_bytes()
     return 2 * GC * RBT * lds_slot<GA>() > NW * EPI_WAVE ? 2 * GC * RBT * lds_slot<GA>() : NW * EPI_WAVE;
 }
 
+// Epilogue operands parked in LDS (64-deep groups): a tile's per-token scales, intermediate codes, and each wavefront's
+// channel scales and channel codes are fetched in the prologue, when the running sums do not exist yet and registers
+// are free, and wait in LDS; requested at the start of the epilogue, their round trip through the memory system
+// (nothing else is left to do by then) would open every tile's epilogue.  sx[128] st[128] | sl[4][64] | lq[4][2][NK][64 x 16 B] |
+// tq[4][NK][64 x 16 B]
+template <int GC, int NK, bool GA>
+constexpr bool park_epilogue()
+{
+    return GC == 1 && !GA;
+}
+template <int NK>
+constexpr int park_bytes()
+{
+    return 2048 + 12 * (NK > 0 ? NK : 1) * 1024;
+}
+
 // One output tile: rows rb0*32.., columns tile_n*256...  Each wavefront owns NRB row blocks x 64
 // columns.  SPLIT = false: the 4 wavefronts sit side by side (tile of NRB*32 x 256).  SPLIT = true
 // (NRB = 2): they are arranged 2 x 2 over a 128 x 128 tile, used for a last tile column that has
@@ -303,10 +319,52 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     // A wavefront whose columns lie past N (the last tile column of a layer whose width is no multiple of 256) only
     // stages its row block of the activation codes, barrier for barrier with the others: it issues no matrix or
     // vector work that would compete with the wavefront it shares a SIMD with.
+    constexpr bool PARK = park_epilogue<GC, NK, GA>();
+    constexpr int NKP = NK > 0 ? NK : 1;
+    uint8_t* park = lds + lds_bytes<GC, GA>();
+    float* park_sx = (float*)park;
+    float* park_st = (float*)(park + 512);
+    float* park_sl = (float*)(park + 1024) + wave * 64;
+    uint8_t* park_lq = park + 2048 + wave * 2 * NKP * 1024;
+    uint8_t* park_tq = park + 2048 + 8 * NKP * 1024;
+    struct ParkRows { float sx, st; v4i tq[NKP]; };
+    struct ParkCols { float sl; v4i lq[2][NKP]; };
+    auto park_load_rows = [&](ParkRows& r) {  // of the row block this wavefront stages
+        r.sx = p.sx[rbs * 32 + l32];
+        r.st = p.st[rbs * 32 + l32];
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) r.tq[kk] = *(const v4i*)(p.tq + (size_t)(rbs * 32 + l32) * p.rp + kk * 32 + half * 16);
+    };
+    auto park_store_rows = [&](const ParkRows& r) {
+        park_sx[wave * 32 + l32] = r.sx;  // (both halves of the wavefront write the same value)
+        park_st[wave * 32 + l32] = r.st;
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) *(v4i*)(park_tq + (size_t)((wave * NKP + kk) * 1024) + lane16) = r.tq[kk];
+    };
+    auto park_load_cols = [&](ParkCols& c) {
+        c.sl = p.sl[cb0 * 32 + lane];
+#pragma unroll
+        for (int cbi = 0; cbi < 2; ++cbi)
+#pragma unroll
+            for (int kk = 0; kk < NK; ++kk)
+                c.lq[cbi][kk] = *(const v4i*)(p.lq + (size_t)((cb0 + cbi) * 32 + l32) * p.rp + kk * 32 + half * 16);
+    };
+    auto park_store_cols = [&](const ParkCols& c) {
+        park_sl[lane] = c.sl;
+#pragma unroll
+        for (int cbi = 0; cbi < 2; ++cbi)
+#pragma unroll
+            for (int kk = 0; kk < NK; ++kk) *(v4i*)(park_lq + (size_t)((cbi * NKP + kk) * 1024) + lane16) = c.lq[cbi][kk];
+    };
     if (cb0 * 32 >= p.N) {  // wave-uniform
         AStage x0, x1;
         load_a(x0, 0);
         load_a(x1, 1);
+        if constexpr (PARK) {  // the other wavefronts read this row block's epilogue operands from LDS
+            ParkRows pr;
+            park_load_rows(pr);
+            park_store_rows(pr);
+        }
         store_a(x0, 0);
         __syncthreads();
         for (int s = 0; s < G; s += 2) {  // step s: the codes of step s + 1 go to the other buffer
@@ -334,7 +392,17 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         load_b(b1, 1);
         store_a(a0, 0);
         load_a(a0, 2);   // (goes to LDS during step 1)
-        __syncthreads();
+        if constexpr (PARK) {
+            ParkRows pr;
+            ParkCols pc;
+            park_load_rows(pr);
+            park_load_cols(pc);
+            __syncthreads();
+            park_store_rows(pr);
+            park_store_cols(pc);
+        } else {
+            __syncthreads();
+        }
         load_s(s0, 0);
         // step s reads weight set s % 3 and requests set (s + 2) % 3; activation set (s + 1) % 2 goes to LDS
         do_step(first, 0, a1, b0, b2, s0);
@@ -406,10 +474,16 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
 #pragma unroll
     for (int cbi = 0; cbi < 2; ++cbi) {
         const int col = (cb0 + cbi) * 32 + l32;
-        slv[cbi] = p.sl[col];
+        if constexpr (PARK) {
+            slv[cbi] = park_sl[cbi * 32 + l32];
 #pragma unroll
-        for (int kk = 0; kk < NK; ++kk)
-            lqf[cbi][kk] = *(const v4i*)(p.lq + (size_t)col * p.rp + kk * 32 + half * 16);
+            for (int kk = 0; kk < NK; ++kk) lqf[cbi][kk] = *(const v4i*)(park_lq + (size_t)((cbi * NKP + kk) * 1024) + lane16);
+        } else {
+            slv[cbi] = p.sl[col];
+#pragma unroll
+            for (int kk = 0; kk < NK; ++kk)
+                lqf[cbi][kk] = *(const v4i*)(p.lq + (size_t)col * p.rp + kk * 32 + half * 16);
+        }
     }
     const int wr_off = (4 * half) * EPI_ROW + l32 * 2;        // this lane's column in the staged block
     const int rd_row = lane >> 3, rd_seg = lane & 7;          // read-back: 8 lanes per 128-byte row
@@ -419,6 +493,12 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     v4i tqf[NKA];
     v4f sxv[4], stv[4];
     auto load_tq = [&](int rbi) {
+        if constexpr (PARK) {  // (slot of the wavefront that staged this row block)
+#pragma unroll
+            for (int kk = 0; kk < NK; ++kk)
+                tqf[kk] = *(const v4i*)(park_tq + (size_t)(((wm * NRB + rbi) * NKP + kk) * 1024) + lane16);
+            return;
+        }
         int rb = rbw + rbi;
         rb = rb < p.nrb ? rb : p.nrb - 1;
 #pragma unroll
@@ -426,6 +506,14 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
             tqf[kk] = *(const v4i*)(p.tq + (size_t)(rb * 32 + l32) * p.rp + kk * 32 + half * 16);
     };
     auto load_scales = [&](int rbi) {  // rows 8*q + 4*half + 0..3 are contiguous -> one 16-byte load each
+        if constexpr (PARK) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                sxv[q] = *(const v4f*)(park_sx + (wm * NRB + rbi) * 32 + 8 * q + 4 * half);
+                stv[q] = *(const v4f*)(park_st + (wm * NRB + rbi) * 32 + 8 * q + 4 * half);
+            }
+            return;
+        }
         int rb = rbw + rbi;
         rb = rb < p.nrb ? rb : p.nrb - 1;
 #pragma unroll
@@ -529,7 +617,8 @@ __device__ __forceinline__ int xcd_order(int b, int n)
 template <int GC, int NK, bool DBG, bool GA = false>
 __global__ __launch_bounds__(NW * 64, 2) void fwd_int_kernel(FwdParams p)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[lds_bytes<GC, GA>() + (GA ? GA_MAXG * 512 : 0)];
+    __shared__ __attribute__((aligned(16))) uint8_t lds[lds_bytes<GC, GA>() + (GA ? GA_MAXG * 512 : 0) +
+                                                       (park_epilogue<GC, NK, GA>() ? park_bytes<NK>() : 0)];
     const int b = blockIdx.x;
     if (b < p.n_full) {
         const int tile = xcd_order(b, p.n_full);
