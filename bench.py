@@ -25,12 +25,12 @@ PEAK_MFMA_TFLOPS = {"int": 5033.0, "mx": 10066.0, "mxb": 10066.0, "mxi": 5033.0}
 # commands and the raw figures are in profiles/hbm_traffic_forward_kernels.md), each scaled by the factor a plain copy
 # of known size gives for the same counter.  A workload without an entry reports "traffic": null.
 TRAFFIC_KIB = {    # name -> (FETCH_SIZE KiB, WRITE_SIZE KiB) per forward dispatch
-    "c2_qkv": (23316.7, 55296.0), "c3_fc1": (33510.0, 73728.0), "c3_fc2": (49937.9, 18432.0),
-    "c4_qkv": (84828.3, 107520.0), "c4_expand": (142838.4, 179200.0),
-    "c5_qkv": (35631.7, 110592.0), "c5_attn_out": (11446.7, 36864.0), "c5_cross_kv": (19981.3, 73728.0),
-    "c5_fc1": (44131.2, 147456.0), "c5_fc2": (55962.2, 36864.0),
+    "c2_qkv": (23067.7, 55296.0), "c3_fc1": (34074.1, 74752.0), "c3_fc2": (50272.8, 18432.0),
+    "c4_qkv": (85620.8, 107520.0), "c4_expand": (141964.1, 179200.0),
+    "c5_qkv": (32643.3, 110592.0), "c5_attn_out": (11150.8, 36864.0), "c5_cross_kv": (17891.1, 73728.0),
+    "c5_fc1": (44283.0, 147456.0), "c5_fc2": (56317.4, 36864.0),
     # same shape, same kernel as c5_attn_out (1152 -> 1152 on 16384 tokens)
-    "c5_cross_q": (11446.7, 36864.0), "c5_cross_out": (11446.7, 36864.0),
+    "c5_cross_q": (11150.8, 36864.0), "c5_cross_out": (11150.8, 36864.0),
 }
 TRAFFIC_SCALE = (2.0, 1.0)   # copy-kernel calibration of FETCH_SIZE and WRITE_SIZE
 HEADLINE = "c4_expand"

@@ -156,6 +156,8 @@ def test_argument_errors_before_any_launch(lq):
     assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, pb, good, ab, 64, None, 128, None, None) == lq.LQ_ERR_NULL
     assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, pb, good, ab, 64, good, 64, None, None) == lq.LQ_ERR_SHAPE
     assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, pb, good, ab, 64, good, 132, None, None) == lq.LQ_ERR_ALIGN
+    # row strides beyond 2^22 elements do not fit the 32-bit offsets of the output's buffer stores
+    assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, pb, good, ab, 64, good, (1 << 22) + 8, None, None) == lq.LQ_ERR_SHAPE
     assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, pb, good, ab, 64, odd, 128, None, None) == lq.LQ_ERR_ALIGN
     # a blob smaller than the configuration (or the token count) needs is refused before any launch
     assert raw.lq_linear_lowrank_fwd(C.byref(cfg), good, pb - 1, good, ab, 64, good, 128, None, None) == lq.LQ_ERR_BUFFER_TOO_SMALL
