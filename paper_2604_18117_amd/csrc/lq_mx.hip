@@ -976,25 +976,32 @@ struct MxFwdParams {
     int64_t ldy;
     int M, N, C64, CQ, S, rp, nrb;
     int tilesM, tilesN, panel;
+    int n_full;  // workgroups that compute whole tiles; the rest of the grid are half tiles
     float* dbg_y32;
 };
 
 // NK = 64-deep chunks of the (padded) rank: 0 | 1 | 2.  BLK: the branch is MXFP8e4 (block scales,
 // accumulated by the scaled MFMA straight into the main product's accumulators).
 // BFMT: operand format code of the block-scaled branch (0 = E4M3, 2 = E2M3).
-template <int NK, bool DBG, bool BLK, int BFMT = 0>
-__global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
+namespace mxf {
+constexpr int WN = 4, RBT = 4;
+constexpr int EPI_ROW = 136, EPI_WAVE = 32 * EPI_ROW;
+constexpr int NBUF = 4;                          // LDS buffers of the activation stream (one stage each)
+constexpr int LDS_MAIN = NBUF * 2 * RBT * 1024;  // [buffer][chunk in stage][row block][lane][16 B]
+constexpr int LDS_BYTES = LDS_MAIN > 4 * EPI_WAVE ? LDS_MAIN : 4 * EPI_WAVE;
+constexpr int LDS_TOTAL = LDS_BYTES + RBT * 32 * 4 + WN * 64 * 4;
+}  // namespace mxf
+
+// One output tile: row blocks rb0 .. rb0 + NRB - 1 (NRB = 4: a whole 128-row tile; 2: a half tile of the grid's last,
+// sparse generation), columns tile_n * 256 ...  The four wavefronts always stage four row blocks (clamped).
+template <int NK, bool DBG, bool BLK, int BFMT, int NRB>
+__device__ __forceinline__ void mx_fwd_tile(const MxFwdParams& p, uint8_t* lds, const int rb0, const int tile_n)
 {
-    constexpr int WN = 4, RBT = 4;
-    constexpr int EPI_ROW = 136, EPI_WAVE = 32 * EPI_ROW;
-    constexpr int NBUF = 4;                          // LDS buffers of the activation stream (one stage each)
-    constexpr int LDS_MAIN = NBUF * 2 * RBT * 1024;  // [buffer][chunk in stage][row block][lane][16 B]
-    constexpr int LDS_BYTES = LDS_MAIN > 4 * EPI_WAVE ? LDS_MAIN : 4 * EPI_WAVE;
+    using namespace mxf;
     // + the tile's 128 per-token scales of the fp32-scaled branch (read back by every wavefront in the epilogue: an LDS
     // broadcast read instead of sixteen 1 KB vector-memory loads per wavefront whose lanes all fetch the same 16 bytes)
     // ... and the tile's 256 per-channel scales of that branch; both are small loads whose round trip would otherwise
     // open the epilogue
-    __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES + RBT * 32 * 4 + WN * 64 * 4];
     float* lds_st = (float*)(lds + LDS_BYTES);
     float* lds_sl = lds_st + RBT * 32;
 
@@ -1002,13 +1009,6 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
 
-    const int tiles = p.tilesM * p.tilesN;
-    const int per = tiles >> 3, rem = tiles & 7;
-    const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
-    const int tile = xcd * per + (xcd < rem ? xcd : rem) + loc;
-    int tile_m, tile_n;
-    panel_tile(tile, p.tilesM, p.tilesN, p.panel, tile_m, tile_n);
-    const int rb0 = tile_m * RBT;
     const int cb0 = tile_n * (WN * 2) + wave * 2;
     const bool active = (cb0 * 32 < p.N) && (rb0 < p.nrb);
     const int C64 = p.C64, CQ = p.CQ, S = p.S;
@@ -1020,9 +1020,9 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     const int cbw = (cb0 * 32 < p.N) ? cb0 : 0;
     const uint8_t* pc_base[2] = {p.pc + (size_t)cbw * C64 * 1024, p.pc + (size_t)(cbw + 1) * C64 * 1024};
     const uint8_t* pe_base[2] = {p.pe + (size_t)cbw * CQ * 256, p.pe + (size_t)(cbw + 1) * CQ * 256};
-    const uint8_t* xe_base[4];
+    const uint8_t* xe_base[NRB];
 #pragma unroll
-    for (int rbi = 0; rbi < 4; ++rbi) {
+    for (int rbi = 0; rbi < NRB; ++rbi) {
         int rb = rb0 + rbi;
         rb = rb < p.nrb ? rb : p.nrb - 1;
         xe_base[rbi] = p.xe + (size_t)rb * CQ * 256;
@@ -1037,9 +1037,9 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     constexpr int RSRC_FLAGS = 0x00020000;
     const __amdgpu_buffer_rsrc_t rs_pe[2] = {__builtin_amdgcn_make_buffer_rsrc((void*)pe_base[0], 0, CQ * 256, RSRC_FLAGS),
                                              __builtin_amdgcn_make_buffer_rsrc((void*)pe_base[1], 0, CQ * 256, RSRC_FLAGS)};
-    __amdgpu_buffer_rsrc_t rs_xe[4];
+    __amdgpu_buffer_rsrc_t rs_xe[NRB];
 #pragma unroll
-    for (int rbi = 0; rbi < 4; ++rbi) rs_xe[rbi] = __builtin_amdgcn_make_buffer_rsrc((void*)xe_base[rbi], 0, CQ * 256, RSRC_FLAGS);
+    for (int rbi = 0; rbi < NRB; ++rbi) rs_xe[rbi] = __builtin_amdgcn_make_buffer_rsrc((void*)xe_base[rbi], 0, CQ * 256, RSRC_FLAGS);
     // A load for a stage (or quad of chunks) past the end goes through a descriptor of zero bytes: every lane is out of
     // range, nothing is fetched and the (unused) result is zero; the loop body stays branch-free.
     auto load_a = [&](AStage& a, int stage) {
@@ -1066,18 +1066,18 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
         }
     };
     // scale dwords of one quad of chunks (= two stages)
-    struct Scales { int a[4]; int b[2]; };
+    struct Scales { int a[NRB]; int b[2]; };
     auto load_s = [&](Scales& sc, int quad) {
         const int q = quad < CQ ? quad : CQ - 1;
 #pragma unroll
-        for (int rbi = 0; rbi < 4; ++rbi) sc.a[rbi] = (int)__builtin_amdgcn_raw_buffer_load_b32(rs_xe[rbi], lane4, q * 256, 0);
+        for (int rbi = 0; rbi < NRB; ++rbi) sc.a[rbi] = (int)__builtin_amdgcn_raw_buffer_load_b32(rs_xe[rbi], lane4, q * 256, 0);
 #pragma unroll
         for (int cbi = 0; cbi < 2; ++cbi) sc.b[cbi] = (int)__builtin_amdgcn_raw_buffer_load_b32(rs_pe[cbi], lane4, q * 256, 0);
     };
 
-    v16f t[4][2];
+    v16f t[NRB][2];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < NRB; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -1092,15 +1092,16 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     // issued through an empty descriptor: at K = 1152 they would be a sixth of the wavefront's vector-memory work.
     // The op_sel immediates of the scale bytes are 2*(P&1) and 2*(P&1)+1.
     v4i fr[4];
-    auto lds_frag = [&](int buf, int f) -> v4i {   // f = chunk * 4 + row block
-        return *(const v4i*)(lds + (size_t)((buf * 2 * RBT + f) * 1024) + lane16);
+    constexpr int NF = 2 * NRB;                    // fragments of a stage
+    auto lds_frag = [&](int buf, int f) -> v4i {   // f = chunk * NRB + row block
+        return *(const v4i*)(lds + (size_t)((buf * 2 * RBT + (f / NRB) * RBT + f % NRB) * 1024) + lane16);
     };
     auto do_stage = [&](auto pc, int s, AStage& a, BStage& b, const Scales& sc) {
         constexpr int P = decltype(pc)::value, PAR = P & 1;
 #pragma unroll
-        for (int f = 0; f < 8; ++f) {
-            const int cc = f >> 2, rbi = f & 3;
-            fr[(f + 2) & 3] = f + 2 < 8 ? lds_frag(P, f + 2) : lds_frag((P + 1) & 3, f + 2 - 8);
+        for (int f = 0; f < NF; ++f) {
+            const int cc = f / NRB, rbi = f % NRB;
+            fr[(f + 2) & 3] = f + 2 < NF ? lds_frag(P, f + 2) : lds_frag((P + 1) & 3, f + 2 - NF);
             if (f == 0) store_a(a, (P + 2) & 3);
             if (f == 1) load_a(a, s + 4);
             const v4i av = fr[f & 3];
@@ -1118,7 +1119,7 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
                     t[rbi][cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b8, a8, t[rbi][cbi], 4, 4, 2 * PAR + 1,
                                                                                  sc.b[cbi], 2 * PAR + 1, sc.a[rbi]);
             }
-            if (f == 7) load_b(b, s + 2);
+            if (f == NF - 1) load_b(b, s + 2);
             __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
@@ -1148,7 +1149,7 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     constexpr int NKA = NKF > 0 ? NKF : 1;
     constexpr bool TQ_ALL = NKF <= 1;
     v8i lf[2][NKA];
-    v8i tf[TQ_ALL ? 4 : 1][NKA];
+    v8i tf[TQ_ALL ? NRB : 1][NKA];
     auto load_tq = [&](int rbi) {
         int rb = rb0 + rbi;
         rb = rb < p.nrb ? rb : p.nrb - 1;
@@ -1205,7 +1206,7 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
                 lsc[cbi] = *(const int*)((const uint8_t*)p.sl + ((size_t)(cb0 + cbi) * 64 + lane) * 4);
             }
 #pragma unroll
-            for (int rbi = 0; rbi < 4; ++rbi) {
+            for (int rbi = 0; rbi < NRB; ++rbi) {
                 int rb = rb0 + rbi;
                 rb = rb < p.nrb ? rb : p.nrb - 1;
                 const v8i ta = *(const v8i*)(p.tq8 + ((size_t)((size_t)rb * NK + cc) * 64 + lane) * 32);
@@ -1245,21 +1246,20 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
         load_tq(0);
     }
     if constexpr (TQ_ALL) {
-        load_tq(1);
-        load_tq(2);
-        load_tq(3);
+#pragma unroll
+        for (int rbi = 1; rbi < NRB; ++rbi) load_tq(rbi);
     }
     // The stores are buffer stores through a descriptor that ends with the wavefront's 128 bytes of the tile's last valid
     // row: rows past M are out of range and dropped by the hardware, so the stores need no branch -- and only stores the
     // compiler can count let it wait for a load issued before them without waiting for the stores themselves.
-    const int rows_valid = p.M - rb0 * 32 < 128 ? p.M - rb0 * 32 : 128;
+    const int rows_valid = p.M - rb0 * 32 < NRB * 32 ? p.M - rb0 * 32 : NRB * 32;
     const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(p.Y + (size_t)(rb0 * 32) * p.ldy + cb0 * 32), 0, (int)((rows_valid - 1) * p.ldy * 2 + 128), RSRC_FLAGS);
     uint32_t yoff = (uint32_t)(rd_row * (int)p.ldy * 2 + rd_seg * 16);
     const uint32_t ystep = (uint32_t)(8 * (int)p.ldy * 2);
     v4i ov[4];
 #pragma unroll
-    for (int rbi = 0; rbi < 4; ++rbi) {
+    for (int rbi = 0; rbi < NRB; ++rbi) {
         const int rbase = (rb0 + rbi) * 32;
         v16f a2[2];
 #pragma unroll
@@ -1269,7 +1269,7 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
             for (int kk = 0; kk < NKF; ++kk)
                 a2[cbi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(lf[cbi][kk], tf[TQ_ALL ? rbi : 0][kk], a2[cbi], 0, 0, 0, 0, 0, 0);
         }
-        if (!TQ_ALL && rbi + 1 < 4) load_tq(rbi + 1);
+        if (!TQ_ALL && rbi + 1 < NRB) load_tq(rbi + 1);
         const float stl = (!BLK && NK > 0) ? lds_st[rbi * 32 + l32] : 0.f;  // this lane's token
         float y[2][16];
 #pragma unroll
@@ -1317,14 +1317,51 @@ __global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
     }
 }
 
+// Grid: the first n_full workgroups compute whole tiles (dealt round-robin to the XCDs, each XCD one contiguous run of the
+// panel order); the tiles left over, if they were split (see the launcher), follow as two half tiles each.
+template <int NK, bool DBG, bool BLK, int BFMT = 0>
+__global__ __launch_bounds__(256, 2) void mx_fwd_kernel(MxFwdParams p)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[mxf::LDS_TOTAL];
+    const int b = (int)blockIdx.x;
+    auto xcd_order = [](int i, int n) {
+        const int per = n >> 3, rem = n & 7, xcd = i & 7, loc = i >> 3;
+        return xcd * per + (xcd < rem ? xcd : rem) + loc;
+    };
+    int tile_m, tile_n;
+    if (b < p.n_full) {
+        panel_tile(xcd_order(b, p.n_full), p.tilesM, p.tilesN, p.panel, tile_m, tile_n);
+        mx_fwd_tile<NK, DBG, BLK, BFMT, 4>(p, lds, tile_m * 4, tile_n);
+    } else {
+        const int hh = xcd_order(b - p.n_full, 2 * (p.tilesM * p.tilesN - p.n_full));
+        panel_tile(p.n_full + (hh >> 1), p.tilesM, p.tilesN, p.panel, tile_m, tile_n);
+        const int rb0 = tile_m * 4 + (hh & 1) * 2;
+        if (rb0 >= p.nrb) return;  // lower half of a partial last row tile
+        mx_fwd_tile<NK, DBG, BLK, BFMT, 2>(p, lds, rb0, tile_n);
+    }
+}
+
 template <int NK, bool BLK, int BFMT = 0>
 static void mx_fwd_launch(const MxFwdParams& p, hipStream_t s)
 {
-    dim3 grid((unsigned)(p.tilesM * p.tilesN)), block(256);
+    dim3 grid((unsigned)(p.n_full + 2 * (p.tilesM * p.tilesN - p.n_full))), block(256);
     if (p.dbg_y32)
         hipLaunchKernelGGL((mx_fwd_kernel<NK, true, BLK, BFMT>), grid, block, 0, s, p);
     else
         hipLaunchKernelGGL((mx_fwd_kernel<NK, false, BLK, BFMT>), grid, block, 0, s, p);
+}
+
+static int mx_workgroup_slots()  // two workgroups (of up to 256 registers per lane) per compute unit
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 512;
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+        cached[dev] = 2 * cus;
+    }
+    return cached[dev];
 }
 
 hipError_t launch_fwd_mx(const Dims& d, const uint8_t* packed, const uint8_t* act, int64_t M, uint16_t* Y, int64_t ldy,
@@ -1353,6 +1390,14 @@ hipError_t launch_fwd_mx(const Dims& d, const uint8_t* packed, const uint8_t* ac
     p.tilesM = (p.nrb + 3) / 4;
     p.tilesN = (p.N + 255) / 256;
     p.panel = panel_width(p.tilesN, p.C64);
+    // Whole generations of the grid (two workgroups per CU) use whole tiles.  A last generation that fills at most a
+    // quarter of the slots is cut into half tiles: one per CU instead of one per second CU (16384 x 4608 -> 1152: 57.6 ->
+    // 54.3 us, 16384 x 1152 -> 1152: 22.4 -> 21.3 us).
+    {
+        const int tiles = p.tilesM * p.tilesN, slots = mx_workgroup_slots() & ~7;
+        const int rest = tiles % slots;
+        p.n_full = (tiles > slots && 4 * rest <= slots) ? tiles - rest : tiles;
+    }
     p.dbg_y32 = dbg ? dbg->y32 : nullptr;
     if (d.mxb_elem == 6) {
         switch (p.rp >> 6) {

@@ -159,7 +159,19 @@ def test_full_size_sampled_rows(oracle, name):
     layer = wl.LAYERS[name]
     X, W, L, R = wl.make_inputs(layer)
     rng = np.random.default_rng(1)
-    rows = np.sort(np.concatenate([[0, layer.M - 1], rng.choice(layer.M, 14, replace=False)]))
+    # (first and last row, both halves of the last row tile -- the last generation of some layers runs as half tiles)
+    rows = np.unique(np.concatenate([[0, layer.M - 1, layer.M - 128, layer.M - 65, layer.M - 64], rng.choice(layer.M, 14, replace=False)]))
+    _compare(oracle, layer, X, W, L, R, rows=rows)
+
+
+def test_half_tiles_of_the_last_generation(oracle):
+    """More tiles than workgroup slots with a sparse last generation: the forward cuts the tiles left over into 64-row half
+    tiles.  Every row of those tiles (ragged end included) and a sample of the others against the oracle."""
+    M = 528 * 128 - 37
+    layer = wl.Layer("t", M, 128, 320, 32, "mx", 32, 8, 8, "bf16", seed=11)
+    X, W, L, R = wl.make_inputs(layer)
+    rng = np.random.default_rng(2)
+    rows = np.unique(np.concatenate([np.arange(M - 16 * 128 - 200, M), [0, 63, 64, 127, 128], rng.choice(M, 24, replace=False)]))
     _compare(oracle, layer, X, W, L, R, rows=rows)
 
 
