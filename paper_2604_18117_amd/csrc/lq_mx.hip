@@ -1125,6 +1125,32 @@ __device__ __forceinline__ void mx_fwd_tile(const MxFwdParams& p, uint8_t* lds, 
         __syncthreads();
     };
 
+    // A wavefront whose columns lie past N (the last tile column of a layer whose width is no multiple of 256) only stages
+    // its row block of the activation codes and the token scales, barrier for barrier with the others: no matrix work, no
+    // weight or scale loads that would compete with the wavefront it shares a SIMD with.
+    if (cb0 * 32 >= p.N) {  // wave-uniform
+        AStage x0, x1;
+        load_a(x0, 0);
+        load_a(x1, 1);
+        if constexpr (!BLK && NK > 0) {
+            if (lane < 32) lds_st[wave * 32 + lane] = p.st[rbs * 32 + lane];
+        }
+        store_a(x0, 0);
+        store_a(x1, 1);
+        load_a(x0, 2);
+        load_a(x1, 3);
+        __syncthreads();
+        for (int s = 0; s < S; s += 2) {  // stage s sends stage s + 2 to its buffer and requests stage s + 4
+            store_a(x0, (s + 2) & 3);
+            load_a(x0, s + 4);
+            __syncthreads();
+            if (s + 1 >= S) break;
+            store_a(x1, (s + 3) & 3);
+            load_a(x1, s + 5);
+            __syncthreads();
+        }
+        return;
+    }
     AStage a0, a1;
     BStage b0, b1;
     Scales s0, s1;
