@@ -41,7 +41,11 @@ def run_gpu(layer, X, W, L, R, debug=True, debug_acc=True, gamma=None):
     if debug and layer.family in ("mx", "mxb", "mxi"):
         debug_acc = False
     # the output starts as a bit pattern the path never produces (a NaN): a tile the grid skipped would keep it
-    Y0 = torch.full((M, layer.N), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+    # ... followed by guard rows of the same pattern: the forward drops rows past M in hardware (range-checked buffer
+    # stores) and must leave them alone
+    GUARD = 40
+    Yall = torch.full((M + GUARD, layer.N), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+    Y0 = Yall[:M]
     act0 = torch.full((lq.lq_act_sizes(cfg, M),), 0xFF, dtype=torch.uint8, device="cuda")
     if debug:
         act, adbg = lq.lq_quantize_act(cfg, packed, Xd, act=act0, debug=True)
@@ -54,6 +58,7 @@ def run_gpu(layer, X, W, L, R, debug=True, debug_acc=True, gamma=None):
         out = GpuRun(cfg, packed, act, Y)
     torch.cuda.synchronize()
     assert not bool((Y.view(torch.int16) == -1).any()), "an output element was never written"
+    assert bool((Yall[M:].view(torch.int16) == -1).all()), "the forward wrote past the last token row"
     return out
 
 
