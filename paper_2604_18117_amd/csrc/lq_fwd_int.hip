@@ -603,10 +603,10 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
 }
 
 // Grid: the first n_full workgroups compute full 128 x 256 tiles, in row-major tile order; the
-// remaining tiles (if they are few, see launch_cfg) are each split into two 64 x 256 half tiles,
-// which shortens the last, sparsely filled round of the grid.  XCD-aware order in both regions: workgroup ids are
+// remaining tiles (see launch_cfg for when and how many) are each split into two 64 x 256 half tiles,
+// which shortens or evens out the last round of the grid.  XCD-aware order in both regions: workgroup ids are
 // dealt round-robin to the 8 XCDs, so each XCD gets one contiguous run of tiles (its L2 then sees
-// few distinct row tiles); n_full is a multiple of 8.
+// few distinct row tiles).
 __device__ __forceinline__ int xcd_order(int b, int n)
 {
     const int per = n >> 3, rem = n & 7;
@@ -690,9 +690,17 @@ static hipError_t launch_cfg(const FwdParams& p0, hipStream_t s)
     // Full rounds of the grid use full tiles.  A half tile costs more than half of a full one (each wavefront
     // reads its weight operands either way), so splitting the remainder pays only while
     // the halves still fit one per compute unit: measured +5 % on a 1152 -> 4608 layer (2.25 rounds),
-    // nothing at 1.75 rounds, a loss at 0.6 rounds.
+    // nothing at 1.75 rounds when the whole remainder is split, a loss at 0.6 rounds.
     int n_full = (tiles / slots) * slots;
-    if (4 * (tiles - n_full) > slots) n_full = tiles;
+    if (4 * (tiles - n_full) > slots) {
+        // A layer of between one and two generations whose second generation fills 50 .. 85 % of the slots (1152 -> 3456:
+        // 896 tiles on 512 slots): as many of the last tiles are halved as it takes to occupy every slot, so that no CU
+        // runs two whole tiles while its neighbour runs one (38.9 -> 36.5 us; with more generations before it, or a
+        // fuller last one, the same split changes nothing or loses).
+        const int rest = tiles - n_full;
+        n_full = tiles;
+        if (tiles > slots && tiles < 2 * slots && 2 * rest > slots && 20 * rest <= 17 * slots) n_full = tiles - (slots - rest);
+    }
     p.n_full = n_full;
     p.split_last = (p.N & 255) == 128;
     p.panel = panel_width(p.tilesN, p.C64, 48);
