@@ -182,11 +182,15 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     };
     auto load_b = [&](BStage& b, int step) {
         const int st = step < G ? step : G - 1;
+        // (the scales first: whatever path leads to their first use, the operand loads below were issued after them, so
+        // the wait the compiler places before that use never has to drain the whole vector-memory queue)
+#pragma unroll
+        for (int cbi = 0; cbi < 2; ++cbi)
+            b.sw[cbi] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_sw, l32x4 + cbi * 128, st * p.N * 4, 0));
 #pragma unroll
         for (int cbi = 0; cbi < 2; ++cbi) {
 #pragma unroll
             for (int cc = 0; cc < GC; ++cc) load_op(b.v[cc][cbi], rs_pq[cbi], st * GC + cc);
-            b.sw[cbi] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_sw, l32x4 + cbi * 128, st * p.N * 4, 0));
         }
     };
 
