@@ -81,11 +81,13 @@ def test_small_shapes_bit_exact(oracle, M, K, N, r, g, bw, ba, xd):
 @pytest.mark.parametrize("M,K,N,r,g,bw,ba", [(2000, 128, 2304, 16, 64, 8, 8), (2100, 256, 2304, 32, 128, 4, 8),
                                                  (2100, 128, 2176, 32, 64, 8, 8), (2100, 128, 2240, 32, 64, 8, 8),
                                                  (4000, 128, 2304, 32, 64, 8, 8), (4100, 192, 2176, 64, 64, 6, 6),
-                                                 (4000, 256, 2240, 32, 128, 4, 8)])
+                                                 (4000, 256, 2240, 32, 128, 4, 8), (2100, 128, 2112, 32, 64, 6, 6),
+                                                 (2100, 256, 2112, 32, 128, 4, 8)])
 def test_full_tiles_bit_exact(oracle, M, K, N, r, g, bw, ba):
     """Large enough (more than a quarter of the device's workgroup slots) that the grid runs
     full 128 x 256 tiles, the small shapes above run as half tiles; ragged last row tile; the third
-    case has a last tile column with 128 valid channels (wavefronts arranged 2 x 2 there), the fourth one with 192 (its
+    case has a last tile column with 128 valid channels (wavefronts arranged 2 x 2 there), the last two one with 64 (three of
+    its four wavefronts only stage), the fourth one with 192 (its
     fourth wavefront only stages).  The last three have between one 128-row tile per compute unit and one per workgroup
     slot and therefore run as 96-row tiles (ragged last tile of one or two row blocks; last tile column of 128 or 192
     channels, whose wavefronts past the end only stage; 64- and 128-deep groups)."""
