@@ -90,7 +90,7 @@ constexpr int lds_bytes()
     return 2 * GC * RBT * lds_slot<GA>() > NW * EPI_WAVE ? 2 * GC * RBT * lds_slot<GA>() : NW * EPI_WAVE;
 }
 
-// Epilogue operands parked in LDS (64-deep groups): a tile's per-token scales, intermediate codes, and each wavefront's
+// Epilogue operands parked in LDS: a tile's per-token scales, intermediate codes, and each wavefront's
 // channel scales and channel codes are fetched in the prologue, when the running sums do not exist yet and registers
 // are free, and wait in LDS; requested at the start of the epilogue, their round trip through the memory system
 // (nothing else is left to do by then) would open every tile's epilogue.  sx[128] st[128] | sl[4][64] | lq[4][2][NK][64 x 16 B] |
@@ -98,7 +98,7 @@ constexpr int lds_bytes()
 template <int GC, int NK, bool GA>
 constexpr bool park_epilogue()
 {
-    return GC == 1 && !GA;
+    return !GA && (GC == 1 || NK <= 3);  // (two workgroups per CU must still fit their LDS; SINT4 blocks keep theirs for the token scales)
 }
 template <int NK>
 constexpr int park_bytes()
@@ -239,9 +239,10 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
                 d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(af[cc], op8(bc.v[cc][cbi]), d, 2, 2, 0, 0, 0, 0);
             return d;
         };
-        // operand of the current row block; double-buffered unless registers are scarce (the next block's
-        // read is issued after the last MFMA that uses the current one, so one buffer is enough)
-        constexpr int AFB = GA ? 1 : 2;
+        // operand of the current row block; double-buffered unless registers are scarce (SINT4 blocks; 128-deep groups,
+        // whose two-chunk operands and weight sets otherwise push the kernel into spills): the next block's read is
+        // then issued after the last MFMA that uses the current one, so one buffer is enough
+        constexpr int AFB = (GA || GC == 2) ? 1 : 2;
         v8i af[AFB][GC];
         v16f dd[2];
         float swc[2];
@@ -455,13 +456,27 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         load_b(b1, 1);
         store_a(a0, 0);
         load_a(a0, 1);
-        __syncthreads();
+        if constexpr (PARK) {
+            ParkRows pr;
+            ParkCols pc;
+            park_load_rows(pr);
+            park_load_cols(pc);
+            __syncthreads();
+            park_store_rows(pr);
+            park_store_cols(pc);
+        } else {
+            __syncthreads();
+        }
         do_step(first, 0, a0, b0, b0, s0);
-        for (int s = 1; s < G; s += 2) {
+        // whole pairs of steps in a loop with one exit, an odd last step after it: with an exit between the two steps
+        // the compiler builds a loop whose header can be reached with a weight scale as the last load issued, and
+        // waits for the whole vector-memory queue before every use of a scale
+        int s = 1;
+        for (; s + 1 < G; s += 2) {
             do_step(later, s, a0, b1, b1, s0);
-            if (s + 1 >= G) break;
             do_step(later, s + 1, a0, b0, b0, s0);
         }
+        if (s < G) do_step(later, s, a0, b1, b1, s0);
     }
 
     // ---- epilogue: rank-r expansion, scales, sum, bf16 -------------------------------------
@@ -530,20 +545,15 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
     load_scales(0);
     // this lane's output pointer: row rd_row of the tile, 16 bytes at column segment rd_seg; it moves
     // down 8 rows per store (4 stores per row block), rows past M are skipped
-    // With 64-deep groups the stores are buffer stores through a descriptor that ends with the wavefront's 128 bytes of
-    // its last valid row: rows past M are out of range and dropped by the hardware, so the stores need no branch -- and
-    // only stores the compiler can count let it wait for a load issued before them without waiting for the stores
-    // themselves (the vector-memory counter retires in order).  Measured: 2240 -> 6720 layer 110 -> 107 us.  The
-    // 128-deep instantiation keeps pointer stores under a row test: with buffer stores the compiler lays out its K loop
-    // differently (a full vector-memory wait inside the loop) and the 4608 -> 1152 layer loses 7 %.
-    constexpr bool BUF_ST = GC == 1;
+    // The stores are buffer stores through a descriptor that ends with the wavefront's 128 bytes of its last valid row:
+    // rows past M are out of range and dropped by the hardware, so the stores need no branch -- and only stores the
+    // compiler can count let it wait for a load issued before them without waiting for the stores themselves (the
+    // vector-memory counter retires in order).  Measured: 2240 -> 6720 layer 110 -> 107 us.
     const int rows_valid = p.M - rbw * 32 < NRB * 32 ? p.M - rbw * 32 : NRB * 32;
     const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(p.Y + (size_t)(rbw * 32) * p.ldy + cb0 * 32), 0, (int)((rows_valid - 1) * p.ldy * 2 + 128), RSRC_FLAGS);
     uint32_t yoff = (uint32_t)(rd_row * (int)p.ldy * 2 + rd_seg * 16);
     const uint32_t ystep = (uint32_t)(8 * (int)p.ldy * 2);
-    uint16_t* yptr = p.Y + (size_t)(rbw * 32 + rd_row) * p.ldy + cb0 * 32 + rd_seg * 8;
-    const size_t yptr_step = (size_t)8 * p.ldy;
     v4i ov[4];
 #pragma unroll
     for (int rbi = 0; rbi < NRB; ++rbi) {
@@ -595,13 +605,8 @@ __device__ __forceinline__ void fwd_tile(const FwdParams& p, uint8_t* lds, const
         for (int q = 0; q < 4; ++q) ov[q] = *(const v4i*)(stage + (q * 8 + rd_row) * EPI_ROW + rd_seg * 16);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if constexpr (BUF_ST) {
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, ov[q]), rs_y, yoff, 0, 0);
-                yoff += ystep;
-            } else {
-                if (rbase + q * 8 + rd_row < p.M) *(v4i*)yptr = ov[q];
-                yptr += yptr_step;
-            }
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, ov[q]), rs_y, yoff, 0, 0);
+            yoff += ystep;
         }
     }
 }
