@@ -905,15 +905,26 @@ __global__ __launch_bounds__(256, 2) void mxi_fwd_kernel(MxiFwdParams p)
                 const uint32_t field = exp_field(am);
                 const float inv4 = field >= 2u ? __uint_as_float((256u - field) << 23) : 0.0f;   // 2^(2-s)
                 const float to8 = field >= 7u ? __uint_as_float((260u - field) << 23) : 0.0f;    // 2^(6-s)
-                uint32_t sum = 0u - 0xFB000000u, c8[2] = {0u, 0u};
+                // Both codes by one fused multiply-add each: scaling by a power of two is exact, so fma(x, 2^-step, magic)
+                // rounds the scaled value to the nearest integer (ties to even) in one step -- the same integer the
+                // activation kernel reaches by rounding on the block's grid and scaling afterwards -- and leaves it in
+                // the low mantissa bits of the magic number.  Clamping after the rounding equals clamping before it.
+                uint32_t sum = 0u - 0xFB000000u, c8[2];
+                uint32_t ub[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const float x = __uint_as_float((e & 1) ? (w[e >> 1] & 0xFFFF0000u) : (w[e >> 1] << 16));
-                    const uint32_t mb = __float_as_uint(__fadd_rn(fminf(__fmul_rn(fabsf(x), inv4), 7.0f), 8388608.0f));
+                    const uint32_t mb = __float_as_uint(fminf(__builtin_fmaf(fabsf(x), inv4, 8388608.0f), 8388615.0f));
                     const int sh = e < 4 ? 8 * e : 8 * ((e - 5) & 3) + 4;
                     sum += mb << sh;
-                    const int code = (int)__fmul_rn(mxint8_round(x, field), to8);   // exact: a multiple of one step
-                    c8[e >> 2] |= ((uint32_t)code & 0xFFu) << (8 * (e & 3));
+                    // 1.5 * 2^23 + code, code in [-127, 127]: the low byte is the two's-complement MXINT8 code
+                    ub[e] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x, to8, 12582912.0f), 12582785.0f, 12583039.0f));
+                }
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t lo = __builtin_amdgcn_perm(ub[4 * h + 1], ub[4 * h], 0x0c0c0400u);      // bytes 0 of two dwords
+                    const uint32_t hi = __builtin_amdgcn_perm(ub[4 * h + 3], ub[4 * h + 2], 0x04000c0cu);  // ... in the upper half
+                    c8[h] = lo | hi;
                 }
                 const uint32_t s03 = __builtin_amdgcn_perm(w[1], w[0], 0x07050301u);
                 const uint32_t s47 = __builtin_amdgcn_perm(w[3], w[2], 0x07050301u);
